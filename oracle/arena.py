@@ -1,0 +1,254 @@
+"""Run-time half of the plan: concrete sizes, lifetimes and arena offsets once
+the symbols (and, with control flow, the Switch decisions) are known
+(Section 4.4.1).
+
+Reading of the two-sentence description in the paper, per executed sub-graph
+in execution order:
+  1. live bytes per step; p* = the step with the most live bytes (earliest on ties);
+  2. the sub-graph's tensors live at p*, by (start step, id), then
+  3. those starting after p*, by (start step, id), then
+  4. those ending before p*, by (end step descending, start step descending, id),
+  are placed one by one at the lowest offset where they overlap no tensor
+  already placed (in this or an earlier sub-graph) whose lifetime intersects.
+Sizes are element count x element size rounded up to 256 bytes.  Control flow
+follows dead-token propagation: the Switch output that is not taken is dead,
+an operator with a dead input does not run, Combine forwards its live input.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from itertools import permutations
+from typing import Dict, List, Sequence, Tuple
+
+from . import rdp as R
+from .plan import Plan, DT_BYTES, align_up, arena_candidate
+
+
+class SymbolOutOfRange(Exception):
+    pass
+
+
+class UnresolvedShape(Exception):
+    pass
+
+
+@dataclass
+class ArenaTensor:
+    tid: int
+    bytes: int
+    start: int
+    end: int
+    offset: int = -1
+
+
+@dataclass
+class Binding:
+    plan: Plan
+    env: Dict[str, int]
+    steps: List[int] = field(default_factory=list)            # executed item indices
+    step_sg: List[int] = field(default_factory=list)          # sub-graph of each step
+    decisions: Dict[int, bool] = field(default_factory=dict)  # Switch op id -> skip?
+    tensors: Dict[int, ArenaTensor] = field(default_factory=dict)
+    dims: Dict[int, List[int]] = field(default_factory=dict)
+    arena_bytes: int = 0
+    peak_live: int = 0
+    dead_ops: set = field(default_factory=set)
+    dyn_base: Dict[int, int] = field(default_factory=dict)
+
+
+def concrete_dims(plan: Plan, t: int, env) -> List[int]:
+    s = plan.rdp.S[t]
+    if not isinstance(s, list) or any(not R.is_expr(d) for d in s):
+        raise UnresolvedShape(f"tensor {t} ({plan.graph.tensors[t].name})")
+    return [d.eval(env) for d in s]
+
+
+def intersects(a: ArenaTensor, b: ArenaTensor) -> bool:
+    return a.start <= b.end and b.start <= a.end
+
+
+def first_fit(t: ArenaTensor, placed: Sequence[ArenaTensor]) -> int:
+    busy = sorted((p.offset, p.offset + p.bytes) for p in placed if intersects(t, p))
+    off = 0
+    for lo, hi in busy:
+        if off + t.bytes <= lo:
+            break
+        off = max(off, hi)
+    return off
+
+
+def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Binding:
+    g = plan.graph
+    for name, lo, hi in g.symbols:
+        if name not in sym or not (lo <= sym[name] <= hi):
+            raise SymbolOutOfRange(name)
+    env = {name: int(sym[name]) for name, _, _ in g.symbols}
+    b = Binding(plan, env)
+    prod = plan.rdp.producer
+    group_dead: Dict[int, bool] = {}
+    memo: Dict[int, Tuple[bool, int]] = {}
+    dec = list(decisions)
+
+    def info(t: int) -> Tuple[bool, int]:
+        """(dead?, tensor whose storage t occupies)."""
+        if t in memo:
+            return memo[t]
+        p = prod[t]
+        if p < 0 or plan.folded[p]:
+            r = (False, t)
+        else:
+            op = g.ops[p]
+            if op.kind == "Switch":
+                d, base = info(op.inputs[0])
+                skip = b.decisions.get(p)
+                taken = (op.outputs.index(t) == 1) == bool(skip)
+                r = (d or skip is None or not taken, base)
+            elif op.kind == "Combine":
+                r = (True, t)
+                for i in op.inputs:
+                    d, base = info(i)
+                    if not d:
+                        r = (False, base)
+                        break
+            elif plan.view[p]:
+                r = info(op.inputs[0])
+            else:
+                r = (group_dead[plan.group_of_op[p]], t)
+        memo[t] = r
+        return r
+
+    reads_at: Dict[int, int] = {}          # base tensor -> last step reading it
+    for s, sg in enumerate(plan.subgraphs):
+        for i in sg:
+            it = plan.items[i]
+            step = len(b.steps)
+            if it.is_group:
+                gr = plan.groups[it.ref]
+                inside = {o for n in gr.ops for o in g.ops[n].outputs}
+                ext = [t for n in gr.ops for t in g.ops[n].inputs if t not in inside]
+                dead = any(info(t)[0] for t in ext)
+                group_dead[gr.gid] = dead
+                if dead:
+                    b.dead_ops.update(gr.ops)
+                    continue
+                for t in ext:
+                    reads_at[info(t)[1]] = step
+                t = gr.out
+                b.dims[t] = concrete_dims(plan, t, env)
+                if arena_candidate(plan, t):
+                    n = DT_BYTES[g.tensors[t].dtype]
+                    for d in b.dims[t]:
+                        n *= d
+                    b.tensors[t] = ArenaTensor(t, align_up(n), step, step)
+            else:
+                op = g.ops[it.ref]
+                if op.kind == "Switch":
+                    if info(op.inputs[0])[0]:
+                        b.dead_ops.add(it.ref)
+                        continue
+                    if not dec:
+                        raise ValueError("a Switch decision is missing")
+                    b.decisions[it.ref] = bool(dec.pop(0))
+                    for t in op.inputs:
+                        reads_at[info(t)[1]] = step
+                else:
+                    live = [t for t in op.inputs if not info(t)[0]]
+                    if not live:
+                        b.dead_ops.add(it.ref)
+                        continue
+                    reads_at[info(live[0])[1]] = step
+            b.steps.append(i)
+            b.step_sg.append(s)
+    for t, at in b.tensors.items():
+        at.end = max(at.start, reads_at.get(t, at.start))
+    for t in range(len(g.tensors)):
+        if prod[t] >= 0 and not plan.folded[prod[t]] and prod[t] not in b.dead_ops:
+            d, base = info(t)
+            if not d:
+                b.dyn_base[t] = base
+
+    nsteps = len(b.steps)
+    live_bytes = [0] * nsteps
+    for at in b.tensors.values():
+        for k in range(at.start, at.end + 1):
+            live_bytes[k] += at.bytes
+    b.peak_live = max(live_bytes, default=0)
+
+    placed: List[ArenaTensor] = []
+    if plan.opts.dmp:
+        for s in sorted(set(b.step_sg)):
+            ks = [k for k in range(nsteps) if b.step_sg[k] == s]
+            mine = [at for at in b.tensors.values() if ks[0] <= at.start <= ks[-1]]
+            if not mine:
+                continue
+            p = max(ks, key=lambda k: (live_bytes[k], -k))
+            at_peak = sorted((a for a in mine if a.start <= p <= a.end), key=lambda a: (a.start, a.tid))
+            after = sorted((a for a in mine if a.start > p), key=lambda a: (a.start, a.tid))
+            before = sorted((a for a in mine if a.end < p), key=lambda a: (-a.end, -a.start, a.tid))
+            for a in at_peak + after + before:
+                a.offset = first_fit(a, placed)
+                placed.append(a)
+    else:
+        for a in sorted(b.tensors.values(), key=lambda a: (a.start, a.tid)):
+            a.offset = best_fit(a, placed)
+            placed.append(a)
+    b.arena_bytes = max((a.offset + a.bytes for a in placed), default=0)
+    return b
+
+
+def best_fit(t: ArenaTensor, placed: Sequence[ArenaTensor]) -> int:
+    """The comparison strategy named in Section 4.4.1: the smallest free slot that holds the tensor."""
+    busy = sorted((p.offset, p.offset + p.bytes) for p in placed if intersects(t, p))
+    top = max((p.offset + p.bytes for p in placed), default=0)
+    gaps, cur = [], 0
+    for lo, hi in busy:
+        if lo > cur:
+            gaps.append((lo - cur, cur))
+        cur = max(cur, hi)
+    if top > cur:
+        gaps.append((top - cur, cur))
+    fits = sorted(gp for gp in gaps if gp[0] >= t.bytes)
+    return fits[0][1] if fits else cur
+
+
+def optimal_arena_bytes(tensors: Sequence[ArenaTensor]) -> int:
+    """Exhaustive optimum (used in Section 4.4.1 to score the planner): the best placement is
+    reached by first-fit in *some* order (sort an optimal layout by offset), so try every order."""
+    assert len(tensors) <= 9
+    best = None
+    for perm in permutations(tensors):
+        placed = []
+        for a in perm:
+            c = ArenaTensor(a.tid, a.bytes, a.start, a.end)
+            c.offset = first_fit(c, placed)
+            placed.append(c)
+        top = max((c.offset + c.bytes for c in placed), default=0)
+        best = top if best is None else min(best, top)
+    return best or 0
+
+
+def check_no_overlap(b: Binding):
+    ts = list(b.tensors.values())
+    for i, x in enumerate(ts):
+        assert x.offset >= 0 and x.offset % 256 == 0
+        for y in ts[i + 1:]:
+            if intersects(x, y):
+                assert x.offset + x.bytes <= y.offset or y.offset + y.bytes <= x.offset, (x, y)
+
+
+def dump(b: Binding) -> str:
+    plan = b.plan
+    lines = ["sym " + " ".join(f"{k}={v}" for k, v in b.env.items())]
+    for k, i in enumerate(b.steps):
+        it = plan.items[i]
+        lines.append(f"step {k} {'g' if it.is_group else 'c'}{it.ref}")
+    for t in sorted(b.dims):
+        dims = " ".join(map(str, b.dims[t]))
+        if t in b.tensors:
+            a = b.tensors[t]
+            lines.append(f"t{t} dims=[{dims}] off={a.offset} bytes={a.bytes} life={a.start}..{a.end}")
+        else:
+            lines.append(f"t{t} dims=[{dims}] external")
+    lines.append(f"arena_bytes={b.arena_bytes}")
+    lines.append(f"peak_live={b.peak_live}")
+    return "\n".join(lines) + "\n"

@@ -1,0 +1,108 @@
+"""Unfused execution of the graph at concrete shapes: the value oracle.
+
+Operators run one by one in the node order, each into a buffer of its own (no
+arena, no fusion, no kernel versions).  Control flow uses dead tokens: Switch
+leaves the branch it does not take dead, an operator with a dead input is not
+run, Combine forwards its live input (Section 3, Fig. 1(d)).
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+from . import ops as O
+
+DEAD = "dead"
+
+
+class Result:
+    def __init__(self):
+        self.values: Dict[int, object] = {}
+        self.decisions: List[bool] = []       # one per executed Switch, True = skip branch taken
+        self.logits: List[float] = []         # predicate value seen by each executed Switch
+
+
+def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dict[int, np.ndarray],
+        forced: Optional[Sequence[bool]] = None, round_weights=True) -> Result:
+    g = graph
+    res = Result()
+    val = res.values
+    for i, t in enumerate(g.tensors):
+        if t.data is not None:
+            val[i] = np.asarray(t.data, dtype=np.int64 if t.dtype in ("i64", "i32") else np.float64)
+        elif i in weights:
+            val[i] = O.round_to(np.asarray(weights[i], np.float64), t.dtype) if round_weights else weights[i]
+        elif i in inputs:
+            val[i] = O.round_to(np.asarray(inputs[i], np.float64), t.dtype)
+    forced = list(forced) if forced is not None else None
+    for n in order:
+        op = g.ops[n]
+        a = op.attrs
+        xs = [val[t] for t in op.inputs]
+        if op.kind == "Combine":
+            live = [x for x in xs if x is not DEAD]
+            val[op.outputs[0]] = live[0] if live else DEAD
+            continue
+        if any(x is DEAD for x in xs):
+            for o in op.outputs:
+                val[o] = DEAD
+            continue
+        if op.kind == "Switch":
+            p = float(np.asarray(xs[1]).reshape(-1)[0])
+            skip = p > a["threshold"]
+            if forced is not None:
+                skip = bool(forced.pop(0))
+            res.decisions.append(bool(skip))
+            res.logits.append(p)
+            val[op.outputs[0]] = DEAD if skip else xs[0]
+            val[op.outputs[1]] = xs[0] if skip else DEAD
+            continue
+        k = op.kind
+        if k == "Shape":
+            y = np.asarray(xs[0].shape, dtype=np.int64)
+        elif k == "Gather":
+            y = np.take(xs[0], np.asarray(xs[1], dtype=np.int64), axis=a["axis"])
+        elif k == "Concat":
+            y = np.concatenate(xs, axis=a["axis"])
+        elif k == "Reshape":
+            tgt = [xs[0].shape[i] if d == 0 else int(d) for i, d in enumerate(xs[1])]
+            y = xs[0].reshape(tgt)
+        elif k == "Slice":
+            y = O.slice_(xs[0], xs[1], xs[2], [int(v) % xs[0].ndim for v in xs[3]])
+        elif k == "Transpose":
+            y = np.transpose(xs[0], a["perm"])
+        elif k == "MatMul":
+            y = O.matmul(xs[0], xs[1], a.get("transB", 0))
+        elif k == "Conv":
+            y = O.conv2d_nhwc(xs[0], xs[1], a["stride"], a["pad"])
+        elif k == "Add":
+            y = xs[0] + xs[1]
+        elif k == "Mul":
+            y = xs[0] * xs[1]
+        elif k == "Relu":
+            y = np.maximum(xs[0], 0.0)
+        elif k == "Gelu":
+            y = O.gelu(xs[0])
+        elif k == "Sigmoid":
+            y = O.sigmoid(xs[0])
+        elif k == "Cast":
+            y = xs[0]
+        elif k == "Softmax":
+            y = O.softmax(xs[0], a.get("causal", 0))
+        elif k == "LayerNorm":
+            y = O.layernorm(xs[0], xs[1], xs[2], a["eps"])
+        elif k == "ReduceMean":
+            y = xs[0].mean(axis=tuple(a["axes"]), keepdims=bool(a.get("keepdims", 1)))
+        elif k == "MaxPool":
+            y = O.maxpool_nhwc(xs[0], a["kernel"], a["stride"], a["pad"])
+        elif k == "ArgMax":
+            y = np.argmax(xs[0], axis=-1)
+        elif k == "CacheAppend":
+            y = np.concatenate([xs[0], xs[1]], axis=0)
+        elif k == "NonZero":
+            y = np.stack(np.nonzero(xs[0])).astype(np.int64)
+        else:
+            raise ValueError(k)
+        val[op.outputs[0]] = O.round_to(np.asarray(y), g.tensors[op.outputs[0]].dtype)
+    return res

@@ -1,0 +1,92 @@
+"""Operator value definitions, one textbook formula each, in float64.
+
+Every function takes and returns numpy float64 (or int64) arrays.  Rounding to
+the storage type of the output tensor is applied by the caller after each
+operator, because the unfused graph materialises every operator output.
+"""
+from __future__ import annotations
+
+import numpy as np
+from scipy.special import erf
+
+INT_MAX = 2 ** 31 - 1
+
+
+def round_to(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Round float64 values to the storage type and return them as float64 again."""
+    if dtype == "f32":
+        return x.astype(np.float32).astype(np.float64)
+    if dtype == "bf16":
+        u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32)
+        r = ((u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)) << np.uint32(16)
+        return r.astype(np.uint32).view(np.float32).astype(np.float64)
+    if dtype in ("i64", "i32"):
+        return x.astype(np.int64)
+    raise ValueError(dtype)
+
+
+def matmul(a, b, transB):
+    return np.matmul(a, np.swapaxes(b, -1, -2) if transB else b)
+
+
+def conv2d_nhwc(x, w, stride, pad):
+    """out[n,oh,ow,o] = sum_{kh,kw,c} x[n, oh*s+kh-p, ow*s+kw-p, c] * w[o,kh,kw,c], zero padding."""
+    n, h, wd, c = x.shape
+    o, kh, kw, ci = w.shape
+    assert c == ci
+    oh = (h + 2 * pad - kh) // stride + 1
+    ow = (wd + 2 * pad - kw) // stride + 1
+    xp = np.zeros((n, h + 2 * pad, wd + 2 * pad, c), dtype=np.float64)
+    xp[:, pad:pad + h, pad:pad + wd, :] = x
+    out = np.zeros((n, oh, ow, o), dtype=np.float64)
+    for i in range(kh):
+        for j in range(kw):
+            patch = xp[:, i:i + (oh - 1) * stride + 1:stride, j:j + (ow - 1) * stride + 1:stride, :]
+            out += np.tensordot(patch, w[:, i, j, :], axes=([3], [1]))
+    return out
+
+
+def maxpool_nhwc(x, k, stride, pad):
+    n, h, wd, c = x.shape
+    oh = (h + 2 * pad - k) // stride + 1
+    ow = (wd + 2 * pad - k) // stride + 1
+    xp = np.full((n, h + 2 * pad, wd + 2 * pad, c), -np.inf)
+    xp[:, pad:pad + h, pad:pad + wd, :] = x
+    out = np.full((n, oh, ow, c), -np.inf)
+    for i in range(k):
+        for j in range(k):
+            out = np.maximum(out, xp[:, i:i + (oh - 1) * stride + 1:stride, j:j + (ow - 1) * stride + 1:stride, :])
+    return out
+
+
+def gelu(x):
+    return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
+
+
+def sigmoid(x):
+    return 1.0 / (1.0 + np.exp(-x))
+
+
+def softmax(x, causal):
+    """Over the last axis; with ``causal`` row i of the last two axes sees columns j <= i + (Lk - Lq)."""
+    if causal:
+        lq, lk = x.shape[-2], x.shape[-1]
+        i = np.arange(lq)[:, None]
+        j = np.arange(lk)[None, :]
+        x = np.where(j <= i + (lk - lq), x, -np.inf)
+    m = x.max(axis=-1, keepdims=True)
+    e = np.exp(x - m)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
+def layernorm(x, gamma, beta, eps):
+    mu = x.mean(axis=-1, keepdims=True)
+    var = ((x - mu) ** 2).mean(axis=-1, keepdims=True)      # biased variance
+    return (x - mu) / np.sqrt(var + eps) * gamma + beta
+
+
+def slice_(x, starts, ends, axes):
+    idx = [slice(None)] * x.ndim
+    for s, e, a in zip(starts, ends, axes):
+        idx[a] = slice(int(s), None if e >= INT_MAX else int(e))
+    return x[tuple(idx)]

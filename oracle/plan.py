@@ -1,0 +1,450 @@
+"""Static planning on top of RDP: fusion groups (Section 4.2), sub-graph
+partition and execution order (Section 4.3).
+
+The paper delegates the fusion rules to an earlier system and gives the
+partition and the search only in outline, so the concrete rules below are this
+build's reading; the library follows the same written rules independently.
+
+R0  An operator whose outputs are all integer tensors with a fully resolved
+    value map is *folded*: its result is known from RDP (Fig. 1(a)), nothing runs.
+R1  Reshape, Slice, Transpose and Gather-with-a-scalar-host-index are *views*:
+    their output aliases the input's storage; no kernel, no arena tensor.
+R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
+    this order and each at most once: Mul by a host scalar; Add of a rank-1
+    weight equal to the last dim (bias); activation; Add of a non-constant
+    tensor whose shape RDP proves equal to the output's (residual);
+    activation; Transpose (stored permuted).  The chain stops at the first
+    operator that does not fit.
+R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero are
+    groups of their own; a non-view Gather absorbs one following Add whose
+    other operand has a proven-equal shape.
+R4  Remaining elementwise operators chain while every aligned dim pair of
+    every operand is proven equal or 1 (the condition of Fig. 4), up to 8 ops.
+R5  Group id = smallest operator id in it; groups are ordered by the position
+    of their last member in the node order (a topological order of groups).
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional
+
+from .expr import Expr
+from . import rdp as R
+
+ALIGN = 256
+MAX_SG = 14
+DT_BYTES = {"f32": 4, "bf16": 2, "i64": 8, "i32": 4}
+VIEW_KINDS = ("Reshape", "Slice", "Transpose")
+ACTS = ("Relu", "Gelu", "Sigmoid")
+ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast")
+SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
+        "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
+        "NonZero": "NONZERO"}
+
+
+@dataclass
+class Opts:
+    fusion: bool = True      # RDP-enabled fusion (R2-R4); off: every operator is its own group
+    sep: bool = True         # static execution planning; off: node order
+    dmp: bool = True         # peak-first arena plan; off: best-fit greedy in execution order
+    mvc: bool = True         # multi-version kernels (library only; no effect on structure)
+
+
+@dataclass
+class Group:
+    gid: int
+    kind: str
+    ops: List[int]
+    out: int                              # tensor id written by the group
+    ins: List[int] = field(default_factory=list)   # base tensors read from outside the group
+
+
+@dataclass
+class Item:                               # a step candidate: a group or a control operator
+    is_group: bool
+    ref: int                              # group id or operator id
+    reads: List[int] = field(default_factory=list)     # static bases read
+    writes: List[int] = field(default_factory=list)    # static bases produced
+
+
+@dataclass
+class Plan:
+    graph: object
+    rdp: R.RDP
+    opts: Opts
+    order: List[int]
+    folded: List[bool]
+    view: List[bool]
+    groups: Dict[int, Group]
+    group_of_op: Dict[int, int]
+    items: List[Item]
+    subgraphs: List[List[int]]            # item indices, in planned execution order
+    sg_class: List[str]
+    sbase: List[int]                      # static base of every tensor
+    versions_unfused: int = 0             # broadcast versions a shape-blind fuser would need
+
+
+def _shape_equal(a, b) -> bool:
+    return isinstance(a, list) and isinstance(b, list) and len(a) == len(b) and \
+        all(R.is_expr(x) and R.is_expr(y) and x == y for x, y in zip(a, b))
+
+
+def _bcast_proven(out, other) -> bool:
+    if not isinstance(out, list) or not isinstance(other, list) or len(other) > len(out):
+        return False
+    pad = [R.C(1)] * (len(out) - len(other)) + other
+    return all(R.pair_proven(x, y) for x, y in zip(out, pad))
+
+
+def tensor_bytes_expr(plan_or_rdp, graph, tid) -> Optional[Expr]:
+    s = plan_or_rdp.S[tid]
+    if not isinstance(s, list) or any(not R.is_expr(d) for d in s):
+        return None
+    e = R.C(DT_BYTES[graph.tensors[tid].dtype])
+    for d in s:
+        e = e * d
+    return e
+
+
+def align_up(n: int) -> int:
+    return (n + ALIGN - 1) // ALIGN * ALIGN
+
+
+def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
+    opts = opts or Opts()
+    g = graph
+    order = rdp.sorted_nodes()
+    pos = {n: i for i, n in enumerate(order)}
+    nops = len(g.ops)
+
+    # R0 / R1 ---------------------------------------------------------------
+    folded, view = [False] * nops, [False] * nops
+    for i, op in enumerate(g.ops):
+        if op.kind in ("Switch", "Combine"):
+            continue
+        outs_int = all(g.tensors[o].dtype in ("i64", "i32") for o in op.outputs)
+        if outs_int and all(isinstance(rdp.V[o], list) and all(R.is_expr(e) for e in rdp.V[o])
+                            for o in op.outputs):
+            folded[i] = True
+        elif op.kind in VIEW_KINDS:
+            view[i] = True
+        elif op.kind == "Gather":
+            idx = g.tensors[op.inputs[1]]
+            view[i] = idx.data is not None and idx.data.ndim == 0
+
+    def sole_consumer(t) -> Optional[int]:
+        if g.tensors[t].is_output or len(rdp.consumers[t]) != 1:
+            return None
+        return rdp.consumers[t][0]
+
+    def other(op, cur):
+        return op.inputs[1] if op.inputs[0] == cur else op.inputs[0]
+
+    def is_host_scalar(t) -> bool:
+        d = g.tensors[t]
+        return d.data is not None and d.data.size == 1
+
+    # R2-R4: fusion -----------------------------------------------------------
+    assigned: Dict[int, int] = {}
+    groups: Dict[int, Group] = {}
+    absorbed_transpose = set()
+
+    def new_group(kind, members):
+        gid = min(members)
+        last = max(members, key=lambda n: pos[n])
+        groups[gid] = Group(gid, kind, sorted(members), g.ops[last].outputs[0])
+        for n in members:
+            assigned[n] = gid
+
+    for n in order:
+        op = g.ops[n]
+        if folded[n] or n in assigned or op.kind in ("Switch", "Combine"):
+            continue
+        if view[n] and n not in absorbed_transpose:
+            continue
+        if op.kind in ("MatMul", "Conv"):
+            members, cur, state = [n], op.outputs[0], 0
+            while opts.fusion:
+                c = sole_consumer(cur)
+                if c is None or folded[c] or c in assigned:
+                    break
+                cop = g.ops[c]
+                nxt = None
+                if cop.kind == "Mul" and state < 1 and is_host_scalar(other(cop, cur)):
+                    nxt = 1
+                elif cop.kind == "Add":
+                    o = other(cop, cur)
+                    so, sc = rdp.S[o], rdp.S[cur]
+                    if state < 2 and g.tensors[o].role == "weight" and isinstance(so, list) and \
+                            len(so) == 1 and isinstance(sc, list) and R.is_expr(sc[-1]) and so[0] == sc[-1]:
+                        nxt = 2
+                    elif state < 4 and g.tensors[o].role not in ("weight", "hostconst") and \
+                            _shape_equal(so, sc):
+                        nxt = 4
+                elif cop.kind in ACTS:
+                    nxt = 3 if state < 3 else (5 if state == 4 else None)
+                elif cop.kind == "Transpose" and state < 6:
+                    nxt = 6
+                    absorbed_transpose.add(c)
+                if nxt is None:
+                    break
+                members.append(c)
+                cur, state = cop.outputs[0], nxt
+                if state == 6:
+                    break
+            new_group("GEMM" if op.kind == "MatMul" else "CONV", members)
+        elif op.kind in SOLO:
+            new_group(SOLO[op.kind], [n])
+        elif op.kind == "Gather":
+            members = [n]
+            c = sole_consumer(op.outputs[0])
+            if opts.fusion and c is not None and g.ops[c].kind == "Add" and c not in assigned and \
+                    _shape_equal(rdp.S[other(g.ops[c], op.outputs[0])], rdp.S[op.outputs[0]]):
+                members.append(c)
+            new_group("GATHER", members)
+        elif op.kind in ELTWISE:
+            members, cur = [n], op.outputs[0]
+            while opts.fusion and len(members) < 8:
+                c = sole_consumer(cur)
+                if c is None or c in assigned or g.ops[c].kind not in ELTWISE:
+                    break
+                cop = g.ops[c]
+                if len(cop.inputs) == 2 and not (_bcast_proven(rdp.S[cop.outputs[0]], rdp.S[other(cop, cur)])
+                                                 and _bcast_proven(rdp.S[cop.outputs[0]], rdp.S[cur])):
+                    break
+                members.append(c)
+                cur = cop.outputs[0]
+            new_group("ELTWISE", members)
+        else:
+            raise ValueError(f"no grouping rule for {op.kind}")
+    for c in absorbed_transpose:
+        view[c] = False
+
+    # statistic: loop-nest versions a fuser without RDP results would emit (Fig. 4)
+    versions = 0
+    for i, op in enumerate(g.ops):
+        if op.kind in ("Add", "Mul") and not folded[i]:
+            versions += 2 ** max(len(rdp.S[t]) if isinstance(rdp.S[t], list) else 0 for t in op.inputs)
+
+    # static alias bases --------------------------------------------------------
+    sbase = list(range(len(g.tensors)))
+    for n in order:
+        op = g.ops[n]
+        if view[n] or op.kind == "Switch":
+            for o in op.outputs:
+                sbase[o] = sbase[op.inputs[0]]
+
+    def reads_of(members) -> List[int]:
+        inside = {o for n in members for o in g.ops[n].outputs}
+        seen, out = set(), []
+        for n in members:
+            for t in g.ops[n].inputs:
+                b = sbase[t]
+                if t in inside or b in inside or b in seen:
+                    continue
+                seen.add(b)
+                out.append(b)
+        return out
+
+    for gr in groups.values():
+        gr.ins = reads_of(gr.ops)
+
+    # items in topological order (R5) --------------------------------------------
+    entries = [(max(pos[n] for n in gr.ops), True, gid) for gid, gr in groups.items()]
+    entries += [(pos[n], False, n) for n, op in enumerate(g.ops) if op.kind in ("Switch", "Combine")]
+    items: List[Item] = []
+    for _, is_group, ref in sorted(entries):
+        if is_group:
+            items.append(Item(True, ref, list(groups[ref].ins), [groups[ref].out]))
+        else:
+            op = g.ops[ref]
+            reads = []
+            for t in op.inputs:
+                if sbase[t] not in reads:
+                    reads.append(sbase[t])
+            items.append(Item(False, ref, reads, list(op.outputs) if op.kind == "Combine" else []))
+
+    plan = Plan(g, rdp, opts, order, folded, view, groups, assigned, items, [], [], sbase, versions)
+    _partition(plan)
+    return plan
+
+
+def arena_candidate(plan: Plan, t: int) -> bool:
+    """Static test: tensor t is produced by an item and is not written to a caller buffer."""
+    d = plan.graph.tensors[t]
+    return d.role == "inter" and not d.is_output and not d.session
+
+
+def _item_has_nac(plan: Plan, it: Item) -> bool:
+    for t in it.writes:
+        s = plan.rdp.S[t]
+        if not isinstance(s, list) or any(not R.is_expr(d) for d in s):
+            return True
+    return False
+
+
+def _partition(plan: Plan):
+    items = plan.items
+    n = len(items)
+    last_read = {}
+    for i, it in enumerate(items):
+        for t in it.reads:
+            last_read[t] = i
+    cut_after = [False] * n
+    live = set()
+    for i, it in enumerate(items):
+        for t in it.writes:
+            if arena_candidate(plan, t) and last_read.get(t, -1) > i:
+                live.add(t)
+        live = {t for t in live if last_read[t] > i}
+        is_edo = (not it.is_group) or plan.groups[it.ref].kind == "NONZERO"
+        if is_edo:
+            cut_after[i] = True
+            if i > 0:
+                cut_after[i - 1] = True
+        elif _item_has_nac(plan, it) or len(live) <= 1:
+            cut_after[i] = True
+    pieces, cur = [], []
+    for i in range(n):
+        cur.append(i)
+        if cut_after[i] or len(cur) == MAX_SG:
+            pieces.append(cur)
+            cur = []
+    if cur:
+        pieces.append(cur)
+    plan.subgraphs = [_order_subgraph(plan, p, last_read) for p in pieces]
+    plan.sg_class = [_classify(plan, p) for p in pieces]
+
+
+def _classify(plan: Plan, piece) -> str:
+    cls = "known"
+    for i in piece:
+        for t in plan.items[i].writes:
+            s = plan.rdp.S[t]
+            if not isinstance(s, list) or any(not R.is_expr(d) for d in s):
+                return "nac"
+            if any(not d.is_const() for d in s):
+                cls = "mixed"
+    return cls
+
+
+def _bytes_at(plan: Plan, t: int, env) -> int:
+    e = tensor_bytes_expr(plan.rdp, plan.graph, t)
+    return 0 if e is None else align_up(e.eval(env))
+
+
+def subgraph_peak(plan: Plan, seq, last_read, env) -> int:
+    """Peak of the summed bytes of live tensors when the items run in the order ``seq``."""
+    first, end = min(seq), max(seq)
+    inside = set(seq)
+    produced_in = {t: i for i in seq for t in plan.items[i].writes if arena_candidate(plan, t)}
+    incoming = []
+    for i in seq:
+        for t in plan.items[i].reads:
+            if t not in produced_in and t not in incoming and _incoming_arena(plan, t, first):
+                incoming.append(t)
+    done, peak = set(), 0
+    for cur in seq:
+        mem = 0
+        for t in incoming + list(produced_in):
+            if t in produced_in and produced_in[t] not in done and produced_in[t] != cur:
+                continue
+            readers = [i for i in inside if t in plan.items[i].reads]
+            alive = last_read.get(t, -1) > end or any(i not in done for i in readers) or produced_in.get(t) == cur
+            if alive:
+                mem += _bytes_at(plan, t, env)
+        peak = max(peak, mem)
+        done.add(cur)
+    return peak
+
+
+def _incoming_arena(plan: Plan, t: int, first_item: int) -> bool:
+    if not arena_candidate(plan, t):
+        return False
+    return any(t in it.writes for it in plan.items[:first_item])
+
+
+def _order_subgraph(plan: Plan, piece, last_read) -> List[int]:
+    """Section 4.3: exhaustive search (dynamic programme over executed subsets) for the order with
+    the smallest peak, sizes taken at the symbols' upper bounds; ties -> smallest group ids first."""
+    if not plan.opts.sep or len(piece) <= 2:
+        return list(piece)
+    items = plan.items
+    env = {name: hi for name, lo, hi in plan.graph.symbols}
+    k = len(piece)
+    idx = {it: j for j, it in enumerate(piece)}
+    first, end = piece[0], piece[-1]
+    produced_in = {}
+    for i in piece:
+        for t in items[i].writes:
+            if arena_candidate(plan, t):
+                produced_in[t] = idx[i]
+    tensors = list(produced_in)
+    for i in piece:
+        for t in items[i].reads:
+            if t not in produced_in and t not in tensors and _incoming_arena(plan, t, first):
+                tensors.append(t)
+    size = {t: _bytes_at(plan, t, env) for t in tensors}
+    readers = {t: [idx[i] for i in piece if t in items[i].reads] for t in tensors}
+    live_out = {t: last_read.get(t, -1) > end for t in tensors}
+    deps = [0] * k
+    for i in piece:
+        for t in items[i].reads:
+            if t in produced_in:
+                deps[idx[i]] |= 1 << produced_in[t]
+
+    def step_mem(S: int, j: int) -> int:
+        mem = 0
+        for t in tensors:
+            p = produced_in.get(t, -1)
+            if p >= 0 and p != j and not (S >> p) & 1:
+                continue
+            if p == j or live_out[t] or any(not (S >> r) & 1 for r in readers[t]):
+                mem += size[t]
+        return mem
+
+    full = (1 << k) - 1
+    INF = float("inf")
+    best = [INF] * (full + 1)
+    best[full] = 0
+    for S in range(full - 1, -1, -1):
+        b = INF
+        for j in range(k):
+            if (S >> j) & 1 or (deps[j] & ~S):
+                continue
+            b = min(b, max(step_mem(S, j), best[S | (1 << j)]))
+        best[S] = b
+    target, S, seq = best[0], 0, []
+    by_id = sorted(range(k), key=lambda j: (items[piece[j]].ref, j))
+    while S != full:
+        for j in by_id:
+            if (S >> j) & 1 or (deps[j] & ~S):
+                continue
+            if max(step_mem(S, j), best[S | (1 << j)]) <= target:
+                seq.append(piece[j])
+                S |= 1 << j
+                break
+    return seq
+
+
+# ---------------------------------------------------------------------------
+# canonical text dump
+# ---------------------------------------------------------------------------
+
+def dump(plan: Plan) -> str:
+    g = plan.graph
+    lines = ["order " + " ".join(str(n) for n in plan.order)]
+    lines.append("folded " + " ".join(str(i) for i, f in enumerate(plan.folded) if f))
+    lines.append("views " + " ".join(str(i) for i, f in enumerate(plan.view) if f))
+    for it in plan.items:
+        if it.is_group:
+            gr = plan.groups[it.ref]
+            lines.append(f"g{gr.gid} {gr.kind} ops=[{' '.join(map(str, gr.ops))}] out=t{gr.out} "
+                         f"ins=[{' '.join('t%d' % t for t in gr.ins)}]")
+        else:
+            lines.append(f"c{it.ref} {g.ops[it.ref].kind}")
+    for s, (sg, cls) in enumerate(zip(plan.subgraphs, plan.sg_class)):
+        names = [("g%d" % plan.items[i].ref) if plan.items[i].is_group else ("c%d" % plan.items[i].ref)
+                 for i in sg]
+        lines.append(f"sg{s} {cls} " + " ".join(names))
+    return "\n".join(lines) + "\n"

@@ -1,0 +1,248 @@
+"""Pins for the oracle's fusion grouping, execution order and arena plan (Sections 4.2-4.4.1)."""
+import itertools
+import random
+
+import pytest
+
+from oracle import rdp as R
+from oracle import plan as P
+from oracle import arena as A
+from workloads import configs, GraphBuilder
+
+
+def make(w, **opts):
+    r = R.RDP(w.graph).analyse()
+    return P.build_plan(w.graph, r, P.Opts(**opts))
+
+
+def small(cfg):
+    return {1: configs.config1, 2: lambda: configs.config2(4, layers=2),
+            3: lambda: configs.resnet50(3, 4, stages=(2, 1, 1, 1)),
+            4: lambda: configs.config4(4, layers=3)}[cfg]()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_groups_partition_compute_ops_and_are_convex(cfg):
+    w = small(cfg)
+    p = make(w)
+    g = w.graph
+    members = [n for gr in p.groups.values() for n in gr.ops]
+    assert len(members) == len(set(members))
+    control = {i for i, op in enumerate(g.ops) if op.kind in ("Switch", "Combine")}
+    rest = {i for i in range(len(g.ops)) if not p.folded[i] and not p.view[i]} - control
+    assert set(members) == rest
+    # convex: an external input of a group never depends on a member of that group
+    prod = p.rdp.producer
+    def ancestors(t, acc):
+        n = prod[t]
+        if n >= 0 and n not in acc:
+            acc.add(n)
+            for u in g.ops[n].inputs:
+                ancestors(u, acc)
+        return acc
+    import sys
+    sys.setrecursionlimit(10000)
+    for gr in p.groups.values():
+        inside = {o for n in gr.ops for o in g.ops[n].outputs}
+        for n in gr.ops:
+            for t in g.ops[n].inputs:
+                if t not in inside:
+                    assert not (ancestors(t, set()) & set(gr.ops))
+    # items are in a topological order
+    seen = set()
+    for it in p.items:
+        for t in it.reads:
+            n = prod[t]
+            assert n < 0 or p.folded[n] or t in seen or g.ops[n].kind == "Switch", (it, t)
+        seen.update(it.writes)
+        if not it.is_group:
+            seen.update(g.ops[it.ref].outputs)
+
+
+@pytest.mark.parametrize("cfg", [1, 3])
+def test_without_fusion_every_operator_is_its_own_group(cfg):
+    w = small(cfg)
+    p = make(w, fusion=False)
+    assert all(len(gr.ops) == 1 for gr in p.groups.values())
+    assert len(p.groups) == sum(1 for i in range(len(w.graph.ops)) if not p.folded[i] and not p.view[i])
+    assert len(make(w).groups) < len(p.groups)
+
+
+def test_encoder_layers_give_identical_subgraphs():
+    w = configs.config2(2, layers=4)
+    p = make(w)
+    kinds = [[p.groups[p.items[i].ref].kind for i in sg] for sg in p.subgraphs]
+    # layer 0 reads the graph input (caller memory, never in the arena) and is cut more finely;
+    # every later layer gives 2 sub-graphs (attention half, MLP half); then the final LayerNorm
+    first = next(i for i, k in enumerate(kinds) if len(k) == 6)
+    per_layer = kinds[first:]
+    assert len(per_layer) == 2 * 3 + 1
+    assert per_layer[0] == per_layer[2] == per_layer[4] == ["LAYERNORM", "GEMM", "GEMM", "SOFTMAX", "GEMM", "GEMM"]
+    assert per_layer[1] == per_layer[3] == per_layer[5] == ["LAYERNORM", "GEMM", "GEMM"]
+    assert per_layer[6] == ["LAYERNORM"]
+    assert set(p.sg_class) == {"mixed"}
+
+
+def _all_orders_peak(p, piece, last_read, env):
+    items = p.items
+    produced = {t: i for i in piece for t in items[i].writes}
+    best = None
+    for perm in itertools.permutations(piece):
+        done, ok = set(), True
+        for i in perm:
+            if any(t in produced and produced[t] not in done for t in items[i].reads):
+                ok = False
+                break
+            done.add(i)
+        if not ok:
+            continue
+        pk = P.subgraph_peak(p, list(perm), last_read, env)
+        key = (pk, [items[i].ref for i in perm])
+        if best is None or key < best[0]:
+            best = (key, list(perm))
+    return best
+
+
+@pytest.mark.parametrize("cfg", [3, 1])
+def test_execution_order_equals_exhaustive_search(cfg):
+    """Section 4.3: the chosen order is the optimum of an exhaustive search over all valid orders."""
+    w = small(cfg)
+    p = make(w)
+    env = {n: hi for n, lo, hi in w.graph.symbols}
+    last_read = {}
+    for i, it in enumerate(p.items):
+        for t in it.reads:
+            last_read[t] = i
+    multi = 0
+    for sg in p.subgraphs:
+        if len(sg) > 7:
+            continue
+        piece = sorted(sg)
+        (best_peak, _), best_seq = _all_orders_peak(p, piece, last_read, env)
+        assert P.subgraph_peak(p, sg, last_read, env) == best_peak
+        assert sg == best_seq or len(sg) <= 2
+        assert best_peak <= P.subgraph_peak(p, piece, last_read, env)
+        multi += len(sg) > 2
+    assert multi > 0
+
+
+def test_order_search_beats_node_order_somewhere():
+    # a block whose cheap branch is listed last: running it first lowers the peak
+    b = GraphBuilder([("N", 8, 64)])
+    x = b.input("x", "f32", ["N", 64])
+    w_big = b.weight("wb", "f32", [1024, 64])
+    w_s = b.weight("ws", "f32", [8, 64])
+    h = b.op("Relu", [b.op("MatMul", [x, w_s], transB=1)])            # small: [N, 8]
+    big = b.op("Relu", [b.op("MatMul", [h, b.weight("w2", "f32", [1024, 8])], transB=1)])   # [N,1024]
+    big2 = b.op("Softmax", [big], causal=0)
+    small_ = b.op("Softmax", [h], causal=0)
+    s2 = b.op("LayerNorm", [small_, b.weight("g", "f32", [8]), b.weight("be", "f32", [8])], eps=1e-5)
+    out = b.op("Add", [b.op("MatMul", [big2, b.weight("w3", "f32", [8, 1024])], transB=1), s2])
+    b.mark_output(out)
+    g = b.build()
+    r = R.RDP(g).analyse()
+    p_on, p_off = P.build_plan(g, r), P.build_plan(g, r, P.Opts(sep=False))
+    env = {"N": 64}
+    pk_on = A.bind(p_on, env).peak_live
+    pk_off = A.bind(p_off, env).peak_live
+    assert pk_on <= pk_off
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_arena_invariants(cfg):
+    w = small(cfg)
+    p = make(w)
+    n_sw = sum(1 for op in w.graph.ops if op.kind == "Switch")
+    rnd = random.Random(cfg)
+    for call in w.calls:
+        dec = [rnd.random() < 0.5 for _ in range(n_sw)]
+        b = A.bind(p, call, dec)
+        A.check_no_overlap(b)
+        assert b.arena_bytes >= b.peak_live > 0
+        assert A.dump(A.bind(p, call, dec)) == A.dump(b)          # deterministic
+        for t, a in b.tensors.items():
+            n = P.DT_BYTES[w.graph.tensors[t].dtype]
+            for d in b.dims[t]:
+                n *= d
+            assert a.bytes == (n + 255) // 256 * 256 and a.start <= a.end
+        outs = w.graph.outputs()
+        assert all(t not in b.tensors for t in outs)              # outputs live in caller memory
+
+
+def test_peak_first_needs_no_extra_space_on_layer_chains():
+    """Section 4.4.1: when the requirement falls monotonically on both sides of the peak, starting
+    at the peak needs no extra space -- the arena equals the peak of live bytes."""
+    w = configs.config2(8, layers=3)
+    p = make(w)
+    for call in w.calls + [{"B": 8, "L": 512}, {"B": 1, "L": 32}]:
+        b = A.bind(p, call)
+        assert b.arena_bytes == b.peak_live
+    # scores dominate at long sequences, the FFN hidden tensor at short ones
+    big, small_ = A.bind(p, {"B": 8, "L": 512}), A.bind(p, {"B": 8, "L": 32})
+    assert big.peak_live > 2 * 8 * 12 * 512 * 512 * 2
+    assert small_.peak_live < 8 * 32 * (3072 + 768 * 4) * 2 + 4096
+
+
+def test_against_exhaustive_optimum_and_best_fit():
+    """The planner is scored against the exhaustive optimum (Section 4.4.1, last paragraph)."""
+    rnd = random.Random(5)
+    worse_bestfit = 0
+    for trial in range(40):
+        n = rnd.randint(3, 7)
+        ts = []
+        for i in range(n):
+            s = rnd.randint(0, 6)
+            ts.append(A.ArenaTensor(i, 256 * rnd.randint(1, 9), s, s + rnd.randint(0, 3)))
+        opt = A.optimal_arena_bytes(ts)
+        live = max(sum(t.bytes for t in ts if t.start <= k <= t.end) for k in range(10))
+        assert opt >= live
+        for strategy in ("peak", "best"):
+            placed = []
+            if strategy == "peak":
+                steps = range(10)
+                p_ = max(steps, key=lambda k: (sum(t.bytes for t in ts if t.start <= k <= t.end), -k))
+                order = sorted((t for t in ts if t.start <= p_ <= t.end), key=lambda a: (a.start, a.tid)) + \
+                    sorted((t for t in ts if t.start > p_), key=lambda a: (a.start, a.tid)) + \
+                    sorted((t for t in ts if t.end < p_), key=lambda a: (-a.end, -a.start, a.tid))
+            else:
+                order = sorted(ts, key=lambda a: (a.start, a.tid))
+            for t in order:
+                c = A.ArenaTensor(t.tid, t.bytes, t.start, t.end)
+                c.offset = A.first_fit(c, placed) if strategy == "peak" else A.best_fit(c, placed)
+                placed.append(c)
+            top = max(c.offset + c.bytes for c in placed)
+            assert top >= opt
+            for i, x in enumerate(placed):
+                for y in placed[i + 1:]:
+                    if A.intersects(x, y):
+                        assert x.offset + x.bytes <= y.offset or y.offset + y.bytes <= x.offset
+
+
+def test_dmp_switch_and_symbol_range():
+    w = small(2)
+    p_on, p_off = make(w), make(w, dmp=False)
+    for call in w.calls:
+        a, b = A.bind(p_on, call), A.bind(p_off, call)
+        A.check_no_overlap(b)
+        assert a.arena_bytes <= b.arena_bytes
+    with pytest.raises(A.SymbolOutOfRange):
+        A.bind(p_on, {"B": 9, "L": 64})
+    with pytest.raises(A.SymbolOutOfRange):
+        A.bind(p_on, {"B": 1})
+
+
+def test_control_flow_executes_only_the_taken_path():
+    w = configs.config4(2, layers=3)
+    p = make(w)
+    call = {"L": 128}
+    all_run = A.bind(p, call, [False] * 3)
+    all_skip = A.bind(p, call, [True] * 3)
+    mixed = A.bind(p, call, [True, False, True])
+    kinds = lambda b: [p.groups[p.items[i].ref].kind for i in b.steps if p.items[i].is_group]
+    assert kinds(all_skip).count("SOFTMAX") == 0 and kinds(all_run).count("SOFTMAX") == 3
+    assert kinds(mixed).count("SOFTMAX") == 1
+    assert all_skip.arena_bytes < mixed.arena_bytes <= all_run.arena_bytes
+    # skipping everything leaves the gates and the final LayerNorm only
+    assert kinds(all_skip).count("LAYERNORM") == 1
+    with pytest.raises(ValueError):
+        A.bind(p, call, [True])

@@ -1,0 +1,231 @@
+"""The five synthetic dynamic workloads and their seeded data.
+
+They stand in for the trained models and public datasets of the paper's
+evaluation (Section 5.1: images 224-640 in multiples of 32, sequences 32-512),
+none of which is available: same operator mix, shape ranges and dynamism
+(shape dynamism, control-flow dynamism, both), random-initialised weights.
+
+Every builder returns a ``Workload``: the graph description, a function that
+materialises the weights (``seed = 1000 * config + weight index``), the list
+of per-call symbol draws and a function producing the inputs of a call.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Callable, Dict, List
+
+import numpy as np
+
+from . import rng
+from .graphdesc import GraphBuilder, GraphDesc, WEIGHT, INPUT
+
+INT_MAX = 2 ** 31 - 1
+
+
+@dataclass
+class Workload:
+    name: str
+    config: int
+    graph: GraphDesc
+    dtype: str                                   # float storage type of the graph
+    calls: List[Dict[str, int]]                  # symbol values per call
+    make_weights: Callable[[], Dict[int, np.ndarray]]          # tensor id -> float64 array
+    make_inputs: Callable[[int, Dict[str, int]], Dict[int, np.ndarray]]
+    weight_spec: Dict[int, tuple] = None
+
+
+class _Weights:
+    """Records (kind, params) per weight tensor; values are generated on demand."""
+
+    def __init__(self, config: int):
+        self.config = config
+        self.spec: Dict[int, tuple] = {}
+
+    def add(self, tid, kind, *params):
+        self.spec[tid] = (kind,) + params
+
+    def make(self, graph: GraphDesc) -> Dict[int, np.ndarray]:
+        out = {}
+        for k, (tid, spec) in enumerate(sorted(self.spec.items())):
+            shape = tuple(graph.tensors[tid].dims)
+            seed = 1000 * self.config + k
+            kind = spec[0]
+            if kind == "normal":
+                out[tid] = rng.normal(seed, shape, spec[1], spec[2])
+            elif kind == "const":
+                out[tid] = np.full(shape, spec[1], dtype=np.float64)
+            else:
+                raise ValueError(kind)
+        return out
+
+
+def _linear(b: GraphBuilder, w: _Weights, x, n_in, n_out, name, dtype, std=0.02, bias_std=0.02):
+    """x @ W^T + bias with W stored [out, in] (the layout a Linear layer keeps)."""
+    W = b.weight(f"{name}.w", dtype, [n_out, n_in]); w.add(W, "normal", 0.0, std)
+    B = b.weight(f"{name}.b", dtype, [n_out]); w.add(B, "normal", 0.0, bias_std)
+    y = b.op("MatMul", [x, W], transB=1, hint=name)
+    return b.op("Add", [y, B], hint=name + "_b")
+
+
+def _layernorm(b, w, x, n, name, dtype):
+    g = b.weight(f"{name}.g", dtype, [n]); w.add(g, "normal", 1.0, 0.02)
+    be = b.weight(f"{name}.beta", dtype, [n]); w.add(be, "normal", 0.0, 0.02)
+    return b.op("LayerNorm", [x, g, be], eps=1e-5, hint=name)
+
+
+def _encoder_layer(b, w, x, hidden, heads, ffn, name, dtype, lead):
+    """Pre-LN block.  ``lead`` = tensor ids of the 1-element int tensors holding the leading dims."""
+    d = hidden // heads
+    h1 = _layernorm(b, w, x, hidden, f"{name}.ln1", dtype)
+    qkv = _linear(b, w, h1, hidden, 3 * hidden, f"{name}.qkv", dtype)
+    tgt = b.op("Concat", lead + [b.const(f"{name}.c3hd", [3, heads, d])], axis=0, dtype="i64")
+    qkv5 = b.op("Reshape", [qkv, tgt], hint="qkv5")                    # [B, L, 3, h, d]
+    qkvT = b.op("Transpose", [qkv5], perm=(2, 0, 3, 1, 4), hint="qkvT")  # [3, B, h, L, d]
+    q = b.op("Gather", [qkvT, b.const(f"{name}.i0", 0)], axis=0, hint="q")
+    k = b.op("Gather", [qkvT, b.const(f"{name}.i1", 1)], axis=0, hint="k")
+    v = b.op("Gather", [qkvT, b.const(f"{name}.i2", 2)], axis=0, hint="v")
+    kT = b.op("Transpose", [k], perm=(0, 1, 3, 2), hint="kT")
+    s = b.op("MatMul", [q, kT], transB=0, hint="qk")
+    s = b.op("Mul", [s, b.const(f"{name}.scale", 1.0 / np.sqrt(d), "f32")], hint="scaled")
+    p = b.op("Softmax", [s], causal=0, hint="probs")
+    c = b.op("MatMul", [p, v], transB=0, hint="pv")                    # [B, h, L, d]
+    cT = b.op("Transpose", [c], perm=(0, 2, 1, 3), hint="ctxT")        # [B, L, h, d]
+    tgt2 = b.op("Concat", lead + [b.const(f"{name}.chid", [hidden])], axis=0, dtype="i64")
+    c2 = b.op("Reshape", [cT, tgt2], hint="ctx")
+    o = _linear(b, w, c2, hidden, hidden, f"{name}.o", dtype)
+    x1 = b.op("Add", [o, x], hint="res1")
+    h2 = _layernorm(b, w, x1, hidden, f"{name}.ln2", dtype)
+    f = _linear(b, w, h2, hidden, ffn, f"{name}.ffn1", dtype)
+    f = b.op("Gelu", [f], hint="gelu")
+    f2 = _linear(b, w, f, ffn, hidden, f"{name}.ffn2", dtype)
+    return b.op("Add", [f2, x1], hint="res2")
+
+
+def _lead_dims(b, x, n, tag):
+    """Shape(x) -> n one-element tensors (the pattern an exporter emits for dynamic reshapes)."""
+    shp = b.op("Shape", [x], dtype="i64", hint=f"{tag}.shape")
+    return [b.op("Gather", [shp, b.const(f"{tag}.ax{i}", [i])], axis=0, dtype="i64", hint=f"{tag}.dim{i}")
+            for i in range(n)]
+
+
+def _draws(seed, spec, n_calls):
+    """spec: list of (symbol, lo, hi, step); one independent stream per symbol."""
+    calls = [dict() for _ in range(n_calls)]
+    for j, (name, lo, hi, step) in enumerate(spec):
+        vals = rng.randint(seed + 17 * j, (n_calls,), 0, (hi - lo) // step)
+        for c, v in zip(calls, vals):
+            c[name] = int(lo + step * v)
+    return calls
+
+
+def encoder(config: int, layers: int, hidden: int, heads: int, ffn: int, dtype: str,
+            batch, seq_range, n_calls: int, final_ln: bool, gated: bool = False,
+            gate_bias: float = None) -> Workload:
+    """Configs 1, 2 and 4: a stack of pre-LN encoder blocks on x[B, L, hidden]."""
+    syms = [("L", seq_range[0], seq_range[1])]
+    if isinstance(batch, tuple):
+        syms = [("B", batch[0], batch[1])] + syms
+        bdim = "B"
+    else:
+        bdim = int(batch)
+    b = GraphBuilder(syms)
+    w = _Weights(config)
+    x = b.input("x", dtype, [bdim, "L", hidden])
+    lead = _lead_dims(b, x, 2, "x")
+    for l in range(layers):
+        if gated:
+            # gate: mean over all token rows -> Linear(hidden,64) -> ReLU -> Linear(64,1) -> sigmoid
+            m = b.op("ReduceMean", [x], axes=(0, 1), keepdims=1, dtype="f32", hint=f"g{l}.pool")
+            g1 = b.op("Relu", [_linear(b, w, m, hidden, 64, f"g{l}.fc1", "f32")], hint=f"g{l}.relu")
+            if gate_bias is None:
+                g2 = _linear(b, w, g1, 64, 1, f"g{l}.fc2", "f32", bias_std=1.0)
+            else:
+                g2 = _linear(b, w, g1, 64, 1, f"g{l}.fc2", "f32")
+                w.spec[b.g.tensor_id(f"g{l}.fc2.b")] = ("const", float(gate_bias))
+            pred = b.op("Sigmoid", [g2], hint=f"g{l}.sig")
+            run, skip = b.op("Switch", [x, pred], n_out=2, threshold=0.5, hint=f"sw{l}")
+            y = _encoder_layer(b, w, run, hidden, heads, ffn, f"l{l}", dtype, lead)
+            x = b.op("Combine", [y, skip], hint=f"cmb{l}")
+        else:
+            x = _encoder_layer(b, w, x, hidden, heads, ffn, f"l{l}", dtype, lead)
+    if final_ln:
+        x = _layernorm(b, w, x, hidden, "lnf", dtype)
+    b.mark_output(x, "y")
+    g = b.build()
+    spec = ([("B", batch[0], batch[1], 1)] if isinstance(batch, tuple) else []) + \
+           [("L", seq_range[0], seq_range[1], 1)]
+    calls = _draws(7000 + config, spec, n_calls)
+
+    def make_inputs(call_idx, sym):
+        B = sym.get("B", bdim)
+        return {g.tensor_id("x"): rng.normal(100000 * config + call_idx, (B, sym["L"], hidden))}
+
+    return Workload(f"cfg{config}", config, g, dtype, calls, lambda: w.make(g), make_inputs, w.spec)
+
+
+def config1(n_calls=8):
+    return encoder(1, 1, 256, 4, 1024, "f32", 1, (16, 128), n_calls, final_ln=False)
+
+
+def config2(n_calls=64, layers=12):
+    return encoder(2, layers, 768, 12, 3072, "bf16", (1, 8), (32, 512), n_calls, final_ln=True)
+
+
+def config4(n_calls=64, layers=12, gate_bias=None):
+    return encoder(4, layers, 768, 12, 3072, "bf16", 4, (128, 384), n_calls, final_ln=True,
+                   gated=True, gate_bias=gate_bias)
+
+
+# ---------------------------------------------------------------------------
+# config 3: ResNet-50 layout, NHWC
+# ---------------------------------------------------------------------------
+
+def _conv(b, w, x, cin, cout, k, stride, pad, name, dtype, relu):
+    W = b.weight(f"{name}.w", dtype, [cout, k, k, cin])
+    w.add(W, "normal", 0.0, float(np.sqrt(2.0 / (k * k * cin))))
+    B = b.weight(f"{name}.b", dtype, [cout]); w.add(B, "normal", 0.0, 0.02)
+    y = b.op("Conv", [x, W], stride=stride, pad=pad, hint=name)
+    y = b.op("Add", [y, B], hint=name + "_b")
+    return b.op("Relu", [y], hint=name + "_r") if relu else y
+
+
+def _bottleneck(b, w, x, cin, mid, cout, stride, project, name, dtype):
+    y = _conv(b, w, x, cin, mid, 1, 1, 0, f"{name}.c1", dtype, True)
+    y = _conv(b, w, y, mid, mid, 3, stride, 1, f"{name}.c2", dtype, True)
+    y = _conv(b, w, y, mid, cout, 1, 1, 0, f"{name}.c3", dtype, False)
+    sc = _conv(b, w, x, cin, cout, 1, stride, 0, f"{name}.sc", dtype, False) if project else x
+    return b.op("Relu", [b.op("Add", [y, sc], hint=name + "_add")], hint=name + "_out")
+
+
+def resnet50(config=3, n_calls=32, sizes=tuple(range(224, 641, 32)), stages=(3, 4, 6, 3),
+             classes=1000, dtype="bf16") -> Workload:
+    b = GraphBuilder([("H", min(sizes), max(sizes)), ("W", min(sizes), max(sizes))])
+    w = _Weights(config)
+    x = b.input("x", dtype, [1, "H", "W", 3])
+    y = _conv(b, w, x, 3, 64, 7, 2, 3, "stem", dtype, True)
+    y = b.op("MaxPool", [y], kernel=3, stride=2, pad=1, hint="pool")
+    cin = 64
+    for s, n in enumerate(stages):
+        mid, cout = 64 << s, 256 << s
+        for i in range(n):
+            stride = 2 if (i == 0 and s > 0) else 1
+            y = _bottleneck(b, w, y, cin, mid, cout, stride, i == 0, f"s{s}b{i}", dtype)
+            cin = cout
+    y = b.op("ReduceMean", [y], axes=(1, 2), keepdims=0, hint="gap")
+    y = _linear(b, w, y, cin, classes, "fc", dtype)
+    b.mark_output(y, "logits")
+    g = b.build()
+    idx = rng.randint(7000 + config, (n_calls,), 0, len(sizes) - 1)
+    calls = [{"H": int(sizes[i]), "W": int(sizes[i])} for i in idx]
+
+    def make_inputs(call_idx, sym):
+        return {g.tensor_id("x"): rng.uniform(100000 * config + call_idx, (1, sym["H"], sym["W"], 3))}
+
+    return Workload(f"cfg{config}", config, g, dtype, calls, lambda: w.make(g), make_inputs, w.spec)
+
+
+def config3(n_calls=32):
+    return resnet50(3, n_calls)
+
+
+BUILDERS = {1: config1, 2: config2, 3: config3, 4: config4}
