@@ -1,0 +1,202 @@
+/*
+ * sod2.h -- C ABI of the MI355X-native SoD2 hot path.
+ *
+ * The library executes a dynamic DNN whose tensor shapes are symbolic
+ * expressions resolved by Rank and Dimension Propagation (RDP), as fused
+ * operator groups over a pre-planned memory arena (Sections 4.1 - 4.4 of the
+ * SoD2 paper).  Five calls form the path:
+ *
+ *   sod2_graph_build  extended computational graph G (Section 4.1, item G;
+ *                     operator classes of Section 3, Table 2)
+ *   sod2_rdp_infer    RDP fixed point (Alg. 1, Tables 3 and 4)
+ *   sod2_plan         fusion groups (4.2), sub-graph partition and static
+ *                     execution order (4.3), kernel-version rules (4.4.2)
+ *   sod2_bind         per input: evaluate the symbols, peak-first arena
+ *                     offsets (4.4.1), kernel version and launch geometry
+ *   sod2_run          launch the fused HIP kernels on a stream
+ *
+ * Conventions
+ *   - All handles are opaque, host side, owned by the library until the
+ *     matching *_destroy.  Handles are not thread safe.
+ *   - Every pointer named "host" is host memory read during the call only.
+ *     Device pointers (arena, weights, inputs, outputs) are owned by the
+ *     caller; the library never allocates or frees device memory in sod2_run.
+ *   - Every function returns a sod2_status; on failure out-parameters are
+ *     untouched and sod2_last_error() describes the failure (thread local).
+ */
+#ifndef SOD2_H
+#define SOD2_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t sod2_status;
+enum {
+  SOD2_OK = 0,
+  SOD2_ERR_INVALID_ARG = -1,
+  SOD2_ERR_SYMBOL_OUT_OF_RANGE = -2,
+  SOD2_ERR_SHAPE_MISMATCH = -3,   /* producer and consumer disagree on a known constant */
+  SOD2_ERR_UNRESOLVED_SHAPE = -4, /* a nac dim reaches a point that needs its value */
+  SOD2_ERR_ARENA_TOO_SMALL = -5,
+  SOD2_ERR_UNSUPPORTED = -6,
+  SOD2_ERR_HIP = -7,
+  SOD2_ERR_BUFFER_TOO_SMALL = -8,
+  SOD2_ERR_NONCAUSAL_PLAN = -9    /* offsets used before a Switch differ from the final plan */
+};
+
+enum { SOD2_F32 = 0, SOD2_BF16 = 1, SOD2_I64 = 2, SOD2_I32 = 3 };
+enum { SOD2_INTER = 0, SOD2_INPUT = 1, SOD2_WEIGHT = 2, SOD2_HOSTCONST = 3 };
+
+/* Operator kinds (ONNX names, Table 2, plus the <Switch, Combine> pair). */
+enum {
+  SOD2_OP_SHAPE = 0, SOD2_OP_GATHER, SOD2_OP_CONCAT, SOD2_OP_RESHAPE, SOD2_OP_SLICE,
+  SOD2_OP_TRANSPOSE, SOD2_OP_MATMUL, SOD2_OP_CONV, SOD2_OP_ADD, SOD2_OP_MUL, SOD2_OP_RELU,
+  SOD2_OP_GELU, SOD2_OP_SIGMOID, SOD2_OP_CAST, SOD2_OP_SOFTMAX, SOD2_OP_LAYERNORM,
+  SOD2_OP_REDUCEMEAN, SOD2_OP_MAXPOOL, SOD2_OP_ARGMAX, SOD2_OP_CACHEAPPEND, SOD2_OP_NONZERO,
+  SOD2_OP_SWITCH, SOD2_OP_COMBINE, SOD2_OP_COUNT
+};
+
+#define SOD2_MAX_RANK 8
+
+typedef struct {
+  const char* name;          /* host, copied */
+  int32_t dtype;             /* SOD2_F32 ... */
+  int32_t role;              /* SOD2_INTER ... */
+  int32_t rank;              /* -1: shape undeclared, to be inferred by RDP */
+  const char* const* dims;   /* rank strings: an integer, a symbol name, or a '+' sum of those */
+  const void* host_data;     /* HOSTCONST only: int64 / int32 / float32 values, copied */
+  int64_t host_count;        /* number of elements of host_data */
+  int32_t is_output;         /* written to the caller's output buffer instead of the arena */
+  int32_t session;           /* persists across calls (a KV cache): placed first in the arena */
+  const char* const* capacity_dims; /* session only: dims the storage is sized for, else NULL */
+} sod2_tensor_desc;
+
+/* Integer attributes per kind, in this order:
+ *   Gather/Concat: axis.  Transpose: the permutation.  MatMul: transB.  Conv: stride, pad.
+ *   Softmax: causal.  ReduceMean: keepdims, then the axes.  MaxPool: kernel, stride, pad.
+ * Float attribute: LayerNorm epsilon; Switch threshold.                                         */
+typedef struct {
+  int32_t kind;
+  int32_t n_inputs;
+  const int32_t* inputs;     /* tensor ids */
+  int32_t n_outputs;
+  const int32_t* outputs;
+  int32_t n_iattr;
+  const int64_t* iattr;
+  double fattr;
+} sod2_op_desc;
+
+typedef struct {
+  int32_t n_symbols;
+  const char* const* symbol_names;
+  const int64_t* symbol_lo;  /* declared range of each symbol, both ends included */
+  const int64_t* symbol_hi;
+  int32_t n_tensors;
+  const sod2_tensor_desc* tensors;
+  int32_t n_ops;
+  const sod2_op_desc* ops;
+} sod2_graph_desc;
+
+/* The four optimisation switches the paper's breakdown study names (Section 5.3). */
+typedef struct {
+  int32_t fusion;  /* RDP-enabled fusion; 0: one group per operator                       */
+  int32_t sep;     /* static execution planning; 0: node order                            */
+  int32_t dmp;     /* peak-first arena plan; 0: best-fit greedy in execution order        */
+  int32_t mvc;     /* multi-version kernels; 0: always the regular version                */
+} sod2_plan_opts;
+
+typedef struct sod2_graph_s sod2_graph_t;
+typedef struct sod2_rdp_s sod2_rdp_t;
+typedef struct sod2_plan_s sod2_plan_t;
+typedef struct sod2_binding_s sod2_binding_t;
+
+/* -- graph (Section 4.1, G; Section 3 classes) -------------------------------------------- */
+sod2_status sod2_graph_build(const sod2_graph_desc* desc_host, sod2_graph_t** out);
+void sod2_graph_destroy(sod2_graph_t*);
+/* class of operator op: 0 ISDO, 1 ISDOS, 2 ISVDOS, 3 EDO (Table 2) */
+sod2_status sod2_graph_op_class(const sod2_graph_t*, int32_t op, int32_t* cls);
+
+/* -- RDP (Alg. 1) ------------------------------------------------------------------------- */
+sod2_status sod2_rdp_infer(const sod2_graph_t*, sod2_rdp_t** out);
+/* same analysis visiting the operators in the given order (a permutation of 0..n_ops-1);
+ * the fixed point must not depend on it (Section 4.1, lattice argument) */
+sod2_status sod2_rdp_infer_ordered(const sod2_graph_t*, const int32_t* order_host, int32_t n, sod2_rdp_t** out);
+void sod2_rdp_destroy(sod2_rdp_t*);
+typedef struct {
+  int32_t cls;        /* 0 known constant, 1 symbolic constant, 2 operation-inferred, 3 nac */
+  int64_t value;      /* cls 0 only */
+  char expr[120];     /* canonical expression text (truncated if longer) */
+} sod2_dim_info;
+/* rank = -1 when the whole shape is nac; dims must hold SOD2_MAX_RANK entries */
+sod2_status sod2_rdp_query(const sod2_rdp_t*, int32_t tensor, int32_t* rank, sod2_dim_info* dims);
+sod2_status sod2_rdp_sweeps(const sod2_rdp_t*, int32_t* sweeps);
+/* canonical text of all S- and V-maps.  Writes at most cap bytes (NUL terminated), stores the
+ * full length in *needed; returns SOD2_ERR_BUFFER_TOO_SMALL when cap was not enough. */
+sod2_status sod2_rdp_dump(const sod2_rdp_t*, char* buf_host, size_t cap, size_t* needed);
+
+/* -- plan (Sections 4.2, 4.3, 4.4.2) -------------------------------------------------------- */
+sod2_status sod2_plan(const sod2_graph_t*, const sod2_rdp_t*, const sod2_plan_opts* opts_host /* NULL: all on */,
+                      sod2_plan_t** out);
+void sod2_plan_destroy(sod2_plan_t*);
+sod2_status sod2_plan_counts(const sod2_plan_t*, int32_t* n_groups, int32_t* n_subgraphs, int32_t* n_switches);
+sod2_status sod2_plan_dump(const sod2_plan_t*, char* buf_host, size_t cap, size_t* needed);
+
+/* -- bind (Section 4.4.1) ------------------------------------------------------------------- */
+/* symbol_values_host: one value per declared symbol, in declaration order.  For graphs with
+ * Switch operators the arena plan depends on the decisions; sod2_bind plans as if every branch
+ * ran and sod2_run re-plans after each decision (Section 4.3: a sub-graph after an
+ * execution-determined operator is planned once that operator has executed). */
+sod2_status sod2_bind(const sod2_plan_t*, const int64_t* symbol_values_host, int32_t n_symbols, sod2_binding_t** out);
+/* pure planning with a given decision vector (1 = the skip output of the Switch is taken); no run */
+sod2_status sod2_bind_decided(const sod2_plan_t*, const int64_t* symbol_values_host, int32_t n_symbols,
+                              const int32_t* decisions_host, int32_t n_decisions, sod2_binding_t** out);
+void sod2_binding_destroy(sod2_binding_t*);
+/* bytes the arena passed to sod2_run must have; peak of summed live tensor bytes */
+sod2_status sod2_binding_arena_bytes(const sod2_binding_t*, size_t* arena_bytes, size_t* peak_live_bytes);
+sod2_status sod2_binding_dump(const sod2_binding_t*, char* buf_host, size_t cap, size_t* needed);
+/* force the decisions of the next runs (replay of a reference decision vector); n = 0 clears */
+sod2_status sod2_binding_force_decisions(sod2_binding_t*, const int32_t* decisions_host, int32_t n);
+/* force one kernel version for every contraction: -1 automatic, 0 regular, 1 fat, 2 skinny */
+sod2_status sod2_binding_force_variant(sod2_binding_t*, int32_t variant);
+
+/* -- run -------------------------------------------------------------------------------------- */
+/* arena: device memory, 256-byte aligned, at least arena_bytes long.  weights / inputs / outputs:
+ * host arrays of device pointers, one per tensor with that role, ordered by tensor id.
+ * hip_stream: a hipStream_t (NULL = the null stream).  Enqueues and returns; synchronises the
+ * stream only at a Switch, whose predicate is read back to the host. */
+sod2_status sod2_run(sod2_binding_t*, void* arena_dev, size_t arena_bytes,
+                     const void* const* weights_dev, int32_t n_weights,
+                     const void* const* inputs_dev, int32_t n_inputs,
+                     void* const* outputs_dev, int32_t n_outputs, void* hip_stream);
+/* decisions taken by the last run, in execution order; *n receives their count */
+sod2_status sod2_run_decisions(const sod2_binding_t*, int32_t* decisions_host, int32_t cap, int32_t* n);
+
+/* plan actually executed by the last run (differs from the bind-time plan only with Switches):
+ * same text format as sod2_binding_dump; arena bytes and live peak of the executed path */
+sod2_status sod2_run_plan_dump(const sod2_binding_t*, char* buf_host, size_t cap, size_t* needed);
+sod2_status sod2_run_arena_bytes(const sod2_binding_t*, size_t* arena_bytes, size_t* peak_live_bytes);
+
+/* per-launch records of the last run (filled when profiling is on: two events per launch) */
+typedef struct {
+  int32_t group;       /* group id */
+  int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other */
+  int32_t variant;
+  int32_t reserved;
+  float ms;            /* event-to-event duration */
+  double flops;        /* algorithmic floating-point operations of the group */
+  double bytes;        /* algorithmic bytes: every operand read once, the result written once */
+} sod2_launch_record;
+sod2_status sod2_binding_set_profiling(sod2_binding_t*, int32_t on);
+sod2_status sod2_binding_launch_records(const sod2_binding_t*, sod2_launch_record* recs_host, int32_t cap, int32_t* n);
+
+const char* sod2_last_error(void);
+const char* sod2_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SOD2_H */

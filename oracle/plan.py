@@ -387,11 +387,12 @@ def _order_subgraph(plan: Plan, piece, last_read) -> List[int]:
     size = {t: _bytes_at(plan, t, env) for t in tensors}
     readers = {t: [idx[i] for i in piece if t in items[i].reads] for t in tensors}
     live_out = {t: last_read.get(t, -1) > end for t in tensors}
+    writer = {t: idx[i] for i in piece for t in items[i].writes}    # includes graph outputs
     deps = [0] * k
     for i in piece:
         for t in items[i].reads:
-            if t in produced_in:
-                deps[idx[i]] |= 1 << produced_in[t]
+            if t in writer:
+                deps[idx[i]] |= 1 << writer[t]
 
     def step_mem(S: int, j: int) -> int:
         mem = 0
@@ -433,9 +434,9 @@ def _order_subgraph(plan: Plan, piece, last_read) -> List[int]:
 
 def dump(plan: Plan) -> str:
     g = plan.graph
-    lines = ["order " + " ".join(str(n) for n in plan.order)]
-    lines.append("folded " + " ".join(str(i) for i, f in enumerate(plan.folded) if f))
-    lines.append("views " + " ".join(str(i) for i, f in enumerate(plan.view) if f))
+    lines = ["order" + "".join(f" {n}" for n in plan.order)]
+    lines.append("folded" + "".join(f" {i}" for i, f in enumerate(plan.folded) if f))
+    lines.append("views" + "".join(f" {i}" for i, f in enumerate(plan.view) if f))
     for it in plan.items:
         if it.is_group:
             gr = plan.groups[it.ref]

@@ -1,0 +1,346 @@
+"""Python binding of libsod2 (argument marshalling only; every step runs in the library).
+
+The functions carry the names of the C entry points (see include/sod2.h):
+sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run and the queries.
+The library must have been built (``python -m paper_2403_00176_amd.build`` or
+``__graft_entry__.build()``); importing fails loudly otherwise.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsod2.so")
+if not os.path.exists(LIB_PATH):
+    raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2403_00176_amd.build`")
+_lib = C.CDLL(LIB_PATH)
+
+DTYPES = {"f32": 0, "bf16": 1, "i64": 2, "i32": 3}
+ROLES = {"inter": 0, "input": 1, "weight": 2, "hostconst": 3}
+OP_KINDS = ["Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul",
+            "Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax",
+            "CacheAppend", "NonZero", "Switch", "Combine"]
+OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
+
+EXPORTS = [
+    "sod2_graph_build", "sod2_graph_destroy", "sod2_graph_op_class", "sod2_rdp_infer", "sod2_rdp_infer_ordered",
+    "sod2_rdp_destroy", "sod2_rdp_query", "sod2_rdp_sweeps", "sod2_rdp_dump", "sod2_plan", "sod2_plan_destroy",
+    "sod2_plan_counts", "sod2_plan_dump", "sod2_bind", "sod2_bind_decided", "sod2_binding_destroy",
+    "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_force_decisions", "sod2_binding_force_variant",
+    "sod2_run", "sod2_run_decisions", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
+    "sod2_binding_launch_records", "sod2_last_error", "sod2_version",
+]
+
+
+class Sod2Error(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"sod2 error {code}: {msg}")
+        self.code = code
+
+
+class _TensorDesc(C.Structure):
+    _fields_ = [("name", C.c_char_p), ("dtype", C.c_int32), ("role", C.c_int32), ("rank", C.c_int32),
+                ("dims", C.POINTER(C.c_char_p)), ("host_data", C.c_void_p), ("host_count", C.c_int64),
+                ("is_output", C.c_int32), ("session", C.c_int32), ("capacity_dims", C.POINTER(C.c_char_p))]
+
+
+class _OpDesc(C.Structure):
+    _fields_ = [("kind", C.c_int32), ("n_inputs", C.c_int32), ("inputs", C.POINTER(C.c_int32)),
+                ("n_outputs", C.c_int32), ("outputs", C.POINTER(C.c_int32)), ("n_iattr", C.c_int32),
+                ("iattr", C.POINTER(C.c_int64)), ("fattr", C.c_double)]
+
+
+class _GraphDesc(C.Structure):
+    _fields_ = [("n_symbols", C.c_int32), ("symbol_names", C.POINTER(C.c_char_p)),
+                ("symbol_lo", C.POINTER(C.c_int64)), ("symbol_hi", C.POINTER(C.c_int64)),
+                ("n_tensors", C.c_int32), ("tensors", C.POINTER(_TensorDesc)),
+                ("n_ops", C.c_int32), ("ops", C.POINTER(_OpDesc))]
+
+
+class PlanOpts(C.Structure):
+    _fields_ = [("fusion", C.c_int32), ("sep", C.c_int32), ("dmp", C.c_int32), ("mvc", C.c_int32)]
+
+
+class DimInfo(C.Structure):
+    _fields_ = [("cls", C.c_int32), ("value", C.c_int64), ("expr", C.c_char * 120)]
+
+
+class LaunchRecord(C.Structure):
+    _fields_ = [("group", C.c_int32), ("kernel", C.c_int32), ("variant", C.c_int32), ("reserved", C.c_int32),
+                ("ms", C.c_float), ("flops", C.c_double), ("bytes", C.c_double)]
+
+
+KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other"]
+
+_lib.sod2_last_error.restype = C.c_char_p
+_lib.sod2_version.restype = C.c_char_p
+for _n in EXPORTS:
+    if _n not in ("sod2_last_error", "sod2_version") and not _n.endswith("_destroy"):
+        getattr(_lib, _n).restype = C.c_int32
+for _n in ("sod2_graph_destroy", "sod2_rdp_destroy", "sod2_plan_destroy", "sod2_binding_destroy"):
+    getattr(_lib, _n).restype = None
+    getattr(_lib, _n).argtypes = [C.c_void_p]
+
+
+def _check(rc):
+    if rc != 0:
+        raise Sod2Error(rc, _lib.sod2_last_error().decode())
+
+
+def _attrs(kind: str, attrs: dict):
+    ia: List[int] = []
+    fa = 0.0
+    if kind in ("Gather", "Concat"):
+        ia = [int(attrs["axis"])]
+    elif kind == "Transpose":
+        ia = [int(v) for v in attrs["perm"]]
+    elif kind == "MatMul":
+        ia = [int(attrs.get("transB", 0))]
+    elif kind == "Conv":
+        ia = [int(attrs["stride"]), int(attrs["pad"])]
+    elif kind == "Softmax":
+        ia = [int(attrs.get("causal", 0))]
+    elif kind == "ReduceMean":
+        ia = [int(attrs.get("keepdims", 1))] + [int(a) for a in attrs["axes"]]
+    elif kind == "MaxPool":
+        ia = [int(attrs["kernel"]), int(attrs["stride"]), int(attrs["pad"])]
+    elif kind == "LayerNorm":
+        fa = float(attrs["eps"])
+    elif kind == "Switch":
+        fa = float(attrs["threshold"])
+    return ia, fa
+
+
+class _Handle:
+    _destroy = None
+
+    def __init__(self, ptr, keep=()):
+        self.ptr = ptr
+        self._keep = keep
+
+    def __del__(self):
+        if getattr(self, "ptr", None):
+            getattr(_lib, self._destroy)(self.ptr)
+            self.ptr = None
+
+
+class Graph(_Handle):
+    _destroy = "sod2_graph_destroy"
+
+
+class Rdp(_Handle):
+    _destroy = "sod2_rdp_destroy"
+
+
+class Plan(_Handle):
+    _destroy = "sod2_plan_destroy"
+
+
+class Binding(_Handle):
+    _destroy = "sod2_binding_destroy"
+
+
+def sod2_graph_build(desc) -> Graph:
+    """desc: a workloads.GraphDesc-like object (symbols, tensors, ops)."""
+    keep = []
+
+    def cstr(s):
+        b = C.c_char_p(str(s).encode())
+        keep.append(b)
+        return b
+
+    ns = len(desc.symbols)
+    names = (C.c_char_p * max(ns, 1))(*[str(s[0]).encode() for s in desc.symbols])
+    lo = (C.c_int64 * max(ns, 1))(*[int(s[1]) for s in desc.symbols])
+    hi = (C.c_int64 * max(ns, 1))(*[int(s[2]) for s in desc.symbols])
+    tds = (_TensorDesc * max(len(desc.tensors), 1))()
+    for i, t in enumerate(desc.tensors):
+        td = tds[i]
+        td.name = str(t.name).encode()
+        td.dtype = DTYPES[t.dtype]
+        td.role = ROLES[t.role]
+        td.is_output = int(t.is_output)
+        td.session = int(getattr(t, "session", False))
+        if t.dims is None:
+            td.rank = -1
+        else:
+            td.rank = len(t.dims)
+            arr = (C.c_char_p * max(len(t.dims), 1))(*[str(d).encode() for d in t.dims])
+            keep.append(arr)
+            td.dims = arr
+            cap = getattr(t, "capacity", None)
+            if cap is not None:
+                carr = (C.c_char_p * max(len(cap), 1))(*[str(d).encode() for d in cap])
+                keep.append(carr)
+                td.capacity_dims = carr
+        if t.data is not None:
+            np_dt = {"i64": np.int64, "i32": np.int32, "f32": np.float32}[t.dtype]
+            a = np.ascontiguousarray(t.data, dtype=np_dt)
+            keep.append(a)
+            td.host_data = a.ctypes.data
+            td.host_count = a.size
+    ods = (_OpDesc * max(len(desc.ops), 1))()
+    for i, op in enumerate(desc.ops):
+        od = ods[i]
+        od.kind = OP_KINDS.index(op.kind)
+        ins = (C.c_int32 * max(len(op.inputs), 1))(*op.inputs)
+        outs = (C.c_int32 * max(len(op.outputs), 1))(*op.outputs)
+        ia, fa = _attrs(op.kind, op.attrs)
+        iarr = (C.c_int64 * max(len(ia), 1))(*ia)
+        keep += [ins, outs, iarr]
+        od.n_inputs, od.inputs = len(op.inputs), ins
+        od.n_outputs, od.outputs = len(op.outputs), outs
+        od.n_iattr, od.iattr, od.fattr = len(ia), iarr, fa
+    gd = _GraphDesc(ns, names, lo, hi, len(desc.tensors), tds, len(desc.ops), ods)
+    out = C.c_void_p()
+    _check(_lib.sod2_graph_build(C.byref(gd), C.byref(out)))
+    g = Graph(out)
+    g.desc = desc
+    return g
+
+
+def sod2_graph_op_class(g: Graph, op: int) -> str:
+    c = C.c_int32()
+    _check(_lib.sod2_graph_op_class(g.ptr, op, C.byref(c)))
+    return OP_CLASS_NAMES[c.value]
+
+
+def sod2_rdp_infer(g: Graph, order: Optional[Sequence[int]] = None) -> Rdp:
+    out = C.c_void_p()
+    if order is None:
+        _check(_lib.sod2_rdp_infer(g.ptr, C.byref(out)))
+    else:
+        arr = (C.c_int32 * len(order))(*order)
+        _check(_lib.sod2_rdp_infer_ordered(g.ptr, arr, len(order), C.byref(out)))
+    return Rdp(out, keep=(g,))
+
+
+def sod2_rdp_query(r: Rdp, tensor: int):
+    rank = C.c_int32()
+    dims = (DimInfo * 8)()
+    _check(_lib.sod2_rdp_query(r.ptr, tensor, C.byref(rank), dims))
+    return rank.value, [(d.cls, d.value, d.expr.decode()) for d in dims[:max(rank.value, 0)]]
+
+
+def sod2_rdp_sweeps(r: Rdp) -> int:
+    n = C.c_int32()
+    _check(_lib.sod2_rdp_sweeps(r.ptr, C.byref(n)))
+    return n.value
+
+
+def _text(fn, ptr) -> str:
+    need = C.c_size_t()
+    fn(ptr, None, 0, C.byref(need))
+    buf = C.create_string_buffer(need.value)
+    _check(fn(ptr, buf, need.value, C.byref(need)))
+    return buf.value.decode()
+
+
+def sod2_rdp_dump(r: Rdp) -> str:
+    return _text(_lib.sod2_rdp_dump, r.ptr)
+
+
+def sod2_plan(g: Graph, r: Rdp, fusion=1, sep=1, dmp=1, mvc=1) -> Plan:
+    out = C.c_void_p()
+    opts = PlanOpts(int(fusion), int(sep), int(dmp), int(mvc))
+    _check(_lib.sod2_plan(g.ptr, r.ptr, C.byref(opts), C.byref(out)))
+    p = Plan(out, keep=(g, r))
+    p.graph = g
+    return p
+
+
+def sod2_plan_counts(p: Plan):
+    a, b, c = C.c_int32(), C.c_int32(), C.c_int32()
+    _check(_lib.sod2_plan_counts(p.ptr, C.byref(a), C.byref(b), C.byref(c)))
+    return a.value, b.value, c.value
+
+
+def sod2_plan_dump(p: Plan) -> str:
+    return _text(_lib.sod2_plan_dump, p.ptr)
+
+
+def _symbols(p: Plan, sym) -> "C.Array":
+    if isinstance(sym, dict):
+        sym = [sym[s[0]] for s in p.graph.desc.symbols]
+    return (C.c_int64 * max(len(sym), 1))(*[int(v) for v in sym]), len(sym)
+
+
+def sod2_bind(p: Plan, sym, decisions: Optional[Sequence[int]] = None) -> Binding:
+    arr, n = _symbols(p, sym)
+    out = C.c_void_p()
+    if decisions is None:
+        _check(_lib.sod2_bind(p.ptr, arr, n, C.byref(out)))
+    else:
+        d = (C.c_int32 * max(len(decisions), 1))(*[int(bool(v)) for v in decisions])
+        _check(_lib.sod2_bind_decided(p.ptr, arr, n, d, len(decisions), C.byref(out)))
+    b = Binding(out, keep=(p,))
+    b.plan = p
+    return b
+
+
+def sod2_binding_arena_bytes(b: Binding):
+    a, pk = C.c_size_t(), C.c_size_t()
+    _check(_lib.sod2_binding_arena_bytes(b.ptr, C.byref(a), C.byref(pk)))
+    return a.value, pk.value
+
+
+def sod2_run_arena_bytes(b: Binding):
+    a, pk = C.c_size_t(), C.c_size_t()
+    _check(_lib.sod2_run_arena_bytes(b.ptr, C.byref(a), C.byref(pk)))
+    return a.value, pk.value
+
+
+def sod2_binding_dump(b: Binding) -> str:
+    return _text(_lib.sod2_binding_dump, b.ptr)
+
+
+def sod2_run_plan_dump(b: Binding) -> str:
+    return _text(_lib.sod2_run_plan_dump, b.ptr)
+
+
+def sod2_binding_force_decisions(b: Binding, decisions: Sequence[int]):
+    d = (C.c_int32 * max(len(decisions), 1))(*[int(bool(v)) for v in decisions])
+    _check(_lib.sod2_binding_force_decisions(b.ptr, d, len(decisions)))
+
+
+def sod2_binding_force_variant(b: Binding, variant: int):
+    _check(_lib.sod2_binding_force_variant(b.ptr, int(variant)))
+
+
+def sod2_binding_set_profiling(b: Binding, on: bool):
+    _check(_lib.sod2_binding_set_profiling(b.ptr, int(on)))
+
+
+def sod2_binding_launch_records(b: Binding):
+    n = C.c_int32()
+    _check(_lib.sod2_binding_launch_records(b.ptr, None, 0, C.byref(n)))
+    recs = (LaunchRecord * max(n.value, 1))()
+    _check(_lib.sod2_binding_launch_records(b.ptr, recs, n.value, C.byref(n)))
+    return [dict(group=r.group, kernel=KERNEL_NAMES[r.kernel], variant=r.variant, ms=r.ms, flops=r.flops,
+                 bytes=r.bytes) for r in recs[:n.value]]
+
+
+def sod2_run_decisions(b: Binding) -> List[int]:
+    n = C.c_int32()
+    _check(_lib.sod2_run_decisions(b.ptr, None, 0, C.byref(n)))
+    arr = (C.c_int32 * max(n.value, 1))()
+    _check(_lib.sod2_run_decisions(b.ptr, arr, n.value, C.byref(n)))
+    return list(arr[:n.value])
+
+
+def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence[int], input_ptrs: Sequence[int],
+             output_ptrs: Sequence[int], stream: int = 0):
+    """All pointers are raw device addresses (e.g. torch.Tensor.data_ptr()); stream is a hipStream_t value."""
+    w = (C.c_void_p * max(len(weight_ptrs), 1))(*weight_ptrs)
+    i = (C.c_void_p * max(len(input_ptrs), 1))(*input_ptrs)
+    o = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
+    _check(_lib.sod2_run(b.ptr, C.c_void_p(arena_ptr), C.c_size_t(arena_bytes), w, len(weight_ptrs), i,
+                         len(input_ptrs), o, len(output_ptrs), C.c_void_p(stream)))
+
+
+def sod2_version() -> str:
+    return _lib.sod2_version().decode()

@@ -1,0 +1,227 @@
+// Run-time half of the plan (Section 4.4.1): evaluate the symbols, derive the executed steps,
+// tensor lifetimes and arena offsets.
+//
+// Per executed sub-graph, in execution order: p* = step with the most live bytes (earliest on
+// ties); the sub-graph's tensors live at p* by (start, id), then those starting after p* by
+// (start, id), then those ending before p* by (end desc, start desc, id) are each placed at the
+// lowest offset that overlaps no already placed tensor with an intersecting lifetime.  Sizes are
+// rounded up to 256 bytes.  Control flow uses dead tokens: the Switch output not taken is dead, an
+// item with a dead input does not run, Combine forwards its live input.
+#include <algorithm>
+#include <functional>
+
+#include "internal.hpp"
+
+namespace sod2 {
+namespace {
+bool intersects(const ArenaTensor& a, const ArenaTensor& b) { return a.start <= b.end && b.start <= a.end; }
+
+int64_t first_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& placed) {
+  std::vector<std::pair<int64_t, int64_t>> busy;
+  for (const ArenaTensor* p : placed) if (intersects(t, *p)) busy.push_back({p->offset, p->offset + p->bytes});
+  std::sort(busy.begin(), busy.end());
+  int64_t off = 0;
+  for (const auto& b : busy) {
+    if (off + t.bytes <= b.first) break;
+    off = std::max(off, b.second);
+  }
+  return off;
+}
+// comparison strategy of Section 4.4.1: the smallest free slot that can hold the tensor
+int64_t best_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& placed) {
+  std::vector<std::pair<int64_t, int64_t>> busy;
+  int64_t top = 0;
+  for (const ArenaTensor* p : placed) {
+    top = std::max(top, p->offset + p->bytes);
+    if (intersects(t, *p)) busy.push_back({p->offset, p->offset + p->bytes});
+  }
+  std::sort(busy.begin(), busy.end());
+  std::vector<std::pair<int64_t, int64_t>> gaps;   // (size, offset)
+  int64_t cur = 0;
+  for (const auto& b : busy) {
+    if (b.first > cur) gaps.push_back({b.first - cur, cur});
+    cur = std::max(cur, b.second);
+  }
+  if (top > cur) gaps.push_back({top - cur, cur});
+  std::sort(gaps.begin(), gaps.end());
+  for (const auto& gp : gaps) if (gp.first >= t.bytes) return gp.second;
+  return cur;
+}
+}  // namespace
+
+BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const std::vector<int>& decisions,
+                     bool allow_undecided) {
+  const Graph& G = *p.g;
+  BindResult b;
+  if (symbols.size() != G.symbols.size()) throw Error(SOD2_ERR_INVALID_ARG, "wrong number of symbol values");
+  for (size_t i = 0; i < symbols.size(); ++i) {
+    const Symbol& s = G.symbols[i];
+    if (symbols[i] < s.lo || symbols[i] > s.hi)
+      throw Error(SOD2_ERR_SYMBOL_OUT_OF_RANGE, "symbol " + s.name + " = " + std::to_string(symbols[i]) +
+                                                    " outside [" + std::to_string(s.lo) + ", " + std::to_string(s.hi) + "]");
+    b.env[s.name] = symbols[i];
+  }
+  std::map<int, bool> group_dead;
+  std::map<int, std::pair<bool, int>> memo;       // tensor -> (dead, storage tensor)
+  size_t next_dec = 0;
+
+  std::function<std::pair<bool, int>(int)> info = [&](int t) -> std::pair<bool, int> {
+    auto it = memo.find(t);
+    if (it != memo.end()) return it->second;
+    std::pair<bool, int> r(false, t);
+    int pr = G.producer[t];
+    if (pr >= 0 && !p.folded[pr]) {
+      const Op& op = G.ops[pr];
+      if (op.kind == SOD2_OP_SWITCH) {
+        auto d = info(op.in[0]);
+        auto dec = b.decisions.find(pr);
+        bool is_skip_out = op.out.size() > 1 && op.out[1] == t;
+        bool taken = dec != b.decisions.end() && (is_skip_out == (dec->second != 0));
+        r = {d.first || dec == b.decisions.end() || !taken, d.second};
+      } else if (op.kind == SOD2_OP_COMBINE) {
+        r = {true, t};
+        for (int i : op.in) {
+          auto d = info(i);
+          if (!d.first) { r = {false, d.second}; break; }
+        }
+      } else if (p.view[pr]) {
+        r = info(op.in[0]);
+      } else {
+        r = {group_dead.at(p.group_of_op[pr]), t};
+      }
+    }
+    memo[t] = r;
+    return r;
+  };
+
+  std::map<int, int> reads_at;
+  for (size_t s = 0; s < p.subgraphs.size(); ++s) {
+    for (int i : p.subgraphs[s]) {
+      const Item& it = p.items[i];
+      int step = (int)b.steps.size();
+      if (it.is_group) {
+        const Group& gr = p.groups.at(it.ref);
+        std::set<int> inside;
+        for (int n : gr.ops) for (int o : G.ops[n].out) inside.insert(o);
+        std::vector<int> ext;
+        for (int n : gr.ops) for (int t : G.ops[n].in) if (!inside.count(t)) ext.push_back(t);
+        bool dead = false;
+        for (int t : ext) if (info(t).first) dead = true;
+        group_dead[gr.gid] = dead;
+        if (dead) { b.dead_ops.insert(gr.ops.begin(), gr.ops.end()); continue; }
+        for (int t : ext) reads_at[info(t).second] = step;
+        int t = gr.out;
+        const LS& sh = p.rdp->S[t];
+        if (!sh.resolved())
+          throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t].name + " is not resolved: " + sh.str());
+        std::vector<int64_t> dims;
+        int64_t n = dtype_bytes(G.tensors[t].dtype);
+        for (const auto& d : sh.d) { dims.push_back(d.e.eval(b.env)); n *= dims.back(); }
+        b.dims[t] = dims;
+        if (p.arena_candidate(t)) b.tensors[t] = ArenaTensor{t, (n + 255) / 256 * 256, step, step, -1};
+      } else {
+        const Op& op = G.ops[it.ref];
+        if (op.kind == SOD2_OP_SWITCH) {
+          if (info(op.in[0]).first) { b.dead_ops.insert(it.ref); continue; }
+          int dec = 0;
+          if (next_dec < decisions.size()) dec = decisions[next_dec++] ? 1 : 0;
+          else if (allow_undecided) ++b.undecided;
+          else throw Error(SOD2_ERR_INVALID_ARG, "a Switch decision is missing");
+          b.decisions[it.ref] = dec;
+          b.switch_order.push_back(it.ref);
+          for (int t : op.in) reads_at[info(t).second] = step;
+        } else {
+          int live = -1;
+          for (int t : op.in) if (!info(t).first) { live = t; break; }
+          if (live < 0) { b.dead_ops.insert(it.ref); continue; }
+          reads_at[info(live).second] = step;
+        }
+      }
+      b.steps.push_back(i);
+      b.step_sg.push_back((int)s);
+    }
+  }
+  for (auto& kv : b.tensors) {
+    auto it = reads_at.find(kv.first);
+    kv.second.end = std::max(kv.second.start, it == reads_at.end() ? kv.second.start : it->second);
+  }
+  for (int t = 0; t < (int)G.tensors.size(); ++t) {
+    int pr = G.producer[t];
+    if (pr < 0 || p.folded[pr] || b.dead_ops.count(pr)) continue;
+    auto d = info(t);
+    if (!d.first) b.dyn_base[t] = d.second;
+  }
+
+  int nsteps = (int)b.steps.size();
+  std::vector<int64_t> live_bytes(nsteps, 0);
+  for (const auto& kv : b.tensors)
+    for (int k = kv.second.start; k <= kv.second.end; ++k) live_bytes[k] += kv.second.bytes;
+  for (int64_t v : live_bytes) b.peak_live = std::max(b.peak_live, v);
+
+  std::vector<const ArenaTensor*> placed;
+  if (p.opts.dmp) {
+    int k0 = 0;
+    while (k0 < nsteps) {
+      int k1 = k0;
+      while (k1 + 1 < nsteps && b.step_sg[k1 + 1] == b.step_sg[k0]) ++k1;
+      std::vector<ArenaTensor*> mine;
+      for (auto& kv : b.tensors) if (kv.second.start >= k0 && kv.second.start <= k1) mine.push_back(&kv.second);
+      if (!mine.empty()) {
+        int pk = k0;
+        for (int k = k0; k <= k1; ++k) if (live_bytes[k] > live_bytes[pk]) pk = k;
+        std::vector<ArenaTensor*> at_peak, after, before;
+        for (ArenaTensor* a : mine) {
+          if (a->start <= pk && pk <= a->end) at_peak.push_back(a);
+          else if (a->start > pk) after.push_back(a);
+          else before.push_back(a);
+        }
+        auto by_start = [](const ArenaTensor* x, const ArenaTensor* y) {
+          return x->start != y->start ? x->start < y->start : x->tid < y->tid;
+        };
+        std::sort(at_peak.begin(), at_peak.end(), by_start);
+        std::sort(after.begin(), after.end(), by_start);
+        std::sort(before.begin(), before.end(), [](const ArenaTensor* x, const ArenaTensor* y) {
+          if (x->end != y->end) return x->end > y->end;
+          if (x->start != y->start) return x->start > y->start;
+          return x->tid < y->tid;
+        });
+        for (auto* lst : {&at_peak, &after, &before})
+          for (ArenaTensor* a : *lst) { a->offset = first_fit(*a, placed); placed.push_back(a); }
+      }
+      k0 = k1 + 1;
+    }
+  } else {
+    std::vector<ArenaTensor*> all;
+    for (auto& kv : b.tensors) all.push_back(&kv.second);
+    std::sort(all.begin(), all.end(), [](const ArenaTensor* x, const ArenaTensor* y) {
+      return x->start != y->start ? x->start < y->start : x->tid < y->tid;
+    });
+    for (ArenaTensor* a : all) { a->offset = best_fit(*a, placed); placed.push_back(a); }
+  }
+  for (const ArenaTensor* a : placed) b.arena_bytes = std::max(b.arena_bytes, a->offset + a->bytes);
+  return b;
+}
+
+std::string BindResult::dump(const Plan& p) const {
+  std::string out = "sym";
+  for (const auto& s : p.g->symbols) out += " " + s.name + "=" + std::to_string(env.at(s.name));
+  out += "\n";
+  for (size_t k = 0; k < steps.size(); ++k) {
+    const Item& it = p.items[steps[k]];
+    out += "step " + std::to_string(k) + " " + (it.is_group ? "g" : "c") + std::to_string(it.ref) + "\n";
+  }
+  for (const auto& kv : dims) {
+    out += "t" + std::to_string(kv.first) + " dims=[";
+    for (size_t i = 0; i < kv.second.size(); ++i) { if (i) out += " "; out += std::to_string(kv.second[i]); }
+    out += "]";
+    auto at = tensors.find(kv.first);
+    if (at != tensors.end())
+      out += " off=" + std::to_string(at->second.offset) + " bytes=" + std::to_string(at->second.bytes) + " life=" +
+             std::to_string(at->second.start) + ".." + std::to_string(at->second.end) + "\n";
+    else
+      out += " external\n";
+  }
+  out += "arena_bytes=" + std::to_string(arena_bytes) + "\npeak_live=" + std::to_string(peak_live) + "\n";
+  return out;
+}
+}  // namespace sod2

@@ -1,0 +1,185 @@
+// Host-side data structures of the SoD2 library: symbolic expressions, the RDP lattice,
+// the graph, the static plan and a binding.  Device code lives in kernels.hip / run.hip.
+#pragma once
+#include <cstdint>
+#include <map>
+#include <memory>
+#include <set>
+#include <stdexcept>
+#include <string>
+#include <vector>
+
+#include "../../include/sod2.h"
+
+namespace sod2 {
+
+struct Error : std::runtime_error {
+  int code;
+  Error(int c, const std::string& m) : std::runtime_error(m), code(c) {}
+};
+
+// ---------------------------------------------------------------------------------------------
+// Expressions: polynomials with integer coefficients over atoms (symbols, unsimplified floordiv /
+// mod).  These are the "operation-inferred constants" of the RDP domain (Section 4.1, V').
+// ---------------------------------------------------------------------------------------------
+struct Expr {
+  typedef std::vector<std::string> Mono;           // sorted atom names
+  std::map<Mono, int64_t> terms;                   // no zero coefficients
+
+  static Expr constant(int64_t c);
+  static Expr symbol(const std::string& name);
+  static Expr parse(const std::string& text);      // int | symbol | sum of those
+
+  bool is_const() const;
+  int64_t const_value() const;
+  bool is_symbol() const;
+  int cls() const;                                 // 0 known, 1 symbolic, 2 operation-inferred
+  std::string str() const;                         // canonical text
+  bool operator==(const Expr& o) const { return terms == o.terms; }
+  bool operator!=(const Expr& o) const { return !(*this == o); }
+
+  Expr operator+(const Expr& o) const;
+  Expr operator-(const Expr& o) const;
+  Expr operator*(const Expr& o) const;
+  Expr floordiv(int64_t c) const;
+  Expr mod(int64_t c) const;
+  bool exact_div(const Expr& o, Expr* q) const;    // o a single term dividing every term
+  int64_t eval(const std::map<std::string, int64_t>& env) const;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Lattice of Fig. 2: undef > {known, symbolic, operation-inferred constant} > nac
+// ---------------------------------------------------------------------------------------------
+struct LV {                                        // one component: a dim or an element
+  enum K { UNDEF, NAC, VAL } k = UNDEF;
+  Expr e;
+  static LV undef() { return LV(); }
+  static LV nac() { LV v; v.k = NAC; return v; }
+  static LV of(const Expr& x) { LV v; v.k = VAL; v.e = x; return v; }
+  static LV c(int64_t x) { return of(Expr::constant(x)); }
+  bool val() const { return k == VAL; }
+  bool is_c(int64_t x) const { return k == VAL && e.is_const() && e.const_value() == x; }
+  bool same(const LV& o) const { return k == o.k && (k != VAL || e == o.e); }
+};
+struct LS {                                        // a shape or a value vector
+  enum K { UNDEF, NAC, LIST } k = UNDEF;
+  std::vector<LV> d;
+  static LS undef() { return LS(); }
+  static LS nac() { LS s; s.k = NAC; return s; }
+  static LS list(const std::vector<LV>& v) { LS s; s.k = LIST; s.d = v; return s; }
+  bool is_list() const { return k == LIST; }
+  bool resolved() const;                           // a list with every component a value
+  bool same(const LS& o) const;
+  bool has_undef() const;
+  std::string str() const;
+};
+LV meet(const LV& a, const LV& b);                 // throws Error(SHAPE_MISMATCH) on two constants
+LS meet(const LS& a, const LS& b);
+
+// ---------------------------------------------------------------------------------------------
+// Graph
+// ---------------------------------------------------------------------------------------------
+struct Tensor {
+  std::string name;
+  int dtype = 0, role = 0;
+  bool declared = false, is_output = false, session = false;
+  std::vector<std::string> dims, capacity;
+  std::vector<int64_t> idata;                      // HOSTCONST integer values
+  std::vector<double> fdata;                       // HOSTCONST float values
+  int host_rank = 0;
+  bool has_data = false;
+};
+struct Op {
+  int kind = 0;
+  std::vector<int> in, out;
+  std::vector<int64_t> ia;
+  double fa = 0;
+};
+struct Symbol { std::string name; int64_t lo, hi; };
+
+struct Graph {
+  std::vector<Symbol> symbols;
+  std::vector<Tensor> tensors;
+  std::vector<Op> ops;
+  std::vector<int> producer;                       // per tensor, -1 for graph inputs / constants
+  std::vector<std::vector<int>> consumers;         // per tensor
+  std::vector<int> weight_ids, input_ids, output_ids;
+  void finish();                                   // fills the derived fields, validates ids
+  std::vector<int> sorted_nodes() const;           // reverse post-order of a depth-first walk
+};
+int op_class(int kind);                            // 0 ISDO, 1 ISDOS, 2 ISVDOS, 3 EDO
+const char* op_name(int kind);
+int dtype_bytes(int dtype);
+inline bool is_int(int dtype) { return dtype == SOD2_I64 || dtype == SOD2_I32; }
+
+struct Rdp {
+  const Graph* g = nullptr;
+  std::vector<LS> S, V;
+  int sweeps = 0;
+  void analyse(const std::vector<int>* order);
+  std::string dump() const;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Static plan
+// ---------------------------------------------------------------------------------------------
+enum GroupKind { G_GEMM, G_CONV, G_LAYERNORM, G_SOFTMAX, G_MAXPOOL, G_REDUCEMEAN, G_ARGMAX,
+                 G_CACHEAPPEND, G_NONZERO, G_GATHER, G_ELTWISE };
+const char* group_kind_name(int k);
+
+struct Group {
+  int gid = 0, kind = 0, out = -1;
+  std::vector<int> ops;                            // sorted by operator id
+  std::vector<int> chain;                          // members in absorption order (seed first)
+  std::vector<int> ins;                            // static bases read from outside
+};
+struct Item {
+  bool is_group = true;
+  int ref = 0;
+  std::vector<int> reads, writes;
+};
+struct Plan {
+  const Graph* g = nullptr;
+  const Rdp* rdp = nullptr;
+  sod2_plan_opts opts{1, 1, 1, 1};
+  std::vector<int> order;
+  std::vector<char> folded, view;
+  std::map<int, Group> groups;
+  std::vector<int> group_of_op;                    // -1 when the operator is in no group
+  std::vector<Item> items;
+  std::vector<std::vector<int>> subgraphs;
+  std::vector<std::string> sg_class;
+  std::vector<int> sbase;
+  int n_switches = 0;
+  void build();
+  std::string dump() const;
+  bool arena_candidate(int t) const;
+};
+
+// ---------------------------------------------------------------------------------------------
+// Binding: concrete shapes, lifetimes, offsets (Section 4.4.1) and the launch table
+// ---------------------------------------------------------------------------------------------
+struct ArenaTensor { int tid; int64_t bytes; int start, end; int64_t offset; };
+
+struct Layout {                                    // where an executed tensor lives
+  int base = -1;                                   // tensor whose storage it occupies
+  std::vector<int64_t> dims;
+};
+
+struct BindResult {
+  std::map<std::string, int64_t> env;
+  std::vector<int> steps, step_sg;                 // executed item indices
+  std::map<int, int> decisions;                    // Switch op id -> 1 when the skip output is taken
+  std::vector<int> switch_order;                   // executed Switch operators in order
+  std::map<int, ArenaTensor> tensors;
+  std::map<int, std::vector<int64_t>> dims;        // outputs of executed groups
+  std::map<int, int> dyn_base;                     // executed tensor -> tensor providing storage
+  std::set<int> dead_ops;
+  int64_t arena_bytes = 0, peak_live = 0;
+  int undecided = 0;                               // Switches met without a given decision
+  std::string dump(const Plan& p) const;
+};
+BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const std::vector<int>& decisions,
+                     bool allow_undecided);
+
+}  // namespace sod2

@@ -1,0 +1,604 @@
+// HIP kernels for gfx950 (CDNA4, wave64).
+//
+//  * gemm_mfma: bf16 x bf16 -> fp32 contraction on v_mfma_f32_32x32x16_bf16 with runtime M/N/K,
+//    two-level batch strides, LDS double buffering and a fused epilogue
+//    (scale, bias, activation, residual, activation, strided store).  The A operand comes from a
+//    loader object: a strided matrix (MatMul) or an NHWC im2col address generator (Conv), so the
+//    convolution is an implicit GEMM on the same main loop.  Tile shape is a template parameter
+//    over a small fixed set (the fat / regular / skinny versions of Section 4.4.2); nothing is
+//    compiled per shape.
+//  * gemm_simple: any dtype, any strides, plain FMA tiles (fp32 graphs, odd layouts).
+//  * row kernels: LayerNorm and softmax with one wavefront per row, 16-byte loads, wave shuffles.
+//  * reduce_mean, maxpool.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "launch.hpp"
+#define SOD2_BF16_TAG 1
+
+namespace sod2 {
+
+typedef uint16_t bf16_t;
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;          // NaN
+  u += 0x7fffu + ((u >> 16) & 1u);                              // round to nearest, ties to even
+  return (bf16_t)(u >> 16);
+}
+template <class T> __device__ __forceinline__ float to_f(T v);
+template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return bf2f(v); }
+template <class T> __device__ __forceinline__ T from_f(float v);
+template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return f2bf(v); }
+
+__device__ __forceinline__ float apply_act(float v, int act) {
+  if (act == ACT_RELU) return fmaxf(v, 0.f);
+  if (act == ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
+  if (act == ACT_SIGMOID) return 1.f / (1.f + __expf(-v));
+  return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+union V16 {
+  uint4 u;
+  bf16x8_t b;
+  bf16_t h[8];
+};
+__device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
+
+// ---------------------------------------------------------------------------------------------
+// A-operand loaders: 8 consecutive k of one row, zero outside the matrix
+// ---------------------------------------------------------------------------------------------
+struct MatA {
+  const bf16_t* p;
+  long long sm, sk;
+  int M, K, vec;
+  __device__ __forceinline__ void row_setup(int, int&, int&, long long&) const {}
+  __device__ __forceinline__ uint4 load(int m, int k) const {
+    if (vec) return (m < M && k < K) ? *(const uint4*)(p + (long long)m * sm + k) : zero4();
+    V16 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v.h[i] = (m < M && k + i < K) ? p[(long long)m * sm + (long long)(k + i) * sk] : (bf16_t)0;
+    return v.u;
+  }
+};
+struct ConvA {                      // x[nb, ih, iw, c], k = (kh * KW + kw) * C + c
+  const bf16_t* p;
+  int H, W, C, KW, stride, pad, OH, OW, M, K, vec;
+  __device__ __forceinline__ uint4 load(int m, int k) const {
+    if (m >= M || k >= K) return zero4();
+    int ow = m % OW, t = m / OW;
+    int oh = t % OH, nb = t / OH;
+    int ih0 = oh * stride - pad, iw0 = ow * stride - pad;
+    const bf16_t* img = p + (long long)nb * H * W * C;
+    if (vec) {
+      int c = k % C, kk = k / C;
+      int ih = ih0 + kk / KW, iw = iw0 + kk % KW;
+      if (ih < 0 || ih >= H || iw < 0 || iw >= W) return zero4();
+      return *(const uint4*)(img + ((long long)ih * W + iw) * C + c);
+    }
+    V16 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      int ke = k + i;
+      bf16_t x = 0;
+      if (ke < K) {
+        int c = ke % C, kk = ke / C;
+        int ih = ih0 + kk / KW, iw = iw0 + kk % KW;
+        if (ih >= 0 && ih < H && iw >= 0 && iw < W) x = img[((long long)ih * W + iw) * C + c];
+      }
+      v.h[i] = x;
+    }
+    return v.u;
+  }
+};
+
+// ---------------------------------------------------------------------------------------------
+// MFMA contraction
+// ---------------------------------------------------------------------------------------------
+template <class AL, int WM, int WN, int TM, int TN>
+__global__ __launch_bounds__(256) void gemm_mfma(AL al, GemmArgs g) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 64, LDK = BK + 8, KV = BK / 8;
+  constexpr int AV = BM * KV / 256, BV = BN * KV / 256;
+  static_assert(WM * WN == 4 && AV >= 1 && BV >= 1, "four waves per workgroup");
+  __shared__ __attribute__((aligned(16))) bf16_t As[2][BM * LDK];
+  __shared__ __attribute__((aligned(16))) bf16_t Bs[2][BN * LDK];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / WN, wn = wave % WN;
+  const int tiles_m = (g.M + BM - 1) / BM;
+  const int tm = blockIdx.x % tiles_m, tn = blockIdx.x / tiles_m;
+  const int b0 = blockIdx.y / g.nb1, b1 = blockIdx.y % g.nb1;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  al.p += b0 * g.a_sb0 + b1 * g.a_sb1;
+  const bf16_t* Bp = (const bf16_t*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
+
+  uint4 ra[AV], rb[BV];
+  auto gload = [&](int kt) {
+    const int k0 = kt * BK;
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      int v = tid + i * 256;
+      ra[i] = al.load(m0 + v / KV, k0 + (v % KV) * 8);
+    }
+    if (g.b_mode == 0) {
+#pragma unroll
+      for (int i = 0; i < BV; ++i) {
+        int v = tid + i * 256;
+        int n = n0 + v / KV, k = k0 + (v % KV) * 8;
+        rb[i] = (n < g.N && k < g.K) ? *(const uint4*)(Bp + (long long)n * g.b_sn + k) : zero4();
+      }
+    } else if (g.b_mode == 1) {
+#pragma unroll
+      for (int i = 0; i < BV; ++i) {
+        int v = tid + i * 256;
+        int k = k0 + v / (BN / 8), n = n0 + (v % (BN / 8)) * 8;
+        rb[i] = (n < g.N && k < g.K) ? *(const uint4*)(Bp + (long long)k * g.b_sk + n) : zero4();
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < BV; ++i) {
+        int v = tid + i * 256;
+        int n = n0 + v / KV, k = k0 + (v % KV) * 8;
+        V16 t;
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+          t.h[e] = (n < g.N && k + e < g.K) ? Bp[(long long)n * g.b_sn + (long long)(k + e) * g.b_sk] : (bf16_t)0;
+        rb[i] = t.u;
+      }
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < AV; ++i) {
+      int v = tid + i * 256;
+      *(uint4*)&As[buf][(v / KV) * LDK + (v % KV) * 8] = ra[i];
+    }
+    if (g.b_mode != 1) {
+#pragma unroll
+      for (int i = 0; i < BV; ++i) {
+        int v = tid + i * 256;
+        *(uint4*)&Bs[buf][(v / KV) * LDK + (v % KV) * 8] = rb[i];
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < BV; ++i) {
+        int v = tid + i * 256;
+        int k = v / (BN / 8), n = (v % (BN / 8)) * 8;
+        V16 t;
+        t.u = rb[i];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) Bs[buf][(n + e) * LDK + k] = t.h[e];
+      }
+    }
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  const int nk = (g.K + BK - 1) / BK;
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  const int arow = (wm * TM * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
+  const int brow = (wn * TN * 32 + (lane & 31)) * LDK + (lane >> 5) * 8;
+  for (int kt = 0; kt < nk; ++kt) {
+    const int buf = kt & 1;
+    if (kt + 1 < nk) gload(kt + 1);
+#pragma unroll
+    for (int ks = 0; ks < BK / 16; ++ks) {
+      V16 af[TM], bf[TN];
+#pragma unroll
+      for (int i = 0; i < TM; ++i) af[i].u = *(const uint4*)&As[buf][arow + i * 32 * LDK + ks * 16];
+#pragma unroll
+      for (int j = 0; j < TN; ++j) bf[j].u = *(const uint4*)&Bs[buf][brow + j * 32 * LDK + ks * 16];
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i].b, bf[j].b, acc[i][j], 0, 0, 0);
+    }
+    if (kt + 1 < nk) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: lane holds column (lane & 31); rows 8*(r/4) + 4*(lane>>5) + r%4 of each 32x32 tile
+  bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
+  const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
+  const bf16_t* bias = (const bf16_t*)g.bias;
+#pragma unroll
+  for (int j = 0; j < TN; ++j) {
+    const int col = n0 + wn * TN * 32 + j * 32 + (lane & 31);
+    if (col >= g.N) continue;
+    const float bv = bias ? bf2f(bias[col]) : 0.f;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row = m0 + wm * TM * 32 + i * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+        if (row >= g.M) continue;
+        float v = acc[i][j][r] * g.scale + bv;
+        v = apply_act(v, g.act1);
+        if (Rp) v += bf2f(Rp[(long long)row * g.r_sm + (long long)col * g.r_sn]);
+        v = apply_act(v, g.act2);
+        Cp[(long long)row * g.c_sm + (long long)col * g.c_sn] = f2bf(v);
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Plain FMA contraction for any dtype and any strides
+// ---------------------------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void gemm_simple(GemmArgs g) {
+  constexpr int BT = 64, BK = 16;
+  __shared__ float As[BK][BT + 1];
+  __shared__ float Bs[BK][BT + 1];
+  const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+  const int tiles_m = (g.M + BT - 1) / BT;
+  const int m0 = (blockIdx.x % tiles_m) * BT, n0 = (blockIdx.x / tiles_m) * BT;
+  const int b0 = blockIdx.y / g.nb1, b1 = blockIdx.y % g.nb1;
+  const T* A = (const T*)g.A + b0 * g.a_sb0 + b1 * g.a_sb1;
+  const T* B = (const T*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
+  float acc[4][4] = {};
+  for (int k0 = 0; k0 < g.K; k0 += BK) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      int e = tid + i * 256;
+      int r = e / BK, k = e % BK;                        // 64 rows x 16 k
+      int m = m0 + r, kk = k0 + k;
+      As[k][r] = (m < g.M && kk < g.K) ? to_f<T>(A[(long long)m * g.a_sm + (long long)kk * g.a_sk]) : 0.f;
+      int n = n0 + r;
+      Bs[k][r] = (n < g.N && kk < g.K) ? to_f<T>(B[(long long)kk * g.b_sk + (long long)n * g.b_sn]) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < BK; ++k) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) { a[i] = As[k][ty * 4 + i]; b[i] = Bs[k][tx * 4 + i]; }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  T* C = (T*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
+  const T* R = g.res ? (const T*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    int row = m0 + ty * 4 + i;
+    if (row >= g.M) continue;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      int col = n0 + tx * 4 + j;
+      if (col >= g.N) continue;
+      float v = acc[i][j] * g.scale + (g.bias ? to_f<T>(((const T*)g.bias)[col]) : 0.f);
+      v = apply_act(v, g.act1);
+      if (R) v += to_f<T>(R[(long long)row * g.r_sm + (long long)col * g.r_sn]);
+      v = apply_act(v, g.act2);
+      C[(long long)row * g.c_sm + (long long)col * g.c_sn] = from_f<T>(v);
+    }
+  }
+}
+
+// direct convolution for any dtype (fp32 graphs): one thread per output element
+template <class T>
+__global__ void conv_simple(ConvArgs c) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long total = (long long)c.NB * c.OH * c.OW * c.O;
+  if (idx >= total) return;
+  int o = idx % c.O;
+  long long m = idx / c.O;
+  int ow = m % c.OW;
+  long long t = m / c.OW;
+  int oh = t % c.OH, nb = t / c.OH;
+  const T* x = (const T*)c.x + (long long)nb * c.H * c.W * c.C;
+  const T* w = (const T*)c.w + (long long)o * c.KH * c.KW * c.C;
+  float acc = 0.f;
+  for (int kh = 0; kh < c.KH; ++kh) {
+    int ih = oh * c.stride - c.pad + kh;
+    if (ih < 0 || ih >= c.H) continue;
+    for (int kw = 0; kw < c.KW; ++kw) {
+      int iw = ow * c.stride - c.pad + kw;
+      if (iw < 0 || iw >= c.W) continue;
+      const T* xp = x + ((long long)ih * c.W + iw) * c.C;
+      const T* wp = w + (kh * c.KW + kw) * c.C;
+      for (int ch = 0; ch < c.C; ++ch) acc = fmaf(to_f<T>(xp[ch]), to_f<T>(wp[ch]), acc);
+    }
+  }
+  float v = acc + (c.bias ? to_f<T>(((const T*)c.bias)[o]) : 0.f);
+  v = apply_act(v, c.act1);
+  if (c.res) v += to_f<T>(((const T*)c.res)[idx]);
+  v = apply_act(v, c.act2);
+  ((T*)c.y)[idx] = from_f<T>(v);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Row kernels: one wavefront per row
+// ---------------------------------------------------------------------------------------------
+template <class T> struct Vec;      // 16-byte vector of T
+template <> struct Vec<bf16_t> {
+  static constexpr int N = 8;
+  static __device__ __forceinline__ void load(const bf16_t* p, float* f) {
+    V16 v; v.u = *(const uint4*)p;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = bf2f(v.h[i]);
+  }
+  static __device__ __forceinline__ void store(bf16_t* p, const float* f) {
+    V16 v;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) v.h[i] = f2bf(f[i]);
+    *(uint4*)p = v.u;
+  }
+};
+template <> struct Vec<float> {
+  static constexpr int N = 4;
+  static __device__ __forceinline__ void load(const float* p, float* f) {
+    float4 v = *(const float4*)p; f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
+  static __device__ __forceinline__ void store(float* p, const float* f) {
+    *(float4*)p = make_float4(f[0], f[1], f[2], f[3]);
+  }
+};
+
+// MODE 0: LayerNorm (biased variance, two passes over registers); MODE 1: softmax (max-subtracted).
+// VEC: rows are 16-byte aligned and cols % Vec::N == 0 and cols <= 64 * Vec::N * MAXV.
+template <class T, int MODE, bool VEC>
+__global__ __launch_bounds__(256) void row_kernel(RowArgs a) {
+  constexpr int VN = Vec<T>::N, MAXV = 4;
+  const int lane = threadIdx.x & 63;
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (row >= a.rows) return;
+  const T* x = (const T*)a.x + row * a.x_stride;
+  T* y = (T*)a.y + row * a.y_stride;
+  int valid = a.cols;                                  // softmax with a causal mask: columns < valid
+  if (MODE == 1 && a.causal) {
+    int i = (int)(row % a.lq);
+    valid = min(a.cols, i + (a.cols - a.lq) + 1);
+  }
+  if (VEC) {
+    float v[MAXV][VN];
+    const int nvec = a.cols / VN;
+#pragma unroll
+    for (int q = 0; q < MAXV; ++q) {
+      int vi = lane + q * 64;
+      if (vi < nvec) Vec<T>::load(x + vi * VN, v[q]);
+    }
+    if (MODE == 0) {
+      float s = 0.f;
+#pragma unroll
+      for (int q = 0; q < MAXV; ++q)
+        if (lane + q * 64 < nvec)
+#pragma unroll
+          for (int e = 0; e < VN; ++e) s += v[q][e];
+      const float mean = wave_sum(s) / a.cols;
+      float ss = 0.f;
+#pragma unroll
+      for (int q = 0; q < MAXV; ++q)
+        if (lane + q * 64 < nvec)
+#pragma unroll
+          for (int e = 0; e < VN; ++e) { float d = v[q][e] - mean; ss += d * d; }
+      const float rstd = rsqrtf(wave_sum(ss) / a.cols + a.eps);
+#pragma unroll
+      for (int q = 0; q < MAXV; ++q) {
+        int vi = lane + q * 64;
+        if (vi < nvec) {
+          float gm[VN], bt[VN], o[VN];
+          Vec<T>::load((const T*)a.gamma + vi * VN, gm);
+          Vec<T>::load((const T*)a.beta + vi * VN, bt);
+#pragma unroll
+          for (int e = 0; e < VN; ++e) o[e] = (v[q][e] - mean) * rstd * gm[e] + bt[e];
+          Vec<T>::store(y + vi * VN, o);
+        }
+      }
+    } else {
+      float mx = -INFINITY;
+#pragma unroll
+      for (int q = 0; q < MAXV; ++q)
+        if (lane + q * 64 < nvec)
+#pragma unroll
+          for (int e = 0; e < VN; ++e)
+            if ((lane + q * 64) * VN + e < valid) mx = fmaxf(mx, v[q][e]);
+      mx = wave_max(mx);
+      float s = 0.f;
+#pragma unroll
+      for (int q = 0; q < MAXV; ++q)
+        if (lane + q * 64 < nvec)
+#pragma unroll
+          for (int e = 0; e < VN; ++e) {
+            float p = ((lane + q * 64) * VN + e < valid) ? __expf(v[q][e] - mx) : 0.f;
+            v[q][e] = p;
+            s += p;
+          }
+      const float inv = 1.f / wave_sum(s);
+#pragma unroll
+      for (int q = 0; q < MAXV; ++q) {
+        int vi = lane + q * 64;
+        if (vi < nvec) {
+          float o[VN];
+#pragma unroll
+          for (int e = 0; e < VN; ++e) o[e] = v[q][e] * inv;
+          Vec<T>::store(y + vi * VN, o);
+        }
+      }
+    }
+  } else {
+    if (MODE == 0) {
+      float s = 0.f;
+      for (int c = lane; c < a.cols; c += 64) s += to_f<T>(x[c]);
+      const float mean = wave_sum(s) / a.cols;
+      float ss = 0.f;
+      for (int c = lane; c < a.cols; c += 64) { float d = to_f<T>(x[c]) - mean; ss += d * d; }
+      const float rstd = rsqrtf(wave_sum(ss) / a.cols + a.eps);
+      for (int c = lane; c < a.cols; c += 64)
+        y[c] = from_f<T>((to_f<T>(x[c]) - mean) * rstd * to_f<T>(((const T*)a.gamma)[c]) + to_f<T>(((const T*)a.beta)[c]));
+    } else {
+      float mx = -INFINITY;
+      for (int c = lane; c < valid; c += 64) mx = fmaxf(mx, to_f<T>(x[c]));
+      mx = wave_max(mx);
+      float s = 0.f;
+      for (int c = lane; c < valid; c += 64) s += __expf(to_f<T>(x[c]) - mx);
+      const float inv = 1.f / wave_sum(s);
+      for (int c = lane; c < a.cols; c += 64)
+        y[c] = from_f<T>(c < valid ? __expf(to_f<T>(x[c]) - mx) * inv : 0.f);
+    }
+  }
+}
+
+// y[b, c] = mean_r x[b, r, c]; 64 columns per workgroup, 4 row groups of 64 lanes... one column per
+// lane keeps loads coalesced; rows are split over the 4 waves and combined through LDS.
+template <class TI, class TO>
+__global__ __launch_bounds__(256) void reduce_mean_kernel(ReduceArgs a) {
+  __shared__ float part[4][64];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c = blockIdx.x * 64 + lane, b = blockIdx.y;
+  float s = 0.f;
+  if (c < a.C) {
+    const TI* x = (const TI*)a.x + (long long)b * a.R * a.C + c;
+    for (long long r = w; r < a.R; r += 4) s += to_f<TI>(x[r * a.C]);
+  }
+  part[w][lane] = s;
+  __syncthreads();
+  if (w == 0 && c < a.C) {
+    float t = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+    ((TO*)a.y)[(long long)b * a.C + c] = from_f<TO>(t / (float)a.R);
+  }
+}
+
+template <class T>
+__global__ void maxpool_kernel(PoolArgs p) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  long long total = (long long)p.NB * p.OH * p.OW * p.C;
+  if (idx >= total) return;
+  int c = idx % p.C;
+  long long m = idx / p.C;
+  int ow = m % p.OW;
+  long long t = m / p.OW;
+  int oh = t % p.OH, nb = t / p.OH;
+  const T* x = (const T*)p.x + (long long)nb * p.H * p.W * p.C;
+  float best = -INFINITY;
+  for (int i = 0; i < p.k; ++i) {
+    int ih = oh * p.stride - p.pad + i;
+    if (ih < 0 || ih >= p.H) continue;
+    for (int j = 0; j < p.k; ++j) {
+      int iw = ow * p.stride - p.pad + j;
+      if (iw < 0 || iw >= p.W) continue;
+      best = fmaxf(best, to_f<T>(x[((long long)ih * p.W + iw) * p.C + c]));
+    }
+  }
+  ((T*)p.y)[idx] = from_f<T>(best);
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side launchers
+// ---------------------------------------------------------------------------------------------
+template <class AL, int WM, int WN, int TM, int TN>
+static hipError_t launch_mfma(const AL& al, const GemmArgs& g, hipStream_t s) {
+  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
+  dim3 grid(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN), g.nb0 * g.nb1);
+  hipLaunchKernelGGL((gemm_mfma<AL, WM, WN, TM, TN>), grid, dim3(256), 0, s, al, g);
+  return hipGetLastError();
+}
+template <class AL>
+static hipError_t launch_mfma_variant(const AL& al, const GemmArgs& g, int variant, hipStream_t s) {
+  switch (variant) {
+    case V_FAT: return launch_mfma<AL, 2, 2, 4, 2>(al, g, s);        // 256 x 128
+    case V_SKINNY: return launch_mfma<AL, 1, 4, 1, 1>(al, g, s);     // 32 x 128
+    default: return launch_mfma<AL, 2, 2, 2, 2>(al, g, s);           // 128 x 128
+  }
+}
+
+hipError_t launch_gemm(const Launch& L, const GemmArgs& g, hipStream_t s) {
+  if (L.variant == V_SIMPLE || L.in_dtype != SOD2_BF16_TAG) {
+    dim3 grid(((g.M + 63) / 64) * ((g.N + 63) / 64), g.nb0 * g.nb1);
+    if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(gemm_simple<bf16_t>, grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL(gemm_simple<float>, grid, dim3(256), 0, s, g);
+    return hipGetLastError();
+  }
+  MatA al{(const bf16_t*)g.A, g.a_sm, g.a_sk, g.M, g.K, g.a_vec};
+  return launch_mfma_variant(al, g, L.variant, s);
+}
+
+hipError_t launch_conv(const Launch& L, const ConvArgs& c, hipStream_t s) {
+  if (L.variant == V_SIMPLE || L.in_dtype != SOD2_BF16_TAG) {
+    long long total = (long long)c.NB * c.OH * c.OW * c.O;
+    dim3 grid((unsigned)((total + 255) / 256));
+    if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(conv_simple<bf16_t>, grid, dim3(256), 0, s, c);
+    else hipLaunchKernelGGL(conv_simple<float>, grid, dim3(256), 0, s, c);
+    return hipGetLastError();
+  }
+  GemmArgs g{};
+  g.M = c.NB * c.OH * c.OW; g.N = c.O; g.K = c.KH * c.KW * c.C;
+  g.nb0 = g.nb1 = 1;
+  g.B = c.w; g.b_sk = 1; g.b_sn = g.K; g.b_mode = (g.K % 8 == 0 && ((uintptr_t)c.w & 15) == 0) ? 0 : 2;
+  g.C = c.y; g.c_sm = c.O; g.c_sn = 1;
+  g.bias = c.bias; g.res = c.res; g.r_sm = c.O; g.r_sn = 1;
+  g.scale = 1.f; g.act1 = c.act1; g.act2 = c.act2;
+  ConvA al{(const bf16_t*)c.x, c.H, c.W, c.C, c.KW, c.stride, c.pad, c.OH, c.OW, g.M, g.K, c.vec};
+  return launch_mfma_variant(al, g, L.variant, s);
+}
+
+template <class T>
+static void launch_row_t(const Launch& L, const RowArgs& a, hipStream_t s) {
+  constexpr int VN = Vec<T>::N;
+  bool vec = a.cols % VN == 0 && a.cols <= 64 * VN * 4 && a.x_stride % VN == 0 && a.y_stride % VN == 0 &&
+             ((uintptr_t)a.x % 16 == 0) && ((uintptr_t)a.y % 16 == 0) &&
+             (!L.is_layernorm || (((uintptr_t)a.gamma % 16 == 0) && ((uintptr_t)a.beta % 16 == 0)));
+  dim3 grid((unsigned)((a.rows + 3) / 4));
+  if (L.is_layernorm) {
+    if (vec) hipLaunchKernelGGL((row_kernel<T, 0, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((row_kernel<T, 0, false>), grid, dim3(256), 0, s, a);
+  } else {
+    if (vec) hipLaunchKernelGGL((row_kernel<T, 1, true>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((row_kernel<T, 1, false>), grid, dim3(256), 0, s, a);
+  }
+}
+hipError_t launch_row(const Launch& L, const RowArgs& a, hipStream_t s) {
+  if (L.in_dtype == SOD2_BF16_TAG) launch_row_t<bf16_t>(L, a, s);
+  else launch_row_t<float>(L, a, s);
+  return hipGetLastError();
+}
+
+hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s) {
+  dim3 grid((a.C + 63) / 64, a.batch);
+  bool ib = L.in_dtype == SOD2_BF16_TAG, ob = L.out_dtype == SOD2_BF16_TAG;
+  if (ib && ob) hipLaunchKernelGGL((reduce_mean_kernel<bf16_t, bf16_t>), grid, dim3(256), 0, s, a);
+  else if (ib) hipLaunchKernelGGL((reduce_mean_kernel<bf16_t, float>), grid, dim3(256), 0, s, a);
+  else if (ob) hipLaunchKernelGGL((reduce_mean_kernel<float, bf16_t>), grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL((reduce_mean_kernel<float, float>), grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_pool(const Launch& L, const PoolArgs& p, hipStream_t s) {
+  long long total = (long long)p.NB * p.OH * p.OW * p.C;
+  dim3 grid((unsigned)((total + 255) / 256));
+  if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(maxpool_kernel<bf16_t>, grid, dim3(256), 0, s, p);
+  else hipLaunchKernelGGL(maxpool_kernel<float>, grid, dim3(256), 0, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace sod2

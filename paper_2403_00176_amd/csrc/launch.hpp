@@ -1,0 +1,76 @@
+// Launch table entries: one per executed group, produced at bind from concrete shapes, strides
+// and arena offsets; consumed by sod2_run.  Pointers are kept as (space, index, byte offset)
+// references because the arena, weight, input and output addresses arrive with each run.
+#pragma once
+#include <cstdint>
+
+namespace sod2 {
+
+enum Space { SP_NONE = 0, SP_ARENA, SP_WEIGHT, SP_INPUT, SP_OUTPUT };
+struct Ref {
+  int space = SP_NONE;
+  int index = 0;           // position among the weights / inputs / outputs
+  int64_t byte_off = 0;    // arena offset, plus any view offset
+};
+
+enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER };
+enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
+enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3 };
+
+// C[b0,b1,m,n] = act2( act1( scale * sum_k A[b0,b1,m,k] * B[b0,b1,k,n] + bias[n] ) + R[b0,b1,m,n] )
+struct GemmArgs {
+  const void* A; const void* B; void* C; const void* bias; const void* res;
+  int M, N, K, nb0, nb1;
+  long long a_sm, a_sk, a_sb0, a_sb1;
+  long long b_sk, b_sn, b_sb0, b_sb1;
+  long long c_sm, c_sn, c_sb0, c_sb1;
+  long long r_sm, r_sn, r_sb0, r_sb1;
+  float scale;
+  int act1, act2;
+  int a_vec, b_mode;       // a_vec: 16-byte loads along k allowed; b_mode 0 k-contiguous vec, 1 n-contiguous vec, 2 scalar
+  int c_vec;               // c_sn == 1 and rows 4-byte aligned
+};
+
+// NHWC implicit GEMM: M = N*OH*OW, Ncol = O, K = KH*KW*C
+struct ConvArgs {
+  const void* x; const void* w; void* y; const void* bias; const void* res;
+  int NB, H, W, C, O, KH, KW, stride, pad, OH, OW;
+  int act1, act2;
+  int vec;                 // C % 8 == 0 (16-byte loads along channels)
+};
+
+struct RowArgs {            // LayerNorm / Softmax over the last dim
+  const void* x; void* y; const void* gamma; const void* beta;
+  long long rows; int cols; long long x_stride, y_stride;
+  float eps;
+  int causal, lq;          // softmax: row index within its [lq, cols] matrix = row % lq
+};
+
+struct ReduceArgs {         // y[b, c] = mean_r x[b, r, c]
+  const void* x; void* y;
+  int batch; long long R; int C;
+};
+
+struct PoolArgs {
+  const void* x; void* y;
+  int NB, H, W, C, OH, OW, k, stride, pad;
+};
+
+struct Launch {
+  int group = -1;
+  int kernel = K_OTHER;
+  int variant = 0;
+  int in_dtype = 0, out_dtype = 0;
+  Ref r[6];                // operand references, meaning depends on the kernel
+  union {
+    GemmArgs gemm;
+    ConvArgs conv;
+    RowArgs row;
+    ReduceArgs red;
+    PoolArgs pool;
+  } u;
+  bool is_layernorm = false;
+  double flops = 0, bytes = 0;
+};
+
+}  // namespace sod2

@@ -1,0 +1,397 @@
+// Static planning on the RDP result: fusion groups (Section 4.2), sub-graph partition and
+// execution order (Section 4.3).
+//
+// Rules (the paper leaves them to an earlier fusion system and to "exhaustive search"):
+//  R0 an operator whose outputs are integer tensors with a fully resolved value map is folded;
+//  R1 Reshape / Slice / Transpose / Gather-with-scalar-host-index are views (no kernel);
+//  R2 MatMul / Conv absorbs, in order and each at most once: Mul by a host scalar, Add of a rank-1
+//     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
+//     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
+//     consumer of the chain so far;
+//  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero stand alone; a
+//     non-view Gather absorbs one Add of proven-equal shape;
+//  R4 other elementwise operators chain while every aligned dim pair is proven equal or 1 (Fig. 4);
+//  R5 group id = smallest member id; groups are ordered by the node-order position of their
+//     last member.
+// Partition: cut around control operators and NonZero, after a group with a nac output, wherever
+// at most one arena tensor is live, and every 14 items.  Order inside a sub-graph: the sequence
+// with the smallest peak of live bytes at the symbols' upper bounds, ties to smaller group ids.
+#include <algorithm>
+#include <limits>
+
+#include "internal.hpp"
+
+namespace sod2 {
+
+static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE"};
+const char* group_kind_name(int k) { return kGroupNames[k]; }
+
+namespace {
+const int kMaxSubgraph = 14;
+
+bool is_act(int k) { return k == SOD2_OP_RELU || k == SOD2_OP_GELU || k == SOD2_OP_SIGMOID; }
+bool is_eltwise(int k) { return k == SOD2_OP_ADD || k == SOD2_OP_MUL || is_act(k) || k == SOD2_OP_CAST; }
+bool is_control(int k) { return k == SOD2_OP_SWITCH || k == SOD2_OP_COMBINE; }
+
+bool shape_equal(const LS& a, const LS& b) {
+  if (!a.resolved() || !b.resolved() || a.d.size() != b.d.size()) return false;
+  for (size_t i = 0; i < a.d.size(); ++i) if (a.d[i].e != b.d[i].e) return false;
+  return true;
+}
+bool pair_proven(const LV& a, const LV& b) {
+  return a.val() && b.val() && (a.e == b.e || a.is_c(1) || b.is_c(1));
+}
+bool bcast_proven(const LS& out, const LS& other) {
+  if (!out.is_list() || !other.is_list() || other.d.size() > out.d.size()) return false;
+  size_t pad = out.d.size() - other.d.size();
+  for (size_t i = 0; i < out.d.size(); ++i)
+    if (!pair_proven(out.d[i], i < pad ? LV::c(1) : other.d[i - pad])) return false;
+  return true;
+}
+int64_t align_up(int64_t n) { return (n + 255) / 256 * 256; }
+}  // namespace
+
+bool Plan::arena_candidate(int t) const {
+  const Tensor& d = g->tensors[t];
+  return d.role == SOD2_INTER && !d.is_output && !d.session;
+}
+
+static int64_t bytes_at(const Plan& p, int t, const std::map<std::string, int64_t>& env) {
+  const LS& s = p.rdp->S[t];
+  if (!s.resolved()) return 0;
+  int64_t n = dtype_bytes(p.g->tensors[t].dtype);
+  for (const auto& d : s.d) n *= d.e.eval(env);
+  return align_up(n);
+}
+
+void Plan::build() {
+  const Graph& G = *g;
+  const Rdp& R = *rdp;
+  int nops = (int)G.ops.size();
+  order = G.sorted_nodes();
+  std::vector<int> pos(nops, -1);
+  for (int i = 0; i < (int)order.size(); ++i) pos[order[i]] = i;
+  for (int i = 0; i < nops; ++i)
+    if (pos[i] < 0) throw Error(SOD2_ERR_INVALID_ARG, "operator unreachable from the graph inputs");
+
+  // R0 / R1
+  folded.assign(nops, 0);
+  view.assign(nops, 0);
+  for (int i = 0; i < nops; ++i) {
+    const Op& op = G.ops[i];
+    if (is_control(op.kind)) { if (op.kind == SOD2_OP_SWITCH) ++n_switches; continue; }
+    bool ints = true, known = true;
+    for (int o : op.out) {
+      if (!is_int(G.tensors[o].dtype)) ints = false;
+      if (!R.V[o].resolved()) known = false;
+    }
+    if (ints && known) folded[i] = 1;
+    else if (op.kind == SOD2_OP_RESHAPE || op.kind == SOD2_OP_SLICE || op.kind == SOD2_OP_TRANSPOSE) view[i] = 1;
+    else if (op.kind == SOD2_OP_GATHER) {
+      const Tensor& idx = G.tensors[op.in[1]];
+      view[i] = idx.has_data && idx.host_rank == 0;
+    }
+  }
+
+  auto sole_consumer = [&](int t) -> int {
+    if (G.tensors[t].is_output || G.consumers[t].size() != 1) return -1;
+    return G.consumers[t][0];
+  };
+  auto other = [&](const Op& op, int cur) { return op.in[0] == cur ? op.in[1] : op.in[0]; };
+  auto host_scalar = [&](int t) {
+    const Tensor& d = G.tensors[t];
+    return d.has_data && (d.idata.size() + d.fdata.size()) == 1;
+  };
+
+  // R2 - R4
+  group_of_op.assign(nops, -1);
+  std::set<int> absorbed_transpose;
+  auto new_group = [&](int kind, const std::vector<int>& chain) {
+    Group gr;
+    gr.kind = kind;
+    gr.chain = chain;
+    gr.ops = chain;
+    std::sort(gr.ops.begin(), gr.ops.end());
+    gr.gid = gr.ops.front();
+    int last = chain[0];
+    for (int n : chain) if (pos[n] > pos[last]) last = n;
+    gr.out = G.ops[last].out[0];
+    for (int n : chain) group_of_op[n] = gr.gid;
+    groups[gr.gid] = gr;
+  };
+  for (int n : order) {
+    const Op& op = G.ops[n];
+    if (folded[n] || group_of_op[n] >= 0 || is_control(op.kind)) continue;
+    if (view[n] && !absorbed_transpose.count(n)) continue;
+    if (op.kind == SOD2_OP_MATMUL || op.kind == SOD2_OP_CONV) {
+      std::vector<int> chain{n};
+      int cur = op.out[0], state = 0;
+      while (opts.fusion) {
+        int c = sole_consumer(cur);
+        if (c < 0 || folded[c] || group_of_op[c] >= 0) break;
+        const Op& cop = G.ops[c];
+        int nxt = -1;
+        if (cop.kind == SOD2_OP_MUL && state < 1 && host_scalar(other(cop, cur))) nxt = 1;
+        else if (cop.kind == SOD2_OP_ADD) {
+          int o = other(cop, cur);
+          const LS &so = R.S[o], &sc = R.S[cur];
+          int role = G.tensors[o].role;
+          if (state < 2 && role == SOD2_WEIGHT && so.is_list() && so.d.size() == 1 && sc.is_list() &&
+              sc.d.back().val() && so.d[0].val() && so.d[0].e == sc.d.back().e) nxt = 2;
+          else if (state < 4 && role != SOD2_WEIGHT && role != SOD2_HOSTCONST && shape_equal(so, sc)) nxt = 4;
+        } else if (is_act(cop.kind)) {
+          nxt = state < 3 ? 3 : (state == 4 ? 5 : -1);
+        } else if (cop.kind == SOD2_OP_TRANSPOSE && state < 6) {
+          nxt = 6;
+          absorbed_transpose.insert(c);
+        }
+        if (nxt < 0) break;
+        chain.push_back(c);
+        cur = cop.out[0];
+        state = nxt;
+        if (state == 6) break;
+      }
+      new_group(op.kind == SOD2_OP_MATMUL ? G_GEMM : G_CONV, chain);
+    } else if (op.kind == SOD2_OP_LAYERNORM) new_group(G_LAYERNORM, {n});
+    else if (op.kind == SOD2_OP_SOFTMAX) new_group(G_SOFTMAX, {n});
+    else if (op.kind == SOD2_OP_MAXPOOL) new_group(G_MAXPOOL, {n});
+    else if (op.kind == SOD2_OP_REDUCEMEAN) new_group(G_REDUCEMEAN, {n});
+    else if (op.kind == SOD2_OP_ARGMAX) new_group(G_ARGMAX, {n});
+    else if (op.kind == SOD2_OP_CACHEAPPEND) new_group(G_CACHEAPPEND, {n});
+    else if (op.kind == SOD2_OP_NONZERO) new_group(G_NONZERO, {n});
+    else if (op.kind == SOD2_OP_GATHER) {
+      std::vector<int> chain{n};
+      int c = sole_consumer(op.out[0]);
+      if (opts.fusion && c >= 0 && G.ops[c].kind == SOD2_OP_ADD && group_of_op[c] < 0 &&
+          shape_equal(R.S[other(G.ops[c], op.out[0])], R.S[op.out[0]]))
+        chain.push_back(c);
+      new_group(G_GATHER, chain);
+    } else if (is_eltwise(op.kind)) {
+      std::vector<int> chain{n};
+      int cur = op.out[0];
+      while (opts.fusion && chain.size() < 8) {
+        int c = sole_consumer(cur);
+        if (c < 0 || group_of_op[c] >= 0 || !is_eltwise(G.ops[c].kind)) break;
+        const Op& cop = G.ops[c];
+        if (cop.in.size() == 2 &&
+            !(bcast_proven(R.S[cop.out[0]], R.S[other(cop, cur)]) && bcast_proven(R.S[cop.out[0]], R.S[cur])))
+          break;
+        chain.push_back(c);
+        cur = cop.out[0];
+      }
+      new_group(G_ELTWISE, chain);
+    } else {
+      throw Error(SOD2_ERR_UNSUPPORTED, std::string("no grouping rule for ") + op_name(op.kind));
+    }
+  }
+  for (int c : absorbed_transpose) view[c] = 0;
+
+  // static storage bases: views and Switch outputs alias their (data) input
+  int nt = (int)G.tensors.size();
+  sbase.resize(nt);
+  for (int t = 0; t < nt; ++t) sbase[t] = t;
+  for (int n : order) {
+    const Op& op = G.ops[n];
+    if (view[n] || op.kind == SOD2_OP_SWITCH)
+      for (int o : op.out) sbase[o] = sbase[op.in[0]];
+  }
+  for (auto& kv : groups) {
+    Group& gr = kv.second;
+    std::set<int> inside, seen;
+    for (int n : gr.ops) for (int o : G.ops[n].out) inside.insert(o);
+    for (int n : gr.ops)
+      for (int t : G.ops[n].in) {
+        int b = sbase[t];
+        if (inside.count(t) || inside.count(b) || seen.count(b)) continue;
+        seen.insert(b);
+        gr.ins.push_back(b);
+      }
+  }
+
+  // items in a topological order of groups and control operators (R5)
+  struct Entry { int pos; bool is_group; int ref; };
+  std::vector<Entry> entries;
+  for (const auto& kv : groups) {
+    int last = 0;
+    for (int n : kv.second.ops) last = std::max(last, pos[n]);
+    entries.push_back({last, true, kv.first});
+  }
+  for (int n = 0; n < nops; ++n) if (is_control(G.ops[n].kind)) entries.push_back({pos[n], false, n});
+  std::sort(entries.begin(), entries.end(), [](const Entry& a, const Entry& b) { return a.pos < b.pos; });
+  for (const auto& e : entries) {
+    Item it;
+    it.is_group = e.is_group;
+    it.ref = e.ref;
+    if (e.is_group) {
+      it.reads = groups[e.ref].ins;
+      it.writes = {groups[e.ref].out};
+    } else {
+      const Op& op = G.ops[e.ref];
+      for (int t : op.in)
+        if (std::find(it.reads.begin(), it.reads.end(), sbase[t]) == it.reads.end()) it.reads.push_back(sbase[t]);
+      if (op.kind == SOD2_OP_COMBINE) it.writes = op.out;
+    }
+    items.push_back(it);
+  }
+
+  // partition ------------------------------------------------------------------------------------
+  int n = (int)items.size();
+  std::map<int, int> last_read;
+  for (int i = 0; i < n; ++i) for (int t : items[i].reads) last_read[t] = i;
+  auto lr = [&](int t) { auto it = last_read.find(t); return it == last_read.end() ? -1 : it->second; };
+  auto has_nac = [&](const Item& it) {
+    for (int t : it.writes) if (!R.S[t].resolved()) return true;
+    return false;
+  };
+  std::vector<char> cut_after(n, 0);
+  std::set<int> live;
+  for (int i = 0; i < n; ++i) {
+    const Item& it = items[i];
+    for (int t : it.writes) if (arena_candidate(t) && lr(t) > i) live.insert(t);
+    for (auto p = live.begin(); p != live.end();) p = (lr(*p) > i) ? std::next(p) : live.erase(p);
+    bool edo = !it.is_group || groups[it.ref].kind == G_NONZERO;
+    if (edo) {
+      cut_after[i] = 1;
+      if (i > 0) cut_after[i - 1] = 1;
+    } else if (has_nac(it) || live.size() <= 1) {
+      cut_after[i] = 1;
+    }
+  }
+  std::vector<std::vector<int>> pieces;
+  std::vector<int> cur;
+  for (int i = 0; i < n; ++i) {
+    cur.push_back(i);
+    if (cut_after[i] || (int)cur.size() == kMaxSubgraph) { pieces.push_back(cur); cur.clear(); }
+  }
+  if (!cur.empty()) pieces.push_back(cur);
+
+  std::map<std::string, int64_t> env_hi;
+  for (const auto& s : G.symbols) env_hi[s.name] = s.hi;
+
+  for (const auto& piece : pieces) {
+    // class of the sub-graph (Section 4.3): all known / mixed / contains nac
+    std::string cls = "known";
+    for (int i : piece)
+      for (int t : items[i].writes) {
+        if (!R.S[t].resolved()) { cls = "nac"; break; }
+        for (const auto& d : R.S[t].d) if (!d.e.is_const() && cls != "nac") cls = "mixed";
+      }
+    sg_class.push_back(cls);
+    int k = (int)piece.size();
+    if (!opts.sep || k <= 2) { subgraphs.push_back(piece); continue; }
+
+    // exhaustive search as a dynamic programme over the set of executed items
+    int first = piece.front(), end = piece.back();
+    std::map<int, int> idx, produced_in;
+    for (int j = 0; j < k; ++j) idx[piece[j]] = j;
+    std::vector<int> tensors;
+    for (int i : piece)
+      for (int t : items[i].writes)
+        if (arena_candidate(t)) { produced_in[t] = idx[i]; tensors.push_back(t); }
+    auto incoming = [&](int t) {
+      if (!arena_candidate(t)) return false;
+      for (int i = 0; i < first; ++i)
+        if (std::find(items[i].writes.begin(), items[i].writes.end(), t) != items[i].writes.end()) return true;
+      return false;
+    };
+    for (int i : piece)
+      for (int t : items[i].reads)
+        if (!produced_in.count(t) && std::find(tensors.begin(), tensors.end(), t) == tensors.end() && incoming(t))
+          tensors.push_back(t);
+    size_t nt2 = tensors.size();
+    std::vector<int64_t> size(nt2);
+    std::vector<int> prod(nt2, -1);
+    std::vector<uint32_t> readers(nt2, 0);
+    std::vector<char> live_out(nt2, 0);
+    for (size_t a = 0; a < nt2; ++a) {
+      int t = tensors[a];
+      size[a] = bytes_at(*this, t, env_hi);
+      if (produced_in.count(t)) prod[a] = produced_in[t];
+      for (int i : piece)
+        if (std::find(items[i].reads.begin(), items[i].reads.end(), t) != items[i].reads.end()) readers[a] |= 1u << idx[i];
+      live_out[a] = lr(t) > end;
+    }
+    std::map<int, int> writer;                         // any tensor written in the piece, outputs included
+    for (int i : piece) for (int t : items[i].writes) writer[t] = idx[i];
+    std::vector<uint32_t> deps(k, 0);
+    for (int i : piece)
+      for (int t : items[i].reads)
+        if (writer.count(t)) deps[idx[i]] |= 1u << writer[t];
+    auto step_mem = [&](uint32_t S, int j) {
+      int64_t mem = 0;
+      for (size_t a = 0; a < nt2; ++a) {
+        int p = prod[a];
+        if (p >= 0 && p != j && !((S >> p) & 1)) continue;
+        if (p == j || live_out[a] || (readers[a] & ~S)) mem += size[a];
+      }
+      return mem;
+    };
+    uint32_t full = (1u << k) - 1;
+    const int64_t INF = std::numeric_limits<int64_t>::max();
+    std::vector<int64_t> best(full + 1, INF);
+    best[full] = 0;
+    for (int64_t Sx = (int64_t)full - 1; Sx >= 0; --Sx) {
+      uint32_t S = (uint32_t)Sx;
+      int64_t b = INF;
+      for (int j = 0; j < k; ++j) {
+        if (((S >> j) & 1) || (deps[j] & ~S)) continue;
+        int64_t nx = best[S | (1u << j)];
+        if (nx == INF) continue;
+        b = std::min(b, std::max(step_mem(S, j), nx));
+      }
+      best[S] = b;
+    }
+    std::vector<int> by_id(k);
+    for (int j = 0; j < k; ++j) by_id[j] = j;
+    std::stable_sort(by_id.begin(), by_id.end(), [&](int a, int b) {
+      if (items[piece[a]].ref != items[piece[b]].ref) return items[piece[a]].ref < items[piece[b]].ref;
+      return a < b;
+    });
+    std::vector<int> seq;
+    uint32_t S = 0;
+    int64_t target = best[0];
+    while (S != full) {
+      bool moved = false;
+      for (int j : by_id) {
+        if (((S >> j) & 1) || (deps[j] & ~S)) continue;
+        int64_t nx = best[S | (1u << j)];
+        if (nx == INF) continue;
+        if (std::max(step_mem(S, j), nx) <= target) { seq.push_back(piece[j]); S |= 1u << j; moved = true; break; }
+      }
+      if (!moved) throw Error(SOD2_ERR_INVALID_ARG, "execution-order search found no valid order");
+    }
+    subgraphs.push_back(seq);
+  }
+}
+
+std::string Plan::dump() const {
+  std::string out = "order";
+  for (int n : order) out += " " + std::to_string(n);
+  out += "\nfolded";
+  for (size_t i = 0; i < folded.size(); ++i) if (folded[i]) out += " " + std::to_string(i);
+  out += "\nviews";
+  for (size_t i = 0; i < view.size(); ++i) if (view[i]) out += " " + std::to_string(i);
+  out += "\n";
+  auto join = [](const std::vector<int>& v, const char* prefix) {
+    std::string s;
+    for (size_t i = 0; i < v.size(); ++i) { if (i) s += " "; s += prefix + std::to_string(v[i]); }
+    return s;
+  };
+  for (const auto& it : items) {
+    if (it.is_group) {
+      const Group& gr = groups.at(it.ref);
+      out += "g" + std::to_string(gr.gid) + " " + group_kind_name(gr.kind) + " ops=[" + join(gr.ops, "") + "] out=t" +
+             std::to_string(gr.out) + " ins=[" + join(gr.ins, "t") + "]\n";
+    } else {
+      out += "c" + std::to_string(it.ref) + " " + op_name(g->ops[it.ref].kind) + "\n";
+    }
+  }
+  for (size_t s = 0; s < subgraphs.size(); ++s) {
+    out += "sg" + std::to_string(s) + " " + sg_class[s];
+    for (int i : subgraphs[s]) out += std::string(" ") + (items[i].is_group ? "g" : "c") + std::to_string(items[i].ref);
+    out += "\n";
+  }
+  return out;
+}
+}  // namespace sod2

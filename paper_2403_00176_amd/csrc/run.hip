@@ -1,0 +1,663 @@
+// Launch-table construction (views, strides, kernel versions) and sod2_run.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <functional>
+
+#include "handles.hpp"
+
+namespace sod2 {
+hipError_t launch_gemm(const Launch& L, const GemmArgs& g, hipStream_t s);
+hipError_t launch_conv(const Launch& L, const ConvArgs& c, hipStream_t s);
+hipError_t launch_row(const Launch& L, const RowArgs& a, hipStream_t s);
+hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s);
+hipError_t launch_pool(const Launch& L, const PoolArgs& p, hipStream_t s);
+
+void destroy_events(void* events, int n) {
+  hipEvent_t* e = (hipEvent_t*)events;
+  for (int i = 0; i < n; ++i) (void)hipEventDestroy(e[i]);
+  delete[] e;
+}
+}  // namespace sod2
+
+sod2_binding_s::~sod2_binding_s() {
+  if (events) sod2::destroy_events(events, n_events);
+}
+extern "C" void sod2_binding_destroy(sod2_binding_t* b) { delete b; }
+
+namespace sod2 {
+namespace {
+
+const int64_t kIntMax = 2147483647LL;
+
+struct View {                    // element units
+  int base = -1;
+  int64_t off = 0;
+  std::vector<int64_t> dims, strides;
+  bool contiguous() const {
+    int64_t s = 1;
+    for (int i = (int)dims.size() - 1; i >= 0; --i) {
+      if (dims[i] != 1 && strides[i] != s) return false;
+      s *= dims[i];
+    }
+    return true;
+  }
+  int64_t numel() const { int64_t n = 1; for (auto d : dims) n *= d; return n; }
+};
+
+std::vector<int64_t> contiguous_strides(const std::vector<int64_t>& d) {
+  std::vector<int64_t> s(d.size(), 1);
+  for (int i = (int)d.size() - 2; i >= 0; --i) s[i] = s[i + 1] * d[i + 1];
+  return s;
+}
+
+// strides of a reshaped view, or false when the new shape would need a copy
+bool reshape_strides(const View& in, const std::vector<int64_t>& nd, std::vector<int64_t>* ns) {
+  struct Run { int64_t size, stride; };
+  std::vector<Run> runs;                        // maximal blocks that are flat in memory
+  for (size_t i = 0; i < in.dims.size(); ++i) {
+    if (in.dims[i] == 1) continue;
+    if (!runs.empty() && runs.back().stride == in.strides[i] * in.dims[i]) {
+      runs.back().size *= in.dims[i];
+      runs.back().stride = in.strides[i];
+    } else {
+      runs.push_back({in.dims[i], in.strides[i]});
+    }
+  }
+  ns->assign(nd.size(), 1);
+  size_t r = 0, i = 0;
+  while (i < nd.size()) {
+    if (nd[i] == 1) { (*ns)[i] = 1; ++i; continue; }
+    if (r >= runs.size()) return false;
+    size_t j = i;
+    int64_t prod = 1;
+    while (j < nd.size() && prod < runs[r].size) { prod *= nd[j]; ++j; }
+    if (prod != runs[r].size) return false;
+    int64_t st = runs[r].stride;
+    for (size_t k = j; k-- > i;) { (*ns)[k] = st; st *= nd[k]; }
+    i = j;
+    ++r;
+  }
+  return r == runs.size();
+}
+
+struct Builder {
+  const Plan& p;
+  const Graph& G;
+  const BindResult& b;
+  int force_variant;
+  std::map<int, View> memo;
+  std::map<int, int> widx, iidx, oidx;
+
+  Builder(const Plan& p_, const BindResult& b_, int fv) : p(p_), G(*p_.g), b(b_), force_variant(fv) {
+    for (size_t i = 0; i < G.weight_ids.size(); ++i) widx[G.weight_ids[i]] = (int)i;
+    for (size_t i = 0; i < G.input_ids.size(); ++i) iidx[G.input_ids[i]] = (int)i;
+    for (size_t i = 0; i < G.output_ids.size(); ++i) oidx[G.output_ids[i]] = (int)i;
+  }
+
+  std::vector<int64_t> eval_dims(int t) const {
+    const LS& s = p.rdp->S[t];
+    if (!s.resolved()) throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t].name + " is not resolved");
+    std::vector<int64_t> d;
+    for (const auto& x : s.d) d.push_back(x.e.eval(b.env));
+    return d;
+  }
+  bool live(int t) const {
+    int pr = G.producer[t];
+    return pr < 0 || p.folded[pr] || b.dyn_base.count(t) > 0;
+  }
+
+  const View& view_of(int t) {
+    auto it = memo.find(t);
+    if (it != memo.end()) return it->second;
+    View v;
+    int pr = G.producer[t];
+    if (pr < 0 || (!p.view[pr] && G.ops[pr].kind != SOD2_OP_SWITCH && G.ops[pr].kind != SOD2_OP_COMBINE)) {
+      if (pr >= 0 && p.groups.at(p.group_of_op[pr]).out != t)
+        throw Error(SOD2_ERR_UNSUPPORTED, "tensor inside a fused group is read from outside: " + G.tensors[t].name);
+      v.base = t;
+      v.dims = eval_dims(t);
+      v.strides = contiguous_strides(v.dims);
+    } else {
+      const Op& op = G.ops[pr];
+      if (op.kind == SOD2_OP_SWITCH) v = view_of(op.in[0]);
+      else if (op.kind == SOD2_OP_COMBINE) {
+        int src = -1;
+        for (int i : op.in) if (live(i)) { src = i; break; }
+        if (src < 0) throw Error(SOD2_ERR_INVALID_ARG, "Combine without a live input");
+        v = view_of(src);
+      } else {
+        const View& in = view_of(op.in[0]);
+        v = in;
+        if (op.kind == SOD2_OP_TRANSPOSE) {
+          for (size_t i = 0; i < op.ia.size(); ++i) { v.dims[i] = in.dims[op.ia[i]]; v.strides[i] = in.strides[op.ia[i]]; }
+        } else if (op.kind == SOD2_OP_GATHER) {
+          int64_t r = (int64_t)in.dims.size();
+          int64_t ax = ((op.ia.at(0) % r) + r) % r;
+          int64_t idx = G.tensors[op.in[1]].idata.at(0);
+          if (idx < 0) idx += in.dims[ax];
+          if (idx < 0 || idx >= in.dims[ax]) throw Error(SOD2_ERR_INVALID_ARG, "Gather index out of range");
+          v.off += idx * in.strides[ax];
+          v.dims.erase(v.dims.begin() + ax);
+          v.strides.erase(v.strides.begin() + ax);
+        } else if (op.kind == SOD2_OP_SLICE) {
+          const Tensor &st = G.tensors[op.in[1]], &en = G.tensors[op.in[2]], &ax = G.tensors[op.in[3]];
+          if (!st.has_data || !en.has_data || !ax.has_data)
+            throw Error(SOD2_ERR_UNSUPPORTED, "Slice bounds must be host constants");
+          for (size_t k = 0; k < ax.idata.size(); ++k) {
+            int64_t r = (int64_t)in.dims.size();
+            int64_t a = ((ax.idata[k] % r) + r) % r, D = in.dims[a];
+            int64_t s = st.idata[k] < 0 ? D + st.idata[k] : st.idata[k];
+            int64_t e = en.idata[k] >= kIntMax ? D : (en.idata[k] < 0 ? D + en.idata[k] : en.idata[k]);
+            if (s < 0 || e > D || s > e) throw Error(SOD2_ERR_INVALID_ARG, "Slice bounds outside the tensor");
+            v.off += s * in.strides[a];
+            v.dims[a] = e - s;
+          }
+        } else if (op.kind == SOD2_OP_RESHAPE) {
+          std::vector<int64_t> nd = eval_dims(t), ns;
+          if (View{0, 0, nd, {}}.numel() != in.numel()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Reshape changes the element count");
+          if (!reshape_strides(in, nd, &ns))
+            throw Error(SOD2_ERR_UNSUPPORTED, "Reshape of a strided view needs a copy: " + G.tensors[t].name);
+          v.dims = nd;
+          v.strides = ns;
+        }
+      }
+    }
+    return memo[t] = v;
+  }
+
+  Ref ref_of(const View& v, int dtype) const {
+    Ref r;
+    int t = v.base;
+    int64_t eb = dtype_bytes(dtype);
+    auto at = b.tensors.find(t);
+    if (at != b.tensors.end()) { r.space = SP_ARENA; r.byte_off = at->second.offset + v.off * eb; return r; }
+    r.byte_off = v.off * eb;
+    if (widx.count(t)) { r.space = SP_WEIGHT; r.index = widx.at(t); }
+    else if (oidx.count(t)) { r.space = SP_OUTPUT; r.index = oidx.at(t); }
+    else if (iidx.count(t)) { r.space = SP_INPUT; r.index = iidx.at(t); }
+    else throw Error(SOD2_ERR_INVALID_ARG, "tensor has no storage: " + G.tensors[t].name);
+    return r;
+  }
+  Ref ref_t(int t) { return ref_of(view_of(t), G.tensors[t].dtype); }
+
+  static int act_of(int kind) {
+    return kind == SOD2_OP_RELU ? ACT_RELU : (kind == SOD2_OP_GELU ? ACT_GELU : ACT_SIGMOID);
+  }
+  int other(const Op& op, int cur) const { return op.in[0] == cur ? op.in[1] : op.in[0]; }
+
+  // epilogue description shared by MatMul and Conv groups
+  struct Epi { float scale = 1.f; int bias = -1, res = -1, act1 = ACT_NONE, act2 = ACT_NONE, transpose = -1; };
+  Epi epilogue(const Group& gr) const {
+    Epi e;
+    int cur = G.ops[gr.chain[0]].out[0];
+    for (size_t k = 1; k < gr.chain.size(); ++k) {
+      const Op& op = G.ops[gr.chain[k]];
+      if (op.kind == SOD2_OP_MUL) e.scale *= (float)G.tensors[other(op, cur)].fdata.at(0);
+      else if (op.kind == SOD2_OP_ADD) {
+        int o = other(op, cur);
+        if (G.tensors[o].role == SOD2_WEIGHT && e.bias < 0 && e.res < 0 && e.act1 == ACT_NONE) e.bias = o;
+        else e.res = o;
+      } else if (op.kind == SOD2_OP_TRANSPOSE) e.transpose = gr.chain[k];
+      else (e.res >= 0 ? e.act2 : e.act1) = act_of(op.kind);
+      cur = op.out[0];
+    }
+    return e;
+  }
+
+  int pick_variant(int dtype, int64_t M, int64_t N, int64_t batch) const {
+    if (dtype != SOD2_BF16) return V_SIMPLE;
+    if (force_variant >= 0) return force_variant;
+    if (!p.opts.mvc) return V_REGULAR;
+    if (M <= 48) return V_SKINNY;                                    // skinny: few rows
+    int64_t fat_tiles = ((M + 255) / 256) * ((N + 127) / 128) * batch;
+    if (fat_tiles >= 512) return V_FAT;                              // fat: enough 256x128 tiles for two waves of CUs
+    return V_REGULAR;
+  }
+
+  Launch gemm(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_GEMM;
+    const Op& mm = G.ops[gr.chain[0]];
+    Epi e = epilogue(gr);
+    int dt = G.tensors[mm.in[0]].dtype;
+    if (G.tensors[mm.in[1]].dtype != dt || G.tensors[gr.out].dtype != dt)
+      throw Error(SOD2_ERR_UNSUPPORTED, "MatMul operands and result must share one float type");
+    L.in_dtype = L.out_dtype = dt;
+    const View &va = view_of(mm.in[0]), &vb = view_of(mm.in[1]);
+    bool tb = !mm.ia.empty() && mm.ia[0];
+    size_t ra = va.dims.size(), rb = vb.dims.size();
+    GemmArgs g{};
+    g.M = (int)va.dims[ra - 2];
+    g.K = (int)va.dims[ra - 1];
+    g.N = (int)(tb ? vb.dims[rb - 2] : vb.dims[rb - 1]);
+    if ((tb ? vb.dims[rb - 1] : vb.dims[rb - 2]) != g.K) throw Error(SOD2_ERR_SHAPE_MISMATCH, "MatMul inner dims differ");
+    g.a_sm = va.strides[ra - 2]; g.a_sk = va.strides[ra - 1];
+    g.b_sn = tb ? vb.strides[rb - 2] : vb.strides[rb - 1];
+    g.b_sk = tb ? vb.strides[rb - 1] : vb.strides[rb - 2];
+
+    std::vector<int64_t> logical = eval_dims(mm.out[0]);
+    size_t nbatch = logical.size() - 2;
+    // strides of C (and the residual) per logical dim
+    std::vector<int64_t> cs;
+    if (e.transpose >= 0) {
+      const Op& tp = G.ops[e.transpose];
+      std::vector<int64_t> od(logical.size());
+      for (size_t i = 0; i < tp.ia.size(); ++i) od[i] = logical[tp.ia[i]];
+      std::vector<int64_t> os = contiguous_strides(od);
+      cs.assign(logical.size(), 0);
+      for (size_t i = 0; i < tp.ia.size(); ++i) cs[tp.ia[i]] = os[i];
+    } else {
+      cs = contiguous_strides(logical);
+    }
+    std::vector<int64_t> rs(logical.size(), 0);
+    if (e.res >= 0) {
+      const View& vr = view_of(e.res);
+      if (vr.dims != logical) throw Error(SOD2_ERR_SHAPE_MISMATCH, "residual shape differs from the MatMul result");
+      rs = vr.strides;
+    }
+    auto bstride = [&](const View& v, size_t j) -> int64_t {       // stride of logical batch dim j in operand v
+      size_t r = v.dims.size() - 2;
+      if (j + r < nbatch) return 0;
+      size_t k = j - (nbatch - r);
+      return v.dims[k] == 1 ? 0 : v.strides[k];
+    };
+    struct BD { int64_t n, a, b, c, r; };
+    std::vector<BD> bd;
+    for (size_t j = 0; j < nbatch; ++j)
+      if (logical[j] != 1) bd.push_back({logical[j], bstride(va, j), bstride(vb, j), cs[j], rs[j]});
+    g.c_sm = cs[nbatch]; g.c_sn = cs[nbatch + 1];
+    g.r_sm = rs[nbatch]; g.r_sn = rs[nbatch + 1];
+    int64_t M = g.M;
+    // fold the innermost batch dims into M while every operand stays a plain row walk
+    while (!bd.empty()) {
+      const BD& x = bd.back();
+      bool ok = x.b == 0 && x.a == g.a_sm * M && x.c == g.c_sm * M && (e.res < 0 || x.r == g.r_sm * M);
+      if (!ok) break;
+      M *= x.n;
+      bd.pop_back();
+    }
+    // merge adjacent batch dims
+    for (size_t j = bd.size(); j-- > 1;) {
+      BD &hi = bd[j - 1], &lo = bd[j];
+      if (hi.a == lo.a * lo.n && hi.b == lo.b * lo.n && hi.c == lo.c * lo.n && hi.r == lo.r * lo.n) {
+        hi = {hi.n * lo.n, lo.a, lo.b, lo.c, lo.r};
+        bd.erase(bd.begin() + j);
+      }
+    }
+    if (bd.size() > 2) throw Error(SOD2_ERR_UNSUPPORTED, "MatMul with more than two independent batch dims");
+    while (bd.size() < 2) bd.insert(bd.begin(), {1, 0, 0, 0, 0});
+    if (M > 0x7fffffffLL) throw Error(SOD2_ERR_UNSUPPORTED, "MatMul M too large");
+    g.M = (int)M;
+    g.nb0 = (int)bd[0].n; g.nb1 = (int)bd[1].n;
+    g.a_sb0 = bd[0].a; g.a_sb1 = bd[1].a; g.b_sb0 = bd[0].b; g.b_sb1 = bd[1].b;
+    g.c_sb0 = bd[0].c; g.c_sb1 = bd[1].c; g.r_sb0 = bd[0].r; g.r_sb1 = bd[1].r;
+    g.scale = e.scale; g.act1 = e.act1; g.act2 = e.act2;
+    L.r[0] = ref_of(va, dt);
+    L.r[1] = ref_of(vb, dt);
+    L.r[2] = ref_t(gr.out);
+    if (e.bias >= 0) L.r[3] = ref_t(e.bias);
+    if (e.res >= 0) L.r[4] = ref_of(view_of(e.res), dt);
+    int64_t batch = (int64_t)g.nb0 * g.nb1;
+    L.variant = pick_variant(dt, g.M, g.N, batch);
+    L.u.gemm = g;
+    double eb = dtype_bytes(dt);
+    L.flops = 2.0 * g.M * g.N * g.K * batch;
+    double bcount = (bd[0].b || bd[1].b) ? (double)batch : ((bd[1].b || g.nb0 == 1) ? 1.0 : 1.0);
+    L.bytes = eb * ((double)g.M * g.K * batch + (double)g.N * g.K * bcount + (double)g.M * g.N * batch * (e.res >= 0 ? 2 : 1) +
+                    (e.bias >= 0 ? g.N : 0));
+    return L;
+  }
+
+  Launch conv(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_CONV;
+    const Op& cv = G.ops[gr.chain[0]];
+    Epi e = epilogue(gr);
+    if (e.transpose >= 0 || e.scale != 1.f) throw Error(SOD2_ERR_UNSUPPORTED, "Conv epilogue with scale or transpose");
+    int dt = G.tensors[cv.in[0]].dtype;
+    L.in_dtype = L.out_dtype = dt;
+    const View &vx = view_of(cv.in[0]), &vw = view_of(cv.in[1]);
+    if (!vx.contiguous() || !vw.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "Conv needs contiguous NHWC operands");
+    std::vector<int64_t> od = eval_dims(cv.out[0]);
+    ConvArgs c{};
+    c.NB = (int)vx.dims[0]; c.H = (int)vx.dims[1]; c.W = (int)vx.dims[2]; c.C = (int)vx.dims[3];
+    c.O = (int)vw.dims[0]; c.KH = (int)vw.dims[1]; c.KW = (int)vw.dims[2];
+    c.stride = (int)cv.ia.at(0); c.pad = (int)cv.ia.at(1);
+    c.OH = (int)od[1]; c.OW = (int)od[2];
+    c.act1 = e.act1; c.act2 = e.act2;
+    c.vec = c.C % 8 == 0;
+    if ((int64_t)c.NB * c.OH * c.OW > 0x7fffffffLL) throw Error(SOD2_ERR_UNSUPPORTED, "Conv output too large");
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_of(vw, dt);
+    L.r[2] = ref_t(gr.out);
+    if (e.bias >= 0) L.r[3] = ref_t(e.bias);
+    if (e.res >= 0) {
+      const View& vr = view_of(e.res);
+      if (!vr.contiguous() || vr.dims != od) throw Error(SOD2_ERR_UNSUPPORTED, "Conv residual must be contiguous and of the output shape");
+      L.r[4] = ref_of(vr, dt);
+    }
+    int64_t M = (int64_t)c.NB * c.OH * c.OW;
+    L.variant = pick_variant(dt, M, c.O, 1);
+    L.u.conv = c;
+    double eb = dtype_bytes(dt), K = (double)c.KH * c.KW * c.C;
+    L.flops = 2.0 * M * c.O * K;
+    L.bytes = eb * ((double)vx.numel() + (double)c.O * K + (double)M * c.O * (e.res >= 0 ? 2 : 1) + c.O);
+    return L;
+  }
+
+  // rows x cols walk of a view whose last dim is dense
+  void rows_of(const View& v, int64_t* rows, int64_t* stride) const {
+    size_t r = v.dims.size();
+    if (r == 0 || (v.dims[r - 1] != 1 && v.strides[r - 1] != 1)) throw Error(SOD2_ERR_UNSUPPORTED, "row kernel needs a dense last dim");
+    int64_t n = 1, st = r >= 2 ? v.strides[r - 2] : v.dims[r - 1];
+    for (size_t i = 0; i + 1 < r; ++i) n *= v.dims[i];
+    int64_t expect = st;
+    for (int i = (int)r - 2; i >= 0; --i) {
+      if (v.dims[i] != 1 && v.strides[i] != expect) throw Error(SOD2_ERR_UNSUPPORTED, "row kernel needs evenly spaced rows");
+      expect *= v.dims[i];
+    }
+    *rows = n;
+    *stride = st;
+  }
+
+  Launch row(const Group& gr, bool layernorm) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = layernorm ? K_LAYERNORM : K_SOFTMAX;
+    L.is_layernorm = layernorm;
+    const Op& op = G.ops[gr.chain[0]];
+    int dt = G.tensors[op.in[0]].dtype;
+    if (G.tensors[gr.out].dtype != dt) throw Error(SOD2_ERR_UNSUPPORTED, "row kernel changes the dtype");
+    L.in_dtype = L.out_dtype = dt;
+    const View& vx = view_of(op.in[0]);
+    RowArgs a{};
+    int64_t rows, xs;
+    rows_of(vx, &rows, &xs);
+    a.rows = rows;
+    a.cols = (int)vx.dims.back();
+    a.x_stride = xs;
+    a.y_stride = a.cols;
+    a.eps = (float)op.fa;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_t(gr.out);
+    if (layernorm) {
+      L.r[2] = ref_t(op.in[1]);
+      L.r[3] = ref_t(op.in[2]);
+    } else {
+      a.causal = !op.ia.empty() && op.ia[0];
+      a.lq = vx.dims.size() >= 2 ? (int)vx.dims[vx.dims.size() - 2] : 1;
+    }
+    L.u.row = a;
+    double eb = dtype_bytes(dt);
+    L.flops = (layernorm ? 8.0 : 5.0) * rows * a.cols;
+    L.bytes = eb * (2.0 * rows * a.cols + (layernorm ? 2.0 * a.cols : 0));
+    return L;
+  }
+
+  Launch reduce(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_REDUCE;
+    const Op& op = G.ops[gr.chain[0]];
+    const View& vx = view_of(op.in[0]);
+    if (!vx.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "ReduceMean needs a contiguous input");
+    int64_t r = (int64_t)vx.dims.size();
+    std::vector<int64_t> axes;
+    for (size_t k = 1; k < op.ia.size(); ++k) axes.push_back(((op.ia[k] % r) + r) % r);
+    std::sort(axes.begin(), axes.end());
+    for (size_t k = 1; k < axes.size(); ++k)
+      if (axes[k] != axes[k - 1] + 1) throw Error(SOD2_ERR_UNSUPPORTED, "ReduceMean axes must be adjacent");
+    ReduceArgs a{};
+    int64_t batch = 1, R = 1, C = 1;
+    for (int64_t i = 0; i < r; ++i) {
+      if (i < axes.front()) batch *= vx.dims[i];
+      else if (i <= axes.back()) R *= vx.dims[i];
+      else C *= vx.dims[i];
+    }
+    a.batch = (int)batch; a.R = R; a.C = (int)C;
+    L.in_dtype = G.tensors[op.in[0]].dtype;
+    L.out_dtype = G.tensors[gr.out].dtype;
+    L.r[0] = ref_of(vx, L.in_dtype);
+    L.r[1] = ref_t(gr.out);
+    L.u.red = a;
+    L.flops = (double)batch * R * C;
+    L.bytes = (double)batch * R * C * dtype_bytes(L.in_dtype) + (double)batch * C * dtype_bytes(L.out_dtype);
+    return L;
+  }
+
+  Launch pool(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_POOL;
+    const Op& op = G.ops[gr.chain[0]];
+    const View& vx = view_of(op.in[0]);
+    if (!vx.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "MaxPool needs a contiguous input");
+    std::vector<int64_t> od = eval_dims(gr.out);
+    PoolArgs a{};
+    a.NB = (int)vx.dims[0]; a.H = (int)vx.dims[1]; a.W = (int)vx.dims[2]; a.C = (int)vx.dims[3];
+    a.OH = (int)od[1]; a.OW = (int)od[2];
+    a.k = (int)op.ia.at(0); a.stride = (int)op.ia.at(1); a.pad = (int)op.ia.at(2);
+    L.in_dtype = L.out_dtype = G.tensors[op.in[0]].dtype;
+    L.r[0] = ref_of(vx, L.in_dtype);
+    L.r[1] = ref_t(gr.out);
+    L.u.pool = a;
+    double n_out = (double)a.NB * a.OH * a.OW * a.C;
+    L.flops = n_out * a.k * a.k;
+    L.bytes = dtype_bytes(L.in_dtype) * ((double)vx.numel() + n_out);
+    return L;
+  }
+
+  Launch make(const Group& gr) {
+    switch (gr.kind) {
+      case G_GEMM: return gemm(gr);
+      case G_CONV: return conv(gr);
+      case G_LAYERNORM: return row(gr, true);
+      case G_SOFTMAX: return row(gr, false);
+      case G_REDUCEMEAN: return reduce(gr);
+      case G_MAXPOOL: return pool(gr);
+      default:
+        throw Error(SOD2_ERR_UNSUPPORTED, std::string("no kernel for group kind ") + group_kind_name(gr.kind));
+    }
+  }
+};
+
+struct Pointers {
+  char* arena; size_t arena_bytes;
+  const void* const* w; int nw;
+  const void* const* in; int nin;
+  void* const* out; int nout;
+  void* at(const Ref& r) const {
+    switch (r.space) {
+      case SP_ARENA: return arena + r.byte_off;
+      case SP_WEIGHT: return (char*)w[r.index] + r.byte_off;
+      case SP_INPUT: return (char*)in[r.index] + r.byte_off;
+      case SP_OUTPUT: return (char*)out[r.index] + r.byte_off;
+      default: return nullptr;
+    }
+  }
+};
+
+bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
+  switch (L.kernel) {
+    case K_GEMM: {
+      GemmArgs g = L.u.gemm;
+      g.A = P.at(L.r[0]); g.B = P.at(L.r[1]); g.C = P.at(L.r[2]);
+      g.bias = P.at(L.r[3]); g.res = P.at(L.r[4]);
+      g.a_vec = g.a_sk == 1 && g.K % 8 == 0 && g.a_sm % 8 == 0 && g.a_sb0 % 8 == 0 && g.a_sb1 % 8 == 0 && al16(g.A);
+      bool bal = g.b_sb0 % 8 == 0 && g.b_sb1 % 8 == 0 && al16(g.B);
+      if (g.b_sk == 1 && g.K % 8 == 0 && g.b_sn % 8 == 0 && bal) g.b_mode = 0;
+      else if (g.b_sn == 1 && g.N % 8 == 0 && g.b_sk % 8 == 0 && bal) g.b_mode = 1;
+      else g.b_mode = 2;
+      return launch_gemm(L, g, s);
+    }
+    case K_CONV: {
+      ConvArgs c = L.u.conv;
+      c.x = P.at(L.r[0]); c.w = P.at(L.r[1]); c.y = P.at(L.r[2]);
+      c.bias = P.at(L.r[3]); c.res = P.at(L.r[4]);
+      c.vec = c.vec && al16(c.x);
+      return launch_conv(L, c, s);
+    }
+    case K_LAYERNORM: case K_SOFTMAX: {
+      RowArgs a = L.u.row;
+      a.x = P.at(L.r[0]); a.y = P.at(L.r[1]); a.gamma = P.at(L.r[2]); a.beta = P.at(L.r[3]);
+      return launch_row(L, a, s);
+    }
+    case K_REDUCE: {
+      ReduceArgs a = L.u.red;
+      a.x = P.at(L.r[0]); a.y = P.at(L.r[1]);
+      return launch_reduce(L, a, s);
+    }
+    case K_POOL: {
+      PoolArgs a = L.u.pool;
+      a.x = P.at(L.r[0]); a.y = P.at(L.r[1]);
+      return launch_pool(L, a, s);
+    }
+    default:
+      return hipErrorInvalidValue;
+  }
+}
+
+// launch table for every executed group step of `b`, indexed by step (-1 kernel for control steps)
+std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force_variant) {
+  Builder B(p, b, force_variant);
+  std::vector<Launch> out;
+  for (int i : b.steps) {
+    const Item& it = p.items[i];
+    if (!it.is_group) { Launch L; L.kernel = -1; L.group = it.ref; out.push_back(L); continue; }
+    out.push_back(B.make(p.groups.at(it.ref)));
+  }
+  return out;
+}
+
+}  // namespace
+}  // namespace sod2
+
+using namespace sod2;
+
+extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_bytes, const void* const* weights,
+                                int32_t n_weights, const void* const* inputs, int32_t n_inputs, void* const* outputs,
+                                int32_t n_outputs, void* stream) {
+  try {
+    if (!h) throw Error(SOD2_ERR_INVALID_ARG, "null binding");
+    const Plan& p = *h->plan;
+    const Graph& G = *p.g;
+    if (n_weights != (int)G.weight_ids.size() || n_inputs != (int)G.input_ids.size() || n_outputs != (int)G.output_ids.size())
+      throw Error(SOD2_ERR_INVALID_ARG, "wrong number of weight, input or output pointers");
+    for (int i = 0; i < n_weights; ++i) if (!weights[i]) throw Error(SOD2_ERR_INVALID_ARG, "null weight pointer");
+    for (int i = 0; i < n_inputs; ++i) if (!inputs[i]) throw Error(SOD2_ERR_INVALID_ARG, "null input pointer");
+    for (int i = 0; i < n_outputs; ++i) if (!outputs[i]) throw Error(SOD2_ERR_INVALID_ARG, "null output pointer");
+    if ((size_t)h->b.arena_bytes > arena_bytes || (h->b.arena_bytes > 0 && !arena))
+      throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, plan needs " +
+                                                std::to_string(h->b.arena_bytes));
+    if (((uintptr_t)arena & 255) != 0) throw Error(SOD2_ERR_INVALID_ARG, "arena must be 256-byte aligned");
+    hipStream_t s = (hipStream_t)stream;
+    Pointers P{(char*)arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs};
+
+    if (!h->launches_valid) {
+      h->launches = build_launches(p, h->b, h->force_variant);
+      h->launches_valid = true;
+    }
+    h->records.clear();
+    h->last_decisions.clear();
+    hipEvent_t* ev = nullptr;
+    if (h->profiling) {
+      int need = 2 * (int)h->b.steps.size() + 2 * (int)p.items.size();
+      if (h->n_events < need) {
+        if (h->events) destroy_events(h->events, h->n_events);
+        ev = new hipEvent_t[need];
+        for (int i = 0; i < need; ++i)
+          if (hipEventCreate(&ev[i]) != hipSuccess) throw Error(SOD2_ERR_HIP, "hipEventCreate failed");
+        h->events = ev;
+        h->n_events = need;
+      }
+      ev = (hipEvent_t*)h->events;
+    }
+    int n_ev = 0;
+    std::vector<std::pair<int, Launch>> timed;
+
+    const BindResult* cur = &h->b;
+    const std::vector<Launch>* launches = &h->launches;
+    BindResult replanned;
+    std::vector<Launch> relaunch;
+    std::vector<int> decisions = h->planned_decisions;
+    std::map<int, int64_t> used_offset;             // arena tensor -> offset used by an executed kernel
+    size_t k = 0;
+    while (k < cur->steps.size()) {
+      const Item& it = p.items[cur->steps[k]];
+      const Launch& L = (*launches)[k];
+      if (it.is_group) {
+        auto at = cur->tensors.find(p.groups.at(it.ref).out);
+        if (at != cur->tensors.end()) used_offset[at->first] = at->second.offset;
+        if (ev) (void)hipEventRecord(ev[n_ev], s);
+        hipError_t e = dispatch(L, P, s);
+        if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
+        if (ev) { (void)hipEventRecord(ev[n_ev + 1], s); timed.push_back({n_ev, L}); n_ev += 2; }
+      } else if (G.ops[it.ref].kind == SOD2_OP_SWITCH) {
+        // position of this Switch among the executed ones
+        size_t which = std::find(cur->switch_order.begin(), cur->switch_order.end(), it.ref) - cur->switch_order.begin();
+        if (which >= decisions.size()) {
+          // the predicate is execution determined: read it back, decide, plan what follows (Section 4.3)
+          int dec;
+          if (h->has_forced && which < h->forced.size()) {
+            dec = h->forced[which] ? 1 : 0;
+          } else {
+            const Op& op = G.ops[it.ref];
+            Builder B(p, *cur, h->force_variant);
+            Ref r = B.ref_t(op.in[1]);
+            float hv = 0.f;
+            uint16_t hb = 0;
+            int dt = G.tensors[op.in[1]].dtype;
+            hipError_t e = dt == SOD2_BF16 ? hipMemcpyAsync(&hb, P.at(r), 2, hipMemcpyDeviceToHost, s)
+                                           : hipMemcpyAsync(&hv, P.at(r), 4, hipMemcpyDeviceToHost, s);
+            if (e == hipSuccess) e = hipStreamSynchronize(s);
+            if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("predicate read failed: ") + hipGetErrorString(e));
+            if (dt == SOD2_BF16) { uint32_t u = (uint32_t)hb << 16; std::memcpy(&hv, &u, 4); }
+            dec = hv > (float)op.fa ? 1 : 0;
+          }
+          decisions.push_back(dec);
+          replanned = bind_plan(p, h->symbols, decisions, true);
+          if ((size_t)replanned.arena_bytes > arena_bytes)
+            throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena too small for the executed path");
+          relaunch = build_launches(p, replanned, h->force_variant);
+          cur = &replanned;
+          launches = &relaunch;
+        }
+      }
+      ++k;
+    }
+    for (int sw : cur->switch_order) h->last_decisions.push_back(cur->decisions.at(sw));
+    for (const auto& kv : used_offset) {
+      auto at = cur->tensors.find(kv.first);
+      if (at == cur->tensors.end() || at->second.offset != kv.second)
+        throw Error(SOD2_ERR_NONCAUSAL_PLAN, "an offset used before a Switch differs from the final plan");
+    }
+    if (ev) {
+      if (hipStreamSynchronize(s) != hipSuccess) throw Error(SOD2_ERR_HIP, "stream synchronise failed");
+      for (const auto& t : timed) {
+        sod2_launch_record r{};
+        r.group = t.second.group; r.kernel = t.second.kernel; r.variant = t.second.variant;
+        (void)hipEventElapsedTime(&r.ms, ev[t.first], ev[t.first + 1]);
+        r.flops = t.second.flops; r.bytes = t.second.bytes;
+        h->records.push_back(r);
+      }
+    }
+    if (cur == &replanned) {          // keep the executed plan for queries
+      h->executed = replanned;
+      h->has_executed = true;
+    }
+  } catch (const sod2::Error& e) {
+    sod2::set_error(e.what());
+    return e.code;
+  } catch (const std::exception& e) {
+    sod2::set_error(e.what());
+    return SOD2_ERR_INVALID_ARG;
+  }
+  return SOD2_OK;
+}

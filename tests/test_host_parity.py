@@ -1,0 +1,130 @@
+"""Host half of the library against the oracle, byte for byte: RDP maps, fusion groups,
+execution order, executed steps, lifetimes and arena offsets.  No GPU needed."""
+import random
+import re
+
+import pytest
+
+import paper_2403_00176_amd as S
+from oracle import rdp as R, plan as P, arena as A
+from workloads import configs, GraphBuilder
+
+
+def small(cfg):
+    return {1: configs.config1, 2: lambda: configs.config2(8, layers=3),
+            3: lambda: configs.resnet50(3, 6, stages=(2, 2, 1, 1)),
+            4: lambda: configs.config4(6, layers=3)}[cfg]()
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(S.LIB_PATH.replace("paper_2403_00176_amd/libsod2.so", "include/sod2.h")).read()
+    declared = set(re.findall(r"\b(sod2_[a-z_0-9]+)\s*\(", header))
+    assert declared, "no declarations found"
+    for name in declared:
+        assert hasattr(S._lib, name), name
+    assert declared == set(S.EXPORTS)
+    assert "gfx950" in S.sod2_version()
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+def test_rdp_plan_bind_match_oracle(cfg):
+    w = small(cfg)
+    g = S.sod2_graph_build(w.graph)
+    r = S.sod2_rdp_infer(g)
+    ro = R.RDP(w.graph).analyse()
+    assert S.sod2_rdp_dump(r) == R.dump(ro)
+    assert S.sod2_rdp_sweeps(r) == ro.sweeps
+    for opts in (dict(), dict(fusion=0), dict(sep=0), dict(dmp=0)):
+        p = S.sod2_plan(g, r, **{k: v for k, v in opts.items()})
+        po = P.build_plan(w.graph, ro, P.Opts(**{k: bool(v) for k, v in opts.items()}))
+        assert S.sod2_plan_dump(p) == P.dump(po)
+        n_sw = sum(1 for op in w.graph.ops if op.kind == "Switch")
+        assert S.sod2_plan_counts(p) == (len(po.groups), len(po.subgraphs), n_sw)
+        rnd = random.Random(cfg)
+        for call in w.calls:
+            dec = [rnd.random() < 0.5 for _ in range(n_sw)]
+            b = S.sod2_bind(p, call, dec)
+            bo = A.bind(po, call, dec)
+            assert S.sod2_binding_dump(b) == A.dump(bo)
+            assert S.sod2_binding_arena_bytes(b) == (bo.arena_bytes, bo.peak_live)
+
+
+def test_full_size_configs_match_oracle():
+    for cfg in (2, 3):
+        w = configs.BUILDERS[cfg]()
+        g = S.sod2_graph_build(w.graph)
+        r = S.sod2_rdp_infer(g)
+        ro = R.RDP(w.graph).analyse()
+        assert S.sod2_rdp_dump(r) == R.dump(ro)
+        p = S.sod2_plan(g, r)
+        po = P.build_plan(w.graph, ro)
+        assert S.sod2_plan_dump(p) == P.dump(po)
+        for call in w.calls[:6]:
+            assert S.sod2_binding_dump(S.sod2_bind(p, call)) == A.dump(A.bind(po, call))
+
+
+def test_order_independence_and_classes():
+    w = configs.config4(1, layers=2)
+    g = S.sod2_graph_build(w.graph)
+    ref = S.sod2_rdp_dump(S.sod2_rdp_infer(g))
+    rnd = random.Random(3)
+    for _ in range(5):
+        order = list(range(len(w.graph.ops)))
+        rnd.shuffle(order)
+        assert S.sod2_rdp_dump(S.sod2_rdp_infer(g, order)) == ref
+    for i, op in enumerate(w.graph.ops):
+        assert S.sod2_graph_op_class(g, i) == R.OP_CLASS[op.kind]
+    rank, dims = S.sod2_rdp_query(S.sod2_rdp_infer(g), w.graph.tensor_id("x"))
+    assert rank == 3 and dims[0][:2] == (0, 4) and dims[1][0] == 1 and dims[1][2] == "L"
+
+
+def test_error_paths():
+    w = configs.config2(1, layers=1)
+    g = S.sod2_graph_build(w.graph)
+    r = S.sod2_rdp_infer(g)
+    p = S.sod2_plan(g, r)
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_bind(p, {"B": 9, "L": 64})
+    assert e.value.code == -2
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_bind(p, [1])
+    assert e.value.code == -1
+    b = GraphBuilder([])
+    x = b.input("x", "f32", [4, 8])
+    b.mark_output(b.op("MatMul", [x, b.weight("w", "f32", [7, 16])], transB=0))
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_rdp_infer(S.sod2_graph_build(b.build()))
+    assert e.value.code == -3
+    # a nac shape reaching a kernel is refused at bind
+    b = GraphBuilder([("I", 1, 9)])
+    x = b.input("x", "f32", ["I", 4])
+    nz = b.op("NonZero", [x], dtype="i64")
+    b.mark_output(b.op("Cast", [nz], dtype="f32"))
+    gd = b.build()
+    g2 = S.sod2_graph_build(gd)
+    r2 = S.sod2_rdp_infer(g2)
+    p2 = S.sod2_plan(g2, r2)
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_bind(p2, {"I": 3})
+    assert e.value.code == -4
+    # run without a device: bad pointers are refused before any launch
+    bnd = S.sod2_bind(p, {"B": 1, "L": 32})
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_run(bnd, 0, 0, [1] * len(w.graph.weights()), [1], [1])
+    assert e.value.code == -5
+    w4 = configs.config4(1, layers=2)
+    g4 = S.sod2_graph_build(w4.graph)
+    p4 = S.sod2_plan(g4, S.sod2_rdp_infer(g4))
+    with pytest.raises(S.Sod2Error):
+        S.sod2_bind(p4, {"L": 128}, [1])          # one decision short
+    assert S.sod2_binding_arena_bytes(S.sod2_bind(p4, {"L": 128}))[0] > 0   # undecided: plans every branch
+
+
+def test_tiny_fixture_graphs_match_oracle():
+    from tests.test_oracle_rdp import _tiny_graphs
+    for gd in _tiny_graphs():
+        g = S.sod2_graph_build(gd)
+        r = S.sod2_rdp_infer(g)
+        ro = R.RDP(gd).analyse()
+        assert S.sod2_rdp_dump(r) == R.dump(ro)
+        assert S.sod2_plan_dump(S.sod2_plan(g, r)) == P.dump(P.build_plan(gd, ro))
