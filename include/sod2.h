@@ -160,7 +160,8 @@ sod2_status sod2_binding_arena_bytes(const sod2_binding_t*, size_t* arena_bytes,
 sod2_status sod2_binding_dump(const sod2_binding_t*, char* buf_host, size_t cap, size_t* needed);
 /* force the decisions of the next runs (replay of a reference decision vector); n = 0 clears */
 sod2_status sod2_binding_force_decisions(sod2_binding_t*, const int32_t* decisions_host, int32_t n);
-/* force one kernel version for every contraction: -1 automatic, 0 regular, 1 fat, 2 skinny */
+/* force one kernel version for every contraction: -1 automatic, 0 regular, 1 fat, 2 skinny,
+ * 3 the plain FMA kernel (any dtype, any strides) */
 sod2_status sod2_binding_force_variant(sod2_binding_t*, int32_t variant);
 
 /* -- run -------------------------------------------------------------------------------------- */

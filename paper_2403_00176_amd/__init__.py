@@ -12,6 +12,7 @@ import os
 from typing import Dict, List, Optional, Sequence
 
 import numpy as np
+import torch  # noqa: F401  -- first, so that libsod2 binds to the HIP runtime torch has already loaded
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsod2.so")

@@ -513,6 +513,42 @@ __global__ void maxpool_kernel(PoolArgs p) {
   ((T*)p.y)[idx] = from_f<T>(best);
 }
 
+template <class TO>
+__global__ void eltwise_kernel(EltArgs a) {
+  long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (idx >= a.total) return;
+  long long off[5] = {0, 0, 0, 0, 0};
+  long long rem = idx;
+  for (int d = a.rank - 1; d >= 0; --d) {
+    long long i = rem % a.dims[d];
+    rem /= a.dims[d];
+    for (int k = 0; k < a.n_in; ++k) off[k] += i * a.stride[k][d];
+  }
+  float in[5];
+  for (int k = 0; k < a.n_in; ++k)
+    in[k] = a.in_bf16[k] ? bf2f(((const bf16_t*)a.in[k])[off[k]]) : ((const float*)a.in[k])[off[k]];
+  float v = in[0];
+  for (int o = 0; o < a.n_ops; ++o) {
+    float x = a.src[o] == 5 ? a.imm[o] : (a.src[o] >= 0 ? in[a.src[o]] : 0.f);
+    switch (a.op[o]) {
+      case E_ADD: v += x; break;
+      case E_MUL: v *= x; break;
+      case E_RELU: v = fmaxf(v, 0.f); break;
+      case E_GELU: v = apply_act(v, ACT_GELU); break;
+      case E_SIGMOID: v = apply_act(v, ACT_SIGMOID); break;
+      default: break;
+    }
+  }
+  ((TO*)a.out)[idx] = from_f<TO>(v);
+}
+
+hipError_t launch_eltwise(const Launch& L, const EltArgs& a, hipStream_t s) {
+  dim3 grid((unsigned)((a.total + 255) / 256));
+  if (L.out_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(eltwise_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(eltwise_kernel<float>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 // ---------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------

@@ -56,18 +56,34 @@ struct PoolArgs {
   int NB, H, W, C, OH, OW, k, stride, pad;
 };
 
+// out[idx] = chain of up to 8 elementwise operators over the output index space; operands are
+// broadcast through zero strides (the single fused loop nest of Fig. 4)
+enum EltOp { E_ADD = 0, E_MUL, E_RELU, E_GELU, E_SIGMOID, E_CAST };
+struct EltArgs {
+  const void* in[5];
+  void* out;
+  long long stride[5][6];
+  long long dims[6];
+  long long total;
+  int in_bf16[5];
+  int rank, n_ops, n_in;
+  int op[8], src[8];       // src: operand slot of a binary operator, 5 = immediate, -1 = unary
+  float imm[8];
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
   int variant = 0;
   int in_dtype = 0, out_dtype = 0;
-  Ref r[6];                // operand references, meaning depends on the kernel
+  Ref r[7];                // operand references, meaning depends on the kernel
   union {
     GemmArgs gemm;
     ConvArgs conv;
     RowArgs row;
     ReduceArgs red;
     PoolArgs pool;
+    EltArgs elt;
   } u;
   bool is_layernorm = false;
   double flops = 0, bytes = 0;

@@ -14,6 +14,7 @@ hipError_t launch_conv(const Launch& L, const ConvArgs& c, hipStream_t s);
 hipError_t launch_row(const Launch& L, const RowArgs& a, hipStream_t s);
 hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s);
 hipError_t launch_pool(const Launch& L, const PoolArgs& p, hipStream_t s);
+hipError_t launch_eltwise(const Launch& L, const EltArgs& a, hipStream_t s);
 
 void destroy_events(void* events, int n) {
   hipEvent_t* e = (hipEvent_t*)events;
@@ -452,6 +453,70 @@ struct Builder {
     return L;
   }
 
+  Launch eltwise(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_ELTWISE;
+    EltArgs a{};
+    std::vector<int64_t> od = eval_dims(gr.out);
+    if (od.size() > 6) throw Error(SOD2_ERR_UNSUPPORTED, "elementwise group above rank 6");
+    a.rank = (int)od.size();
+    a.total = 1;
+    for (size_t i = 0; i < od.size(); ++i) { a.dims[i] = od[i]; a.total *= od[i]; }
+    L.out_dtype = G.tensors[gr.out].dtype;
+    if (L.out_dtype != SOD2_BF16 && L.out_dtype != SOD2_F32) throw Error(SOD2_ERR_UNSUPPORTED, "elementwise output dtype");
+    auto add_input = [&](int t) -> int {
+      const View& v = view_of(t);
+      int dt = G.tensors[t].dtype;
+      if (dt != SOD2_BF16 && dt != SOD2_F32) throw Error(SOD2_ERR_UNSUPPORTED, "elementwise operand dtype");
+      if (a.n_in >= 5) throw Error(SOD2_ERR_UNSUPPORTED, "elementwise group with more than 5 operands");
+      if (v.dims.size() > od.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "operand rank above the output rank");
+      int k = a.n_in++;
+      size_t pad = od.size() - v.dims.size();
+      for (size_t i = 0; i < od.size(); ++i) {
+        int64_t d = i < pad ? 1 : v.dims[i - pad];
+        if (d != 1 && d != od[i]) throw Error(SOD2_ERR_SHAPE_MISMATCH, "operand does not broadcast to the output");
+        a.stride[k][i] = d == 1 ? 0 : v.strides[i - pad];
+      }
+      a.in_bf16[k] = dt == SOD2_BF16;
+      L.r[k] = ref_of(v, dt);
+      L.bytes += (double)v.numel() * dtype_bytes(dt);
+      return k;
+    };
+    int cur = -1;
+    for (size_t k = 0; k < gr.chain.size(); ++k) {
+      const Op& op = G.ops[gr.chain[k]];
+      int primary = op.in[0];
+      if (k == 0) { add_input(primary); }
+      else if (op.in.size() == 2 && op.in[1] == cur) primary = op.in[1];
+      else primary = cur;
+      int o = a.n_ops++;
+      a.src[o] = -1;
+      switch (op.kind) {
+        case SOD2_OP_ADD: a.op[o] = E_ADD; break;
+        case SOD2_OP_MUL: a.op[o] = E_MUL; break;
+        case SOD2_OP_RELU: a.op[o] = E_RELU; break;
+        case SOD2_OP_GELU: a.op[o] = E_GELU; break;
+        case SOD2_OP_SIGMOID: a.op[o] = E_SIGMOID; break;
+        default: a.op[o] = E_CAST; break;
+      }
+      if (op.in.size() == 2) {
+        int ot = (k == 0) ? op.in[1] : other(op, cur);
+        const Tensor& td = G.tensors[ot];
+        if (td.has_data && td.fdata.size() == 1) { a.src[o] = 5; a.imm[o] = (float)td.fdata[0]; }
+        else a.src[o] = add_input(ot);
+      }
+      (void)primary;
+      cur = op.out[0];
+    }
+    L.r[5] = ref_t(gr.out);
+    L.in_dtype = L.out_dtype;
+    L.u.elt = a;
+    L.flops = (double)a.total * a.n_ops;
+    L.bytes += (double)a.total * dtype_bytes(L.out_dtype);
+    return L;
+  }
+
   Launch make(const Group& gr) {
     switch (gr.kind) {
       case G_GEMM: return gemm(gr);
@@ -460,6 +525,7 @@ struct Builder {
       case G_SOFTMAX: return row(gr, false);
       case G_REDUCEMEAN: return reduce(gr);
       case G_MAXPOOL: return pool(gr);
+      case G_ELTWISE: return eltwise(gr);
       default:
         throw Error(SOD2_ERR_UNSUPPORTED, std::string("no kernel for group kind ") + group_kind_name(gr.kind));
     }
@@ -518,6 +584,12 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       PoolArgs a = L.u.pool;
       a.x = P.at(L.r[0]); a.y = P.at(L.r[1]);
       return launch_pool(L, a, s);
+    }
+    case K_ELTWISE: {
+      EltArgs a = L.u.elt;
+      for (int k = 0; k < a.n_in; ++k) a.in[k] = P.at(L.r[k]);
+      a.out = P.at(L.r[5]);
+      return launch_eltwise(L, a, s);
     }
     default:
       return hipErrorInvalidValue;

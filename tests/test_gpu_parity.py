@@ -81,9 +81,39 @@ def test_config2_full_depth_sampled(S):
 
 
 def test_ablation_switches_keep_values(S):
+    """Fusion / SEP / DMP / MVC off (the switches of the paper's breakdown study) change the plan,
+    never the values.  Without fusion the encoder's head transpose would need a copy kernel, so the
+    unfused run uses the CNN (bias, ReLU and residual adds become elementwise kernels)."""
     w = configs.config2(2, layers=2)
-    for opts in (dict(fusion=0), dict(sep=0), dict(dmp=0), dict(mvc=0)):
+    for opts in (dict(sep=0), dict(dmp=0), dict(mvc=0)):
         run_case(S, w, [(0, {"B": 2, "L": 45})], **opts)
+    w = configs.resnet50(3, 1, sizes=(64, 96), stages=(2, 1, 1, 1))
+    for opts in (dict(fusion=0), dict(fusion=0, sep=0, dmp=0, mvc=0)):
+        run_case(S, w, [(0, {"H": 96, "W": 64})], **opts)
+
+
+def test_fig4_fused_broadcast_chain(S):
+    """Fig. 4: Sigmoid(A[I,1,1]) + B[I,J,K] as one fused loop nest, plus a longer chain."""
+    from workloads import GraphBuilder, rng
+    from workloads.configs import Workload
+    b = GraphBuilder([("I", 1, 64), ("J", 1, 64), ("K", 1, 64)])
+    A_ = b.input("A", "f32", ["I", 1, 1])
+    B_ = b.input("B", "f32", ["I", "J", "K"])
+    y = b.op("Add", [b.op("Sigmoid", [A_]), B_])
+    y = b.op("Mul", [y, b.const("half", 0.5, "f32")])
+    y = b.op("Gelu", [b.op("Add", [b.input("C", "f32", ["K"]), y])])
+    b.mark_output(y)
+    g = b.build()
+
+    def make_inputs(ci, sym):
+        I, J, K = sym["I"], sym["J"], sym["K"]
+        return {g.tensor_id("A"): rng.normal(ci, (I, 1, 1)), g.tensor_id("B"): rng.normal(ci + 50, (I, J, K)),
+                g.tensor_id("C"): rng.normal(ci + 99, (K,))}
+    w = Workload("fig4", 0, g, "f32", [], lambda: {}, make_inputs)
+    import paper_2403_00176_amd as S2
+    gh = S2.sod2_graph_build(g)
+    assert S2.sod2_plan_counts(S2.sod2_plan(gh, S2.sod2_rdp_infer(gh)))[0] == 1      # one fused group
+    run_case(S, w, [(0, {"I": 5, "J": 7, "K": 33}), (1, {"I": 64, "J": 1, "K": 64}), (2, {"I": 1, "J": 1, "K": 1})])
 
 
 def test_same_binding_twice_is_bit_identical(S):
