@@ -124,7 +124,7 @@ class _Handle:
         self._keep = keep
 
     def __del__(self):
-        if getattr(self, "ptr", None):
+        if getattr(self, "ptr", None) and _lib is not None:      # _lib is gone at interpreter exit
             getattr(_lib, self._destroy)(self.ptr)
             self.ptr = None
 

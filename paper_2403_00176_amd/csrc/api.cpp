@@ -224,7 +224,7 @@ sod2_status sod2_binding_force_decisions(sod2_binding_t* b, const int32_t* dec, 
   return SOD2_OK;
 }
 sod2_status sod2_binding_force_variant(sod2_binding_t* b, int32_t v) {
-  if (!b || v < -1 || v > 3) { g_err = "variant must be -1, 0, 1, 2 or 3"; return SOD2_ERR_INVALID_ARG; }
+  if (!b || v < -1 || v > 5) { g_err = "variant must be -1 .. 5"; return SOD2_ERR_INVALID_ARG; }
   b->force_variant = v;
   b->launches_valid = false;
   return SOD2_OK;

@@ -15,7 +15,7 @@ struct Ref {
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
-enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3 };
+enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5 };
 
 // C[b0,b1,m,n] = act2( act1( scale * sum_k A[b0,b1,m,k] * B[b0,b1,k,n] + bias[n] ) + R[b0,b1,m,n] )
 struct GemmArgs {

@@ -212,10 +212,12 @@ struct Builder {
     if (dtype != SOD2_BF16) return V_SIMPLE;
     if (force_variant >= 0) return force_variant;
     if (!p.opts.mvc) return V_REGULAR;
-    if (M <= 48) return V_SKINNY;                                    // skinny: few rows
-    int64_t fat_tiles = ((M + 255) / 256) * ((N + 127) / 128) * batch;
-    if (fat_tiles >= 512) return V_FAT;                              // fat: enough 256x128 tiles for two waves of CUs
-    return V_REGULAR;
+    // the largest tile that still yields enough workgroups for 256 CUs (two workgroups fit a CU)
+    auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch; };
+    if (M <= 32) return V_SKINNY;
+    if (tiles(256, 128) >= 512) return V_FAT;
+    if (tiles(128, 128) >= 256) return V_REGULAR;
+    return V_SMALL;
   }
 
   Launch gemm(const Group& gr) {
@@ -561,6 +563,9 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       if (g.b_sk == 1 && g.K % 8 == 0 && g.b_sn % 8 == 0 && bal) g.b_mode = 0;
       else if (g.b_sn == 1 && g.N % 8 == 0 && g.b_sk % 8 == 0 && bal) g.b_mode = 1;
       else g.b_mode = 2;
+      g.c_vec = g.c_sn == 1 && g.c_sm % 8 == 0 && g.c_sb0 % 8 == 0 && g.c_sb1 % 8 == 0 && al16(g.C) &&
+                (!g.bias || al16(g.bias)) &&
+                (!g.res || (g.r_sn == 1 && g.r_sm % 8 == 0 && g.r_sb0 % 8 == 0 && g.r_sb1 % 8 == 0 && al16(g.res)));
       return launch_gemm(L, g, s);
     }
     case K_CONV: {
