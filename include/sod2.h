@@ -149,7 +149,11 @@ sod2_status sod2_plan_dump(const sod2_plan_t*, char* buf_host, size_t cap, size_
 /* symbol_values_host: one value per declared symbol, in declaration order.  For graphs with
  * Switch operators the arena plan depends on the decisions; sod2_bind plans as if every branch
  * ran and sod2_run re-plans after each decision (Section 4.3: a sub-graph after an
- * execution-determined operator is planned once that operator has executed). */
+ * execution-determined operator is planned once that operator has executed).  The size reported by
+ * sod2_binding_arena_bytes is then that of the all-branches plan; a particular path usually needs
+ * less but may need more, in which case sod2_run stops at the Switch with SOD2_ERR_ARENA_TOO_SMALL
+ * (nothing after it launched), sod2_run_arena_bytes reports the size needed, and the call can be
+ * repeated with a larger arena. */
 sod2_status sod2_bind(const sod2_plan_t*, const int64_t* symbol_values_host, int32_t n_symbols, sod2_binding_t** out);
 /* pure planning with a given decision vector (1 = the skip output of the Switch is taken); no run */
 sod2_status sod2_bind_decided(const sod2_plan_t*, const int64_t* symbol_values_host, int32_t n_symbols,

@@ -700,8 +700,12 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
           }
           decisions.push_back(dec);
           replanned = bind_plan(p, h->symbols, decisions, true);
-          if ((size_t)replanned.arena_bytes > arena_bytes)
-            throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena too small for the executed path");
+          if ((size_t)replanned.arena_bytes > arena_bytes) {
+            h->executed = replanned;           // sod2_run_arena_bytes now reports what this path needs
+            h->has_executed = true;
+            throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, the path taken needs " +
+                                                      std::to_string(replanned.arena_bytes) + "; nothing after the Switch was launched");
+          }
           relaunch = build_launches(p, replanned, h->force_variant);
           cur = &replanned;
           launches = &relaunch;

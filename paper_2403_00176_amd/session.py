@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 from . import (sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run, sod2_binding_arena_bytes,
-               sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes)
+               sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes, Sod2Error)
 
 _NP = {"f32": np.float32, "i64": np.int64, "i32": np.int32}
 _TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "i64": torch.int64, "i32": torch.int32}
@@ -69,9 +69,19 @@ class Session:
 
     def run(self, binding, inputs: List[torch.Tensor], outputs: List[torch.Tensor]):
         nbytes, _ = sod2_binding_arena_bytes(binding)
-        arena = self.ensure_arena(nbytes)
-        sod2_run(binding, arena.data_ptr(), arena.numel(), [w.data_ptr() for w in self.weights],
-                 [t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs], self.stream.cuda_stream)
+        for attempt in range(4):
+            arena = self.ensure_arena(nbytes)
+            try:
+                sod2_run(binding, arena.data_ptr(), arena.numel(), [w.data_ptr() for w in self.weights],
+                         [t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs], self.stream.cuda_stream)
+                return
+            except Sod2Error as e:
+                # with Switches the path taken can need more than the bind-time plan: grow and repeat
+                if e.code != -5 or attempt == 3:
+                    raise
+                self.stream.synchronize()
+                nbytes = max(sod2_run_arena_bytes(binding)[0], arena.numel() + 1)
+                self.arena = None
 
     def output_shapes(self, binding) -> List[List[int]]:
         """Concrete shapes of the graph outputs, read from the binding's text dump."""

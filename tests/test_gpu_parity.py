@@ -167,3 +167,76 @@ def test_arena_too_small_is_refused(S):
         S.sod2_run(b, arena.data_ptr(), arena.numel(), [x.data_ptr() for x in ses.weights],
                    [x.data_ptr() for x in ins], [x.data_ptr() for x in outs], 0)
     assert e.value.code == -5
+
+
+def _run_gated(S, w, ci, sym, forced=None):
+    from paper_2403_00176_amd.session import Session, to_host
+    import torch
+    ses = _run_gated.cache.get(id(w))
+    if ses is None:
+        ses = Session(w.graph)
+        ses.W = w.make_weights()
+        ses.upload_weights(ses.W)
+        _run_gated.cache[id(w)] = ses
+    b = ses.bind(sym)
+    if forced is not None:
+        S.sod2_binding_force_decisions(b, forced)
+    ins = w.make_inputs(ci, sym)
+    outs = ses.alloc_outputs(ses.output_shapes(b))
+    ses.run(b, ses.upload_inputs(ins), outs)
+    torch.cuda.synchronize()
+    return ses, b, ins, to_host(outs[0])
+
+
+_run_gated.cache = {}
+
+
+def test_config4_control_flow(S):
+    """Layer skipping: decisions, executed plan (steps, offsets) and values against the oracle.
+    A decision is compared only where the oracle's gate value is clear of the threshold; the
+    values are compared on a replay with the oracle's decisions forced."""
+    w = configs.config4(4, layers=4)
+    ro = R.RDP(w.graph).analyse()
+    po = P.build_plan(w.graph, ro)
+    seen = set()
+    for ci, sym in list(enumerate(w.calls[:3])) + [(7, {"L": 131})]:
+        print(f"case cfg4 call {ci} sym {sym}", flush=True)
+        ses, b, ins, got = _run_gated(S, w, ci, sym)
+        ref = execute.run(w.graph, po.order, ses.W, ins)
+        dec = S.sod2_run_decisions(b)
+        assert len(dec) == len(ref.decisions)
+        for d, dr, p in zip(dec, ref.decisions, ref.logits):
+            if abs(p - 0.5) > 5e-3:
+                assert bool(d) == dr
+        seen.update(ref.decisions)
+        if [bool(d) for d in dec] != ref.decisions:
+            ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
+        assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
+        assert S.sod2_run_arena_bytes(b)[0] == A.bind(po, sym, ref.decisions).arena_bytes
+        t = w.graph.outputs()[0]
+        assert rel_err(got, ref.values[t]) <= TOL["bf16"]
+    # forcing the opposite decisions changes the executed plan accordingly
+    sym = {"L": 128}
+    for forced in ([1, 1, 1, 1], [0, 0, 0, 0], [1, 0, 0, 1]):
+        ses, b, ins, got = _run_gated(S, w, 9, sym, forced=forced)
+        assert S.sod2_run_decisions(b) == forced
+        ref = execute.run(w.graph, po.order, ses.W, ins, forced=[bool(f) for f in forced])
+        assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, [bool(f) for f in forced]))
+        assert rel_err(got, ref.values[w.graph.outputs()[0]]) <= TOL["bf16"]
+
+
+def test_config4_gate_closed_forms(S):
+    """Gate bias +10: every layer skipped, the output is the final LayerNorm of the input and the
+    arena holds the gate tensors only.  Gate bias -10: every layer runs."""
+    sym = {"L": 150}
+    for bias, expect in ((10.0, 1), (-10.0, 0)):
+        w = configs.config4(1, layers=3, gate_bias=bias)
+        ro = R.RDP(w.graph).analyse()
+        po = P.build_plan(w.graph, ro)
+        ses, b, ins, got = _run_gated(S, w, 0, sym)
+        assert S.sod2_run_decisions(b) == [expect] * 3
+        ref = execute.run(w.graph, po.order, ses.W, ins)
+        assert rel_err(got, ref.values[w.graph.outputs()[0]]) <= TOL["bf16"]
+        arena_exec = S.sod2_run_arena_bytes(b)[0]
+        arena_all = S.sod2_binding_arena_bytes(b)[0]
+        assert (arena_exec < arena_all // 20) if expect else (arena_exec == arena_all)
