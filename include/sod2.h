@@ -188,7 +188,8 @@ sod2_status sod2_run_arena_bytes(const sod2_binding_t*, size_t* arena_bytes, siz
 /* per-launch records of the last run (filled when profiling is on: two events per launch) */
 typedef struct {
   int32_t group;       /* group id */
-  int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other */
+  int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other,
+                          8 gather, 9 cache append, 10 argmax */
   int32_t variant;
   int32_t reserved;
   float ms;            /* event-to-event duration */

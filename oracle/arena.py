@@ -13,6 +13,11 @@ in execution order:
 Sizes are element count x element size rounded up to 256 bytes.  Control flow
 follows dead-token propagation: the Switch output that is not taken is dead,
 an operator with a dead input does not run, Combine forwards its live input.
+
+Session tensors (a KV cache: tensors that persist across calls) take a region of
+their own at the bottom of the arena: one slot per session input, in tensor-id
+order, sized for its declared capacity at the bound symbols; every other offset
+starts above that region.  CacheAppend writes into the slot of its first input.
 """
 from __future__ import annotations
 
@@ -21,6 +26,7 @@ from itertools import permutations
 from typing import Dict, List, Sequence, Tuple
 
 from . import rdp as R
+from .expr import Expr
 from .plan import Plan, DT_BYTES, align_up, arena_candidate
 
 
@@ -29,6 +35,10 @@ class SymbolOutOfRange(Exception):
 
 
 class UnresolvedShape(Exception):
+    pass
+
+
+class CapacityExceeded(Exception):
     pass
 
 
@@ -54,6 +64,9 @@ class Binding:
     peak_live: int = 0
     dead_ops: set = field(default_factory=set)
     dyn_base: Dict[int, int] = field(default_factory=dict)
+    session: Dict[int, Tuple[int, int]] = field(default_factory=dict)   # session input -> (offset, bytes)
+    session_root: Dict[int, int] = field(default_factory=dict)          # session tensor -> its session input
+    session_bytes: int = 0
 
 
 def concrete_dims(plan: Plan, t: int, env) -> List[int]:
@@ -85,6 +98,17 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Bin
     env = {name: int(sym[name]) for name, _, _ in g.symbols}
     b = Binding(plan, env)
     prod = plan.rdp.producer
+    cap_elems = {}
+    for t, d in enumerate(g.tensors):
+        if d.role == "input" and d.session:
+            n = 1
+            for c in d.capacity:
+                n *= Expr.parse(c).eval(env)
+            cap_elems[t] = n
+            nbytes = align_up(n * DT_BYTES[d.dtype])
+            b.session[t] = (b.session_bytes, nbytes)
+            b.session_root[t] = t
+            b.session_bytes += nbytes
     group_dead: Dict[int, bool] = {}
     memo: Dict[int, Tuple[bool, int]] = {}
     dec = list(decisions)
@@ -135,6 +159,16 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Bin
                     reads_at[info(t)[1]] = step
                 t = gr.out
                 b.dims[t] = concrete_dims(plan, t, env)
+                if gr.kind == "CACHEAPPEND":
+                    src = g.ops[gr.ops[0]].inputs[0]
+                    if src not in b.session_root:
+                        raise ValueError("CacheAppend must extend a session tensor")
+                    b.session_root[t] = b.session_root[src]
+                    n = 1
+                    for d in b.dims[t]:
+                        n *= d
+                    if n > cap_elems[b.session_root[t]]:
+                        raise CapacityExceeded(g.tensors[t].name)
                 if arena_candidate(plan, t):
                     n = DT_BYTES[g.tensors[t].dtype]
                     for d in b.dims[t]:
@@ -172,7 +206,7 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Bin
     for at in b.tensors.values():
         for k in range(at.start, at.end + 1):
             live_bytes[k] += at.bytes
-    b.peak_live = max(live_bytes, default=0)
+    b.peak_live = max(live_bytes, default=0) + b.session_bytes
 
     placed: List[ArenaTensor] = []
     if plan.opts.dmp:
@@ -192,7 +226,9 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Bin
         for a in sorted(b.tensors.values(), key=lambda a: (a.start, a.tid)):
             a.offset = best_fit(a, placed)
             placed.append(a)
-    b.arena_bytes = max((a.offset + a.bytes for a in placed), default=0)
+    for a in placed:
+        a.offset += b.session_bytes
+    b.arena_bytes = max((a.offset + a.bytes for a in placed), default=b.session_bytes)
     return b
 
 
@@ -229,8 +265,12 @@ def optimal_arena_bytes(tensors: Sequence[ArenaTensor]) -> int:
 
 def check_no_overlap(b: Binding):
     ts = list(b.tensors.values())
+    slots = sorted(b.session.values())
+    for (o1, n1), (o2, n2) in zip(slots, slots[1:]):
+        assert o1 + n1 <= o2
+    assert not slots or slots[-1][0] + slots[-1][1] == b.session_bytes
     for i, x in enumerate(ts):
-        assert x.offset >= 0 and x.offset % 256 == 0
+        assert x.offset >= b.session_bytes and x.offset % 256 == 0
         for y in ts[i + 1:]:
             if intersects(x, y):
                 assert x.offset + x.bytes <= y.offset or y.offset + y.bytes <= x.offset, (x, y)
@@ -239,6 +279,8 @@ def check_no_overlap(b: Binding):
 def dump(b: Binding) -> str:
     plan = b.plan
     lines = ["sym " + " ".join(f"{k}={v}" for k, v in b.env.items())]
+    for t in sorted(b.session):
+        lines.append(f"session t{t} off={b.session[t][0]} bytes={b.session[t][1]}")
     for k, i in enumerate(b.steps):
         it = plan.items[i]
         lines.append(f"step {k} {'g' if it.is_group else 'c'}{it.ref}")
@@ -247,6 +289,8 @@ def dump(b: Binding) -> str:
         if t in b.tensors:
             a = b.tensors[t]
             lines.append(f"t{t} dims=[{dims}] off={a.offset} bytes={a.bytes} life={a.start}..{a.end}")
+        elif t in b.session_root:
+            lines.append(f"t{t} dims=[{dims}] session=t{b.session_root[t]}")
         else:
             lines.append(f"t{t} dims=[{dims}] external")
     lines.append(f"arena_bytes={b.arena_bytes}")

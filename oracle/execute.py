@@ -21,15 +21,26 @@ class Result:
         self.values: Dict[int, object] = {}
         self.decisions: List[bool] = []       # one per executed Switch, True = skip branch taken
         self.logits: List[float] = []         # predicate value seen by each executed Switch
+        self.state: Dict[str, np.ndarray] = {}   # session tensors after the run, by the session input's name
 
 
 def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dict[int, np.ndarray],
-        forced: Optional[Sequence[bool]] = None, round_weights=True) -> Result:
+        forced: Optional[Sequence[bool]] = None, round_weights=True,
+        state: Optional[Dict[str, np.ndarray]] = None) -> Result:
+    """``state``: contents of the session tensors (a KV cache) when the call starts, by name; a session
+    input that is missing starts with zero rows.  ``Result.state`` is what the next call starts from."""
     g = graph
     res = Result()
     val = res.values
+    root = {}                                 # session tensor id -> name of the session input it continues
+    res.state = dict(state or {})
     for i, t in enumerate(g.tensors):
-        if t.data is not None:
+        if t.role == "input" and t.session:
+            root[i] = t.name
+            if t.name not in res.state:
+                res.state[t.name] = np.zeros([0] + [int(d) for d in t.dims[1:]])
+            val[i] = O.round_to(np.asarray(res.state[t.name], np.float64), t.dtype)
+        elif t.data is not None:
             val[i] = np.asarray(t.data, dtype=np.int64 if t.dtype in ("i64", "i32") else np.float64)
         elif i in weights:
             val[i] = O.round_to(np.asarray(weights[i], np.float64), t.dtype) if round_weights else weights[i]
@@ -105,4 +116,7 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
         else:
             raise ValueError(k)
         val[op.outputs[0]] = O.round_to(np.asarray(y), g.tensors[op.outputs[0]].dtype)
+        if k == "CacheAppend":
+            root[op.outputs[0]] = root[op.inputs[0]]
+            res.state[root[op.outputs[0]]] = val[op.outputs[0]]
     return res

@@ -7,6 +7,10 @@
 // lowest offset that overlaps no already placed tensor with an intersecting lifetime.  Sizes are
 // rounded up to 256 bytes.  Control flow uses dead tokens: the Switch output not taken is dead, an
 // item with a dead input does not run, Combine forwards its live input.
+//
+// Session tensors (a KV cache) persist across calls: one slot per session input at the bottom of
+// the arena, in tensor-id order, sized for the declared capacity at the bound symbols; every other
+// offset starts above that region.  CacheAppend writes into the slot of its first input.
 #include <algorithm>
 #include <functional>
 
@@ -60,6 +64,16 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
       throw Error(SOD2_ERR_SYMBOL_OUT_OF_RANGE, "symbol " + s.name + " = " + std::to_string(symbols[i]) +
                                                     " outside [" + std::to_string(s.lo) + ", " + std::to_string(s.hi) + "]");
     b.env[s.name] = symbols[i];
+  }
+  std::map<int, int64_t> cap_elems;
+  for (int t : G.session_ids) {
+    int64_t n = 1;
+    for (const auto& c : G.tensors[t].capacity) n *= Expr::parse(c).eval(b.env);
+    cap_elems[t] = n;
+    int64_t nbytes = (n * dtype_bytes(G.tensors[t].dtype) + 255) / 256 * 256;
+    b.session[t] = {b.session_bytes, nbytes};
+    b.session_root[t] = t;
+    b.session_bytes += nbytes;
   }
   std::map<int, bool> group_dead;
   std::map<int, std::pair<bool, int>> memo;       // tensor -> (dead, storage tensor)
@@ -118,6 +132,15 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         int64_t n = dtype_bytes(G.tensors[t].dtype);
         for (const auto& d : sh.d) { dims.push_back(d.e.eval(b.env)); n *= dims.back(); }
         b.dims[t] = dims;
+        if (gr.kind == G_CACHEAPPEND) {
+          auto root = b.session_root.find(G.ops[gr.ops[0]].in[0]);
+          if (root == b.session_root.end()) throw Error(SOD2_ERR_UNSUPPORTED, "CacheAppend must extend a session tensor");
+          b.session_root[t] = root->second;
+          int64_t elems = 1;
+          for (int64_t d : dims) elems *= d;
+          if (elems > cap_elems.at(root->second))
+            throw Error(SOD2_ERR_INVALID_ARG, "session tensor " + G.tensors[t].name + " would outgrow its capacity");
+        }
         if (p.arena_candidate(t)) b.tensors[t] = ArenaTensor{t, (n + 255) / 256 * 256, step, step, -1};
       } else {
         const Op& op = G.ops[it.ref];
@@ -157,6 +180,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
   for (const auto& kv : b.tensors)
     for (int k = kv.second.start; k <= kv.second.end; ++k) live_bytes[k] += kv.second.bytes;
   for (int64_t v : live_bytes) b.peak_live = std::max(b.peak_live, v);
+  b.peak_live += b.session_bytes;
 
   std::vector<const ArenaTensor*> placed;
   if (p.opts.dmp) {
@@ -198,7 +222,11 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
     });
     for (ArenaTensor* a : all) { a->offset = best_fit(*a, placed); placed.push_back(a); }
   }
-  for (const ArenaTensor* a : placed) b.arena_bytes = std::max(b.arena_bytes, a->offset + a->bytes);
+  b.arena_bytes = b.session_bytes;
+  for (auto& kv : b.tensors) {
+    kv.second.offset += b.session_bytes;
+    b.arena_bytes = std::max(b.arena_bytes, kv.second.offset + kv.second.bytes);
+  }
   return b;
 }
 
@@ -206,6 +234,9 @@ std::string BindResult::dump(const Plan& p) const {
   std::string out = "sym";
   for (const auto& s : p.g->symbols) out += " " + s.name + "=" + std::to_string(env.at(s.name));
   out += "\n";
+  for (const auto& kv : session)
+    out += "session t" + std::to_string(kv.first) + " off=" + std::to_string(kv.second.first) + " bytes=" +
+           std::to_string(kv.second.second) + "\n";
   for (size_t k = 0; k < steps.size(); ++k) {
     const Item& it = p.items[steps[k]];
     out += "step " + std::to_string(k) + " " + (it.is_group ? "g" : "c") + std::to_string(it.ref) + "\n";
@@ -218,6 +249,8 @@ std::string BindResult::dump(const Plan& p) const {
     if (at != tensors.end())
       out += " off=" + std::to_string(at->second.offset) + " bytes=" + std::to_string(at->second.bytes) + " life=" +
              std::to_string(at->second.start) + ".." + std::to_string(at->second.end) + "\n";
+    else if (session_root.count(kv.first))
+      out += " session=t" + std::to_string(session_root.at(kv.first)) + "\n";
     else
       out += " external\n";
   }

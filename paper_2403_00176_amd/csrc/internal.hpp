@@ -103,7 +103,8 @@ struct Graph {
   std::vector<Op> ops;
   std::vector<int> producer;                       // per tensor, -1 for graph inputs / constants
   std::vector<std::vector<int>> consumers;         // per tensor
-  std::vector<int> weight_ids, input_ids, output_ids;
+  std::vector<int> weight_ids, input_ids, output_ids;   // input_ids: inputs passed by pointer
+  std::vector<int> session_ids;                        // session inputs (stored in the arena)
   void finish();                                   // fills the derived fields, validates ids
   std::vector<int> sorted_nodes() const;           // reverse post-order of a depth-first walk
 };
@@ -175,6 +176,9 @@ struct BindResult {
   std::map<int, std::vector<int64_t>> dims;        // outputs of executed groups
   std::map<int, int> dyn_base;                     // executed tensor -> tensor providing storage
   std::set<int> dead_ops;
+  std::map<int, std::pair<int64_t, int64_t>> session;   // session input -> (offset, bytes) at the arena bottom
+  std::map<int, int> session_root;                 // session tensor -> the session input whose slot it occupies
+  int64_t session_bytes = 0;
   int64_t arena_bytes = 0, peak_live = 0;
   int undecided = 0;                               // Switches met without a given decision
   std::string dump(const Plan& p) const;

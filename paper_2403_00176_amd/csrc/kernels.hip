@@ -782,6 +782,90 @@ __global__ void eltwise_kernel(EltArgs a) {
   ((TO*)a.out)[idx] = from_f<TO>(v);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Embedding gather (+ add), KV-cache append, arg-max
+// ---------------------------------------------------------------------------------------------
+template <class T, class I>
+__global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
+  const long long r = blockIdx.x;
+  long long id = (long long)((const I*)a.idx)[r];
+  id = id < 0 ? 0 : (id >= a.table_rows ? a.table_rows - 1 : id);
+  const T* src = (const T*)a.table + id * a.cols;
+  const T* add = a.add ? (const T*)a.add + r * a.add_stride : nullptr;
+  T* dst = (T*)a.y + r * a.cols;
+  for (int c = threadIdx.x; c < a.cols; c += 256) {
+    float v = to_f<T>(src[c]);
+    if (add) v += to_f<T>(add[c]);
+    dst[c] = from_f<T>(v);
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
+  const long long r = blockIdx.x;
+  const T* src = (const T*)a.x + r * a.x_stride;
+  T* dst = (T*)a.cache + (a.past + r) * a.cols;
+  for (int c = threadIdx.x; c < a.cols; c += 256) dst[c] = src[c];
+}
+
+template <class T>
+__global__ __launch_bounds__(256) void argmax_kernel(ArgmaxArgs a) {
+  __shared__ float bv[4];
+  __shared__ int bi[4];
+  const long long r = blockIdx.x;
+  const T* x = (const T*)a.x + r * a.x_stride;
+  float best = -INFINITY;
+  int at = 0x7fffffff;
+  for (int c = threadIdx.x; c < a.cols; c += 256) {      // ascending c per thread: '>' keeps the lowest index
+    float v = to_f<T>(x[c]);
+    if (v > best || at == 0x7fffffff) { best = v; at = c; }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(best, o, 64);
+    int oi = __shfl_xor(at, o, 64);
+    if (ov > best || (ov == best && oi < at)) { best = ov; at = oi; }
+  }
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (lane == 0) { bv[w] = best; bi[w] = at; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int k = 1; k < 4; ++k)
+      if (bv[k] > best || (bv[k] == best && bi[k] < at)) { best = bv[k]; at = bi[k]; }
+    if (a.out_i32) ((int*)a.y)[r] = at;
+    else ((long long*)a.y)[r] = at;
+  }
+}
+
+hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s) {
+  if (a.rows <= 0) return hipSuccess;
+  dim3 grid((unsigned)a.rows);
+  if (L.in_dtype == SOD2_BF16_TAG) {
+    if (a.idx_i32) hipLaunchKernelGGL((gather_kernel<bf16_t, int>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((gather_kernel<bf16_t, long long>), grid, dim3(256), 0, s, a);
+  } else {
+    if (a.idx_i32) hipLaunchKernelGGL((gather_kernel<float, int>), grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL((gather_kernel<float, long long>), grid, dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_append(const Launch& L, const AppendArgs& a, hipStream_t s) {
+  if (a.rows <= 0) return hipSuccess;
+  dim3 grid((unsigned)a.rows);
+  if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(append_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(append_kernel<float>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+hipError_t launch_argmax(const Launch& L, const ArgmaxArgs& a, hipStream_t s) {
+  if (a.rows <= 0) return hipSuccess;
+  dim3 grid((unsigned)a.rows);
+  if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(argmax_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(argmax_kernel<float>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_eltwise(const Launch& L, const EltArgs& a, hipStream_t s) {
   dim3 grid((unsigned)((a.total + 255) / 256));
   if (L.out_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(eltwise_kernel<bf16_t>, grid, dim3(256), 0, s, a);

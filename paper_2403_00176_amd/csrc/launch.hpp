@@ -13,7 +13,8 @@ struct Ref {
   int64_t byte_off = 0;    // arena offset, plus any view offset
 };
 
-enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER };
+enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
+                  K_ARGMAX };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5 };
 
@@ -71,6 +72,27 @@ struct EltArgs {
   float imm[8];
 };
 
+// y[r, :] = table[idx[r], :] (+ add[r, :]); an index outside the table is clamped into it
+struct GatherArgs {
+  const void* table; const void* idx; const void* add; void* y;
+  long long rows, table_rows, add_stride;
+  int cols, idx_i32;
+};
+
+// cache[past + r, :] = x[r, :] for r < rows (the in-place CacheAppend of a session tensor)
+struct AppendArgs {
+  const void* x; void* cache;
+  long long rows, past, x_stride;
+  int cols;
+};
+
+// y[r] = index of the largest x[r, :], the lowest index among equals
+struct ArgmaxArgs {
+  const void* x; void* y;
+  long long rows, x_stride;
+  int cols, out_i32;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -84,6 +106,9 @@ struct Launch {
     ReduceArgs red;
     PoolArgs pool;
     EltArgs elt;
+    GatherArgs gather;
+    AppendArgs append;
+    ArgmaxArgs argmax;
   } u;
   bool is_layernorm = false;
   double flops = 0, bytes = 0;

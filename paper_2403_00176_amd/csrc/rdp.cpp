@@ -45,9 +45,21 @@ void Graph::finish() {
   }
   for (int t = 0; t < nt; ++t) {
     if (tensors[t].role == SOD2_WEIGHT) weight_ids.push_back(t);
-    if (tensors[t].role == SOD2_INPUT) input_ids.push_back(t);
+    if (tensors[t].role == SOD2_INPUT && !tensors[t].session) input_ids.push_back(t);
     if (tensors[t].is_output) output_ids.push_back(t);
+    if (tensors[t].role == SOD2_INPUT && tensors[t].session) {
+      // a session input lives in the arena; CacheAppend extends it in place, so nothing else may read it
+      if (!tensors[t].declared || tensors[t].capacity.size() != tensors[t].dims.size())
+        throw Error(SOD2_ERR_INVALID_ARG, "session input needs declared dims and capacity dims: " + tensors[t].name);
+      for (int c : consumers[t])
+        if (ops[c].kind != SOD2_OP_CACHEAPPEND || ops[c].in[0] != t || consumers[t].size() != 1)
+          throw Error(SOD2_ERR_UNSUPPORTED, "a session input may only be extended by one CacheAppend: " + tensors[t].name);
+      session_ids.push_back(t);
+    }
   }
+  for (const Op& op : ops)
+    if (op.kind == SOD2_OP_CACHEAPPEND && !tensors[op.in[0]].session)
+      throw Error(SOD2_ERR_UNSUPPORTED, "CacheAppend must extend a session tensor");
 }
 
 std::vector<int> Graph::sorted_nodes() const {

@@ -15,6 +15,9 @@ hipError_t launch_row(const Launch& L, const RowArgs& a, hipStream_t s);
 hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s);
 hipError_t launch_pool(const Launch& L, const PoolArgs& p, hipStream_t s);
 hipError_t launch_eltwise(const Launch& L, const EltArgs& a, hipStream_t s);
+hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s);
+hipError_t launch_append(const Launch& L, const AppendArgs& a, hipStream_t s);
+hipError_t launch_argmax(const Launch& L, const ArgmaxArgs& a, hipStream_t s);
 
 void destroy_events(void* events, int n) {
   hipEvent_t* e = (hipEvent_t*)events;
@@ -115,7 +118,12 @@ struct Builder {
     if (it != memo.end()) return it->second;
     View v;
     int pr = G.producer[t];
-    if (pr < 0 || (!p.view[pr] && G.ops[pr].kind != SOD2_OP_SWITCH && G.ops[pr].kind != SOD2_OP_COMBINE)) {
+    auto sr = b.session_root.find(t);
+    if (sr != b.session_root.end()) {               // a session tensor: dense rows in its root's arena slot
+      v.base = sr->second;
+      v.dims = eval_dims(t);
+      v.strides = contiguous_strides(v.dims);
+    } else if (pr < 0 || (!p.view[pr] && G.ops[pr].kind != SOD2_OP_SWITCH && G.ops[pr].kind != SOD2_OP_COMBINE)) {
       if (pr >= 0 && p.groups.at(p.group_of_op[pr]).out != t)
         throw Error(SOD2_ERR_UNSUPPORTED, "tensor inside a fused group is read from outside: " + G.tensors[t].name);
       v.base = t;
@@ -175,6 +183,8 @@ struct Builder {
     int64_t eb = dtype_bytes(dtype);
     auto at = b.tensors.find(t);
     if (at != b.tensors.end()) { r.space = SP_ARENA; r.byte_off = at->second.offset + v.off * eb; return r; }
+    auto ss = b.session.find(t);
+    if (ss != b.session.end()) { r.space = SP_ARENA; r.byte_off = ss->second.first + v.off * eb; return r; }
     r.byte_off = v.off * eb;
     if (widx.count(t)) { r.space = SP_WEIGHT; r.index = widx.at(t); }
     else if (oidx.count(t)) { r.space = SP_OUTPUT; r.index = oidx.at(t); }
@@ -519,8 +529,94 @@ struct Builder {
     return L;
   }
 
+  Launch gather(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_GATHER;
+    const Op& op = G.ops[gr.chain[0]];
+    const View &vt = view_of(op.in[0]), &vi = view_of(op.in[1]);
+    int dt = G.tensors[op.in[0]].dtype, it = G.tensors[op.in[1]].dtype;
+    if (vt.dims.size() != 2 || !vt.contiguous() || vi.dims.size() != 1 || !vi.contiguous() || !is_int(it) ||
+        (!op.ia.empty() && op.ia[0] != 0) || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt)
+      throw Error(SOD2_ERR_UNSUPPORTED, "Gather kernel: rows of a contiguous rank-2 float table by a rank-1 index tensor");
+    GatherArgs a{};
+    a.rows = vi.dims[0];
+    a.cols = (int)vt.dims[1];
+    a.table_rows = vt.dims[0];
+    a.idx_i32 = it == SOD2_I32;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vt, dt);
+    L.r[1] = ref_of(vi, it);
+    L.r[2] = ref_t(gr.out);
+    if (gr.chain.size() > 1) {
+      const Op& add = G.ops[gr.chain[1]];
+      int o = other(add, op.out[0]);
+      const View& va = view_of(o);
+      if (G.tensors[o].dtype != dt || va.dims.size() != 2 || va.dims[0] != a.rows || va.dims[1] != a.cols ||
+          va.strides[1] != 1)
+        throw Error(SOD2_ERR_UNSUPPORTED, "Gather kernel: the added operand must be a [rows, cols] tensor of the same type");
+      a.add_stride = va.strides[0];
+      L.r[3] = ref_of(va, dt);
+    }
+    L.u.gather = a;
+    L.flops = gr.chain.size() > 1 ? (double)a.rows * a.cols : 0;
+    L.bytes = dtype_bytes(dt) * (double)a.rows * a.cols * (gr.chain.size() > 1 ? 3 : 2) + dtype_bytes(it) * (double)a.rows;
+    return L;
+  }
+
+  Launch append(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_APPEND;
+    const Op& op = G.ops[gr.chain[0]];
+    const View &vc = view_of(op.in[0]), &vx = view_of(op.in[1]), &vo = view_of(gr.out);
+    int dt = G.tensors[op.in[0]].dtype;
+    if (G.tensors[op.in[1]].dtype != dt || vx.dims.size() != 2 || vc.dims.size() != 2 || vx.dims[1] != vc.dims[1] ||
+        (vx.dims[1] != 1 && vx.strides[1] != 1) || vo.dims[0] != vc.dims[0] + vx.dims[0])
+      throw Error(SOD2_ERR_UNSUPPORTED, "CacheAppend kernel: [past, cols] extended by [rows, cols] with a dense last dim");
+    AppendArgs a{};
+    a.rows = vx.dims[0];
+    a.cols = (int)vx.dims[1];
+    a.past = vc.dims[0];
+    a.x_stride = vx.strides[0];
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_of(vo, dt);
+    L.u.append = a;
+    L.bytes = 2.0 * dtype_bytes(dt) * a.rows * a.cols;
+    return L;
+  }
+
+  Launch argmax(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_ARGMAX;
+    const Op& op = G.ops[gr.chain[0]];
+    const View& vx = view_of(op.in[0]);
+    int dt = G.tensors[op.in[0]].dtype, ot = G.tensors[gr.out].dtype;
+    if ((dt != SOD2_BF16 && dt != SOD2_F32) || !is_int(ot)) throw Error(SOD2_ERR_UNSUPPORTED, "ArgMax kernel: float rows to an integer index");
+    ArgmaxArgs a{};
+    int64_t nrows, xs;
+    rows_of(vx, &nrows, &xs);
+    a.rows = nrows;
+    a.x_stride = xs;
+    a.cols = (int)vx.dims.back();
+    a.out_i32 = ot == SOD2_I32;
+    L.in_dtype = dt;
+    L.out_dtype = ot;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_t(gr.out);
+    L.u.argmax = a;
+    L.flops = (double)a.rows * a.cols;
+    L.bytes = dtype_bytes(dt) * (double)a.rows * a.cols + dtype_bytes(ot) * (double)a.rows;
+    return L;
+  }
+
   Launch make(const Group& gr) {
     switch (gr.kind) {
+      case G_GATHER: return gather(gr);
+      case G_CACHEAPPEND: return append(gr);
+      case G_ARGMAX: return argmax(gr);
       case G_GEMM: return gemm(gr);
       case G_CONV: return conv(gr);
       case G_LAYERNORM: return row(gr, true);
@@ -595,6 +691,21 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       for (int k = 0; k < a.n_in; ++k) a.in[k] = P.at(L.r[k]);
       a.out = P.at(L.r[5]);
       return launch_eltwise(L, a, s);
+    }
+    case K_GATHER: {
+      GatherArgs a = L.u.gather;
+      a.table = P.at(L.r[0]); a.idx = P.at(L.r[1]); a.y = P.at(L.r[2]); a.add = P.at(L.r[3]);
+      return launch_gather(L, a, s);
+    }
+    case K_APPEND: {
+      AppendArgs a = L.u.append;
+      a.x = P.at(L.r[0]); a.cache = P.at(L.r[1]);
+      return launch_append(L, a, s);
+    }
+    case K_ARGMAX: {
+      ArgmaxArgs a = L.u.argmax;
+      a.x = P.at(L.r[0]); a.y = P.at(L.r[1]);
+      return launch_argmax(L, a, s);
     }
     default:
       return hipErrorInvalidValue;

@@ -91,3 +91,61 @@ class Session:
                 tid = int(line[1:line.index(" ")])
                 dims[tid] = [int(v) for v in line[line.index("[") + 1:line.index("]")].split()]
         return [dims[t] for t in self.desc.outputs()]
+
+
+class DecoderSession:
+    """A prefill graph and a decode graph that declare the same weights and the same session tensors
+    (the KV cache): one set of device weights, one arena whose bottom region holds the cache."""
+
+    def __init__(self, prefill_desc, decode_desc, t_max: int, device="cuda:0", **plan_opts):
+        self.pre = Session(prefill_desc, device, **plan_opts)
+        self.dec = Session(decode_desc, device, **plan_opts)
+        self.t_max = int(t_max)
+        self.device = self.pre.device
+        self.stream = self.pre.stream
+        self.arena: Optional[torch.Tensor] = None
+        self.logits_dtype = _TORCH[prefill_desc.tensors[prefill_desc.tensor_id("logits")].dtype]
+
+    def upload_weights(self, by_name: Dict[str, np.ndarray]):
+        d = self.pre.desc
+        self.pre.weights = [to_device(by_name[d.tensors[t].name], d.tensors[t].dtype, self.device) for t in d.weights()]
+        names = [self.dec.desc.tensors[t].name for t in self.dec.desc.weights()]
+        assert names == [d.tensors[t].name for t in d.weights()], "the two graphs must declare the same weights"
+        self.dec.weights = self.pre.weights
+
+    def start(self, P: int, vocab: int):
+        """Buffers of one sequence: the arena (sized for the prompt pass and the last decode step), the
+        token ids and positions, one row of logits per produced token."""
+        self.P = int(P)
+        self.b_pre = self.pre.bind({"P": P})
+        need = sod2_binding_arena_bytes(self.b_pre)[0]
+        need = max(need, sod2_binding_arena_bytes(self.dec.bind({"P": P, "t": self.t_max - 1}))[0])
+        if self.arena is None or self.arena.numel() < need:
+            self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
+        self.tokens = torch.zeros(P + self.t_max + 1, dtype=torch.int64, device=self.device)
+        self.positions = torch.arange(P + self.t_max + 1, dtype=torch.int64, device=self.device)
+        self.logits = torch.zeros(self.t_max + 1, vocab, dtype=self.logits_dtype, device=self.device)
+
+    def _run(self, ses, binding, ids_ptr, pos_ptr, logits_ptr, next_ptr):
+        d = ses.desc
+        ins = {d.tensor_id("ids"): ids_ptr, d.tensor_id("pos"): pos_ptr}
+        outs = {d.tensor_id("logits"): logits_ptr, d.tensor_id("next"): next_ptr}
+        sod2_run(binding, self.arena.data_ptr(), self.arena.numel(), [w.data_ptr() for w in ses.weights],
+                 [ins[t] for t in d.inputs()], [outs[t] for t in d.outputs()], self.stream.cuda_stream)
+
+    def prefill(self, prompt: torch.Tensor):
+        """Runs the prompt pass; logits row 0 and token P (the first generated one) are written."""
+        P = self.P
+        self.tokens[:P] = prompt
+        self._run(self.pre, self.b_pre, self.tokens.data_ptr(), self.positions.data_ptr(), self.logits.data_ptr(),
+                  self.tokens.data_ptr() + 8 * P)
+
+    def decode(self, t: int, binding=None):
+        """Step t consumes token P+t (written by the previous step or by the caller) and writes
+        logits row t+1 and token P+t+1.  Nothing is synchronised."""
+        P = self.P
+        b = binding if binding is not None else self.dec.bind({"P": P, "t": t})
+        self._run(self.dec, b, self.tokens.data_ptr() + 8 * (P + t), self.positions.data_ptr() + 8 * (P + t),
+                  self.logits.data_ptr() + (t + 1) * self.logits.stride(0) * self.logits.element_size(),
+                  self.tokens.data_ptr() + 8 * (P + t + 1))
+        return b

@@ -228,4 +228,112 @@ def config3(n_calls=32):
     return resnet50(3, n_calls)
 
 
+# ---------------------------------------------------------------------------
+# config 5: autoregressive decoder with a KV cache in the arena (two graphs, one set of weights)
+# ---------------------------------------------------------------------------
+
+@dataclass
+class DecoderWorkload:
+    name: str
+    config: int
+    prefill: GraphDesc                           # symbols P; ids/pos [P]
+    decode: GraphDesc                            # symbols P, t; ids/pos [1]; caches hold P+t rows
+    dtype: str
+    prompts: List[int]                           # prompt length per sequence
+    t_max: int                                   # generated tokens per sequence
+    vocab: int
+    weight_spec: Dict[str, tuple]                # weight name -> (kind, params, seed index)
+    make_prompt: Callable[[int], np.ndarray] = None
+
+    def make_weights_by_name(self, threads: int = 8) -> Dict[str, np.ndarray]:
+        from concurrent.futures import ThreadPoolExecutor
+        by_name = {t.name: t for t in self.prefill.tensors if t.role == WEIGHT}
+
+        def one(item):
+            name, (kind, a, b_, k) = item
+            return name, rng.normal(1000 * self.config + k, tuple(by_name[name].dims), a, b_)
+        with ThreadPoolExecutor(max_workers=threads) as ex:      # the generator is counter based: order free
+            return dict(ex.map(one, self.weight_spec.items()))
+
+    @staticmethod
+    def weights_for(graph: GraphDesc, by_name: Dict[str, np.ndarray]) -> Dict[int, np.ndarray]:
+        return {i: by_name[t.name] for i, t in enumerate(graph.tensors) if t.role == WEIGHT}
+
+
+def _decoder_graph(mode, layers, hidden, heads, ffn, vocab, max_pos, p_range, t_max, dtype, w: _Weights):
+    """Pre-LN decoder blocks on x[n, hidden] (batch 1): n = P rows for the prompt, 1 row per generated
+    token.  K and V of every layer are appended to session tensors holding ``past`` rows."""
+    d = hidden // heads
+    if mode == "prefill":
+        b = GraphBuilder([("P", p_range[0], p_range[1])])
+        n, past = "P", 0
+    else:
+        b = GraphBuilder([("P", p_range[0], p_range[1]), ("t", 0, t_max - 1)])
+        n, past = 1, "P+t"
+    ids = b.input("ids", "i64", [n])
+    pos = b.input("pos", "i64", [n])
+    tok = b.weight("tok_emb", dtype, [vocab, hidden]); w.add(tok, "normal", 0.0, 0.02)
+    pw = b.weight("pos_emb", dtype, [max_pos, hidden]); w.add(pw, "normal", 0.0, 0.02)
+    caches = [(b.session_input(f"l{l}.kc", dtype, [past, hidden], [f"P+{t_max}", hidden]),
+               b.session_input(f"l{l}.vc", dtype, [past, hidden], [f"P+{t_max}", hidden])) for l in range(layers)]
+    e_pos = b.op("Gather", [pw, pos], axis=0, hint="e_pos")
+    x = b.op("Add", [b.op("Gather", [tok, ids], axis=0, hint="e_tok"), e_pos], hint="embed")
+    split = b.const("c.split", [0, 3, heads, d])
+    flat = b.const("c.flat", [0, hidden])
+    heads3 = b.const("c.heads", [0, heads, d])
+    sel = [b.const(f"c.i{i}", i) for i in range(3)]
+    scale = b.const("c.scale", 1.0 / np.sqrt(d), "f32")
+    for l in range(layers):
+        name = f"l{l}"
+        h1 = _layernorm(b, w, x, hidden, f"{name}.ln1", dtype)
+        qkv = _linear(b, w, h1, hidden, 3 * hidden, f"{name}.qkv", dtype)
+        qkv4 = b.op("Reshape", [qkv, split], hint="qkv4")                            # [n, 3, h, d]
+        q = b.op("Gather", [qkv4, sel[0]], axis=1, hint="q")                         # [n, h, d]
+        k_new = b.op("Reshape", [b.op("Gather", [qkv4, sel[1]], axis=1, hint="k")    , flat], hint="k_new")
+        v_new = b.op("Reshape", [b.op("Gather", [qkv4, sel[2]], axis=1, hint="v"), flat], hint="v_new")
+        kc = b.op("CacheAppend", [caches[l][0], k_new], hint=f"{name}.kc_out")      # [past + n, hidden]
+        vc = b.op("CacheAppend", [caches[l][1], v_new], hint=f"{name}.vc_out")
+        qT = b.op("Transpose", [q], perm=(1, 0, 2), hint="qT")                       # [h, n, d]
+        kT = b.op("Transpose", [b.op("Reshape", [kc, heads3], hint="k3")], perm=(1, 2, 0), hint="kT")   # [h, d, T]
+        s = b.op("MatMul", [qT, kT], transB=0, hint="qk")                            # [h, n, T]
+        s = b.op("Mul", [s, scale], hint="scaled")
+        p = b.op("Softmax", [s], causal=1, hint="probs")
+        vT = b.op("Transpose", [b.op("Reshape", [vc, heads3], hint="v3")], perm=(1, 0, 2), hint="vT")   # [h, T, d]
+        c = b.op("MatMul", [p, vT], transB=0, hint="pv")                             # [h, n, d]
+        c = b.op("Reshape", [b.op("Transpose", [c], perm=(1, 0, 2), hint="ctxT"), flat], hint="ctx")
+        x1 = b.op("Add", [_linear(b, w, c, hidden, hidden, f"{name}.o", dtype), x], hint="res1")
+        h2 = _layernorm(b, w, x1, hidden, f"{name}.ln2", dtype)
+        f = b.op("Gelu", [_linear(b, w, h2, hidden, ffn, f"{name}.ffn1", dtype)], hint="gelu")
+        x = b.op("Add", [_linear(b, w, f, ffn, hidden, f"{name}.ffn2", dtype), x1], hint="res2")
+    last = b.op("Slice", [x, b.const("c.m1", [-1]), b.const("c.end", [INT_MAX]), b.const("c.ax0", [0])], hint="last")
+    hN = _layernorm(b, w, last, hidden, "lnf", dtype)
+    lm = b.weight("lm_head", dtype, [vocab, hidden]); w.add(lm, "normal", 0.0, 0.02)
+    logits = b.mark_output(b.op("MatMul", [hN, lm], transB=1, hint="lm"), "logits")   # [1, vocab]
+    b.mark_output(b.op("ArgMax", [logits], dtype="i64", hint="argmax"), "next")        # [1]
+    return b.build()
+
+
+def decoder(config=5, layers=24, hidden=1024, heads=16, ffn=4096, vocab=32000, p_range=(64, 512), t_max=256,
+            n_prompts=8, dtype="bf16") -> DecoderWorkload:
+    """Config 5.  Architecture details the config leaves open: pre-LN blocks with erf GELU, a final
+    LayerNorm, learned absolute positions, an untied LM head without bias, softmax scale 1/sqrt(d)."""
+    graphs, specs = {}, {}
+    for mode in ("prefill", "decode"):
+        w = _Weights(config)
+        graphs[mode] = _decoder_graph(mode, layers, hidden, heads, ffn, vocab, p_range[1] + t_max, p_range, t_max, dtype, w)
+        specs[mode] = {graphs[mode].tensors[tid].name: spec + (k,) for k, (tid, spec) in enumerate(sorted(w.spec.items()))}
+    assert specs["prefill"] == specs["decode"], "the two graphs must declare the same weights in the same order"
+    prompts = [int(v) for v in rng.randint(7000 + config, (n_prompts,), p_range[0], p_range[1])]
+
+    def make_prompt(i):
+        return rng.randint(100000 * config + i, (prompts[i],), 0, vocab - 1)
+
+    return DecoderWorkload(f"cfg{config}", config, graphs["prefill"], graphs["decode"], dtype, prompts, t_max, vocab,
+                           specs["prefill"], make_prompt)
+
+
+def config5(n_prompts=8, layers=24):
+    return decoder(5, layers=layers, n_prompts=n_prompts)
+
+
 BUILDERS = {1: config1, 2: config2, 3: config3, 4: config4}

@@ -57,7 +57,8 @@ class TensorDesc:
     dims: Optional[List[Dim]] = None      # None: undeclared (to be inferred)
     data: Optional[np.ndarray] = None     # HOSTCONST only: small host array
     is_output: bool = False
-    session: bool = False                 # persists across calls (KV cache)
+    session: bool = False                 # persists across calls (KV cache): stored in the arena's session region
+    capacity: Optional[List[Dim]] = None  # session inputs only: dims the storage is sized for
 
 
 @dataclass
@@ -75,7 +76,11 @@ class GraphDesc:
     ops: List[OpDesc]
 
     def inputs(self) -> List[int]:
-        return [i for i, t in enumerate(self.tensors) if t.role == INPUT]
+        """Inputs the caller passes by pointer (session inputs live in the arena instead)."""
+        return [i for i, t in enumerate(self.tensors) if t.role == INPUT and not t.session]
+
+    def session_inputs(self) -> List[int]:
+        return [i for i, t in enumerate(self.tensors) if t.role == INPUT and t.session]
 
     def weights(self) -> List[int]:
         return [i for i, t in enumerate(self.tensors) if t.role == WEIGHT]
@@ -105,6 +110,11 @@ class GraphBuilder:
     def input(self, name, dtype, dims) -> int:
         return self._add(TensorDesc(name, dtype, INPUT, None if dims is None else list(dims)))
 
+    def session_input(self, name, dtype, dims, capacity) -> int:
+        """A tensor that persists across calls (and across graphs that declare it alike): its storage is
+        a fixed region at the bottom of the arena sized for ``capacity``; ``dims`` is what it holds now."""
+        return self._add(TensorDesc(name, dtype, INPUT, list(dims), session=True, capacity=list(capacity)))
+
     def weight(self, name, dtype, dims) -> int:
         return self._add(TensorDesc(name, dtype, WEIGHT, list(dims)))
 
@@ -129,6 +139,8 @@ class GraphBuilder:
         if dtype is None:
             dtype = self.g.tensors[inputs[0]].dtype
         outs = [self._tmp(dtype, hint or kind.lower()) for _ in range(n_out)]
+        if kind == "CacheAppend":                       # the result lives on in the session storage of input 0
+            self.g.tensors[outs[0]].session = True
         self.g.ops.append(OpDesc(kind, list(inputs), outs, dict(attrs)))
         return outs[0] if n_out == 1 else outs
 
