@@ -22,6 +22,13 @@ R4  Remaining elementwise operators chain while every aligned dim pair of
     every operand is proven equal or 1 (the condition of Fig. 4), up to 8 ops.
 R5  Group id = smallest operator id in it; groups are ordered by the position
     of their last member in the node order (a topological order of groups).
+R6  Attention: a GEMM group that is only MatMul [+ Mul by a host scalar], whose
+    result is read by one Softmax alone, whose result in turn is the first
+    operand of one MatMul alone that leads a GEMM group of MatMul [+ Transpose]:
+    the three groups become one ATTENTION group (scores and probabilities are
+    never materialised, Section 4.2's "fusion removes intermediate results").
+    Only for bf16 tensors with a known head size of 64 (the size the one fused
+    kernel of the library is written for).
 """
 from __future__ import annotations
 
@@ -219,6 +226,43 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             raise ValueError(f"no grouping rule for {op.kind}")
     for c in absorbed_transpose:
         view[c] = False
+
+    # R6: attention --------------------------------------------------------------
+    if opts.fusion:
+        for n in order:
+            op = g.ops[n]
+            if op.kind != "Softmax" or n not in assigned or groups[assigned[n]].kind != "SOFTMAX":
+                continue
+            x, y = op.inputs[0], op.outputs[0]
+            p1 = rdp.producer[x]
+            if p1 < 0 or p1 not in assigned or sole_consumer(x) != n:
+                continue
+            g1 = groups[assigned[p1]]
+            kinds1 = [g.ops[m].kind for m in g1.ops]
+            if g1.kind != "GEMM" or g1.out != x or kinds1 not in (["MatMul"], ["MatMul", "Mul"]):
+                continue
+            c2 = sole_consumer(y)
+            if c2 is None or g.ops[c2].kind != "MatMul" or g.ops[c2].inputs[0] != y or g.ops[c2].inputs[1] == y:
+                continue
+            g2 = groups[assigned[c2]]
+            kinds2 = [g.ops[m].kind for m in g2.ops]
+            if g2.kind != "GEMM" or min(g2.ops) != c2 or kinds2 not in (["MatMul"], ["MatMul", "Transpose"]):
+                continue
+            mm1 = g.ops[g1.ops[0]]
+            tensors = [mm1.inputs[0], mm1.inputs[1], g.ops[c2].inputs[1], x, y, g2.out]
+            if any(g.tensors[t].dtype != "bf16" for t in tensors):
+                continue
+            sq, sv = rdp.S[mm1.inputs[0]], rdp.S[g.ops[c2].inputs[1]]
+            if not (isinstance(sq, list) and isinstance(sv, list) and sq and sv and R.is_expr(sq[-1]) and
+                    R.is_expr(sv[-1]) and sq[-1] == R.C(64) and sv[-1] == R.C(64)):
+                continue
+            members = g1.ops + [n] + g2.ops
+            for gid in (g1.gid, assigned[n], g2.gid):
+                del groups[gid]
+            gid = min(members)
+            groups[gid] = Group(gid, "ATTENTION", sorted(members), g2.out)
+            for m in members:
+                assigned[m] = gid
 
     # statistic: loop-nest versions a fuser without RDP results would emit (Fig. 4)
     versions = 0

@@ -75,7 +75,7 @@ class LaunchRecord(C.Structure):
                 ("ms", C.c_float), ("flops", C.c_double), ("bytes", C.c_double)]
 
 
-KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other", "gather", "append", "argmax"]
+KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other", "gather", "append", "argmax", "attention"]
 
 _lib.sod2_last_error.restype = C.c_char_p
 _lib.sod2_version.restype = C.c_char_p

@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsod2.so")
-SOURCES = ["expr.cpp", "rdp.cpp", "plan.cpp", "bind.cpp", "api.cpp", "kernels.hip", "run.hip"]
+SOURCES = ["expr.cpp", "rdp.cpp", "plan.cpp", "bind.cpp", "api.cpp", "kernels.hip", "gemm.hip", "attention.hip", "run.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 

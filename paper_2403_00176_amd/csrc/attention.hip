@@ -1,0 +1,191 @@
+// Fused attention for gfx950: O = softmax(scale * Q K^T [+ causal mask]) V per (batch, head), head
+// size 64, bf16 operands, fp32 accumulation; scores and probabilities never leave the registers.
+//
+// Both contractions run on v_mfma_f32_32x32x16_bf16 in the *transposed* form, so that a lane owns one
+// query for the whole kernel:
+//   S^T[key, query] = sum_d K[key, d] Q[query, d]      A = K tile (LDS, d contiguous), B = Q (registers)
+//   O^T[d,   query] = sum_key V[key, d] P[query, key]  A = V^T tile (LDS, keys contiguous), B = P (registers)
+// The MFMA result layout puts column (lane & 31) = query in every lane, 16 rows per lane.  Hence the
+// softmax statistics of a query are reductions inside a lane plus one exchange with lane ^ 32, the
+// rescaling of O is a per-lane scalar, and the probabilities a lane holds after the first
+// contraction are exactly the B operand of the second one: the 8 accumulators 8s .. 8s+7 of a
+// 32-key block are the keys {16s + 4h + i, 16s + 8 + 4h + i : i < 4} of lane half h.  V is written
+// to LDS transposed with the key index permuted the same way (bits 2 and 3 swapped), so one 16-byte
+// LDS read yields the matching A operand.
+//
+// One workgroup = NW waves = NW * 32 queries of one (batch, head); K / V tiles of 64 keys are
+// shared through LDS, double buffered, next tile prefetched into registers during the MFMAs.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_common.hpp"
+
+namespace sod2 {
+
+__device__ __forceinline__ int attn_swz(int row, int chunk) { return chunk ^ ((row >> 1) & 7); }   // 128-byte rows
+
+template <int NW>
+__global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
+  constexpr int NT = NW * 64, D = 64, BKV = 64;
+  constexpr int LPT = BKV * 8 / NT;                      // 16-byte chunks of a K (or V) tile per thread
+  __shared__ __attribute__((aligned(16))) bf16_t Ks[2][BKV * D];    // [key][d], chunk-swizzled
+  __shared__ __attribute__((aligned(16))) bf16_t Vt[2][D * BKV];    // [d][permuted key], chunk-swizzled
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, half = lane >> 5;
+  const int b0 = blockIdx.y / a.nb1, b1 = blockIdx.y % a.nb1;
+  const int q_wg = blockIdx.x * (NW * 32);
+  const int query = q_wg + wave * 32 + col;
+  const int off = a.Lk - a.Lq;                           // causal: query i sees keys <= i + off
+
+  const bf16_t* Qp = (const bf16_t*)a.q + b0 * a.q_sb0 + b1 * a.q_sb1;
+  const bf16_t* Kp = (const bf16_t*)a.k + b0 * a.k_sb0 + b1 * a.k_sb1;
+  const bf16_t* Vp = (const bf16_t*)a.v + b0 * a.v_sb0 + b1 * a.v_sb1;
+
+  // Q as the B operand of S^T: lane (query, half) holds d = 16 ks + 8 half .. + 7
+  V16 qf[4];
+  {
+    const bf16_t* qr = Qp + (long long)min(query, a.Lq - 1) * a.q_sm;
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) qf[ks].u = *(const uint4*)(qr + ks * 16 + half * 8);
+  }
+
+  int n_tiles = (a.Lk + BKV - 1) / BKV;
+  if (a.causal) {
+    const int last_q = min(q_wg + NW * 32, a.Lq) - 1;    // keys beyond last_q + off are masked for everyone here
+    n_tiles = min(n_tiles, (last_q + off) / BKV + 1);
+  }
+
+  // tile loads: chunk p = tid + i * NT  ->  key p / 8, d chunk p % 8
+  uint4 kr[LPT], vr[LPT];
+  auto gload = [&](int t) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int p = tid + i * NT;
+      const int key = min(t * BKV + p / 8, a.Lk - 1);
+      kr[i] = *(const uint4*)(Kp + (long long)key * a.k_sn + (p % 8) * 8);
+      vr[i] = *(const uint4*)(Vp + (long long)key * a.v_sn + (p % 8) * 8);
+    }
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LPT; ++i) {
+      const int p = tid + i * NT;
+      const int key = p / 8, dc = p % 8;
+      *(uint4*)&Ks[buf][key * D + attn_swz(key, dc) * 8] = kr[i];
+      const int kp = (key & ~0xC) | ((key & 4) << 1) | ((key & 8) >> 1);       // swap bits 2 and 3
+      V16 v; v.u = vr[i];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int d = dc * 8 + e;
+        Vt[buf][d * BKV + attn_swz(d, kp >> 3) * 8 + (kp & 7)] = v.h[e];
+      }
+    }
+  };
+
+  f32x16_t oacc[2];
+#pragma unroll
+  for (int db = 0; db < 2; ++db)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) oacc[db][r] = 0.f;
+  float m_run = -INFINITY, l_run = 0.f;
+  const float sc = a.scale * 1.4426950408889634f;        // scores in units of log2 e
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  for (int t = 0; t < n_tiles; ++t) {
+    const int buf = t & 1;
+    if (t + 1 < n_tiles) gload(t + 1);
+
+    // ---- S^T for the 64 keys of the tile: two 32-key blocks ----
+    f32x16_t s[2];
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s[kb][r] = 0.f;
+      const int krow = kb * 32 + col;
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        V16 kf;
+        kf.u = *(const uint4*)&Ks[buf][krow * D + attn_swz(krow, ks * 2 + half) * 8];
+        s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qf[ks].b, s[kb], 0, 0, 0);
+      }
+    }
+    // ---- mask, running max and sum for this lane's query ----
+    const int key_hi = a.causal ? min(a.Lk - 1, query + off) : a.Lk - 1;     // last visible key
+    float mx = m_run;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int key = t * BKV + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+        const float v = key <= key_hi ? s[kb][r] * sc : -INFINITY;
+        s[kb][r] = v;
+        mx = fmaxf(mx, v);
+      }
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float alpha = exp2f(m_run - mx);               // 0 on the first tile (m_run = -inf, mx finite)
+    float sum = 0.f;
+    V16 pf[2][2];                                        // B operands of O^T: [32-key block][16-key step]
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const float p = exp2f(s[kb][r] - mx);
+        const bf16_t pb = f2bf(p);
+        sum += bf2f(pb);                                 // normalise by what is actually multiplied
+        pf[kb][r >> 3].h[r & 7] = pb;
+      }
+    sum += __shfl_xor(sum, 32, 64);
+    l_run = l_run * alpha + sum;
+    m_run = mx;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    // ---- O^T += V^T P ----
+#pragma unroll
+    for (int db = 0; db < 2; ++db) {
+      const int drow = db * 32 + col;
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int s2 = 0; s2 < 2; ++s2) {
+          V16 vf;
+          vf.u = *(const uint4*)&Vt[buf][drow * BKV + attn_swz(drow, (kb * 2 + s2) * 2 + half) * 8];
+          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, pf[kb][s2].b, oacc[db], 0, 0, 0);
+        }
+    }
+    if (t + 1 < n_tiles) sstore(buf ^ 1);
+    __syncthreads();
+  }
+
+  // ---- O[query, d] = O^T / l : lane (query, half) holds d = 32 db + 8 g + 4 half + i ----
+  if (query < a.Lq) {
+    const float inv = 1.f / l_run;
+    bf16_t* orow = (bf16_t*)a.o + b0 * a.o_sb0 + b1 * a.o_sb1 + (long long)query * a.o_sm;
+#pragma unroll
+    for (int db = 0; db < 2; ++db)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 w;
+        w.x = (uint32_t)f2bf(oacc[db][g * 4 + 0] * inv) | ((uint32_t)f2bf(oacc[db][g * 4 + 1] * inv) << 16);
+        w.y = (uint32_t)f2bf(oacc[db][g * 4 + 2] * inv) | ((uint32_t)f2bf(oacc[db][g * 4 + 3] * inv) << 16);
+        *(uint2*)(orow + db * 32 + g * 8 + half * 4) = w;
+      }
+  }
+}
+
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
+  if (a.Lq <= 0 || a.Lk <= 0) return hipSuccess;
+  const int batch = a.nb0 * a.nb1;
+  // 128 queries per workgroup when that still gives every CU work, else 64
+  if ((long long)((a.Lq + 127) / 128) * batch >= 256)
+    hipLaunchKernelGGL(attention_kernel<4>, dim3((a.Lq + 127) / 128, batch), dim3(256), 0, s, a);
+  else
+    hipLaunchKernelGGL(attention_kernel<2>, dim3((a.Lq + 63) / 64, batch), dim3(128), 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace sod2

@@ -1,0 +1,386 @@
+// MFMA contraction with direct global -> LDS loads (gfx950).
+//
+// C[M,N] = epilogue(A[M,K] * B[N,K]^T), A and B both k-contiguous bf16, fp32 accumulation on
+// v_mfma_f32_32x32x16_bf16.  The A operand comes from a loader (a strided matrix, or an NHWC
+// im2col address generator: the convolution is an implicit GEMM on the same main loop).
+//
+// Data movement: every lane issues global_load_lds_dwordx4, which copies 16 bytes from a per-lane
+// global address straight into LDS at (M0 base + lane * 16): no staging registers, no LDS store
+// instructions.  A ring of ST stages keeps ST-1 k-tiles in flight per workgroup, one barrier per
+// k-tile.  Because the hardware fixes the LDS position of a lane, the XOR swizzle that keeps the
+// MFMA fragment reads free of bank conflicts is applied on the global side: the lane that owns LDS
+// slot s of row r fetches k-chunk s ^ f(r).  Rows past M, k past K and padding taps of a convolution
+// fetch from a 16-byte block of zeros, so tails need no masking in the main loop.
+//
+// Loads are written as inline assembly together with their wait counts: the compiler would
+// otherwise wait for *all* outstanding loads before any LDS read, which serialises the ring.
+//
+// Split-K (gridDim.z > 1): each z computes a k range and stores fp32 partial tiles to a workspace;
+// splitk_reduce sums them in a fixed order and applies the epilogue (bit-reproducible).
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_common.hpp"
+
+namespace sod2 {
+
+static __device__ __attribute__((aligned(256))) uint4 g_zero_chunk[16];   // never written: all zero
+
+template <int KV> __device__ __forceinline__ int swz(int row, int c) {
+  if (KV == 8) return c ^ (row & 7);                                  // 128-byte rows
+  return c ^ ((row >> 1) & 3) ^ ((row >> 3) & 1);                     // 64-byte rows: two rows share a bank line
+}
+
+// ---- A-operand loaders: address of the 8 elements at k = (current tile) + kc of one row, or null ----
+struct DlMat {
+  const bf16_t* p;
+  long long sm;
+  int M, K, k0;
+  struct Row { const bf16_t* ptr; };
+  __device__ __forceinline__ void init_row(Row& r, int m) const { r.ptr = m < M ? p + (long long)m * sm : nullptr; }
+  __device__ __forceinline__ void tile(int k) { k0 = k; }
+  __device__ __forceinline__ const bf16_t* addr(const Row& r, int kc) const {
+    return (r.ptr && k0 + kc < K) ? r.ptr + k0 + kc : nullptr;
+  }
+};
+struct DlConv {                     // x[nb, ih, iw, c], k = (kh * KW + kw) * C + c; needs C % BK == 0
+  const bf16_t* p;
+  int H, W, C, KW, stride, pad, OH, OW, M, K;
+  int kh, kw, c0;
+  struct Row { const bf16_t* img; int ih0, iw0; };
+  __device__ __forceinline__ void init_row(Row& r, int m) const {
+    if (m >= M) { r.img = nullptr; r.ih0 = r.iw0 = 0; return; }
+    int ow = m % OW, t = m / OW;
+    int oh = t % OH, nb = t / OH;
+    r.img = p + (long long)nb * H * W * C;
+    r.ih0 = oh * stride - pad;
+    r.iw0 = ow * stride - pad;
+  }
+  __device__ __forceinline__ void tile(int k) {
+    if (k >= K) { kh = -0x40000000; kw = 0; c0 = 0; return; }       // past the end: every tap is outside
+    int kk = k / C;
+    c0 = k - kk * C;
+    kh = kk / KW;
+    kw = kk - kh * KW;
+  }
+  __device__ __forceinline__ const bf16_t* addr(const Row& r, int kc) const {
+    int ih = r.ih0 + kh, iw = r.iw0 + kw;
+    if (!r.img || ih < 0 || ih >= H || iw < 0 || iw >= W) return nullptr;
+    return r.img + ((long long)ih * W + iw) * C + c0 + kc;
+  }
+};
+
+__device__ __forceinline__ void load_lds16(const void* gptr, uint32_t lds_wave_base) {
+  // LDS address of lane l = lds_wave_base + 16 * l
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_wave_base), "v"(gptr) : "memory");
+}
+template <int N> __device__ __forceinline__ void wait_loads() {
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
+__device__ __forceinline__ void act8(float* x, int act) {
+  if (act == ACT_RELU) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = fmaxf(x[e], 0.f);
+  } else if (act == ACT_GELU) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = 0.5f * x[e] * (1.f + erff(x[e] * 0.70710678118654752f));
+  } else if (act == ACT_SIGMOID) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] = 1.f / (1.f + __expf(-x[e]));
+  }
+}
+
+// scale, bias, activation, residual, activation and the store of 8 consecutive columns of one row
+__device__ __forceinline__ void epilogue8(float* x, const GemmArgs& g, bf16_t* Cp, const bf16_t* Rp, int row, int col) {
+  const bf16_t* bias = (const bf16_t*)g.bias;
+  const bool full = g.c_vec && col + 8 <= g.N;
+  if (bias) {
+    if (full) {
+      V16 bv; bv.u = *(const uint4*)(bias + col);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = x[e] * g.scale + bf2f(bv.h[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] = x[e] * g.scale + (col + e < g.N ? bf2f(bias[col + e]) : 0.f);
+    }
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) x[e] *= g.scale;
+  }
+  act8(x, g.act1);
+  if (Rp) {
+    if (full) {
+      V16 rv; rv.u = *(const uint4*)(Rp + (long long)row * g.r_sm + col);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) x[e] += bf2f(rv.h[e]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
+        if (col + e < g.N) x[e] += bf2f(Rp[(long long)row * g.r_sm + (long long)(col + e) * g.r_sn]);
+    }
+    act8(x, g.act2);
+  }
+  if (full) {
+    V16 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o.h[e] = f2bf(x[e]);
+    *(uint4*)(Cp + (long long)row * g.c_sm + col) = o.u;
+  } else {
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      if (col + e < g.N) Cp[(long long)row * g.c_sm + (long long)(col + e) * g.c_sn] = f2bf(x[e]);
+  }
+}
+
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int DBG = 0>
+__global__ __launch_bounds__(256, OCC) void gemm_dl(AL al, GemmArgs g) {
+  constexpr int KV = BK / 8, TM = BM / (WM * 32), TN = BN / (WN * 32);
+  constexpr int LA = BM * KV / 256, LB = BN * KV / 256;         // 16-byte loads per thread per k-tile
+  constexpr int STAGE = (BM + BN) * BK;                         // bf16 elements per stage
+  constexpr int EW = TN * 32, ELD = EW + 4;
+  constexpr int EPI = 4 * 32 * ELD * 2;                         // four wave-private fp32 patches, in bf16 units
+  constexpr int LDS_ELEMS = (ST * STAGE > EPI) ? ST * STAGE : EPI;
+  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && LA >= 1 && LB >= 1 && ST >= 2, "four waves per workgroup");
+  static_assert((ST - 2) * (LA + LB) <= 63, "vmcnt is a 6-bit counter");
+  __shared__ __attribute__((aligned(16))) bf16_t lds[LDS_ELEMS];
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave / WN, wn = wave % WN;
+  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
+  // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give each XCD one
+  // contiguous range of tile ids, and walk the ids in panels of g.group_m tile rows (m fastest inside
+  // a panel), so that the tiles an XCD works on at one time share few A rows and few B columns.
+  const int nblk = tiles_m * tiles_n;
+  int lid;
+  {
+    const int b = blockIdx.x, q = nblk >> 3, r = nblk & 7, x = b & 7;
+    lid = x * q + min(x, r) + (b >> 3);
+  }
+  int tm, tn;
+  {
+    const int gm = g.group_m, per = gm * tiles_n;
+    const int panel = lid / per, rem = lid - panel * per;
+    const int pm0 = panel * gm, w = min(gm, tiles_m - pm0);
+    tm = pm0 + rem % w;
+    tn = rem / w;
+  }
+  const int b0 = blockIdx.y / g.nb1, b1 = blockIdx.y % g.nb1;
+  const int m0 = tm * BM, n0 = tn * BN;
+
+  al.p += b0 * g.a_sb0 + b1 * g.a_sb1;
+  const bf16_t* Bp = (const bf16_t*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
+
+  // k range of this split
+  const int nk_all = (g.K + BK - 1) / BK;
+  const int per_split = (nk_all + gridDim.z - 1) / gridDim.z;
+  const int kt0 = blockIdx.z * per_split;
+  const int nk = max(0, min(per_split, nk_all - kt0));
+
+  // fixed per thread: for load j the lane owns LDS position p = (j * 4 + wave) * 64 + lane of the A
+  // (or B) region, i.e. row p / KV, slot p % KV, and fetches k-chunk (slot ^ f(row))
+  typename AL::Row arow[LA];
+  int akc[LA];
+  const bf16_t* brow[LB];
+  int bkc[LB];
+#pragma unroll
+  for (int j = 0; j < LA; ++j) {
+    const int p = (j * 4 + wave) * 64 + lane, row = p / KV;
+    al.init_row(arow[j], m0 + row);
+    akc[j] = swz<KV>(row, p % KV) * 8;
+  }
+#pragma unroll
+  for (int j = 0; j < LB; ++j) {
+    const int p = (j * 4 + wave) * 64 + lane, row = p / KV;
+    brow[j] = (n0 + row < g.N) ? Bp + (long long)(n0 + row) * g.b_sn : nullptr;
+    bkc[j] = swz<KV>(row, p % KV) * 8;
+  }
+  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
+  const bf16_t* zero = (const bf16_t*)g_zero_chunk;
+
+  auto issue = [&](int t, int stage) {                         // k-tile t of this split into a stage
+    const int k0 = (kt0 + t) * BK;
+    al.tile(t < nk ? k0 : g.K);
+    const uint32_t sa = lds_base + stage * (STAGE * 2) + wave * 1024;
+#pragma unroll
+    for (int j = 0; j < LA; ++j) {
+      const bf16_t* a = al.addr(arow[j], akc[j]);
+      load_lds16(a ? a : zero, sa + j * 4096);
+    }
+    const uint32_t sb = sa + BM * BK * 2;
+#pragma unroll
+    for (int j = 0; j < LB; ++j) {
+      const bf16_t* b = (brow[j] && t < nk && k0 + bkc[j] < g.K) ? brow[j] + k0 + bkc[j] : zero;
+      load_lds16(b, sb + j * 4096);
+    }
+  };
+
+  f32x16_t acc[TM][TN];
+#pragma unroll
+  for (int i = 0; i < TM; ++i)
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
+
+  // MFMA fragments are double buffered in registers: the LDS reads of k-step ks+1 are issued before
+  // the MFMAs of k-step ks, and the ring's global loads go out between the first fragment reads and
+  // the first MFMAs, so that LDS latency, address arithmetic and the matrix pipe overlap even with a
+  // single wave per SIMD.
+  const int frow = lane & 31, fchunk = lane >> 5;
+  constexpr int KS = BK / 16;
+  int fslot[KS];
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) fslot[ks] = swz<KV>(frow, ks * 2 + fchunk) * 8;   // tile rows are multiples of 32: f(row) = f(frow)
+  const int a_off = (wm * TM * 32 + frow) * BK, b_off = BM * BK + (wn * TN * 32 + frow) * BK;
+  V16 af[2][TM], bf[2][TN];
+  auto frag_load = [&](const bf16_t* S, int ks, int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i) af[buf][i].u = *(const uint4*)&S[a_off + i * 32 * BK + fslot[ks]];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) bf[buf][j].u = *(const uint4*)&S[b_off + j * 32 * BK + fslot[ks]];
+  };
+  auto mfma_step = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][i].b, bf[buf][j].b, acc[i][j], 0, 0, 0);
+  };
+
+  // ring: tiles t .. t+ST-2 are in flight while tile t is computed.  Loads past the last tile are
+  // still issued (they fetch zeros into a stage nobody reads again), so the wait counts stay uniform.
+#pragma unroll
+  for (int s = 0; s < ST - 1; ++s) issue(s, s);
+  int rd = 0, wr = ST - 1;
+  for (int t = 0; t < nk; ++t) {
+    wait_loads<(ST - 2) * (LA + LB)>();                         // tile t has landed (this wave's part)
+    __syncthreads();                                            // ... everyone's part; stage wr is free again
+    const bf16_t* S = lds + rd * STAGE;
+    if (DBG != 2) frag_load(S, 0, 0);
+    if (DBG != 1) issue(t + ST - 1, wr);
+    if (DBG != 2) {
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      if (ks + 1 < KS) frag_load(S, ks + 1, (ks + 1) & 1);
+      if (DBG != 3) mfma_step(ks & 1);
+    }
+    }
+    rd = (rd + 1 == ST) ? 0 : rd + 1;
+    wr = (wr + 1 == ST) ? 0 : wr + 1;
+  }
+  wait_loads<0>();
+  __syncthreads();                                              // the stages become the epilogue patches
+
+  // ---- epilogue: 32 rows of the wave tile at a time through a wave-private fp32 LDS patch ----
+  float* patch = (float*)lds + wave * 32 * ELD;
+  bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
+  const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
+  float* Wp = gridDim.z > 1 ? (float*)g.ws + ((long long)blockIdx.z * gridDim.y + blockIdx.y) * (long long)g.M * g.N : nullptr;
+  const int colw = n0 + wn * EW;
+#pragma unroll
+  for (int i = 0; i < TM; ++i) {
+#pragma unroll
+    for (int j = 0; j < TN; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r)
+        patch[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * ELD + j * 32 + (lane & 31)] = acc[i][j][r];
+    const int roww = m0 + wm * TM * 32 + i * 32;
+#pragma unroll 1
+    for (int q = 0; q < 32 * EW / 8 / 64; ++q) {
+      const int v = lane + q * 64;
+      const int rr = v / (EW / 8), cc = (v % (EW / 8)) * 8;
+      const int row = roww + rr, col = colw + cc;
+      if (row >= g.M || col >= g.N) continue;
+      float x[8];
+      {
+        const float4 p0 = *(const float4*)&patch[rr * ELD + cc], p1 = *(const float4*)&patch[rr * ELD + cc + 4];
+        x[0] = p0.x; x[1] = p0.y; x[2] = p0.z; x[3] = p0.w; x[4] = p1.x; x[5] = p1.y; x[6] = p1.z; x[7] = p1.w;
+      }
+      if (Wp) {                                                 // fp32 partial sums of this k range
+        float* w = Wp + (long long)row * g.N + col;
+        if ((g.N & 3) == 0 && col + 8 <= g.N) {
+          *(float4*)w = make_float4(x[0], x[1], x[2], x[3]);
+          *(float4*)(w + 4) = make_float4(x[4], x[5], x[6], x[7]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) if (col + e < g.N) w[e] = x[e];
+        }
+      } else {
+        epilogue8(x, g, Cp, Rp, row, col);
+      }
+    }
+  }
+}
+
+// sums the split-K partials z = 0 .. splits-1 in that order and applies the epilogue
+__global__ __launch_bounds__(256) void splitk_reduce(GemmArgs g, int splits) {
+  const long long v = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int nv = (g.N + 7) / 8;
+  const int batch = blockIdx.y;
+  if (v >= (long long)g.M * nv) return;
+  const int row = (int)(v / nv), col = (int)(v % nv) * 8;
+  const int b0 = batch / g.nb1, b1 = batch % g.nb1;
+  const long long plane = (long long)g.M * g.N, nbatch = (long long)g.nb0 * g.nb1;
+  float x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int z = 0; z < splits; ++z) {
+    const float* w = (const float*)g.ws + (z * nbatch + batch) * plane + (long long)row * g.N + col;
+    if ((g.N & 3) == 0 && col + 8 <= g.N) {
+      const float4 p0 = *(const float4*)w, p1 = *(const float4*)(w + 4);
+      x[0] += p0.x; x[1] += p0.y; x[2] += p0.z; x[3] += p0.w; x[4] += p1.x; x[5] += p1.y; x[6] += p1.z; x[7] += p1.w;
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) if (col + e < g.N) x[e] += w[e];
+    }
+  }
+  bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
+  const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
+  epilogue8(x, g, Cp, Rp, row, col);
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-side launchers
+// ---------------------------------------------------------------------------------------------
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int DBG = 0>
+static hipError_t launch_dl(const AL& al, const GemmArgs& g, hipStream_t s) {
+  const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
+  const int splits = g.splits > 1 ? g.splits : 1;
+  dim3 grid(tiles, g.nb0 * g.nb1, splits);
+  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC, DBG>), grid, dim3(256), 0, s, al, g);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || splits == 1) return e;
+  const long long nvec = (long long)g.M * ((g.N + 7) / 8);
+  hipLaunchKernelGGL(splitk_reduce, dim3((unsigned)((nvec + 255) / 256), g.nb0 * g.nb1), dim3(256), 0, s, g, splits);
+  return hipGetLastError();
+}
+
+template <class AL>
+hipError_t launch_dl_variant(const AL& al, const GemmArgs& g, int tile, hipStream_t s) {
+  switch (tile) {
+    case DL_128x128x64_S3: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1>(al, g, s);
+    case DL_128x128x64_S4: return launch_dl<AL, 128, 128, 64, 4, 2, 2, 1>(al, g, s);
+    case DL_128x128x32_S3: return launch_dl<AL, 128, 128, 32, 3, 2, 2, 3>(al, g, s);
+    case DL_128x128x32_S4: return launch_dl<AL, 128, 128, 32, 4, 2, 2, 2>(al, g, s);
+    case DL_256x128x64_S3: return launch_dl<AL, 256, 128, 64, 3, 2, 2, 1>(al, g, s);
+    case DL_256x128x32_S3: return launch_dl<AL, 256, 128, 32, 3, 2, 2, 2>(al, g, s);
+    case DL_64x128x64_S4: return launch_dl<AL, 64, 128, 64, 4, 1, 4, 2>(al, g, s);
+    case DL_64x64x64_S4: return launch_dl<AL, 64, 64, 64, 4, 2, 2, 3>(al, g, s);
+    case DL_32x128x64_S4: return launch_dl<AL, 32, 128, 64, 4, 1, 4, 3>(al, g, s);
+    case 9: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1, 1>(al, g, s);
+    case 10: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1, 2>(al, g, s);
+    case 11: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1, 3>(al, g, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_gemm_dl(const GemmArgs& g, int tile, hipStream_t s) {
+  DlMat al{(const bf16_t*)g.A, g.a_sm, g.M, g.K, 0};
+  return launch_dl_variant(al, g, tile, s);
+}
+hipError_t launch_conv_dl(const ConvArgs& c, const GemmArgs& g, int tile, hipStream_t s) {
+  DlConv al{(const bf16_t*)c.x, c.H, c.W, c.C, c.KW, c.stride, c.pad, c.OH, c.OW, g.M, g.K, 0, 0, 0};
+  return launch_dl_variant(al, g, tile, s);
+}
+
+}  // namespace sod2

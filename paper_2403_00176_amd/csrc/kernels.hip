@@ -13,53 +13,10 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include "launch.hpp"
+#include "device_common.hpp"
 #define SOD2_BF16_TAG 1
 
 namespace sod2 {
-
-typedef uint16_t bf16_t;
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x16_t __attribute__((ext_vector_type(16)));
-
-__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
-__device__ __forceinline__ bf16_t f2bf(float f) {
-  uint32_t u = __float_as_uint(f);
-  if ((u & 0x7fffffffu) > 0x7f800000u) return 0x7fc0;          // NaN
-  u += 0x7fffu + ((u >> 16) & 1u);                              // round to nearest, ties to even
-  return (bf16_t)(u >> 16);
-}
-template <class T> __device__ __forceinline__ float to_f(T v);
-template <> __device__ __forceinline__ float to_f<float>(float v) { return v; }
-template <> __device__ __forceinline__ float to_f<bf16_t>(bf16_t v) { return bf2f(v); }
-template <class T> __device__ __forceinline__ T from_f(float v);
-template <> __device__ __forceinline__ float from_f<float>(float v) { return v; }
-template <> __device__ __forceinline__ bf16_t from_f<bf16_t>(float v) { return f2bf(v); }
-
-__device__ __forceinline__ float apply_act(float v, int act) {
-  if (act == ACT_RELU) return fmaxf(v, 0.f);
-  if (act == ACT_GELU) return 0.5f * v * (1.f + erff(v * 0.70710678118654752f));
-  if (act == ACT_SIGMOID) return 1.f / (1.f + __expf(-v));
-  return v;
-}
-
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
-}
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
-  return v;
-}
-
-union V16 {
-  uint4 u;
-  bf16x8_t b;
-  bf16_t h[8];
-};
-__device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
 
 // ---------------------------------------------------------------------------------------------
 // A-operand loaders: 8 consecutive k of one row, zero outside the matrix
@@ -912,7 +869,12 @@ static hipError_t launch_fast_variant(const AL& al, const GemmArgs& g, int varia
   }
 }
 
+hipError_t launch_gemm_dl(const GemmArgs& g, int tile, hipStream_t s);
+hipError_t launch_conv_dl(const ConvArgs& c, const GemmArgs& g, int tile, hipStream_t s);
+
 hipError_t launch_gemm(const Launch& L, const GemmArgs& g, hipStream_t s) {
+  if (L.variant >= V_DL0 && L.in_dtype == SOD2_BF16_TAG && g.a_vec && g.b_mode == 0)
+    return launch_gemm_dl(g, L.variant - V_DL0, s);
   if (L.variant == V_SIMPLE || L.in_dtype != SOD2_BF16_TAG) {
     dim3 grid(((g.M + 63) / 64) * ((g.N + 63) / 64), g.nb0 * g.nb1);
     if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(gemm_simple<bf16_t>, grid, dim3(256), 0, s, g);
@@ -944,6 +906,10 @@ hipError_t launch_conv(const Launch& L, const ConvArgs& c, hipStream_t s) {
   g.scale = 1.f; g.act1 = c.act1; g.act2 = c.act2;
   g.c_vec = (c.O % 8 == 0) && (((uintptr_t)c.y & 15) == 0) && (!c.bias || ((uintptr_t)c.bias & 15) == 0) &&
             (!c.res || ((uintptr_t)c.res & 15) == 0);
+  if (L.variant >= V_DL0 && c.vec && c.C % 64 == 0 && g.b_mode == 0) {
+    g.group_m = 8;
+    return launch_conv_dl(c, g, L.variant - V_DL0, s);
+  }
   if (c.vec && c.C % 32 == 0 && g.b_mode == 0) {
     ConvAF af{(const bf16_t*)c.x, c.H, c.W, c.C, c.KW, c.stride, c.pad, c.OH, c.OW, g.M, 0, 0, 0};
     return launch_fast_variant(af, g, L.variant, s);

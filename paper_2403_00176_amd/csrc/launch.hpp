@@ -14,9 +14,12 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX };
+                  K_ARGMAX, K_ATTENTION };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
-enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5 };
+enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_DL0 = 10 };
+// tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
+enum DlTile { DL_128x128x64_S3 = 0, DL_128x128x64_S4, DL_128x128x32_S3, DL_128x128x32_S4, DL_256x128x64_S3,
+              DL_256x128x32_S3, DL_64x128x64_S4, DL_64x64x64_S4, DL_32x128x64_S4, DL_DBG1, DL_DBG2, DL_DBG3, DL_TILES };
 
 // C[b0,b1,m,n] = act2( act1( scale * sum_k A[b0,b1,m,k] * B[b0,b1,k,n] + bias[n] ) + R[b0,b1,m,n] )
 struct GemmArgs {
@@ -30,6 +33,9 @@ struct GemmArgs {
   int act1, act2;
   int a_vec, b_mode;       // a_vec: 16-byte loads along k allowed; b_mode 0 k-contiguous vec, 1 n-contiguous vec, 2 scalar
   int c_vec;               // c_sn == 1 and rows 4-byte aligned
+  int splits;              // > 1: split-K, fp32 partials in ws, summed in a fixed order by a second kernel
+  int group_m;             // tile rows per panel of the tile walk (L2 locality)
+  void* ws;                // split-K workspace: splits x batch x M x N floats
 };
 
 // NHWC implicit GEMM: M = N*OH*OW, Ncol = O, K = KH*KW*C
@@ -93,6 +99,18 @@ struct ArgmaxArgs {
   int cols, out_i32;
 };
 
+// O[b0,b1,q,:] = softmax_k(scale * Q[b0,b1,q,:] . K[b0,b1,k,:] (+ causal mask)) V[b0,b1,k,:], head size 64,
+// last dim dense; strides in elements
+struct AttnArgs {
+  const void* q; const void* k; const void* v; void* o;
+  int Lq, Lk, nb0, nb1, causal;
+  float scale;
+  long long q_sb0, q_sb1, q_sm;
+  long long k_sb0, k_sb1, k_sn;
+  long long v_sb0, v_sb1, v_sn;
+  long long o_sb0, o_sb1, o_sm;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -109,6 +127,7 @@ struct Launch {
     GatherArgs gather;
     AppendArgs append;
     ArgmaxArgs argmax;
+    AttnArgs attn;
   } u;
   bool is_layernorm = false;
   double flops = 0, bytes = 0;

@@ -12,7 +12,11 @@
 //     non-view Gather absorbs one Add of proven-equal shape;
 //  R4 other elementwise operators chain while every aligned dim pair is proven equal or 1 (Fig. 4);
 //  R5 group id = smallest member id; groups are ordered by the node-order position of their
-//     last member.
+//     last member;
+//  R6 attention: a GEMM group of MatMul [+ Mul by a host scalar] read by one Softmax alone, whose
+//     result is the first operand of one MatMul alone leading a GEMM group of MatMul [+ Transpose]:
+//     the three become one ATTENTION group (scores and probabilities never reach memory); bf16
+//     tensors and a known head size of 64 only (what the fused kernel is written for).
 // Partition: cut around control operators and NonZero, after a group with a nac output, wherever
 // at most one arena tensor is live, and every 14 items.  Order inside a sub-graph: the sequence
 // with the smallest peak of live bytes at the symbols' upper bounds, ties to smaller group ids.
@@ -24,7 +28,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -186,6 +190,49 @@ void Plan::build() {
     }
   }
   for (int c : absorbed_transpose) view[c] = 0;
+
+  // R6: attention
+  if (opts.fusion) {
+    auto kinds_are = [&](const Group& gr, std::initializer_list<int> a, std::initializer_list<int> b) {
+      std::vector<int> k;
+      for (int m : gr.ops) k.push_back(G.ops[m].kind);
+      return k == std::vector<int>(a) || k == std::vector<int>(b);
+    };
+    for (int n : order) {
+      const Op& op = G.ops[n];
+      if (op.kind != SOD2_OP_SOFTMAX || group_of_op[n] < 0 || groups[group_of_op[n]].kind != G_SOFTMAX) continue;
+      int x = op.in[0], y = op.out[0];
+      int p1 = G.producer[x];
+      if (p1 < 0 || group_of_op[p1] < 0 || sole_consumer(x) != n) continue;
+      const Group g1 = groups[group_of_op[p1]];
+      if (g1.kind != G_GEMM || g1.out != x || !kinds_are(g1, {SOD2_OP_MATMUL}, {SOD2_OP_MATMUL, SOD2_OP_MUL})) continue;
+      int c2 = sole_consumer(y);
+      if (c2 < 0 || G.ops[c2].kind != SOD2_OP_MATMUL || G.ops[c2].in[0] != y || G.ops[c2].in[1] == y) continue;
+      const Group g2 = groups[group_of_op[c2]];
+      if (g2.kind != G_GEMM || g2.ops.front() != c2 || !kinds_are(g2, {SOD2_OP_MATMUL}, {SOD2_OP_MATMUL, SOD2_OP_TRANSPOSE}))
+        continue;
+      const Op& mm1 = G.ops[g1.ops[0]];
+      bool bf = true;
+      for (int t : {mm1.in[0], mm1.in[1], G.ops[c2].in[1], x, y, g2.out}) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
+      const LS &sq = R.S[mm1.in[0]], &sv = R.S[G.ops[c2].in[1]];
+      if (!bf || !sq.is_list() || !sv.is_list() || sq.d.empty() || sv.d.empty() || !sq.d.back().is_c(64) || !sv.d.back().is_c(64))
+        continue;
+      Group gr;
+      gr.kind = G_ATTENTION;
+      gr.chain = g1.chain;
+      gr.chain.push_back(n);
+      gr.chain.insert(gr.chain.end(), g2.chain.begin(), g2.chain.end());
+      gr.ops = gr.chain;
+      std::sort(gr.ops.begin(), gr.ops.end());
+      gr.gid = gr.ops.front();
+      gr.out = g2.out;
+      groups.erase(g1.gid);
+      groups.erase(group_of_op[n]);
+      groups.erase(g2.gid);
+      for (int m : gr.ops) group_of_op[m] = gr.gid;
+      groups[gr.gid] = gr;
+    }
+  }
 
   // static storage bases: views and Switch outputs alias their (data) input
   int nt = (int)G.tensors.size();

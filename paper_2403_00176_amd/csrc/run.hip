@@ -18,6 +18,7 @@ hipError_t launch_eltwise(const Launch& L, const EltArgs& a, hipStream_t s);
 hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s);
 hipError_t launch_append(const Launch& L, const AppendArgs& a, hipStream_t s);
 hipError_t launch_argmax(const Launch& L, const ArgmaxArgs& a, hipStream_t s);
+hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 
 void destroy_events(void* events, int n) {
   hipEvent_t* e = (hipEvent_t*)events;
@@ -612,8 +613,97 @@ struct Builder {
     return L;
   }
 
+  // fused attention group: MatMul(q, k^T) [* scale] -> Softmax -> MatMul(p, v) [-> Transpose]
+  Launch attention(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_ATTENTION;
+    const Op *mm1 = nullptr, *mm2 = nullptr, *sm = nullptr, *tp = nullptr;
+    float scale = 1.f;
+    int cur = -1;
+    for (int n : gr.chain) {
+      const Op& op = G.ops[n];
+      if (op.kind == SOD2_OP_MATMUL) { (mm1 ? mm2 : mm1) = &op; }
+      else if (op.kind == SOD2_OP_MUL) scale *= (float)G.tensors[other(op, cur)].fdata.at(0);
+      else if (op.kind == SOD2_OP_SOFTMAX) sm = &op;
+      else if (op.kind == SOD2_OP_TRANSPOSE) tp = &op;
+      cur = op.out[0];
+    }
+    if (!mm1 || !mm2 || !sm) throw Error(SOD2_ERR_UNSUPPORTED, "malformed attention group");
+    const int dt = SOD2_BF16;
+    L.in_dtype = L.out_dtype = dt;
+    const View &vq = view_of(mm1->in[0]), &vk = view_of(mm1->in[1]), &vv = view_of(mm2->in[1]);
+    bool tb1 = !mm1->ia.empty() && mm1->ia[0], tb2 = !mm2->ia.empty() && mm2->ia[0];
+    size_t r = vq.dims.size();
+    if (r < 2 || vk.dims.size() != r || vv.dims.size() != r || r > 4)
+      throw Error(SOD2_ERR_UNSUPPORTED, "attention operands must share one rank of 2 to 4");
+    // logical [batch..., Lq, d] x [batch..., Lk, d] -> [batch..., Lq, Lk]; the second operand of a MatMul without
+    // transB is [.., d, Lk]
+    auto dim = [](const View& v, size_t i) { return v.dims[i]; };
+    auto str = [](const View& v, size_t i) { return v.strides[i]; };
+    const size_t kd = tb1 ? r - 1 : r - 2, kn = tb1 ? r - 2 : r - 1;      // d axis / key axis of k
+    const size_t vn = tb2 ? r - 1 : r - 2, vd = tb2 ? r - 2 : r - 1;      // key axis / d axis of v
+    AttnArgs a{};
+    a.Lq = (int)dim(vq, r - 2);
+    a.Lk = (int)dim(vk, kn);
+    if (dim(vq, r - 1) != 64 || dim(vk, kd) != 64 || dim(vv, vd) != 64 || dim(vv, vn) != a.Lk)
+      throw Error(SOD2_ERR_SHAPE_MISMATCH, "attention needs head size 64 and matching key counts");
+    if ((dim(vq, r - 1) != 1 && str(vq, r - 1) != 1) || str(vk, kd) != 1 || str(vv, vd) != 1)
+      throw Error(SOD2_ERR_UNSUPPORTED, "attention operands need a dense head dim");
+    a.causal = !sm->ia.empty() && sm->ia[0];
+    if (a.causal && a.Lk < a.Lq) throw Error(SOD2_ERR_UNSUPPORTED, "causal attention with fewer keys than queries");
+    a.scale = scale;
+    a.q_sm = a.Lq == 1 ? 0 : str(vq, r - 2);            // the stride of a dim of size 1 carries no meaning
+    a.k_sn = a.Lk == 1 ? 0 : str(vk, kn);
+    a.v_sn = a.Lk == 1 ? 0 : str(vv, vn);
+    // output strides per logical dim of mm2's result [batch..., Lq, d], through the absorbed Transpose
+    std::vector<int64_t> logical = eval_dims(mm2->out[0]), cs;
+    if (tp) {
+      std::vector<int64_t> od(logical.size());
+      for (size_t i = 0; i < tp->ia.size(); ++i) od[i] = logical[tp->ia[i]];
+      std::vector<int64_t> os = contiguous_strides(od);
+      cs.assign(logical.size(), 0);
+      for (size_t i = 0; i < tp->ia.size(); ++i) cs[tp->ia[i]] = os[i];
+    } else {
+      cs = contiguous_strides(logical);
+    }
+    if (cs[r - 1] != 1) throw Error(SOD2_ERR_UNSUPPORTED, "attention output needs a dense head dim");
+    a.o_sm = a.Lq == 1 ? 0 : cs[r - 2];
+    size_t nbatch = r - 2;
+    if (nbatch > 2) throw Error(SOD2_ERR_UNSUPPORTED, "attention with more than two batch dims");
+    int64_t nb[2] = {1, 1}, qs[2] = {0, 0}, ks[2] = {0, 0}, vs[2] = {0, 0}, os[2] = {0, 0};
+    for (size_t j = 0; j < nbatch; ++j) {
+      size_t slot = 2 - nbatch + j;
+      nb[slot] = logical[j];
+      auto bs = [&](const View& v) { return v.dims[j] == 1 ? 0 : v.strides[j]; };
+      if ((vq.dims[j] != 1 && vq.dims[j] != logical[j]) || (vk.dims[j] != 1 && vk.dims[j] != logical[j]) ||
+          (vv.dims[j] != 1 && vv.dims[j] != logical[j]))
+        throw Error(SOD2_ERR_SHAPE_MISMATCH, "attention batch dims do not broadcast");
+      qs[slot] = bs(vq); ks[slot] = bs(vk); vs[slot] = bs(vv); os[slot] = cs[j];
+    }
+    a.nb0 = (int)nb[0]; a.nb1 = (int)nb[1];
+    a.q_sb0 = qs[0]; a.q_sb1 = qs[1]; a.k_sb0 = ks[0]; a.k_sb1 = ks[1];
+    a.v_sb0 = vs[0]; a.v_sb1 = vs[1]; a.o_sb0 = os[0]; a.o_sb1 = os[1];
+    for (int64_t s8 : {a.q_sm, a.k_sn, a.v_sn, a.q_sb0, a.q_sb1, a.k_sb0, a.k_sb1, a.v_sb0, a.v_sb1})
+      if (s8 % 8 != 0) throw Error(SOD2_ERR_UNSUPPORTED, "attention operand strides must be multiples of 8 elements");
+    for (int64_t s4 : {a.o_sm, a.o_sb0, a.o_sb1})
+      if (s4 % 4 != 0) throw Error(SOD2_ERR_UNSUPPORTED, "attention output strides must be multiples of 4 elements");
+    L.r[0] = ref_of(vq, dt);
+    L.r[1] = ref_of(vk, dt);
+    L.r[2] = ref_of(vv, dt);
+    L.r[3] = ref_t(gr.out);
+    for (int i = 0; i < 4; ++i)
+      if (L.r[i].byte_off % 16 != 0) throw Error(SOD2_ERR_UNSUPPORTED, "attention operands must be 16-byte aligned");
+    L.u.attn = a;
+    double batch = (double)a.nb0 * a.nb1;
+    L.flops = 4.0 * batch * a.Lq * a.Lk * 64 * (a.causal ? 0.5 : 1.0);
+    L.bytes = 2.0 * batch * 64 * (2.0 * a.Lq + 2.0 * a.Lk);
+    return L;
+  }
+
   Launch make(const Group& gr) {
     switch (gr.kind) {
+      case G_ATTENTION: return attention(gr);
       case G_GATHER: return gather(gr);
       case G_CACHEAPPEND: return append(gr);
       case G_ARGMAX: return argmax(gr);
@@ -648,6 +738,11 @@ struct Pointers {
 
 bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
 
+int tune_group_m() {
+  static int v = [] { const char* e = getenv("SOD2_GROUP_M"); int x = e ? atoi(e) : 8; return x > 0 ? x : 8; }();
+  return v;
+}
+
 hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
   switch (L.kernel) {
     case K_GEMM: {
@@ -662,6 +757,7 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       g.c_vec = g.c_sn == 1 && g.c_sm % 8 == 0 && g.c_sb0 % 8 == 0 && g.c_sb1 % 8 == 0 && al16(g.C) &&
                 (!g.bias || al16(g.bias)) &&
                 (!g.res || (g.r_sn == 1 && g.r_sm % 8 == 0 && g.r_sb0 % 8 == 0 && g.r_sb1 % 8 == 0 && al16(g.res)));
+      g.group_m = tune_group_m();
       return launch_gemm(L, g, s);
     }
     case K_CONV: {
@@ -691,6 +787,12 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       for (int k = 0; k < a.n_in; ++k) a.in[k] = P.at(L.r[k]);
       a.out = P.at(L.r[5]);
       return launch_eltwise(L, a, s);
+    }
+    case K_ATTENTION: {
+      AttnArgs a = L.u.attn;
+      a.q = P.at(L.r[0]); a.k = P.at(L.r[1]); a.v = P.at(L.r[2]); a.o = P.at(L.r[3]);
+      if (!al16(a.q) || !al16(a.k) || !al16(a.v) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
+      return launch_attention(a, s);
     }
     case K_GATHER: {
       GatherArgs a = L.u.gather;
