@@ -27,7 +27,7 @@ namespace sod2 {
 static __device__ __attribute__((aligned(256))) uint4 g_zero_chunk[16];   // never written: all zero
 
 template <int KV> __device__ __forceinline__ int swz(int row, int c) {
-  if (KV == 8) return c ^ (row & 7);                                  // 128-byte rows
+  if (KV == 8) return c ^ ((row >> 1) & 7);                           // 128-byte rows (measured conflict free; row & 7 is not)
   return c ^ ((row >> 1) & 3) ^ ((row >> 3) & 1);                     // 64-byte rows: two rows share a bank line
 }
 
@@ -84,7 +84,7 @@ __device__ __forceinline__ void act8(float* x, int act) {
     for (int e = 0; e < 8; ++e) x[e] = fmaxf(x[e], 0.f);
   } else if (act == ACT_GELU) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) x[e] = 0.5f * x[e] * (1.f + erff(x[e] * 0.70710678118654752f));
+    for (int e = 0; e < 8; ++e) x[e] = gelu_erf(x[e]);
   } else if (act == ACT_SIGMOID) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] = 1.f / (1.f + __expf(-x[e]));
@@ -133,15 +133,17 @@ __device__ __forceinline__ void epilogue8(float* x, const GemmArgs& g, bf16_t* C
   }
 }
 
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int DBG = 0>
-__global__ __launch_bounds__(256, OCC) void gemm_dl(AL al, GemmArgs g) {
+// WM x WN waves per workgroup, OCC workgroups per CU (the second launch bound counts waves per SIMD)
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC>
+__global__ __launch_bounds__(WM * WN * 64, OCC * WM * WN / 4) void gemm_dl(AL al, GemmArgs g) {
+  constexpr int NWV = WM * WN, NT = NWV * 64;
   constexpr int KV = BK / 8, TM = BM / (WM * 32), TN = BN / (WN * 32);
-  constexpr int LA = BM * KV / 256, LB = BN * KV / 256;         // 16-byte loads per thread per k-tile
+  constexpr int LA = BM * KV / NT, LB = BN * KV / NT;           // 16-byte loads per thread per k-tile
   constexpr int STAGE = (BM + BN) * BK;                         // bf16 elements per stage
   constexpr int EW = TN * 32, ELD = EW + 4;
-  constexpr int EPI = 4 * 32 * ELD * 2;                         // four wave-private fp32 patches, in bf16 units
+  constexpr int EPI = NWV * 32 * ELD * 2;                       // wave-private fp32 patches, in bf16 units
   constexpr int LDS_ELEMS = (ST * STAGE > EPI) ? ST * STAGE : EPI;
-  static_assert(WM * WN == 4 && TM >= 1 && TN >= 1 && LA >= 1 && LB >= 1 && ST >= 2, "four waves per workgroup");
+  static_assert((NWV == 4 || NWV == 8) && TM >= 1 && TN >= 1 && LA >= 1 && LB >= 1 && ST >= 2, "4 or 8 waves per workgroup");
   static_assert((ST - 2) * (LA + LB) <= 63, "vmcnt is a 6-bit counter");
   __shared__ __attribute__((aligned(16))) bf16_t lds[LDS_ELEMS];
 
@@ -178,7 +180,7 @@ __global__ __launch_bounds__(256, OCC) void gemm_dl(AL al, GemmArgs g) {
   const int kt0 = blockIdx.z * per_split;
   const int nk = max(0, min(per_split, nk_all - kt0));
 
-  // fixed per thread: for load j the lane owns LDS position p = (j * 4 + wave) * 64 + lane of the A
+  // fixed per thread: for load j the lane owns LDS position p = (j * NWV + wave) * 64 + lane of the A
   // (or B) region, i.e. row p / KV, slot p % KV, and fetches k-chunk (slot ^ f(row))
   typename AL::Row arow[LA];
   int akc[LA];
@@ -186,13 +188,13 @@ __global__ __launch_bounds__(256, OCC) void gemm_dl(AL al, GemmArgs g) {
   int bkc[LB];
 #pragma unroll
   for (int j = 0; j < LA; ++j) {
-    const int p = (j * 4 + wave) * 64 + lane, row = p / KV;
+    const int p = (j * NWV + wave) * 64 + lane, row = p / KV;
     al.init_row(arow[j], m0 + row);
     akc[j] = swz<KV>(row, p % KV) * 8;
   }
 #pragma unroll
   for (int j = 0; j < LB; ++j) {
-    const int p = (j * 4 + wave) * 64 + lane, row = p / KV;
+    const int p = (j * NWV + wave) * 64 + lane, row = p / KV;
     brow[j] = (n0 + row < g.N) ? Bp + (long long)(n0 + row) * g.b_sn : nullptr;
     bkc[j] = swz<KV>(row, p % KV) * 8;
   }
@@ -206,13 +208,13 @@ __global__ __launch_bounds__(256, OCC) void gemm_dl(AL al, GemmArgs g) {
 #pragma unroll
     for (int j = 0; j < LA; ++j) {
       const bf16_t* a = al.addr(arow[j], akc[j]);
-      load_lds16(a ? a : zero, sa + j * 4096);
+      load_lds16(a ? a : zero, sa + j * (NWV * 1024));
     }
     const uint32_t sb = sa + BM * BK * 2;
 #pragma unroll
     for (int j = 0; j < LB; ++j) {
       const bf16_t* b = (brow[j] && t < nk && k0 + bkc[j] < g.K) ? brow[j] + k0 + bkc[j] : zero;
-      load_lds16(b, sb + j * 4096);
+      load_lds16(b, sb + j * (NWV * 1024));
     }
   };
 
@@ -258,14 +260,12 @@ __global__ __launch_bounds__(256, OCC) void gemm_dl(AL al, GemmArgs g) {
     wait_loads<(ST - 2) * (LA + LB)>();                         // tile t has landed (this wave's part)
     __syncthreads();                                            // ... everyone's part; stage wr is free again
     const bf16_t* S = lds + rd * STAGE;
-    if (DBG != 2) frag_load(S, 0, 0);
-    if (DBG != 1) issue(t + ST - 1, wr);
-    if (DBG != 2) {
+    frag_load(S, 0, 0);
+    issue(t + ST - 1, wr);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
       if (ks + 1 < KS) frag_load(S, ks + 1, (ks + 1) & 1);
-      if (DBG != 3) mfma_step(ks & 1);
-    }
+      mfma_step(ks & 1);
     }
     rd = (rd + 1 == ST) ? 0 : rd + 1;
     wr = (wr + 1 == ST) ? 0 : wr + 1;
@@ -342,12 +342,12 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs g, int splits) {
 // ---------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int DBG = 0>
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC>
 static hipError_t launch_dl(const AL& al, const GemmArgs& g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const int splits = g.splits > 1 ? g.splits : 1;
   dim3 grid(tiles, g.nb0 * g.nb1, splits);
-  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC, DBG>), grid, dim3(256), 0, s, al, g);
+  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC>), grid, dim3(WM * WN * 64), 0, s, al, g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   const long long nvec = (long long)g.M * ((g.N + 7) / 8);
@@ -358,18 +358,17 @@ static hipError_t launch_dl(const AL& al, const GemmArgs& g, hipStream_t s) {
 template <class AL>
 hipError_t launch_dl_variant(const AL& al, const GemmArgs& g, int tile, hipStream_t s) {
   switch (tile) {
-    case DL_128x128x64_S3: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1>(al, g, s);
-    case DL_128x128x64_S4: return launch_dl<AL, 128, 128, 64, 4, 2, 2, 1>(al, g, s);
-    case DL_128x128x32_S3: return launch_dl<AL, 128, 128, 32, 3, 2, 2, 3>(al, g, s);
-    case DL_128x128x32_S4: return launch_dl<AL, 128, 128, 32, 4, 2, 2, 2>(al, g, s);
-    case DL_256x128x64_S3: return launch_dl<AL, 256, 128, 64, 3, 2, 2, 1>(al, g, s);
-    case DL_256x128x32_S3: return launch_dl<AL, 256, 128, 32, 3, 2, 2, 2>(al, g, s);
-    case DL_64x128x64_S4: return launch_dl<AL, 64, 128, 64, 4, 1, 4, 2>(al, g, s);
-    case DL_64x64x64_S4: return launch_dl<AL, 64, 64, 64, 4, 2, 2, 3>(al, g, s);
-    case DL_32x128x64_S4: return launch_dl<AL, 32, 128, 64, 4, 1, 4, 3>(al, g, s);
-    case 9: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1, 1>(al, g, s);
-    case 10: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1, 2>(al, g, s);
-    case 11: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1, 3>(al, g, s);
+    case DL_128x128x64_S3_W4: return launch_dl<AL, 128, 128, 64, 3, 2, 2, 1>(al, g, s);
+    case DL_128x128x64_S2_W4: return launch_dl<AL, 128, 128, 64, 2, 2, 2, 2>(al, g, s);
+    case DL_128x128x32_S3_W4: return launch_dl<AL, 128, 128, 32, 3, 2, 2, 3>(al, g, s);
+    case DL_128x128x64_S2_W8: return launch_dl<AL, 128, 128, 64, 2, 2, 4, 2>(al, g, s);
+    case DL_256x128x64_S2_W8: return launch_dl<AL, 256, 128, 64, 2, 4, 2, 1>(al, g, s);
+    case DL_256x128x32_S3_W8: return launch_dl<AL, 256, 128, 32, 3, 4, 2, 2>(al, g, s);
+    case DL_64x128x64_S3_W4: return launch_dl<AL, 64, 128, 64, 3, 1, 4, 2>(al, g, s);
+    case DL_64x64x64_S4_W4: return launch_dl<AL, 64, 64, 64, 4, 2, 2, 2>(al, g, s);
+    case DL_128x64x64_S3_W4: return launch_dl<AL, 128, 64, 64, 3, 4, 1, 2>(al, g, s);
+    case DL_128x128x64_S3_W8: return launch_dl<AL, 128, 128, 64, 3, 2, 4, 1>(al, g, s);
+    case DL_256x256x32_S3_W8: return launch_dl<AL, 256, 256, 32, 3, 2, 4, 1>(al, g, s);
     default: return hipErrorInvalidValue;
   }
 }

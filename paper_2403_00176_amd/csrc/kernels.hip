@@ -377,7 +377,7 @@ __global__ __launch_bounds__(256, (TM * TN > 4) ? 1 : 2) void gemm_fast(AL al, G
       for (int e = 0; e < 8; ++e) x[e] = fmaxf(x[e], 0.f);
     } else if (act == ACT_GELU) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = 0.5f * x[e] * (1.f + erff(x[e] * 0.70710678118654752f));
+      for (int e = 0; e < 8; ++e) x[e] = gelu_erf(x[e]);
     } else if (act == ACT_SIGMOID) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) x[e] = 1.f / (1.f + __expf(-x[e]));

@@ -219,16 +219,18 @@ struct Builder {
     return e;
   }
 
-  int pick_variant(int dtype, int64_t M, int64_t N, int64_t batch) const {
+  // Kernel version (Section 4.4.2: fat / regular / skinny versions chosen at run time by shape), a
+  // pure function of the contraction's shape.  Measured on MI355X: with at least ~160 tiles of
+  // 128 x 128 the 8-wave 128 x 128 x 64 kernel wins (three ring stages when k is long, two stages
+  // and two workgroups per CU otherwise); below that the 64 x 64 x 64 tile with a four-stage ring
+  // puts more workgroups (more loads in flight) on the chip.
+  int pick_variant(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch) const {
     if (dtype != SOD2_BF16) return V_SIMPLE;
     if (force_variant >= 0) return force_variant;
     if (!p.opts.mvc) return V_REGULAR;
-    // the largest tile that still yields enough workgroups for 256 CUs (two workgroups fit a CU)
-    auto tiles = [&](int64_t bm, int64_t bn) { return ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch; };
-    if (M <= 32) return V_SKINNY;
-    if (tiles(256, 128) >= 512) return V_FAT;
-    if (tiles(128, 128) >= 256) return V_REGULAR;
-    return V_SMALL;
+    const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+    if (t128 >= 160) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
+    return V_DL0 + DL_64x64x64_S4_W4;
   }
 
   Launch gemm(const Group& gr) {
@@ -316,7 +318,7 @@ struct Builder {
     if (e.bias >= 0) L.r[3] = ref_t(e.bias);
     if (e.res >= 0) L.r[4] = ref_of(view_of(e.res), dt);
     int64_t batch = (int64_t)g.nb0 * g.nb1;
-    L.variant = pick_variant(dt, g.M, g.N, batch);
+    L.variant = pick_variant(dt, g.M, g.N, g.K, batch);
     L.u.gemm = g;
     double eb = dtype_bytes(dt);
     L.flops = 2.0 * g.M * g.N * g.K * batch;
@@ -356,7 +358,7 @@ struct Builder {
       L.r[4] = ref_of(vr, dt);
     }
     int64_t M = (int64_t)c.NB * c.OH * c.OW;
-    L.variant = pick_variant(dt, M, c.O, 1);
+    L.variant = pick_variant(dt, M, c.O, (int64_t)c.KH * c.KW * c.C, 1);
     L.u.conv = c;
     double eb = dtype_bytes(dt), K = (double)c.KH * c.KW * c.C;
     L.flops = 2.0 * M * c.O * K;

@@ -70,6 +70,17 @@ def test_encoder_bf16_small(S, variant):
     print("encoder small max rel err", variant, max(errs))
 
 
+@pytest.mark.parametrize("variant", list(range(10, 21)))
+def test_direct_to_lds_tiles(S, variant):
+    """Every tile of the direct-to-LDS contraction kernel forced in turn (variant 10 + tile) on ragged
+    encoder shapes (M tails, several k tiles, K = 3072 ring wrap-around) and on a small CNN."""
+    w = configs.config2(2, layers=1)
+    errs = run_case(S, w, [(0, {"B": 3, "L": 77}), (1, {"B": 2, "L": 200})], variant=variant)
+    w = configs.resnet50(3, 1, sizes=(64, 96), stages=(1, 1, 1, 1))
+    errs += run_case(S, w, [(0, {"H": 96, "W": 96})], variant=variant)
+    print("dl tile", variant - 10, "max rel err", max(errs))
+
+
 def test_config2_full_depth_sampled(S):
     """12 layers at the smallest and a mid-size call of the benchmark's draw list; the largest
     shapes are checked on the first two layers only (oracle time)."""
