@@ -16,6 +16,50 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def bench_decoder(args, S, dev):
+    """Config 5 (not the headline workload): per sequence one prompt pass and `t_max` greedy decode steps, the
+    next token read on the device; reports ms per generated token and the prompt-pass latency."""
+    import numpy as np
+    import torch
+    from paper_2403_00176_amd.session import DecoderSession
+    from workloads import configs
+    w = configs.config5(n_prompts=max(1, min(args.steps, 8)))
+    ses = DecoderSession(w.prefill, w.decode, w.t_max, device=dev)
+    ses.upload_weights(w.make_weights_by_name())
+    rows = []
+    for i, P in enumerate(w.prompts):
+        prompt = torch.from_numpy(np.asarray(w.make_prompt(i), dtype=np.int64)).to(dev)
+        ses.start(P, w.vocab)
+        for rep in range(2):                       # first repetition warms up
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            ses.prefill(prompt)
+            torch.cuda.synchronize()
+            t1 = time.perf_counter()
+            for t in range(w.t_max):
+                ses.decode(t)
+            torch.cuda.synchronize()
+            t2 = time.perf_counter()
+        b = ses.dec.bind({"P": P, "t": w.t_max - 1})
+        S.sod2_binding_set_profiling(b, True)
+        ses.decode(w.t_max - 1, b)
+        torch.cuda.synchronize()
+        per = {}
+        for r in S.sod2_binding_launch_records(b):
+            k = per.setdefault(r["kernel"], [0, 0.0, 0.0])
+            k[0] += 1; k[1] += r["ms"]; k[2] += r["bytes"]
+        rows.append(dict(P=P, prefill_ms=round((t1 - t0) * 1e3, 3), decode_ms_per_token=round((t2 - t1) * 1e3 / w.t_max, 4),
+                         arena_mb=round(ses.arena.numel() / 2 ** 20, 2),
+                         last_step_kernels={k: dict(n=v[0], us=round(v[1] * 1e3, 1), gbs=round(v[2] / max(v[1], 1e-9) / 1e6, 1))
+                                            for k, v in per.items()}))
+        print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    out = {"metric": "decode latency per generated token", "unit": "ms",
+           "value": round(sum(r["decode_ms_per_token"] for r in rows) / len(rows), 4), "n_gpus": 1,
+           "config": {"workload": "config 5: 24-layer decoder, hidden 1024, KV cache in the arena, greedy 256 tokens"},
+           "dtype": "bf16", "data": "synthetic", "sequences": rows}
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -40,6 +84,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.config == 5:
+        return bench_decoder(args, S, dev)
     n_calls = args.steps + args.warmup
     w = configs.BUILDERS[args.config](n_calls=max(n_calls, 64)) if args.config != 2 else configs.config2(max(n_calls, 64))
     t0 = time.perf_counter()
@@ -114,7 +160,7 @@ def main():
         S.sod2_binding_set_profiling(b, True)
         ses.run(b, ins, outs)
         stream.synchronize()
-        tokens += sym.get("B", 1) * sym.get("L", 1)
+        tokens += sym.get("B", 1) * sym.get("L", sym.get("H", 1))
         for r in S.sod2_binding_launch_records(b):
             k = per.setdefault(r["kernel"], dict(launches=0, ms=0.0, flops=0.0, bytes=0.0))
             k["launches"] += 1

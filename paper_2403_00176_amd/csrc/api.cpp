@@ -224,8 +224,8 @@ sod2_status sod2_binding_force_decisions(sod2_binding_t* b, const int32_t* dec, 
   return SOD2_OK;
 }
 sod2_status sod2_binding_force_variant(sod2_binding_t* b, int32_t v) {
-  if (!b || v < -1 || (v > 5 && v < sod2::V_DL0) || v >= sod2::V_DL0 + sod2::DL_TILES) {
-    g_err = "variant must be -1 .. 5, or 10 + a tile of the direct-to-LDS kernel";
+  if (!b || v < -1 || (v > 6 && v < sod2::V_DL0) || v >= sod2::V_DL0 + sod2::DL_TILES) {
+    g_err = "variant must be -1 .. 6, or 10 + a tile of the direct-to-LDS kernel";
     return SOD2_ERR_INVALID_ARG;
   }
   b->force_variant = v;

@@ -177,9 +177,96 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
   }
 }
 
+// Few queries against a long key / value cache (the decode step): one workgroup per (batch, head,
+// query).  HBM-bound streaming of K and V, plain fp32 FMAs: 8 lanes share a key (16 bytes of its 64
+// values each), 32 keys per pass; probabilities are kept in LDS, so Lk <= 4096.
+constexpr int DEC_MAX_KEYS = 4096;
+__global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a) {
+  __shared__ float prob[DEC_MAX_KEYS];
+  __shared__ float red[32][65];
+  __shared__ float stat[8];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int kg = tid >> 3, dc = tid & 7;
+  const int query = blockIdx.x;
+  const int b0 = blockIdx.y / a.nb1, b1 = blockIdx.y % a.nb1;
+  const bf16_t* Qp = (const bf16_t*)a.q + b0 * a.q_sb0 + b1 * a.q_sb1 + (long long)query * a.q_sm;
+  const bf16_t* Kp = (const bf16_t*)a.k + b0 * a.k_sb0 + b1 * a.k_sb1;
+  const bf16_t* Vp = (const bf16_t*)a.v + b0 * a.v_sb0 + b1 * a.v_sb1;
+  const int n_keys = a.causal ? min(a.Lk, query + (a.Lk - a.Lq) + 1) : a.Lk;     // visible keys: 0 .. n_keys-1
+  float qf[8];
+  {
+    V16 q; q.u = *(const uint4*)(Qp + dc * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) qf[e] = bf2f(q.h[e]) * a.scale;
+  }
+  // scores
+  float mx = -INFINITY;
+  for (int t0 = kg; t0 < n_keys; t0 += 128) {           // four keys per thread and pass: four loads in flight
+    V16 k[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) k[u].u = *(const uint4*)(Kp + (long long)min(t0 + u * 32, n_keys - 1) * a.k_sn + dc * 8);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s = fmaf(qf[e], bf2f(k[u].h[e]), s);
+      s += __shfl_xor(s, 1, 64);
+      s += __shfl_xor(s, 2, 64);
+      s += __shfl_xor(s, 4, 64);
+      const int t = t0 + u * 32;
+      if (t < n_keys) {
+        if (dc == 0) prob[t] = s;
+        mx = fmaxf(mx, s);
+      }
+    }
+  }
+  mx = wave_max(mx);
+  if (lane == 0) stat[wave] = mx;
+  __syncthreads();
+  mx = fmaxf(fmaxf(stat[0], stat[1]), fmaxf(stat[2], stat[3]));
+  float sum = 0.f;
+  for (int t = tid; t < n_keys; t += 256) {
+    const float p = __expf(prob[t] - mx);
+    prob[t] = p;
+    sum += p;
+  }
+  sum = wave_sum(sum);
+  if (lane == 0) stat[4 + wave] = sum;
+  __syncthreads();
+  const float inv = 1.f / (stat[4] + stat[5] + stat[6] + stat[7]);
+  // values
+  float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  for (int t0 = kg; t0 < n_keys; t0 += 128) {
+    V16 v[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) v[u].u = *(const uint4*)(Vp + (long long)min(t0 + u * 32, n_keys - 1) * a.v_sn + dc * 8);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int t = t0 + u * 32;
+      const float p = t < n_keys ? prob[t] : 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) o[e] = fmaf(p, bf2f(v[u].h[e]), o[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) red[kg][dc * 8 + e] = o[e];
+  __syncthreads();
+  if (tid < 64) {
+    float t = 0.f;
+#pragma unroll
+    for (int r = 0; r < 32; ++r) t += red[r][tid];
+    bf16_t* orow = (bf16_t*)a.o + b0 * a.o_sb0 + b1 * a.o_sb1 + (long long)query * a.o_sm;
+    orow[tid] = f2bf(t * inv);
+  }
+}
+
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
   if (a.Lq <= 0 || a.Lk <= 0) return hipSuccess;
   const int batch = a.nb0 * a.nb1;
+  if (a.Lq <= 4 && a.Lk <= DEC_MAX_KEYS) {
+    hipLaunchKernelGGL(decode_attention_kernel, dim3(a.Lq, batch), dim3(256), 0, s, a);
+    return hipGetLastError();
+  }
   // 128 queries per workgroup when that still gives every CU work, else 64
   if ((long long)((a.Lq + 127) / 128) * batch >= 256)
     hipLaunchKernelGGL(attention_kernel<4>, dim3((a.Lq + 127) / 128, batch), dim3(256), 0, s, a);

@@ -340,6 +340,64 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs g, int splits) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Skinny contraction (M <= 8, the decode shape): weight streaming bound by HBM, no MFMA.  One wave
+// per output column n: the 64 lanes split k in 16-byte chunks of B[n, :], multiply them with the
+// matching chunks of the (L1-resident) A rows, and a wave shuffle tree finishes the sums.  Four
+// columns per workgroup, so N / 4 workgroups stream the weight matrix with every CU pulling.
+// ---------------------------------------------------------------------------------------------
+template <int MR>
+__global__ __launch_bounds__(256) void gemv_kernel(GemmArgs g) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 4 + wave;
+  const int b0 = blockIdx.y / g.nb1, b1 = blockIdx.y % g.nb1;
+  if (n >= g.N) return;
+  const bf16_t* A = (const bf16_t*)g.A + b0 * g.a_sb0 + b1 * g.a_sb1;
+  const bf16_t* B = (const bf16_t*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1 + (long long)n * g.b_sn;
+  float acc[MR];
+#pragma unroll
+  for (int m = 0; m < MR; ++m) acc[m] = 0.f;
+  const int nchunk = g.K >> 3;
+#pragma unroll 4
+  for (int c = lane; c < nchunk; c += 64) {
+    V16 w; w.u = *(const uint4*)(B + c * 8);
+    float wf[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) wf[e] = bf2f(w.h[e]);
+#pragma unroll
+    for (int m = 0; m < MR; ++m) {
+      if (m < g.M) {
+        V16 a; a.u = *(const uint4*)(A + (long long)m * g.a_sm + c * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[m] = fmaf(bf2f(a.h[e]), wf[e], acc[m]);
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < MR; ++m) acc[m] = wave_sum(acc[m]);
+  if (lane == 0) {
+    const float bv = g.bias ? bf2f(((const bf16_t*)g.bias)[n]) : 0.f;
+    bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
+    const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
+#pragma unroll
+    for (int m = 0; m < MR; ++m) {
+      if (m < g.M) {
+        float v = apply_act(acc[m] * g.scale + bv, g.act1);
+        if (Rp) v = apply_act(v + bf2f(Rp[(long long)m * g.r_sm + (long long)n * g.r_sn]), g.act2);
+        Cp[(long long)m * g.c_sm + (long long)n * g.c_sn] = f2bf(v);
+      }
+    }
+  }
+}
+
+hipError_t launch_gemv(const GemmArgs& g, hipStream_t s) {
+  dim3 grid((g.N + 3) / 4, g.nb0 * g.nb1);
+  if (g.M <= 1) hipLaunchKernelGGL(gemv_kernel<1>, grid, dim3(256), 0, s, g);
+  else if (g.M <= 4) hipLaunchKernelGGL(gemv_kernel<4>, grid, dim3(256), 0, s, g);
+  else hipLaunchKernelGGL(gemv_kernel<8>, grid, dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------
 template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC>

@@ -16,7 +16,7 @@ struct Ref {
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
                   K_ARGMAX, K_ATTENTION };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
-enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_DL0 = 10 };
+enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
 enum DlTile { DL_128x128x64_S3_W4 = 0, DL_128x128x64_S2_W4, DL_128x128x32_S3_W4, DL_128x128x64_S2_W8, DL_256x128x64_S2_W8,
               DL_256x128x32_S3_W8, DL_64x128x64_S3_W4, DL_64x64x64_S4_W4, DL_128x64x64_S3_W4, DL_128x128x64_S3_W8,

@@ -228,6 +228,7 @@ struct Builder {
     if (dtype != SOD2_BF16) return V_SIMPLE;
     if (force_variant >= 0) return force_variant;
     if (!p.opts.mvc) return V_REGULAR;
+    if (M <= 8) return V_GEMV;                     // decode shape: weight streaming, one wave per column
     const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
     if (t128 >= 160) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
     return V_DL0 + DL_64x64x64_S4_W4;
@@ -751,6 +752,7 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       GemmArgs g = L.u.gemm;
       g.A = P.at(L.r[0]); g.B = P.at(L.r[1]); g.C = P.at(L.r[2]);
       g.bias = P.at(L.r[3]); g.res = P.at(L.r[4]);
+      if (g.M == 1) { g.a_sm = g.K; g.c_sm = g.N; g.r_sm = g.N; }     // the stride of a single row carries no meaning
       g.a_vec = g.a_sk == 1 && g.K % 8 == 0 && g.a_sm % 8 == 0 && g.a_sb0 % 8 == 0 && g.a_sb1 % 8 == 0 && al16(g.A);
       bool bal = g.b_sb0 % 8 == 0 && g.b_sb1 % 8 == 0 && al16(g.B);
       if (g.b_sk == 1 && g.K % 8 == 0 && g.b_sn % 8 == 0 && bal) g.b_mode = 0;
