@@ -60,6 +60,27 @@ def bench_decoder(args, S, dev):
     print(json.dumps(out))
 
 
+def measured_traffic(family):
+    """HBM bytes per launch of a kernel family, from the committed rocprofv3 --pmc summaries of this same
+    command (FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size): counters cannot be read
+    from inside the process, so the number comes from profiles/ and is None when no summary is there."""
+    total = 0.0
+    for name in ("config2_fetch_size.txt", "config2_write_size.txt"):
+        path = os.path.join(ROOT, "profiles", name)
+        if not os.path.exists(path):
+            return None
+        val = None
+        for line in open(path):
+            if line.startswith(f"ALL {family} kernels"):
+                parts = [p.strip() for p in line.split("|")]
+                if len(parts) >= 4:
+                    val = float(parts[3])
+        if val is None:
+            return None
+        total += val
+    return total
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +88,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg (0 = skip)")
+    ap.add_argument("--calibration-copy-mb", type=int, default=0,
+                    help="before the timed region, run a plain device copy of this many MiB three times: under "
+                         "rocprofv3 --pmc it gives the scale of FETCH_SIZE / WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (each call is an independent request; "
@@ -118,6 +142,12 @@ def main():
             stream.synchronize()
         return b
 
+    if args.calibration_copy_mb:
+        src = torch.ones(args.calibration_copy_mb << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     one_call(*calls[0][1:])
     first_call_ms = (time.perf_counter() - t0) * 1e3
@@ -175,16 +205,18 @@ def main():
                              gbs=round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1) if k["ms"] else 0.0)
     dom = max(per, key=lambda n: per[n]["ms"])
     d = per[dom]
+    traffic = measured_traffic(dom) if args.config == 2 else None
     if dom in ("gemm", "conv"):
         achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=None,
+                        frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
+                        algorithmic_bytes_per_launch=d["bytes"] / d["launches"],
                         avg_launch_us=round(1e3 * d["ms"] / d["launches"], 2),
                         flops_per_launch=d["flops"] / d["launches"])
     else:
         achieved = d["bytes"] / (d["ms"] * 1e-3) / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(achieved / PEAK_HBM_GBS, 4), traffic=None,
+                        frac=round(achieved / PEAK_HBM_GBS, 4), traffic=traffic,
                         avg_launch_us=round(1e3 * d["ms"] / d["launches"], 2),
                         bytes_per_launch=d["bytes"] / d["launches"])
 

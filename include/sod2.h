@@ -168,6 +168,14 @@ sod2_status sod2_binding_force_decisions(sod2_binding_t*, const int32_t* decisio
  * 3 the plain FMA kernel (any dtype, any strides) */
 sod2_status sod2_binding_force_variant(sod2_binding_t*, int32_t variant);
 
+/* force the number of k ranges of every contraction that can split k (split-K: fp32 partial tiles
+ * summed in a fixed order): 0 automatic, 1 never, n <= 16 that many where the workspace allows */
+sod2_status sod2_binding_force_splits(sod2_binding_t*, int32_t n);
+/* Optional workspace.  When the arena handed to sod2_run is at least this many bytes longer than
+ * sod2_binding_arena_bytes (rounded up to 256), its last workspace_bytes are used for split-K partial
+ * sums; with a shorter arena no contraction splits k.  Either way the same call is bit-reproducible. */
+sod2_status sod2_binding_workspace_bytes(const sod2_binding_t*, size_t* workspace_bytes);
+
 /* -- run -------------------------------------------------------------------------------------- */
 /* arena: device memory, 256-byte aligned, at least arena_bytes long.  weights / inputs / outputs:
  * host arrays of device pointers, one per tensor with that role, ordered by tensor id.

@@ -32,6 +32,7 @@ EXPORTS = [
     "sod2_rdp_destroy", "sod2_rdp_query", "sod2_rdp_sweeps", "sod2_rdp_dump", "sod2_plan", "sod2_plan_destroy",
     "sod2_plan_counts", "sod2_plan_dump", "sod2_bind", "sod2_bind_decided", "sod2_binding_destroy",
     "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_force_decisions", "sod2_binding_force_variant",
+    "sod2_binding_force_splits", "sod2_binding_workspace_bytes",
     "sod2_run", "sod2_run_decisions", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
     "sod2_binding_launch_records", "sod2_last_error", "sod2_version",
 ]
@@ -310,6 +311,16 @@ def sod2_binding_force_decisions(b: Binding, decisions: Sequence[int]):
 
 def sod2_binding_force_variant(b: Binding, variant: int):
     _check(_lib.sod2_binding_force_variant(b.ptr, int(variant)))
+
+
+def sod2_binding_force_splits(b: Binding, n: int):
+    _check(_lib.sod2_binding_force_splits(b.ptr, int(n)))
+
+
+def sod2_binding_workspace_bytes(b: Binding) -> int:
+    n = C.c_size_t()
+    _check(_lib.sod2_binding_workspace_bytes(b.ptr, C.byref(n)))
+    return n.value
 
 
 def sod2_binding_set_profiling(b: Binding, on: bool):

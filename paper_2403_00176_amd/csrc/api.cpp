@@ -232,6 +232,17 @@ sod2_status sod2_binding_force_variant(sod2_binding_t* b, int32_t v) {
   b->launches_valid = false;
   return SOD2_OK;
 }
+sod2_status sod2_binding_force_splits(sod2_binding_t* b, int32_t n) {
+  if (!b || n < 0 || n > 16) { g_err = "splits must be 0 (automatic) .. 16"; return SOD2_ERR_INVALID_ARG; }
+  b->force_splits = n;
+  b->launches_valid = false;
+  return SOD2_OK;
+}
+sod2_status sod2_binding_workspace_bytes(const sod2_binding_t* b, size_t* bytes) {
+  if (!b || !bytes) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
+  *bytes = (size_t)sod2::WS_BYTES;
+  return SOD2_OK;
+}
 sod2_status sod2_run_decisions(const sod2_binding_t* b, int32_t* dec, int32_t cap, int32_t* n) {
   if (!b || !n) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
   *n = (int)b->last_decisions.size();

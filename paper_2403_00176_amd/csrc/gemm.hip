@@ -15,8 +15,11 @@
 // Loads are written as inline assembly together with their wait counts: the compiler would
 // otherwise wait for *all* outstanding loads before any LDS read, which serialises the ring.
 //
-// Split-K (gridDim.z > 1): each z computes a k range and stores fp32 partial tiles to a workspace;
-// splitk_reduce sums them in a fixed order and applies the epilogue (bit-reproducible).
+// Split-K (gridDim.z > 1): each z computes a k range and stores its fp32 partial tile to a
+// workspace; splitk_reduce, launched behind it, sums the partials in the order z = 0, 1, ... and
+// applies the epilogue (bit-reproducible).  A single-kernel version (the last workgroup of a tile,
+// found by a ticket counter, does the sum) was measured slower here: partials that must be visible
+// across XCDs inside one kernel need device-scope stores and loads, which bypass the L2.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

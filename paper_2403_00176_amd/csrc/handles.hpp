@@ -14,6 +14,7 @@ struct sod2_binding_s {
   std::vector<int> forced;                  // decisions forced on the next runs
   bool has_forced = false;
   int force_variant = -1;
+  int force_splits = 0;                     // 0 automatic, 1 never split k, n > 1 that many k ranges where possible
   bool profiling = false;
   std::vector<int> last_decisions;
   sod2::BindResult executed;                // plan of the last run when it contained Switches

@@ -34,10 +34,14 @@ struct GemmArgs {
   int act1, act2;
   int a_vec, b_mode;       // a_vec: 16-byte loads along k allowed; b_mode 0 k-contiguous vec, 1 n-contiguous vec, 2 scalar
   int c_vec;               // c_sn == 1 and rows 4-byte aligned
-  int splits;              // > 1: split-K, fp32 partials in ws, summed in a fixed order by a second kernel
+  int splits;              // > 1: split-K, fp32 partials in ws, summed in z order by a second kernel
   int group_m;             // tile rows per panel of the tile walk (L2 locality)
   void* ws;                // split-K workspace: splits x batch x M x N floats
 };
+
+// Optional workspace behind the planned arena (fp32 partial tiles of split-K contractions)
+constexpr long long WS_PARTIAL_BYTES = 16 << 20;
+constexpr long long WS_BYTES = WS_PARTIAL_BYTES;
 
 // NHWC implicit GEMM: M = N*OH*OW, Ncol = O, K = KH*KW*C
 struct ConvArgs {

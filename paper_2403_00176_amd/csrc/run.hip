@@ -93,6 +93,7 @@ struct Builder {
   const Graph& G;
   const BindResult& b;
   int force_variant;
+  int force_splits = 0;
   std::map<int, View> memo;
   std::map<int, int> widx, iidx, oidx;
 
@@ -234,6 +235,25 @@ struct Builder {
     return V_DL0 + DL_64x64x64_S4_W4;
   }
 
+  // Split-K (only with the direct-to-LDS kernel; costs a second launch that sums the partials): for a
+  // long k with few tiles, where one workgroup per tile would walk k alone while most CUs idle.
+  int pick_splits(int variant, int64_t M, int64_t N, int64_t K, int64_t batch) const {
+    if (variant < V_DL0 || force_splits == 1 || (!p.opts.mvc && force_splits == 0)) return 1;
+    const bool small = variant == V_DL0 + DL_64x64x64_S4_W4;
+    const int64_t bm = small ? 64 : 128, bn = small ? 64 : 128;
+    const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
+    int64_t s = force_splits;
+    if (force_splits == 0) {
+      if (!small || K < 2048 || tiles > 256) return 1;
+      s = std::min<int64_t>(512 / std::max<int64_t>(tiles, 1), K / 384);
+    }
+    int64_t pow2 = 1;
+    while (pow2 * 2 <= s && pow2 < (force_splits > 1 ? 16 : 8)) pow2 *= 2;
+    s = pow2;
+    while (s > 1 && (double)s * M * N * 4.0 * batch > (double)WS_PARTIAL_BYTES) s /= 2;
+    return (int)std::max<int64_t>(s, 1);
+  }
+
   Launch gemm(const Group& gr) {
     Launch L;
     L.group = gr.gid;
@@ -320,6 +340,7 @@ struct Builder {
     if (e.res >= 0) L.r[4] = ref_of(view_of(e.res), dt);
     int64_t batch = (int64_t)g.nb0 * g.nb1;
     L.variant = pick_variant(dt, g.M, g.N, g.K, batch);
+    g.splits = pick_splits(L.variant, g.M, g.N, g.K, batch);
     L.u.gemm = g;
     double eb = dtype_bytes(dt);
     L.flops = 2.0 * g.M * g.N * g.K * batch;
@@ -724,6 +745,7 @@ struct Builder {
 };
 
 struct Pointers {
+  char* ws = nullptr;        // optional workspace behind the planned arena, or null
   char* arena; size_t arena_bytes;
   const void* const* w; int nw;
   const void* const* in; int nin;
@@ -762,6 +784,11 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
                 (!g.bias || al16(g.bias)) &&
                 (!g.res || (g.r_sn == 1 && g.r_sm % 8 == 0 && g.r_sb0 % 8 == 0 && g.r_sb1 % 8 == 0 && al16(g.res)));
       g.group_m = tune_group_m();
+      if (g.splits > 1 && P.ws) {
+        g.ws = P.ws;
+      } else {
+        g.splits = 1;
+      }
       return launch_gemm(L, g, s);
     }
     case K_CONV: {
@@ -819,8 +846,9 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
 }
 
 // launch table for every executed group step of `b`, indexed by step (-1 kernel for control steps)
-std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force_variant) {
+std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force_variant, int force_splits) {
   Builder B(p, b, force_variant);
+  B.force_splits = force_splits;
   std::vector<Launch> out;
   for (int i : b.steps) {
     const Item& it = p.items[i];
@@ -852,10 +880,17 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
                                                 std::to_string(h->b.arena_bytes));
     if (((uintptr_t)arena & 255) != 0) throw Error(SOD2_ERR_INVALID_ARG, "arena must be 256-byte aligned");
     hipStream_t s = (hipStream_t)stream;
-    Pointers P{(char*)arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs};
+    Pointers P{nullptr, (char*)arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs};
+    // an arena longer than the plan by WS_BYTES carries the optional workspace at its end
+    auto workspace_for = [&](int64_t plan_bytes) -> char* {
+      size_t end = arena_bytes & ~(size_t)255;
+      if (end < (size_t)WS_BYTES || end - (size_t)WS_BYTES < (size_t)((plan_bytes + 255) / 256 * 256)) return nullptr;
+      return (char*)arena + end - WS_BYTES;
+    };
+    P.ws = workspace_for(h->b.arena_bytes);
 
     if (!h->launches_valid) {
-      h->launches = build_launches(p, h->b, h->force_variant);
+      h->launches = build_launches(p, h->b, h->force_variant, h->force_splits);
       h->launches_valid = true;
     }
     h->records.clear();
@@ -923,7 +958,8 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
             throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, the path taken needs " +
                                                       std::to_string(replanned.arena_bytes) + "; nothing after the Switch was launched");
           }
-          relaunch = build_launches(p, replanned, h->force_variant);
+          relaunch = build_launches(p, replanned, h->force_variant, h->force_splits);
+          P.ws = workspace_for(replanned.arena_bytes);
           cur = &replanned;
           launches = &relaunch;
         }

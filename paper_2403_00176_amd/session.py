@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 from . import (sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run, sod2_binding_arena_bytes,
-               sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes, Sod2Error)
+               sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes, sod2_binding_workspace_bytes, Sod2Error)
 
 _NP = {"f32": np.float32, "i64": np.int64, "i32": np.int32}
 _TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "i64": torch.int64, "i32": torch.int32}
@@ -47,14 +47,17 @@ class Session:
         self.plan = sod2_plan(self.graph, self.rdp, **plan_opts)
         self.weights: List[torch.Tensor] = []
         self.arena: Optional[torch.Tensor] = None
+        self.workspace_bytes = 0
         self.stream = torch.cuda.current_stream(self.device)
 
     def upload_weights(self, weights: Dict[int, np.ndarray]):
         self.weights = [to_device(weights[t], self.desc.tensors[t].dtype, self.device) for t in self.desc.weights()]
 
     def ensure_arena(self, nbytes: int):
+        """The planned arena plus the optional workspace behind it (enables split-K)."""
+        nbytes = (max(nbytes, 256) + 255) // 256 * 256 + self.workspace_bytes
         if self.arena is None or self.arena.numel() < nbytes:
-            self.arena = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.device)
+            self.arena = torch.empty(nbytes, dtype=torch.uint8, device=self.device)
         return self.arena
 
     def upload_inputs(self, inputs: Dict[int, np.ndarray]) -> List[torch.Tensor]:
@@ -65,7 +68,10 @@ class Session:
                 for t, s in zip(self.desc.outputs(), out_shapes)]
 
     def bind(self, sym):
-        return sod2_bind(self.plan, sym)
+        b = sod2_bind(self.plan, sym)
+        if not self.workspace_bytes:
+            self.workspace_bytes = sod2_binding_workspace_bytes(b)
+        return b
 
     def run(self, binding, inputs: List[torch.Tensor], outputs: List[torch.Tensor]):
         nbytes, _ = sod2_binding_arena_bytes(binding)
@@ -120,6 +126,7 @@ class DecoderSession:
         self.b_pre = self.pre.bind({"P": P})
         need = sod2_binding_arena_bytes(self.b_pre)[0]
         need = max(need, sod2_binding_arena_bytes(self.dec.bind({"P": P, "t": self.t_max - 1}))[0])
+        need = (need + 255) // 256 * 256 + sod2_binding_workspace_bytes(self.b_pre)
         if self.arena is None or self.arena.numel() < need:
             self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
         self.tokens = torch.zeros(P + self.t_max + 1, dtype=torch.int64, device=self.device)

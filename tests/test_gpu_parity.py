@@ -24,7 +24,7 @@ def S():
     return S
 
 
-def run_case(S, w, calls, variant=-1, check_structure=True, **opts):
+def run_case(S, w, calls, variant=-1, check_structure=True, splits=0, **opts):
     from paper_2403_00176_amd.session import Session, to_host
     import torch
     ses = Session(w.graph, **opts)
@@ -39,6 +39,8 @@ def run_case(S, w, calls, variant=-1, check_structure=True, **opts):
         b = ses.bind(sym)
         if variant >= 0:
             S.sod2_binding_force_variant(b, variant)
+        if splits:
+            S.sod2_binding_force_splits(b, splits)
         if check_structure:
             assert S.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
         outs = ses.alloc_outputs(ses.output_shapes(b))
@@ -79,6 +81,35 @@ def test_direct_to_lds_tiles(S, variant):
     w = configs.resnet50(3, 1, sizes=(64, 96), stages=(1, 1, 1, 1))
     errs += run_case(S, w, [(0, {"H": 96, "W": 96})], variant=variant)
     print("dl tile", variant - 10, "max rel err", max(errs))
+
+
+@pytest.mark.parametrize("splits", [2, 4, 16])
+def test_split_k(S, splits):
+    """Split-K forced on every contraction that can split (fp32 partials in the workspace behind the
+    arena, summed in a fixed order by the last workgroup of a tile): values stay within the bar, two
+    runs are bit-identical, and without the workspace the same binding still runs (unsplit)."""
+    import torch
+    from paper_2403_00176_amd.session import Session
+    w = configs.config2(2, layers=2)
+    for variant in (17, 13):
+        run_case(S, w, [(0, {"B": 3, "L": 77}), (1, {"B": 1, "L": 32}), (2, {"B": 2, "L": 200})], variant=variant, splits=splits)
+    ses = Session(w.graph)
+    ses.upload_weights(w.make_weights())
+    sym = {"B": 2, "L": 100}
+    b = ses.bind(sym)
+    S.sod2_binding_force_splits(b, splits)
+    ins = ses.upload_inputs(w.make_inputs(0, sym))
+    outs = [ses.alloc_outputs(ses.output_shapes(b)) for _ in range(3)]
+    ses.run(b, ins, outs[0])
+    ses.run(b, ins, outs[1])
+    need = S.sod2_binding_arena_bytes(b)[0]
+    arena = torch.empty(need, dtype=torch.uint8, device="cuda")          # no room for the workspace
+    S.sod2_run(b, arena.data_ptr(), arena.numel(), [x.data_ptr() for x in ses.weights], [x.data_ptr() for x in ins],
+               [x.data_ptr() for x in outs[2]], ses.stream.cuda_stream)
+    torch.cuda.synchronize()
+    assert torch.equal(outs[0][0].view(torch.int16), outs[1][0].view(torch.int16))
+    ref = outs[0][0].float()
+    assert float((outs[2][0].float() - ref).abs().max() / ref.abs().max()) <= 2e-2
 
 
 def test_config2_full_depth_sampled(S):
