@@ -193,7 +193,9 @@ sod2_status sod2_run_decisions(const sod2_binding_t*, int32_t* decisions_host, i
 sod2_status sod2_run_plan_dump(const sod2_binding_t*, char* buf_host, size_t cap, size_t* needed);
 sod2_status sod2_run_arena_bytes(const sod2_binding_t*, size_t* arena_bytes, size_t* peak_live_bytes);
 
-/* per-launch records of the last run (filled when profiling is on: two events per launch) */
+/* per-launch records of the last run (filled when profiling is on: two events per launch).  The
+ * first two records (kernel 7, groups -1 and -2) are one and two empty launches timed the same way:
+ * twice the first minus the second is what the pair of events adds to every duration. */
 typedef struct {
   int32_t group;       /* group id */
   int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other,
