@@ -43,7 +43,8 @@ def pmc(path, counter, copy_bytes=None):
             print(f"# calibration: {len(big)} dispatches of {k} moving {copy_bytes} bytes read {sum(big) / len(big):.1f} {counter} units"
                   f" -> {scale:.2f} bytes per unit")
     print(f"# kernel | dispatches | average {counter} per dispatch" + (" | average bytes per dispatch" if scale else ""))
-    groups = collections.defaultdict(list)
+    total = collections.defaultdict(float)
+    count = collections.defaultdict(int)
     for k, v in sorted(per.items(), key=lambda kv: -sum(kv[1])):
         line = f"{k} | {len(v)} | {sum(v) / len(v):.1f}"
         if scale:
@@ -51,11 +52,13 @@ def pmc(path, counter, copy_bytes=None):
         print(line)
         fam = "gemm" if ("gemm" in k or "gemv" in k or "splitk" in k) else ("attention" if "attention" in k else None)
         if fam:
-            groups[fam] += v
-    for fam, v in groups.items():
-        line = f"ALL {fam} kernels | {len(v)} | {sum(v) / len(v):.1f}"
+            total[fam] += sum(v)
+            if "splitk" not in k:            # the partial-sum pass belongs to the contraction launched before it
+                count[fam] += len(v)
+    for fam in total:
+        line = f"ALL {fam} kernels | {count[fam]} | {total[fam] / count[fam]:.1f}"
         if scale:
-            line += f" | {scale * sum(v) / len(v):.0f}"
+            line += f" | {scale * total[fam] / count[fam]:.0f}"
         print(line)
 
 
