@@ -33,8 +33,14 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, half = lane >> 5;
-  const int b0 = blockIdx.y / a.nb1, b1 = blockIdx.y % a.nb1;
-  const int q_wg = blockIdx.x * (NW * 32);
+  // Workgroups are dealt round-robin to the 8 XCDs: keep all query tiles of one (batch, head) on one
+  // XCD, so that its K and V are fetched into a single L2 (grid = 8 * ceil(batch / 8) * query tiles)
+  const int n_qt = (a.Lq + NW * 32 - 1) / (NW * 32);
+  const int slot = blockIdx.x >> 3;
+  const int bh = (slot / n_qt) * 8 + (blockIdx.x & 7);
+  if (bh >= a.nb0 * a.nb1) return;
+  const int b0 = bh / a.nb1, b1 = bh % a.nb1;
+  const int q_wg = (slot % n_qt) * (NW * 32);
   const int query = q_wg + wave * 32 + col;
   const int off = a.Lk - a.Lq;                           // causal: query i sees keys <= i + off
 
@@ -268,10 +274,11 @@ hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
     return hipGetLastError();
   }
   // 128 queries per workgroup when that still gives every CU work, else 64
+  const int batch8 = (batch + 7) / 8 * 8;
   if ((long long)((a.Lq + 127) / 128) * batch >= 256)
-    hipLaunchKernelGGL(attention_kernel<4>, dim3((a.Lq + 127) / 128, batch), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(attention_kernel<4>, dim3(((a.Lq + 127) / 128) * batch8), dim3(256), 0, s, a);
   else
-    hipLaunchKernelGGL(attention_kernel<2>, dim3((a.Lq + 63) / 64, batch), dim3(128), 0, s, a);
+    hipLaunchKernelGGL(attention_kernel<2>, dim3(((a.Lq + 63) / 64) * batch8), dim3(128), 0, s, a);
   return hipGetLastError();
 }
 
