@@ -136,18 +136,23 @@ __device__ __forceinline__ void epilogue8(float* x, const GemmArgs& g, bf16_t* C
   }
 }
 
-// WM x WN waves per workgroup, OCC workgroups per CU (the second launch bound counts waves per SIMD)
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC>
-__global__ __launch_bounds__(WM * WN * 64, OCC * WM * WN / 4) void gemm_dl(AL al, GemmArgs g) {
-  constexpr int NWV = WM * WN, NT = NWV * 64;
+// WM x WN compute waves, LW >= WM * WN waves in all: every wave issues its share of the global -> LDS
+// loads (a wave sustains only ~1 KB per 100 ns of such loads, so the extra "loader" waves raise the
+// rate at which a workgroup walks k); waves past WM * WN skip the MFMA part and the epilogue.
+// OCC workgroups per CU (the second launch bound counts waves per SIMD).
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN>
+__global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs g) {
+  constexpr int NCW = WM * WN, NWV = LW, NT = NWV * 64;
   constexpr int KV = BK / 8, TM = BM / (WM * 32), TN = BN / (WN * 32);
-  constexpr int LA = BM * KV / NT, LB = BN * KV / NT;           // 16-byte loads per thread per k-tile
+  constexpr int LT = (BM + BN) * KV / NT;                       // 16-byte loads per thread per k-tile (A rows, then B rows)
   constexpr int STAGE = (BM + BN) * BK;                         // bf16 elements per stage
   constexpr int EW = TN * 32, ELD = EW + 4;
-  constexpr int EPI = NWV * 32 * ELD * 2;                       // wave-private fp32 patches, in bf16 units
+  constexpr int EPI = NCW * 32 * ELD * 2;                       // wave-private fp32 patches, in bf16 units
   constexpr int LDS_ELEMS = (ST * STAGE > EPI) ? ST * STAGE : EPI;
-  static_assert((NWV == 4 || NWV == 8) && TM >= 1 && TN >= 1 && LA >= 1 && LB >= 1 && ST >= 2, "4 or 8 waves per workgroup");
-  static_assert((ST - 2) * (LA + LB) <= 63, "vmcnt is a 6-bit counter");
+  static_assert((NCW == 4 || NCW == 8) && LW >= NCW && LW <= 16 && TM >= 1 && TN >= 1 && LT >= 1 && ST >= 2 &&
+                    (BM + BN) * KV % NT == 0 && BM % (64 / KV) == 0,
+                "4 or 8 compute waves, at most 16 waves");
+  static_assert((ST - 2) * LT <= 63, "vmcnt is a 6-bit counter");
   __shared__ __attribute__((aligned(16))) bf16_t lds[LDS_ELEMS];
 
   const int tid = threadIdx.x, lane = tid & 63;
@@ -183,23 +188,27 @@ __global__ __launch_bounds__(WM * WN * 64, OCC * WM * WN / 4) void gemm_dl(AL al
   const int kt0 = blockIdx.z * per_split;
   const int nk = max(0, min(per_split, nk_all - kt0));
 
-  // fixed per thread: for load j the lane owns LDS position p = (j * NWV + wave) * 64 + lane of the A
-  // (or B) region, i.e. row p / KV, slot p % KV, and fetches k-chunk (slot ^ f(row))
-  typename AL::Row arow[LA];
-  int akc[LA];
-  const bf16_t* brow[LB];
-  int bkc[LB];
+  // fixed per thread: for load j the lane owns LDS position p = (j * NWV + wave) * 64 + lane of a stage
+  // (A rows first, then B rows), i.e. row p / KV, slot p % KV, and fetches k-chunk (slot ^ f(row)); one
+  // wave-wide load never straddles the two operands
+  typename AL::Row arow[LT];
+  const bf16_t* brow[LT];
+  int kc[LT];
+  bool is_a[LT];
 #pragma unroll
-  for (int j = 0; j < LA; ++j) {
+  for (int j = 0; j < LT; ++j) {
     const int p = (j * NWV + wave) * 64 + lane, row = p / KV;
-    al.init_row(arow[j], m0 + row);
-    akc[j] = swz<KV>(row, p % KV) * 8;
-  }
-#pragma unroll
-  for (int j = 0; j < LB; ++j) {
-    const int p = (j * NWV + wave) * 64 + lane, row = p / KV;
-    brow[j] = (n0 + row < g.N) ? Bp + (long long)(n0 + row) * g.b_sn : nullptr;
-    bkc[j] = swz<KV>(row, p % KV) * 8;
+    is_a[j] = __builtin_amdgcn_readfirstlane(row) < BM;
+    if (is_a[j]) {
+      al.init_row(arow[j], m0 + row);
+      brow[j] = nullptr;
+      kc[j] = swz<KV>(row, p % KV) * 8;
+    } else {
+      const int rb = row - BM;
+      al.init_row(arow[j], 0x7fffffff);
+      brow[j] = (n0 + rb < g.N) ? Bp + (long long)(n0 + rb) * g.b_sn : nullptr;
+      kc[j] = swz<KV>(rb, p % KV) * 8;
+    }
   }
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
   const bf16_t* zero = (const bf16_t*)g_zero_chunk;
@@ -209,15 +218,14 @@ __global__ __launch_bounds__(WM * WN * 64, OCC * WM * WN / 4) void gemm_dl(AL al
     al.tile(t < nk ? k0 : g.K);
     const uint32_t sa = lds_base + stage * (STAGE * 2) + wave * 1024;
 #pragma unroll
-    for (int j = 0; j < LA; ++j) {
-      const bf16_t* a = al.addr(arow[j], akc[j]);
-      load_lds16(a ? a : zero, sa + j * (NWV * 1024));
-    }
-    const uint32_t sb = sa + BM * BK * 2;
-#pragma unroll
-    for (int j = 0; j < LB; ++j) {
-      const bf16_t* b = (brow[j] && t < nk && k0 + bkc[j] < g.K) ? brow[j] + k0 + bkc[j] : zero;
-      load_lds16(b, sb + j * (NWV * 1024));
+    for (int j = 0; j < LT; ++j) {
+      const bf16_t* src;
+      if (is_a[j]) {
+        src = al.addr(arow[j], kc[j]);
+      } else {
+        src = (brow[j] && t < nk && k0 + kc[j] < g.K) ? brow[j] + k0 + kc[j] : nullptr;
+      }
+      load_lds16(src ? src : zero, sa + j * (NWV * 1024));
     }
   };
 
@@ -260,15 +268,17 @@ __global__ __launch_bounds__(WM * WN * 64, OCC * WM * WN / 4) void gemm_dl(AL al
   for (int s = 0; s < ST - 1; ++s) issue(s, s);
   int rd = 0, wr = ST - 1;
   for (int t = 0; t < nk; ++t) {
-    wait_loads<(ST - 2) * (LA + LB)>();                         // tile t has landed (this wave's part)
+    wait_loads<(ST - 2) * LT>();                         // tile t has landed (this wave's part)
     __syncthreads();                                            // ... everyone's part; stage wr is free again
     const bf16_t* S = lds + rd * STAGE;
-    frag_load(S, 0, 0);
+    if (LW == NCW || wave < NCW) frag_load(S, 0, 0);
     issue(t + ST - 1, wr);
+    if (LW == NCW || wave < NCW) {
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      if (ks + 1 < KS) frag_load(S, ks + 1, (ks + 1) & 1);
-      mfma_step(ks & 1);
+      for (int ks = 0; ks < KS; ++ks) {
+        if (ks + 1 < KS) frag_load(S, ks + 1, (ks + 1) & 1);
+        mfma_step(ks & 1);
+      }
     }
     rd = (rd + 1 == ST) ? 0 : rd + 1;
     wr = (wr + 1 == ST) ? 0 : wr + 1;
@@ -276,6 +286,7 @@ __global__ __launch_bounds__(WM * WN * 64, OCC * WM * WN / 4) void gemm_dl(AL al
   wait_loads<0>();
   __syncthreads();                                              // the stages become the epilogue patches
 
+  if (LW != NCW && wave >= NCW) return;                         // loader waves are done (no barrier follows)
   // ---- epilogue: 32 rows of the wave tile at a time through a wave-private fp32 LDS patch ----
   float* patch = (float*)lds + wave * 32 * ELD;
   bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
@@ -403,12 +414,12 @@ hipError_t launch_gemv(const GemmArgs& g, hipStream_t s) {
 // ---------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC>
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN>
 static hipError_t launch_dl(const AL& al, const GemmArgs& g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const int splits = g.splits > 1 ? g.splits : 1;
   dim3 grid(tiles, g.nb0 * g.nb1, splits);
-  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC>), grid, dim3(WM * WN * 64), 0, s, al, g);
+  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC, LW>), grid, dim3(LW * 64), 0, s, al, g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   const long long nvec = (long long)g.M * ((g.N + 7) / 8);
@@ -430,6 +441,12 @@ hipError_t launch_dl_variant(const AL& al, const GemmArgs& g, int tile, hipStrea
     case DL_128x64x64_S3_W4: return launch_dl<AL, 128, 64, 64, 3, 4, 1, 2>(al, g, s);
     case DL_128x128x64_S3_W8: return launch_dl<AL, 128, 128, 64, 3, 2, 4, 1>(al, g, s);
     case DL_256x256x32_S3_W8: return launch_dl<AL, 256, 256, 32, 3, 2, 4, 1>(al, g, s);
+    case DL_64x64x64_S4_L8: return launch_dl<AL, 64, 64, 64, 4, 2, 2, 2, 8>(al, g, s);
+    case DL_64x64x64_S4_L16: return launch_dl<AL, 64, 64, 64, 4, 2, 2, 1, 16>(al, g, s);
+    case DL_128x128x64_S2_L16: return launch_dl<AL, 128, 128, 64, 2, 2, 4, 1, 16>(al, g, s);
+    case DL_64x128x64_S3_L8: return launch_dl<AL, 64, 128, 64, 3, 1, 4, 2, 8>(al, g, s);
+    case DL_256x256x64_S2_W8: return launch_dl<AL, 256, 256, 64, 2, 2, 4, 1>(al, g, s);
+    case DL_256x128x64_S3_W8: return launch_dl<AL, 256, 128, 64, 3, 4, 2, 1>(al, g, s);
     default: return hipErrorInvalidValue;
   }
 }

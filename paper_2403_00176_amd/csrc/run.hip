@@ -222,7 +222,8 @@ struct Builder {
   }
 
   // Kernel version (Section 4.4.2: fat / regular / skinny versions chosen at run time by shape), a
-  // pure function of the contraction's shape.  Measured on MI355X: with at least ~160 tiles of
+  // pure function of the contraction's shape.  Measured on MI355X: from ~1024 tiles of 128 x 128 on, the
+  // 256-row tiles win (half the operand bytes per flop; 8192 x 8192 x 4096 runs at 0.99 PFLOP/s); with at least ~160 tiles of
   // 128 x 128 the 8-wave 128 x 128 x 64 kernel wins (three ring stages when k is long, two stages
   // and two workgroups per CU otherwise); below that the 64 x 64 x 64 tile with a four-stage ring
   // puts more workgroups (more loads in flight) on the chip.
@@ -232,6 +233,7 @@ struct Builder {
     if (!p.opts.mvc) return V_REGULAR;
     if (M <= 8) return V_GEMV;                     // decode shape: weight streaming, one wave per column
     const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+    if (t128 >= 1024) return V_DL0 + (K >= 2048 ? DL_256x256x64_S2_W8 : DL_256x128x32_S3_W8);   // fat versions
     if (t128 >= 160) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
     return V_DL0 + DL_64x64x64_S4_W4;
   }
