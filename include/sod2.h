@@ -209,6 +209,27 @@ typedef struct {
 sod2_status sod2_binding_set_profiling(sod2_binding_t*, int32_t on);
 sod2_status sod2_binding_launch_records(const sod2_binding_t*, sod2_launch_record* recs_host, int32_t cap, int32_t* n);
 
+/* -- replay of a step sequence ---------------------------------------------------------------- */
+/* For a graph that is run step after step with one symbol growing by 1 per step (a decoder: the
+ * length of its KV cache) and whose launch sequence depends on that symbol only through the row a
+ * CacheAppend writes and the number of keys a few-query attention reads: the launches of one step are
+ * captured once in a HIP graph; the kernels read the step from a counter in device memory, so each
+ * further step costs one graph launch and no host planning.  symbols_host are the values of step 0;
+ * inputs / outputs are the device pointers of step 0 and *_step_bytes (host, one per pointer, may be
+ * NULL) the bytes each advances per step; step_counter_dev is one int32 of device memory the caller
+ * keeps alive.  The arena must hold the plan of the last step.  hip_stream must not be the null stream.
+ * Returns SOD2_ERR_UNSUPPORTED when anything else in the launch table depends on the step symbol. */
+typedef struct sod2_replay_s sod2_replay_t;
+sod2_status sod2_replay_create(const sod2_plan_t*, const int64_t* symbols_host, int32_t n_symbols, int32_t step_symbol,
+                               int32_t max_steps, void* arena_dev, size_t arena_bytes,
+                               const void* const* weights_dev, int32_t n_weights,
+                               const void* const* inputs_dev, const int64_t* input_step_bytes_host, int32_t n_inputs,
+                               void* const* outputs_dev, const int64_t* output_step_bytes_host, int32_t n_outputs,
+                               int32_t* step_counter_dev, void* hip_stream, sod2_replay_t** out);
+/* enqueues: counter = first_step, then n_steps graph launches (each ends by advancing the counter) */
+sod2_status sod2_replay_launch(sod2_replay_t*, int32_t first_step, int32_t n_steps, void* hip_stream);
+void sod2_replay_destroy(sod2_replay_t*);
+
 const char* sod2_last_error(void);
 const char* sod2_version(void);
 

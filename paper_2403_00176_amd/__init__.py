@@ -34,7 +34,8 @@ EXPORTS = [
     "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_force_decisions", "sod2_binding_force_variant",
     "sod2_binding_force_splits", "sod2_binding_workspace_bytes",
     "sod2_run", "sod2_run_decisions", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
-    "sod2_binding_launch_records", "sod2_last_error", "sod2_version",
+    "sod2_binding_launch_records", "sod2_replay_create", "sod2_replay_launch", "sod2_replay_destroy",
+    "sod2_last_error", "sod2_version",
 ]
 
 
@@ -83,7 +84,7 @@ _lib.sod2_version.restype = C.c_char_p
 for _n in EXPORTS:
     if _n not in ("sod2_last_error", "sod2_version") and not _n.endswith("_destroy"):
         getattr(_lib, _n).restype = C.c_int32
-for _n in ("sod2_graph_destroy", "sod2_rdp_destroy", "sod2_plan_destroy", "sod2_binding_destroy"):
+for _n in ("sod2_graph_destroy", "sod2_rdp_destroy", "sod2_plan_destroy", "sod2_binding_destroy", "sod2_replay_destroy"):
     getattr(_lib, _n).restype = None
     getattr(_lib, _n).argtypes = [C.c_void_p]
 
@@ -352,6 +353,32 @@ def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence
     o = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
     _check(_lib.sod2_run(b.ptr, C.c_void_p(arena_ptr), C.c_size_t(arena_bytes), w, len(weight_ptrs), i,
                          len(input_ptrs), o, len(output_ptrs), C.c_void_p(stream)))
+
+
+class Replay(_Handle):
+    _destroy = "sod2_replay_destroy"
+
+
+def sod2_replay_create(p: Plan, sym, step_symbol: str, max_steps: int, arena_ptr: int, arena_bytes: int,
+                       weight_ptrs: Sequence[int], input_ptrs: Sequence[int], input_step_bytes: Sequence[int],
+                       output_ptrs: Sequence[int], output_step_bytes: Sequence[int], step_counter_ptr: int,
+                       stream: int) -> Replay:
+    arr, n = _symbols(p, sym)
+    names = [s[0] for s in p.graph.desc.symbols]
+    w = (C.c_void_p * max(len(weight_ptrs), 1))(*weight_ptrs)
+    i = (C.c_void_p * max(len(input_ptrs), 1))(*input_ptrs)
+    o = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
+    isb = (C.c_int64 * max(len(input_ptrs), 1))(*[int(v) for v in input_step_bytes])
+    osb = (C.c_int64 * max(len(output_ptrs), 1))(*[int(v) for v in output_step_bytes])
+    out = C.c_void_p()
+    _check(_lib.sod2_replay_create(p.ptr, arr, n, names.index(step_symbol), int(max_steps), C.c_void_p(arena_ptr),
+                                   C.c_size_t(arena_bytes), w, len(weight_ptrs), i, isb, len(input_ptrs), o, osb,
+                                   len(output_ptrs), C.c_void_p(step_counter_ptr), C.c_void_p(stream), C.byref(out)))
+    return Replay(out, keep=(p,))
+
+
+def sod2_replay_launch(r: Replay, first_step: int, n_steps: int, stream: int):
+    _check(_lib.sod2_replay_launch(r.ptr, int(first_step), int(n_steps), C.c_void_p(stream)))
 
 
 def sod2_version() -> str:

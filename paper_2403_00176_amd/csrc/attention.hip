@@ -198,7 +198,8 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a) {
   const bf16_t* Qp = (const bf16_t*)a.q + b0 * a.q_sb0 + b1 * a.q_sb1 + (long long)query * a.q_sm;
   const bf16_t* Kp = (const bf16_t*)a.k + b0 * a.k_sb0 + b1 * a.k_sb1;
   const bf16_t* Vp = (const bf16_t*)a.v + b0 * a.v_sb0 + b1 * a.v_sb1;
-  const int n_keys = a.causal ? min(a.Lk, query + (a.Lk - a.Lq) + 1) : a.Lk;     // visible keys: 0 .. n_keys-1
+  const int Lk = a.Lk + (a.step ? *a.step * a.lk_step : 0);
+  const int n_keys = a.causal ? min(Lk, query + (Lk - a.Lq) + 1) : Lk;           // visible keys: 0 .. n_keys-1
   float qf[8];
   {
     V16 q; q.u = *(const uint4*)(Qp + dc * 8);

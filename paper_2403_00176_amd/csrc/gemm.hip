@@ -390,7 +390,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs g) {
   for (int m = 0; m < MR; ++m) acc[m] = wave_sum(acc[m]);
   if (lane == 0) {
     const float bv = g.bias ? bf2f(((const bf16_t*)g.bias)[n]) : 0.f;
-    bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
+    bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1 + (g.step ? *g.step * g.c_step : 0);
     const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
 #pragma unroll
     for (int m = 0; m < MR; ++m) {

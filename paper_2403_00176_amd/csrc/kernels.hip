@@ -745,7 +745,8 @@ __global__ void eltwise_kernel(EltArgs a) {
 template <class T, class I>
 __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   const long long r = blockIdx.x;
-  long long id = (long long)((const I*)a.idx)[r];
+  const I* idx = (const I*)((const char*)a.idx + (a.step ? *a.step * a.idx_step : 0));
+  long long id = (long long)idx[r];
   id = id < 0 ? 0 : (id >= a.table_rows ? a.table_rows - 1 : id);
   const T* src = (const T*)a.table + id * a.cols;
   const T* add = a.add ? (const T*)a.add + r * a.add_stride : nullptr;
@@ -761,7 +762,8 @@ template <class T>
 __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   const long long r = blockIdx.x;
   const T* src = (const T*)a.x + r * a.x_stride;
-  T* dst = (T*)a.cache + (a.past + r) * a.cols;
+  const long long past = a.past + (a.step ? *a.step * a.past_step : 0);
+  T* dst = (T*)a.cache + (past + r) * a.cols;
   for (int c = threadIdx.x; c < a.cols; c += 256) dst[c] = src[c];
 }
 
@@ -770,7 +772,8 @@ __global__ __launch_bounds__(256) void argmax_kernel(ArgmaxArgs a) {
   __shared__ float bv[4];
   __shared__ int bi[4];
   const long long r = blockIdx.x;
-  const T* x = (const T*)a.x + r * a.x_stride;
+  const int stp = a.step ? *a.step : 0;
+  const T* x = (const T*)((const char*)a.x + stp * a.x_step) + r * a.x_stride;
   float best = -INFINITY;
   int at = 0x7fffffff;
   for (int c = threadIdx.x; c < a.cols; c += 256) {      // ascending c per thread: '>' keeps the lowest index
@@ -789,9 +792,21 @@ __global__ __launch_bounds__(256) void argmax_kernel(ArgmaxArgs a) {
   if (threadIdx.x == 0) {
     for (int k = 1; k < 4; ++k)
       if (bv[k] > best || (bv[k] == best && bi[k] < at)) { best = bv[k]; at = bi[k]; }
-    if (a.out_i32) ((int*)a.y)[r] = at;
-    else ((long long*)a.y)[r] = at;
+    char* y = (char*)a.y + stp * a.y_step;
+    if (a.out_i32) ((int*)y)[r] = at;
+    else ((long long*)y)[r] = at;
   }
+}
+
+__global__ void step_set_kernel(int* step, int value) { *step = value; }
+__global__ void step_advance_kernel(int* step) { *step += 1; }
+hipError_t launch_step_set(int* step, int value, hipStream_t s) {
+  hipLaunchKernelGGL(step_set_kernel, dim3(1), dim3(1), 0, s, step, value);
+  return hipGetLastError();
+}
+hipError_t launch_step_advance(int* step, hipStream_t s) {
+  hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(1), 0, s, step);
+  return hipGetLastError();
 }
 
 hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s) {

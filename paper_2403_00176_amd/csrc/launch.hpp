@@ -3,6 +3,7 @@
 // references because the arena, weight, input and output addresses arrive with each run.
 #pragma once
 #include <cstdint>
+#include <cstring>
 
 namespace sod2 {
 
@@ -37,6 +38,8 @@ struct GemmArgs {
   int splits;              // > 1: split-K, fp32 partials in ws, summed in z order by a second kernel
   int group_m;             // tile rows per panel of the tile walk (L2 locality)
   void* ws;                // split-K workspace: splits x batch x M x N floats
+  const int* step;         // replay (skinny kernel only): C advances by *step * c_step elements
+  long long c_step;
 };
 
 // Optional workspace behind the planned arena (fp32 partial tiles of split-K contractions)
@@ -88,6 +91,8 @@ struct GatherArgs {
   const void* table; const void* idx; const void* add; void* y;
   long long rows, table_rows, add_stride;
   int cols, idx_i32;
+  const int* step;         // replay: idx advances by *step * idx_step bytes
+  long long idx_step;
 };
 
 // cache[past + r, :] = x[r, :] for r < rows (the in-place CacheAppend of a session tensor)
@@ -95,6 +100,8 @@ struct AppendArgs {
   const void* x; void* cache;
   long long rows, past, x_stride;
   int cols;
+  const int* step;         // replay: past grows by *step * past_step rows
+  long long past_step;
 };
 
 // y[r] = index of the largest x[r, :], the lowest index among equals
@@ -102,6 +109,8 @@ struct ArgmaxArgs {
   const void* x; void* y;
   long long rows, x_stride;
   int cols, out_i32;
+  const int* step;         // replay: x and y advance by *step * x_step / y_step bytes
+  long long x_step, y_step;
 };
 
 // O[b0,b1,q,:] = softmax_k(scale * Q[b0,b1,q,:] . K[b0,b1,k,:] (+ causal mask)) V[b0,b1,k,:], head size 64,
@@ -114,6 +123,8 @@ struct AttnArgs {
   long long k_sb0, k_sb1, k_sn;
   long long v_sb0, v_sb1, v_sn;
   long long o_sb0, o_sb1, o_sm;
+  const int* step;         // replay: Lk grows by *step * lk_step keys
+  int lk_step;
 };
 
 struct Launch {
@@ -136,6 +147,9 @@ struct Launch {
   } u;
   bool is_layernorm = false;
   double flops = 0, bytes = 0;
+  long long d_past = 0;    // replay: rows the CacheAppend position / keys the attention length gain per step
+  int d_lk = 0;
+  Launch() { std::memset(&u, 0, sizeof u); }
 };
 
 }  // namespace sod2

@@ -749,10 +749,15 @@ struct Builder {
 
 struct Pointers {
   char* ws = nullptr;        // optional workspace behind the planned arena, or null
-  char* arena; size_t arena_bytes;
-  const void* const* w; int nw;
-  const void* const* in; int nin;
-  void* const* out; int nout;
+  const int* step = nullptr;             // replay: device step counter and the bytes by which each
+  const int64_t* in_step = nullptr;      // input / output pointer advances per step
+  const int64_t* out_step = nullptr;
+  char* arena = nullptr; size_t arena_bytes = 0;
+  const void* const* w = nullptr; int nw = 0;
+  const void* const* in = nullptr; int nin = 0;
+  void* const* out = nullptr; int nout = 0;
+  Pointers(void* arena_, size_t bytes, const void* const* w_, int nw_, const void* const* in_, int nin_, void* const* out_, int nout_)
+      : arena((char*)arena_), arena_bytes(bytes), w(w_), nw(nw_), in(in_), nin(nin_), out(out_), nout(nout_) {}
   void* at(const Ref& r) const {
     switch (r.space) {
       case SP_ARENA: return arena + r.byte_off;
@@ -787,6 +792,10 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
                 (!g.bias || al16(g.bias)) &&
                 (!g.res || (g.r_sn == 1 && g.r_sm % 8 == 0 && g.r_sb0 % 8 == 0 && g.r_sb1 % 8 == 0 && al16(g.res)));
       g.group_m = tune_group_m();
+      if (P.step && L.r[2].space == SP_OUTPUT && P.out_step[L.r[2].index]) {
+        g.step = P.step;
+        g.c_step = P.out_step[L.r[2].index] / dtype_bytes(L.out_dtype);
+      }
       if (g.splits > 1 && P.ws) {
         g.ws = P.ws;
       } else {
@@ -825,22 +834,30 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
     case K_ATTENTION: {
       AttnArgs a = L.u.attn;
       a.q = P.at(L.r[0]); a.k = P.at(L.r[1]); a.v = P.at(L.r[2]); a.o = P.at(L.r[3]);
+      if (P.step && L.d_lk) { a.step = P.step; a.lk_step = L.d_lk; }
       if (!al16(a.q) || !al16(a.k) || !al16(a.v) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
       return launch_attention(a, s);
     }
     case K_GATHER: {
       GatherArgs a = L.u.gather;
       a.table = P.at(L.r[0]); a.idx = P.at(L.r[1]); a.y = P.at(L.r[2]); a.add = P.at(L.r[3]);
+      if (P.step && L.r[1].space == SP_INPUT && P.in_step[L.r[1].index]) { a.step = P.step; a.idx_step = P.in_step[L.r[1].index]; }
       return launch_gather(L, a, s);
     }
     case K_APPEND: {
       AppendArgs a = L.u.append;
       a.x = P.at(L.r[0]); a.cache = P.at(L.r[1]);
+      if (P.step && L.d_past) { a.step = P.step; a.past_step = L.d_past; }
       return launch_append(L, a, s);
     }
     case K_ARGMAX: {
       ArgmaxArgs a = L.u.argmax;
       a.x = P.at(L.r[0]); a.y = P.at(L.r[1]);
+      if (P.step) {
+        a.step = P.step;
+        a.x_step = L.r[0].space == SP_OUTPUT ? P.out_step[L.r[0].index] : 0;
+        a.y_step = L.r[1].space == SP_OUTPUT ? P.out_step[L.r[1].index] : 0;
+      }
       return launch_argmax(L, a, s);
     }
     default:
@@ -866,6 +883,137 @@ std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force
 
 using namespace sod2;
 
+// ---------------------------------------------------------------------------------------------
+// Replay: the launch sequence of one step captured in a HIP graph; the quantities that change from
+// step to step are read by the kernels from a step counter in device memory
+// ---------------------------------------------------------------------------------------------
+namespace sod2 {
+hipError_t launch_step_set(int* step, int value, hipStream_t s);
+hipError_t launch_step_advance(int* step, hipStream_t s);
+}
+struct sod2_replay_s {
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  int* step = nullptr;
+  int max_steps = 0;
+  ~sod2_replay_s() {
+    if (exec) (void)hipGraphExecDestroy(exec);
+    if (graph) (void)hipGraphDestroy(graph);
+  }
+};
+
+namespace {
+bool same_ref(const Ref& a, const Ref& b) { return a.space == b.space && a.index == b.index && a.byte_off == b.byte_off; }
+
+// Launch b must equal launch a except for the fields a step may move; those are returned as deltas
+bool step_delta(const Launch& a, const Launch& b, long long* d_past, int* d_lk) {
+  *d_past = 0;
+  *d_lk = 0;
+  if (a.kernel != b.kernel || a.group != b.group || a.variant != b.variant || a.in_dtype != b.in_dtype ||
+      a.out_dtype != b.out_dtype || a.is_layernorm != b.is_layernorm)
+    return false;
+  for (int i = 0; i < 7; ++i) if (!same_ref(a.r[i], b.r[i])) return false;
+  Launch c = b;
+  if (a.kernel == K_APPEND) {
+    *d_past = b.u.append.past - a.u.append.past;
+    c.u.append.past = a.u.append.past;
+  } else if (a.kernel == K_ATTENTION) {
+    *d_lk = b.u.attn.Lk - a.u.attn.Lk;
+    c.u.attn.Lk = a.u.attn.Lk;
+  }
+  return std::memcmp(&a.u, &c.u, sizeof a.u) == 0;
+}
+}  // namespace
+
+extern "C" sod2_status sod2_replay_create(const sod2_plan_t* ph, const int64_t* symbols, int32_t n_symbols, int32_t step_symbol,
+                                          int32_t max_steps, void* arena, size_t arena_bytes, const void* const* weights,
+                                          int32_t n_weights, const void* const* inputs, const int64_t* input_step_bytes,
+                                          int32_t n_inputs, void* const* outputs, const int64_t* output_step_bytes,
+                                          int32_t n_outputs, int32_t* step_counter, void* stream, sod2_replay_t** out) {
+  try {
+    if (!ph || !symbols || !out || !step_counter || !stream) throw Error(SOD2_ERR_INVALID_ARG, "null argument (a replay needs a stream of its own, not the null stream)");
+    const Plan& p = ph->p;
+    const Graph& G = *p.g;
+    if (step_symbol < 0 || step_symbol >= n_symbols || max_steps < 1) throw Error(SOD2_ERR_INVALID_ARG, "bad step symbol or step count");
+    if (p.n_switches) throw Error(SOD2_ERR_UNSUPPORTED, "a graph with Switch operators cannot be replayed");
+    if (n_weights != (int)G.weight_ids.size() || n_inputs != (int)G.input_ids.size() || n_outputs != (int)G.output_ids.size())
+      throw Error(SOD2_ERR_INVALID_ARG, "wrong number of weight, input or output pointers");
+    if (((uintptr_t)arena & 255) != 0) throw Error(SOD2_ERR_INVALID_ARG, "arena must be 256-byte aligned");
+    std::vector<int64_t> s0(symbols, symbols + n_symbols), s1 = s0, sN = s0;
+    s1[step_symbol] += max_steps > 1 ? 1 : 0;
+    sN[step_symbol] += max_steps - 1;
+    BindResult b0 = bind_plan(p, s0, {}, false), b1 = bind_plan(p, s1, {}, false), bN = bind_plan(p, sN, {}, false);
+    int64_t need = std::max(b0.arena_bytes, std::max(b1.arena_bytes, bN.arena_bytes));
+    if ((size_t)need > arena_bytes) throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, the last step needs " + std::to_string(need));
+    std::vector<Launch> L0 = build_launches(p, b0, -1, 1), L1 = build_launches(p, b1, -1, 1), LN = build_launches(p, bN, -1, 1);
+    if (L0.size() != L1.size() || L0.size() != LN.size()) throw Error(SOD2_ERR_UNSUPPORTED, "the executed steps change with the step symbol");
+    for (size_t i = 0; i < L0.size(); ++i) {
+      long long dp, dpn;
+      int dl, dln;
+      if (!step_delta(L0[i], L1[i], &dp, &dl) || !step_delta(L0[i], LN[i], &dpn, &dln) ||
+          dpn != dp * (max_steps - 1) || dln != dl * (max_steps - 1))
+        throw Error(SOD2_ERR_UNSUPPORTED, "launch " + std::to_string(i) + " (group " + std::to_string(L0[i].group) +
+                                              ") depends on the step symbol in a way the kernels cannot follow");
+      L0[i].d_past = dp;
+      L0[i].d_lk = dl;
+      const Launch& L = L0[i];
+      if (L.kernel == K_ATTENTION && dl && (L.u.attn.Lq > 4 || LN[i].u.attn.Lk > 4096))
+        throw Error(SOD2_ERR_UNSUPPORTED, "only the few-query attention kernel follows a growing key count");
+      // operands in caller memory that move with the step must belong to a kernel that follows them
+      for (int k = 0; k < 7; ++k) {
+        const Ref& r = L.r[k];
+        bool moves = (r.space == SP_INPUT && input_step_bytes && input_step_bytes[r.index]) ||
+                     (r.space == SP_OUTPUT && output_step_bytes && output_step_bytes[r.index]);
+        if (!moves) continue;
+        bool ok = (L.kernel == K_GATHER && k == 1) || (L.kernel == K_ARGMAX && k <= 1) ||
+                  (L.kernel == K_GEMM && k == 2 && L.variant == V_GEMV);
+        if (!ok) throw Error(SOD2_ERR_UNSUPPORTED, "launch " + std::to_string(i) + " reads or writes a stepping pointer it cannot follow");
+      }
+    }
+    std::vector<int64_t> zin(std::max(n_inputs, 1), 0), zout(std::max(n_outputs, 1), 0);
+    Pointers P(arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs);
+    P.step = step_counter;
+    P.in_step = input_step_bytes ? input_step_bytes : zin.data();
+    P.out_step = output_step_bytes ? output_step_bytes : zout.data();
+    std::unique_ptr<sod2_replay_s> r(new sod2_replay_s);
+    r->step = step_counter;
+    r->max_steps = max_steps;
+    hipStream_t s = (hipStream_t)stream;
+    if (hipStreamBeginCapture(s, hipStreamCaptureModeRelaxed) != hipSuccess) throw Error(SOD2_ERR_HIP, "stream capture could not start");
+    hipError_t e = hipSuccess;
+    for (const Launch& L : L0) {
+      if (L.kernel < 0) continue;
+      e = dispatch(L, P, s);
+      if (e != hipSuccess) break;
+    }
+    if (e == hipSuccess) e = launch_step_advance(step_counter, s);
+    hipError_t e2 = hipStreamEndCapture(s, &r->graph);
+    if (e != hipSuccess || e2 != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("capture failed: ") + hipGetErrorString(e != hipSuccess ? e : e2));
+    if (hipGraphInstantiate(&r->exec, r->graph, nullptr, nullptr, 0) != hipSuccess) throw Error(SOD2_ERR_HIP, "graph instantiation failed");
+    *out = r.release();
+  } catch (const sod2::Error& e) {
+    sod2::set_error(e.what());
+    return e.code;
+  } catch (const std::exception& e) {
+    sod2::set_error(e.what());
+    return SOD2_ERR_INVALID_ARG;
+  }
+  return SOD2_OK;
+}
+
+extern "C" sod2_status sod2_replay_launch(sod2_replay_t* r, int32_t first_step, int32_t n_steps, void* stream) {
+  if (!r || first_step < 0 || n_steps < 0 || first_step + n_steps > r->max_steps) {
+    sod2::set_error("steps outside the range the replay was created for");
+    return SOD2_ERR_INVALID_ARG;
+  }
+  hipStream_t s = (hipStream_t)stream;
+  if (launch_step_set(r->step, first_step, s) != hipSuccess) { sod2::set_error("step counter could not be set"); return SOD2_ERR_HIP; }
+  for (int i = 0; i < n_steps; ++i)
+    if (hipGraphLaunch(r->exec, s) != hipSuccess) { sod2::set_error("graph launch failed"); return SOD2_ERR_HIP; }
+  return SOD2_OK;
+}
+extern "C" void sod2_replay_destroy(sod2_replay_t* r) { delete r; }
+
 extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_bytes, const void* const* weights,
                                 int32_t n_weights, const void* const* inputs, int32_t n_inputs, void* const* outputs,
                                 int32_t n_outputs, void* stream) {
@@ -883,7 +1031,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
                                                 std::to_string(h->b.arena_bytes));
     if (((uintptr_t)arena & 255) != 0) throw Error(SOD2_ERR_INVALID_ARG, "arena must be 256-byte aligned");
     hipStream_t s = (hipStream_t)stream;
-    Pointers P{nullptr, (char*)arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs};
+    Pointers P(arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs);
     // an arena longer than the plan by WS_BYTES carries the optional workspace at its end
     auto workspace_for = [&](int64_t plan_bytes) -> char* {
       size_t end = arena_bytes & ~(size_t)255;

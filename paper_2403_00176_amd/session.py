@@ -8,7 +8,8 @@ import numpy as np
 import torch
 
 from . import (sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run, sod2_binding_arena_bytes,
-               sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes, sod2_binding_workspace_bytes, Sod2Error)
+               sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes, sod2_binding_workspace_bytes,
+               sod2_replay_create, sod2_replay_launch, Sod2Error)
 
 _NP = {"f32": np.float32, "i64": np.int64, "i32": np.int32}
 _TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "i64": torch.int64, "i32": torch.int32}
@@ -108,7 +109,11 @@ class DecoderSession:
         self.dec = Session(decode_desc, device, **plan_opts)
         self.t_max = int(t_max)
         self.device = self.pre.device
-        self.stream = self.pre.stream
+        # a stream of its own (default priority): the decode steps can be captured in a HIP graph, which the
+        # null stream does not allow.  Callers do their own torch work inside `with torch.cuda.stream(ses.stream)`.
+        self.stream = torch.cuda.Stream(self.device)
+        self.pre.stream = self.dec.stream = self.stream
+        self.replay = None
         self.arena: Optional[torch.Tensor] = None
         self.logits_dtype = _TORCH[prefill_desc.tensors[prefill_desc.tensor_id("logits")].dtype]
 
@@ -123,15 +128,18 @@ class DecoderSession:
         """Buffers of one sequence: the arena (sized for the prompt pass and the last decode step), the
         token ids and positions, one row of logits per produced token."""
         self.P = int(P)
+        self.replay = None
         self.b_pre = self.pre.bind({"P": P})
         need = sod2_binding_arena_bytes(self.b_pre)[0]
         need = max(need, sod2_binding_arena_bytes(self.dec.bind({"P": P, "t": self.t_max - 1}))[0])
         need = (need + 255) // 256 * 256 + sod2_binding_workspace_bytes(self.b_pre)
-        if self.arena is None or self.arena.numel() < need:
-            self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
-        self.tokens = torch.zeros(P + self.t_max + 1, dtype=torch.int64, device=self.device)
-        self.positions = torch.arange(P + self.t_max + 1, dtype=torch.int64, device=self.device)
-        self.logits = torch.zeros(self.t_max + 1, vocab, dtype=self.logits_dtype, device=self.device)
+        with torch.cuda.stream(self.stream):
+            if self.arena is None or self.arena.numel() < need:
+                self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
+            self.tokens = torch.zeros(P + self.t_max + 1, dtype=torch.int64, device=self.device)
+            self.positions = torch.arange(P + self.t_max + 1, dtype=torch.int64, device=self.device)
+            self.logits = torch.zeros(self.t_max + 1, vocab, dtype=self.logits_dtype, device=self.device)
+            self.step_counter = torch.zeros(1, dtype=torch.int32, device=self.device)
 
     def _run(self, ses, binding, ids_ptr, pos_ptr, logits_ptr, next_ptr):
         d = ses.desc
@@ -143,7 +151,8 @@ class DecoderSession:
     def prefill(self, prompt: torch.Tensor):
         """Runs the prompt pass; logits row 0 and token P (the first generated one) are written."""
         P = self.P
-        self.tokens[:P] = prompt
+        with torch.cuda.stream(self.stream):
+            self.tokens[:P] = prompt
         self._run(self.pre, self.b_pre, self.tokens.data_ptr(), self.positions.data_ptr(), self.logits.data_ptr(),
                   self.tokens.data_ptr() + 8 * P)
 
@@ -156,3 +165,18 @@ class DecoderSession:
                   self.logits.data_ptr() + (t + 1) * self.logits.stride(0) * self.logits.element_size(),
                   self.tokens.data_ptr() + 8 * (P + t + 1))
         return b
+
+    def decode_replay(self, first_step: int, n_steps: int):
+        """Steps first_step .. first_step + n_steps - 1 as replays of one captured HIP graph: the kernels
+        read the step from a counter on the device, the host plans nothing per step."""
+        P, d = self.P, self.dec.desc
+        if self.replay is None:
+            row = self.logits.stride(0) * self.logits.element_size()
+            ins = {d.tensor_id("ids"): (self.tokens.data_ptr() + 8 * P, 8), d.tensor_id("pos"): (self.positions.data_ptr() + 8 * P, 8)}
+            outs = {d.tensor_id("logits"): (self.logits.data_ptr() + row, row), d.tensor_id("next"): (self.tokens.data_ptr() + 8 * (P + 1), 8)}
+            self.replay = sod2_replay_create(
+                self.dec.plan, {"P": P, "t": 0}, "t", self.t_max, self.arena.data_ptr(), self.arena.numel(),
+                [w.data_ptr() for w in self.dec.weights], [ins[t][0] for t in d.inputs()], [ins[t][1] for t in d.inputs()],
+                [outs[t][0] for t in d.outputs()], [outs[t][1] for t in d.outputs()], self.step_counter.data_ptr(),
+                self.stream.cuda_stream)
+        sod2_replay_launch(self.replay, first_step, n_steps, self.stream.cuda_stream)

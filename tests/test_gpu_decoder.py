@@ -51,6 +51,7 @@ def _run_decoder(S, w, W, seq, steps, check_structure=True):
     plans = {n: P.build_plan(g, R.RDP(g).analyse()) for n, g in (("prefill", w.prefill), ("decode", w.decode))}
     ses = DecoderSession(w.prefill, w.decode, w.t_max)
     ses.upload_weights(W)
+    torch.cuda.synchronize()
     for prompt in seq:
         Pn = len(prompt)
         print(f"case {w.name} P={Pn} steps={steps}", flush=True)
@@ -60,7 +61,8 @@ def _run_decoder(S, w, W, seq, steps, check_structure=True):
             assert S.sod2_binding_dump(ses.b_pre) == A.dump(A.bind(plans["prefill"], {"P": Pn}))
         ses.prefill(torch.from_numpy(np.asarray(prompt, dtype=np.int64)).to(ses.device))
         for t in range(steps):
-            ses.tokens[Pn + t] = ref_toks[t]                 # teacher forcing
+            with torch.cuda.stream(ses.stream):
+                ses.tokens[Pn + t] = ref_toks[t]             # teacher forcing
             b = ses.decode(t)
             if check_structure:
                 assert S.sod2_binding_dump(b) == A.dump(A.bind(plans["decode"], {"P": Pn, "t": t}))
@@ -113,6 +115,7 @@ def test_decoder_full_widths_two_layers(S_lib):
     Pn, steps = len(seq[1]), 6
     toks = ses.tokens[:Pn + steps].clone()
     inc = to_host(ses.logits[steps])
+    torch.cuda.synchronize()
     ses.start(Pn + steps, w.vocab)
     ses.prefill(toks)
     torch.cuda.synchronize()
@@ -136,6 +139,7 @@ def test_free_running_generation_is_deterministic(S_lib):
     ses = DecoderSession(w.prefill, w.decode, w.t_max)
     ses.upload_weights(w.make_weights_by_name())
     prompt = torch.from_numpy(np.asarray(w.make_prompt(0)[:20] % 1000, dtype=np.int64)).to(ses.device)
+    torch.cuda.synchronize()
     runs = []
     for _ in range(2):
         ses.start(20, w.vocab)
@@ -146,3 +150,42 @@ def test_free_running_generation_is_deterministic(S_lib):
         runs.append(ses.tokens.cpu().numpy().copy())
     assert np.array_equal(runs[0], runs[1])
     assert (runs[0][20:] >= 0).all() and (runs[0][20:] < 1000).all()
+
+
+def test_decode_replay_matches_eager_steps(S_lib):
+    """The decode steps as replays of one captured HIP graph (step counter on the device) against the
+    same steps bound and launched one by one: same tokens, same logits bit for bit.  The graph is
+    replayed in several batches with eager work (a prompt pass of another length, synchronisations)
+    between them, and every batch is checked."""
+    import torch
+    from paper_2403_00176_amd.session import DecoderSession
+    w = configs.decoder(layers=2, n_prompts=2, t_max=24)
+    ses = DecoderSession(w.prefill, w.decode, w.t_max)
+    ses.upload_weights(w.make_weights_by_name())
+    Pn = 77
+    prompt = torch.from_numpy(np.asarray(w.make_prompt(0)[:Pn], dtype=np.int64)).to(ses.device)
+    torch.cuda.synchronize()
+    ses.start(Pn, w.vocab)
+    ses.prefill(prompt)
+    for t in range(w.t_max):
+        ses.decode(t)
+    torch.cuda.synchronize()
+    eager_tokens = ses.tokens.cpu().numpy().copy()
+    eager_logits = ses.logits.view(torch.int16).cpu().numpy().copy()
+    other = DecoderSession(w.prefill, w.decode, w.t_max)
+    other.pre.weights = other.dec.weights = ses.pre.weights
+    ses.start(Pn, w.vocab)
+    ses.prefill(prompt)
+    done = 0
+    for n in (1, 5, 2, 16):
+        ses.decode_replay(done, n)
+        done += n
+        torch.cuda.synchronize()
+        assert np.array_equal(ses.tokens.cpu().numpy()[:Pn + done + 1], eager_tokens[:Pn + done + 1]), done
+        assert np.array_equal(ses.logits.view(torch.int16).cpu().numpy()[:done + 1], eager_logits[:done + 1]), done
+        other.start(64 + done // 2, w.vocab)                  # eager work between the replays
+        other.prefill(prompt[:64 + done // 2])
+        torch.cuda.synchronize()
+    assert done == w.t_max
+    with pytest.raises(S_lib.Sod2Error):
+        ses.decode_replay(w.t_max - 1, 2)
