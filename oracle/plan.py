@@ -29,6 +29,12 @@ R6  Attention: a GEMM group that is only MatMul [+ Mul by a host scalar], whose
     never materialised, Section 4.2's "fusion removes intermediate results").
     Only for bf16 tensors with a known head size of 64 (the size the one fused
     kernel of the library is written for).
+R7  LayerNorm as a prologue: a LAYERNORM group whose result is read by one
+    MatMul alone, as its first operand, joins that MatMul's GEMM group when the
+    normalised dim (= the contraction dim) is a known constant of at most 1024,
+    a multiple of 64, and everything is bf16: the contraction kernel normalises
+    its rows while they sit in on-chip memory, the LayerNorm result is never
+    materialised.
 """
 from __future__ import annotations
 
@@ -261,6 +267,36 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
                 del groups[gid]
             gid = min(members)
             groups[gid] = Group(gid, "ATTENTION", sorted(members), g2.out)
+            for m in members:
+                assigned[m] = gid
+
+    # R7: LayerNorm as the prologue of a contraction ------------------------------
+    if opts.fusion:
+        for n in order:
+            op = g.ops[n]
+            if op.kind != "LayerNorm" or n not in assigned or groups[assigned[n]].kind != "LAYERNORM":
+                continue
+            y = op.outputs[0]
+            c = sole_consumer(y)
+            if c is None or g.ops[c].kind != "MatMul" or g.ops[c].inputs[0] != y or g.ops[c].inputs[1] == y:
+                continue
+            gm = groups[assigned[c]]
+            if gm.kind != "GEMM" or min(gm.ops) != c:
+                continue
+            sx = rdp.S[op.inputs[0]]
+            tensors = list(op.inputs) + [y, g.ops[c].inputs[1], gm.out]
+            if any(g.tensors[t].dtype != "bf16" for t in tensors):
+                continue
+            if not (isinstance(sx, list) and sx and R.is_expr(sx[-1]) and sx[-1].is_const()):
+                continue
+            kdim = sx[-1].const_value()
+            if kdim > 1024 or kdim % 64 != 0:
+                continue
+            members = [n] + gm.ops
+            del groups[assigned[n]]
+            del groups[gm.gid]
+            gid = min(members)
+            groups[gid] = Group(gid, "GEMM", sorted(members), gm.out)
             for m in members:
                 assigned[m] = gid
 

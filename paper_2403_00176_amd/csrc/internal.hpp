@@ -132,6 +132,7 @@ struct Group {
   int gid = 0, kind = 0, out = -1;
   std::vector<int> ops;                            // sorted by operator id
   std::vector<int> chain;                          // members in absorption order (seed first)
+  int prologue = -1;                               // LayerNorm operator applied to the contraction's first operand, or -1
   std::vector<int> ins;                            // static bases read from outside
 };
 struct Item {

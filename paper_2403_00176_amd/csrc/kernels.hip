@@ -888,8 +888,10 @@ hipError_t launch_gemm_dl(const GemmArgs& g, int tile, hipStream_t s);
 hipError_t launch_conv_dl(const ConvArgs& c, const GemmArgs& g, int tile, hipStream_t s);
 
 hipError_t launch_gemv(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_ln(const GemmArgs& g, hipStream_t s);
 
 hipError_t launch_gemm(const Launch& L, const GemmArgs& g, hipStream_t s) {
+  if (g.ln_gamma) return L.in_dtype == SOD2_BF16_TAG ? launch_gemm_ln(g, s) : hipErrorInvalidValue;
   if (L.variant == V_GEMV && L.in_dtype == SOD2_BF16_TAG && g.a_vec && g.b_mode == 0 && g.M <= 8) return launch_gemv(g, s);
   if (L.variant >= V_DL0 && L.in_dtype == SOD2_BF16_TAG && g.a_vec && g.b_mode == 0)
     return launch_gemm_dl(g, L.variant - V_DL0, s);

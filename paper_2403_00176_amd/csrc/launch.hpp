@@ -17,7 +17,7 @@ struct Ref {
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
                   K_ARGMAX, K_ATTENTION };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
-enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };
+enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
 enum DlTile { DL_128x128x64_S3_W4 = 0, DL_128x128x64_S2_W4, DL_128x128x32_S3_W4, DL_128x128x64_S2_W8, DL_256x128x64_S2_W8,
               DL_256x128x32_S3_W8, DL_64x128x64_S3_W4, DL_64x64x64_S4_W4, DL_128x64x64_S3_W4, DL_128x128x64_S3_W8,
@@ -40,6 +40,9 @@ struct GemmArgs {
   void* ws;                // split-K workspace: splits x batch x M x N floats
   const int* step;         // replay (skinny kernel only): C advances by *step * c_step elements
   long long c_step;
+  const void* ln_gamma;    // LayerNorm prologue over the rows of A (all of K), or null
+  const void* ln_beta;
+  float ln_eps;
 };
 
 // Optional workspace behind the planned arena (fp32 partial tiles of split-K contractions)

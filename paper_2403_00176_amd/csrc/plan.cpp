@@ -234,6 +234,39 @@ void Plan::build() {
     }
   }
 
+  // R7: LayerNorm as the prologue of a contraction
+  if (opts.fusion) {
+    for (int n : order) {
+      const Op& op = G.ops[n];
+      if (op.kind != SOD2_OP_LAYERNORM || group_of_op[n] < 0 || groups[group_of_op[n]].kind != G_LAYERNORM) continue;
+      int y = op.out[0];
+      int c = sole_consumer(y);
+      if (c < 0 || G.ops[c].kind != SOD2_OP_MATMUL || G.ops[c].in[0] != y || G.ops[c].in[1] == y) continue;
+      const Group gm = groups[group_of_op[c]];
+      if (gm.kind != G_GEMM || gm.ops.front() != c) continue;
+      bool bf = true;
+      for (int t : op.in) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
+      for (int t : {y, G.ops[c].in[1], gm.out}) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
+      const LS& sx = R.S[op.in[0]];
+      if (!bf || !sx.is_list() || sx.d.empty() || !sx.d.back().val() || !sx.d.back().e.is_const()) continue;
+      int64_t kdim = sx.d.back().e.const_value();
+      if (kdim > 1024 || kdim % 64 != 0) continue;
+      Group gr;
+      gr.kind = G_GEMM;
+      gr.chain = gm.chain;                       // the contraction stays the seed; the LayerNorm is its prologue
+      gr.prologue = n;
+      gr.ops = gm.ops;
+      gr.ops.push_back(n);
+      std::sort(gr.ops.begin(), gr.ops.end());
+      gr.gid = gr.ops.front();
+      gr.out = gm.out;
+      groups.erase(group_of_op[n]);
+      groups.erase(gm.gid);
+      for (int m : gr.ops) group_of_op[m] = gr.gid;
+      groups[gr.gid] = gr;
+    }
+  }
+
   // static storage bases: views and Switch outputs alias their (data) input
   int nt = (int)G.tensors.size();
   sbase.resize(nt);

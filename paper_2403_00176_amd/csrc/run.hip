@@ -267,7 +267,9 @@ struct Builder {
     if (G.tensors[mm.in[1]].dtype != dt || G.tensors[gr.out].dtype != dt)
       throw Error(SOD2_ERR_UNSUPPORTED, "MatMul operands and result must share one float type");
     L.in_dtype = L.out_dtype = dt;
-    const View &va = view_of(mm.in[0]), &vb = view_of(mm.in[1]);
+    // with a LayerNorm prologue the first operand is the LayerNorm's input: its result has no storage
+    const Op* ln = gr.prologue >= 0 ? &G.ops[gr.prologue] : nullptr;
+    const View &va = view_of(ln ? ln->in[0] : mm.in[0]), &vb = view_of(mm.in[1]);
     bool tb = !mm.ia.empty() && mm.ia[0];
     size_t ra = va.dims.size(), rb = vb.dims.size();
     GemmArgs g{};
@@ -344,12 +346,24 @@ struct Builder {
     int64_t batch = (int64_t)g.nb0 * g.nb1;
     L.variant = pick_variant(dt, g.M, g.N, g.K, batch);
     g.splits = pick_splits(L.variant, g.M, g.N, g.K, batch);
+    if (ln) {
+      if (g.a_sk != 1 || g.K % 64 != 0 || g.K > 1024 || (g.M > 1 && g.a_sm % 8 != 0) || !tb || g.b_sk != 1)
+        throw Error(SOD2_ERR_UNSUPPORTED, "LayerNorm prologue needs dense k-contiguous operands and K a multiple of 64 up to 1024");
+      L.r[5] = ref_t(ln->in[1]);
+      L.r[6] = ref_t(ln->in[2]);
+      g.ln_eps = (float)ln->fa;
+      g.splits = 1;
+    }
     L.u.gemm = g;
     double eb = dtype_bytes(dt);
     L.flops = 2.0 * g.M * g.N * g.K * batch;
     double bcount = (bd[0].b || bd[1].b) ? (double)batch : ((bd[1].b || g.nb0 == 1) ? 1.0 : 1.0);
     L.bytes = eb * ((double)g.M * g.K * batch + (double)g.N * g.K * bcount + (double)g.M * g.N * batch * (e.res >= 0 ? 2 : 1) +
                     (e.bias >= 0 ? g.N : 0));
+    if (ln) {
+      L.flops += 8.0 * g.M * g.K * batch;
+      L.bytes += eb * 2.0 * g.K;
+    }
     return L;
   }
 
@@ -782,6 +796,8 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       GemmArgs g = L.u.gemm;
       g.A = P.at(L.r[0]); g.B = P.at(L.r[1]); g.C = P.at(L.r[2]);
       g.bias = P.at(L.r[3]); g.res = P.at(L.r[4]);
+      g.ln_gamma = P.at(L.r[5]); g.ln_beta = P.at(L.r[6]);
+      if (g.ln_gamma && (!al16(g.ln_gamma) || !al16(g.ln_beta))) return hipErrorInvalidValue;
       if (g.M == 1) { g.a_sm = g.K; g.c_sm = g.N; g.r_sm = g.N; }     // the stride of a single row carries no meaning
       g.a_vec = g.a_sk == 1 && g.K % 8 == 0 && g.a_sm % 8 == 0 && g.a_sb0 % 8 == 0 && g.a_sb1 % 8 == 0 && al16(g.A);
       bool bal = g.b_sb0 % 8 == 0 && g.b_sb1 % 8 == 0 && al16(g.B);
