@@ -31,10 +31,12 @@ R6  Attention: a GEMM group that is only MatMul [+ Mul by a host scalar], whose
     kernel of the library is written for).
 R7  LayerNorm as a prologue: a LAYERNORM group whose result is read by one
     MatMul alone, as its first operand, joins that MatMul's GEMM group when the
-    normalised dim (= the contraction dim) is a known constant of at most 1024,
-    a multiple of 64, and everything is bf16: the contraction kernel normalises
-    its rows while they sit in on-chip memory, the LayerNorm result is never
-    materialised.
+    row count is a known constant of at most 8 (the decode step: every wave of
+    the skinny contraction kernel can afford to normalise the few rows itself),
+    the normalised dim (= the contraction dim) is a known constant of at most
+    1024 and a multiple of 64, and everything is bf16.  The LayerNorm result is
+    never materialised.  (For many rows a fused version was measured slower
+    than the two kernels, so the rule stops at 8.)
 """
 from __future__ import annotations
 
@@ -287,10 +289,12 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             tensors = list(op.inputs) + [y, g.ops[c].inputs[1], gm.out]
             if any(g.tensors[t].dtype != "bf16" for t in tensors):
                 continue
-            if not (isinstance(sx, list) and sx and R.is_expr(sx[-1]) and sx[-1].is_const()):
+            if not (isinstance(sx, list) and sx and all(R.is_expr(d) and d.is_const() for d in sx)):
                 continue
-            kdim = sx[-1].const_value()
-            if kdim > 1024 or kdim % 64 != 0:
+            kdim, rows = sx[-1].const_value(), 1
+            for d in sx[:-1]:
+                rows *= d.const_value()
+            if kdim > 1024 or kdim % 64 != 0 or rows > 8:
                 continue
             members = [n] + gm.ops
             del groups[assigned[n]]

@@ -188,26 +188,37 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
   const int kt0 = blockIdx.z * per_split;
   const int nk = max(0, min(per_split, nk_all - kt0));
 
-  // fixed per thread: for load j the lane owns LDS position p = (j * NWV + wave) * 64 + lane of a stage
-  // (A rows first, then B rows), i.e. row p / KV, slot p % KV, and fetches k-chunk (slot ^ f(row)); one
-  // wave-wide load never straddles the two operands
-  typename AL::Row arow[LT];
-  const bf16_t* brow[LT];
+  // fixed per thread: load j moves the 16 bytes of LDS position p of a stage (A rows first, then B rows):
+  // row p / KV, slot p % KV, k-chunk (slot ^ f(row)).  When both operands divide evenly among the
+  // threads, loads 0 .. LA-1 are A and the rest B (decided at compile time); otherwise (more loader
+  // waves than one operand has 1 KB blocks) a wave-uniform flag tells which operand a load belongs to.
+  constexpr bool EVEN = (BM * KV) % NT == 0 && (BN * KV) % NT == 0;
+  constexpr int LA = EVEN ? BM * KV / NT : 0;
+  typename AL::Row arow[EVEN ? (LA > 0 ? LA : 1) : LT];
+  const bf16_t* brow[EVEN ? (LT - LA > 0 ? LT - LA : 1) : LT];
   int kc[LT];
   bool is_a[LT];
 #pragma unroll
   for (int j = 0; j < LT; ++j) {
-    const int p = (j * NWV + wave) * 64 + lane, row = p / KV;
-    is_a[j] = __builtin_amdgcn_readfirstlane(row) < BM;
-    if (is_a[j]) {
-      al.init_row(arow[j], m0 + row);
-      brow[j] = nullptr;
-      kc[j] = swz<KV>(row, p % KV) * 8;
+    int row, slot;
+    if (EVEN) {
+      is_a[j] = j < LA;
+      const int p = ((is_a[j] ? j : j - LA) * NWV + wave) * 64 + lane;
+      row = p / KV;
+      slot = p % KV;
     } else {
-      const int rb = row - BM;
-      al.init_row(arow[j], 0x7fffffff);
-      brow[j] = (n0 + rb < g.N) ? Bp + (long long)(n0 + rb) * g.b_sn : nullptr;
-      kc[j] = swz<KV>(rb, p % KV) * 8;
+      const int p = (j * NWV + wave) * 64 + lane;
+      is_a[j] = __builtin_amdgcn_readfirstlane(p / KV) < BM;
+      row = is_a[j] ? p / KV : p / KV - BM;
+      slot = p % KV;
+    }
+    kc[j] = swz<KV>(row, slot) * 8;
+    if (is_a[j]) {
+      al.init_row(arow[EVEN ? j : j], m0 + row);
+      if (!EVEN) brow[j] = nullptr;
+    } else {
+      if (!EVEN) al.init_row(arow[j], 0x7fffffff);
+      brow[EVEN ? j - LA : j] = (n0 + row < g.N) ? Bp + (long long)(n0 + row) * g.b_sn : nullptr;
     }
   }
   const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
@@ -223,9 +234,13 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
       if (is_a[j]) {
         src = al.addr(arow[j], kc[j]);
       } else {
-        src = (brow[j] && t < nk && k0 + kc[j] < g.K) ? brow[j] + k0 + kc[j] : nullptr;
+        const bf16_t* br = brow[EVEN ? j - LA : j];
+        src = (br && t < nk && k0 + kc[j] < g.K) ? br + k0 + kc[j] : nullptr;
       }
-      load_lds16(src ? src : zero, sa + j * (NWV * 1024));
+      // even split: the B region starts right after the A rows; uneven: one run of positions over both
+      const uint32_t dst = EVEN ? (is_a[j] ? sa + j * (NWV * 1024) : sa + BM * BK * 2 + (j - LA) * (NWV * 1024))
+                                : sa + j * (NWV * 1024);
+      load_lds16(src ? src : zero, dst);
     }
   };
 
@@ -354,203 +369,6 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs g, int splits) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Contraction with a LayerNorm prologue: C = epilogue(LayerNorm(A) * B^T), K <= KMAX, K % 64 == 0.
-// The whole BM x K panel of A is brought into LDS once (same direct loads, same swizzled k-tile
-// layout as a ring stage), each wave normalises its share of the rows in place (two passes over
-// the row in registers, biased variance, result rounded to bf16 exactly where the separate
-// LayerNorm kernel would round it), and the k loop then streams only B through the ring.  The
-// LayerNorm result never reaches memory.  Four compute waves (2 x 2, 32 x 64 each) and four more
-// that only load.
-// ---------------------------------------------------------------------------------------------
-template <int BM, int BN, int KMAX, int ST>
-__global__ __launch_bounds__(512, 1) void gemm_ln(GemmArgs g) {
-  constexpr int BK = 64, KV = 8, NWV = 8, NT = 512, NCW = 4, WN = 2, TM = BM / 64, TN = BN / 64;
-  constexpr int NKT = KMAX / BK;
-  constexpr int ASZ = NKT * BM * BK, BST = BN * BK;            // bf16 elements: A panel, one B stage
-  constexpr int LB = BN * KV / NT;                              // B loads per thread per k-tile
-  constexpr int EW = TN * 32, ELD = EW + 4;
-  static_assert(TM >= 1 && TN >= 1 && LB >= 1 && NCW * 32 * ELD * 2 <= ASZ && (ASZ + ST * BST) * 2 <= 160 * 1024, "tile shape");
-  __shared__ __attribute__((aligned(16))) bf16_t lds[ASZ + ST * BST];
-
-  const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wm = wave / WN, wn = wave % WN;                     // meaningful for wave < NCW
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  const int nblk = tiles_m * tiles_n;
-  int lid;
-  {
-    const int b = blockIdx.x, q = nblk >> 3, r = nblk & 7, x = b & 7;
-    lid = x * q + min(x, r) + (b >> 3);
-  }
-  int tm, tn;
-  {
-    const int gm = g.group_m, per = gm * tiles_n;
-    const int panel = lid / per, rem = lid - panel * per;
-    const int pm0 = panel * gm, w = min(gm, tiles_m - pm0);
-    tm = pm0 + rem % w;
-    tn = rem / w;
-  }
-  const int b0 = blockIdx.y / g.nb1, b1 = blockIdx.y % g.nb1;
-  const int m0 = tm * BM, n0 = tn * BN;
-  const bf16_t* Ap = (const bf16_t*)g.A + b0 * g.a_sb0 + b1 * g.a_sb1;
-  const bf16_t* Bp = (const bf16_t*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
-  const int nk = g.K / BK;
-  const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)lds;
-  const bf16_t* zero = (const bf16_t*)g_zero_chunk;
-
-  // ---- A panel: position p = kt * (BM * 8) + row * 8 + slot, 64 consecutive positions per wave load ----
-  const int a_loads = nk * BM * KV / NT;                        // per thread (nk * BM * 8 is a multiple of 512)
-  for (int j = 0; j < a_loads; ++j) {
-    const int p = (j * NWV + wave) * 64 + lane;
-    const int kt = p / (BM * KV), row = (p / KV) % BM, c = swz<KV>(row, p % KV);
-    const bf16_t* src = (m0 + row < g.M) ? Ap + (long long)(m0 + row) * g.a_sm + kt * BK + c * 8 : zero;
-    load_lds16(src, lds_base + (j * NWV + wave) * 1024);
-  }
-  // ---- B ring ----
-  const bf16_t* brow[LB];
-  int bkc[LB];
-#pragma unroll
-  for (int j = 0; j < LB; ++j) {
-    const int p = (j * NWV + wave) * 64 + lane, row = p / KV;
-    brow[j] = (n0 + row < g.N) ? Bp + (long long)(n0 + row) * g.b_sn : nullptr;
-    bkc[j] = swz<KV>(row, p % KV) * 8;
-  }
-  auto issue_b = [&](int t, int stage) {
-    const uint32_t sb = lds_base + (ASZ + stage * BST) * 2 + wave * 1024;
-#pragma unroll
-    for (int j = 0; j < LB; ++j) {
-      const bf16_t* b = (brow[j] && t < nk) ? brow[j] + t * BK + bkc[j] : zero;
-      load_lds16(b, sb + j * (NWV * 1024));
-    }
-  };
-#pragma unroll
-  for (int s = 0; s < ST - 1; ++s) issue_b(s, s);
-  wait_loads<(ST - 1) * LB>();                                  // the A panel (issued first) has landed
-  __syncthreads();
-
-  // ---- LayerNorm of the panel rows, in place: wave w takes rows w, w + 8, ...; a lane owns the 16-byte
-  //      chunks lane and lane + 64 of a row ----
-  {
-    const bf16_t* gam = (const bf16_t*)g.ln_gamma;
-    const bf16_t* bet = (const bf16_t*)g.ln_beta;
-    const int nch = g.K / 8;
-    float gm_[2][8], bt_[2][8];
-#pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int q = lane + h * 64;
-      V16 gv, bv;
-      gv.u = q < nch ? *(const uint4*)(gam + q * 8) : zero4();
-      bv.u = q < nch ? *(const uint4*)(bet + q * 8) : zero4();
-#pragma unroll
-      for (int e = 0; e < 8; ++e) { gm_[h][e] = bf2f(gv.h[e]); bt_[h][e] = bf2f(bv.h[e]); }
-    }
-    for (int row = wave; row < BM; row += NWV) {
-      if (m0 + row >= g.M) break;                               // rows are in order: the rest is outside too
-      float x[2][8];
-      int at[2];
-      float sum = 0.f;
-#pragma unroll
-      for (int h = 0; h < 2; ++h) {
-        const int q = lane + h * 64;
-        at[h] = (q / KV) * (BM * BK) + row * BK + swz<KV>(row, q % KV) * 8;
-        V16 v;
-        v.u = q < nch ? *(const uint4*)&lds[at[h]] : zero4();
-#pragma unroll
-        for (int e = 0; e < 8; ++e) { x[h][e] = bf2f(v.h[e]); sum += x[h][e]; }
-      }
-      const float mean = wave_sum(sum) / g.K;
-      float ss = 0.f;
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-        if (lane + h * 64 < nch)
-#pragma unroll
-          for (int e = 0; e < 8; ++e) { const float d = x[h][e] - mean; ss += d * d; }
-      const float rstd = rsqrtf(wave_sum(ss) / g.K + g.ln_eps);
-#pragma unroll
-      for (int h = 0; h < 2; ++h)
-        if (lane + h * 64 < nch) {
-          V16 o;
-#pragma unroll
-          for (int e = 0; e < 8; ++e) o.h[e] = f2bf((x[h][e] - mean) * rstd * gm_[h][e] + bt_[h][e]);
-          *(uint4*)&lds[at[h]] = o.u;
-        }
-    }
-  }
-  __syncthreads();
-
-  // ---- k loop: A fragments from the panel, B through the ring ----
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-  const int frow = lane & 31, fchunk = lane >> 5;
-  int fslot[4];
-#pragma unroll
-  for (int ks = 0; ks < 4; ++ks) fslot[ks] = swz<KV>(frow, ks * 2 + fchunk) * 8;
-  const int a_off = (wm * TM * 32 + frow) * BK, b_off = (wn * TN * 32 + frow) * BK;
-  V16 af[2][TM], bf[2][TN];
-  int rd = 0, wr = ST - 1;
-  for (int t = 0; t < nk; ++t) {
-    wait_loads<(ST - 2) * LB>();
-    __syncthreads();
-    const bf16_t* As = lds + t * (BM * BK);
-    const bf16_t* Bs = lds + ASZ + rd * BST;
-    auto frag_load = [&](int ks, int buf) {
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[buf][i].u = *(const uint4*)&As[a_off + i * 32 * BK + fslot[ks]];
-#pragma unroll
-      for (int j = 0; j < TN; ++j) bf[buf][j].u = *(const uint4*)&Bs[b_off + j * 32 * BK + fslot[ks]];
-    };
-    if (wave < NCW) frag_load(0, 0);
-    issue_b(t + ST - 1, wr);
-    if (wave < NCW) {
-#pragma unroll
-      for (int ks = 0; ks < 4; ++ks) {
-        if (ks + 1 < 4) frag_load(ks + 1, (ks + 1) & 1);
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-          for (int j = 0; j < TN; ++j)
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[ks & 1][i].b, bf[ks & 1][j].b, acc[i][j], 0, 0, 0);
-      }
-    }
-    rd = (rd + 1 == ST) ? 0 : rd + 1;
-    wr = (wr + 1 == ST) ? 0 : wr + 1;
-  }
-  wait_loads<0>();
-  __syncthreads();
-  if (wave >= NCW) return;
-
-  // ---- epilogue (patches where the A panel was) ----
-  float* patch = (float*)lds + wave * 32 * ELD;
-  bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
-  const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
-  const int colw = n0 + wn * EW;
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        patch[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * ELD + j * 32 + (lane & 31)] = acc[i][j][r];
-    const int roww = m0 + wm * TM * 32 + i * 32;
-#pragma unroll 1
-    for (int q = 0; q < 32 * EW / 8 / 64; ++q) {
-      const int v = lane + q * 64;
-      const int rr = v / (EW / 8), cc = (v % (EW / 8)) * 8;
-      const int row = roww + rr, col = colw + cc;
-      if (row >= g.M || col >= g.N) continue;
-      float x[8];
-      const float4 p0 = *(const float4*)&patch[rr * ELD + cc], p1 = *(const float4*)&patch[rr * ELD + cc + 4];
-      x[0] = p0.x; x[1] = p0.y; x[2] = p0.z; x[3] = p0.w; x[4] = p1.x; x[5] = p1.y; x[6] = p1.z; x[7] = p1.w;
-      epilogue8(x, g, Cp, Rp, row, col);
-    }
-  }
-}
-
 // M <= 8 with a LayerNorm prologue (K <= 1024): every wave normalises the few rows in registers
 // (a lane owns chunks lane and lane + 64 of each row), then streams its weight column
 template <int MR>
@@ -621,23 +439,13 @@ __global__ __launch_bounds__(256) void gemv_ln_kernel(GemmArgs g) {
   }
 }
 
-// LayerNorm-prologue contraction: needs k-contiguous 16-byte aligned operands, K % 64 == 0, K <= 1024
+// LayerNorm-prologue contraction (M <= 8): needs k-contiguous 16-byte aligned operands, K % 64 == 0, K <= 1024
 hipError_t launch_gemm_ln(const GemmArgs& g, hipStream_t s) {
-  if (!g.a_vec || g.b_mode != 0 || g.K % 64 != 0 || g.K > 1024 || g.a_sk != 1) return hipErrorInvalidValue;
-  if (g.M <= 8) {
-    dim3 grid((g.N + 3) / 4, g.nb0 * g.nb1);
-    if (g.M <= 1) hipLaunchKernelGGL(gemv_ln_kernel<1>, grid, dim3(256), 0, s, g);
-    else if (g.M <= 4) hipLaunchKernelGGL(gemv_ln_kernel<4>, grid, dim3(256), 0, s, g);
-    else hipLaunchKernelGGL(gemv_ln_kernel<8>, grid, dim3(256), 0, s, g);
-    return hipGetLastError();
-  }
-  if (g.K <= 768) {
-    dim3 grid(((g.M + 63) / 64) * ((g.N + 127) / 128), g.nb0 * g.nb1);
-    hipLaunchKernelGGL((gemm_ln<64, 128, 768, 3>), grid, dim3(512), 0, s, g);
-  } else {
-    dim3 grid(((g.M + 63) / 64) * ((g.N + 63) / 64), g.nb0 * g.nb1);
-    hipLaunchKernelGGL((gemm_ln<64, 64, 1024, 3>), grid, dim3(512), 0, s, g);
-  }
+  if (!g.a_vec || g.b_mode != 0 || g.K % 64 != 0 || g.K > 1024 || g.a_sk != 1 || g.M > 8) return hipErrorInvalidValue;
+  dim3 grid((g.N + 3) / 4, g.nb0 * g.nb1);
+  if (g.M <= 1) hipLaunchKernelGGL(gemv_ln_kernel<1>, grid, dim3(256), 0, s, g);
+  else if (g.M <= 4) hipLaunchKernelGGL(gemv_ln_kernel<4>, grid, dim3(256), 0, s, g);
+  else hipLaunchKernelGGL(gemv_ln_kernel<8>, grid, dim3(256), 0, s, g);
   return hipGetLastError();
 }
 

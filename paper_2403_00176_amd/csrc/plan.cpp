@@ -248,9 +248,13 @@ void Plan::build() {
       for (int t : op.in) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
       for (int t : {y, G.ops[c].in[1], gm.out}) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
       const LS& sx = R.S[op.in[0]];
-      if (!bf || !sx.is_list() || sx.d.empty() || !sx.d.back().val() || !sx.d.back().e.is_const()) continue;
-      int64_t kdim = sx.d.back().e.const_value();
-      if (kdim > 1024 || kdim % 64 != 0) continue;
+      if (!bf || !sx.is_list() || sx.d.empty()) continue;
+      bool known = true;
+      for (const auto& d : sx.d) if (!d.val() || !d.e.is_const()) known = false;
+      if (!known) continue;
+      int64_t kdim = sx.d.back().e.const_value(), rows = 1;
+      for (size_t i = 0; i + 1 < sx.d.size(); ++i) rows *= sx.d[i].e.const_value();
+      if (kdim > 1024 || kdim % 64 != 0 || rows > 8) continue;
       Group gr;
       gr.kind = G_GEMM;
       gr.chain = gm.chain;                       // the contraction stays the seed; the LayerNorm is its prologue

@@ -349,6 +349,7 @@ struct Builder {
     if (ln) {
       if (g.a_sk != 1 || g.K % 64 != 0 || g.K > 1024 || (g.M > 1 && g.a_sm % 8 != 0) || !tb || g.b_sk != 1)
         throw Error(SOD2_ERR_UNSUPPORTED, "LayerNorm prologue needs dense k-contiguous operands and K a multiple of 64 up to 1024");
+      if (g.M > 8 || batch != 1) throw Error(SOD2_ERR_UNSUPPORTED, "LayerNorm prologue is for at most 8 rows");
       L.r[5] = ref_t(ln->in[1]);
       L.r[6] = ref_t(ln->in[2]);
       g.ln_eps = (float)ln->fa;
