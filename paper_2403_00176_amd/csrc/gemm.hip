@@ -269,7 +269,17 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
 #pragma unroll
     for (int j = 0; j < TN; ++j) bf[buf][j].u = *(const uint4*)&S[b_off + j * 32 * BK + fslot[ks]];
   };
-  auto mfma_step = [&](int buf) {
+  // a wave with a single 32 x 32 tile would issue a chain of dependent MFMAs: odd k-steps go to a second
+  // accumulator (added in once, after the k loop), so that two independent chains interleave
+  constexpr bool TWO_CHAINS = TM * TN == 1;
+  f32x16_t acc_odd;
+#pragma unroll
+  for (int r = 0; r < 16; ++r) acc_odd[r] = 0.f;
+  auto mfma_step = [&](int buf, int ks) {
+    if (TWO_CHAINS && (ks & 1)) {
+      acc_odd = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[buf][0].b, bf[buf][0].b, acc_odd, 0, 0, 0);
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -292,7 +302,7 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
         if (ks + 1 < KS) frag_load(S, ks + 1, (ks + 1) & 1);
-        mfma_step(ks & 1);
+        mfma_step(ks & 1, ks);
       }
     }
     rd = (rd + 1 == ST) ? 0 : rd + 1;
@@ -300,6 +310,10 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
   }
   wait_loads<0>();
   __syncthreads();                                              // the stages become the epilogue patches
+  if (TWO_CHAINS) {
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[0][0][r] += acc_odd[r];
+  }
 
   if (LW != NCW && wave >= NCW) return;                         // loader waves are done (no barrier follows)
   // ---- epilogue: 32 rows of the wave tile at a time through a wave-private fp32 LDS patch ----
