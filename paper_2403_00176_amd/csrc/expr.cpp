@@ -12,7 +12,8 @@ struct AtomDef { int kind; std::string sym; std::shared_ptr<Expr> inner; int64_t
 std::map<std::string, AtomDef>& atoms() { static std::map<std::string, AtomDef> a; return a; }
 std::mutex& atoms_mu() { static std::mutex m; return m; }
 
-AtomDef atom_of(const std::string& name) {
+// (entries are never erased and std::map nodes do not move: the reference stays valid)
+const AtomDef& atom_of(const std::string& name) {
   std::lock_guard<std::mutex> lk(atoms_mu());
   auto it = atoms().find(name);
   if (it == atoms().end()) throw Error(SOD2_ERR_INVALID_ARG, "unknown atom " + name);
@@ -149,7 +150,7 @@ int64_t Expr::eval(const std::map<std::string, int64_t>& env) const {
   for (const auto& t : terms) {
     int64_t v = t.second;
     for (const auto& a : t.first) {
-      AtomDef d = atom_of(a);
+      const AtomDef& d = atom_of(a);
       if (d.kind == 0) {
         auto it = env.find(d.sym);
         if (it == env.end()) throw Error(SOD2_ERR_INVALID_ARG, "symbol without a value: " + d.sym);
