@@ -145,9 +145,13 @@ def main():
     torch.cuda.synchronize()
     stream = ses.stream
 
+    enqueue_ms = []
+
     def one_call(sym, ins, outs, sync=True):
         b = ses.bind(sym)
+        t_run = time.perf_counter()
         ses.run(b, ins, outs)
+        enqueue_ms.append((time.perf_counter() - t_run) * 1e3)   # launch table + enqueue, host side
         if sync:
             stream.synchronize()
         return b
@@ -168,6 +172,7 @@ def main():
     # ---- timed region: exactly `steps` calls, each synchronised (a latency, not a pipelined rate)
     torch.cuda.synchronize()
     lat, arena_mb = [], []
+    del enqueue_ms[:]
     t_begin = time.perf_counter()
     for ci, sym, ins, outs in timed:
         t1 = time.perf_counter()
@@ -177,6 +182,7 @@ def main():
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_begin
     ms_per_step = total_s * 1e3 / len(timed)
+    run_enqueue_ms = sum(enqueue_ms) / len(enqueue_ms)
 
     # ---- same calls without the per-call synchronise (host planning overlaps the GPU)
     torch.cuda.synchronize()
@@ -292,6 +298,7 @@ def main():
         "latency_ms": {"mean": round(sum(lat) / len(lat), 4), "min": round(min(lat), 4), "max": round(max(lat), 4)},
         "pipelined_ms_per_step": round(pipelined_ms, 4),
         "bind_ms": round(bind_ms, 4),
+        "run_enqueue_ms": round(run_enqueue_ms, 4),
         "first_call_ms": round(first_call_ms, 3),
         "compile_once_ms": round(compile_ms, 2),
         "peak_arena_mb": {"min": round(min(arena_mb), 3), "max": round(max(arena_mb), 3),

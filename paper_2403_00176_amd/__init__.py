@@ -345,10 +345,16 @@ def sod2_run_decisions(b: Binding) -> List[int]:
     return list(arr[:n.value])
 
 
+def pointer_array(ptrs: Sequence[int]):
+    """Device addresses as the `const void* const*` argument of sod2_run (reusable across calls)."""
+    return (C.c_void_p * len(ptrs))(*ptrs)
+
+
 def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence[int], input_ptrs: Sequence[int],
              output_ptrs: Sequence[int], stream: int = 0):
-    """All pointers are raw device addresses (e.g. torch.Tensor.data_ptr()); stream is a hipStream_t value."""
-    w = (C.c_void_p * max(len(weight_ptrs), 1))(*weight_ptrs)
+    """All pointers are raw device addresses (e.g. torch.Tensor.data_ptr()); stream is a hipStream_t value.
+    weight_ptrs may be an array made once by pointer_array()."""
+    w = weight_ptrs if isinstance(weight_ptrs, C.Array) else pointer_array(weight_ptrs)
     i = (C.c_void_p * max(len(input_ptrs), 1))(*input_ptrs)
     o = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
     _check(_lib.sod2_run(b.ptr, C.c_void_p(arena_ptr), C.c_size_t(arena_bytes), w, len(weight_ptrs), i,

@@ -75,50 +75,54 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
     b.session_root[t] = t;
     b.session_bytes += nbytes;
   }
-  std::map<int, bool> group_dead;
-  std::map<int, std::pair<bool, int>> memo;       // tensor -> (dead, storage tensor)
+  p.xc.atom_values(symbols, &b.atom_vals);
+  const int nt = (int)G.tensors.size();
+  std::vector<char> group_dead(G.ops.size(), 0);   // by group id (= an operator id)
+  std::vector<signed char> memo_dead(nt, -1);       // tensor -> dead?  (-1: not computed yet)
+  std::vector<int> memo_base(nt, -1);               // tensor -> storage tensor
   size_t next_dec = 0;
 
-  std::function<std::pair<bool, int>(int)> info = [&](int t) -> std::pair<bool, int> {
-    auto it = memo.find(t);
-    if (it != memo.end()) return it->second;
-    std::pair<bool, int> r(false, t);
-    int pr = G.producer[t];
-    if (pr >= 0 && !p.folded[pr]) {
-      const Op& op = G.ops[pr];
-      if (op.kind == SOD2_OP_SWITCH) {
-        auto d = info(op.in[0]);
-        auto dec = b.decisions.find(pr);
-        bool is_skip_out = op.out.size() > 1 && op.out[1] == t;
-        bool taken = dec != b.decisions.end() && (is_skip_out == (dec->second != 0));
-        r = {d.first || dec == b.decisions.end() || !taken, d.second};
-      } else if (op.kind == SOD2_OP_COMBINE) {
-        r = {true, t};
-        for (int i : op.in) {
-          auto d = info(i);
-          if (!d.first) { r = {false, d.second}; break; }
+  struct Info {
+    const Plan& p; const Graph& G; BindResult& b;
+    std::vector<char>& group_dead; std::vector<signed char>& memo_dead; std::vector<int>& memo_base;
+    std::pair<bool, int> operator()(int t) {
+      if (memo_dead[t] >= 0) return {memo_dead[t] != 0, memo_base[t]};
+      std::pair<bool, int> r(false, t);
+      int pr = G.producer[t];
+      if (pr >= 0 && !p.folded[pr]) {
+        const Op& op = G.ops[pr];
+        if (op.kind == SOD2_OP_SWITCH) {
+          auto d = (*this)(op.in[0]);
+          auto dec = b.decisions.find(pr);
+          bool is_skip_out = op.out.size() > 1 && op.out[1] == t;
+          bool taken = dec != b.decisions.end() && (is_skip_out == (dec->second != 0));
+          r = {d.first || dec == b.decisions.end() || !taken, d.second};
+        } else if (op.kind == SOD2_OP_COMBINE) {
+          r = {true, t};
+          for (int i : op.in) {
+            auto d = (*this)(i);
+            if (!d.first) { r = {false, d.second}; break; }
+          }
+        } else if (p.view[pr]) {
+          r = (*this)(op.in[0]);
+        } else {
+          r = {group_dead[p.group_of_op[pr]] != 0, t};
         }
-      } else if (p.view[pr]) {
-        r = info(op.in[0]);
-      } else {
-        r = {group_dead.at(p.group_of_op[pr]), t};
       }
+      memo_dead[t] = r.first ? 1 : 0;
+      memo_base[t] = r.second;
+      return r;
     }
-    memo[t] = r;
-    return r;
-  };
+  } info{p, G, b, group_dead, memo_dead, memo_base};
 
-  std::map<int, int> reads_at;
+  std::vector<int> reads_at(nt, -1);
   for (size_t s = 0; s < p.subgraphs.size(); ++s) {
     for (int i : p.subgraphs[s]) {
       const Item& it = p.items[i];
       int step = (int)b.steps.size();
       if (it.is_group) {
         const Group& gr = p.groups.at(it.ref);
-        std::set<int> inside;
-        for (int n : gr.ops) for (int o : G.ops[n].out) inside.insert(o);
-        std::vector<int> ext;
-        for (int n : gr.ops) for (int t : G.ops[n].in) if (!inside.count(t)) ext.push_back(t);
+        const std::vector<int>& ext = p.item_ext[i];
         bool dead = false;
         for (int t : ext) if (info(t).first) dead = true;
         group_dead[gr.gid] = dead;
@@ -130,7 +134,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
           throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t].name + " is not resolved: " + sh.str());
         std::vector<int64_t> dims;
         int64_t n = dtype_bytes(G.tensors[t].dtype);
-        for (const auto& d : sh.d) { dims.push_back(d.e.eval(b.env)); n *= dims.back(); }
+        for (const CompiledExpr& d : p.cshape[t]) { dims.push_back(d.eval(b.atom_vals)); n *= dims.back(); }
         b.dims[t] = dims;
         if (gr.kind == G_CACHEAPPEND) {
           auto root = b.session_root.find(G.ops[gr.ops[0]].in[0]);
@@ -165,8 +169,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
     }
   }
   for (auto& kv : b.tensors) {
-    auto it = reads_at.find(kv.first);
-    kv.second.end = std::max(kv.second.start, it == reads_at.end() ? kv.second.start : it->second);
+    kv.second.end = std::max(kv.second.start, reads_at[kv.first]);
   }
   for (int t = 0; t < (int)G.tensors.size(); ++t) {
     int pr = G.producer[t];

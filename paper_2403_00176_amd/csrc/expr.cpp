@@ -165,6 +165,41 @@ int64_t Expr::eval(const std::map<std::string, int64_t>& env) const {
   return total;
 }
 
+// ---- flattened form ----------------------------------------------------------------------------
+int ExprCompiler::intern(const std::string& name) {
+  auto it = index.find(name);
+  if (it != index.end()) return it->second;
+  const AtomDef& d = atom_of(name);
+  Atom a{d.kind, -1, d.c, CompiledExpr()};
+  if (d.kind == 0) {
+    for (size_t i = 0; i < symbols.size(); ++i) if (symbols[i] == d.sym) a.sym = (int)i;
+    if (a.sym < 0) throw Error(SOD2_ERR_INVALID_ARG, "symbol without a declaration: " + d.sym);
+  } else {
+    a.inner = compile(*d.inner);                   // its atoms get smaller indices than this one
+  }
+  atoms.push_back(a);
+  index[name] = (int)atoms.size() - 1;
+  return (int)atoms.size() - 1;
+}
+CompiledExpr ExprCompiler::compile(const Expr& e) {
+  CompiledExpr c;
+  for (const auto& t : e.terms) {
+    CompiledExpr::Term ct{t.second, {}};
+    for (const auto& a : t.first) ct.atoms.push_back(intern(a));
+    c.terms.push_back(ct);
+  }
+  return c;
+}
+void ExprCompiler::atom_values(const std::vector<int64_t>& sv, std::vector<int64_t>* out) const {
+  out->assign(atoms.size(), 0);
+  for (size_t i = 0; i < atoms.size(); ++i) {
+    const Atom& a = atoms[i];
+    if (a.kind == 0) { (*out)[i] = sv[a.sym]; continue; }
+    int64_t inner = a.inner.eval(*out);
+    (*out)[i] = a.kind == 1 ? floor_div(inner, a.c) : floor_mod(inner, a.c);
+  }
+}
+
 // ---- lattice ----------------------------------------------------------------------------------
 LV meet(const LV& a, const LV& b) {
   if (a.k == LV::UNDEF) return b;

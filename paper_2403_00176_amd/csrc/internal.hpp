@@ -47,6 +47,32 @@ struct Expr {
   int64_t eval(const std::map<std::string, int64_t>& env) const;
 };
 
+// Expressions flattened for repeated evaluation at bind: atoms become indices into a table whose
+// values are computed once per binding (inner expressions of floordiv / mod before their users).
+struct CompiledExpr {
+  struct Term { int64_t coef; std::vector<int> atoms; };
+  std::vector<Term> terms;
+  int64_t eval(const std::vector<int64_t>& atom_vals) const {
+    int64_t total = 0;
+    for (const Term& t : terms) {
+      int64_t v = t.coef;
+      for (int a : t.atoms) v *= atom_vals[a];
+      total += v;
+    }
+    return total;
+  }
+};
+struct ExprCompiler {
+  struct Atom { int kind; int sym; int64_t c; CompiledExpr inner; };   // 0 symbol, 1 floordiv, 2 mod
+  std::vector<std::string> symbols;                // position = index of the value handed to atom_values
+  std::vector<Atom> atoms;
+  std::map<std::string, int> index;
+  CompiledExpr compile(const Expr& e);
+  void atom_values(const std::vector<int64_t>& symbol_values, std::vector<int64_t>* out) const;
+ private:
+  int intern(const std::string& atom_name);
+};
+
 // ---------------------------------------------------------------------------------------------
 // Lattice of Fig. 2: undef > {known, symbolic, operation-inferred constant} > nac
 // ---------------------------------------------------------------------------------------------
@@ -105,6 +131,7 @@ struct Graph {
   std::vector<std::vector<int>> consumers;         // per tensor
   std::vector<int> weight_ids, input_ids, output_ids;   // input_ids: inputs passed by pointer
   std::vector<int> session_ids;                        // session inputs (stored in the arena)
+  std::vector<int> weight_pos, input_pos, output_pos;  // per tensor: position in the lists above, or -1
   void finish();                                   // fills the derived fields, validates ids
   std::vector<int> sorted_nodes() const;           // reverse post-order of a depth-first walk
 };
@@ -153,6 +180,11 @@ struct Plan {
   std::vector<std::string> sg_class;
   std::vector<int> sbase;
   int n_switches = 0;
+  // flattened for bind: per tensor the compiled dims (empty when unresolved), per item the tensors a
+  // group reads from outside itself
+  ExprCompiler xc;
+  std::vector<std::vector<CompiledExpr>> cshape;
+  std::vector<std::vector<int>> item_ext;
   void build();
   std::string dump() const;
   bool arena_candidate(int t) const;
@@ -170,6 +202,7 @@ struct Layout {                                    // where an executed tensor l
 
 struct BindResult {
   std::map<std::string, int64_t> env;
+  std::vector<int64_t> atom_vals;                  // values of Plan::xc's atoms at the bound symbols
   std::vector<int> steps, step_sg;                 // executed item indices
   std::map<int, int> decisions;                    // Switch op id -> 1 when the skip output is taken
   std::vector<int> switch_order;                   // executed Switch operators in order

@@ -447,6 +447,22 @@ void Plan::build() {
     }
     subgraphs.push_back(seq);
   }
+
+  // flattened forms used by every bind
+  for (const Symbol& sy : G.symbols) xc.symbols.push_back(sy.name);
+  cshape.assign(nt, {});
+  for (int t = 0; t < nt; ++t) {
+    if (!R.S[t].resolved()) continue;
+    for (const LV& d : R.S[t].d) cshape[t].push_back(xc.compile(d.e));
+  }
+  item_ext.assign(items.size(), {});
+  for (size_t i = 0; i < items.size(); ++i) {
+    if (!items[i].is_group) continue;
+    const Group& gr = groups.at(items[i].ref);
+    std::set<int> inside;
+    for (int n : gr.ops) for (int o : G.ops[n].out) inside.insert(o);
+    for (int n : gr.ops) for (int t : G.ops[n].in) if (!inside.count(t)) item_ext[i].push_back(t);
+  }
 }
 
 std::string Plan::dump() const {

@@ -43,10 +43,13 @@ void Graph::finish() {
       consumers[t].push_back(i);
     }
   }
+  weight_pos.assign(nt, -1);
+  input_pos.assign(nt, -1);
+  output_pos.assign(nt, -1);
   for (int t = 0; t < nt; ++t) {
-    if (tensors[t].role == SOD2_WEIGHT) weight_ids.push_back(t);
-    if (tensors[t].role == SOD2_INPUT && !tensors[t].session) input_ids.push_back(t);
-    if (tensors[t].is_output) output_ids.push_back(t);
+    if (tensors[t].role == SOD2_WEIGHT) { weight_pos[t] = (int)weight_ids.size(); weight_ids.push_back(t); }
+    if (tensors[t].role == SOD2_INPUT && !tensors[t].session) { input_pos[t] = (int)input_ids.size(); input_ids.push_back(t); }
+    if (tensors[t].is_output) { output_pos[t] = (int)output_ids.size(); output_ids.push_back(t); }
     if (tensors[t].role == SOD2_INPUT && tensors[t].session) {
       // a session input lives in the arena; CacheAppend extends it in place, so nothing else may read it
       if (!tensors[t].declared || tensors[t].capacity.size() != tensors[t].dims.size())

@@ -96,19 +96,14 @@ struct Builder {
   int force_variant;
   int force_splits = 0;
   std::map<int, View> memo;
-  std::map<int, int> widx, iidx, oidx;
 
-  Builder(const Plan& p_, const BindResult& b_, int fv) : p(p_), G(*p_.g), b(b_), force_variant(fv) {
-    for (size_t i = 0; i < G.weight_ids.size(); ++i) widx[G.weight_ids[i]] = (int)i;
-    for (size_t i = 0; i < G.input_ids.size(); ++i) iidx[G.input_ids[i]] = (int)i;
-    for (size_t i = 0; i < G.output_ids.size(); ++i) oidx[G.output_ids[i]] = (int)i;
-  }
+  Builder(const Plan& p_, const BindResult& b_, int fv) : p(p_), G(*p_.g), b(b_), force_variant(fv) {}
 
   std::vector<int64_t> eval_dims(int t) const {
     const LS& s = p.rdp->S[t];
     if (!s.resolved()) throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t].name + " is not resolved");
     std::vector<int64_t> d;
-    for (const auto& x : s.d) d.push_back(x.e.eval(b.env));
+    for (const CompiledExpr& x : p.cshape[t]) d.push_back(x.eval(b.atom_vals));
     return d;
   }
   bool live(int t) const {
@@ -189,9 +184,9 @@ struct Builder {
     auto ss = b.session.find(t);
     if (ss != b.session.end()) { r.space = SP_ARENA; r.byte_off = ss->second.first + v.off * eb; return r; }
     r.byte_off = v.off * eb;
-    if (widx.count(t)) { r.space = SP_WEIGHT; r.index = widx.at(t); }
-    else if (oidx.count(t)) { r.space = SP_OUTPUT; r.index = oidx.at(t); }
-    else if (iidx.count(t)) { r.space = SP_INPUT; r.index = iidx.at(t); }
+    if (G.weight_pos[t] >= 0) { r.space = SP_WEIGHT; r.index = G.weight_pos[t]; }
+    else if (G.output_pos[t] >= 0) { r.space = SP_OUTPUT; r.index = G.output_pos[t]; }
+    else if (G.input_pos[t] >= 0) { r.space = SP_INPUT; r.index = G.input_pos[t]; }
     else throw Error(SOD2_ERR_INVALID_ARG, "tensor has no storage: " + G.tensors[t].name);
     return r;
   }

@@ -7,7 +7,7 @@ from typing import Dict, List, Optional, Sequence
 import numpy as np
 import torch
 
-from . import (sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run, sod2_binding_arena_bytes,
+from . import (pointer_array, sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run, sod2_binding_arena_bytes,
                sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes, sod2_binding_workspace_bytes,
                sod2_replay_create, sod2_replay_launch, Sod2Error)
 
@@ -47,6 +47,7 @@ class Session:
         self.rdp = sod2_rdp_infer(self.graph)
         self.plan = sod2_plan(self.graph, self.rdp, **plan_opts)
         self.weights: List[torch.Tensor] = []
+        self._wptrs = self._wptrs_of = None              # the weights' addresses as a C array, made once
         self.arena: Optional[torch.Tensor] = None
         self.workspace_bytes = 0
         self.stream = torch.cuda.current_stream(self.device)
@@ -79,7 +80,9 @@ class Session:
         for attempt in range(4):
             arena = self.ensure_arena(nbytes)
             try:
-                sod2_run(binding, arena.data_ptr(), arena.numel(), [w.data_ptr() for w in self.weights],
+                if self._wptrs is None or self._wptrs_of is not self.weights:
+                    self._wptrs, self._wptrs_of = pointer_array([w.data_ptr() for w in self.weights]), self.weights
+                sod2_run(binding, arena.data_ptr(), arena.numel(), self._wptrs,
                          [t.data_ptr() for t in inputs], [t.data_ptr() for t in outputs], self.stream.cuda_stream)
                 return
             except Sod2Error as e:
