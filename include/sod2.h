@@ -57,7 +57,7 @@ enum {
   SOD2_OP_TRANSPOSE, SOD2_OP_MATMUL, SOD2_OP_CONV, SOD2_OP_ADD, SOD2_OP_MUL, SOD2_OP_RELU,
   SOD2_OP_GELU, SOD2_OP_SIGMOID, SOD2_OP_CAST, SOD2_OP_SOFTMAX, SOD2_OP_LAYERNORM,
   SOD2_OP_REDUCEMEAN, SOD2_OP_MAXPOOL, SOD2_OP_ARGMAX, SOD2_OP_CACHEAPPEND, SOD2_OP_NONZERO,
-  SOD2_OP_SWITCH, SOD2_OP_COMBINE, SOD2_OP_COUNT
+  SOD2_OP_SWITCH, SOD2_OP_COMBINE, SOD2_OP_SCATTERROWS, SOD2_OP_COUNT
 };
 
 #define SOD2_MAX_RANK 8
@@ -158,6 +158,17 @@ sod2_status sod2_bind(const sod2_plan_t*, const int64_t* symbol_values_host, int
 /* pure planning with a given decision vector (1 = the skip output of the Switch is taken); no run */
 sod2_status sod2_bind_decided(const sod2_plan_t*, const int64_t* symbol_values_host, int32_t n_symbols,
                               const int32_t* decisions_host, int32_t n_decisions, sod2_binding_t** out);
+/* The same for graphs with execution-determined extents (NonZero, Table 2's EDO class; Section 4.3):
+ * exec_values_host = the counts found by the NonZero operators that have executed so far, in
+ * execution order.  A NonZero still to run is planned at its upper bound, the element count of its
+ * input (this is also what sod2_bind does for all of them).  sod2_run reads each count back when the
+ * operator has run and plans what follows with it; the exact plan usually needs less than the
+ * upper-bound plan but may need more (first fit is not monotone in the sizes): then sod2_run stops
+ * there with SOD2_ERR_ARENA_TOO_SMALL as described for Switch.  A count outside
+ * [0, element count of the input] is SOD2_ERR_INVALID_ARG. */
+sod2_status sod2_bind_executed(const sod2_plan_t*, const int64_t* symbol_values_host, int32_t n_symbols,
+                               const int32_t* decisions_host, int32_t n_decisions,
+                               const int64_t* exec_values_host, int32_t n_exec_values, sod2_binding_t** out);
 void sod2_binding_destroy(sod2_binding_t*);
 /* bytes the arena passed to sod2_run must have; peak of summed live tensor bytes */
 sod2_status sod2_binding_arena_bytes(const sod2_binding_t*, size_t* arena_bytes, size_t* peak_live_bytes);
@@ -180,13 +191,16 @@ sod2_status sod2_binding_workspace_bytes(const sod2_binding_t*, size_t* workspac
 /* arena: device memory, 256-byte aligned, at least arena_bytes long.  weights / inputs / outputs:
  * host arrays of device pointers, one per tensor with that role, ordered by tensor id.
  * hip_stream: a hipStream_t (NULL = the null stream).  Enqueues and returns; synchronises the
- * stream only at a Switch, whose predicate is read back to the host. */
+ * stream only at a Switch, whose predicate is read back to the host, and after a NonZero, whose count
+ * is read back (8 bytes) so that what follows can be sized and planned. */
 sod2_status sod2_run(sod2_binding_t*, void* arena_dev, size_t arena_bytes,
                      const void* const* weights_dev, int32_t n_weights,
                      const void* const* inputs_dev, int32_t n_inputs,
                      void* const* outputs_dev, int32_t n_outputs, void* hip_stream);
 /* decisions taken by the last run, in execution order; *n receives their count */
 sod2_status sod2_run_decisions(const sod2_binding_t*, int32_t* decisions_host, int32_t cap, int32_t* n);
+/* counts found by the NonZero operators of the last run, in execution order; *n receives their number */
+sod2_status sod2_run_exec_values(const sod2_binding_t*, int64_t* values_host, int32_t cap, int32_t* n);
 
 /* plan actually executed by the last run (differs from the bind-time plan only with Switches):
  * same text format as sod2_binding_dump; arena bytes and live peak of the executed path */

@@ -18,6 +18,17 @@ Session tensors (a KV cache: tensors that persist across calls) take a region of
 their own at the bottom of the arena: one slot per session input, in tensor-id
 order, sized for its declared capacity at the bound symbols; every other offset
 starts above that region.  CacheAppend writes into the slot of its first input.
+
+Execution-determined extents (Section 4.3): ``exec_values`` holds the counts of
+the NonZero operators that have executed so far, in execution order.  A NonZero
+that has not run yet is planned at its upper bound (the element count of its
+input); binding again with the count known gives the plan for what follows
+(offsets of what has already run do not change: a cut follows every NonZero and
+sub-graphs are placed in execution order).  The greedy placement is not
+monotone in the sizes, so the exact plan can need more bytes than the
+upper-bound one; whoever runs the plan must check before going on.  The
+result of a NonZero is allocated before its extent is known: its storage is
+always rank x upper bound indices plus one 8-byte slot that receives the count.
 """
 from __future__ import annotations
 
@@ -67,6 +78,7 @@ class Binding:
     session: Dict[int, Tuple[int, int]] = field(default_factory=dict)   # session input -> (offset, bytes)
     session_root: Dict[int, int] = field(default_factory=dict)          # session tensor -> its session input
     session_bytes: int = 0
+    exec: List[Tuple[int, int, bool]] = field(default_factory=list)     # executed NonZero: (op id, extent used, known?)
 
 
 def concrete_dims(plan: Plan, t: int, env) -> List[int]:
@@ -90,7 +102,8 @@ def first_fit(t: ArenaTensor, placed: Sequence[ArenaTensor]) -> int:
     return off
 
 
-def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Binding:
+def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
+         exec_values: Sequence[int] = ()) -> Binding:
     g = plan.graph
     for name, lo, hi in g.symbols:
         if name not in sym or not (lo <= sym[name] <= hi):
@@ -112,6 +125,7 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Bin
     group_dead: Dict[int, bool] = {}
     memo: Dict[int, Tuple[bool, int]] = {}
     dec = list(decisions)
+    counts = list(exec_values)
 
     def info(t: int) -> Tuple[bool, int]:
         """(dead?, tensor whose storage t occupies)."""
@@ -158,6 +172,20 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Bin
                 for t in ext:
                     reads_at[info(t)[1]] = step
                 t = gr.out
+                nz_bytes = None
+                if gr.kind == "NONZERO":
+                    n_op = gr.ops[0]
+                    src = concrete_dims(plan, g.ops[n_op].inputs[0], env)
+                    ub = 1
+                    for d in src:
+                        ub *= d
+                    known = bool(counts)
+                    v = int(counts.pop(0)) if known else ub
+                    if not 0 <= v <= ub:
+                        raise ValueError("a NonZero count outside [0, element count of its input]")
+                    env[R.exec_symbol(n_op)] = v
+                    b.exec.append((n_op, v, known))
+                    nz_bytes = align_up((len(src) * ub + 1) * DT_BYTES[g.tensors[t].dtype])
                 b.dims[t] = concrete_dims(plan, t, env)
                 if gr.kind == "CACHEAPPEND":
                     src = g.ops[gr.ops[0]].inputs[0]
@@ -173,7 +201,7 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = ()) -> Bin
                     n = DT_BYTES[g.tensors[t].dtype]
                     for d in b.dims[t]:
                         n *= d
-                    b.tensors[t] = ArenaTensor(t, align_up(n), step, step)
+                    b.tensors[t] = ArenaTensor(t, nz_bytes if nz_bytes is not None else align_up(n), step, step)
             else:
                 op = g.ops[it.ref]
                 if op.kind == "Switch":
@@ -278,7 +306,9 @@ def check_no_overlap(b: Binding):
 
 def dump(b: Binding) -> str:
     plan = b.plan
-    lines = ["sym " + " ".join(f"{k}={v}" for k, v in b.env.items())]
+    lines = ["sym " + " ".join(f"{name}={b.env[name]}" for name, _, _ in plan.graph.symbols)]
+    for n_op, v, known in b.exec:
+        lines.append(f"exec {R.exec_symbol(n_op)}={v} {'known' if known else 'bound'}")
     for t in sorted(b.session):
         lines.append(f"session t{t} off={b.session[t][0]} bytes={b.session[t][1]}")
     for k, i in enumerate(b.steps):

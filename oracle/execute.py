@@ -22,6 +22,7 @@ class Result:
         self.decisions: List[bool] = []       # one per executed Switch, True = skip branch taken
         self.logits: List[float] = []         # predicate value seen by each executed Switch
         self.state: Dict[str, np.ndarray] = {}   # session tensors after the run, by the session input's name
+        self.exec_values: List[int] = []      # number of non-zeros found by each executed NonZero, in order
 
 
 def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dict[int, np.ndarray],
@@ -112,7 +113,12 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
         elif k == "CacheAppend":
             y = np.concatenate([xs[0], xs[1]], axis=0)
         elif k == "NonZero":
-            y = np.stack(np.nonzero(xs[0])).astype(np.int64)
+            y = O.nonzero(xs[0])
+            res.exec_values.append(int(y.shape[1]))
+        elif k == "ScatterRows":
+            y = np.array(xs[0], copy=True)
+            for j, r in enumerate(np.asarray(xs[1], dtype=np.int64).reshape(-1)):
+                y[int(r)] = xs[2][j]
         else:
             raise ValueError(k)
         val[op.outputs[0]] = O.round_to(np.asarray(y), g.tensors[op.outputs[0]].dtype)

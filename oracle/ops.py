@@ -90,3 +90,10 @@ def slice_(x, starts, ends, axes):
     for s, e, a in zip(starts, ends, axes):
         idx[a] = slice(int(s), None if e >= INT_MAX else int(e))
     return x[tuple(idx)]
+
+
+def nonzero(x):
+    """Coordinates of the non-zero elements, one column per element in row-major order: [rank, count]."""
+    x = np.asarray(x)
+    cols = [idx for idx in np.ndindex(*x.shape) if x[idx] != 0]
+    return np.asarray(cols, dtype=np.int64).reshape(len(cols), x.ndim).T

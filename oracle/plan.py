@@ -15,8 +15,8 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     tensor whose shape RDP proves equal to the output's (residual);
     activation; Transpose (stored permuted).  The chain stops at the first
     operator that does not fit.
-R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero are
-    groups of their own; a non-view Gather absorbs one following Add whose
+R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
+    ScatterRows are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
 R4  Remaining elementwise operators chain while every aligned dim pair of
     every operand is proven equal or 1 (the condition of Fig. 4), up to 8 ops.
@@ -37,6 +37,14 @@ R7  LayerNorm as a prologue: a LAYERNORM group whose result is read by one
     1024 and a multiple of 64, and everything is bf16.  The LayerNorm result is
     never materialised.  (For many rows a fused version was measured slower
     than the two kernels, so the rule stops at 8.)
+
+Execution-determined extents (Section 4.3: what follows an EDO can only be
+planned once it has executed).  When the graph holds a NonZero the plan uses
+the analysis with *named* EDO extents (``RDP(named_edo=True)``): sizes after
+the NonZero are expressions in its execution symbol, evaluated at run time as
+soon as the count is known.  A tensor that is nac or mentions an execution
+symbol counts as nac for the partition: a cut follows every item that writes
+one, and such sub-graphs keep the node order (no search).
 """
 from __future__ import annotations
 
@@ -54,7 +62,7 @@ ACTS = ("Relu", "Gelu", "Sigmoid")
 ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast")
 SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
         "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
-        "NonZero": "NONZERO"}
+        "NonZero": "NONZERO", "ScatterRows": "SCATTER"}
 
 
 @dataclass
@@ -97,6 +105,8 @@ class Plan:
     sg_class: List[str]
     sbase: List[int]                      # static base of every tensor
     versions_unfused: int = 0             # broadcast versions a shape-blind fuser would need
+    paper_rdp: R.RDP = None               # Alg. 1 as printed (EDO outputs nac); == rdp without a NonZero
+    exec_ops: List[int] = field(default_factory=list)    # NonZero operators, in the node order
 
 
 def _shape_equal(a, b) -> bool:
@@ -128,6 +138,9 @@ def align_up(n: int) -> int:
 def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     opts = opts or Opts()
     g = graph
+    paper_rdp = rdp
+    if any(op.kind == "NonZero" for op in g.ops):
+        rdp = R.RDP(g, named_edo=True).analyse()
     order = rdp.sorted_nodes()
     pos = {n: i for i, n in enumerate(order)}
     nops = len(g.ops)
@@ -348,7 +361,8 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
                     reads.append(sbase[t])
             items.append(Item(False, ref, reads, list(op.outputs) if op.kind == "Combine" else []))
 
-    plan = Plan(g, rdp, opts, order, folded, view, groups, assigned, items, [], [], sbase, versions)
+    plan = Plan(g, rdp, opts, order, folded, view, groups, assigned, items, [], [], sbase, versions,
+                paper_rdp, [n for n in order if g.ops[n].kind == "NonZero"])
     _partition(plan)
     return plan
 
@@ -359,12 +373,14 @@ def arena_candidate(plan: Plan, t: int) -> bool:
     return d.role == "inter" and not d.is_output and not d.session
 
 
+def execution_determined(plan: Plan, t: int) -> bool:
+    """nac in the paper's lattice: unresolved, or an expression in an execution symbol."""
+    s = plan.rdp.S[t]
+    return not isinstance(s, list) or any(not R.is_expr(d) or R.mentions_exec(d) for d in s)
+
+
 def _item_has_nac(plan: Plan, it: Item) -> bool:
-    for t in it.writes:
-        s = plan.rdp.S[t]
-        if not isinstance(s, list) or any(not R.is_expr(d) for d in s):
-            return True
-    return False
+    return any(execution_determined(plan, t) for t in it.writes)
 
 
 def _partition(plan: Plan):
@@ -404,17 +420,17 @@ def _classify(plan: Plan, piece) -> str:
     cls = "known"
     for i in piece:
         for t in plan.items[i].writes:
-            s = plan.rdp.S[t]
-            if not isinstance(s, list) or any(not R.is_expr(d) for d in s):
+            if execution_determined(plan, t):
                 return "nac"
-            if any(not d.is_const() for d in s):
+            if any(not d.is_const() for d in plan.rdp.S[t]):
                 cls = "mixed"
     return cls
 
 
 def _bytes_at(plan: Plan, t: int, env) -> int:
+    """Size used by the order search; an execution-determined tensor counts as 0 (unknown)."""
     e = tensor_bytes_expr(plan.rdp, plan.graph, t)
-    return 0 if e is None else align_up(e.eval(env))
+    return 0 if e is None or execution_determined(plan, t) else align_up(e.eval(env))
 
 
 def subgraph_peak(plan: Plan, seq, last_read, env) -> int:
@@ -451,7 +467,7 @@ def _incoming_arena(plan: Plan, t: int, first_item: int) -> bool:
 def _order_subgraph(plan: Plan, piece, last_read) -> List[int]:
     """Section 4.3: exhaustive search (dynamic programme over executed subsets) for the order with
     the smallest peak, sizes taken at the symbols' upper bounds; ties -> smallest group ids first."""
-    if not plan.opts.sep or len(piece) <= 2:
+    if not plan.opts.sep or len(piece) <= 2 or _classify(plan, piece) == "nac":
         return list(piece)
     items = plan.items
     env = {name: hi for name, lo, hi in plan.graph.symbols}
@@ -521,6 +537,10 @@ def dump(plan: Plan) -> str:
     lines = ["order" + "".join(f" {n}" for n in plan.order)]
     lines.append("folded" + "".join(f" {i}" for i, f in enumerate(plan.folded) if f))
     lines.append("views" + "".join(f" {i}" for i, f in enumerate(plan.view) if f))
+    for t in range(len(g.tensors)):                      # shapes that wait for an EDO to execute
+        s = plan.rdp.S[t]
+        if isinstance(s, list) and any(R.mentions_exec(d) for d in s):
+            lines.append(f"named t{t} S={R.fmt_list(s)}")
     for it in plan.items:
         if it.is_group:
             gr = plan.groups[it.ref]

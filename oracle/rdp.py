@@ -32,11 +32,21 @@ OP_CLASS = {
     "Gather": ISDOS, "Concat": ISDOS, "Transpose": ISDOS, "MatMul": ISDOS, "Conv": ISDOS,
     "Add": ISDOS, "Mul": ISDOS, "Relu": ISDOS, "Gelu": ISDOS, "Sigmoid": ISDOS, "Cast": ISDOS,
     "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
-    "ArgMax": ISDOS, "CacheAppend": ISDOS,
+    "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
     "Reshape": ISVDOS, "Slice": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
 UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm")
+EXEC_PREFIX = "@nz"   # name of an execution symbol: EXEC_PREFIX + operator id
+
+
+def exec_symbol(op_id: int) -> str:
+    return f"{EXEC_PREFIX}{op_id}"
+
+
+def mentions_exec(e) -> bool:
+    """Does a lattice value depend on an execution symbol (nested floordiv / mod atoms included)?"""
+    return is_expr(e) and EXEC_PREFIX in str(e)
 
 
 class ShapeMismatch(Exception):
@@ -174,8 +184,17 @@ def fused_versions(a, b) -> int:
 # ---------------------------------------------------------------------------
 
 class RDP:
-    def __init__(self, graph):
+    """``named_edo=False`` is Alg. 1 as printed: every output of an execution-determined operator is
+    nac.  ``named_edo=True`` runs the same transfer functions with one change: the extent NonZero
+    produces (unknown until it has executed, then a constant for the rest of the call) is given a
+    name, the execution symbol ``@nz<operator id>``, so that everything downstream is an expression
+    in it and can be evaluated, not re-inferred, once the operator has run.  The second analysis
+    refines the first: where the first has a value the second has the same one, and whatever is nac
+    or mentions an execution symbol in the second is nac in the first."""
+
+    def __init__(self, graph, named_edo: bool = False):
         self.g = graph
+        self.named_edo = named_edo
         nt = len(graph.tensors)
         self.S: List = [UNDEF] * nt
         self.V: List = [UNDEF] * nt
@@ -253,7 +272,7 @@ class RDP:
                     for o in op.outputs:                       # and back (input = output)
                         changed |= self._refine(self.S, op.inputs[0], self.S[o])
                     continue
-                changed |= self._forward(op)
+                changed |= self._forward(op, n)
                 for k, t in enumerate(op.inputs):
                     if has_undef(self.S[t]):
                         changed |= self._backward(op, k)
@@ -278,9 +297,14 @@ class RDP:
         return ch
 
     # -- forward transfer ----------------------------------------------------
-    def _forward(self, op) -> bool:
+    def _forward(self, op, n: int) -> bool:
         cls = OP_CLASS[op.kind]
-        if cls == EDO:
+        if cls == EDO and self.named_edo and op.kind == "NonZero":
+            s = self.S[op.inputs[0]]                    # result [rank of the input, number of non-zeros]
+            if s is UNDEF:
+                return False
+            res = [(NAC if s == NAC else [C(len(s)), Expr.sym(exec_symbol(n))], NAC)]
+        elif cls == EDO:
             res = [(NAC, NAC) for _ in op.outputs]
         else:
             r = getattr(self, "_f_" + op.kind if op.kind not in UNARY else "_f_unary")(op)
@@ -515,6 +539,10 @@ class RDP:
         if x is UNDEF:
             return None
         return (NAC if x == NAC else list(x[:-1])), UNDEF
+
+    def _f_ScatterRows(self, op):
+        s = self.S[op.inputs[0]]                        # a copy of input 0 with some rows replaced
+        return None if s is UNDEF else ((NAC if s == NAC else list(s)), UNDEF)
 
     def _f_CacheAppend(self, op):
         p, n = self.S[op.inputs[0]], self.S[op.inputs[1]]

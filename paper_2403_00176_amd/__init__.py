@@ -24,16 +24,17 @@ DTYPES = {"f32": 0, "bf16": 1, "i64": 2, "i32": 3}
 ROLES = {"inter": 0, "input": 1, "weight": 2, "hostconst": 3}
 OP_KINDS = ["Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul",
             "Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax",
-            "CacheAppend", "NonZero", "Switch", "Combine"]
+            "CacheAppend", "NonZero", "Switch", "Combine", "ScatterRows"]
 OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
 
 EXPORTS = [
     "sod2_graph_build", "sod2_graph_destroy", "sod2_graph_op_class", "sod2_rdp_infer", "sod2_rdp_infer_ordered",
     "sod2_rdp_destroy", "sod2_rdp_query", "sod2_rdp_sweeps", "sod2_rdp_dump", "sod2_plan", "sod2_plan_destroy",
-    "sod2_plan_counts", "sod2_plan_dump", "sod2_bind", "sod2_bind_decided", "sod2_binding_destroy",
+    "sod2_plan_counts", "sod2_plan_dump", "sod2_bind", "sod2_bind_decided", "sod2_bind_executed",
+    "sod2_binding_destroy",
     "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_force_decisions", "sod2_binding_force_variant",
     "sod2_binding_force_splits", "sod2_binding_workspace_bytes",
-    "sod2_run", "sod2_run_decisions", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
+    "sod2_run", "sod2_run_decisions", "sod2_run_exec_values", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
     "sod2_binding_launch_records", "sod2_replay_create", "sod2_replay_launch", "sod2_replay_destroy",
     "sod2_last_error", "sod2_version",
 ]
@@ -77,7 +78,8 @@ class LaunchRecord(C.Structure):
                 ("ms", C.c_float), ("flops", C.c_double), ("bytes", C.c_double)]
 
 
-KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other", "gather", "append", "argmax", "attention"]
+KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other", "gather", "append", "argmax", "attention",
+                "nonzero", "scatter"]
 
 _lib.sod2_last_error.restype = C.c_char_p
 _lib.sod2_version.restype = C.c_char_p
@@ -272,11 +274,18 @@ def _symbols(p: Plan, sym) -> "C.Array":
     return (C.c_int64 * max(len(sym), 1))(*[int(v) for v in sym]), len(sym)
 
 
-def sod2_bind(p: Plan, sym, decisions: Optional[Sequence[int]] = None) -> Binding:
+def sod2_bind(p: Plan, sym, decisions: Optional[Sequence[int]] = None,
+              exec_values: Optional[Sequence[int]] = None) -> Binding:
+    """decisions / exec_values: plan for given Switch decisions / NonZero counts (no run needed)."""
     arr, n = _symbols(p, sym)
     out = C.c_void_p()
-    if decisions is None:
+    if decisions is None and exec_values is None:
         _check(_lib.sod2_bind(p.ptr, arr, n, C.byref(out)))
+    elif exec_values is not None:
+        decisions = decisions or []
+        d = (C.c_int32 * max(len(decisions), 1))(*[int(bool(v)) for v in decisions])
+        e = (C.c_int64 * max(len(exec_values), 1))(*[int(v) for v in exec_values])
+        _check(_lib.sod2_bind_executed(p.ptr, arr, n, d, len(decisions), e, len(exec_values), C.byref(out)))
     else:
         d = (C.c_int32 * max(len(decisions), 1))(*[int(bool(v)) for v in decisions])
         _check(_lib.sod2_bind_decided(p.ptr, arr, n, d, len(decisions), C.byref(out)))
@@ -348,6 +357,14 @@ def sod2_run_decisions(b: Binding) -> List[int]:
 def pointer_array(ptrs: Sequence[int]):
     """Device addresses as the `const void* const*` argument of sod2_run (reusable across calls)."""
     return (C.c_void_p * len(ptrs))(*ptrs)
+
+
+def sod2_run_exec_values(b: Binding) -> List[int]:
+    n = C.c_int32()
+    _check(_lib.sod2_run_exec_values(b.ptr, None, 0, C.byref(n)))
+    arr = (C.c_int64 * max(n.value, 1))()
+    _check(_lib.sod2_run_exec_values(b.ptr, arr, n.value, C.byref(n)))
+    return list(arr[:n.value])
 
 
 def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence[int], input_ptrs: Sequence[int],

@@ -94,7 +94,7 @@ sod2_status sod2_graph_build(const sod2_graph_desc* d, sod2_graph_t** out) {
     op.out.assign(od.outputs, od.outputs + od.n_outputs);
     if (od.n_iattr) op.ia.assign(od.iattr, od.iattr + od.n_iattr);
     op.fa = od.fattr;
-    static const int n_in[SOD2_OP_COUNT] = {1, 2, -1, 2, 4, 1, 2, 2, 2, 2, 1, 1, 1, 1, 1, 3, 1, 1, 1, 2, 1, 2, -1};
+    static const int n_in[SOD2_OP_COUNT] = {1, 2, -1, 2, 4, 1, 2, 2, 2, 2, 1, 1, 1, 1, 1, 3, 1, 1, 1, 2, 1, 2, -1, 3};
     if (n_in[op.kind] >= 0 && (int)op.in.size() != n_in[op.kind])
       throw Error(SOD2_ERR_INVALID_ARG, std::string("wrong input count for ") + op_name(op.kind));
     if (op.out.empty() || (op.kind == SOD2_OP_SWITCH && op.out.size() != 2))
@@ -188,14 +188,15 @@ sod2_status sod2_plan_dump(const sod2_plan_t* p, char* buf, size_t cap, size_t* 
 }
 
 static sod2_status do_bind(const sod2_plan_t* p, const int64_t* sym, int32_t n, const int32_t* dec, int32_t nd,
-                           bool allow_undecided, sod2_binding_t** out) {
+                           bool allow_undecided, sod2_binding_t** out, const int64_t* ev = nullptr, int32_t ne = 0) {
   SOD2_TRY
-  if (!p || !out || (n > 0 && !sym) || (nd > 0 && !dec)) throw Error(SOD2_ERR_INVALID_ARG, "null argument");
+  if (!p || !out || (n > 0 && !sym) || (nd > 0 && !dec) || (ne > 0 && !ev)) throw Error(SOD2_ERR_INVALID_ARG, "null argument");
   std::unique_ptr<sod2_binding_s> h(new sod2_binding_s);
   h->plan = &p->p;
   h->symbols.assign(sym, sym + n);
   std::vector<int> d(dec, dec + nd);
-  h->b = bind_plan(p->p, h->symbols, d, allow_undecided);
+  h->planned_exec.assign(ev, ev + ne);
+  h->b = bind_plan(p->p, h->symbols, d, allow_undecided, h->planned_exec);
   h->planned_decisions = d;
   *out = h.release();
   SOD2_CATCH
@@ -206,6 +207,10 @@ sod2_status sod2_bind(const sod2_plan_t* p, const int64_t* sym, int32_t n, sod2_
 sod2_status sod2_bind_decided(const sod2_plan_t* p, const int64_t* sym, int32_t n, const int32_t* dec, int32_t nd,
                               sod2_binding_t** out) {
   return do_bind(p, sym, n, dec, nd, false, out);
+}
+sod2_status sod2_bind_executed(const sod2_plan_t* p, const int64_t* sym, int32_t n, const int32_t* dec, int32_t nd,
+                               const int64_t* ev, int32_t ne, sod2_binding_t** out) {
+  return do_bind(p, sym, n, dec, nd, false, out, ev, ne);
 }
 sod2_status sod2_binding_arena_bytes(const sod2_binding_t* b, size_t* arena, size_t* peak) {
   if (!b) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
@@ -247,6 +252,12 @@ sod2_status sod2_run_decisions(const sod2_binding_t* b, int32_t* dec, int32_t ca
   if (!b || !n) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
   *n = (int)b->last_decisions.size();
   for (int i = 0; i < *n && i < cap && dec; ++i) dec[i] = b->last_decisions[i];
+  return SOD2_OK;
+}
+sod2_status sod2_run_exec_values(const sod2_binding_t* b, int64_t* vals, int32_t cap, int32_t* n) {
+  if (!b || !n) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
+  *n = (int)b->last_exec.size();
+  for (int i = 0; i < *n && i < cap && vals; ++i) vals[i] = b->last_exec[i];
   return SOD2_OK;
 }
 sod2_status sod2_run_plan_dump(const sod2_binding_t* b, char* buf, size_t cap, size_t* needed) {

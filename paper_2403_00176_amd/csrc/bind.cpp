@@ -11,6 +11,13 @@
 // Session tensors (a KV cache) persist across calls: one slot per session input at the bottom of
 // the arena, in tensor-id order, sized for the declared capacity at the bound symbols; every other
 // offset starts above that region.  CacheAppend writes into the slot of its first input.
+//
+// Execution-determined extents (Section 4.3): a NonZero whose count is not known yet is planned at
+// its upper bound (the element count of its input); binding again with the count gives the plan for
+// what follows, and nothing that already ran moves (a cut follows every NonZero, sub-graphs are
+// placed in execution order).  Its result is allocated before the extent is known: always rank x
+// upper bound indices plus one 8-byte slot for the count.  First fit is not monotone in the sizes:
+// the exact plan may need more bytes than the upper-bound plan, the caller must check.
 #include <algorithm>
 #include <functional>
 
@@ -54,7 +61,7 @@ int64_t best_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& pl
 }  // namespace
 
 BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const std::vector<int>& decisions,
-                     bool allow_undecided) {
+                     bool allow_undecided, const std::vector<int64_t>& exec_values) {
   const Graph& G = *p.g;
   BindResult b;
   if (symbols.size() != G.symbols.size()) throw Error(SOD2_ERR_INVALID_ARG, "wrong number of symbol values");
@@ -75,7 +82,10 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
     b.session_root[t] = t;
     b.session_bytes += nbytes;
   }
-  p.xc.atom_values(symbols, &b.atom_vals);
+  std::vector<int64_t> sv = symbols;                  // graph symbols, then one slot per execution symbol
+  sv.resize(p.xc.symbols.size(), 0);
+  p.xc.atom_values(sv, &b.atom_vals);
+  size_t next_exec = 0;
   const int nt = (int)G.tensors.size();
   std::vector<char> group_dead(G.ops.size(), 0);   // by group id (= an operator id)
   std::vector<signed char> memo_dead(nt, -1);       // tensor -> dead?  (-1: not computed yet)
@@ -129,6 +139,22 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         if (dead) { b.dead_ops.insert(gr.ops.begin(), gr.ops.end()); continue; }
         for (int t : ext) reads_at[info(t).second] = step;
         int t = gr.out;
+        int64_t nz_bytes = -1;
+        if (gr.kind == G_NONZERO) {
+          int n_op = gr.ops[0], src = G.ops[n_op].in[0];
+          if (p.cshape[src].empty() && !p.rdp->S[src].resolved())
+            throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[src].name + " is not resolved");
+          int64_t ub = 1;
+          for (const CompiledExpr& d : p.cshape[src]) ub *= d.eval(b.atom_vals);
+          bool known = next_exec < exec_values.size();
+          int64_t v = known ? exec_values[next_exec++] : ub;
+          if (v < 0 || v > ub) throw Error(SOD2_ERR_INVALID_ARG, "a NonZero count outside [0, element count of its input]");
+          size_t slot = G.symbols.size() + (std::find(p.exec_ops.begin(), p.exec_ops.end(), n_op) - p.exec_ops.begin());
+          sv[slot] = v;
+          p.xc.atom_values(sv, &b.atom_vals);
+          b.exec.push_back({n_op, v, known});
+          nz_bytes = ((int64_t)p.cshape[src].size() * ub + 1) * dtype_bytes(G.tensors[t].dtype);
+        }
         const LS& sh = p.rdp->S[t];
         if (!sh.resolved())
           throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t].name + " is not resolved: " + sh.str());
@@ -145,6 +171,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
           if (elems > cap_elems.at(root->second))
             throw Error(SOD2_ERR_INVALID_ARG, "session tensor " + G.tensors[t].name + " would outgrow its capacity");
         }
+        if (nz_bytes >= 0) n = nz_bytes;
         if (p.arena_candidate(t)) b.tensors[t] = ArenaTensor{t, (n + 255) / 256 * 256, step, step, -1};
       } else {
         const Op& op = G.ops[it.ref];
@@ -237,6 +264,8 @@ std::string BindResult::dump(const Plan& p) const {
   std::string out = "sym";
   for (const auto& s : p.g->symbols) out += " " + s.name + "=" + std::to_string(env.at(s.name));
   out += "\n";
+  for (const Exec& e : exec)
+    out += "exec " + exec_symbol(e.op) + "=" + std::to_string(e.value) + (e.known ? " known\n" : " bound\n");
   for (const auto& kv : session)
     out += "session t" + std::to_string(kv.first) + " off=" + std::to_string(kv.second.first) + " bytes=" +
            std::to_string(kv.second.second) + "\n";

@@ -165,6 +165,12 @@ int64_t Expr::eval(const std::map<std::string, int64_t>& env) const {
   return total;
 }
 
+bool mentions_exec(const Expr& e) {
+  for (const auto& t : e.terms)
+    for (const auto& a : t.first) if (a.find("@nz") != std::string::npos) return true;
+  return false;
+}
+
 // ---- flattened form ----------------------------------------------------------------------------
 int ExprCompiler::intern(const std::string& name) {
   auto it = index.find(name);

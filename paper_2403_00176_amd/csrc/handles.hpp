@@ -11,6 +11,8 @@ struct sod2_binding_s {
   std::vector<int64_t> symbols;
   sod2::BindResult b;
   std::vector<int> planned_decisions;       // decisions b was planned with
+  std::vector<int64_t> planned_exec;        // NonZero counts b was planned with
+  std::vector<int64_t> last_exec;           // NonZero counts found by the last run
   std::vector<int> forced;                  // decisions forced on the next runs
   bool has_forced = false;
   int force_variant = -1;

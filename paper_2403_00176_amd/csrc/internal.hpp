@@ -140,10 +140,18 @@ const char* op_name(int kind);
 int dtype_bytes(int dtype);
 inline bool is_int(int dtype) { return dtype == SOD2_I64 || dtype == SOD2_I32; }
 
+// Name of the extent an execution-determined operator produces (known once it has run).
+inline std::string exec_symbol(int op_id) { return "@nz" + std::to_string(op_id); }
+bool mentions_exec(const Expr& e);                 // nested floordiv / mod atoms included
+
 struct Rdp {
   const Graph* g = nullptr;
   std::vector<LS> S, V;
   int sweeps = 0;
+  // false: Alg. 1 as printed (every EDO output nac).  true: the extent a NonZero produces is named
+  // by an execution symbol, so what follows is an expression in it; this refines the first analysis
+  // (same values where that one has values; nac there wherever this one has nac or such a symbol).
+  bool named_edo = false;
   void analyse(const std::vector<int>* order);
   std::string dump() const;
 };
@@ -152,7 +160,7 @@ struct Rdp {
 // Static plan
 // ---------------------------------------------------------------------------------------------
 enum GroupKind { G_GEMM, G_CONV, G_LAYERNORM, G_SOFTMAX, G_MAXPOOL, G_REDUCEMEAN, G_ARGMAX,
-                 G_CACHEAPPEND, G_NONZERO, G_GATHER, G_ELTWISE, G_ATTENTION };
+                 G_CACHEAPPEND, G_NONZERO, G_GATHER, G_ELTWISE, G_ATTENTION, G_SCATTER };
 const char* group_kind_name(int k);
 
 struct Group {
@@ -169,7 +177,11 @@ struct Item {
 };
 struct Plan {
   const Graph* g = nullptr;
-  const Rdp* rdp = nullptr;
+  const Rdp* rdp = nullptr;                        // the analysis the plan is built on
+  const Rdp* paper_rdp = nullptr;                  // Alg. 1 as printed; == rdp unless the graph holds a NonZero
+  std::shared_ptr<Rdp> named;                      // analysis with named EDO extents, owned (see Rdp::named_edo)
+  std::vector<int> exec_ops;                       // NonZero operators in the node order
+  bool execution_determined(int t) const;          // nac in the paper's lattice: unresolved or in an execution symbol
   sod2_plan_opts opts{1, 1, 1, 1};
   std::vector<int> order;
   std::vector<char> folded, view;
@@ -215,9 +227,13 @@ struct BindResult {
   int64_t session_bytes = 0;
   int64_t arena_bytes = 0, peak_live = 0;
   int undecided = 0;                               // Switches met without a given decision
+  struct Exec { int op; int64_t value; bool known; };   // an executed NonZero and the extent planned with
+  std::vector<Exec> exec;                          // in execution order; !known: the upper bound was used
   std::string dump(const Plan& p) const;
 };
+// exec_values: extents found by the NonZero operators that have executed so far, in execution order;
+// the ones still to run are planned at their upper bound (the element count of their input)
 BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const std::vector<int>& decisions,
-                     bool allow_undecided);
+                     bool allow_undecided, const std::vector<int64_t>& exec_values = {});
 
 }  // namespace sod2

@@ -8,7 +8,7 @@
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
 //     consumer of the chain so far;
-//  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero stand alone; a
+//  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
 //  R4 other elementwise operators chain while every aligned dim pair is proven equal or 1 (Fig. 4);
 //  R5 group id = smallest member id; groups are ordered by the node-order position of their
@@ -20,6 +20,10 @@
 // Partition: cut around control operators and NonZero, after a group with a nac output, wherever
 // at most one arena tensor is live, and every 14 items.  Order inside a sub-graph: the sequence
 // with the smallest peak of live bytes at the symbols' upper bounds, ties to smaller group ids.
+//
+// Execution-determined extents (Section 4.3): with a NonZero in the graph the plan is built on the
+// analysis with named EDO extents; a tensor that is unresolved or sized by an execution symbol
+// counts as nac: a cut follows every item that writes one and such sub-graphs keep the node order.
 #include <algorithm>
 #include <limits>
 
@@ -28,7 +32,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -61,9 +65,17 @@ bool Plan::arena_candidate(int t) const {
   return d.role == SOD2_INTER && !d.is_output && !d.session;
 }
 
+bool Plan::execution_determined(int t) const {
+  const LS& s = rdp->S[t];
+  if (!s.resolved()) return true;
+  for (const auto& d : s.d) if (mentions_exec(d.e)) return true;
+  return false;
+}
+
+// size used by the order search; an execution-determined tensor counts as 0 (unknown)
 static int64_t bytes_at(const Plan& p, int t, const std::map<std::string, int64_t>& env) {
   const LS& s = p.rdp->S[t];
-  if (!s.resolved()) return 0;
+  if (p.execution_determined(t)) return 0;
   int64_t n = dtype_bytes(p.g->tensors[t].dtype);
   for (const auto& d : s.d) n *= d.e.eval(env);
   return align_up(n);
@@ -71,6 +83,17 @@ static int64_t bytes_at(const Plan& p, int t, const std::map<std::string, int64_
 
 void Plan::build() {
   const Graph& G = *g;
+  paper_rdp = rdp;
+  for (const Op& op : G.ops)
+    if (op.kind == SOD2_OP_NONZERO && !named) {
+      // Section 4.3: what follows an EDO is planned when it has executed.  With its extent named,
+      // the sizes that follow are expressions evaluated at that moment instead of re-inferred.
+      named = std::make_shared<Rdp>();
+      named->g = g;
+      named->named_edo = true;
+      named->analyse(nullptr);
+      rdp = named.get();
+    }
   const Rdp& R = *rdp;
   int nops = (int)G.ops.size();
   order = G.sorted_nodes();
@@ -164,6 +187,7 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_ARGMAX) new_group(G_ARGMAX, {n});
     else if (op.kind == SOD2_OP_CACHEAPPEND) new_group(G_CACHEAPPEND, {n});
     else if (op.kind == SOD2_OP_NONZERO) new_group(G_NONZERO, {n});
+    else if (op.kind == SOD2_OP_SCATTERROWS) new_group(G_SCATTER, {n});
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);
@@ -325,7 +349,7 @@ void Plan::build() {
   for (int i = 0; i < n; ++i) for (int t : items[i].reads) last_read[t] = i;
   auto lr = [&](int t) { auto it = last_read.find(t); return it == last_read.end() ? -1 : it->second; };
   auto has_nac = [&](const Item& it) {
-    for (int t : it.writes) if (!R.S[t].resolved()) return true;
+    for (int t : it.writes) if (execution_determined(t)) return true;
     return false;
   };
   std::vector<char> cut_after(n, 0);
@@ -358,12 +382,12 @@ void Plan::build() {
     std::string cls = "known";
     for (int i : piece)
       for (int t : items[i].writes) {
-        if (!R.S[t].resolved()) { cls = "nac"; break; }
+        if (execution_determined(t)) { cls = "nac"; break; }
         for (const auto& d : R.S[t].d) if (!d.e.is_const() && cls != "nac") cls = "mixed";
       }
     sg_class.push_back(cls);
     int k = (int)piece.size();
-    if (!opts.sep || k <= 2) { subgraphs.push_back(piece); continue; }
+    if (!opts.sep || k <= 2 || cls == "nac") { subgraphs.push_back(piece); continue; }
 
     // exhaustive search as a dynamic programme over the set of executed items
     int first = piece.front(), end = piece.back();
@@ -450,6 +474,8 @@ void Plan::build() {
 
   // flattened forms used by every bind
   for (const Symbol& sy : G.symbols) xc.symbols.push_back(sy.name);
+  for (int n : order) if (G.ops[n].kind == SOD2_OP_NONZERO) exec_ops.push_back(n);
+  for (int n : exec_ops) xc.symbols.push_back(exec_symbol(n));   // their values follow the graph symbols'
   cshape.assign(nt, {});
   for (int t = 0; t < nt; ++t) {
     if (!R.S[t].resolved()) continue;
@@ -473,6 +499,12 @@ std::string Plan::dump() const {
   out += "\nviews";
   for (size_t i = 0; i < view.size(); ++i) if (view[i]) out += " " + std::to_string(i);
   out += "\n";
+  for (size_t t = 0; t < g->tensors.size(); ++t) {      // shapes that wait for an EDO to execute
+    const LS& s = rdp->S[t];
+    bool named_dim = false;
+    if (s.is_list()) for (const auto& d : s.d) if (d.val() && mentions_exec(d.e)) named_dim = true;
+    if (named_dim) out += "named t" + std::to_string(t) + " S=" + s.str() + "\n";
+  }
   auto join = [](const std::vector<int>& v, const char* prefix) {
     std::string s;
     for (size_t i = 0; i < v.size(); ++i) { if (i) s += " "; s += prefix + std::to_string(v[i]); }

@@ -15,7 +15,7 @@ namespace sod2 {
 static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
-    "NonZero", "Switch", "Combine"};
+    "NonZero", "Switch", "Combine", "ScatterRows"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
@@ -149,7 +149,8 @@ struct Analyser {
   const Graph& g;
   std::vector<LS>& S;
   std::vector<LS>& V;
-  Analyser(const Graph& g_, std::vector<LS>& s, std::vector<LS>& v) : g(g_), S(s), V(v) {}
+  bool named_edo;
+  Analyser(const Graph& g_, std::vector<LS>& s, std::vector<LS>& v, bool named) : g(g_), S(s), V(v), named_edo(named) {}
 
   bool refine(std::vector<LS>& store, int t, const LS& nw) {
     if (nw.k == LS::UNDEF) return false;
@@ -159,7 +160,7 @@ struct Analyser {
     return true;
   }
 
-  Out forward(const Op& op) {
+  Out forward(const Op& op, int op_id) {
     Out r;
     auto in_s = [&](int k) -> const LS& { return S[op.in[k]]; };
     auto in_v = [&](int k) -> const LS& { return V[op.in[k]]; };
@@ -374,8 +375,18 @@ struct Analyser {
         for (size_t k = 1; k < p.d.size() && k < n.d.size(); ++k) o.d.push_back(meet(p.d[k], n.d[k]));
         return done(o);
       }
-      case SOD2_OP_NONZERO:
-        return done(LS::nac(), LS::nac());               // execution determined
+      case SOD2_OP_NONZERO: {                            // execution determined
+        if (!named_edo) return done(LS::nac(), LS::nac());
+        // the extent is unknown until the operator has run and a constant afterwards: give it a name
+        const LS& x = in_s(0);
+        if (x.k == LS::UNDEF) return r;
+        if (x.k == LS::NAC) return done(LS::nac(), LS::nac());
+        return done(LS::list({LV::c((int64_t)x.d.size()), LV::of(Expr::symbol(exec_symbol(op_id)))}), LS::nac());
+      }
+      case SOD2_OP_SCATTERROWS: {                        // a copy of input 0 with some rows replaced
+        if (in_s(0).k == LS::UNDEF) return r;
+        return done(in_s(0));
+      }
       default:
         throw Error(SOD2_ERR_UNSUPPORTED, std::string("no transfer function for ") + op_name(op.kind));
     }
@@ -443,7 +454,7 @@ void Rdp::analyse(const std::vector<int>* order_in) {
       for (int64_t v : t.idata) V[i].d.push_back(LV::c(v));
     }
   }
-  Analyser A(gr, S, V);
+  Analyser A(gr, S, V, named_edo);
   bool changed = true;
   sweeps = 0;
   while (changed) {
@@ -465,7 +476,7 @@ void Rdp::analyse(const std::vector<int>* order_in) {
         for (int o : op.out) changed |= A.refine(S, op.in[0], S[o]);
         continue;
       }
-      Out r = A.forward(op);
+      Out r = A.forward(op, n);
       if (r.ready) {
         for (int o : op.out) {
           changed |= A.refine(S, o, r.s);

@@ -13,7 +13,8 @@ from workloads import configs, GraphBuilder
 def small(cfg):
     return {1: configs.config1, 2: lambda: configs.config2(8, layers=3),
             3: lambda: configs.resnet50(3, 6, stages=(2, 2, 1, 1)),
-            4: lambda: configs.config4(6, layers=3)}[cfg]()
+            4: lambda: configs.config4(6, layers=3),
+            6: lambda: configs.config6(6, layers=3)}[cfg]()
 
 
 def test_library_exports_every_declared_symbol():
@@ -26,7 +27,7 @@ def test_library_exports_every_declared_symbol():
     assert "gfx950" in S.sod2_version()
 
 
-@pytest.mark.parametrize("cfg", [1, 2, 3, 4])
+@pytest.mark.parametrize("cfg", [1, 2, 3, 4, 6])
 def test_rdp_plan_bind_match_oracle(cfg):
     w = small(cfg)
     g = S.sod2_graph_build(w.graph)
@@ -47,6 +48,11 @@ def test_rdp_plan_bind_match_oracle(cfg):
             bo = A.bind(po, call, dec)
             assert S.sod2_binding_dump(b) == A.dump(bo)
             assert S.sod2_binding_arena_bytes(b) == (bo.arena_bytes, bo.peak_live)
+            # execution-determined extents: none, some and all of the NonZero counts known
+            n_nz = len(po.exec_ops)
+            for known in sorted({0, n_nz // 2, n_nz} - {0} if n_nz else ()):
+                ev = [rnd.randint(0, call.get("B", 1)) for _ in range(known)]
+                assert S.sod2_binding_dump(S.sod2_bind(p, call, exec_values=ev)) == A.dump(A.bind(po, call, exec_values=ev))
 
 
 def test_full_size_configs_match_oracle():
@@ -96,17 +102,32 @@ def test_error_paths():
         S.sod2_rdp_infer(S.sod2_graph_build(b.build()))
     assert e.value.code == -3
     # a nac shape reaching a kernel is refused at bind
-    b = GraphBuilder([("I", 1, 9)])
-    x = b.input("x", "f32", ["I", 4])
-    nz = b.op("NonZero", [x], dtype="i64")
-    b.mark_output(b.op("Cast", [nz], dtype="f32"))
+    # (branches whose symbolic dims differ meet in a Combine: those dims are nac, Section 3 / Fig. 1(d))
+    b = GraphBuilder([("I", 1, 9), ("J", 1, 9)])
+    x = b.input("x", "f32", ["I", "J"])
+    pr = b.input("p", "f32", [1])
+    run, skip = b.op("Switch", [x, pr], n_out=2, threshold=0.5)
+    y = b.op("Gelu", [b.op("Transpose", [run], perm=(1, 0))])
+    b.mark_output(b.op("Relu", [b.op("Combine", [y, skip])]))
     gd = b.build()
     g2 = S.sod2_graph_build(gd)
     r2 = S.sod2_rdp_infer(g2)
     p2 = S.sod2_plan(g2, r2)
     with pytest.raises(S.Sod2Error) as e:
-        S.sod2_bind(p2, {"I": 3})
+        S.sod2_bind(p2, {"I": 3, "J": 4})
     assert e.value.code == -4
+    # an execution-determined extent is not an error: it is planned at its upper bound until known
+    b = GraphBuilder([("I", 1, 9)])
+    x = b.input("x", "f32", ["I", 4])
+    nz = b.op("NonZero", [x], dtype="i64")
+    b.mark_output(b.op("Cast", [nz], dtype="f32"))
+    g3 = S.sod2_graph_build(b.build())
+    p3 = S.sod2_plan(g3, S.sod2_rdp_infer(g3))
+    assert "exec @nz0=12 bound" in S.sod2_binding_dump(S.sod2_bind(p3, {"I": 3}))
+    assert "exec @nz0=5 known" in S.sod2_binding_dump(S.sod2_bind(p3, {"I": 3}, exec_values=[5]))
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_bind(p3, {"I": 3}, exec_values=[13])
+    assert e.value.code == -1
     # run without a device: bad pointers are refused before any launch
     bnd = S.sod2_bind(p, {"B": 1, "L": 32})
     with pytest.raises(S.Sod2Error) as e:

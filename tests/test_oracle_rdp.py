@@ -225,7 +225,7 @@ def test_fixed_point_does_not_depend_on_visiting_order(cfg):
     for n_ in r.sorted_nodes():
         op = w.graph.ops[n_]
         if op.kind not in ("Switch", "Combine"):
-            assert not r._forward(op)
+            assert not r._forward(op, n_)
     assert R.dump(r) == before
 
 

@@ -119,9 +119,14 @@ def _draws(seed, spec, n_calls):
 
 
 def encoder(config: int, layers: int, hidden: int, heads: int, ffn: int, dtype: str,
-            batch, seq_range, n_calls: int, final_ln: bool, gated: bool = False,
+            batch, seq_range, n_calls: int, final_ln: bool, gated=False,
             gate_bias: float = None) -> Workload:
-    """Configs 1, 2 and 4: a stack of pre-LN encoder blocks on x[B, L, hidden]."""
+    """Configs 1, 2, 4 and 6: a stack of pre-LN encoder blocks on x[B, L, hidden].
+
+    ``gated=True``: one skip decision per layer and call (<Switch, Combine>, config 4).
+    ``gated="sample"``: one decision per layer and *sequence*; the sequences that run the layer are
+    compacted with NonZero + Gather (an execution-determined batch size), the block runs on the
+    compacted batch, ScatterRows writes its rows back (config 6)."""
     syms = [("L", seq_range[0], seq_range[1])]
     if isinstance(batch, tuple):
         syms = [("B", batch[0], batch[1])] + syms
@@ -133,7 +138,25 @@ def encoder(config: int, layers: int, hidden: int, heads: int, ffn: int, dtype: 
     x = b.input("x", dtype, [bdim, "L", hidden])
     lead = _lead_dims(b, x, 2, "x")
     for l in range(layers):
-        if gated:
+        if gated == "sample":
+            # per-sequence gate: mean over the tokens of a sequence -> Linear -> ReLU -> Linear -> ReLU;
+            # a sequence runs the layer when its gate value is non-zero (logit > 0)
+            m = b.op("ReduceMean", [x], axes=(1,), keepdims=0, dtype="f32", hint=f"g{l}.pool")
+            g1 = b.op("Relu", [_linear(b, w, m, hidden, 64, f"g{l}.fc1", "f32", std=0.5)], hint=f"g{l}.relu")
+            if gate_bias is None:
+                z = _linear(b, w, g1, 64, 1, f"g{l}.fc2", "f32", std=0.25, bias_std=1.0)
+            else:
+                z = _linear(b, w, g1, 64, 1, f"g{l}.fc2", "f32")
+                w.spec[b.g.tensor_id(f"g{l}.fc2.b")] = ("const", float(gate_bias))
+            keep = b.op("Relu", [z], hint=f"g{l}.keep")                          # [B, 1]
+            kv = b.op("Reshape", [keep, b.const(f"g{l}.flat", [-1])], hint=f"g{l}.keepv")   # [B]
+            nz = b.op("NonZero", [kv], dtype="i64", hint=f"g{l}.nz")             # [1, B'] execution determined
+            idx = b.op("Gather", [nz, b.const(f"g{l}.row0", 0)], axis=0, dtype="i64", hint=f"g{l}.idx")   # [B']
+            xs = b.op("Gather", [x, idx], axis=0, hint=f"g{l}.xs")               # [B', L, hidden]
+            lead_s = _lead_dims(b, xs, 2, f"xs{l}")
+            ys = _encoder_layer(b, w, xs, hidden, heads, ffn, f"l{l}", dtype, lead_s)
+            x = b.op("ScatterRows", [x, idx, ys], hint=f"g{l}.merge")
+        elif gated:
             # gate: mean over all token rows -> Linear(hidden,64) -> ReLU -> Linear(64,1) -> sigmoid
             m = b.op("ReduceMean", [x], axes=(0, 1), keepdims=1, dtype="f32", hint=f"g{l}.pool")
             g1 = b.op("Relu", [_linear(b, w, m, hidden, 64, f"g{l}.fc1", "f32")], hint=f"g{l}.relu")
@@ -174,6 +197,14 @@ def config2(n_calls=64, layers=12):
 def config4(n_calls=64, layers=12, gate_bias=None):
     return encoder(4, layers, 768, 12, 3072, "bf16", 4, (128, 384), n_calls, final_ln=True,
                    gated=True, gate_bias=gate_bias)
+
+
+def config6(n_calls=32, layers=12, gate_bias=None):
+    """Config 4 with the decision taken per sequence and the batch compacted: control-flow dynamism
+    that turns into shape dynamism through an execution-determined operator (NonZero).  Not one of
+    the five benchmark configurations; it exercises the EDO class of Table 2 end to end."""
+    return encoder(6, layers, 768, 12, 3072, "bf16", (2, 8), (128, 384), n_calls, final_ln=True,
+                   gated="sample", gate_bias=gate_bias)
 
 
 # ---------------------------------------------------------------------------
@@ -336,4 +367,4 @@ def config5(n_prompts=8, layers=24):
     return decoder(5, layers=layers, n_prompts=n_prompts)
 
 
-BUILDERS = {1: config1, 2: config2, 3: config3, 4: config4}
+BUILDERS = {1: config1, 2: config2, 3: config3, 4: config4, 6: config6}
