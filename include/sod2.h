@@ -213,7 +213,8 @@ sod2_status sod2_run_arena_bytes(const sod2_binding_t*, size_t* arena_bytes, siz
 typedef struct {
   int32_t group;       /* group id */
   int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other,
-                          8 gather, 9 cache append, 10 argmax, 11 fused attention */
+                          8 gather, 9 cache append, 10 argmax, 11 fused attention, 12 nonzero,
+                          13 scatter rows */
   int32_t variant;
   int32_t reserved;
   float ms;            /* event-to-event duration */

@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "device_common.hpp"
 #define SOD2_BF16_TAG 1
 
@@ -758,6 +760,9 @@ __global__ __launch_bounds__(256) void gather_kernel(GatherArgs a) {
   }
 }
 
+template <class I>
+__global__ void gather_rows16_kernel(GatherArgs a, long long row_units);    // wide rows, defined with ScatterRows below
+
 template <class T>
 __global__ __launch_bounds__(256) void append_kernel(AppendArgs a) {
   const long long r = blockIdx.x;
@@ -811,6 +816,14 @@ hipError_t launch_step_advance(int* step, hipStream_t s) {
 
 hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s) {
   if (a.rows <= 0) return hipSuccess;
+  const long long row_bytes = (long long)a.cols * (L.in_dtype == SOD2_BF16_TAG ? 2 : 4);
+  if (!a.add && !a.step && row_bytes >= 4096 && row_bytes % 16 == 0 && (((uintptr_t)a.table | (uintptr_t)a.y) & 15) == 0) {
+    const long long units = row_bytes / 16;
+    dim3 wide((unsigned)std::min<long long>((units + 255) / 256, 64), (unsigned)a.rows);
+    if (a.idx_i32) hipLaunchKernelGGL(gather_rows16_kernel<int>, wide, dim3(256), 0, s, a, units);
+    else hipLaunchKernelGGL(gather_rows16_kernel<long long>, wide, dim3(256), 0, s, a, units);
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)a.rows);
   if (L.in_dtype == SOD2_BF16_TAG) {
     if (a.idx_i32) hipLaunchKernelGGL((gather_kernel<bf16_t, int>), grid, dim3(256), 0, s, a);
@@ -818,6 +831,102 @@ hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s) {
   } else {
     if (a.idx_i32) hipLaunchKernelGGL((gather_kernel<float, int>), grid, dim3(256), 0, s, a);
     else hipLaunchKernelGGL((gather_kernel<float, long long>), grid, dim3(256), 0, s, a);
+  }
+  return hipGetLastError();
+}
+
+// ---------------------------------------------------------------------------------------------
+// NonZero and ScatterRows (execution-determined batch compaction)
+// ---------------------------------------------------------------------------------------------
+template <int KIND>
+__device__ inline bool is_nonzero(const void* x, long long i) {
+  if (KIND == 0) return ((const float*)x)[i] != 0.0f;
+  if (KIND == 1) return (((const unsigned short*)x)[i] & 0x7fff) != 0;     // +0 and -0 are zero
+  if (KIND == 2) return ((const long long*)x)[i] != 0;
+  return ((const int*)x)[i] != 0;
+}
+
+// One workgroup of 256: a counting pass, then a compaction pass in element order (deterministic:
+// positions come from prefix counts, no atomics).
+template <int KIND>
+__global__ __launch_bounds__(256) void nonzero_kernel(NonzeroArgs a) {
+  __shared__ long long wave_n[4];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  long long mine = 0;
+  for (long long i = tid; i < a.n; i += 256) mine += is_nonzero<KIND>(a.x, i) ? 1 : 0;
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+  if (lane == 0) wave_n[wave] = mine;
+  __syncthreads();
+  const long long total = wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
+  __syncthreads();
+  long long run = 0;                                  // non-zeros before the current chunk
+  for (long long c = 0; c < a.n; c += 256) {
+    const long long i = c + tid;
+    const bool f = i < a.n && is_nonzero<KIND>(a.x, i);
+    const unsigned long long m = __ballot(f);
+    if (lane == 0) wave_n[wave] = __popcll(m);
+    __syncthreads();
+    long long pos = run + __popcll(m & ((1ull << lane) - 1));
+    for (int w = 0; w < wave; ++w) pos += wave_n[w];
+    if (f) {
+      long long rem = i;
+      for (int r = a.rank - 1; r >= 0; --r) {
+        a.out[(long long)r * total + pos] = rem % a.dims[r];
+        rem /= a.dims[r];
+      }
+    }
+    run += wave_n[0] + wave_n[1] + wave_n[2] + wave_n[3];
+    __syncthreads();
+  }
+  if (tid == 0) *a.count = total;
+}
+
+hipError_t launch_nonzero(const NonzeroArgs& a, hipStream_t s) {
+  switch (a.x_kind) {
+    case 0: hipLaunchKernelGGL(nonzero_kernel<0>, dim3(1), dim3(256), 0, s, a); break;
+    case 1: hipLaunchKernelGGL(nonzero_kernel<1>, dim3(1), dim3(256), 0, s, a); break;
+    case 2: hipLaunchKernelGGL(nonzero_kernel<2>, dim3(1), dim3(256), 0, s, a); break;
+    default: hipLaunchKernelGGL(nonzero_kernel<3>, dim3(1), dim3(256), 0, s, a); break;
+  }
+  return hipGetLastError();
+}
+
+// V: the unit a row is copied in (16 bytes when rows and pointers allow it, else one element)
+template <class V, class I>
+__global__ __launch_bounds__(256) void scatter_rows_kernel(ScatterArgs a, long long row_units) {
+  const long long b = blockIdx.y;
+  long long m = -1;
+  for (long long j = 0; j < a.n; ++j) if ((long long)((const I*)a.idx)[j] == b) m = j;
+  const V* src = m >= 0 ? (const V*)a.y + m * row_units : (const V*)a.x + b * row_units;
+  V* dst = (V*)a.out + b * row_units;
+  for (long long u = (long long)blockIdx.x * 256 + threadIdx.x; u < row_units; u += (long long)gridDim.x * 256) dst[u] = src[u];
+}
+
+// rows of a wide table picked by index, copied in 16-byte units by several workgroups per row
+template <class I>
+__global__ __launch_bounds__(256) void gather_rows16_kernel(GatherArgs a, long long row_units) {
+  long long id = (long long)((const I*)a.idx)[blockIdx.y];
+  id = id < 0 ? 0 : (id >= a.table_rows ? a.table_rows - 1 : id);
+  const uint4* src = (const uint4*)a.table + id * row_units;
+  uint4* dst = (uint4*)a.y + (long long)blockIdx.y * row_units;
+  for (long long u = (long long)blockIdx.x * 256 + threadIdx.x; u < row_units; u += (long long)gridDim.x * 256) dst[u] = src[u];
+}
+
+hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s) {
+  if (a.rows <= 0 || a.cols <= 0) return hipSuccess;
+  const long long eb = L.out_dtype == SOD2_BF16_TAG ? 2 : 4, row_bytes = a.cols * eb;
+  const bool v16 = row_bytes % 16 == 0 && (((uintptr_t)a.x | (uintptr_t)a.y | (uintptr_t)a.out) & 15) == 0;
+  const long long units = v16 ? row_bytes / 16 : a.cols;
+  dim3 grid((unsigned)std::min<long long>((units + 255) / 256, 64), (unsigned)a.rows);
+  if (v16) {
+    if (a.idx_i32) hipLaunchKernelGGL((scatter_rows_kernel<uint4, int>), grid, dim3(256), 0, s, a, units);
+    else hipLaunchKernelGGL((scatter_rows_kernel<uint4, long long>), grid, dim3(256), 0, s, a, units);
+  } else if (eb == 2) {
+    if (a.idx_i32) hipLaunchKernelGGL((scatter_rows_kernel<unsigned short, int>), grid, dim3(256), 0, s, a, units);
+    else hipLaunchKernelGGL((scatter_rows_kernel<unsigned short, long long>), grid, dim3(256), 0, s, a, units);
+  } else {
+    if (a.idx_i32) hipLaunchKernelGGL((scatter_rows_kernel<unsigned, int>), grid, dim3(256), 0, s, a, units);
+    else hipLaunchKernelGGL((scatter_rows_kernel<unsigned, long long>), grid, dim3(256), 0, s, a, units);
   }
   return hipGetLastError();
 }

@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -130,6 +130,24 @@ struct AttnArgs {
   int lk_step;
 };
 
+// NonZero (Table 2's EDO class): out[r, j] = r-th coordinate of the j-th non-zero element of x in
+// row-major order, rows of `count` entries; the count goes to *count (8 bytes behind the indices'
+// upper-bound storage).  One workgroup; x has n elements and rank <= 4.
+struct NonzeroArgs {
+  const void* x; long long* out; long long* count;
+  long long n;
+  int rank, x_kind;          // x_kind: 0 f32, 1 bf16, 2 i64, 3 i32
+  long long dims[4];
+};
+
+// out = x with the rows idx[j] replaced by y[j] (j < n; the last j wins on duplicates); rows of
+// `cols` elements, everything dense
+struct ScatterArgs {
+  const void* x; const void* idx; const void* y; void* out;
+  long long rows, n, cols;
+  int idx_i32;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -147,11 +165,14 @@ struct Launch {
     AppendArgs append;
     ArgmaxArgs argmax;
     AttnArgs attn;
+    NonzeroArgs nz;
+    ScatterArgs scatter;
   } u;
   bool is_layernorm = false;
   double flops = 0, bytes = 0;
   long long d_past = 0;    // replay: rows the CacheAppend position / keys the attention length gain per step
   int d_lk = 0;
+  bool empty = false;      // the group's result has no elements: nothing is launched
   Launch() { std::memset(&u, 0, sizeof u); }
 };
 

@@ -18,6 +18,8 @@ hipError_t launch_eltwise(const Launch& L, const EltArgs& a, hipStream_t s);
 hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s);
 hipError_t launch_append(const Launch& L, const AppendArgs& a, hipStream_t s);
 hipError_t launch_argmax(const Launch& L, const ArgmaxArgs& a, hipStream_t s);
+hipError_t launch_nonzero(const NonzeroArgs& a, hipStream_t s);
+hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
 
@@ -574,12 +576,15 @@ struct Builder {
     const Op& op = G.ops[gr.chain[0]];
     const View &vt = view_of(op.in[0]), &vi = view_of(op.in[1]);
     int dt = G.tensors[op.in[0]].dtype, it = G.tensors[op.in[1]].dtype;
-    if (vt.dims.size() != 2 || !vt.contiguous() || vi.dims.size() != 1 || !vi.contiguous() || !is_int(it) ||
+    if (vt.dims.size() < 2 || !vt.contiguous() || vi.dims.size() != 1 || !vi.contiguous() || !is_int(it) ||
         (!op.ia.empty() && op.ia[0] != 0) || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt)
-      throw Error(SOD2_ERR_UNSUPPORTED, "Gather kernel: rows of a contiguous rank-2 float table by a rank-1 index tensor");
+      throw Error(SOD2_ERR_UNSUPPORTED, "Gather kernel: leading-dim slices of a contiguous float tensor by a rank-1 index tensor");
     GatherArgs a{};
+    int64_t slice = 1;                                 // elements of one slice table[i, ...]
+    for (size_t k = 1; k < vt.dims.size(); ++k) slice *= vt.dims[k];
+    if (slice > 0x7fffffff) throw Error(SOD2_ERR_UNSUPPORTED, "Gather kernel: slice too large");
     a.rows = vi.dims[0];
-    a.cols = (int)vt.dims[1];
+    a.cols = (int)slice;
     a.table_rows = vt.dims[0];
     a.idx_i32 = it == SOD2_I32;
     L.in_dtype = L.out_dtype = dt;
@@ -738,8 +743,74 @@ struct Builder {
     return L;
   }
 
+  // NonZero: indices [rank, count] into the upper-bound storage, the count behind them
+  Launch nonzero(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_NONZERO;
+    const Op& op = G.ops[gr.ops[0]];
+    const View& vx = view_of(op.in[0]);
+    int dt = G.tensors[op.in[0]].dtype;
+    if (!vx.contiguous() || vx.dims.size() > 4 || G.tensors[gr.out].dtype != SOD2_I64)
+      throw Error(SOD2_ERR_UNSUPPORTED, "NonZero kernel: a contiguous tensor of rank <= 4, int64 result");
+    if (!b.tensors.count(gr.out))                      // a caller buffer has no room for the count
+      throw Error(SOD2_ERR_UNSUPPORTED, "the result of NonZero must be an intermediate tensor (read it through a Gather or Cast)");
+    NonzeroArgs a{};
+    a.rank = (int)vx.dims.size();
+    a.n = 1;
+    for (int k = 0; k < a.rank; ++k) { a.dims[k] = vx.dims[k]; a.n *= vx.dims[k]; }
+    a.x_kind = dt == SOD2_F32 ? 0 : (dt == SOD2_BF16 ? 1 : (dt == SOD2_I64 ? 2 : 3));
+    L.in_dtype = dt;
+    L.out_dtype = SOD2_I64;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_t(gr.out);
+    L.r[2] = L.r[1];                                   // the count: behind rank x upper bound indices
+    L.r[2].byte_off += (int64_t)a.rank * a.n * 8;
+    L.u.nz = a;
+    L.bytes = (double)a.n * dtype_bytes(dt);
+    return L;
+  }
+
+  Launch scatter(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_SCATTER;
+    const Op& op = G.ops[gr.ops[0]];
+    const View &vx = view_of(op.in[0]), &vi = view_of(op.in[1]), &vy = view_of(op.in[2]);
+    int dt = G.tensors[op.in[0]].dtype, it = G.tensors[op.in[1]].dtype;
+    bool same_tail = vx.dims.size() == vy.dims.size() && vx.dims.size() >= 1;
+    for (size_t k = 1; same_tail && k < vx.dims.size(); ++k) same_tail = vx.dims[k] == vy.dims[k];
+    if (!same_tail || !vx.contiguous() || !vy.contiguous() || vi.dims.size() != 1 || !vi.contiguous() || !is_int(it) ||
+        vy.dims[0] != vi.dims[0] || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[op.in[2]].dtype != dt ||
+        G.tensors[gr.out].dtype != dt)
+      throw Error(SOD2_ERR_UNSUPPORTED, "ScatterRows kernel: contiguous float tensors x[rows, ...], y[n, ...] and a rank-1 index tensor of n entries");
+    ScatterArgs a{};
+    a.rows = vx.dims[0];
+    a.n = vi.dims[0];
+    a.cols = 1;
+    for (size_t k = 1; k < vx.dims.size(); ++k) a.cols *= vx.dims[k];
+    a.idx_i32 = it == SOD2_I32;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_of(vi, it);
+    L.r[2] = ref_of(vy, dt);
+    L.r[3] = ref_t(gr.out);
+    L.u.scatter = a;
+    L.bytes = 2.0 * a.rows * a.cols * dtype_bytes(dt);
+    return L;
+  }
+
   Launch make(const Group& gr) {
+    // a result without elements (an empty compacted batch): nothing to compute
+    auto od = b.dims.find(gr.out);
+    if (od != b.dims.end()) {
+      int64_t n = 1;
+      for (int64_t d : od->second) n *= d;
+      if (n == 0 && gr.kind != G_NONZERO) { Launch L; L.group = gr.gid; L.kernel = K_OTHER; L.empty = true; return L; }
+    }
     switch (gr.kind) {
+      case G_NONZERO: return nonzero(gr);
+      case G_SCATTER: return scatter(gr);
       case G_ATTENTION: return attention(gr);
       case G_GATHER: return gather(gr);
       case G_CACHEAPPEND: return append(gr);
@@ -787,7 +858,18 @@ int tune_group_m() {
 }
 
 hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
+  if (L.empty) return hipSuccess;
   switch (L.kernel) {
+    case K_NONZERO: {
+      NonzeroArgs a = L.u.nz;
+      a.x = P.at(L.r[0]); a.out = (long long*)P.at(L.r[1]); a.count = (long long*)P.at(L.r[2]);
+      return launch_nonzero(a, s);
+    }
+    case K_SCATTER: {
+      ScatterArgs a = L.u.scatter;
+      a.x = P.at(L.r[0]); a.idx = P.at(L.r[1]); a.y = P.at(L.r[2]); a.out = P.at(L.r[3]);
+      return launch_scatter(L, a, s);
+    }
     case K_GEMM: {
       GemmArgs g = L.u.gemm;
       g.A = P.at(L.r[0]); g.B = P.at(L.r[1]); g.C = P.at(L.r[2]);
@@ -877,13 +959,16 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
   }
 }
 
-// launch table for every executed group step of `b`, indexed by step (-1 kernel for control steps)
-std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force_variant, int force_splits) {
+// launch table for every executed group step of `b`, indexed by step (-1 kernel for control steps);
+// steps before `first_step` (already run when a plan is rebuilt in mid-run) are left unbuilt (-2)
+std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force_variant, int force_splits,
+                                   size_t first_step = 0) {
   Builder B(p, b, force_variant);
   B.force_splits = force_splits;
   std::vector<Launch> out;
-  for (int i : b.steps) {
-    const Item& it = p.items[i];
+  for (size_t k = 0; k < b.steps.size(); ++k) {
+    const Item& it = p.items[b.steps[k]];
+    if (k < first_step) { Launch L; L.kernel = -2; L.group = it.ref; out.push_back(L); continue; }
     if (!it.is_group) { Launch L; L.kernel = -1; L.group = it.ref; out.push_back(L); continue; }
     out.push_back(B.make(p.groups.at(it.ref)));
   }
@@ -1091,8 +1176,25 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
     BindResult replanned;
     std::vector<Launch> relaunch;
     std::vector<int> decisions = h->planned_decisions;
+    std::vector<int64_t> exec_values = h->planned_exec;
+    h->last_exec.clear();
     std::map<int, int64_t> used_offset;             // arena tensor -> offset used by an executed kernel
-    size_t k = 0;
+    // an execution-determined fact (a Switch decision, a NonZero count) has just become known at
+    // step k: plan what follows with it (Section 4.3) and build the launches of the remaining steps
+    auto replan = [&](size_t k, const char* what) {
+      replanned = bind_plan(p, h->symbols, decisions, true, exec_values);
+      if ((size_t)replanned.arena_bytes > arena_bytes) {
+        h->executed = replanned;               // sod2_run_arena_bytes now reports what this path needs
+        h->has_executed = true;
+        throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, the path taken needs " +
+                                                  std::to_string(replanned.arena_bytes) + "; nothing after the " + what + " was launched");
+      }
+      relaunch = build_launches(p, replanned, h->force_variant, h->force_splits, k + 1);
+      P.ws = workspace_for(replanned.arena_bytes);
+      cur = &replanned;
+      launches = &relaunch;
+    };
+    size_t k = 0, n_nz = 0;
     while (k < cur->steps.size()) {
       const Item& it = p.items[cur->steps[k]];
       const Launch& L = (*launches)[k];
@@ -1103,6 +1205,24 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
         hipError_t e = dispatch(L, P, s);
         if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
         if (ev) { (void)hipEventRecord(ev[n_ev + 1], s); timed.push_back({n_ev, L}); n_ev += 2; }
+        if (L.kernel == K_NONZERO) {
+          // the extent is execution determined: read the count back, then size and plan what follows
+          long long count = -1;
+          void* slot = P.at(L.r[2]);
+          e = hipMemcpyAsync(&count, slot, 8, hipMemcpyDeviceToHost, s);
+          if (e == hipSuccess) e = hipStreamSynchronize(s);
+          if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("NonZero count read failed: ") + hipGetErrorString(e));
+          if (count < 0 || count > L.u.nz.n) throw Error(SOD2_ERR_HIP, "NonZero kernel reported an impossible count");
+          h->last_exec.push_back(count);
+          if (n_nz >= exec_values.size()) {
+            exec_values.push_back(count);
+            replan(k, "NonZero");
+          } else if (exec_values[n_nz] != count) {
+            throw Error(SOD2_ERR_INVALID_ARG, "the binding was planned for a NonZero count of " + std::to_string(exec_values[n_nz]) +
+                                                  ", the run found " + std::to_string(count));
+          }
+          ++n_nz;
+        }
       } else if (G.ops[it.ref].kind == SOD2_OP_SWITCH) {
         // position of this Switch among the executed ones
         size_t which = std::find(cur->switch_order.begin(), cur->switch_order.end(), it.ref) - cur->switch_order.begin();
@@ -1126,17 +1246,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
             dec = hv > (float)op.fa ? 1 : 0;
           }
           decisions.push_back(dec);
-          replanned = bind_plan(p, h->symbols, decisions, true);
-          if ((size_t)replanned.arena_bytes > arena_bytes) {
-            h->executed = replanned;           // sod2_run_arena_bytes now reports what this path needs
-            h->has_executed = true;
-            throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, the path taken needs " +
-                                                      std::to_string(replanned.arena_bytes) + "; nothing after the Switch was launched");
-          }
-          relaunch = build_launches(p, replanned, h->force_variant, h->force_splits);
-          P.ws = workspace_for(replanned.arena_bytes);
-          cur = &replanned;
-          launches = &relaunch;
+          replan(k, "Switch");
         }
       }
       ++k;
