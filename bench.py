@@ -171,14 +171,15 @@ def main():
 
     # ---- timed region: exactly `steps` calls, each synchronised (a latency, not a pipelined rate)
     torch.cuda.synchronize()
-    lat, arena_mb = [], []
+    lat, arena_mb, kept = [], [], []
     del enqueue_ms[:]
     t_begin = time.perf_counter()
     for ci, sym, ins, outs in timed:
         t1 = time.perf_counter()
         b = one_call(sym, ins, outs)
         lat.append((time.perf_counter() - t1) * 1e3)
-        arena_mb.append(S.sod2_binding_arena_bytes(b)[0] / 2 ** 20)
+        arena_mb.append(S.sod2_run_arena_bytes(b)[0] / 2 ** 20)       # the executed plan (== the bound one without control flow)
+        kept.append(S.sod2_run_exec_values(b))
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t_begin
     ms_per_step = total_s * 1e3 / len(timed)
@@ -293,7 +294,9 @@ def main():
             2: "12-layer pre-LN encoder, hidden 768, 12 heads, FFN 3072 GELU, bf16 storage / fp32 accumulate, "
                "B in [1,8] and L in [32,512] redrawn per call",
             3: "ResNet-50 layout NHWC bf16, batch 1, H=W in {224..640 step 32}",
-            4: "config 2 with per-layer skip gates, batch 4, L in [128,384]"}[args.config],
+            4: "config 2 with per-layer skip gates, batch 4, L in [128,384]",
+            6: "config 2's encoder with a skip gate per layer and sequence: kept sequences compacted by "
+               "NonZero + Gather (execution-determined batch), ScatterRows back; B in [2,8], L in [128,384]"}[args.config],
             "calls": len(timed), "tokens": tokens},
         "latency_ms": {"mean": round(sum(lat) / len(lat), 4), "min": round(min(lat), 4), "max": round(max(lat), 4)},
         "pipelined_ms_per_step": round(pipelined_ms, 4),
@@ -304,6 +307,8 @@ def main():
         "peak_arena_mb": {"min": round(min(arena_mb), 3), "max": round(max(arena_mb), 3),
                           "mean": round(sum(arena_mb) / len(arena_mb), 3)},
         "weight_mb": round(weight_bytes / 2 ** 20, 1),
+        **({"kept_fraction": round(sum(sum(k) for k in kept) / max(sum(len(k) * c[1]["B"] for k, c in zip(kept, timed)), 1), 3)}
+           if any(kept) else {}),
         "tokens_per_s": round(tokens / total_s, 1),
         "roofline": roofline,
         "kernels": kernels,

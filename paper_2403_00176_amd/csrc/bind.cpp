@@ -198,9 +198,10 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
   for (auto& kv : b.tensors) {
     kv.second.end = std::max(kv.second.start, reads_at[kv.first]);
   }
-  for (int t = 0; t < (int)G.tensors.size(); ++t) {
+  b.dyn_base.assign(nt, -1);
+  for (int t = 0; t < nt; ++t) {
     int pr = G.producer[t];
-    if (pr < 0 || p.folded[pr] || b.dead_ops.count(pr)) continue;
+    if (pr < 0 || p.folded[pr] || (!b.dead_ops.empty() && b.dead_ops.count(pr))) continue;
     auto d = info(t);
     if (!d.first) b.dyn_base[t] = d.second;
   }
@@ -214,12 +215,18 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
 
   std::vector<const ArenaTensor*> placed;
   if (p.opts.dmp) {
+    std::vector<ArenaTensor*> by_start;                // every sub-graph takes its tensors from the front
+    for (auto& kv : b.tensors) by_start.push_back(&kv.second);
+    std::stable_sort(by_start.begin(), by_start.end(), [](const ArenaTensor* x, const ArenaTensor* y) { return x->start < y->start; });
+    size_t next_t = 0;
     int k0 = 0;
     while (k0 < nsteps) {
       int k1 = k0;
       while (k1 + 1 < nsteps && b.step_sg[k1 + 1] == b.step_sg[k0]) ++k1;
+      // a tensor that ended before this sub-graph starts can no longer intersect anything placed from here on
+      placed.erase(std::remove_if(placed.begin(), placed.end(), [k0](const ArenaTensor* a) { return a->end < k0; }), placed.end());
       std::vector<ArenaTensor*> mine;
-      for (auto& kv : b.tensors) if (kv.second.start >= k0 && kv.second.start <= k1) mine.push_back(&kv.second);
+      while (next_t < by_start.size() && by_start[next_t]->start <= k1) mine.push_back(by_start[next_t++]);
       if (!mine.empty()) {
         int pk = k0;
         for (int k = k0; k <= k1; ++k) if (live_bytes[k] > live_bytes[pk]) pk = k;

@@ -220,7 +220,7 @@ struct BindResult {
   std::vector<int> switch_order;                   // executed Switch operators in order
   std::map<int, ArenaTensor> tensors;
   std::map<int, std::vector<int64_t>> dims;        // outputs of executed groups
-  std::map<int, int> dyn_base;                     // executed tensor -> tensor providing storage
+  std::vector<int> dyn_base;                       // per tensor: the tensor providing its storage, -1 when not executed
   std::set<int> dead_ops;
   std::map<int, std::pair<int64_t, int64_t>> session;   // session input -> (offset, bytes) at the arena bottom
   std::map<int, int> session_root;                 // session tensor -> the session input whose slot it occupies

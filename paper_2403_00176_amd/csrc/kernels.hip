@@ -688,6 +688,34 @@ __global__ __launch_bounds__(256) void reduce_mean_kernel(ReduceArgs a) {
   }
 }
 
+// The same for bf16 rows of a multiple of 8 channels: a lane owns 8 channels (16-byte loads), 16
+// waves split the rows so that every wave has only a few independent loads in flight.
+template <class TO>
+__global__ __launch_bounds__(1024) void reduce_mean_bf16x8_kernel(ReduceArgs a) {
+  __shared__ float part[16][512];
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  const int c0 = (blockIdx.x * 64 + lane) * 8, b = blockIdx.y;
+  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  if (c0 < a.C) {
+    const bf16_t* x = (const bf16_t*)a.x + (long long)b * a.R * a.C + c0;
+    for (long long r = w; r < a.R; r += 16) {
+      V16 v; v.u = *(const uint4*)(x + r * a.C);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) s[e] += bf2f(v.h[e]);
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) part[w][lane * 8 + e] = s[e];
+  __syncthreads();
+  const int t = threadIdx.x, c = blockIdx.x * 512 + t;
+  if (t < 512 && c < a.C) {
+    float tot = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) tot += part[k][t];
+    ((TO*)a.y)[(long long)b * a.C + c] = from_f<TO>(tot / (float)a.R);
+  }
+}
+
 template <class T>
 __global__ void maxpool_kernel(PoolArgs p) {
   long long idx = (long long)blockIdx.x * blockDim.x + threadIdx.x;
@@ -999,8 +1027,63 @@ hipError_t launch_conv_dl(const ConvArgs& c, const GemmArgs& g, int tile, hipStr
 hipError_t launch_gemv(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_ln(const GemmArgs& g, hipStream_t s);
 
+// fp32 contraction with at most 8 rows (the gate networks of the control-flow graphs): one wave per
+// output column, the lanes split k in 16-byte chunks of B[n, :], a shuffle tree finishes the sums
+template <int MR>
+__global__ __launch_bounds__(256) void gemv_f32_kernel(GemmArgs g) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = blockIdx.x * 4 + wave;
+  const int b0 = blockIdx.y / g.nb1, b1 = blockIdx.y % g.nb1;
+  if (n >= g.N) return;
+  const float* A = (const float*)g.A + b0 * g.a_sb0 + b1 * g.a_sb1;
+  const float* B = (const float*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1 + (long long)n * g.b_sn;
+  float acc[MR];
+#pragma unroll
+  for (int m = 0; m < MR; ++m) acc[m] = 0.f;
+  const int nchunk = g.K >> 2;
+  for (int c = lane; c < nchunk; c += 64) {
+    const float4 w = *(const float4*)(B + c * 4);
+#pragma unroll
+    for (int m = 0; m < MR; ++m) {
+      if (m < g.M) {
+        const float4 a = *(const float4*)(A + (long long)m * g.a_sm + c * 4);
+        acc[m] = fmaf(a.x, w.x, fmaf(a.y, w.y, fmaf(a.z, w.z, fmaf(a.w, w.w, acc[m]))));
+      }
+    }
+  }
+#pragma unroll
+  for (int m = 0; m < MR; ++m) acc[m] = wave_sum(acc[m]);
+  if (lane == 0) {
+    const float bv = g.bias ? ((const float*)g.bias)[n] : 0.f;
+    float* Cp = (float*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
+    const float* Rp = g.res ? (const float*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
+#pragma unroll
+    for (int m = 0; m < MR; ++m) {
+      if (m < g.M) {
+        float v = apply_act(acc[m] * g.scale + bv, g.act1);
+        if (Rp) v = apply_act(v + Rp[(long long)m * g.r_sm + (long long)n * g.r_sn], g.act2);
+        Cp[(long long)m * g.c_sm + (long long)n * g.c_sn] = v;
+      }
+    }
+  }
+}
+
+static bool gemv_f32_ok(const Launch& L, const GemmArgs& g) {
+  auto al = [](const void* p) { return ((uintptr_t)p & 15) == 0; };
+  return L.in_dtype != SOD2_BF16_TAG && L.out_dtype != SOD2_BF16_TAG && L.variant == V_GEMV && g.M <= 8 &&
+         g.a_sk == 1 && g.b_sk == 1 && g.K % 4 == 0 && g.a_sm % 4 == 0 && g.b_sn % 4 == 0 && g.a_sb0 % 4 == 0 &&
+         g.a_sb1 % 4 == 0 && g.b_sb0 % 4 == 0 && g.b_sb1 % 4 == 0 && al(g.A) && al(g.B);
+}
+
 hipError_t launch_gemm(const Launch& L, const GemmArgs& g, hipStream_t s) {
   if (g.ln_gamma) return L.in_dtype == SOD2_BF16_TAG ? launch_gemm_ln(g, s) : hipErrorInvalidValue;
+  if (gemv_f32_ok(L, g)) {
+    dim3 grid((g.N + 3) / 4, g.nb0 * g.nb1);
+    if (g.M <= 1) hipLaunchKernelGGL(gemv_f32_kernel<1>, grid, dim3(256), 0, s, g);
+    else if (g.M <= 4) hipLaunchKernelGGL(gemv_f32_kernel<4>, grid, dim3(256), 0, s, g);
+    else hipLaunchKernelGGL(gemv_f32_kernel<8>, grid, dim3(256), 0, s, g);
+    return hipGetLastError();
+  }
   if (L.variant == V_GEMV && L.in_dtype == SOD2_BF16_TAG && g.a_vec && g.b_mode == 0 && g.M <= 8) return launch_gemv(g, s);
   if (L.variant >= V_DL0 && L.in_dtype == SOD2_BF16_TAG && g.a_vec && g.b_mode == 0)
     return launch_gemm_dl(g, L.variant - V_DL0, s);
@@ -1069,8 +1152,14 @@ hipError_t launch_row(const Launch& L, const RowArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s) {
-  dim3 grid((a.C + 63) / 64, a.batch);
   bool ib = L.in_dtype == SOD2_BF16_TAG, ob = L.out_dtype == SOD2_BF16_TAG;
+  if (ib && a.C % 8 == 0 && ((uintptr_t)a.x & 15) == 0 && a.R >= 64) {
+    dim3 wide((a.C + 511) / 512, a.batch);
+    if (ob) hipLaunchKernelGGL(reduce_mean_bf16x8_kernel<bf16_t>, wide, dim3(1024), 0, s, a);
+    else hipLaunchKernelGGL(reduce_mean_bf16x8_kernel<float>, wide, dim3(1024), 0, s, a);
+    return hipGetLastError();
+  }
+  dim3 grid((a.C + 63) / 64, a.batch);
   if (ib && ob) hipLaunchKernelGGL((reduce_mean_kernel<bf16_t, bf16_t>), grid, dim3(256), 0, s, a);
   else if (ib) hipLaunchKernelGGL((reduce_mean_kernel<bf16_t, float>), grid, dim3(256), 0, s, a);
   else if (ob) hipLaunchKernelGGL((reduce_mean_kernel<float, bf16_t>), grid, dim3(256), 0, s, a);

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstring>
 #include <functional>
+#include <memory>
 
 #include "handles.hpp"
 
@@ -110,7 +111,7 @@ struct Builder {
   }
   bool live(int t) const {
     int pr = G.producer[t];
-    return pr < 0 || p.folded[pr] || b.dyn_base.count(t) > 0;
+    return pr < 0 || p.folded[pr] || b.dyn_base[t] >= 0;
   }
 
   const View& view_of(int t) {
@@ -225,7 +226,7 @@ struct Builder {
   // and two workgroups per CU otherwise); below that the 64 x 64 x 64 tile with a four-stage ring
   // puts more workgroups (more loads in flight) on the chip.
   int pick_variant(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch) const {
-    if (dtype != SOD2_BF16) return V_SIMPLE;
+    if (dtype != SOD2_BF16) return (M <= 8 && force_variant != V_SIMPLE && p.opts.mvc) ? V_GEMV : V_SIMPLE;   // fp32: plain FMA kernels
     if (force_variant >= 0) return force_variant;
     if (!p.opts.mvc) return V_REGULAR;
     if (M <= 8) return V_GEMV;                     // decode shape: weight streaming, one wave per column
@@ -980,6 +981,17 @@ std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force
 
 using namespace sod2;
 
+// Pinned host memory that receives the few bytes read back at a Switch or after a NonZero: one slot
+// per host thread, allocated on first use and kept until the process ends.
+static void* readback_slot() {
+  static thread_local void* slot = nullptr;
+  if (!slot && hipHostMalloc(&slot, 64, hipHostMallocDefault) != hipSuccess) {
+    slot = nullptr;
+    throw Error(SOD2_ERR_HIP, "pinned host memory for read-backs could not be allocated");
+  }
+  return slot;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Replay: the launch sequence of one step captured in a HIP graph; the quantities that change from
 // step to step are read by the kernels from a step counter in device memory
@@ -1179,6 +1191,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
     std::vector<int64_t> exec_values = h->planned_exec;
     h->last_exec.clear();
     std::map<int, int64_t> used_offset;             // arena tensor -> offset used by an executed kernel
+    std::unique_ptr<Builder> lazy;                  // builds the launches of `replanned` on demand
     // an execution-determined fact (a Switch decision, a NonZero count) has just become known at
     // step k: plan what follows with it (Section 4.3) and build the launches of the remaining steps
     auto replan = [&](size_t k, const char* what) {
@@ -1189,15 +1202,28 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
         throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, the path taken needs " +
                                                   std::to_string(replanned.arena_bytes) + "; nothing after the " + what + " was launched");
       }
-      relaunch = build_launches(p, replanned, h->force_variant, h->force_splits, k + 1);
+      // launches of the new plan are built one by one as the run reaches them (another fact may
+      // arrive before most of them are needed)
+      relaunch.clear();
+      for (size_t j = 0; j < replanned.steps.size(); ++j) {
+        const Item& it = p.items[replanned.steps[j]];
+        Launch L;
+        L.kernel = it.is_group ? -2 : -1;
+        L.group = it.ref;
+        relaunch.push_back(L);
+      }
+      lazy.reset(new Builder(p, replanned, h->force_variant));
+      lazy->force_splits = h->force_splits;
       P.ws = workspace_for(replanned.arena_bytes);
       cur = &replanned;
       launches = &relaunch;
     };
     size_t k = 0, n_nz = 0;
+    bool assumed = false;                           // a fact confirmed what the plan in use had assumed
     while (k < cur->steps.size()) {
       const Item& it = p.items[cur->steps[k]];
-      const Launch& L = (*launches)[k];
+      if (it.is_group && (*launches)[k].kernel == -2) relaunch[k] = lazy->make(p.groups.at(it.ref));
+      const Launch L = (*launches)[k];                // a copy: a re-plan below rebuilds the table
       if (it.is_group) {
         auto at = cur->tensors.find(p.groups.at(it.ref).out);
         if (at != cur->tensors.end()) used_offset[at->first] = at->second.offset;
@@ -1207,16 +1233,20 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
         if (ev) { (void)hipEventRecord(ev[n_ev + 1], s); timed.push_back({n_ev, L}); n_ev += 2; }
         if (L.kernel == K_NONZERO) {
           // the extent is execution determined: read the count back, then size and plan what follows
-          long long count = -1;
           void* slot = P.at(L.r[2]);
-          e = hipMemcpyAsync(&count, slot, 8, hipMemcpyDeviceToHost, s);
+          long long* host = (long long*)readback_slot();
+          *host = -1;
+          e = hipMemcpyAsync(host, slot, 8, hipMemcpyDeviceToHost, s);
           if (e == hipSuccess) e = hipStreamSynchronize(s);
           if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("NonZero count read failed: ") + hipGetErrorString(e));
+          const long long count = *host;
           if (count < 0 || count > L.u.nz.n) throw Error(SOD2_ERR_HIP, "NonZero kernel reported an impossible count");
           h->last_exec.push_back(count);
           if (n_nz >= exec_values.size()) {
             exec_values.push_back(count);
-            replan(k, "NonZero");
+            // the current plan assumed the upper bound: a count equal to it changes nothing
+            if (count != L.u.nz.n) replan(k, "NonZero");
+            else assumed = true;
           } else if (exec_values[n_nz] != count) {
             throw Error(SOD2_ERR_INVALID_ARG, "the binding was planned for a NonZero count of " + std::to_string(exec_values[n_nz]) +
                                                   ", the run found " + std::to_string(count));
@@ -1236,20 +1266,28 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
             Builder B(p, *cur, h->force_variant);
             Ref r = B.ref_t(op.in[1]);
             float hv = 0.f;
-            uint16_t hb = 0;
+            void* host = readback_slot();
             int dt = G.tensors[op.in[1]].dtype;
-            hipError_t e = dt == SOD2_BF16 ? hipMemcpyAsync(&hb, P.at(r), 2, hipMemcpyDeviceToHost, s)
-                                           : hipMemcpyAsync(&hv, P.at(r), 4, hipMemcpyDeviceToHost, s);
+            hipError_t e = hipMemcpyAsync(host, P.at(r), dt == SOD2_BF16 ? 2 : 4, hipMemcpyDeviceToHost, s);
             if (e == hipSuccess) e = hipStreamSynchronize(s);
             if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("predicate read failed: ") + hipGetErrorString(e));
-            if (dt == SOD2_BF16) { uint32_t u = (uint32_t)hb << 16; std::memcpy(&hv, &u, 4); }
+            if (dt == SOD2_BF16) { uint32_t u = (uint32_t)(*(uint16_t*)host) << 16; std::memcpy(&hv, &u, 4); }
+            else std::memcpy(&hv, host, 4);
             dec = hv > (float)op.fa ? 1 : 0;
           }
           decisions.push_back(dec);
-          replan(k, "Switch");
+          // the current plan assumed that the layer runs: only the other outcome changes it
+          if (dec != 0) replan(k, "Switch");
+          else assumed = true;
         }
       }
       ++k;
+    }
+    if (assumed) {
+      // same steps and offsets as the plan in use; computed again only so that the executed plan
+      // reports every fact as known (the kernels are already enqueued: this overlaps their execution)
+      replanned = bind_plan(p, h->symbols, decisions, true, exec_values);
+      cur = &replanned;
     }
     for (int sw : cur->switch_order) h->last_decisions.push_back(cur->decisions.at(sw));
     for (const auto& kv : used_offset) {
