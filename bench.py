@@ -16,6 +16,54 @@ PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA
 PEAK_HBM_GBS = 8000.0
 
 
+def bench_ablation(args, S, dev):
+    """The paper's optimisation breakdown (Figs. 5 and 6: latency and memory as RDP-enabled fusion, static
+    execution planning, dynamic memory planning and multi-version kernels are switched on one after the
+    other) on the synthetic workload: same calls, same weights, one Session per setting."""
+    import torch
+    from paper_2403_00176_amd.session import Session
+    from workloads import configs
+    w = configs.BUILDERS[args.config](n_calls=args.steps + args.warmup)
+    W = w.make_weights()
+    stages = [("none", dict(fusion=0, sep=0, dmp=0, mvc=0)), ("+fusion", dict(fusion=1, sep=0, dmp=0, mvc=0)),
+              ("+sep", dict(fusion=1, sep=1, dmp=0, mvc=0)), ("+dmp", dict(fusion=1, sep=1, dmp=1, mvc=0)),
+              ("+mvc", dict(fusion=1, sep=1, dmp=1, mvc=1))]
+    rows = {}
+    for name, opts in stages:
+        ses = Session(w.graph, device=dev, **opts)
+        ses.upload_weights(W)
+        calls, max_arena = [], 0
+        for ci in range(args.steps + args.warmup):
+            sym = w.calls[ci]
+            b = ses.bind(sym)
+            max_arena = max(max_arena, S.sod2_binding_arena_bytes(b)[0])
+            calls.append((sym, ses.upload_inputs(w.make_inputs(ci, sym)), ses.alloc_outputs(ses.output_shapes(b))))
+        ses.ensure_arena(max_arena)
+        lat, arena, steps = [], [], []
+        for k, (sym, ins, outs) in enumerate(calls):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            b = ses.bind(sym)
+            ses.run(b, ins, outs)
+            ses.stream.synchronize()
+            if k >= args.warmup:
+                lat.append((time.perf_counter() - t0) * 1e3)
+                arena.append(S.sod2_run_arena_bytes(b)[0] / 2 ** 20)
+                steps.append(sum(1 for line in S.sod2_run_plan_dump(b).splitlines() if line.startswith("step ")))
+        rows[name] = dict(latency_ms=round(sum(lat) / len(lat), 4), peak_arena_mb_mean=round(sum(arena) / len(arena), 3),
+                          peak_arena_mb_max=round(max(arena), 3), steps_per_call=round(sum(steps) / len(steps), 1))
+        del ses
+        torch.cuda.empty_cache()
+    base = rows["none"]
+    for r in rows.values():
+        r["speedup_vs_none"] = round(base["latency_ms"] / r["latency_ms"], 3)
+        r["arena_vs_none"] = round(r["peak_arena_mb_mean"] / base["peak_arena_mb_mean"], 3)
+    print(json.dumps({"metric": "optimisation breakdown (latency ms per call, peak arena MB)", "unit": "ms", "n_gpus": 1,
+                      "steps": args.steps, "warmup": args.warmup, "data": "synthetic", "dtype": w.dtype,
+                      "config": {"workload": f"config {args.config}", "calls": args.steps}, "stages": rows,
+                      "paper_context": "Figs. 5-6: each optimisation switched on after the previous one"}))
+
+
 def bench_decoder(args, S, dev):
     """Config 5 (not the headline workload): per sequence one prompt pass and `t_max` greedy decode steps, the
     next token read on the device; reports ms per generated token (steps replayed from one captured HIP
@@ -98,6 +146,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2)
     ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg (0 = skip)")
+    ap.add_argument("--ablation", action="store_true",
+                    help="optimisation breakdown: the same calls with fusion, execution planning, memory planning and "
+                         "kernel versions switched on one after the other")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="before the timed region, run a plain device copy of this many MiB three times: under "
                          "rocprofv3 --pmc it gives the scale of FETCH_SIZE / WRITE_SIZE")
@@ -118,6 +169,8 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
+    if args.ablation:
+        return bench_ablation(args, S, dev)
     if args.config == 5:
         return bench_decoder(args, S, dev)
     n_calls = args.steps + args.warmup
@@ -206,6 +259,7 @@ def main():
     per = {}
     tokens = 0
     empty_ms = []
+    t_roof_ms = 0.0          # per launch max(flops / MFMA peak, bytes / HBM peak), summed over the timed calls
     for ci, sym, ins, outs in timed:
         b = ses.bind(sym)
         S.sod2_binding_set_profiling(b, True)
@@ -224,6 +278,7 @@ def main():
             k["raw_ms"] += max(r["ms"] - base, 1e-4)
             k["flops"] += r["flops"]
             k["bytes"] += r["bytes"]
+            t_roof_ms += max(r["flops"] / (PEAK_BF16_TFLOPS * 1e12), r["bytes"] / (PEAK_HBM_GBS * 1e9)) * 1e3
     kernels = {}
     for name, k in per.items():
         kernels[name] = dict(launches=k["launches"], total_ms=round(k["ms"], 3),
@@ -311,6 +366,10 @@ def main():
            if any(kept) else {}),
         "tokens_per_s": round(tokens / total_s, 1),
         "roofline": roofline,
+        # whole call against the roofline: what the launches of a call would take at the peak that binds each
+        # of them, over the measured latency of the call (launch gaps, planning and the synchronise included)
+        "call_roofline": {"t_roof_ms_per_call": round(t_roof_ms / len(timed), 4),
+                          "frac_of_latency": round(t_roof_ms / len(timed) / (sum(lat) / len(lat)), 4)},
         "kernels": kernels,
         "event_overhead_us": round(1e3 * sum(empty_ms) / max(len(empty_ms), 1), 2),
         "cpu_baseline": cpu,

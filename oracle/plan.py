@@ -14,7 +14,9 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     weight equal to the last dim (bias); activation; Add of a non-constant
     tensor whose shape RDP proves equal to the output's (residual);
     activation; Transpose (stored permuted).  The chain stops at the first
-    operator that does not fit.
+    operator that does not fit.  With fusion switched off only a directly
+    following Transpose is still taken: the permuted store is a layout choice
+    of the contraction, and without it the Reshape behind it would need a copy.
 R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
     ScatterRows are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
@@ -192,11 +194,13 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             continue
         if op.kind in ("MatMul", "Conv"):
             members, cur, state = [n], op.outputs[0], 0
-            while opts.fusion:
+            while True:
                 c = sole_consumer(cur)
                 if c is None or folded[c] or c in assigned:
                     break
                 cop = g.ops[c]
+                if not opts.fusion and cop.kind != "Transpose":
+                    break           # fusion off: only the permuted store (a layout choice, no arithmetic merged) remains
                 nxt = None
                 if cop.kind == "Mul" and state < 1 and is_host_scalar(other(cop, cur)):
                     nxt = 1

@@ -154,10 +154,13 @@ void Plan::build() {
     if (op.kind == SOD2_OP_MATMUL || op.kind == SOD2_OP_CONV) {
       std::vector<int> chain{n};
       int cur = op.out[0], state = 0;
-      while (opts.fusion) {
+      while (true) {
         int c = sole_consumer(cur);
         if (c < 0 || folded[c] || group_of_op[c] >= 0) break;
         const Op& cop = G.ops[c];
+        // with fusion off only the permuted store remains: it is a layout choice of the contraction
+        // (no arithmetic is merged), and without it the Reshape that follows would need a copy
+        if (!opts.fusion && cop.kind != SOD2_OP_TRANSPOSE) break;
         int nxt = -1;
         if (cop.kind == SOD2_OP_MUL && state < 1 && host_scalar(other(cop, cur))) nxt = 1;
         else if (cop.kind == SOD2_OP_ADD) {

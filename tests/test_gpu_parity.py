@@ -124,11 +124,11 @@ def test_config2_full_depth_sampled(S):
 
 def test_ablation_switches_keep_values(S):
     """Fusion / SEP / DMP / MVC off (the switches of the paper's breakdown study) change the plan,
-    never the values.  Without fusion the encoder's head transpose would need a copy kernel, so the
-    unfused run uses the CNN (bias, ReLU and residual adds become elementwise kernels)."""
+    never the values.  Without fusion bias, scale, GELU, ReLU and residual adds become elementwise
+    kernels and the scores go through the arena (three kernels instead of the fused attention)."""
     w = configs.config2(2, layers=2)
-    for opts in (dict(sep=0), dict(dmp=0), dict(mvc=0)):
-        run_case(S, w, [(0, {"B": 2, "L": 45})], **opts)
+    for opts in (dict(sep=0), dict(dmp=0), dict(mvc=0), dict(fusion=0), dict(fusion=0, sep=0, dmp=0, mvc=0)):
+        run_case(S, w, [(0, {"B": 2, "L": 45}), (1, {"B": 3, "L": 136})], **opts)
     w = configs.resnet50(3, 1, sizes=(64, 96), stages=(2, 1, 1, 1))
     for opts in (dict(fusion=0), dict(fusion=0, sep=0, dmp=0, mvc=0)):
         run_case(S, w, [(0, {"H": 96, "W": 64})], **opts)
