@@ -62,15 +62,21 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
     n_tiles = min(n_tiles, (last_q + off) / BKV + 1);
   }
 
-  // tile loads: chunk p = tid + i * NT  ->  key p / 8, d chunk p % 8
+  // tile loads.  K: chunk p = tid + i * NT -> key p / 8, d chunk p % 8.  V: a thread takes the same d
+  // chunk of LPT consecutive keys, which are LPT consecutive positions of the permuted key order too
+  // (LPT is 2 or 4, the permutation moves bits 2 and 3), so the transposed store is one 4- or 8-byte
+  // write per d instead of LPT 2-byte writes
+  static_assert(LPT == 2 || LPT == 4, "V store packs 2 or 4 keys");
   uint4 kr[LPT], vr[LPT];
+  const int v_dc = tid & 7, v_key0 = (tid >> 3) * LPT;
   auto gload = [&](int t) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int p = tid + i * NT;
       const int key = min(t * BKV + p / 8, a.Lk - 1);
       kr[i] = *(const uint4*)(Kp + (long long)key * a.k_sn + (p % 8) * 8);
-      vr[i] = *(const uint4*)(Vp + (long long)key * a.v_sn + (p % 8) * 8);
+      const int vkey = min(t * BKV + v_key0 + i, a.Lk - 1);
+      vr[i] = *(const uint4*)(Vp + (long long)vkey * a.v_sn + v_dc * 8);
     }
   };
   auto sstore = [&](int buf) {
@@ -79,12 +85,22 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
       const int p = tid + i * NT;
       const int key = p / 8, dc = p % 8;
       *(uint4*)&Ks[buf][key * D + attn_swz(key, dc) * 8] = kr[i];
-      const int kp = (key & ~0xC) | ((key & 4) << 1) | ((key & 8) >> 1);       // swap bits 2 and 3
-      V16 v; v.u = vr[i];
+    }
+    const int kp0 = (v_key0 & ~0xC) | ((v_key0 & 4) << 1) | ((v_key0 & 8) >> 1);   // swap bits 2 and 3
+    V16 v[LPT];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int d = dc * 8 + e;
-        Vt[buf][d * BKV + attn_swz(d, kp >> 3) * 8 + (kp & 7)] = v.h[e];
+    for (int i = 0; i < LPT; ++i) v[i].u = vr[i];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int d = v_dc * 8 + e;
+      bf16_t* dst = &Vt[buf][d * BKV + attn_swz(d, kp0 >> 3) * 8 + (kp0 & 7)];
+      if (LPT == 4) {
+        uint2 w;
+        w.x = (uint32_t)v[0].h[e] | ((uint32_t)v[1].h[e] << 16);
+        w.y = (uint32_t)v[2 % LPT].h[e] | ((uint32_t)v[3 % LPT].h[e] << 16);
+        *(uint2*)dst = w;
+      } else {
+        *(uint32_t*)dst = (uint32_t)v[0].h[e] | ((uint32_t)v[1].h[e] << 16);
       }
     }
   };
@@ -120,36 +136,51 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
     }
     // ---- mask, running max and sum for this lane's query ----
     const int key_hi = a.causal ? min(a.Lk - 1, query + off) : a.Lk - 1;     // last visible key
+    // every key of the tile visible to every query of this wave (the usual case): no compare per score
+    const int wave_lo = a.causal ? min(a.Lk - 1, q_wg + wave * 32 + off) : a.Lk - 1;
+    // the running maximum is kept on the raw scores (scale > 0), the scale enters with the subtraction:
+    // p = 2^(s * sc - max * sc) is one fused multiply-add and one v_exp_f32 per score
     float mx = m_run;
+    if (t * BKV + BKV - 1 <= wave_lo) {
 #pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
+      for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int key = t * BKV + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
-        const float v = key <= key_hi ? s[kb][r] * sc : -INFINITY;
-        s[kb][r] = v;
-        mx = fmaxf(mx, v);
-      }
+        for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[kb][r]);
+    } else {
+#pragma unroll
+      for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int key = t * BKV + kb * 32 + (r >> 2) * 8 + half * 4 + (r & 3);
+          const float v = key <= key_hi ? s[kb][r] : -INFINITY;
+          s[kb][r] = v;
+          mx = fmaxf(mx, v);
+        }
+    }
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    const float alpha = exp2f(m_run - mx);               // 0 on the first tile (m_run = -inf, mx finite)
+    const float msc = mx * sc;
+    const float alpha = __builtin_amdgcn_exp2f((m_run - mx) * sc);   // 0 on the first tile (m_run = -inf, mx finite)
     float sum = 0.f;
     V16 pf[2][2];                                        // B operands of O^T: [32-key block][16-key step]
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const float p = exp2f(s[kb][r] - mx);
-        const bf16_t pb = f2bf(p);
-        sum += bf2f(pb);                                 // normalise by what is actually multiplied
-        pf[kb][r >> 3].h[r & 7] = pb;
+      for (int r = 0; r < 16; r += 2) {
+        const uint32_t pb = f2bf2(__builtin_amdgcn_exp2f(fmaf(s[kb][r], sc, -msc)),
+                                  __builtin_amdgcn_exp2f(fmaf(s[kb][r + 1], sc, -msc)));
+        sum += __uint_as_float(pb << 16) + __uint_as_float(pb & 0xffff0000u);   // normalise by what is actually multiplied
+        pf[kb][r >> 3].h[r & 7] = (bf16_t)pb;
+        pf[kb][r >> 3].h[(r & 7) + 1] = (bf16_t)(pb >> 16);
       }
     sum += __shfl_xor(sum, 32, 64);
     l_run = l_run * alpha + sum;
     m_run = mx;
+    if (!__all(alpha == 1.f)) {                          // the maximum of some query of this wave moved
 #pragma unroll
-    for (int db = 0; db < 2; ++db)
+      for (int db = 0; db < 2; ++db)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+        for (int r = 0; r < 16; ++r) oacc[db][r] *= alpha;
+    }
     // ---- O^T += V^T P ----
 #pragma unroll
     for (int db = 0; db < 2; ++db) {
@@ -176,8 +207,8 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 w;
-        w.x = (uint32_t)f2bf(oacc[db][g * 4 + 0] * inv) | ((uint32_t)f2bf(oacc[db][g * 4 + 1] * inv) << 16);
-        w.y = (uint32_t)f2bf(oacc[db][g * 4 + 2] * inv) | ((uint32_t)f2bf(oacc[db][g * 4 + 3] * inv) << 16);
+        w.x = f2bf2(oacc[db][g * 4 + 0] * inv, oacc[db][g * 4 + 1] * inv);
+        w.y = f2bf2(oacc[db][g * 4 + 2] * inv, oacc[db][g * 4 + 3] * inv);
         *(uint2*)(orow + db * 32 + g * 8 + half * 4) = w;
       }
   }

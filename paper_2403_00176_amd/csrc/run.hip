@@ -695,6 +695,7 @@ struct Builder {
       throw Error(SOD2_ERR_UNSUPPORTED, "attention operands need a dense head dim");
     a.causal = !sm->ia.empty() && sm->ia[0];
     if (a.causal && a.Lk < a.Lq) throw Error(SOD2_ERR_UNSUPPORTED, "causal attention with fewer keys than queries");
+    if (!(scale > 0.f)) throw Error(SOD2_ERR_UNSUPPORTED, "fused attention kernel: the score scale must be positive");
     a.scale = scale;
     a.q_sm = a.Lq == 1 ? 0 : str(vq, r - 2);            // the stride of a dim of size 1 carries no meaning
     a.k_sn = a.Lk == 1 ? 0 : str(vk, kn);

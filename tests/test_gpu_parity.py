@@ -56,6 +56,34 @@ def run_case(S, w, calls, variant=-1, check_structure=True, splits=0, **opts):
     return errs
 
 
+def test_bf16_store_rounds_to_nearest_even(S):
+    """The kernels store bf16 with the GPU's conversion instruction: ties go to the even mantissa,
+    exactly as the oracle's rounding (a Cast from fp32 is the smallest graph that shows it)."""
+    import torch
+    from workloads import GraphBuilder
+    from oracle import ops as O
+    from paper_2403_00176_amd.session import Session, to_host
+    b = GraphBuilder([("N", 1, 4096)])
+    x = b.input("x", "f32", ["N"])
+    b.mark_output(b.op("Cast", [x], dtype="bf16"), "y")
+    g = b.build()
+    rs = np.random.RandomState(11)
+    ties = np.array([1.0 + 2.0 ** -8, 1.0 + 3 * 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -20, 1.0 + 2.0 ** -8 - 2.0 ** -20,
+                     -(1.0 + 2.0 ** -8), -(1.0 + 3 * 2.0 ** -8), 0.0, -0.0, 3.3895e38, 1e-40, 2.0 ** -126,
+                     (2.0 - 2.0 ** -8) * 2.0 ** 10])
+    vals = np.concatenate([ties, rs.randn(3000) * 10.0 ** rs.randint(-6, 6, 3000),
+                           np.float32(1.0) + np.arange(1, 512, dtype=np.float64) * 2.0 ** -9]).astype(np.float32)
+    ses = Session(g)
+    ses.upload_weights({})
+    bnd = ses.bind({"N": len(vals)})
+    outs = ses.alloc_outputs(ses.output_shapes(bnd))
+    ses.run(bnd, ses.upload_inputs({0: vals.astype(np.float64)}), outs)
+    torch.cuda.synchronize()
+    got = to_host(outs[0])
+    ref = O.round_to(vals.astype(np.float64), "bf16")
+    assert np.array_equal(got, ref), np.flatnonzero(got != ref)[:8]
+
+
 def test_config1_fp32_block(S):
     w = configs.config1()
     errs = run_case(S, w, list(enumerate(w.calls)) + [(8, {"L": 16}), (9, {"L": 128}), (10, {"L": 17})])
