@@ -14,7 +14,7 @@
 // LDS read yields the matching A operand.
 //
 // One workgroup = NW waves = NW * 32 queries of one (batch, head); K / V tiles of 64 keys are
-// shared through LDS, double buffered, next tile prefetched into registers during the MFMAs.
+// shared through LDS, double buffered, the next two tiles prefetched into registers during the MFMAs.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -67,9 +67,10 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
   // (LPT is 2 or 4, the permutation moves bits 2 and 3), so the transposed store is one 4- or 8-byte
   // write per d instead of LPT 2-byte writes
   static_assert(LPT == 2 || LPT == 4, "V store packs 2 or 4 keys");
-  uint4 kr[LPT], vr[LPT];
+  // two register sets: the tile after next is already on its way while the next one waits for its store
+  uint4 krA[LPT], vrA[LPT], krB[LPT], vrB[LPT];
   const int v_dc = tid & 7, v_key0 = (tid >> 3) * LPT;
-  auto gload = [&](int t) {
+  auto gload = [&](int t, uint4 (&kr)[LPT], uint4 (&vr)[LPT]) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int p = tid + i * NT;
@@ -79,7 +80,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
       vr[i] = *(const uint4*)(Vp + (long long)vkey * a.v_sn + v_dc * 8);
     }
   };
-  auto sstore = [&](int buf) {
+  auto sstore = [&](int buf, const uint4 (&kr)[LPT], const uint4 (&vr)[LPT]) {
 #pragma unroll
     for (int i = 0; i < LPT; ++i) {
       const int p = tid + i * NT;
@@ -113,12 +114,14 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
   float m_run = -INFINITY, l_run = 0.f;
   const float sc = a.scale * 1.4426950408889634f;        // scores in units of log2 e
 
-  gload(0);
-  sstore(0);
+  gload(0, krA, vrA);
+  sstore(0, krA, vrA);
+  if (n_tiles > 1) gload(1, krA, vrA);
   __syncthreads();
-  for (int t = 0; t < n_tiles; ++t) {
+  // one key / value tile: `cur` holds tile t + 1 (loaded one step ago), `nxt` receives tile t + 2
+  auto step = [&](int t, uint4 (&kr_cur)[LPT], uint4 (&vr_cur)[LPT], uint4 (&kr_nxt)[LPT], uint4 (&vr_nxt)[LPT]) {
     const int buf = t & 1;
-    if (t + 1 < n_tiles) gload(t + 1);
+    if (t + 2 < n_tiles) gload(t + 2, kr_nxt, vr_nxt);
 
     // ---- S^T for the 64 keys of the tile: two 32-key blocks ----
     f32x16_t s[2];
@@ -169,8 +172,7 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
         const uint32_t pb = f2bf2(__builtin_amdgcn_exp2f(fmaf(s[kb][r], sc, -msc)),
                                   __builtin_amdgcn_exp2f(fmaf(s[kb][r + 1], sc, -msc)));
         sum += __uint_as_float(pb << 16) + __uint_as_float(pb & 0xffff0000u);   // normalise by what is actually multiplied
-        pf[kb][r >> 3].h[r & 7] = (bf16_t)pb;
-        pf[kb][r >> 3].h[(r & 7) + 1] = (bf16_t)(pb >> 16);
+        pf[kb][r >> 3].w[(r & 7) >> 1] = pb;
       }
     sum += __shfl_xor(sum, 32, 64);
     l_run = l_run * alpha + sum;
@@ -194,8 +196,12 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
           oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf.b, pf[kb][s2].b, oacc[db], 0, 0, 0);
         }
     }
-    if (t + 1 < n_tiles) sstore(buf ^ 1);
+    if (t + 1 < n_tiles) sstore(buf ^ 1, kr_cur, vr_cur);
     __syncthreads();
+  };
+  for (int t = 0; t < n_tiles; t += 2) {                 // n_tiles is the same for the whole workgroup
+    step(t, krA, vrA, krB, vrB);
+    if (t + 1 < n_tiles) step(t + 1, krB, vrB, krA, vrA);
   }
 
   // ---- O[query, d] = O^T / l : lane (query, half) holds d = 32 db + 8 g + 4 half + i ----

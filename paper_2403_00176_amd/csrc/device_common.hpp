@@ -65,6 +65,7 @@ union V16 {
   uint4 u;
   bf16x8_t b;
   bf16_t h[8];
+  uint32_t w[4];
 };
 __device__ __forceinline__ uint4 zero4() { return make_uint4(0, 0, 0, 0); }
 
