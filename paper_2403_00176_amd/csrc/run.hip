@@ -231,8 +231,11 @@ struct Builder {
     if (!p.opts.mvc) return V_REGULAR;
     if (M <= 8) return V_GEMV;                     // decode shape: weight streaming, one wave per column
     const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
+    const int64_t t64 = ((M + 63) / 64) * ((N + 63) / 64) * batch;
     if (t128 >= 1024) return V_DL0 + (K >= 2048 ? DL_256x256x64_S2_W8 : DL_256x128x32_S3_W8);   // fat versions
-    if (t128 >= 160) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
+    // the 64x64 tile runs two workgroups per CU: as long as all its tiles are resident at once
+    // (512 on 256 CUs) it finishes first; one tile more and a second round starts, then 128x128 wins
+    if (t64 > 512) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
     return V_DL0 + DL_64x64x64_S4_W4;
   }
 
