@@ -163,7 +163,8 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
             if it.is_group:
                 gr = plan.groups[it.ref]
                 inside = {o for n in gr.ops for o in g.ops[n].outputs}
-                ext = [t for n in gr.ops for t in g.ops[n].inputs if t not in inside]
+                ext = [t for n in gr.ops for t in g.ops[n].inputs
+                       if t not in inside and plan.sbase[t] not in inside]     # a view of a member's result is internal
                 dead = any(info(t)[0] for t in ext)
                 group_dead[gr.gid] = dead
                 if dead:
@@ -187,16 +188,20 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
                     b.exec.append((n_op, v, known))
                     nz_bytes = align_up((len(src) * ub + 1) * DT_BYTES[g.tensors[t].dtype])
                 b.dims[t] = concrete_dims(plan, t, env)
-                if gr.kind == "CACHEAPPEND":
-                    src = g.ops[gr.ops[0]].inputs[0]
+                for n_op in gr.ops:                       # a CACHEAPPEND group, or appends inside an attention group
+                    if g.ops[n_op].kind != "CacheAppend":
+                        continue
+                    tc = g.ops[n_op].outputs[0]
+                    src = g.ops[n_op].inputs[0]
                     if src not in b.session_root:
                         raise ValueError("CacheAppend must extend a session tensor")
-                    b.session_root[t] = b.session_root[src]
+                    b.dims[tc] = concrete_dims(plan, tc, env)
+                    b.session_root[tc] = b.session_root[src]
                     n = 1
-                    for d in b.dims[t]:
+                    for d in b.dims[tc]:
                         n *= d
-                    if n > cap_elems[b.session_root[t]]:
-                        raise CapacityExceeded(g.tensors[t].name)
+                    if n > cap_elems[b.session_root[tc]]:
+                        raise CapacityExceeded(g.tensors[tc].name)
                 if arena_candidate(plan, t):
                     n = DT_BYTES[g.tensors[t].dtype]
                     for d in b.dims[t]:

@@ -31,6 +31,12 @@ R6  Attention: a GEMM group that is only MatMul [+ Mul by a host scalar], whose
     never materialised, Section 4.2's "fusion removes intermediate results").
     Only for bf16 tensors with a known head size of 64 (the size the one fused
     kernel of the library is written for).
+R8  Cache append inside attention: when the key operand and the value operand
+    of an ATTENTION group are, through views only and with no other reader, the
+    results of two CacheAppend operators that each append a known number of at
+    most 4 bf16 rows (the decode step), the two CACHEAPPEND groups join the
+    ATTENTION group: its kernel writes the new rows into the session slots and
+    reads them from where they were produced.
 R7  LayerNorm as a prologue: a LAYERNORM group whose result is read by one
     MatMul alone, as its first operand, joins that MatMul's GEMM group when the
     row count is a known constant of at most 8 (the decode step: every wave of
@@ -252,6 +258,25 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     for c in absorbed_transpose:
         view[c] = False
 
+    def _append_behind(t) -> Optional[int]:
+        """The CacheAppend whose result reaches tensor t through views only, each link read by nobody
+        else, when it appends a known number of at most 4 bf16 rows (R8); else None."""
+        while True:
+            p = rdp.producer[t]
+            if p < 0 or g.tensors[t].is_output or len(rdp.consumers[t]) != 1:
+                return None
+            if view[p]:
+                t = g.ops[p].inputs[0]
+                continue
+            op = g.ops[p]
+            if op.kind != "CacheAppend" or p not in assigned or groups[assigned[p]].kind != "CACHEAPPEND":
+                return None
+            rows = rdp.S[op.inputs[1]]
+            if g.tensors[t].dtype != "bf16" or not isinstance(rows, list) or not rows or not R.is_expr(rows[0]) \
+                    or not rows[0].is_const() or rows[0].const_value() > 4:
+                return None
+            return p
+
     # R6: attention --------------------------------------------------------------
     if opts.fusion:
         for n in order:
@@ -284,6 +309,16 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             members = g1.ops + [n] + g2.ops
             for gid in (g1.gid, assigned[n], g2.gid):
                 del groups[gid]
+            # R8: the decode step's attention appends the new key / value rows itself
+            appends = []
+            for t in (mm1.inputs[1], g.ops[c2].inputs[1]):
+                ca = _append_behind(t)
+                if ca is not None:
+                    appends.append(ca)
+            if len(appends) == 2 and appends[0] != appends[1]:
+                for ca in appends:
+                    del groups[assigned[ca]]
+                members = appends + members
             gid = min(members)
             groups[gid] = Group(gid, "ATTENTION", sorted(members), g2.out)
             for m in members:

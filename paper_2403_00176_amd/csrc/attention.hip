@@ -220,14 +220,18 @@ __global__ __launch_bounds__(NW * 64) void attention_kernel(AttnArgs a) {
   }
 }
 
-// Few queries against a long key / value cache (the decode step): one workgroup per (batch, head,
-// query).  HBM-bound streaming of K and V, plain fp32 FMAs: 8 lanes share a key (16 bytes of its 64
-// values each), 32 keys per pass; probabilities are kept in LDS, so Lk <= 4096.
+// Few queries against a long key / value cache (the decode step): one workgroup of 16 waves per
+// (batch, head, query).  HBM-bound streaming of K and V with plain fp32 FMAs: 8 lanes share a key (16
+// bytes of its 64 values each), a thread has 8 keys in flight, so one pass covers 1024 keys and the
+// usual cache length costs two memory round trips (scores, values).  Probabilities are kept in LDS,
+// hence Lk <= 4096.  With n_new > 0 the kernel also performs the cache append (rule R8).
 constexpr int DEC_MAX_KEYS = 4096;
-__global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a) {
+constexpr int DEC_THREADS = 1024, DEC_KG = DEC_THREADS / 8, DEC_U = 8;
+__global__ __launch_bounds__(DEC_THREADS) void decode_attention_kernel(AttnArgs a) {
   __shared__ float prob[DEC_MAX_KEYS];
-  __shared__ float red[32][65];
-  __shared__ float stat[8];
+  __shared__ float red[DEC_THREADS / 64][64];
+  __shared__ float stat[2 * DEC_THREADS / 64];
+  constexpr int NWV = DEC_THREADS / 64;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int kg = tid >> 3, dc = tid & 7;
   const int query = blockIdx.x;
@@ -237,6 +241,18 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a) {
   const bf16_t* Vp = (const bf16_t*)a.v + b0 * a.v_sb0 + b1 * a.v_sb1;
   const int Lk = a.Lk + (a.step ? *a.step * a.lk_step : 0);
   const int n_keys = a.causal ? min(Lk, query + (Lk - a.Lq) + 1) : Lk;           // visible keys: 0 .. n_keys-1
+  // cache append: the last n_new keys are new.  Everybody reads them from where they were produced; the
+  // workgroups of query 0 copy their head's 64 values of every new row into the cache for later calls
+  const int past = Lk - a.n_new;
+  const bf16_t* NK = a.n_new ? (const bf16_t*)a.new_k + b1 * a.k_sb1 : nullptr;
+  const bf16_t* NV = a.n_new ? (const bf16_t*)a.new_v + b1 * a.v_sb1 : nullptr;
+  auto krow = [&](int t) { return (NK && t >= past) ? NK + (long long)(t - past) * a.new_k_sn : Kp + (long long)t * a.k_sn; };
+  auto vrow = [&](int t) { return (NV && t >= past) ? NV + (long long)(t - past) * a.new_v_sn : Vp + (long long)t * a.v_sn; };
+  if (NK && query == 0 && tid < 16 * a.n_new) {
+    const int r = tid >> 4, c = tid & 15;
+    if (c < 8) *(uint4*)((bf16_t*)Kp + (long long)(past + r) * a.k_sn + c * 8) = *(const uint4*)(NK + (long long)r * a.new_k_sn + c * 8);
+    else *(uint4*)((bf16_t*)Vp + (long long)(past + r) * a.v_sn + (c - 8) * 8) = *(const uint4*)(NV + (long long)r * a.new_v_sn + (c - 8) * 8);
+  }
   float qf[8];
   {
     V16 q; q.u = *(const uint4*)(Qp + dc * 8);
@@ -245,19 +261,19 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a) {
   }
   // scores
   float mx = -INFINITY;
-  for (int t0 = kg; t0 < n_keys; t0 += 128) {           // four keys per thread and pass: four loads in flight
-    V16 k[4];
+  for (int t0 = kg; t0 < n_keys; t0 += DEC_KG * DEC_U) {
+    V16 k[DEC_U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) k[u].u = *(const uint4*)(Kp + (long long)min(t0 + u * 32, n_keys - 1) * a.k_sn + dc * 8);
+    for (int u = 0; u < DEC_U; ++u) k[u].u = *(const uint4*)(krow(min(t0 + u * DEC_KG, n_keys - 1)) + dc * 8);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
+    for (int u = 0; u < DEC_U; ++u) {
       float s = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) s = fmaf(qf[e], bf2f(k[u].h[e]), s);
       s += __shfl_xor(s, 1, 64);
       s += __shfl_xor(s, 2, 64);
       s += __shfl_xor(s, 4, 64);
-      const int t = t0 + u * 32;
+      const int t = t0 + u * DEC_KG;
       if (t < n_keys) {
         if (dc == 0) prob[t] = s;
         mx = fmaxf(mx, s);
@@ -267,38 +283,52 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a) {
   mx = wave_max(mx);
   if (lane == 0) stat[wave] = mx;
   __syncthreads();
-  mx = fmaxf(fmaxf(stat[0], stat[1]), fmaxf(stat[2], stat[3]));
+  mx = stat[0];
+#pragma unroll
+  for (int w = 1; w < NWV; ++w) mx = fmaxf(mx, stat[w]);
   float sum = 0.f;
-  for (int t = tid; t < n_keys; t += 256) {
+  for (int t = tid; t < n_keys; t += DEC_THREADS) {
     const float p = __expf(prob[t] - mx);
     prob[t] = p;
     sum += p;
   }
   sum = wave_sum(sum);
-  if (lane == 0) stat[4 + wave] = sum;
+  if (lane == 0) stat[NWV + wave] = sum;
   __syncthreads();
-  const float inv = 1.f / (stat[4] + stat[5] + stat[6] + stat[7]);
+  float total = 0.f;
+#pragma unroll
+  for (int w = 0; w < NWV; ++w) total += stat[NWV + w];
+  const float inv = 1.f / total;
   // values
   float o[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int t0 = kg; t0 < n_keys; t0 += 128) {
-    V16 v[4];
+  for (int t0 = kg; t0 < n_keys; t0 += DEC_KG * DEC_U) {
+    V16 v[DEC_U];
 #pragma unroll
-    for (int u = 0; u < 4; ++u) v[u].u = *(const uint4*)(Vp + (long long)min(t0 + u * 32, n_keys - 1) * a.v_sn + dc * 8);
+    for (int u = 0; u < DEC_U; ++u) v[u].u = *(const uint4*)(vrow(min(t0 + u * DEC_KG, n_keys - 1)) + dc * 8);
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int t = t0 + u * 32;
+    for (int u = 0; u < DEC_U; ++u) {
+      const int t = t0 + u * DEC_KG;
       const float p = t < n_keys ? prob[t] : 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) o[e] = fmaf(p, bf2f(v[u].h[e]), o[e]);
     }
   }
+  // the 8 key groups of a wave (lane bits 3..5) first, then the 16 waves through LDS
 #pragma unroll
-  for (int e = 0; e < 8; ++e) red[kg][dc * 8 + e] = o[e];
+  for (int e = 0; e < 8; ++e) {
+    o[e] += __shfl_xor(o[e], 8, 64);
+    o[e] += __shfl_xor(o[e], 16, 64);
+    o[e] += __shfl_xor(o[e], 32, 64);
+  }
+  if (lane < 8) {
+#pragma unroll
+    for (int e = 0; e < 8; ++e) red[wave][dc * 8 + e] = o[e];
+  }
   __syncthreads();
   if (tid < 64) {
     float t = 0.f;
 #pragma unroll
-    for (int r = 0; r < 32; ++r) t += red[r][tid];
+    for (int w = 0; w < NWV; ++w) t += red[w][tid];
     bf16_t* orow = (bf16_t*)a.o + b0 * a.o_sb0 + b1 * a.o_sb1 + (long long)query * a.o_sm;
     orow[tid] = f2bf(t * inv);
   }
@@ -307,8 +337,9 @@ __global__ __launch_bounds__(256) void decode_attention_kernel(AttnArgs a) {
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s) {
   if (a.Lq <= 0 || a.Lk <= 0) return hipSuccess;
   const int batch = a.nb0 * a.nb1;
+  if (a.n_new > 0 && !(a.Lq <= 4 && a.Lk <= DEC_MAX_KEYS)) return hipErrorInvalidValue;   // only the few-query kernel appends
   if (a.Lq <= 4 && a.Lk <= DEC_MAX_KEYS) {
-    hipLaunchKernelGGL(decode_attention_kernel, dim3(a.Lq, batch), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(decode_attention_kernel, dim3(a.Lq, batch), dim3(DEC_THREADS), 0, s, a);
     return hipGetLastError();
   }
   // 128 queries per workgroup when that still gives every CU work, else 64

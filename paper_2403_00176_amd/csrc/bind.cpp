@@ -162,14 +162,21 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         int64_t n = dtype_bytes(G.tensors[t].dtype);
         for (const CompiledExpr& d : p.cshape[t]) { dims.push_back(d.eval(b.atom_vals)); n *= dims.back(); }
         b.dims[t] = dims;
-        if (gr.kind == G_CACHEAPPEND) {
-          auto root = b.session_root.find(G.ops[gr.ops[0]].in[0]);
+        for (int n_op : gr.ops) {                       // a CACHEAPPEND group, or appends inside an attention group
+          if (G.ops[n_op].kind != SOD2_OP_CACHEAPPEND) continue;
+          int tc = G.ops[n_op].out[0];
+          auto root = b.session_root.find(G.ops[n_op].in[0]);
           if (root == b.session_root.end()) throw Error(SOD2_ERR_UNSUPPORTED, "CacheAppend must extend a session tensor");
-          b.session_root[t] = root->second;
+          std::vector<int64_t> cd;
           int64_t elems = 1;
-          for (int64_t d : dims) elems *= d;
-          if (elems > cap_elems.at(root->second))
-            throw Error(SOD2_ERR_INVALID_ARG, "session tensor " + G.tensors[t].name + " would outgrow its capacity");
+          for (const CompiledExpr& d : p.cshape[tc]) { cd.push_back(d.eval(b.atom_vals)); elems *= cd.back(); }
+          if (p.cshape[tc].empty() && !p.rdp->S[tc].resolved())
+            throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[tc].name + " is not resolved");
+          b.dims[tc] = cd;
+          int root_id = root->second;
+          b.session_root[tc] = root_id;
+          if (elems > cap_elems.at(root_id))
+            throw Error(SOD2_ERR_INVALID_ARG, "session tensor " + G.tensors[tc].name + " would outgrow its capacity");
         }
         if (nz_bytes >= 0) n = nz_bytes;
         if (p.arena_candidate(t)) b.tensors[t] = ArenaTensor{t, (n + 255) / 256 * 256, step, step, -1};

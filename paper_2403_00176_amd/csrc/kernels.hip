@@ -831,6 +831,43 @@ __global__ __launch_bounds__(256) void argmax_kernel(ArgmaxArgs a) {
   }
 }
 
+// bf16 rows read in 16-byte chunks by 16 waves: every load of a thread is in flight at once for the
+// row lengths met here (a vocabulary of 32 000 is 4 chunks per thread)
+__global__ __launch_bounds__(1024) void argmax_bf16x8_kernel(ArgmaxArgs a) {
+  __shared__ float bv[16];
+  __shared__ int bi[16];
+  const long long r = blockIdx.x;
+  const int stp = a.step ? *a.step : 0;
+  const bf16_t* x = (const bf16_t*)((const char*)a.x + stp * a.x_step) + r * a.x_stride;
+  float best = -INFINITY;
+  int at = 0x7fffffff;
+  const int nchunk = a.cols >> 3;
+  for (int c = threadIdx.x; c < nchunk; c += 1024) {     // ascending indices per thread: '>' keeps the lowest
+    V16 v; v.u = *(const uint4*)(x + c * 8);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float f = bf2f(v.h[e]);
+      if (f > best || at == 0x7fffffff) { best = f; at = c * 8 + e; }
+    }
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    float ov = __shfl_xor(best, o, 64);
+    int oi = __shfl_xor(at, o, 64);
+    if (ov > best || (ov == best && oi < at)) { best = ov; at = oi; }
+  }
+  const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+  if (lane == 0) { bv[w] = best; bi[w] = at; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int k = 1; k < 16; ++k)
+      if (bv[k] > best || (bv[k] == best && bi[k] < at)) { best = bv[k]; at = bi[k]; }
+    char* y = (char*)a.y + stp * a.y_step;
+    if (a.out_i32) ((int*)y)[r] = at;
+    else ((long long*)y)[r] = at;
+  }
+}
+
 __global__ void step_set_kernel(int* step, int value) { *step = value; }
 __global__ void step_advance_kernel(int* step) { *step += 1; }
 hipError_t launch_step_set(int* step, int value, hipStream_t s) {
@@ -970,6 +1007,11 @@ hipError_t launch_append(const Launch& L, const AppendArgs& a, hipStream_t s) {
 hipError_t launch_argmax(const Launch& L, const ArgmaxArgs& a, hipStream_t s) {
   if (a.rows <= 0) return hipSuccess;
   dim3 grid((unsigned)a.rows);
+  if (L.in_dtype == SOD2_BF16_TAG && a.cols % 8 == 0 && a.cols >= 2048 && a.x_stride % 8 == 0 && a.x_step % 16 == 0 &&
+      ((uintptr_t)a.x & 15) == 0) {
+    hipLaunchKernelGGL(argmax_bf16x8_kernel, grid, dim3(1024), 0, s, a);
+    return hipGetLastError();
+  }
   if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(argmax_kernel<bf16_t>, grid, dim3(256), 0, s, a);
   else hipLaunchKernelGGL(argmax_kernel<float>, grid, dim3(256), 0, s, a);
   return hipGetLastError();

@@ -128,6 +128,11 @@ struct AttnArgs {
   long long o_sb0, o_sb1, o_sm;
   const int* step;         // replay: Lk grows by *step * lk_step keys
   int lk_step;
+  // cache append inside the few-query kernel: the last n_new of the Lk keys are new; their rows are read
+  // from new_k / new_v ([n_new, heads * 64], row strides in elements) and written to rows Lk - n_new .. of k / v
+  const void* new_k; const void* new_v;
+  int n_new;
+  long long new_k_sn, new_v_sn;
 };
 
 // NonZero (Table 2's EDO class): out[r, j] = r-th coordinate of the j-th non-zero element of x in

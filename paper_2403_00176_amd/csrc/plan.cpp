@@ -17,6 +17,10 @@
 //     result is the first operand of one MatMul alone leading a GEMM group of MatMul [+ Transpose]:
 //     the three become one ATTENTION group (scores and probabilities never reach memory); bf16
 //     tensors and a known head size of 64 only (what the fused kernel is written for).
+//  R8 cache append inside attention: when the key and the value operand of an ATTENTION group are,
+//     through views only and with no other reader, the results of two CacheAppend operators that
+//     each append a known number of at most 4 bf16 rows (the decode step), their CACHEAPPEND groups
+//     join the ATTENTION group: its kernel writes the new rows into the session slots itself.
 // Partition: cut around control operators and NonZero, after a group with a nac output, wherever
 // at most one arena tensor is live, and every 14 items.  Order inside a sub-graph: the sequence
 // with the smallest peak of live bytes at the symbols' upper bounds, ties to smaller group ids.
@@ -225,6 +229,22 @@ void Plan::build() {
       for (int m : gr.ops) k.push_back(G.ops[m].kind);
       return k == std::vector<int>(a) || k == std::vector<int>(b);
     };
+    // R8 helper: the CacheAppend whose result reaches tensor t through views only, each link read by
+    // nobody else, when it appends a known number of at most 4 bf16 rows; else -1
+    auto append_behind = [&](int t) -> int {
+      while (true) {
+        int pr = G.producer[t];
+        if (pr < 0 || G.tensors[t].is_output || G.consumers[t].size() != 1) return -1;
+        if (view[pr]) { t = G.ops[pr].in[0]; continue; }
+        const Op& ca = G.ops[pr];
+        if (ca.kind != SOD2_OP_CACHEAPPEND || group_of_op[pr] < 0 || groups[group_of_op[pr]].kind != G_CACHEAPPEND) return -1;
+        const LS& rows = R.S[ca.in[1]];
+        if (G.tensors[t].dtype != SOD2_BF16 || !rows.is_list() || rows.d.empty() || !rows.d[0].val() ||
+            !rows.d[0].e.is_const() || rows.d[0].e.const_value() > 4)
+          return -1;
+        return pr;
+      }
+    };
     for (int n : order) {
       const Op& op = G.ops[n];
       if (op.kind != SOD2_OP_SOFTMAX || group_of_op[n] < 0 || groups[group_of_op[n]].kind != G_SOFTMAX) continue;
@@ -249,13 +269,20 @@ void Plan::build() {
       gr.chain = g1.chain;
       gr.chain.push_back(n);
       gr.chain.insert(gr.chain.end(), g2.chain.begin(), g2.chain.end());
+      groups.erase(g1.gid);
+      groups.erase(group_of_op[n]);
+      groups.erase(g2.gid);
+      // R8: the decode step's attention appends the new key / value rows itself
+      int ca_k = append_behind(mm1.in[1]), ca_v = append_behind(G.ops[c2].in[1]);
+      if (ca_k >= 0 && ca_v >= 0 && ca_k != ca_v) {
+        groups.erase(group_of_op[ca_k]);
+        groups.erase(group_of_op[ca_v]);
+        gr.chain.insert(gr.chain.begin(), {ca_k, ca_v});
+      }
       gr.ops = gr.chain;
       std::sort(gr.ops.begin(), gr.ops.end());
       gr.gid = gr.ops.front();
       gr.out = g2.out;
-      groups.erase(g1.gid);
-      groups.erase(group_of_op[n]);
-      groups.erase(g2.gid);
       for (int m : gr.ops) group_of_op[m] = gr.gid;
       groups[gr.gid] = gr;
     }
@@ -490,7 +517,9 @@ void Plan::build() {
     const Group& gr = groups.at(items[i].ref);
     std::set<int> inside;
     for (int n : gr.ops) for (int o : G.ops[n].out) inside.insert(o);
-    for (int n : gr.ops) for (int t : G.ops[n].in) if (!inside.count(t)) item_ext[i].push_back(t);
+    for (int n : gr.ops)
+      for (int t : G.ops[n].in)
+        if (!inside.count(t) && !inside.count(sbase[t])) item_ext[i].push_back(t);     // a view of a member's result is internal
   }
 }
 

@@ -665,10 +665,12 @@ struct Builder {
     L.group = gr.gid;
     L.kernel = K_ATTENTION;
     const Op *mm1 = nullptr, *mm2 = nullptr, *sm = nullptr, *tp = nullptr;
+    std::vector<const Op*> appends;                 // CacheAppend members: the kernel writes the new rows
     float scale = 1.f;
     int cur = -1;
     for (int n : gr.chain) {
       const Op& op = G.ops[n];
+      if (op.kind == SOD2_OP_CACHEAPPEND) { appends.push_back(&op); continue; }
       if (op.kind == SOD2_OP_MATMUL) { (mm1 ? mm2 : mm1) = &op; }
       else if (op.kind == SOD2_OP_MUL) scale *= (float)G.tensors[other(op, cur)].fdata.at(0);
       else if (op.kind == SOD2_OP_SOFTMAX) sm = &op;
@@ -739,7 +741,32 @@ struct Builder {
     L.r[1] = ref_of(vk, dt);
     L.r[2] = ref_of(vv, dt);
     L.r[3] = ref_t(gr.out);
-    for (int i = 0; i < 4; ++i)
+    if (!appends.empty()) {
+      // which append feeds the keys, which the values: by the session slot the operand views live in
+      const Op *ak = nullptr, *av = nullptr;
+      for (const Op* ca : appends) {
+        int root = b.session_root.at(ca->out[0]);
+        if (root == vk.base) ak = ca;
+        if (root == vv.base) av = ca;
+      }
+      if (appends.size() != 2 || !ak || !av || ak == av) throw Error(SOD2_ERR_UNSUPPORTED, "attention with cache appends: one for the keys, one for the values");
+      const View &nk = view_of(ak->in[1]), &nv = view_of(av->in[1]);
+      const View &ck = view_of(ak->out[0]), &cv = view_of(av->out[0]);
+      const int64_t row = ck.dims.size() == 2 ? ck.dims[1] : -1;
+      bool ok = nk.dims.size() == 2 && nv.dims.size() == 2 && cv.dims.size() == 2 && nk.dims[0] == nv.dims[0] &&
+                nk.dims[1] == row && nv.dims[1] == row && cv.dims[1] == row && nk.strides[1] == 1 && nv.strides[1] == 1 &&
+                ck.dims[0] == a.Lk && cv.dims[0] == a.Lk && nk.dims[0] <= 4 && a.Lq <= 4 && a.Lk <= 4096 && a.nb0 == 1 &&
+                a.k_sb1 == 64 && a.v_sb1 == 64 && (int64_t)a.nb1 * 64 == row && (a.Lk == 1 || (a.k_sn == row && a.v_sn == row)) &&
+                G.tensors[ak->in[1]].dtype == dt && G.tensors[av->in[1]].dtype == dt;
+      if (!ok) throw Error(SOD2_ERR_UNSUPPORTED, "attention with cache appends: at most 4 new bf16 rows [n, heads * 64], at most 4 queries, at most 4096 keys");
+      a.n_new = (int)nk.dims[0];
+      a.new_k_sn = a.n_new == 1 ? 0 : nk.strides[0];
+      a.new_v_sn = a.n_new == 1 ? 0 : nv.strides[0];
+      if (a.new_k_sn % 8 != 0 || a.new_v_sn % 8 != 0) throw Error(SOD2_ERR_UNSUPPORTED, "attention operand strides must be multiples of 8 elements");
+      L.r[4] = ref_of(nk, dt);
+      L.r[5] = ref_of(nv, dt);
+    }
+    for (int i = 0; i < 6; ++i)
       if (L.r[i].byte_off % 16 != 0) throw Error(SOD2_ERR_UNSUPPORTED, "attention operands must be 16-byte aligned");
     L.u.attn = a;
     double batch = (double)a.nb0 * a.nb1;
@@ -933,8 +960,9 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
     case K_ATTENTION: {
       AttnArgs a = L.u.attn;
       a.q = P.at(L.r[0]); a.k = P.at(L.r[1]); a.v = P.at(L.r[2]); a.o = P.at(L.r[3]);
+      if (a.n_new > 0) { a.new_k = P.at(L.r[4]); a.new_v = P.at(L.r[5]); }
       if (P.step && L.d_lk) { a.step = P.step; a.lk_step = L.d_lk; }
-      if (!al16(a.q) || !al16(a.k) || !al16(a.v) || ((uintptr_t)a.o & 7)) return hipErrorInvalidValue;
+      if (!al16(a.q) || !al16(a.k) || !al16(a.v) || ((uintptr_t)a.o & 7) || !al16(a.new_k) || !al16(a.new_v)) return hipErrorInvalidValue;
       return launch_attention(a, s);
     }
     case K_GATHER: {
