@@ -1162,6 +1162,7 @@ hipError_t launch_conv(const Launch& L, const ConvArgs& c, hipStream_t s) {
             (!c.res || ((uintptr_t)c.res & 15) == 0);
   if (L.variant >= V_DL0 && c.vec && c.C % 64 == 0 && g.b_mode == 0) {
     g.group_m = 8;
+    if (c.splits > 1 && c.ws) { g.splits = c.splits; g.ws = c.ws; }
     return launch_conv_dl(c, g, L.variant - V_DL0, s);
   }
   if (c.vec && c.C % 32 == 0 && g.b_mode == 0) {

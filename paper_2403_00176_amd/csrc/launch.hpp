@@ -55,6 +55,8 @@ struct ConvArgs {
   int NB, H, W, C, O, KH, KW, stride, pad, OH, OW;
   int act1, act2;
   int vec;                 // C % 8 == 0 (16-byte loads along channels)
+  int splits;              // > 1: split-K over (kh, kw, c) as in GemmArgs, partials in ws
+  void* ws;
 };
 
 struct RowArgs {            // LayerNorm / Softmax over the last dim

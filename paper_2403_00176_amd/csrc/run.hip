@@ -400,6 +400,7 @@ struct Builder {
     }
     int64_t M = (int64_t)c.NB * c.OH * c.OW;
     L.variant = pick_variant(dt, M, c.O, (int64_t)c.KH * c.KW * c.C, 1);
+    c.splits = (c.vec && c.C % 64 == 0) ? pick_splits(L.variant, M, c.O, (int64_t)c.KH * c.KW * c.C, 1) : 1;
     L.u.conv = c;
     double eb = dtype_bytes(dt), K = (double)c.KH * c.KW * c.C;
     L.flops = 2.0 * M * c.O * K;
@@ -934,6 +935,8 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       c.x = P.at(L.r[0]); c.w = P.at(L.r[1]); c.y = P.at(L.r[2]);
       c.bias = P.at(L.r[3]); c.res = P.at(L.r[4]);
       c.vec = c.vec && al16(c.x);
+      if (c.splits > 1 && P.ws) c.ws = P.ws;
+      else c.splits = 1;
       return launch_conv(L, c, s);
     }
     case K_LAYERNORM: case K_SOFTMAX: {

@@ -121,6 +121,9 @@ def test_split_k(S, splits):
     w = configs.config2(2, layers=2)
     for variant in (17, 13):
         run_case(S, w, [(0, {"B": 3, "L": 77}), (1, {"B": 1, "L": 32}), (2, {"B": 2, "L": 200})], variant=variant, splits=splits)
+    # the implicit-GEMM convolutions split over (kh, kw, c) the same way
+    wc = configs.resnet50(3, 1, sizes=(64, 96), stages=(1, 1, 1, 1))
+    run_case(S, wc, [(0, {"H": 96, "W": 64})], variant=17, splits=splits)
     ses = Session(w.graph)
     ses.upload_weights(w.make_weights())
     sym = {"B": 2, "L": 100}
