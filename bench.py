@@ -95,6 +95,13 @@ def bench_decoder(args, S, dev):
             ses.decode_replay(0, w.t_max)
             torch.cuda.synchronize()
             t4 = time.perf_counter()
+        pre = []                                   # the prompt pass again, five times: the median is reported
+        for _ in range(5):
+            torch.cuda.synchronize()
+            tp = time.perf_counter()
+            ses.prefill(prompt)
+            torch.cuda.synchronize()
+            pre.append((time.perf_counter() - tp) * 1e3)
         b = ses.dec.bind({"P": P, "t": w.t_max - 1})
         S.sod2_binding_set_profiling(b, True)
         ses.decode(w.t_max - 1, b)
@@ -105,7 +112,7 @@ def bench_decoder(args, S, dev):
                 continue
             k = per.setdefault(r["kernel"], [0, 0.0, 0.0])
             k[0] += 1; k[1] += r["ms"]; k[2] += r["bytes"]
-        rows.append(dict(P=P, prefill_ms=round((t1 - t0) * 1e3, 3), decode_ms_per_token=round((t4 - t3) * 1e3 / w.t_max, 4),
+        rows.append(dict(P=P, prefill_ms=round(sorted(pre)[2], 3), decode_ms_per_token=round((t4 - t3) * 1e3 / w.t_max, 4),
                          decode_ms_per_token_step_by_step=round((t2 - t1) * 1e3 / w.t_max, 4),
                          arena_mb=round(ses.arena.numel() / 2 ** 20, 2),
                          last_step_kernels={k: dict(n=v[0], us=round(v[1] * 1e3, 1), gbs=round(v[2] / max(v[1], 1e-9) / 1e6, 1))

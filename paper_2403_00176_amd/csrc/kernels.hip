@@ -688,27 +688,37 @@ __global__ __launch_bounds__(256) void reduce_mean_kernel(ReduceArgs a) {
   }
 }
 
-// The same for bf16 rows of a multiple of 8 channels: a lane owns 8 channels (16-byte loads), 16
-// waves split the rows so that every wave has only a few independent loads in flight.
-template <class TO>
-__global__ __launch_bounds__(1024) void reduce_mean_bf16x8_kernel(ReduceArgs a) {
-  __shared__ float part[16][512];
+// The same for bf16 rows with 16 waves splitting the rows, so that every wave has only a few
+// independent loads in flight.  A lane owns CPL consecutive channels (8: 16-byte loads, a workgroup
+// covers 512 channels; 2: 4-byte loads, 128 channels per workgroup, for when 512-channel workgroups
+// would be too few to pull the rows through more than a couple of CUs).
+template <class TO, int CPL>
+__global__ __launch_bounds__(1024) void reduce_mean_bf16_wide_kernel(ReduceArgs a) {
+  __shared__ float part[16][64 * CPL];
   const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-  const int c0 = (blockIdx.x * 64 + lane) * 8, b = blockIdx.y;
-  float s[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const int c0 = (blockIdx.x * 64 + lane) * CPL, b = blockIdx.y;
+  float s[CPL];
+#pragma unroll
+  for (int e = 0; e < CPL; ++e) s[e] = 0.f;
   if (c0 < a.C) {
     const bf16_t* x = (const bf16_t*)a.x + (long long)b * a.R * a.C + c0;
     for (long long r = w; r < a.R; r += 16) {
-      V16 v; v.u = *(const uint4*)(x + r * a.C);
+      if (CPL == 8) {
+        V16 v; v.u = *(const uint4*)(x + r * a.C);
 #pragma unroll
-      for (int e = 0; e < 8; ++e) s[e] += bf2f(v.h[e]);
+        for (int e = 0; e < CPL; ++e) s[e] += bf2f(v.h[e]);
+      } else {
+        const uint32_t v = *(const uint32_t*)(x + r * a.C);
+        s[0] += __uint_as_float(v << 16);
+        s[CPL - 1] += __uint_as_float(v & 0xffff0000u);
+      }
     }
   }
 #pragma unroll
-  for (int e = 0; e < 8; ++e) part[w][lane * 8 + e] = s[e];
+  for (int e = 0; e < CPL; ++e) part[w][lane * CPL + e] = s[e];
   __syncthreads();
-  const int t = threadIdx.x, c = blockIdx.x * 512 + t;
-  if (t < 512 && c < a.C) {
+  const int t = threadIdx.x, c = blockIdx.x * 64 * CPL + t;
+  if (t < 64 * CPL && c < a.C) {
     float tot = 0.f;
 #pragma unroll
     for (int k = 0; k < 16; ++k) tot += part[k][t];
@@ -1197,9 +1207,15 @@ hipError_t launch_row(const Launch& L, const RowArgs& a, hipStream_t s) {
 hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s) {
   bool ib = L.in_dtype == SOD2_BF16_TAG, ob = L.out_dtype == SOD2_BF16_TAG;
   if (ib && a.C % 8 == 0 && ((uintptr_t)a.x & 15) == 0 && a.R >= 64) {
-    dim3 wide((a.C + 511) / 512, a.batch);
-    if (ob) hipLaunchKernelGGL(reduce_mean_bf16x8_kernel<bf16_t>, wide, dim3(1024), 0, s, a);
-    else hipLaunchKernelGGL(reduce_mean_bf16x8_kernel<float>, wide, dim3(1024), 0, s, a);
+    if ((long long)((a.C + 511) / 512) * a.batch >= 16) {
+      dim3 wide((a.C + 511) / 512, a.batch);
+      if (ob) hipLaunchKernelGGL((reduce_mean_bf16_wide_kernel<bf16_t, 8>), wide, dim3(1024), 0, s, a);
+      else hipLaunchKernelGGL((reduce_mean_bf16_wide_kernel<float, 8>), wide, dim3(1024), 0, s, a);
+    } else {                                             // few rows of workgroups: narrower ones, more CUs
+      dim3 wide((a.C + 127) / 128, a.batch);
+      if (ob) hipLaunchKernelGGL((reduce_mean_bf16_wide_kernel<bf16_t, 2>), wide, dim3(1024), 0, s, a);
+      else hipLaunchKernelGGL((reduce_mean_bf16_wide_kernel<float, 2>), wide, dim3(1024), 0, s, a);
+    }
     return hipGetLastError();
   }
   dim3 grid((a.C + 63) / 64, a.batch);
