@@ -2,14 +2,18 @@
 the symbols (and, with control flow, the Switch decisions) are known
 (Section 4.4.1).
 
-Reading of the two-sentence description in the paper, per executed sub-graph
-in execution order:
-  1. live bytes per step; p* = the step with the most live bytes (earliest on ties);
-  2. the sub-graph's tensors live at p*, by (start step, id), then
-  3. those starting after p*, by (start step, id), then
-  4. those ending before p*, by (end step descending, start step descending, id),
+Reading of the two-sentence description in the paper.  Executed sub-graphs are
+taken in execution order; consecutive ones with resolved sizes and no control
+operator are planned together as one region (a stack of blocks has a peak in
+every block, and a tensor that lives from one block into the next must not be
+placed before the next peak is known).  Within a region:
+  1. live bytes per step; the steps are visited from the one with the most live
+     bytes down (earlier step first on ties): the peak first, as in the paper,
+     then the next highest step, and so on;
+  2. at each visited step the tensors live there that have no offset yet, by
+     (start step, id),
   are placed one by one at the lowest offset where they overlap no tensor
-  already placed (in this or an earlier sub-graph) whose lifetime intersects.
+  already placed (in this or an earlier region) whose lifetime intersects.
 Sizes are element count x element size rounded up to 256 bytes.  Control flow
 follows dead-token propagation: the Switch output that is not taken is dead,
 an operator with a dead input does not run, Combine forwards its live input.
@@ -243,18 +247,8 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
 
     placed: List[ArenaTensor] = []
     if plan.opts.dmp:
-        for s in sorted(set(b.step_sg)):
-            ks = [k for k in range(nsteps) if b.step_sg[k] == s]
-            mine = [at for at in b.tensors.values() if ks[0] <= at.start <= ks[-1]]
-            if not mine:
-                continue
-            p = max(ks, key=lambda k: (live_bytes[k], -k))
-            at_peak = sorted((a for a in mine if a.start <= p <= a.end), key=lambda a: (a.start, a.tid))
-            after = sorted((a for a in mine if a.start > p), key=lambda a: (a.start, a.tid))
-            before = sorted((a for a in mine if a.end < p), key=lambda a: (-a.end, -a.start, a.tid))
-            for a in at_peak + after + before:
-                a.offset = first_fit(a, placed)
-                placed.append(a)
+        for ks in planning_regions(plan, b):
+            place_region([at for at in b.tensors.values() if ks[0] <= at.start <= ks[-1]], ks, live_bytes, placed)
     else:
         for a in sorted(b.tensors.values(), key=lambda a: (a.start, a.tid)):
             a.offset = best_fit(a, placed)
@@ -263,6 +257,33 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
         a.offset += b.session_bytes
     b.arena_bytes = max((a.offset + a.bytes for a in placed), default=b.session_bytes)
     return b
+
+
+def place_region(mine: Sequence[ArenaTensor], ks: Sequence[int], live_bytes: Sequence[int], placed: List[ArenaTensor]):
+    """Peak-first placement of the tensors that start in the steps ``ks``: the steps are visited from the
+    one with the most live bytes down (earlier first on ties); at each, the tensors live there that have
+    no offset yet are placed by (start, id) at the lowest offset that fits."""
+    for p in sorted(ks, key=lambda k: (-live_bytes[k], k)):
+        for a in sorted((a for a in mine if a.offset < 0 and a.start <= p <= a.end), key=lambda a: (a.start, a.tid)):
+            a.offset = first_fit(a, placed)
+            placed.append(a)
+
+
+def planning_regions(plan: Plan, b: Binding) -> List[List[int]]:
+    """Executed steps grouped into the stretches that are planned together: consecutive sub-graphs with
+    resolved sizes and no control operator form one region; a sub-graph holding a Switch, a Combine or a
+    NonZero, or one with execution-determined sizes, is a region of its own (what follows it is planned
+    when it has executed, and nothing placed before may depend on it)."""
+    def alone(k: int) -> bool:
+        it = plan.items[b.steps[k]]
+        return (not it.is_group) or plan.groups[it.ref].kind == "NONZERO" or plan.sg_class[b.step_sg[k]] == "nac"
+    regions: List[List[int]] = []
+    for k in range(len(b.steps)):
+        new_sg = k == 0 or b.step_sg[k] != b.step_sg[k - 1]
+        if not regions or (new_sg and (alone(k) or alone(k - 1))):
+            regions.append([])
+        regions[-1].append(k)
+    return regions
 
 
 def best_fit(t: ArenaTensor, placed: Sequence[ArenaTensor]) -> int:

@@ -1,11 +1,13 @@
 // Run-time half of the plan (Section 4.4.1): evaluate the symbols, derive the executed steps,
 // tensor lifetimes and arena offsets.
 //
-// Per executed sub-graph, in execution order: p* = step with the most live bytes (earliest on
-// ties); the sub-graph's tensors live at p* by (start, id), then those starting after p* by
-// (start, id), then those ending before p* by (end desc, start desc, id) are each placed at the
-// lowest offset that overlaps no already placed tensor with an intersecting lifetime.  Sizes are
-// rounded up to 256 bytes.  Control flow uses dead tokens: the Switch output not taken is dead, an
+// Executed sub-graphs in execution order; consecutive ones with resolved sizes and no control operator
+// are planned together as one region (a tensor that lives from one block into the next must not be
+// placed before the next block's peak is known).  Within a region the steps are visited from the one
+// with the most live bytes down (earlier first on ties): the peak first, then the next highest step,
+// ...; at each the tensors live there that have no offset yet, by (start, id), are placed at the lowest
+// offset that overlaps no already placed tensor with an intersecting lifetime.  Sizes are rounded up
+// to 256 bytes.  Control flow uses dead tokens: the Switch output not taken is dead, an
 // item with a dead input does not run, Combine forwards its live input.
 //
 // Session tensors (a KV cache) persist across calls: one slot per session input at the bottom of
@@ -222,39 +224,47 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
 
   std::vector<const ArenaTensor*> placed;
   if (p.opts.dmp) {
-    std::vector<ArenaTensor*> by_start;                // every sub-graph takes its tensors from the front
+    std::vector<ArenaTensor*> by_start;                // every region takes its tensors from the front
     for (auto& kv : b.tensors) by_start.push_back(&kv.second);
     std::stable_sort(by_start.begin(), by_start.end(), [](const ArenaTensor* x, const ArenaTensor* y) { return x->start < y->start; });
     size_t next_t = 0;
+    // a sub-graph with a control operator, a NonZero or execution-determined sizes is planned alone
+    auto alone = [&](int k) {
+      const Item& it = p.items[b.steps[k]];
+      return !it.is_group || p.groups.at(it.ref).kind == G_NONZERO || p.sg_class[b.step_sg[k]] == "nac";
+    };
     int k0 = 0;
     while (k0 < nsteps) {
+      // region: consecutive sub-graphs with resolved sizes and no control operator are planned together
       int k1 = k0;
-      while (k1 + 1 < nsteps && b.step_sg[k1 + 1] == b.step_sg[k0]) ++k1;
-      // a tensor that ended before this sub-graph starts can no longer intersect anything placed from here on
+      while (k1 + 1 < nsteps) {
+        bool new_sg = b.step_sg[k1 + 1] != b.step_sg[k1];
+        if (new_sg && (alone(k1 + 1) || alone(k1))) break;
+        ++k1;
+      }
+      // a tensor that ended before this region starts can no longer intersect anything placed from here on
       placed.erase(std::remove_if(placed.begin(), placed.end(), [k0](const ArenaTensor* a) { return a->end < k0; }), placed.end());
       std::vector<ArenaTensor*> mine;
       while (next_t < by_start.size() && by_start[next_t]->start <= k1) mine.push_back(by_start[next_t++]);
       if (!mine.empty()) {
-        int pk = k0;
-        for (int k = k0; k <= k1; ++k) if (live_bytes[k] > live_bytes[pk]) pk = k;
-        std::vector<ArenaTensor*> at_peak, after, before;
-        for (ArenaTensor* a : mine) {
-          if (a->start <= pk && pk <= a->end) at_peak.push_back(a);
-          else if (a->start > pk) after.push_back(a);
-          else before.push_back(a);
-        }
-        auto by_start = [](const ArenaTensor* x, const ArenaTensor* y) {
+        // the peak first, then the next highest step, and so on; at each step the tensors live there
+        // that have no offset yet, by (start, id), each at the lowest offset that fits
+        std::vector<int> steps_by_need;
+        for (int k = k0; k <= k1; ++k) steps_by_need.push_back(k);
+        std::stable_sort(steps_by_need.begin(), steps_by_need.end(), [&](int x, int y) { return live_bytes[x] > live_bytes[y]; });
+        std::sort(mine.begin(), mine.end(), [](const ArenaTensor* x, const ArenaTensor* y) {
           return x->start != y->start ? x->start < y->start : x->tid < y->tid;
-        };
-        std::sort(at_peak.begin(), at_peak.end(), by_start);
-        std::sort(after.begin(), after.end(), by_start);
-        std::sort(before.begin(), before.end(), [](const ArenaTensor* x, const ArenaTensor* y) {
-          if (x->end != y->end) return x->end > y->end;
-          if (x->start != y->start) return x->start > y->start;
-          return x->tid < y->tid;
         });
-        for (auto* lst : {&at_peak, &after, &before})
-          for (ArenaTensor* a : *lst) { a->offset = first_fit(*a, placed); placed.push_back(a); }
+        size_t left = mine.size();
+        for (int pk : steps_by_need) {
+          if (left == 0) break;
+          for (ArenaTensor* a : mine) {
+            if (a->offset >= 0 || a->start > pk || a->end < pk) continue;
+            a->offset = first_fit(*a, placed);
+            placed.push_back(a);
+            --left;
+          }
+        }
       }
       k0 = k1 + 1;
     }

@@ -176,11 +176,12 @@ def test_arena_invariants(cfg):
 
 def test_peak_first_needs_no_extra_space_on_layer_chains():
     """Section 4.4.1: when the requirement falls monotonically on both sides of the peak, starting
-    at the peak needs no extra space -- the arena equals the peak of live bytes.  That precondition
-    holds inside one sub-graph chain: a single encoder block, and every call of the CNN.  Across
-    sub-graph cuts a tensor that lives through (the residual stream) was placed before the next
-    sub-graph's peak is known, so a stack of blocks may exceed the peak; the excess stays small
-    (the paper reports 1.05x of the optimum for its planner, not 1.0)."""
+    at the peak needs no extra space -- the arena equals the peak of live bytes.  A stack of blocks
+    has one such peak per block; planned as one region (the steps visited from the highest
+    requirement down) every block's peak gets its tensors placed before the tensors around it, and
+    the arena equals the peak for the whole stack, for every call of configs 1-5.  (Planned one
+    sub-graph at a time the stack needed 7/6 of the peak: the residual stream had been placed before
+    the next block's peak was known.)"""
     w = configs.config2(8, layers=1)
     p = make(w)
     for call in w.calls + [{"B": 8, "L": 512}, {"B": 1, "L": 32}]:
@@ -195,7 +196,22 @@ def test_peak_first_needs_no_extra_space_on_layer_chains():
     p = make(w)
     for call in w.calls + [{"B": 8, "L": 512}, {"B": 1, "L": 32}]:
         b = A.bind(p, call)
-        assert b.peak_live <= b.arena_bytes <= 1.17 * b.peak_live
+        assert b.arena_bytes == b.peak_live
+    w1 = configs.config1()
+    p1 = make(w1)
+    assert all(A.bind(p1, c).arena_bytes == A.bind(p1, c).peak_live for c in w1.calls)
+    w4 = small(4)
+    p4 = make(w4)
+    rnd = random.Random(4)
+    for call in w4.calls:
+        dec = [rnd.random() < 0.5 for _ in range(3)]
+        b = A.bind(p4, call, dec)
+        assert b.arena_bytes == b.peak_live
+    w5 = configs.config5(1, layers=3)
+    for gd, sym in ((w5.prefill, {"P": 300}), (w5.prefill, {"P": 64}), (w5.decode, {"P": 300, "t": 7}), (w5.decode, {"P": 64, "t": 255})):
+        p5 = P.build_plan(gd, R.RDP(gd).analyse())
+        b = A.bind(p5, sym)
+        assert b.arena_bytes == b.peak_live
     # with fused attention the FFN hidden tensor dominates at every length
     big, small_ = A.bind(p, {"B": 8, "L": 512}), A.bind(p, {"B": 8, "L": 32})
     assert big.peak_live == 8 * 512 * (3072 + 768 + 768) * 2
@@ -203,38 +219,39 @@ def test_peak_first_needs_no_extra_space_on_layer_chains():
 
 
 def test_against_exhaustive_optimum_and_best_fit():
-    """The planner is scored against the exhaustive optimum (Section 4.4.1, last paragraph)."""
+    """The planner is scored against the exhaustive optimum (Section 4.4.1, last paragraph: the paper
+    reports 1.05x of the optimum for its planner and 1.16x for the greedy comparison)."""
     rnd = random.Random(5)
-    worse_bestfit = 0
-    for trial in range(40):
+    ratio = {"peak": [], "best": []}
+    for trial in range(60):
         n = rnd.randint(3, 7)
         ts = []
         for i in range(n):
             s = rnd.randint(0, 6)
             ts.append(A.ArenaTensor(i, 256 * rnd.randint(1, 9), s, s + rnd.randint(0, 3)))
         opt = A.optimal_arena_bytes(ts)
-        live = max(sum(t.bytes for t in ts if t.start <= k <= t.end) for k in range(10))
-        assert opt >= live
+        live = [sum(t.bytes for t in ts if t.start <= k <= t.end) for k in range(10)]
+        assert opt >= max(live)
         for strategy in ("peak", "best"):
             placed = []
+            mine = [A.ArenaTensor(t.tid, t.bytes, t.start, t.end) for t in ts]
             if strategy == "peak":
-                steps = range(10)
-                p_ = max(steps, key=lambda k: (sum(t.bytes for t in ts if t.start <= k <= t.end), -k))
-                order = sorted((t for t in ts if t.start <= p_ <= t.end), key=lambda a: (a.start, a.tid)) + \
-                    sorted((t for t in ts if t.start > p_), key=lambda a: (a.start, a.tid)) + \
-                    sorted((t for t in ts if t.end < p_), key=lambda a: (-a.end, -a.start, a.tid))
+                A.place_region(mine, list(range(10)), live, placed)
             else:
-                order = sorted(ts, key=lambda a: (a.start, a.tid))
-            for t in order:
-                c = A.ArenaTensor(t.tid, t.bytes, t.start, t.end)
-                c.offset = A.first_fit(c, placed) if strategy == "peak" else A.best_fit(c, placed)
-                placed.append(c)
+                for c in sorted(mine, key=lambda a: (a.start, a.tid)):
+                    c.offset = A.best_fit(c, placed)
+                    placed.append(c)
+            assert len(placed) == n and all(c.offset >= 0 for c in placed)
             top = max(c.offset + c.bytes for c in placed)
             assert top >= opt
+            ratio[strategy].append(top / opt)
             for i, x in enumerate(placed):
                 for y in placed[i + 1:]:
                     if A.intersects(x, y):
                         assert x.offset + x.bytes <= y.offset or y.offset + y.bytes <= x.offset
+    mean = {k: sum(v) / len(v) for k, v in ratio.items()}
+    print("arena / optimum on random lifetimes: peak-first %.3f, best-fit %.3f" % (mean["peak"], mean["best"]))
+    assert mean["peak"] <= mean["best"] and mean["peak"] < 1.06
 
 
 def test_dmp_switch_and_symbol_range():
