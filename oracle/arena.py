@@ -271,16 +271,23 @@ def place_region(mine: Sequence[ArenaTensor], ks: Sequence[int], live_bytes: Seq
 
 def planning_regions(plan: Plan, b: Binding) -> List[List[int]]:
     """Executed steps grouped into the stretches that are planned together: consecutive sub-graphs with
-    resolved sizes and no control operator form one region; a sub-graph holding a Switch, a Combine or a
-    NonZero, or one with execution-determined sizes, is a region of its own (what follows it is planned
-    when it has executed, and nothing placed before may depend on it)."""
-    def alone(k: int) -> bool:
+    known sizes and no control operator form one region.  A sub-graph holding a Switch, a Combine or a
+    NonZero is a region of its own (what follows it is planned when it has executed, and nothing placed
+    before may depend on it); so is a sub-graph with execution-determined sizes as long as a NonZero
+    that ran before it still has no known count (it is then planned at the upper bound and planned
+    again, together with its neighbours, once the count is there: Section 4.3)."""
+    known = sum(1 for _, _, k in b.exec if k)
+    seen = 0                                   # NonZero groups executed before the current step
+    alone = []
+    for k in range(len(b.steps)):
         it = plan.items[b.steps[k]]
-        return (not it.is_group) or plan.groups[it.ref].kind == "NONZERO" or plan.sg_class[b.step_sg[k]] == "nac"
+        nz = it.is_group and plan.groups[it.ref].kind == "NONZERO"
+        alone.append((not it.is_group) or nz or (plan.sg_class[b.step_sg[k]] == "nac" and seen > known))
+        seen += nz
     regions: List[List[int]] = []
     for k in range(len(b.steps)):
         new_sg = k == 0 or b.step_sg[k] != b.step_sg[k - 1]
-        if not regions or (new_sg and (alone(k) or alone(k - 1))):
+        if not regions or (new_sg and (alone[k] or alone[k - 1])):
             regions.append([])
         regions[-1].append(k)
     return regions

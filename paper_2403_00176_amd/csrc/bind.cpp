@@ -228,11 +228,20 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
     for (auto& kv : b.tensors) by_start.push_back(&kv.second);
     std::stable_sort(by_start.begin(), by_start.end(), [](const ArenaTensor* x, const ArenaTensor* y) { return x->start < y->start; });
     size_t next_t = 0;
-    // a sub-graph with a control operator, a NonZero or execution-determined sizes is planned alone
-    auto alone = [&](int k) {
-      const Item& it = p.items[b.steps[k]];
-      return !it.is_group || p.groups.at(it.ref).kind == G_NONZERO || p.sg_class[b.step_sg[k]] == "nac";
-    };
+    // a sub-graph with a control operator or a NonZero is planned alone; so is one with execution-
+    // determined sizes as long as a NonZero that ran before it has no known count yet
+    std::vector<char> alone_v(nsteps, 0);
+    {
+      int known = 0, seen = 0;
+      for (const auto& e : b.exec) known += e.known ? 1 : 0;
+      for (int k = 0; k < nsteps; ++k) {
+        const Item& it = p.items[b.steps[k]];
+        bool nz = it.is_group && p.groups.at(it.ref).kind == G_NONZERO;
+        alone_v[k] = !it.is_group || nz || (p.sg_class[b.step_sg[k]] == "nac" && seen > known);
+        seen += nz ? 1 : 0;
+      }
+    }
+    auto alone = [&](int k) { return alone_v[k] != 0; };
     int k0 = 0;
     while (k0 < nsteps) {
       // region: consecutive sub-graphs with resolved sizes and no control operator are planned together
