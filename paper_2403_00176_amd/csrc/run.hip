@@ -1279,9 +1279,9 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
           h->last_exec.push_back(count);
           if (n_nz >= exec_values.size()) {
             exec_values.push_back(count);
-            // the current plan assumed the upper bound: a count equal to it changes nothing
-            if (count != L.u.nz.n) replan(k, "NonZero");
-            else assumed = true;
+            // (also when the count equals the assumed upper bound: with the count known the sub-graphs
+            //  that follow are planned together instead of one by one)
+            replan(k, "NonZero");
           } else if (exec_values[n_nz] != count) {
             throw Error(SOD2_ERR_INVALID_ARG, "the binding was planned for a NonZero count of " + std::to_string(exec_values[n_nz]) +
                                                   ", the run found " + std::to_string(count));

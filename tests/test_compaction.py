@@ -190,6 +190,13 @@ def test_upper_bound_plan_then_exact_plan():
             assert list(res.values[t].shape) == dims, w.graph.tensors[t].name
     with pytest.raises(ValueError):
         A.bind(plan, w.calls[0], exec_values=[w.calls[0]["B"] + 1])
+    # a count that is known is not the same as the upper bound assumed for an unknown one, even when the
+    # numbers agree: with the count known the sub-graphs behind the NonZero are planned together, so a
+    # run must plan again after every NonZero (the library once skipped that when count == bound)
+    sym = w.calls[0]
+    assumed, known = A.bind(plan, sym), A.bind(plan, sym, exec_values=[sym["B"]])
+    assert [v for _, v, _ in assumed.exec][:1] == [v for _, v, _ in known.exec][:1]
+    assert len(A.planning_regions(plan, known)) < len(A.planning_regions(plan, assumed))
 
 
 def test_partition_cuts_after_every_execution_determined_item():
