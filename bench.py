@@ -357,6 +357,8 @@ def main():
                "B in [1,8] and L in [32,512] redrawn per call",
             3: "ResNet-50 layout NHWC bf16, batch 1, H=W in {224..640 step 32}",
             4: "config 2 with per-layer skip gates, batch 4, L in [128,384]",
+            7: "ResNet-50 backbone + detection-style neck (Resize to a computed shape, Concat, 3x3 convs), bf16 NHWC, "
+               "batch 1, H=W in {224..640 step 32}",
             6: "config 2's encoder with a skip gate per layer and sequence: kept sequences compacted by "
                "NonZero + Gather (execution-determined batch), ScatterRows back; B in [2,8], L in [128,384]"}[args.config],
             "calls": len(timed), "tokens": tokens},

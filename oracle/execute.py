@@ -115,6 +115,8 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
         elif k == "NonZero":
             y = O.nonzero(xs[0])
             res.exec_values.append(int(y.shape[1]))
+        elif k == "Resize":
+            y = O.resize_nearest(xs[0], xs[1])
         elif k == "ScatterRows":
             y = np.array(xs[0], copy=True)
             for j, r in enumerate(np.asarray(xs[1], dtype=np.int64).reshape(-1)):

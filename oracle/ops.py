@@ -97,3 +97,13 @@ def nonzero(x):
     x = np.asarray(x)
     cols = [idx for idx in np.ndindex(*x.shape) if x[idx] != 0]
     return np.asarray(cols, dtype=np.int64).reshape(len(cols), x.ndim).T
+
+
+def resize_nearest(x, sizes):
+    """Nearest neighbour over every axis: out[i0, i1, ..] = x[floor(i0 * D0 / S0), floor(i1 * D1 / S1), ..]."""
+    x = np.asarray(x)
+    out = x
+    for ax, (d, s_) in enumerate(zip(x.shape, [int(v) for v in sizes])):
+        idx = [(i * d) // s_ for i in range(s_)]
+        out = np.take(out, idx, axis=ax)
+    return out

@@ -33,7 +33,7 @@ OP_CLASS = {
     "Add": ISDOS, "Mul": ISDOS, "Relu": ISDOS, "Gelu": ISDOS, "Sigmoid": ISDOS, "Cast": ISDOS,
     "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
-    "Reshape": ISVDOS, "Slice": ISVDOS,
+    "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
 UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm")
@@ -539,6 +539,19 @@ class RDP:
         if x is UNDEF:
             return None
         return (NAC if x == NAC else list(x[:-1])), UNDEF
+
+    def _f_Resize(self, op):
+        """Output shape = the values of the sizes input (ISVDOS; lowered when they are resolved)."""
+        x, ts, tv = self.S[op.inputs[0]], self.S[op.inputs[1]], self.V[op.inputs[1]]
+        if x is UNDEF or ts is UNDEF or tv is UNDEF:
+            return None
+        if isinstance(tv, list):
+            if isinstance(x, list) and len(x) != len(tv):
+                raise ShapeMismatch("Resize rank")
+            return list(tv), UNDEF
+        if isinstance(x, list):
+            return [NAC] * len(x), UNDEF               # the rank survives, the extents do not
+        return NAC, UNDEF
 
     def _f_ScatterRows(self, op):
         s = self.S[op.inputs[0]]                        # a copy of input 0 with some rows replaced

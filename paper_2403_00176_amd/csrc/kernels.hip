@@ -987,6 +987,54 @@ __global__ __launch_bounds__(256) void gather_rows16_kernel(GatherArgs a, long l
   for (long long u = (long long)blockIdx.x * 256 + threadIdx.x; u < row_units; u += (long long)gridDim.x * 256) dst[u] = src[u];
 }
 
+// nearest-neighbour resize and concat along the last dim: pure copies in units of V
+template <class V>
+__global__ __launch_bounds__(256) void resize_nearest_kernel(ResizeArgs a) {
+  const long long total = a.out[0] * a.out[1] * a.out[2] * a.row_units;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const long long u = i % a.row_units;
+    long long pix = i / a.row_units;
+    const long long o2 = pix % a.out[2]; pix /= a.out[2];
+    const long long o1 = pix % a.out[1];
+    const long long o0 = pix / a.out[1];
+    const long long s0 = o0 * a.in[0] / a.out[0], s1 = o1 * a.in[1] / a.out[1], s2 = o2 * a.in[2] / a.out[2];
+    ((V*)a.y)[i] = ((const V*)a.x)[((s0 * a.in[1] + s1) * a.in[2] + s2) * a.row_units + u];
+  }
+}
+
+template <class V>
+__global__ __launch_bounds__(256) void concat_last_kernel(ConcatArgs a) {
+  const long long row_units = a.units[0] + a.units[1] + a.units[2] + a.units[3];
+  const long long total = a.rows * row_units;
+  for (long long i = (long long)blockIdx.x * 256 + threadIdx.x; i < total; i += (long long)gridDim.x * 256) {
+    const long long r = i / row_units;
+    long long u = i % row_units;
+    int k = 0;
+    while (k < 3 && u >= a.units[k]) { u -= a.units[k]; ++k; }
+    ((V*)a.y)[i] = ((const V*)a.x[k])[r * a.units[k] + u];
+  }
+}
+
+template <class K, class A>
+static hipError_t launch_copy_units(K kernel16, K kernel4, K kernel2, int unit_bytes, long long total, const A& a, hipStream_t s) {
+  if (total <= 0) return hipSuccess;
+  dim3 grid((unsigned)std::min<long long>((total + 255) / 256, 4096));
+  if (unit_bytes == 16) hipLaunchKernelGGL(kernel16, grid, dim3(256), 0, s, a);
+  else if (unit_bytes == 4) hipLaunchKernelGGL(kernel4, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(kernel2, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+hipError_t launch_resize(const Launch& L, const ResizeArgs& a, hipStream_t s) {
+  typedef void (*K)(ResizeArgs);
+  return launch_copy_units<K>(resize_nearest_kernel<uint4>, resize_nearest_kernel<unsigned>, resize_nearest_kernel<unsigned short>,
+                              L.unit_bytes, a.out[0] * a.out[1] * a.out[2] * a.row_units, a, s);
+}
+hipError_t launch_concat(const Launch& L, const ConcatArgs& a, hipStream_t s) {
+  typedef void (*K)(ConcatArgs);
+  return launch_copy_units<K>(concat_last_kernel<uint4>, concat_last_kernel<unsigned>, concat_last_kernel<unsigned short>,
+                              L.unit_bytes, a.rows * (a.units[0] + a.units[1] + a.units[2] + a.units[3]), a, s);
+}
+
 hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s) {
   if (a.rows <= 0 || a.cols <= 0) return hipSuccess;
   const long long eb = L.out_dtype == SOD2_BF16_TAG ? 2 : 4, row_bytes = a.cols * eb;

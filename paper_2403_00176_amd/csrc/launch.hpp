@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -155,6 +155,22 @@ struct ScatterArgs {
   int idx_i32;
 };
 
+// Nearest-neighbour Resize of a dense tensor [d0, d1, d2, c] -> [o0, o1, o2, c] (the last dim is kept):
+// out[i0, i1, i2, :] = x[floor(i0 * d0 / o0), floor(i1 * d1 / o1), floor(i2 * d2 / o2), :]
+struct ResizeArgs {
+  const void* x; void* y;
+  long long in[3], out[3];
+  long long row_units;       // copy units (16 bytes or one element) per innermost vector
+};
+
+// Concat of up to 4 dense tensors along the last dim: out[r, :] = x0[r, :] | x1[r, :] | ...
+struct ConcatArgs {
+  const void* x[4]; void* y;
+  long long rows;
+  long long units[4];        // copy units per row of each input (0 beyond n_in)
+  int n_in;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -174,7 +190,10 @@ struct Launch {
     AttnArgs attn;
     NonzeroArgs nz;
     ScatterArgs scatter;
+    ResizeArgs resize;
+    ConcatArgs concat;
   } u;
+  int unit_bytes = 0;      // resize / concat: bytes of one copy unit
   bool is_layernorm = false;
   double flops = 0, bytes = 0;
   long long d_past = 0;    // replay: rows the CacheAppend position / keys the attention length gain per step

@@ -15,13 +15,13 @@ namespace sod2 {
 static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
-    "NonZero", "Switch", "Combine", "ScatterRows"};
+    "NonZero", "Switch", "Combine", "ScatterRows", "Resize"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
   switch (kind) {
     case SOD2_OP_SHAPE: return 0;
-    case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: return 2;
+    case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: return 2;
     case SOD2_OP_NONZERO: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
     default: return 1;
   }
@@ -382,6 +382,16 @@ struct Analyser {
         if (x.k == LS::UNDEF) return r;
         if (x.k == LS::NAC) return done(LS::nac(), LS::nac());
         return done(LS::list({LV::c((int64_t)x.d.size()), LV::of(Expr::symbol(exec_symbol(op_id)))}), LS::nac());
+      }
+      case SOD2_OP_RESIZE: {                             // output shape = the values of the sizes input (ISVDOS)
+        const LS &x = in_s(0), &ts = in_s(1), &tv = in_v(1);
+        if (x.k == LS::UNDEF || ts.k == LS::UNDEF || tv.k == LS::UNDEF) return r;
+        if (tv.is_list()) {
+          if (x.is_list() && x.d.size() != tv.d.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Resize rank");
+          return done(LS::list(tv.d));
+        }
+        if (x.is_list()) return done(LS::list(std::vector<LV>(x.d.size(), LV::nac())));   // the rank survives
+        return done(LS::nac());
       }
       case SOD2_OP_SCATTERROWS: {                        // a copy of input 0 with some rows replaced
         if (in_s(0).k == LS::UNDEF) return r;

@@ -21,6 +21,8 @@ hipError_t launch_append(const Launch& L, const AppendArgs& a, hipStream_t s);
 hipError_t launch_argmax(const Launch& L, const ArgmaxArgs& a, hipStream_t s);
 hipError_t launch_nonzero(const NonzeroArgs& a, hipStream_t s);
 hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s);
+hipError_t launch_resize(const Launch& L, const ResizeArgs& a, hipStream_t s);
+hipError_t launch_concat(const Launch& L, const ConcatArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
 
@@ -833,6 +835,77 @@ struct Builder {
     return L;
   }
 
+  // copy unit of a dense row of `elems` elements: 16 bytes when every pointer offset and row allows it
+  static int copy_unit(int64_t eb, std::initializer_list<int64_t> row_elems, std::initializer_list<int64_t> byte_offs) {
+    bool v16 = true;
+    for (int64_t e : row_elems) if ((e * eb) % 16 != 0) v16 = false;
+    for (int64_t o : byte_offs) if (o % 16 != 0) v16 = false;
+    return v16 ? 16 : (int)eb;
+  }
+
+  Launch resize(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_RESIZE;
+    const Op& op = G.ops[gr.ops[0]];
+    const View &vx = view_of(op.in[0]), &vo = view_of(gr.out);
+    int dt = G.tensors[op.in[0]].dtype;
+    size_t r = vx.dims.size();
+    if (!vx.contiguous() || r < 1 || r > 4 || vo.dims.size() != r || vo.dims[r - 1] != vx.dims[r - 1] ||
+        (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt)
+      throw Error(SOD2_ERR_UNSUPPORTED, "Resize kernel: nearest neighbour on a dense float tensor of rank <= 4 whose last dim is kept");
+    ResizeArgs a{};
+    for (int k = 0; k < 3; ++k) a.in[k] = a.out[k] = 1;
+    for (size_t k = 0; k + 1 < r; ++k) { a.in[3 - (r - 1) + k] = vx.dims[k]; a.out[3 - (r - 1) + k] = vo.dims[k]; }
+    for (int k = 0; k < 3; ++k) if (a.in[k] <= 0 && a.out[k] > 0) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Resize from an empty dim");
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_t(gr.out);
+    int64_t eb = dtype_bytes(dt), c = vx.dims[r - 1];
+    L.unit_bytes = copy_unit(eb, {c}, {L.r[0].byte_off, L.r[1].byte_off});
+    a.row_units = c * eb / L.unit_bytes;
+    L.u.resize = a;
+    L.bytes = (double)eb * ((double)vx.numel() + (double)vo.numel());
+    return L;
+  }
+
+  Launch concat(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_CONCAT;
+    const Op& op = G.ops[gr.ops[0]];
+    const View& vo = view_of(gr.out);
+    int dt = G.tensors[gr.out].dtype;
+    size_t r = vo.dims.size(), n = op.in.size();
+    int64_t ax = op.ia.empty() ? 0 : ((op.ia[0] % (int64_t)r) + (int64_t)r) % (int64_t)r;
+    if (n < 1 || n > 4 || r < 1 || ax != (int64_t)r - 1 || (dt != SOD2_BF16 && dt != SOD2_F32))
+      throw Error(SOD2_ERR_UNSUPPORTED, "Concat kernel: up to 4 dense float tensors along the last dim");
+    ConcatArgs a{};
+    a.n_in = (int)n;
+    a.rows = 1;
+    for (size_t k = 0; k + 1 < r; ++k) a.rows *= vo.dims[k];
+    int64_t eb = dtype_bytes(dt);
+    int64_t cols[4] = {0, 0, 0, 0};
+    bool v16 = true;
+    for (size_t k = 0; k < n; ++k) {
+      const View& vi = view_of(op.in[k]);
+      if (!vi.contiguous() || vi.dims.size() != r || G.tensors[op.in[k]].dtype != dt)
+        throw Error(SOD2_ERR_UNSUPPORTED, "Concat kernel: operands must be dense and of the result's type and rank");
+      for (size_t j = 0; j + 1 < r; ++j) if (vi.dims[j] != vo.dims[j]) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Concat operands differ outside the axis");
+      cols[k] = vi.dims[r - 1];
+      L.r[k] = ref_of(vi, dt);
+      if ((cols[k] * eb) % 16 != 0 || L.r[k].byte_off % 16 != 0) v16 = false;
+    }
+    L.r[4] = ref_t(gr.out);
+    if (L.r[4].byte_off % 16 != 0) v16 = false;
+    L.unit_bytes = v16 ? 16 : (int)eb;
+    for (size_t k = 0; k < n; ++k) a.units[k] = cols[k] * eb / L.unit_bytes;
+    L.in_dtype = L.out_dtype = dt;
+    L.u.concat = a;
+    L.bytes = 2.0 * eb * (double)vo.numel();
+    return L;
+  }
+
   Launch make(const Group& gr) {
     // a result without elements (an empty compacted batch): nothing to compute
     auto od = b.dims.find(gr.out);
@@ -844,6 +917,8 @@ struct Builder {
     switch (gr.kind) {
       case G_NONZERO: return nonzero(gr);
       case G_SCATTER: return scatter(gr);
+      case G_RESIZE: return resize(gr);
+      case G_CONCAT: return concat(gr);
       case G_ATTENTION: return attention(gr);
       case G_GATHER: return gather(gr);
       case G_CACHEAPPEND: return append(gr);
@@ -897,6 +972,22 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       NonzeroArgs a = L.u.nz;
       a.x = P.at(L.r[0]); a.out = (long long*)P.at(L.r[1]); a.count = (long long*)P.at(L.r[2]);
       return launch_nonzero(a, s);
+    }
+    case K_RESIZE: {
+      ResizeArgs a = L.u.resize;
+      a.x = P.at(L.r[0]); a.y = P.at(L.r[1]);
+      if (L.unit_bytes == 16 && (!al16(a.x) || !al16(a.y))) return hipErrorInvalidValue;
+      return launch_resize(L, a, s);
+    }
+    case K_CONCAT: {
+      ConcatArgs a = L.u.concat;
+      for (int k = 0; k < a.n_in; ++k) {
+        a.x[k] = P.at(L.r[k]);
+        if (L.unit_bytes == 16 && !al16(a.x[k])) return hipErrorInvalidValue;
+      }
+      a.y = P.at(L.r[4]);
+      if (L.unit_bytes == 16 && !al16(a.y)) return hipErrorInvalidValue;
+      return launch_concat(L, a, s);
     }
     case K_SCATTER: {
       ScatterArgs a = L.u.scatter;

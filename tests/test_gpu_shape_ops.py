@@ -1,0 +1,79 @@
+"""Resize (nearest) and Concat kernels and the detection-style neck on the GPU against the oracle."""
+import numpy as np
+import pytest
+
+from oracle import rdp as R, plan as P, arena as A, execute
+from workloads import configs, GraphBuilder
+
+pytestmark = pytest.mark.gpu
+
+
+def rel_err(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+@pytest.fixture(scope="module")
+def S():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2403_00176_amd as S
+    return S
+
+
+@pytest.mark.parametrize("dtype,c", [("bf16", 256), ("bf16", 5), ("f32", 6), ("f32", 64)])
+def test_resize_and_concat_kernels(S, dtype, c):
+    """Pure copies: exact.  Channel counts with and without 16-byte rows; enlarging, shrinking, identity."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    b = GraphBuilder([("H", 1, 64), ("W", 1, 64), ("OH", 1, 128), ("OW", 1, 128)])
+    x = b.input("x", dtype, [2, "H", "W", c])
+    like = b.input("like", dtype, [2, "OH", "OW", 3 * c])
+    shp_x = b.op("Shape", [x], dtype="i64")
+    shp_l = b.op("Shape", [like], dtype="i64")
+    ax0 = b.const("ax0", [0])
+    sizes = b.op("Concat", [b.op("Slice", [shp_x, b.const("a0", [0]), b.const("a1", [1]), ax0], dtype="i64"),
+                            b.op("Slice", [shp_l, b.const("b1", [1]), b.const("b3", [3]), ax0], dtype="i64"),
+                            b.op("Slice", [shp_x, b.const("c3", [3]), b.const("c4", [4]), ax0], dtype="i64")], axis=0, dtype="i64")
+    up = b.op("Resize", [x, sizes], hint="up")
+    b.mark_output(b.op("Concat", [up, like, up], axis=3, hint="cat"), "y")
+    g = b.build()
+    ses = Session(g)
+    ses.upload_weights({})
+    po = P.build_plan(g, R.RDP(g).analyse())
+    rs = np.random.RandomState(c)
+    for H, W, OH, OW in ((3, 5, 6, 10), (8, 8, 3, 5), (4, 4, 4, 4), (1, 1, 7, 2), (16, 12, 32, 24)):
+        sym = {"H": H, "W": W, "OH": OH, "OW": OW}
+        print(f"case resize/concat {dtype} c={c} {sym}", flush=True)
+        ins = {0: rs.randn(2, H, W, c), 1: rs.randn(2, OH, OW, 3 * c)}
+        bnd = ses.bind(sym)
+        assert S.sod2_binding_dump(bnd) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(bnd))
+        ses.run(bnd, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {}, ins)
+        assert np.array_equal(to_host(outs[0]), ref.values[g.tensor_id("y")])
+
+
+def test_detection_neck(S):
+    """Reduced backbone + the full neck at three image sizes: structure byte for byte, the three output
+    maps within the bf16 bar."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    w = configs.fpn(7, 3, sizes=(64, 96, 128), stages=(1, 1, 1, 1))
+    ses = Session(w.graph)
+    W = w.make_weights()
+    ses.upload_weights(W)
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    for ci, sym in [(0, {"H": 96, "W": 64}), (1, {"H": 64, "W": 64}), (2, {"H": 128, "W": 96})]:
+        print(f"case neck {sym}", flush=True)
+        ins = w.make_inputs(ci, sym)
+        b = ses.bind(sym)
+        assert S.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(w.graph, po.order, W, ins)
+        for t, o in zip(w.graph.outputs(), outs):
+            got = to_host(o)
+            assert got.shape == ref.values[t].shape and np.isfinite(got).all()
+            assert rel_err(got, ref.values[t]) <= 2e-2, (w.graph.tensors[t].name, sym, rel_err(got, ref.values[t]))

@@ -1,0 +1,121 @@
+"""Pins for the input-shape-and-value determined operators added for the detection-style neck
+(Table 2, ISVDOS): Resize whose target shape is computed from Shape of another tensor, arithmetic on
+value maps, and Concat of activations.  CPU only."""
+import numpy as np
+import pytest
+
+import paper_2403_00176_amd as S
+from oracle import ops as O
+from oracle import execute, rdp as R, plan as P, arena as A
+from workloads import configs, GraphBuilder
+
+
+def test_resize_nearest_brute_force_and_repeat():
+    rs = np.random.RandomState(9)
+    x = rs.randn(2, 3, 5, 4)
+    for sizes in ((2, 6, 10, 4), (2, 7, 3, 4), (2, 3, 5, 4), (4, 1, 11, 4)):
+        got = O.resize_nearest(x, sizes)
+        ref = np.zeros(sizes)
+        for i0 in range(sizes[0]):
+            for i1 in range(sizes[1]):
+                for i2 in range(sizes[2]):
+                    ref[i0, i1, i2] = x[i0 * 2 // sizes[0], i1 * 3 // sizes[1], i2 * 5 // sizes[2]]
+        assert np.array_equal(got, ref)
+    # an exact doubling repeats every pixel (what the neck does on images in multiples of 32)
+    assert np.array_equal(O.resize_nearest(x, (2, 6, 10, 4)), np.repeat(np.repeat(x, 2, axis=1), 2, axis=2))
+
+
+def test_resize_is_lowered_when_its_sizes_are_known_symbolically():
+    # sizes = [Shape(x)[0], 2 * Shape(x)[1:3], Shape(x)[3]]: arithmetic on a value map, then Resize
+    b = GraphBuilder([("H", 2, 64), ("W", 2, 64)])
+    x = b.input("x", "f32", [1, "H", "W", 8])
+    shp = b.op("Shape", [x], dtype="i64")
+    ax0 = b.const("ax0", [0])
+    n = b.op("Slice", [shp, b.const("c0", [0]), b.const("c1", [1]), ax0], dtype="i64")
+    hw = b.op("Slice", [shp, b.const("d1", [1]), b.const("d3", [3]), ax0], dtype="i64")
+    hw2 = b.op("Mul", [hw, b.const("two", [2, 2])], dtype="i64")
+    c = b.op("Slice", [shp, b.const("e3", [3]), b.const("e4", [4]), ax0], dtype="i64")
+    sizes = b.op("Concat", [n, hw2, c], axis=0, dtype="i64")
+    y = b.op("Resize", [x, sizes])
+    b.mark_output(y, "y")
+    g = b.build()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.V[sizes]) == "[k:1, e:2*H, e:2*W, k:8]"
+    assert R.fmt_list(r.S[y]) == "[k:1, e:2*H, e:2*W, k:8]"
+    assert R.OP_CLASS["Resize"] == R.ISVDOS
+    plan = P.build_plan(g, r)
+    assert all(plan.folded[n_] for n_, op in enumerate(g.ops) if op.kind != "Resize")     # only the Resize runs
+    # brute force over a box of symbol values: the expression equals the shape the operator really produces
+    for H in (2, 3, 7):
+        for W in (2, 5):
+            res = execute.run(g, plan.order, {}, {0: np.zeros((1, H, W, 8))})
+            assert list(res.values[y].shape) == [d.eval({"H": H, "W": W}) for d in r.S[y]]
+    # the library agrees byte for byte
+    gl = S.sod2_graph_build(g)
+    rl = S.sod2_rdp_infer(gl)
+    assert S.sod2_rdp_dump(rl) == R.dump(r)
+    assert S.sod2_plan_dump(S.sod2_plan(gl, rl)) == P.dump(plan)
+    assert S.sod2_graph_op_class(gl, len(g.ops) - 1) == "ISVDOS"
+
+
+def test_resize_with_unknown_sizes_is_nac():
+    b = GraphBuilder([("H", 2, 64)])
+    x = b.input("x", "f32", [1, "H", 4, 8])
+    sizes = b.input("sizes", "i64", [4])                  # values arrive at run time: nothing to propagate
+    y = b.op("Resize", [x, sizes])
+    b.mark_output(y)
+    g = b.build()
+    r = R.RDP(g).analyse()
+    assert r.S[y] == R.NAC                                 # an ISVDOS operator that cannot be lowered
+    gl = S.sod2_graph_build(g)
+    assert S.sod2_rdp_dump(S.sod2_rdp_infer(gl)) == R.dump(r)
+    mismatch = GraphBuilder([])
+    x2 = mismatch.input("x", "f32", [1, 4, 4, 8])
+    mismatch.mark_output(mismatch.op("Resize", [x2, mismatch.const("s", [8, 8, 8])]))
+    with pytest.raises(R.ShapeMismatch):
+        R.RDP(mismatch.build()).analyse()
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_rdp_infer(S.sod2_graph_build(mismatch.build()))
+    assert e.value.code == -3
+
+
+def small_fpn():
+    return configs.fpn(7, 4, sizes=(64, 96, 128), stages=(1, 1, 1, 1))
+
+
+def test_neck_shapes_groups_and_arena():
+    w = small_fpn()
+    g = w.graph
+    r = R.RDP(g).analyse()
+    plan = P.build_plan(g, r)
+    # the enlarged map has, symbolically, the shape of the map it is concatenated with: no nac anywhere
+    assert all(isinstance(s, list) and all(R.is_expr(d) for d in s) for s in r.S)
+    for op in g.ops:
+        if op.kind == "Resize":
+            like = [o for o in g.ops if o.kind == "Concat" and op.outputs[0] in o.inputs and g.tensors[o.outputs[0]].dtype == "bf16"][0]
+            other = [t for t in like.inputs if t != op.outputs[0]][0]
+            assert [str(d) for d in r.S[op.outputs[0]]] == [str(d) for d in r.S[other]]
+    kinds = [plan.groups[it.ref].kind for it in plan.items if it.is_group]
+    assert kinds.count("RESIZE") == 2 and kinds.count("CONCAT") == 2
+    for n_, op in enumerate(g.ops):                        # every shape computation is folded
+        if op.kind in ("Shape", "Slice") or (op.kind == "Concat" and g.tensors[op.outputs[0]].dtype == "i64"):
+            assert plan.folded[n_]
+    for call in w.calls + [{"H": 96, "W": 64}]:
+        b = A.bind(plan, call)
+        A.check_no_overlap(b)
+        assert b.arena_bytes == b.peak_live
+        res = execute.run(g, plan.order, w.make_weights(), w.make_inputs(0, call)) if call is w.calls[0] else None
+        if res is not None:
+            for t, dims in b.dims.items():
+                assert list(res.values[t].shape) == dims
+            for t in g.outputs():                          # strides 8, 16, 32
+                s_ = {"out8": 8, "out16": 16, "out32": 32}[g.tensors[t].name]
+                assert list(res.values[t].shape) == [1, call["H"] // s_, call["W"] // s_, 256]
+    # library: same maps, plan and bindings
+    gl = S.sod2_graph_build(g)
+    rl = S.sod2_rdp_infer(gl)
+    assert S.sod2_rdp_dump(rl) == R.dump(r)
+    pl = S.sod2_plan(gl, rl)
+    assert S.sod2_plan_dump(pl) == P.dump(plan)
+    for call in w.calls + [{"H": 96, "W": 64}]:
+        assert S.sod2_binding_dump(S.sod2_bind(pl, call)) == A.dump(A.bind(plan, call))

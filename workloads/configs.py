@@ -259,6 +259,61 @@ def config3(n_calls=32):
     return resnet50(3, n_calls)
 
 
+def fpn(config=7, n_calls=16, sizes=tuple(range(224, 641, 32)), stages=(3, 4, 6, 3), width=256, dtype="bf16") -> Workload:
+    """A detection-style neck on the ResNet backbone (after the paper's YOLO-V6 experiment: images in
+    multiples of 32): features of stride 8 / 16 / 32, a top-down path that enlarges the coarser map to
+    the size of the finer one (Resize whose target shape is *computed* from Shape of the other tensor:
+    an ISVDOS operator, Table 2), Concat along the channels, 3x3 convolutions; three output maps."""
+    b = GraphBuilder([("H", min(sizes), max(sizes)), ("W", min(sizes), max(sizes))])
+    w = _Weights(config)
+    x = b.input("x", dtype, [1, "H", "W", 3])
+    y = _conv(b, w, x, 3, 64, 7, 2, 3, "stem", dtype, True)
+    y = b.op("MaxPool", [y], kernel=3, stride=2, pad=1, hint="pool")
+    cin, feats = 64, []
+    for s, n in enumerate(stages):
+        mid, cout = 64 << s, 256 << s
+        for i in range(n):
+            stride = 2 if (i == 0 and s > 0) else 1
+            y = _bottleneck(b, w, y, cin, mid, cout, stride, i == 0, f"s{s}b{i}", dtype)
+            cin = cout
+        feats.append((y, cout))
+    (c3, n3), (c4, n4), (c5, n5) = feats[1], feats[2], feats[3]
+    zero, one, three, four = (b.const(f"k{v}", [v]) for v in (0, 1, 3, 4))
+    axis0 = b.const("ax0", [0])
+
+    def part(t, lo, hi, tag):        # Shape(t)[lo:hi] as an exporter writes it
+        shp = b.op("Shape", [t], dtype="i64", hint=tag + ".shape")
+        return b.op("Slice", [shp, lo, hi, axis0], dtype="i64", hint=tag + ".part")
+
+    def enlarge(small, like, tag):   # nearest-neighbour Resize of `small` to the spatial size of `like`
+        sizes_t = b.op("Concat", [part(small, zero, one, tag + ".n"), part(like, one, three, tag + ".hw"),
+                                  part(small, three, four, tag + ".c")], axis=0, dtype="i64", hint=tag + ".sizes")
+        return b.op("Resize", [small, sizes_t], hint=tag)
+
+    p5 = _conv(b, w, c5, n5, width, 1, 1, 0, "lat5", dtype, False)
+    p4 = _conv(b, w, c4, n4, width, 1, 1, 0, "lat4", dtype, False)
+    m4 = b.op("Concat", [enlarge(p5, p4, "up5"), p4], axis=3, hint="cat4")
+    m4 = _conv(b, w, m4, 2 * width, width, 3, 1, 1, "fuse4", dtype, True)
+    p3 = _conv(b, w, c3, n3, width, 1, 1, 0, "lat3", dtype, False)
+    m3 = b.op("Concat", [enlarge(m4, p3, "up4"), p3], axis=3, hint="cat3")
+    m3 = _conv(b, w, m3, 2 * width, width, 3, 1, 1, "fuse3", dtype, True)
+    b.mark_output(_conv(b, w, m3, width, width, 1, 1, 0, "head3", dtype, False), "out8")
+    b.mark_output(_conv(b, w, m4, width, width, 1, 1, 0, "head4", dtype, False), "out16")
+    b.mark_output(_conv(b, w, p5, width, width, 1, 1, 0, "head5", dtype, False), "out32")
+    g = b.build()
+    idx = rng.randint(7000 + config, (n_calls,), 0, len(sizes) - 1)
+    calls = [{"H": int(sizes[i]), "W": int(sizes[i])} for i in idx]
+
+    def make_inputs(call_idx, sym):
+        return {g.tensor_id("x"): rng.uniform(100000 * config + call_idx, (1, sym["H"], sym["W"], 3))}
+
+    return Workload(f"cfg{config}", config, g, dtype, calls, lambda: w.make(g), make_inputs, w.spec)
+
+
+def config7(n_calls=16):
+    return fpn(7, n_calls)
+
+
 # ---------------------------------------------------------------------------
 # config 5: autoregressive decoder with a KV cache in the arena (two graphs, one set of weights)
 # ---------------------------------------------------------------------------
@@ -367,4 +422,4 @@ def config5(n_prompts=8, layers=24):
     return decoder(5, layers=layers, n_prompts=n_prompts)
 
 
-BUILDERS = {1: config1, 2: config2, 3: config3, 4: config4, 6: config6}
+BUILDERS = {1: config1, 2: config2, 3: config3, 4: config4, 6: config6, 7: config7}

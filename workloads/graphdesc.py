@@ -45,6 +45,7 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "NonZero": (),
     "Switch": (),             # float attr threshold
     "Combine": (),
+    "Resize": (),             # nearest neighbour, target shape = the values of input 1 ("sizes")
     "ScatterRows": (),        # ScatterND with row indices: copy of input 0 whose rows input 1 are replaced by input 2
 }
 OP_KINDS = tuple(OP_ATTRS)
