@@ -1201,7 +1201,112 @@ hipError_t launch_gemm(const Launch& L, const GemmArgs& g, hipStream_t s) {
   return launch_mfma_variant(al, g, L.variant, s);
 }
 
+// ---------------------------------------------------------------------------------------------
+// Convolution with very few input channels and 64 output channels (the 7x7 / 2 stem on RGB images).
+// The implicit-GEMM kernels gather such an operand element by element (k = (kh, kw, c) with c < 8 has
+// no 16-byte runs).  Here a workgroup takes 128 consecutive output pixels of one output row, stages
+// the KH input rows they touch in LDS once (contiguous in memory: [iw, c] is dense), and reads MFMA
+// operands straight from that patch: with k ordered (kh, j = kw * C + c) and j padded from KW * C to 24,
+// the 8 consecutive k of a lane are 8 consecutive patch elements starting at stride * C * pixel + 8 r.
+// The weights are re-laid to the same padded order in LDS (zeros in the padding, so whatever the patch
+// holds there does not count).
+constexpr int STEM_BM = 128, STEM_ROW = 1056, STEM_KH = 7, STEM_J = 24, STEM_O = 64, STEM_K = 176, STEM_WROW = 184;
+__global__ __launch_bounds__(256) void conv_stem_kernel(ConvArgs c) {
+  __shared__ __attribute__((aligned(16))) bf16_t patch[STEM_KH][STEM_ROW];
+  __shared__ __attribute__((aligned(16))) bf16_t wt[STEM_O][STEM_WROW];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tiles_w = (c.OW + STEM_BM - 1) / STEM_BM;
+  int t = blockIdx.x;
+  const int ow0 = (t % tiles_w) * STEM_BM; t /= tiles_w;
+  const int oh = t % c.OH, nb = t / c.OH;
+  const int J = c.KW * c.C, step = c.stride * c.C;
+  const bf16_t* w = (const bf16_t*)c.w;
+  {
+    // one output channel per lane, the kh rows dealt over the 4 waves; fixed trip counts so that all
+    // loads of a thread are in flight together
+    const int n = tid & 63;
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      const int kh = wave + 4 * kk;
+      const bf16_t* wr = w + ((long long)n * c.KH + kh) * J;
+      bf16_t v[STEM_J];
+#pragma unroll
+      for (int j = 0; j < STEM_J; ++j) v[j] = (kh < c.KH && j < J) ? wr[j] : (bf16_t)0;
+#pragma unroll
+      for (int j = 0; j < STEM_J; ++j) if (kh * STEM_J + j < STEM_K) wt[n][kh * STEM_J + j] = v[j];
+    }
+  }
+  const int need = step * (STEM_BM - 1) + STEM_J + 8;               // patch elements a row of this tile can touch
+  const long long first = (long long)(ow0 * c.stride - c.pad) * c.C;  // element offset of patch[.][0] in its input row
+  const long long row_len = (long long)c.W * c.C;
+#pragma unroll
+  for (int kh = 0; kh < STEM_KH; ++kh) {
+    const int ih = oh * c.stride - c.pad + kh;
+    const bf16_t* xr = (const bf16_t*)c.x + ((long long)nb * c.H + ih) * row_len;
+    const bool row_ok = kh < c.KH && ih >= 0 && ih < c.H;
+    bf16_t v[(STEM_ROW + 255) / 256];
+#pragma unroll
+    for (int i = 0; i < (STEM_ROW + 255) / 256; ++i) {
+      const int e = tid + 256 * i;
+      const long long off = first + e;
+      v[i] = (row_ok && e < need && off >= 0 && off < row_len) ? xr[off] : (bf16_t)0;
+    }
+#pragma unroll
+    for (int i = 0; i < (STEM_ROW + 255) / 256; ++i) {
+      const int e = tid + 256 * i;
+      if (e < need) patch[kh][e] = v[i];
+    }
+  }
+  __syncthreads();
+  const int m = wave * 32 + (lane & 31), kg = lane >> 5;
+  f32x16_t acc[2];
+#pragma unroll
+  for (int j = 0; j < 2; ++j)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+#pragma unroll
+  for (int ks = 0; ks < STEM_K / 16; ++ks) {
+    const int q = 2 * ks + kg, kh = q / 3, r8 = (q % 3) * 8;
+    V16 af;
+    af.u = zero4();
+    if (kh < c.KH) {
+      const bf16_t* p = &patch[kh][step * m + r8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) af.h[e] = p[e];
+    }
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      V16 bf;
+      bf.u = *(const uint4*)&wt[j * 32 + (lane & 31)][ks * 16 + kg * 8];
+      acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af.b, bf.b, acc[j], 0, 0, 0);
+    }
+  }
+  const bf16_t* bias = (const bf16_t*)c.bias;
+  bf16_t* y = (bf16_t*)c.y + ((long long)nb * c.OH + oh) * c.OW * STEM_O;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int n = j * 32 + (lane & 31);
+    const float bv = bias ? bf2f(bias[n]) : 0.f;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int ow = ow0 + wave * 32 + (r >> 2) * 8 + kg * 4 + (r & 3);
+      if (ow < c.OW) y[(long long)ow * STEM_O + n] = f2bf(apply_act(acc[j][r] + bv, c.act1));
+    }
+  }
+}
+
+static bool stem_ok(const Launch& L, const ConvArgs& c) {
+  return L.in_dtype == SOD2_BF16_TAG && L.variant >= V_DL0 && c.O == STEM_O && c.KH <= STEM_KH && c.KW * c.C <= STEM_J &&
+         c.C < 8 && c.stride * c.C * (STEM_BM - 1) + STEM_J + 8 <= STEM_ROW && !c.res && c.act2 == ACT_NONE;
+}
+
 hipError_t launch_conv(const Launch& L, const ConvArgs& c, hipStream_t s) {
+  if (stem_ok(L, c)) {
+    const long long tiles = (long long)c.NB * c.OH * ((c.OW + STEM_BM - 1) / STEM_BM);
+    if (tiles <= 0) return hipSuccess;
+    hipLaunchKernelGGL(conv_stem_kernel, dim3((unsigned)tiles), dim3(256), 0, s, c);
+    return hipGetLastError();
+  }
   if (L.variant == V_SIMPLE || L.in_dtype != SOD2_BF16_TAG) {
     long long total = (long long)c.NB * c.OH * c.OW * c.O;
     dim3 grid((unsigned)((total + 255) / 256));
