@@ -118,8 +118,22 @@ def bench_decoder(args, S, dev):
                          last_step_kernels={k: dict(n=v[0], us=round(v[1] * 1e3, 1), gbs=round(v[2] / max(v[1], 1e-9) / 1e6, 1))
                                             for k, v in per.items()}))
         print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+    # a decode step must stream every weight once (the embedding rows aside) and the keys / values cached so far
+    d = w.decode
+    emb = {d.tensor_id("tok_emb"), d.tensor_id("pos_emb")}
+    hidden = d.tensors[d.tensor_id("tok_emb")].dims[1]
+    wbytes = sum(x.numel() * x.element_size() for t, x in zip(d.weights(), ses.dec.weights) if t not in emb) + 2 * hidden * 2
+    kv_row_bytes = sum(d.tensors[t].dims[1] * 2 for t in d.session_inputs())     # one cached row of every layer's K and V
+    for r in rows:
+        kv = kv_row_bytes * (r["P"] + w.t_max / 2)                         # mean over the generated tokens
+        gbs = (wbytes + kv) / (r["decode_ms_per_token"] * 1e-3) / 1e9
+        r["roofline"] = dict(bound="hbm", achieved=round(gbs, 1), peak=PEAK_HBM_GBS, unit="GB/s", frac=round(gbs / PEAK_HBM_GBS, 4),
+                             algorithmic_bytes_per_token=int(wbytes + kv))
     out = {"metric": "decode latency per generated token", "unit": "ms",
            "value": round(sum(r["decode_ms_per_token"] for r in rows) / len(rows), 4), "n_gpus": 1,
+           "roofline": dict(bound="hbm", unit="GB/s", peak=PEAK_HBM_GBS,
+                            achieved=round(sum(r["roofline"]["achieved"] for r in rows) / len(rows), 1),
+                            frac=round(sum(r["roofline"]["frac"] for r in rows) / len(rows), 4), traffic=None),
            "config": {"workload": "config 5: 24-layer decoder, hidden 1024, KV cache in the arena, greedy 256 tokens"},
            "dtype": "bf16", "data": "synthetic", "sequences": rows}
     print(json.dumps(out))
