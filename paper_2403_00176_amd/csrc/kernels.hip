@@ -8,8 +8,14 @@
 //    over a small fixed set (the fat / regular / skinny versions of Section 4.4.2); nothing is
 //    compiled per shape.
 //  * gemm_simple: any dtype, any strides, plain FMA tiles (fp32 graphs, odd layouts).
+//  * conv_stem_kernel: convolutions with fewer than 8 input channels and 64 output channels.
+//  * gemv_f32_kernel: fp32 contractions with at most 8 rows (the gate networks).
 //  * row kernels: LayerNorm and softmax with one wavefront per row, 16-byte loads, wave shuffles.
-//  * reduce_mean, maxpool.
+//  * reduce_mean (plain and wide), maxpool, elementwise chains (Fig. 4).
+//  * gather, cache append, arg-max; NonZero, ScatterRows, wide row gather (batch compaction);
+//    nearest-neighbour Resize and Concat along the last dim.
+// The direct-to-LDS contraction, its split-K pass and the skinny bf16 kernels are in gemm.hip, the
+// fused attention kernels in attention.hip.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
