@@ -119,6 +119,8 @@ sod2_status sod2_graph_build(const sod2_graph_desc* desc_host, sod2_graph_t** ou
 void sod2_graph_destroy(sod2_graph_t*);
 /* class of operator op: 0 ISDO, 1 ISDOS, 2 ISVDOS, 3 EDO (Table 2) */
 sod2_status sod2_graph_op_class(const sod2_graph_t*, int32_t op, int32_t* cls);
+/* the same for an operator kind (sod2_op_kind), without a graph */
+sod2_status sod2_op_kind_class(int32_t kind, int32_t* cls);
 
 /* -- RDP (Alg. 1) ------------------------------------------------------------------------- */
 sod2_status sod2_rdp_infer(const sod2_graph_t*, sod2_rdp_t** out);

@@ -28,7 +28,7 @@ OP_KINDS = ["Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMu
 OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
 
 EXPORTS = [
-    "sod2_graph_build", "sod2_graph_destroy", "sod2_graph_op_class", "sod2_rdp_infer", "sod2_rdp_infer_ordered",
+    "sod2_graph_build", "sod2_graph_destroy", "sod2_graph_op_class", "sod2_op_kind_class", "sod2_rdp_infer", "sod2_rdp_infer_ordered",
     "sod2_rdp_destroy", "sod2_rdp_query", "sod2_rdp_sweeps", "sod2_rdp_dump", "sod2_plan", "sod2_plan_destroy",
     "sod2_plan_counts", "sod2_plan_dump", "sod2_bind", "sod2_bind_decided", "sod2_bind_executed",
     "sod2_binding_destroy",
@@ -211,6 +211,12 @@ def sod2_graph_build(desc) -> Graph:
 def sod2_graph_op_class(g: Graph, op: int) -> str:
     c = C.c_int32()
     _check(_lib.sod2_graph_op_class(g.ptr, op, C.byref(c)))
+    return OP_CLASS_NAMES[c.value]
+
+
+def sod2_op_kind_class(kind: str) -> str:
+    c = C.c_int32()
+    _check(_lib.sod2_op_kind_class(OP_KINDS.index(kind), C.byref(c)))
     return OP_CLASS_NAMES[c.value]
 
 

@@ -114,6 +114,13 @@ sod2_status sod2_graph_op_class(const sod2_graph_t* g, int32_t op, int32_t* cls)
   SOD2_CATCH
 }
 
+sod2_status sod2_op_kind_class(int32_t kind, int32_t* cls) {
+  SOD2_TRY
+  if (!cls || kind < 0 || kind >= SOD2_OP_COUNT) throw Error(SOD2_ERR_INVALID_ARG, "bad operator kind");
+  *cls = op_class(kind);
+  SOD2_CATCH
+}
+
 static sod2_status infer(const sod2_graph_t* g, const std::vector<int>* order, sod2_rdp_t** out) {
   SOD2_TRY
   if (!g || !out) throw Error(SOD2_ERR_INVALID_ARG, "null argument");

@@ -235,3 +235,17 @@ def test_known_constant_conflict_is_an_error():
     b.mark_output(b.op("MatMul", [x, b.weight("w", "f32", [7, 16])], transB=0))
     with pytest.raises(R.ShapeMismatch):
         analyse(b.build())
+
+
+def test_operator_classes_follow_table2():
+    """The classes of Table 2 for the operators it lists (fixture: tests/golden/table2_operator_classes.txt;
+    "Reduce" and "Elementwise w/ broadcast" of the table appear as ReduceMean and Mul), in the oracle and
+    in the library."""
+    import os
+    import paper_2403_00176_amd as S
+    rows = [l.split() for l in open(os.path.join(os.path.dirname(__file__), "golden", "table2_operator_classes.txt"))
+            if l.strip() and not l.startswith("#")]
+    assert len(rows) >= 19
+    for name, cls in rows:
+        assert R.OP_CLASS[name] == cls, name
+        assert S.sod2_op_kind_class(name) == cls, name
