@@ -115,6 +115,12 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
         elif k == "NonZero":
             y = O.nonzero(xs[0])
             res.exec_values.append(int(y.shape[1]))
+        elif k == "Range":
+            y = np.arange(int(np.asarray(xs[0]).reshape(-1)[0]), int(np.asarray(xs[1]).reshape(-1)[0]),
+                          int(np.asarray(xs[2]).reshape(-1)[0]), dtype=np.int64)
+        elif k == "Expand":
+            tgt = np.broadcast_shapes(xs[0].shape, tuple(int(v) for v in xs[1]))
+            y = np.broadcast_to(xs[0], tgt)
         elif k == "Resize":
             y = O.resize_nearest(xs[0], xs[1])
         elif k == "ScatterRows":

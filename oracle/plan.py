@@ -7,7 +7,7 @@ build's reading; the library follows the same written rules independently.
 
 R0  An operator whose outputs are all integer tensors with a fully resolved
     value map is *folded*: its result is known from RDP (Fig. 1(a)), nothing runs.
-R1  Reshape, Slice, Transpose and Gather-with-a-scalar-host-index are *views*:
+R1  Reshape, Slice, Transpose, Expand and Gather-with-a-scalar-host-index are *views*:
     their output aliases the input's storage; no kernel, no arena tensor.
 R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     this order and each at most once: Mul by a host scalar; Add of a rank-1
@@ -18,7 +18,7 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     following Transpose is still taken: the permuted store is a layout choice
     of the contraction, and without it the Reshape behind it would need a copy.
 R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
-    ScatterRows, Resize and a Concat that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
+    ScatterRows, Resize, and a Concat or Range that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
 R4  Remaining elementwise operators chain while every aligned dim pair of
     every operand is proven equal or 1 (the condition of Fig. 4), up to 8 ops.
@@ -65,12 +65,12 @@ from . import rdp as R
 ALIGN = 256
 MAX_SG = 14
 DT_BYTES = {"f32": 4, "bf16": 2, "i64": 8, "i32": 4}
-VIEW_KINDS = ("Reshape", "Slice", "Transpose")
+VIEW_KINDS = ("Reshape", "Slice", "Transpose", "Expand")
 ACTS = ("Relu", "Gelu", "Sigmoid")
 ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast")
 SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
         "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
-        "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT"}
+        "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE"}
 
 
 @dataclass

@@ -33,7 +33,7 @@ OP_CLASS = {
     "Add": ISDOS, "Mul": ISDOS, "Relu": ISDOS, "Gelu": ISDOS, "Sigmoid": ISDOS, "Cast": ISDOS,
     "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
-    "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS,
+    "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS, "Range": ISVDOS, "Expand": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
 UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm")
@@ -539,6 +539,35 @@ class RDP:
         if x is UNDEF:
             return None
         return (NAC if x == NAC else list(x[:-1])), UNDEF
+
+    def _f_Range(self, op):
+        """[start, start + delta, ...) below limit: the length is ceil((limit - start) / delta) for a known
+        positive delta (the expression assumes limit >= start); the values are kept while they are few."""
+        vs = [self.V[t] for t in op.inputs]
+        if any(v is UNDEF for v in vs):
+            return None
+        if any(not isinstance(v, list) or len(v) != 1 or not is_expr(v[0]) for v in vs):
+            return [NAC], NAC
+        start, limit, delta = (v[0] for v in vs)
+        if not delta.is_const() or delta.const_value() <= 0:
+            return [NAC], NAC
+        d = delta.const_value()
+        n = (limit - start + C(d - 1)).floordiv(d)
+        if n.is_const() and n.const_value() < 0:
+            n = C(0)
+        vals = NAC
+        if n.is_const() and n.const_value() <= MAX_V:
+            vals = [start + C(i * d) for i in range(n.const_value())]
+        return [n], vals
+
+    def _f_Expand(self, op):
+        """Broadcast of input 0 against the shape held by the values of input 1."""
+        x, tv = self.S[op.inputs[0]], self.V[op.inputs[1]]
+        if x is UNDEF or tv is UNDEF:
+            return None
+        if not isinstance(x, list) or not isinstance(tv, list):
+            return NAC, UNDEF
+        return broadcast_shapes(list(x), list(tv)), UNDEF
 
     def _f_Resize(self, op):
         """Output shape = the values of the sizes input (ISVDOS; lowered when they are resolved)."""

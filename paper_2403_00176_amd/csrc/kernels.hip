@@ -1041,6 +1041,19 @@ hipError_t launch_concat(const Launch& L, const ConcatArgs& a, hipStream_t s) {
                               L.unit_bytes, a.rows * (a.units[0] + a.units[1] + a.units[2] + a.units[3]), a, s);
 }
 
+__global__ __launch_bounds__(256) void range_kernel(RangeArgs a) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.n) return;
+  const long long v = a.start + i * a.delta;
+  if (a.out_i32) ((int*)a.y)[i] = (int)v;
+  else ((long long*)a.y)[i] = v;
+}
+hipError_t launch_range(const RangeArgs& a, hipStream_t s) {
+  if (a.n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(range_kernel, dim3((unsigned)((a.n + 255) / 256)), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s) {
   if (a.rows <= 0 || a.cols <= 0) return hipSuccess;
   const long long eb = L.out_dtype == SOD2_BF16_TAG ? 2 : 4, row_bytes = a.cols * eb;

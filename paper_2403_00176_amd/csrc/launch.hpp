@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -171,6 +171,13 @@ struct ConcatArgs {
   int n_in;
 };
 
+// y[i] = start + i * delta for i < n (int64 or int32 result)
+struct RangeArgs {
+  void* y;
+  long long start, delta, n;
+  int out_i32;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -192,6 +199,7 @@ struct Launch {
     ScatterArgs scatter;
     ResizeArgs resize;
     ConcatArgs concat;
+    RangeArgs range;
   } u;
   int unit_bytes = 0;      // resize / concat: bytes of one copy unit
   bool is_layernorm = false;

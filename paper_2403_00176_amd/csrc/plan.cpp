@@ -3,13 +3,13 @@
 //
 // Rules (the paper leaves them to an earlier fusion system and to "exhaustive search"):
 //  R0 an operator whose outputs are integer tensors with a fully resolved value map is folded;
-//  R1 Reshape / Slice / Transpose / Gather-with-scalar-host-index are views (no kernel);
+//  R1 Reshape / Slice / Transpose / Expand / Gather-with-scalar-host-index are views (no kernel);
 //  R2 MatMul / Conv absorbs, in order and each at most once: Mul by a host scalar, Add of a rank-1
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
 //     consumer of the chain so far;
-//  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize and a
-//     Concat that is not folded stand alone; a
+//  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, and a
+//     Concat or Range that is not folded stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
 //  R4 other elementwise operators chain while every aligned dim pair is proven equal or 1 (Fig. 4);
 //  R5 group id = smallest member id; groups are ordered by the node-order position of their
@@ -37,7 +37,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -119,7 +119,7 @@ void Plan::build() {
       if (!R.V[o].resolved()) known = false;
     }
     if (ints && known) folded[i] = 1;
-    else if (op.kind == SOD2_OP_RESHAPE || op.kind == SOD2_OP_SLICE || op.kind == SOD2_OP_TRANSPOSE) view[i] = 1;
+    else if (op.kind == SOD2_OP_RESHAPE || op.kind == SOD2_OP_SLICE || op.kind == SOD2_OP_TRANSPOSE || op.kind == SOD2_OP_EXPAND) view[i] = 1;
     else if (op.kind == SOD2_OP_GATHER) {
       const Tensor& idx = G.tensors[op.in[1]];
       view[i] = idx.has_data && idx.host_rank == 0;
@@ -198,6 +198,7 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_SCATTERROWS) new_group(G_SCATTER, {n});
     else if (op.kind == SOD2_OP_RESIZE) new_group(G_RESIZE, {n});
     else if (op.kind == SOD2_OP_CONCAT) new_group(G_CONCAT, {n});
+    else if (op.kind == SOD2_OP_RANGE) new_group(G_RANGE, {n});
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);

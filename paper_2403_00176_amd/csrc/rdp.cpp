@@ -15,13 +15,13 @@ namespace sod2 {
 static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
-    "NonZero", "Switch", "Combine", "ScatterRows", "Resize"};
+    "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
   switch (kind) {
     case SOD2_OP_SHAPE: return 0;
-    case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: return 2;
+    case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: case SOD2_OP_RANGE: case SOD2_OP_EXPAND: return 2;
     case SOD2_OP_NONZERO: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
     default: return 1;
   }
@@ -382,6 +382,29 @@ struct Analyser {
         if (x.k == LS::UNDEF) return r;
         if (x.k == LS::NAC) return done(LS::nac(), LS::nac());
         return done(LS::list({LV::c((int64_t)x.d.size()), LV::of(Expr::symbol(exec_symbol(op_id)))}), LS::nac());
+      }
+      case SOD2_OP_RANGE: {          // length ceil((limit - start) / delta) for a known positive delta (limit >= start assumed)
+        for (int k = 0; k < 3; ++k) if (in_v(k).k == LS::UNDEF) return r;
+        bool ok = true;
+        for (int k = 0; k < 3; ++k) if (!in_v(k).is_list() || in_v(k).d.size() != 1 || !in_v(k).d[0].val()) ok = false;
+        if (!ok || !in_v(2).d[0].e.is_const() || in_v(2).d[0].e.const_value() <= 0)
+          return done(LS::list({LV::nac()}), LS::nac());
+        const Expr &start = in_v(0).d[0].e, &limit = in_v(1).d[0].e;
+        const int64_t d = in_v(2).d[0].e.const_value();
+        Expr n = (limit - start + Expr::constant(d - 1)).floordiv(d);
+        if (n.is_const() && n.const_value() < 0) n = Expr::constant(0);
+        LS v = LS::nac();
+        if (n.is_const() && n.const_value() <= 16) {
+          v = LS::list({});
+          for (int64_t i = 0; i < n.const_value(); ++i) v.d.push_back(LV::of(start + Expr::constant(i * d)));
+        }
+        return done(LS::list({LV::of(n)}), v);
+      }
+      case SOD2_OP_EXPAND: {         // broadcast of input 0 against the shape held by the values of input 1
+        const LS &x = in_s(0), &tv = in_v(1);
+        if (x.k == LS::UNDEF || tv.k == LS::UNDEF) return r;
+        if (!x.is_list() || !tv.is_list()) return done(LS::nac());
+        return done(LS::list(bcast(x.d, tv.d)));
       }
       case SOD2_OP_RESIZE: {                             // output shape = the values of the sizes input (ISVDOS)
         const LS &x = in_s(0), &ts = in_s(1), &tv = in_v(1);

@@ -23,6 +23,7 @@ hipError_t launch_nonzero(const NonzeroArgs& a, hipStream_t s);
 hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s);
 hipError_t launch_resize(const Launch& L, const ResizeArgs& a, hipStream_t s);
 hipError_t launch_concat(const Launch& L, const ConcatArgs& a, hipStream_t s);
+hipError_t launch_range(const RangeArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
 
@@ -167,6 +168,16 @@ struct Builder {
             v.off += s * in.strides[a];
             v.dims[a] = e - s;
           }
+        } else if (op.kind == SOD2_OP_EXPAND) {         // broadcast dims get stride 0
+          std::vector<int64_t> nd = eval_dims(t), ns(nd.size(), 0);
+          if (nd.size() < in.dims.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Expand lowers the rank");
+          size_t pad = nd.size() - in.dims.size();
+          for (size_t i = 0; i < in.dims.size(); ++i) {
+            if (in.dims[i] == nd[pad + i]) ns[pad + i] = in.strides[i];
+            else if (in.dims[i] != 1) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Expand of a dim that is neither 1 nor the target");
+          }
+          v.dims = nd;
+          v.strides = ns;
         } else if (op.kind == SOD2_OP_RESHAPE) {
           std::vector<int64_t> nd = eval_dims(t), ns;
           if (View{0, 0, nd, {}}.numel() != in.numel()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Reshape changes the element count");
@@ -906,6 +917,28 @@ struct Builder {
     return L;
   }
 
+  Launch range(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_RANGE;
+    const Op& op = G.ops[gr.ops[0]];
+    int dt = G.tensors[gr.out].dtype;
+    const LS &vs = p.rdp->V[op.in[0]], &vd = p.rdp->V[op.in[2]];
+    if (!is_int(dt) || !vs.is_list() || vs.d.size() != 1 || !vs.d[0].val() || !vd.is_list() || vd.d.size() != 1 ||
+        !vd.d[0].val() || !vd.d[0].e.is_const())
+      throw Error(SOD2_ERR_UNSUPPORTED, "Range kernel: start and delta must be known from the value maps");
+    RangeArgs a{};
+    a.start = vs.d[0].e.eval(b.env);
+    a.delta = vd.d[0].e.const_value();
+    a.n = eval_dims(gr.out).at(0);
+    a.out_i32 = dt == SOD2_I32;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_t(gr.out);
+    L.u.range = a;
+    L.bytes = (double)a.n * dtype_bytes(dt);
+    return L;
+  }
+
   Launch make(const Group& gr) {
     // a result without elements (an empty compacted batch): nothing to compute
     auto od = b.dims.find(gr.out);
@@ -917,6 +950,7 @@ struct Builder {
     switch (gr.kind) {
       case G_NONZERO: return nonzero(gr);
       case G_SCATTER: return scatter(gr);
+      case G_RANGE: return range(gr);
       case G_RESIZE: return resize(gr);
       case G_CONCAT: return concat(gr);
       case G_ATTENTION: return attention(gr);
@@ -972,6 +1006,11 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       NonzeroArgs a = L.u.nz;
       a.x = P.at(L.r[0]); a.out = (long long*)P.at(L.r[1]); a.count = (long long*)P.at(L.r[2]);
       return launch_nonzero(a, s);
+    }
+    case K_RANGE: {
+      RangeArgs a = L.u.range;
+      a.y = P.at(L.r[0]);
+      return launch_range(a, s);
     }
     case K_RESIZE: {
       ResizeArgs a = L.u.resize;

@@ -77,3 +77,30 @@ def test_detection_neck(S):
             got = to_host(o)
             assert got.shape == ref.values[t].shape and np.isfinite(got).all()
             assert rel_err(got, ref.values[t]) <= 2e-2, (w.graph.tensors[t].name, sym, rel_err(got, ref.values[t]))
+
+
+def test_range_gather_expand(S):
+    """Position ids made in the graph (Range up to a dim read from Shape), table rows gathered by them and
+    broadcast over the batch through an Expand view (stride 0) into an elementwise Add."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    from tests.test_shape_ops import _positions_graph
+    g, pos, rows, wide = _positions_graph()
+    ses = Session(g)
+    rs = np.random.RandomState(2)
+    table = rs.randn(512, 8)
+    ses.upload_weights({g.tensor_id("table"): table})
+    po = P.build_plan(g, R.RDP(g).analyse())
+    for B, L in ((1, 1), (3, 7), (8, 300), (2, 257)):
+        sym = {"B": B, "L": L}
+        print(f"case positions {sym}", flush=True)
+        ins = {g.tensor_id("x"): rs.randn(B, L, 8)}
+        b = ses.bind(sym)
+        assert S.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {g.tensor_id("table"): table}, ins)
+        by_name = dict(zip([g.tensors[t].name for t in g.outputs()], outs))
+        assert np.array_equal(to_host(by_name["positions"]), np.arange(L))
+        assert rel_err(to_host(by_name["y"]), ref.values[g.tensor_id("y")]) <= 1e-2

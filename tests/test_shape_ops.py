@@ -119,3 +119,53 @@ def test_neck_shapes_groups_and_arena():
     assert S.sod2_plan_dump(pl) == P.dump(plan)
     for call in w.calls + [{"H": 96, "W": 64}]:
         assert S.sod2_binding_dump(S.sod2_bind(pl, call)) == A.dump(A.bind(plan, call))
+
+
+def _positions_graph(dtype="bf16"):
+    """x[B, L, 8] + table[Range(0, L)] broadcast over the batch: position ids made in the graph (Range
+    with a limit read from Shape), rows gathered by them, Expand to the shape of x."""
+    b = GraphBuilder([("B", 1, 8), ("L", 1, 300)])
+    x = b.input("x", dtype, ["B", "L", 8])
+    table = b.weight("table", dtype, [512, 8])
+    shp = b.op("Shape", [x], dtype="i64")
+    L = b.op("Gather", [shp, b.const("i1", [1])], axis=0, dtype="i64")
+    pos = b.op("Range", [b.const("zero", [0]), L, b.const("one", [1])], dtype="i64", hint="pos")
+    rows = b.op("Gather", [table, pos], axis=0, hint="rows")                 # [L, 8]
+    wide = b.op("Expand", [rows, shp], hint="wide")                         # [B, L, 8]
+    b.mark_output(b.op("Add", [x, wide]), "y")
+    b.mark_output(pos, "positions")
+    return b.build(), pos, rows, wide
+
+
+def test_range_and_expand_are_lowered():
+    g, pos, rows, wide = _positions_graph()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.S[pos]) == "[s:L]" and r.V[pos] == R.NAC            # too many values to carry
+    assert R.fmt_list(r.S[rows]) == "[s:L, k:8]"
+    assert R.fmt_list(r.S[wide]) == "[s:B, s:L, k:8]"
+    plan = P.build_plan(g, r)
+    kinds = [plan.groups[it.ref].kind for it in plan.items if it.is_group]
+    assert kinds == ["RANGE", "GATHER", "ELTWISE"]                           # Expand is a view, the shape ops fold
+    for B, L in ((1, 1), (3, 7), (2, 40)):
+        res = execute.run(g, plan.order, {1: np.arange(512 * 8).reshape(512, 8) / 64.0}, {0: np.zeros((B, L, 8))})
+        assert list(res.values[pos]) == list(range(L))
+        assert list(res.values[wide].shape) == [d.eval({"B": B, "L": L}) for d in r.S[wide]]
+        assert np.array_equal(res.values[g.tensor_id("y")][B - 1], res.values[rows])
+    # a short constant range keeps its values; a step of 3; an empty one
+    for start, limit, delta, expect in ((2, 11, 3, [2, 5, 8]), (0, 4, 1, [0, 1, 2, 3]), (5, 5, 2, []), (7, 3, 1, [])):
+        b = GraphBuilder([])
+        t = b.op("Range", [b.const("s", [start]), b.const("l", [limit]), b.const("d", [delta])], dtype="i64")
+        b.mark_output(b.op("Cast", [t], dtype="f32"))
+        gd = b.build()
+        rr = R.RDP(gd).analyse()
+        assert [e.const_value() for e in rr.V[t]] == expect and rr.S[t][0].const_value() == len(expect)
+        assert list(np.arange(start, limit, delta)) == expect
+        gl = S.sod2_graph_build(gd)
+        assert S.sod2_rdp_dump(S.sod2_rdp_infer(gl)) == R.dump(rr)
+    gl = S.sod2_graph_build(g)
+    rl = S.sod2_rdp_infer(gl)
+    assert S.sod2_rdp_dump(rl) == R.dump(r)
+    pl = S.sod2_plan(gl, rl)
+    assert S.sod2_plan_dump(pl) == P.dump(plan)
+    for sym in ({"B": 3, "L": 7}, {"B": 8, "L": 300}):
+        assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))

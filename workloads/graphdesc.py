@@ -45,6 +45,8 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "NonZero": (),
     "Switch": (),             # float attr threshold
     "Combine": (),
+    "Range": (),              # inputs start, limit, delta (one-element int tensors)
+    "Expand": (),             # input 1 = the shape to broadcast to
     "Resize": (),             # nearest neighbour, target shape = the values of input 1 ("sizes")
     "ScatterRows": (),        # ScatterND with row indices: copy of input 0 whose rows input 1 are replaced by input 2
 }
