@@ -139,24 +139,30 @@ __device__ __forceinline__ void epilogue8(float* x, const GemmArgs& g, bf16_t* C
 // WM x WN compute waves, LW >= WM * WN waves in all: every wave issues its share of the global -> LDS
 // loads (a wave sustains only ~1 KB per 100 ns of such loads, so the extra "loader" waves raise the
 // rate at which a workgroup walks k); waves past WM * WN skip the MFMA part and the epilogue.
+// KG > 1: KG groups of WM x WN waves share one output tile; group q loads and multiplies the k-tiles
+// q, q + KG, q + 2 KG, ... (each group has its own part of every ring stage), and the groups' fp32
+// accumulators are summed through LDS in the order q = 0, 1, ... before the epilogue: a workgroup walks
+// k KG times faster, which is what bounds a contraction with fewer tiles than CUs.
 // OCC workgroups per CU (the second launch bound counts waves per SIMD).
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN>
-__global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs g) {
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN, int KG = 1>
+__global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al, GemmArgs g) {
   constexpr int NCW = WM * WN, NWV = LW, NT = NWV * 64;
   constexpr int KV = BK / 8, TM = BM / (WM * 32), TN = BN / (WN * 32);
   constexpr int LT = (BM + BN) * KV / NT;                       // 16-byte loads per thread per k-tile (A rows, then B rows)
-  constexpr int STAGE = (BM + BN) * BK;                         // bf16 elements per stage
+  constexpr int STAGE = (BM + BN) * BK;                         // bf16 elements per stage and group
   constexpr int EW = TN * 32, ELD = EW + 4;
   constexpr int EPI = NCW * 32 * ELD * 2;                       // wave-private fp32 patches, in bf16 units
-  constexpr int LDS_ELEMS = (ST * STAGE > EPI) ? ST * STAGE : EPI;
-  static_assert((NCW == 4 || NCW == 8) && LW >= NCW && LW <= 16 && TM >= 1 && TN >= 1 && LT >= 1 && ST >= 2 &&
-                    (BM + BN) * KV % NT == 0 && BM % (64 / KV) == 0,
-                "4 or 8 compute waves, at most 16 waves");
+  constexpr int RED = (KG - 1) * NCW * TM * TN * 16 * 64 * 2;   // the other groups' accumulators, in bf16 units
+  constexpr int LDS_ELEMS = (ST * KG * STAGE > EPI + RED) ? ST * KG * STAGE : EPI + RED;
+  static_assert((NCW == 4 || NCW == 8) && LW >= NCW && LW * KG <= 16 && TM >= 1 && TN >= 1 && LT >= 1 && ST >= 2 &&
+                    (BM + BN) * KV % NT == 0 && BM % (64 / KV) == 0 && (KG == 1 || LW == NCW),
+                "4 or 8 compute waves per group, at most 16 waves");
   static_assert((ST - 2) * LT <= 63, "vmcnt is a 6-bit counter");
   __shared__ __attribute__((aligned(16))) bf16_t lds[LDS_ELEMS];
 
   const int tid = threadIdx.x, lane = tid & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int kg = KG > 1 ? wave_all / LW : 0, wave = KG > 1 ? wave_all % LW : wave_all;
   const int wm = wave / WN, wn = wave % WN;
   const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
   // Workgroups are dealt round-robin to the 8 XCDs (each with its own L2).  Give each XCD one
@@ -183,7 +189,7 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
   const bf16_t* Bp = (const bf16_t*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
 
   // k range of this split
-  const int nk_all = (g.K + BK - 1) / BK;
+  const int nk_all = (g.K + BK * KG - 1) / (BK * KG);         // steps: one k-tile per group and step
   const int per_split = (nk_all + gridDim.z - 1) / gridDim.z;
   const int kt0 = blockIdx.z * per_split;
   const int nk = max(0, min(per_split, nk_all - kt0));
@@ -225,9 +231,9 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
   const bf16_t* zero = (const bf16_t*)g_zero_chunk;
 
   auto issue = [&](int t, int stage) {                         // k-tile t of this split into a stage
-    const int k0 = (kt0 + t) * BK;
+    const int k0 = ((kt0 + t) * KG + kg) * BK;
     al.tile(t < nk ? k0 : g.K);
-    const uint32_t sa = lds_base + stage * (STAGE * 2) + wave * 1024;
+    const uint32_t sa = lds_base + (stage * KG + kg) * (STAGE * 2) + wave * 1024;
 #pragma unroll
     for (int j = 0; j < LT; ++j) {
       const bf16_t* src;
@@ -295,7 +301,7 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
   for (int t = 0; t < nk; ++t) {
     wait_loads<(ST - 2) * LT>();                         // tile t has landed (this wave's part)
     __syncthreads();                                            // ... everyone's part; stage wr is free again
-    const bf16_t* S = lds + rd * STAGE;
+    const bf16_t* S = lds + (rd * KG + kg) * STAGE;
     if (LW == NCW || wave < NCW) frag_load(S, 0, 0);
     issue(t + ST - 1, wr);
     if (LW == NCW || wave < NCW) {
@@ -316,6 +322,30 @@ __global__ __launch_bounds__(LW * 64, OCC * LW / 4) void gemm_dl(AL al, GemmArgs
   }
 
   if (LW != NCW && wave >= NCW) return;                         // loader waves are done (no barrier follows)
+  if (KG > 1) {                                                 // sum the groups' accumulators in group order
+    float* red = (float*)lds + EPI / 2;
+    if (kg > 0) {
+      float* mine = red + ((kg - 1) * NCW + wave) * (TM * TN * 16 * 64) + lane;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) mine[((i * TN + j) * 16 + r) * 64] = acc[i][j][r];
+    }
+    __syncthreads();
+    if (kg > 0) return;
+#pragma unroll
+    for (int q = 1; q < KG; ++q) {
+      const float* theirs = red + ((q - 1) * NCW + wave) * (TM * TN * 16 * 64) + lane;
+#pragma unroll
+      for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+          for (int r = 0; r < 16; ++r) acc[i][j][r] += theirs[((i * TN + j) * 16 + r) * 64];
+    }
+  }
   // ---- epilogue: 32 rows of the wave tile at a time through a wave-private fp32 LDS patch ----
   float* patch = (float*)lds + wave * 32 * ELD;
   bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
@@ -524,12 +554,12 @@ hipError_t launch_gemv(const GemmArgs& g, hipStream_t s) {
 // ---------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN>
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN, int KG = 1>
 static hipError_t launch_dl(const AL& al, const GemmArgs& g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const int splits = g.splits > 1 ? g.splits : 1;
   dim3 grid(tiles, g.nb0 * g.nb1, splits);
-  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC, LW>), grid, dim3(LW * 64), 0, s, al, g);
+  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC, LW, KG>), grid, dim3(LW * KG * 64), 0, s, al, g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   const long long nvec = (long long)g.M * ((g.N + 7) / 8);
@@ -557,6 +587,10 @@ hipError_t launch_dl_variant(const AL& al, const GemmArgs& g, int tile, hipStrea
     case DL_64x128x64_S3_L8: return launch_dl<AL, 64, 128, 64, 3, 1, 4, 2, 8>(al, g, s);
     case DL_256x256x64_S2_W8: return launch_dl<AL, 256, 256, 64, 2, 2, 4, 1>(al, g, s);
     case DL_256x128x64_S3_W8: return launch_dl<AL, 256, 128, 64, 3, 4, 2, 1>(al, g, s);
+    case DL_64x64x64_S4_G2: return launch_dl<AL, 64, 64, 64, 4, 2, 2, 1, 4, 2>(al, g, s);
+    case DL_64x64x64_S3_G2: return launch_dl<AL, 64, 64, 64, 3, 2, 2, 1, 4, 2>(al, g, s);
+    case DL_64x64x64_S2_G4: return launch_dl<AL, 64, 64, 64, 2, 2, 2, 1, 4, 4>(al, g, s);
+    case DL_128x128x64_S2_G2: return launch_dl<AL, 128, 128, 64, 2, 2, 2, 1, 4, 2>(al, g, s);
     default: return hipErrorInvalidValue;
   }
 }

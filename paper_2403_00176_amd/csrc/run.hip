@@ -249,20 +249,25 @@ struct Builder {
     // the 64x64 tile runs two workgroups per CU: as long as all its tiles are resident at once
     // (512 on 256 CUs) it finishes first; one tile more and a second round starts, then 128x128 wins
     if (t64 > 512) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
-    return V_DL0 + DL_64x64x64_S4_W4;
+    // with at most one tile per CU a workgroup's walk over k is the whole duration: two wave groups
+    // share the tile and split k between them (0.5 - 4 us less per launch on config 2's shapes)
+    return V_DL0 + (t64 <= 256 ? DL_64x64x64_S3_G2 : DL_64x64x64_S4_W4);
   }
 
   // Split-K (only with the direct-to-LDS kernel; costs a second launch that sums the partials): for a
   // long k with few tiles, where one workgroup per tile would walk k alone while most CUs idle.
   int pick_splits(int variant, int64_t M, int64_t N, int64_t K, int64_t batch) const {
     if (variant < V_DL0 || force_splits == 1 || (!p.opts.mvc && force_splits == 0)) return 1;
-    const bool small = variant == V_DL0 + DL_64x64x64_S4_W4;
+    const bool grouped = variant == V_DL0 + DL_64x64x64_S3_G2;
+    const bool small = grouped || variant == V_DL0 + DL_64x64x64_S4_W4;
     const int64_t bm = small ? 64 : 128, bn = small ? 64 : 128;
     const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
     int64_t s = force_splits;
     if (force_splits == 0) {
       if (!small || K < 2048 || tiles > 256) return 1;
-      s = std::min<int64_t>(512 / std::max<int64_t>(tiles, 1), K / 384);
+      // measured: two wave groups walk k about twice as fast and one such workgroup fills a CU
+      s = grouped ? std::min<int64_t>(256 / std::max<int64_t>(tiles, 1), K / 512)
+                  : std::min<int64_t>(512 / std::max<int64_t>(tiles, 1), K / 384);
     }
     int64_t pow2 = 1;
     while (pow2 * 2 <= s && pow2 < (force_splits > 1 ? 16 : 8)) pow2 *= 2;
