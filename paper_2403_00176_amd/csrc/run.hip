@@ -251,7 +251,8 @@ struct Builder {
     if (t64 > 512) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
     // with at most one tile per CU a workgroup's walk over k is the whole duration: two wave groups
     // share the tile and split k between them (0.5 - 4 us less per launch on config 2's shapes)
-    return V_DL0 + (t64 <= 256 ? DL_64x64x64_S3_G2 : DL_64x64x64_S4_W4);
+    if (t64 <= 256) return V_DL0 + DL_64x64x64_S3_G2;
+    return V_DL0 + (K >= 2048 ? DL_64x64x64_S2_G2 : DL_64x64x64_S4_W4);   // two per CU; the groups pay off on a long k (9 % at k = 3072)
   }
 
   // Split-K (only with the direct-to-LDS kernel; costs a second launch that sums the partials): for a
@@ -259,7 +260,7 @@ struct Builder {
   int pick_splits(int variant, int64_t M, int64_t N, int64_t K, int64_t batch) const {
     if (variant < V_DL0 || force_splits == 1 || (!p.opts.mvc && force_splits == 0)) return 1;
     const bool grouped = variant == V_DL0 + DL_64x64x64_S3_G2;
-    const bool small = grouped || variant == V_DL0 + DL_64x64x64_S4_W4;
+    const bool small = grouped || variant == V_DL0 + DL_64x64x64_S4_W4 || variant == V_DL0 + DL_64x64x64_S2_G2;
     const int64_t bm = small ? 64 : 128, bn = small ? 64 : 128;
     const int64_t tiles = ((M + bm - 1) / bm) * ((N + bn - 1) / bn) * batch;
     int64_t s = force_splits;
