@@ -592,6 +592,7 @@ hipError_t launch_dl_variant(const AL& al, const GemmArgs& g, int tile, hipStrea
     case DL_64x64x64_S2_G4: return launch_dl<AL, 64, 64, 64, 2, 2, 2, 1, 4, 4>(al, g, s);
     case DL_128x128x64_S2_G2: return launch_dl<AL, 128, 128, 64, 2, 2, 2, 1, 4, 2>(al, g, s);
     case DL_64x64x64_S2_G2: return launch_dl<AL, 64, 64, 64, 2, 2, 2, 2, 4, 2>(al, g, s);
+    case DL_128x128x64_S2_W8G2: return launch_dl<AL, 128, 128, 64, 2, 2, 4, 1, 8, 2>(al, g, s);
     default: return hipErrorInvalidValue;
   }
 }

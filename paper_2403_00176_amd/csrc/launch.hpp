@@ -22,7 +22,7 @@ enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL
 enum DlTile { DL_128x128x64_S3_W4 = 0, DL_128x128x64_S2_W4, DL_128x128x32_S3_W4, DL_128x128x64_S2_W8, DL_256x128x64_S2_W8,
               DL_256x128x32_S3_W8, DL_64x128x64_S3_W4, DL_64x64x64_S4_W4, DL_128x64x64_S3_W4, DL_128x128x64_S3_W8,
               DL_256x256x32_S3_W8, DL_64x64x64_S4_L8, DL_64x64x64_S4_L16, DL_128x128x64_S2_L16, DL_64x128x64_S3_L8, DL_256x256x64_S2_W8, DL_256x128x64_S3_W8,
-              DL_64x64x64_S4_G2, DL_64x64x64_S3_G2, DL_64x64x64_S2_G4, DL_128x128x64_S2_G2, DL_64x64x64_S2_G2, DL_TILES };   // _Gn: n wave groups split k inside the workgroup
+              DL_64x64x64_S4_G2, DL_64x64x64_S3_G2, DL_64x64x64_S2_G4, DL_128x128x64_S2_G2, DL_64x64x64_S2_G2, DL_128x128x64_S2_W8G2, DL_TILES };   // _Gn: n wave groups split k inside the workgroup
 
 // C[b0,b1,m,n] = act2( act1( scale * sum_k A[b0,b1,m,k] * B[b0,b1,k,n] + bias[n] ) + R[b0,b1,m,n] )
 struct GemmArgs {

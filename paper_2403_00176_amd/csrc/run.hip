@@ -248,7 +248,7 @@ struct Builder {
     if (t128 >= 1024) return V_DL0 + (K >= 2048 ? DL_256x256x64_S2_W8 : DL_256x128x32_S3_W8);   // fat versions
     // the 64x64 tile runs two workgroups per CU: as long as all its tiles are resident at once
     // (512 on 256 CUs) it finishes first; one tile more and a second round starts, then 128x128 wins
-    if (t64 > 512) return V_DL0 + (K >= 2048 ? DL_128x128x64_S3_W8 : DL_128x128x64_S2_W8);
+    if (t64 > 512) return V_DL0 + (K >= 2048 ? (t128 <= 256 ? DL_128x128x64_S2_W8G2 : DL_128x128x64_S3_W8) : DL_128x128x64_S2_W8);
     // with at most one tile per CU a workgroup's walk over k is the whole duration: two wave groups
     // share the tile and split k between them (0.5 - 4 us less per launch on config 2's shapes)
     if (t64 <= 256) return V_DL0 + DL_64x64x64_S3_G2;

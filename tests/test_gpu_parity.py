@@ -100,7 +100,7 @@ def test_encoder_bf16_small(S, variant):
     print("encoder small max rel err", variant, max(errs))
 
 
-@pytest.mark.parametrize("variant", list(range(10, 32)))
+@pytest.mark.parametrize("variant", list(range(10, 33)))
 def test_direct_to_lds_tiles(S, variant):
     """Every tile of the direct-to-LDS contraction kernel forced in turn (variant 10 + tile) on ragged
     encoder shapes (M tails, several k tiles, K = 3072 ring wrap-around) and on a small CNN."""
