@@ -195,7 +195,10 @@ sod2_status sod2_binding_workspace_bytes(const sod2_binding_t*, size_t* workspac
  * host arrays of device pointers, one per tensor with that role, ordered by tensor id.
  * hip_stream: a hipStream_t (NULL = the null stream).  Enqueues and returns; synchronises the
  * stream only at a Switch, whose predicate is read back to the host, and after a NonZero, whose count
- * is read back (8 bytes) so that what follows can be sized and planned. */
+ * is read back (8 bytes) so that what follows can be sized and planned.  Kernel arguments are
+ * prepared step by step while earlier kernels already execute: when a call fails (a group the
+ * kernels do not support, an arena too small for the path taken) the groups before the failing one
+ * may have run and the contents of the outputs and of the arena are unspecified. */
 sod2_status sod2_run(sod2_binding_t*, void* arena_dev, size_t arena_bytes,
                      const void* const* weights_dev, int32_t n_weights,
                      const void* const* inputs_dev, int32_t n_inputs,

@@ -1320,9 +1320,21 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
     };
     P.ws = workspace_for(h->b.arena_bytes);
 
+    // The launch table of a new binding is filled step by step as the run reaches each step, so the
+    // first kernels are already executing while the later launches are still being prepared (an
+    // unsupported group is therefore reported after the groups before it were launched).
+    std::unique_ptr<Builder> first;
     if (!h->launches_valid) {
-      h->launches = build_launches(p, h->b, h->force_variant, h->force_splits);
-      h->launches_valid = true;
+      h->launches.clear();
+      for (size_t j = 0; j < h->b.steps.size(); ++j) {
+        const Item& it = p.items[h->b.steps[j]];
+        Launch L;
+        L.kernel = it.is_group ? -2 : -1;
+        L.group = it.ref;
+        h->launches.push_back(L);
+      }
+      first.reset(new Builder(p, h->b, h->force_variant));
+      first->force_splits = h->force_splits;
     }
     h->records.clear();
     h->last_decisions.clear();
@@ -1393,7 +1405,10 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
     bool assumed = false;                           // a fact confirmed what the plan in use had assumed
     while (k < cur->steps.size()) {
       const Item& it = p.items[cur->steps[k]];
-      if (it.is_group && (*launches)[k].kernel == -2) relaunch[k] = lazy->make(p.groups.at(it.ref));
+      if (it.is_group && (*launches)[k].kernel == -2) {
+        if (launches == &relaunch) relaunch[k] = lazy->make(p.groups.at(it.ref));
+        else h->launches[k] = first->make(p.groups.at(it.ref));
+      }
       const Launch L = (*launches)[k];                // a copy: a re-plan below rebuilds the table
       if (it.is_group) {
         auto at = cur->tensors.find(p.groups.at(it.ref).out);
@@ -1454,6 +1469,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
       }
       ++k;
     }
+    if (launches == &h->launches) h->launches_valid = true;      // complete: a second run of this binding reuses it
     if (assumed) {
       // same steps and offsets as the plan in use; computed again only so that the executed plan
       // reports every fact as known (the kernels are already enqueued: this overlaps their execution)
