@@ -25,9 +25,10 @@ def bench_ablation(args, S, dev):
     from workloads import configs
     w = configs.BUILDERS[args.config](n_calls=args.steps + args.warmup)
     W = w.make_weights()
-    stages = [("none", dict(fusion=0, sep=0, dmp=0, mvc=0)), ("+fusion", dict(fusion=1, sep=0, dmp=0, mvc=0)),
-              ("+sep", dict(fusion=1, sep=1, dmp=0, mvc=0)), ("+dmp", dict(fusion=1, sep=1, dmp=1, mvc=0)),
-              ("+mvc", dict(fusion=1, sep=1, dmp=1, mvc=1))]
+    # (in-place reuse of a dying operand's storage belongs to the memory plan: on from the DMP stage)
+    stages = [("none", dict(fusion=0, sep=0, dmp=0, mvc=0, inplace=0)), ("+fusion", dict(fusion=1, sep=0, dmp=0, mvc=0, inplace=0)),
+              ("+sep", dict(fusion=1, sep=1, dmp=0, mvc=0, inplace=0)), ("+dmp", dict(fusion=1, sep=1, dmp=1, mvc=0, inplace=1)),
+              ("+mvc", dict(fusion=1, sep=1, dmp=1, mvc=1, inplace=1))]
     rows = {}
     for name, opts in stages:
         ses = Session(w.graph, device=dev, **opts)

@@ -108,6 +108,7 @@ typedef struct {
   int32_t sep;     /* static execution planning; 0: node order                            */
   int32_t dmp;     /* peak-first arena plan; 0: best-fit greedy in execution order        */
   int32_t mvc;     /* multi-version kernels; 0: always the regular version                */
+  int32_t inplace; /* a group's result may take over the storage of an operand that dies there */
 } sod2_plan_opts;
 
 typedef struct sod2_graph_s sod2_graph_t;

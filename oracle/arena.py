@@ -154,6 +154,8 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
                         break
             elif plan.view[p]:
                 r = info(op.inputs[0])
+            elif t in plan.inplace:                    # the result took over an operand's storage
+                r = (group_dead[plan.group_of_op[p]], info(plan.inplace[t])[1])
             else:
                 r = (group_dead[plan.group_of_op[p]], t)
         memo[t] = r
@@ -206,7 +208,7 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
                         n *= d
                     if n > cap_elems[b.session_root[tc]]:
                         raise CapacityExceeded(g.tensors[tc].name)
-                if arena_candidate(plan, t):
+                if arena_candidate(plan, t) and t not in plan.inplace:
                     n = DT_BYTES[g.tensors[t].dtype]
                     for d in b.dims[t]:
                         n *= d
@@ -354,6 +356,8 @@ def dump(b: Binding) -> str:
             lines.append(f"t{t} dims=[{dims}] off={a.offset} bytes={a.bytes} life={a.start}..{a.end}")
         elif t in b.session_root:
             lines.append(f"t{t} dims=[{dims}] session=t{b.session_root[t]}")
+        elif t in plan.inplace:
+            lines.append(f"t{t} dims=[{dims}] inplace=t{b.dyn_base[t]}")
         else:
             lines.append(f"t{t} dims=[{dims}] external")
     lines.append(f"arena_bytes={b.arena_bytes}")

@@ -79,6 +79,7 @@ class Opts:
     sep: bool = True         # static execution planning; off: node order
     dmp: bool = True         # peak-first arena plan; off: best-fit greedy in execution order
     mvc: bool = True         # multi-version kernels (library only; no effect on structure)
+    inplace: bool = True     # a group's result may take over the storage of an operand that dies there
 
 
 @dataclass
@@ -115,6 +116,7 @@ class Plan:
     versions_unfused: int = 0             # broadcast versions a shape-blind fuser would need
     paper_rdp: R.RDP = None               # Alg. 1 as printed (EDO outputs nac); == rdp without a NonZero
     exec_ops: List[int] = field(default_factory=list)    # NonZero operators, in the node order
+    inplace: Dict[int, int] = field(default_factory=dict)   # group result -> the operand whose storage it takes over
 
 
 def _shape_equal(a, b) -> bool:
@@ -403,7 +405,63 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     plan = Plan(g, rdp, opts, order, folded, view, groups, assigned, items, [], [], sbase, versions,
                 paper_rdp, [n for n in order if g.ops[n].kind == "NonZero"])
     _partition(plan)
+    if opts.inplace:
+        _mark_inplace(plan)
     return plan
+
+
+def _mark_inplace(plan: Plan):
+    """In-place reuse (a refinement of the lifetime rule of Section 4.4.1; the paper does not spell it
+    out).  The result of a contraction group with a residual operand, or of an elementwise group,
+    takes over the storage of one operand r when, whatever path is executed,
+      * r is the result of a group, lives in the arena, and has the type and (provably) the shape of
+        the result, which lives in the arena too;
+      * the group reads the storage of r through that operand only (each kernel thread reads the
+        elements of r it is about to write, nothing else of r), and stores without a permutation;
+      * the group is the last item, in the planned execution order, that reads the storage of r, and
+        no Combine forwards r (its output would keep the storage alive on some paths)."""
+    g, rdp = plan.graph, plan.rdp
+    position = {}
+    for sg in plan.subgraphs:
+        for i in sg:
+            position[i] = len(position)
+    combined = {t for it in plan.items if not it.is_group and g.ops[it.ref].kind == "Combine" for t in it.reads}
+    readers: Dict[int, List[int]] = {}
+    for i, it in enumerate(plan.items):
+        for t in it.reads:
+            readers.setdefault(t, []).append(i)
+    prod = rdp.producer
+    for i, it in enumerate(plan.items):
+        if not it.is_group:
+            continue
+        gr = plan.groups[it.ref]
+        if gr.kind not in ("GEMM", "CONV", "ELTWISE") or not arena_candidate(plan, gr.out):
+            continue
+        if any(g.ops[n].kind in ("Transpose", "LayerNorm", "CacheAppend") for n in gr.ops):
+            continue
+        inside = {o for n in gr.ops for o in g.ops[n].outputs}
+        outer = [t for n in gr.ops for t in g.ops[n].inputs if t not in inside and plan.sbase[t] not in inside]
+        if gr.kind == "ELTWISE":
+            cands = [t for t in outer]
+        else:                            # the operand added in the epilogue: an Add member's outside operand
+            cands = [t for n in gr.ops if g.ops[n].kind == "Add" for t in g.ops[n].inputs if t in outer]
+        for r in cands:
+            d = g.tensors[r]
+            if d.role != "inter" or not arena_candidate(plan, r) or r in combined or r in plan.inplace.values():
+                continue
+            pr = prod[r]
+            if pr < 0 or plan.folded[pr] or plan.view[pr] or g.ops[pr].kind in ("Switch", "Combine", "NonZero"):
+                continue
+            if plan.groups[plan.group_of_op[pr]].out != r:
+                continue
+            if d.dtype != g.tensors[gr.out].dtype or not _shape_equal(rdp.S[r], rdp.S[gr.out]):
+                continue
+            if [t for t in outer if plan.sbase[t] == r] != [r]:
+                continue
+            if any(position[j] > position[i] for j in readers.get(r, []) if j != i):
+                continue
+            plan.inplace[gr.out] = r
+            break
 
 
 def arena_candidate(plan: Plan, t: int) -> bool:
@@ -587,6 +645,8 @@ def dump(plan: Plan) -> str:
                          f"ins=[{' '.join('t%d' % t for t in gr.ins)}]")
         else:
             lines.append(f"c{it.ref} {g.ops[it.ref].kind}")
+    for t in sorted(plan.inplace):
+        lines.append(f"inplace t{t}=t{plan.inplace[t]}")
     for s, (sg, cls) in enumerate(zip(plan.subgraphs, plan.sg_class)):
         names = [("g%d" % plan.items[i].ref) if plan.items[i].is_group else ("c%d" % plan.items[i].ref)
                  for i in sg]

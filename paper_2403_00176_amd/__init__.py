@@ -66,7 +66,8 @@ class _GraphDesc(C.Structure):
 
 
 class PlanOpts(C.Structure):
-    _fields_ = [("fusion", C.c_int32), ("sep", C.c_int32), ("dmp", C.c_int32), ("mvc", C.c_int32)]
+    _fields_ = [("fusion", C.c_int32), ("sep", C.c_int32), ("dmp", C.c_int32), ("mvc", C.c_int32),
+                ("inplace", C.c_int32)]
 
 
 class DimInfo(C.Structure):
@@ -255,9 +256,9 @@ def sod2_rdp_dump(r: Rdp) -> str:
     return _text(_lib.sod2_rdp_dump, r.ptr)
 
 
-def sod2_plan(g: Graph, r: Rdp, fusion=1, sep=1, dmp=1, mvc=1) -> Plan:
+def sod2_plan(g: Graph, r: Rdp, fusion=1, sep=1, dmp=1, mvc=1, inplace=1) -> Plan:
     out = C.c_void_p()
-    opts = PlanOpts(int(fusion), int(sep), int(dmp), int(mvc))
+    opts = PlanOpts(int(fusion), int(sep), int(dmp), int(mvc), int(inplace))
     _check(_lib.sod2_plan(g.ptr, r.ptr, C.byref(opts), C.byref(out)))
     p = Plan(out, keep=(g, r))
     p.graph = g

@@ -117,6 +117,8 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
           }
         } else if (p.view[pr]) {
           r = (*this)(op.in[0]);
+        } else if (p.inplace[t] >= 0) {             // the result took over an operand's storage
+          r = {group_dead[p.group_of_op[pr]] != 0, (*this)(p.inplace[t]).second};
         } else {
           r = {group_dead[p.group_of_op[pr]] != 0, t};
         }
@@ -181,7 +183,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
             throw Error(SOD2_ERR_INVALID_ARG, "session tensor " + G.tensors[tc].name + " would outgrow its capacity");
         }
         if (nz_bytes >= 0) n = nz_bytes;
-        if (p.arena_candidate(t)) b.tensors[t] = ArenaTensor{t, (n + 255) / 256 * 256, step, step, -1};
+        if (p.arena_candidate(t) && p.inplace[t] < 0) b.tensors[t] = ArenaTensor{t, (n + 255) / 256 * 256, step, step, -1};
       } else {
         const Op& op = G.ops[it.ref];
         if (op.kind == SOD2_OP_SWITCH) {
@@ -316,6 +318,8 @@ std::string BindResult::dump(const Plan& p) const {
              std::to_string(at->second.start) + ".." + std::to_string(at->second.end) + "\n";
     else if (session_root.count(kv.first))
       out += " session=t" + std::to_string(session_root.at(kv.first)) + "\n";
+    else if (p.inplace[kv.first] >= 0)
+      out += " inplace=t" + std::to_string(dyn_base[kv.first]) + "\n";
     else
       out += " external\n";
   }

@@ -182,7 +182,7 @@ struct Plan {
   std::shared_ptr<Rdp> named;                      // analysis with named EDO extents, owned (see Rdp::named_edo)
   std::vector<int> exec_ops;                       // NonZero operators in the node order
   bool execution_determined(int t) const;          // nac in the paper's lattice: unresolved or in an execution symbol
-  sod2_plan_opts opts{1, 1, 1, 1};
+  sod2_plan_opts opts{1, 1, 1, 1, 1};
   std::vector<int> order;
   std::vector<char> folded, view;
   std::map<int, Group> groups;
@@ -200,6 +200,7 @@ struct Plan {
   void build();
   std::string dump() const;
   bool arena_candidate(int t) const;
+  std::vector<int> inplace;                        // group result -> the operand whose storage it takes over, or -1
 };
 
 // ---------------------------------------------------------------------------------------------

@@ -506,6 +506,63 @@ void Plan::build() {
     subgraphs.push_back(seq);
   }
 
+  // In-place reuse (a refinement of the lifetime rule of Section 4.4.1): the result of a contraction
+  // group with a residual operand, or of an elementwise group, takes over the storage of an operand r
+  // when, on every path, (1) r is a group's result in the arena with the type and provably the shape
+  // of the result, which lives in the arena too; (2) the group reads the storage of r through that
+  // operand only (a kernel thread reads just the elements of r it is about to write) and stores
+  // without a permutation; (3) the group is the last item in the planned order that reads the storage
+  // of r and no Combine forwards r.
+  inplace.assign(nt, -1);
+  if (opts.inplace) {
+    std::map<int, int> position;
+    for (const auto& sg : subgraphs) for (int i : sg) { int k = (int)position.size(); position[i] = k; }
+    std::set<int> combined, taken;
+    std::map<int, std::vector<int>> readers;
+    for (size_t i = 0; i < items.size(); ++i) {
+      if (!items[i].is_group && G.ops[items[i].ref].kind == SOD2_OP_COMBINE) combined.insert(items[i].reads.begin(), items[i].reads.end());
+      for (int t : items[i].reads) readers[t].push_back((int)i);
+    }
+    for (size_t i = 0; i < items.size(); ++i) {
+      if (!items[i].is_group) continue;
+      const Group& gr = groups.at(items[i].ref);
+      if ((gr.kind != G_GEMM && gr.kind != G_CONV && gr.kind != G_ELTWISE) || !arena_candidate(gr.out)) continue;
+      bool barred = false;
+      for (int n : gr.ops) {
+        int k = G.ops[n].kind;
+        if (k == SOD2_OP_TRANSPOSE || k == SOD2_OP_LAYERNORM || k == SOD2_OP_CACHEAPPEND) barred = true;
+      }
+      if (barred) continue;
+      std::set<int> inside;
+      for (int n : gr.ops) for (int o : G.ops[n].out) inside.insert(o);
+      std::vector<int> outer, cands;
+      for (int n : gr.ops)
+        for (int t : G.ops[n].in)
+          if (!inside.count(t) && !inside.count(sbase[t])) {
+            outer.push_back(t);
+            if (gr.kind == G_ELTWISE || G.ops[n].kind == SOD2_OP_ADD) cands.push_back(t);
+          }
+      for (int r : cands) {
+        const Tensor& d = G.tensors[r];
+        if (d.role != SOD2_INTER || !arena_candidate(r) || combined.count(r) || taken.count(r)) continue;
+        int pr = G.producer[r];
+        if (pr < 0 || folded[pr] || view[pr] || is_control(G.ops[pr].kind) || G.ops[pr].kind == SOD2_OP_NONZERO) continue;
+        if (groups.at(group_of_op[pr]).out != r) continue;
+        if (d.dtype != G.tensors[gr.out].dtype || !shape_equal(R.S[r], R.S[gr.out])) continue;
+        int through = 0;
+        bool only_r = true;
+        for (int t : outer) if (sbase[t] == r) { ++through; if (t != r) only_r = false; }
+        if (through != 1 || !only_r) continue;
+        bool last = true;
+        for (int j : readers[r]) if (j != (int)i && position.at(j) > position.at((int)i)) last = false;
+        if (!last) continue;
+        inplace[gr.out] = r;
+        taken.insert(r);
+        break;
+      }
+    }
+  }
+
   // flattened forms used by every bind
   for (const Symbol& sy : G.symbols) xc.symbols.push_back(sy.name);
   for (int n : order) if (G.ops[n].kind == SOD2_OP_NONZERO) exec_ops.push_back(n);
@@ -555,6 +612,8 @@ std::string Plan::dump() const {
       out += "c" + std::to_string(it.ref) + " " + op_name(g->ops[it.ref].kind) + "\n";
     }
   }
+  for (size_t t = 0; t < inplace.size(); ++t)
+    if (inplace[t] >= 0) out += "inplace t" + std::to_string(t) + "=t" + std::to_string(inplace[t]) + "\n";
   for (size_t s = 0; s < subgraphs.size(); ++s) {
     out += "sg" + std::to_string(s) + " " + sg_class[s];
     for (int i : subgraphs[s]) out += std::string(" ") + (items[i].is_group ? "g" : "c") + std::to_string(items[i].ref);

@@ -130,7 +130,7 @@ struct Builder {
     } else if (pr < 0 || (!p.view[pr] && G.ops[pr].kind != SOD2_OP_SWITCH && G.ops[pr].kind != SOD2_OP_COMBINE)) {
       if (pr >= 0 && p.groups.at(p.group_of_op[pr]).out != t)
         throw Error(SOD2_ERR_UNSUPPORTED, "tensor inside a fused group is read from outside: " + G.tensors[t].name);
-      v.base = t;
+      v.base = (pr >= 0 && p.inplace[t] >= 0 && b.dyn_base[t] >= 0) ? b.dyn_base[t] : t;   // in place: the operand's storage
       v.dims = eval_dims(t);
       v.strides = contiguous_strides(v.dims);
     } else {

@@ -161,7 +161,9 @@ def test_ablation_switches_keep_values(S):
     for opts in (dict(sep=0), dict(dmp=0), dict(mvc=0), dict(fusion=0), dict(fusion=0, sep=0, dmp=0, mvc=0)):
         run_case(S, w, [(0, {"B": 2, "L": 45}), (1, {"B": 3, "L": 136})], **opts)
     w = configs.resnet50(3, 1, sizes=(64, 96), stages=(2, 1, 1, 1))
-    for opts in (dict(fusion=0), dict(fusion=0, sep=0, dmp=0, mvc=0)):
+    # (with the default options the last convolution of a block writes over its residual operand; without
+    #  fusion the Add + ReLU group does; inplace=0 gives every result its own storage)
+    for opts in (dict(fusion=0), dict(inplace=0), dict(fusion=0, inplace=0), dict(fusion=0, sep=0, dmp=0, mvc=0)):
         run_case(S, w, [(0, {"H": 96, "W": 64})], **opts)
 
 

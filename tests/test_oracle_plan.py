@@ -321,3 +321,145 @@ def test_layernorm_prologue_rule():
     assert [gr.kind for gr in pp.groups.values()].count("LAYERNORM") == 4      # the final one sees one row: fused
     assert [gr.kind for gr in make(configs.config2(1, layers=2)).groups.values()].count("LAYERNORM") == 5
     assert [gr.kind for gr in P.build_plan(g, R.RDP(g).analyse(), P.Opts(fusion=False)).groups.values()].count("LAYERNORM") == 5
+
+
+# ---- in-place reuse -----------------------------------------------------------------------------
+def replay_storage(plan, b):
+    """Walks the executed steps with one tag per arena storage (the tensor whose data it holds now) and
+    checks every read: the storage of the tensor being read must still hold that tensor's data.  This
+    knows nothing of the in-place rule; it fails when a result overwrote storage that is read later."""
+    g = plan.graph
+    prod = plan.rdp.producer
+
+    def data_of(t):                       # the group result (or external tensor) whose data t shows
+        p = prod[t]
+        if p < 0 or plan.folded[p]:
+            return t
+        op = g.ops[p]
+        if op.kind == "Switch" or plan.view[p]:
+            return data_of(op.inputs[0])
+        if op.kind == "Combine":
+            live = [i for i in op.inputs if i in b.dyn_base]
+            return data_of(live[0])
+        return t
+    tag, reads = {}, 0
+    for i in b.steps:
+        it = plan.items[i]
+        if not it.is_group:
+            continue
+        gr = plan.groups[it.ref]
+        inside = {o for n in gr.ops for o in g.ops[n].outputs}
+        for n in gr.ops:
+            for t in g.ops[n].inputs:
+                if t in inside or plan.sbase[t] in inside:
+                    continue
+                d = data_of(t)
+                if b.dyn_base.get(d) in b.tensors:
+                    assert tag[b.dyn_base[d]] == d, (g.tensors[t].name, g.tensors[d].name)
+                    reads += 1
+        if b.dyn_base.get(gr.out) in b.tensors:
+            tag[b.dyn_base[gr.out]] = gr.out
+    return reads
+
+
+def test_inplace_reuse_on_the_residual_blocks():
+    w = configs.resnet50(3, 4, stages=(3, 4, 6, 3))
+    g = w.graph
+    on, off = make(w), make(w, inplace=False)
+    assert not off.inplace
+    # every bottleneck ends in a contraction whose epilogue adds an operand that dies there: 16 blocks
+    assert len(on.inplace) == 16
+    for out, r in on.inplace.items():
+        assert on.groups[on.group_of_op[on.rdp.producer[out]]].kind == "CONV"
+        assert R.fmt_list(on.rdp.S[out]) == R.fmt_list(on.rdp.S[r]) and g.tensors[out].dtype == g.tensors[r].dtype
+    for sym in w.calls:
+        b1, b0 = A.bind(on, sym), A.bind(off, sym)
+        A.check_no_overlap(b1)
+        assert replay_storage(on, b1) > 40
+        assert b1.arena_bytes == b1.peak_live            # still no extra space
+        assert b1.arena_bytes <= 0.8 * b0.arena_bytes    # x + mid + out at the block's last conv was the peak
+        for out, r in on.inplace.items():
+            assert out not in b1.tensors and b1.dyn_base[out] == b1.dyn_base[r]
+        assert [b1.dims[t] for t in sorted(b1.dims)] == [b0.dims[t] for t in sorted(b0.dims)]
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_storage_replay_on_every_config(cfg):
+    w = small(cfg)
+    p = make(w)
+    n_sw = sum(op.kind == "Switch" for op in w.graph.ops)
+    for ci, sym in enumerate(w.calls):
+        for dec in ([False] * n_sw, [bool((ci + k) % 2) for k in range(n_sw)]):
+            b = A.bind(p, sym, dec)
+            A.check_no_overlap(b)
+            replay_storage(p, b)
+
+
+def inplace_case(build):
+    b = GraphBuilder([("N", 1, 64)])
+    x = b.input("x", "bf16", ["N", 64])
+    w1, w2 = b.weight("w1", "bf16", [64, 64]), b.weight("w2", "bf16", [64, 64])
+    r = b.op("Relu", [b.op("MatMul", [x, w1], transB=1)])          # r: a group result in the arena
+    build(b, x, r, w2)
+    g = b.build()
+    p = P.build_plan(g, R.RDP(g).analyse())
+    bd = A.bind(p, {"N": 7})
+    A.check_no_overlap(bd)
+    replay_storage(p, bd)
+    return g, p
+
+
+def test_inplace_rule_cases():
+    def kinds(g, p):                      # (operator writing the result, operator that wrote the operand)
+        return [(g.ops[p.rdp.producer[o]].kind, g.ops[p.rdp.producer[r]].kind) for o, r in p.inplace.items()]
+    # the residual dies at the contraction: taken over
+    def ok(b, x, r, w2):
+        m = b.op("Gelu", [b.op("MatMul", [x, w2], transB=1)])
+        y = b.op("Add", [b.op("MatMul", [m, w2], transB=1), r])
+        b.mark_output(b.op("Relu", [b.op("MatMul", [y, w2], transB=1)]))
+    g, p = inplace_case(ok)
+    assert kinds(g, p) == [("Add", "Relu")]
+    # read again later: not taken over
+    def later(b, x, r, w2):
+        m = b.op("Gelu", [b.op("MatMul", [x, w2], transB=1)])
+        y = b.op("Add", [b.op("MatMul", [m, w2], transB=1), r])
+        z = b.op("Add", [b.op("MatMul", [y, w2], transB=1), r])
+        b.mark_output(b.op("Relu", [b.op("MatMul", [z, w2], transB=1)]))
+    g, p = inplace_case(later)
+    assert len(p.inplace) == 1           # only the second, last, reader
+    (o, r), = p.inplace.items()
+    assert p.rdp.producer[o] > min(n for n, op in enumerate(g.ops) if op.kind == "Add")
+    # the residual is also the contraction's own operand: every tile would read rows it overwrites
+    def same(b, x, r, w2):
+        y = b.op("Add", [b.op("MatMul", [r, w2], transB=1), r])
+        b.mark_output(b.op("Relu", [b.op("MatMul", [y, w2], transB=1)]))
+    assert not inplace_case(same)[1].inplace
+    # read through a view as well
+    def viewed(b, x, r, w2):
+        v = b.op("Reshape", [r, b.const("s", [-1, 64], "i64")])
+        y = b.op("Add", [b.op("MatMul", [v, w2], transB=1), r])
+        b.mark_output(b.op("Relu", [b.op("MatMul", [y, w2], transB=1)]))
+    assert not inplace_case(viewed)[1].inplace
+    # the result is a graph output (caller memory), or the operand is a graph input
+    def out_is_output(b, x, r, w2):
+        m = b.op("Gelu", [b.op("MatMul", [x, w2], transB=1)])
+        b.mark_output(b.op("Add", [b.op("MatMul", [m, w2], transB=1), r]))
+    assert not inplace_case(out_is_output)[1].inplace
+    def operand_is_input(b, x, r, w2):
+        y = b.op("Add", [b.op("MatMul", [r, w2], transB=1), x])
+        b.mark_output(b.op("Relu", [b.op("MatMul", [y, w2], transB=1)]))
+    assert not inplace_case(operand_is_input)[1].inplace
+    # a permuted store writes other positions than it reads
+    def permuted(b, x, r, w2):
+        m = b.op("Gelu", [b.op("MatMul", [x, w2], transB=1)])
+        y = b.op("Transpose", [b.op("Add", [b.op("MatMul", [m, w2], transB=1), r])], perm=[1, 0])
+        b.mark_output(b.op("Relu", [b.op("MatMul", [w2, y])]))
+    assert not inplace_case(permuted)[1].inplace
+    # an elementwise group takes over the first operand that qualifies; a broadcast operand never does
+    def eltwise(b, x, r, w2):
+        m = b.op("Gelu", [b.op("MatMul", [x, w2], transB=1)])
+        row = b.op("ReduceMean", [m], axes=[0], keepdims=1)
+        y = b.op("Mul", [b.op("Add", [row, m]), r])
+        b.mark_output(b.op("Relu", [b.op("MatMul", [y, w2], transB=1)]))
+    g, p = inplace_case(eltwise)
+    assert kinds(g, p) == [("Mul", "Gelu")]           # m: the first full-shape operand that dies there
