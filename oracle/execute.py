@@ -123,6 +123,18 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
             y = np.broadcast_to(xs[0], tgt)
         elif k == "Resize":
             y = O.resize_nearest(xs[0], xs[1])
+        elif k == "Upsample":
+            y = O.resize_nearest(xs[0], [int(d) * int(f) for d, f in zip(xs[0].shape, np.asarray(xs[1]).reshape(-1))])
+        elif k == "ConstantOfShape":
+            y = np.full(tuple(int(v) for v in np.asarray(xs[0]).reshape(-1)), float(a.get("value", 0.0)))
+        elif k == "EyeLike":
+            y = np.eye(xs[0].shape[0], xs[0].shape[1], k=int(a.get("k", 0)))
+        elif k == "OneHot":
+            depth = int(np.asarray(xs[1]).reshape(-1)[0])
+            off, on = (float(v) for v in np.asarray(xs[2]).reshape(-1))
+            idx = np.asarray(xs[0], dtype=np.int64)
+            idx = np.where(idx < 0, idx + depth, idx)
+            y = np.where(idx[..., None] == np.arange(depth), on, off)
         elif k == "ScatterRows":
             y = np.array(xs[0], copy=True)
             for j, r in enumerate(np.asarray(xs[1], dtype=np.int64).reshape(-1)):

@@ -18,7 +18,7 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     following Transpose is still taken: the permuted store is a layout choice
     of the contraction, and without it the Reshape behind it would need a copy.
 R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
-    ScatterRows, Resize, and a Concat or Range that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
+    ScatterRows, Resize, Upsample, OneHot, and a Concat, Range, ConstantOfShape or EyeLike that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
 R4  Remaining elementwise operators chain while every aligned dim pair of
     every operand is proven equal or 1 (the condition of Fig. 4), up to 8 ops.
@@ -70,7 +70,8 @@ ACTS = ("Relu", "Gelu", "Sigmoid")
 ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast")
 SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
         "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
-        "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE"}
+        "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE",
+        "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT"}
 
 
 @dataclass

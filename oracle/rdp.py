@@ -28,12 +28,13 @@ INT_MAX = 2 ** 31 - 1
 
 ISDO, ISDOS, ISVDOS, EDO = "ISDO", "ISDOS", "ISVDOS", "EDO"
 OP_CLASS = {
-    "Shape": ISDO,
+    "Shape": ISDO, "ConstantOfShape": ISDO, "EyeLike": ISDO,
     "Gather": ISDOS, "Concat": ISDOS, "Transpose": ISDOS, "MatMul": ISDOS, "Conv": ISDOS,
     "Add": ISDOS, "Mul": ISDOS, "Relu": ISDOS, "Gelu": ISDOS, "Sigmoid": ISDOS, "Cast": ISDOS,
     "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
     "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS, "Range": ISVDOS, "Expand": ISVDOS,
+    "OneHot": ISVDOS, "Upsample": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
 UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm")
@@ -568,6 +569,58 @@ class RDP:
         if not isinstance(x, list) or not isinstance(tv, list):
             return NAC, UNDEF
         return broadcast_shapes(list(x), list(tv)), UNDEF
+
+    def _f_ConstantOfShape(self, op):
+        """A tensor of the shape held by the *values* of the input, every element the attribute value
+        (Table 2 lists it with Shape: the result is known from the input alone, nothing is computed)."""
+        ts, tv = self.S[op.inputs[0]], self.V[op.inputs[0]]
+        if ts is UNDEF or tv is UNDEF:
+            return None
+        if isinstance(tv, list):
+            v = UNDEF
+            if len(tv) <= 1 and all(is_expr(d) and d.is_const() for d in tv):
+                n = tv[0].const_value() if tv else 1
+                if n <= MAX_V:
+                    v = [C(int(op.attrs.get("value", 0)))] * n
+            return list(tv), v
+        if isinstance(ts, list) and len(ts) == 1 and is_expr(ts[0]) and ts[0].is_const():
+            return [NAC] * ts[0].const_value(), UNDEF    # the rank is the length of the shape tensor
+        return NAC, UNDEF
+
+    def _f_EyeLike(self, op):
+        s = self.S[op.inputs[0]]
+        if s is UNDEF:
+            return None
+        if isinstance(s, list) and len(s) != 2:
+            raise ShapeMismatch("EyeLike needs a matrix")
+        return (NAC if s == NAC else list(s)), UNDEF
+
+    def _f_OneHot(self, op):
+        """indices.shape + [depth], the depth read from the value of input 1 (last axis)."""
+        s, dv = self.S[op.inputs[0]], self.V[op.inputs[1]]
+        if s is UNDEF or dv is UNDEF:
+            return None
+        if s == NAC:
+            return NAC, UNDEF
+        depth = dv[0] if isinstance(dv, list) and len(dv) == 1 and is_expr(dv[0]) else NAC
+        return list(s) + [depth], UNDEF
+
+    def _f_Upsample(self, op):
+        """Nearest-neighbour enlargement by whole-number factors held in a host constant: every extent is
+        the input's times its factor (with constant factors the operator is as tractable as an ISDOS one,
+        the case Section 3 mentions for Upsample)."""
+        x = self.S[op.inputs[0]]
+        sc = self.g.tensors[op.inputs[1]].data
+        if sc is None or any(float(v) != int(v) or int(v) < 1 for v in sc.reshape(-1)):
+            raise ShapeMismatch("Upsample factors must be whole host constants >= 1")
+        if x is UNDEF:
+            return None
+        if x == NAC:
+            return NAC, UNDEF
+        f = [int(v) for v in sc.reshape(-1)]
+        if len(f) != len(x):
+            raise ShapeMismatch("Upsample rank")
+        return [d_mul(d, C(k)) for d, k in zip(x, f)], UNDEF
 
     def _f_Resize(self, op):
         """Output shape = the values of the sizes input (ISVDOS; lowered when they are resolved)."""

@@ -24,7 +24,8 @@ DTYPES = {"f32": 0, "bf16": 1, "i64": 2, "i32": 3}
 ROLES = {"inter": 0, "input": 1, "weight": 2, "hostconst": 3}
 OP_KINDS = ["Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul",
             "Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax",
-            "CacheAppend", "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand"]
+            "CacheAppend", "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand",
+            "Upsample", "ConstantOfShape", "EyeLike", "OneHot"]
 OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
 
 EXPORTS = [
@@ -80,7 +81,7 @@ class LaunchRecord(C.Structure):
 
 
 KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other", "gather", "append", "argmax", "attention",
-                "nonzero", "scatter", "resize", "concat", "range"]
+                "nonzero", "scatter", "resize", "concat", "range", "fill", "onehot"]
 
 _lib.sod2_last_error.restype = C.c_char_p
 _lib.sod2_version.restype = C.c_char_p
@@ -118,6 +119,10 @@ def _attrs(kind: str, attrs: dict):
         fa = float(attrs["eps"])
     elif kind == "Switch":
         fa = float(attrs["threshold"])
+    elif kind == "ConstantOfShape":
+        fa = float(attrs.get("value", 0.0))
+    elif kind == "EyeLike":
+        ia = [int(attrs.get("k", 0))]
     return ia, fa
 
 

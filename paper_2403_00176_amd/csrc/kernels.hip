@@ -1054,6 +1054,39 @@ hipError_t launch_range(const RangeArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+__global__ __launch_bounds__(256) void fill_kernel(FillArgs a) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.n) return;
+  float v = a.value;
+  if (a.cols > 0) { const long long r = i / a.cols, c = i - r * a.cols; v = (c == r + a.diag) ? 1.f : 0.f; }
+  if (a.dtype == SOD2_BF16_TAG) ((bf16_t*)a.y)[i] = f2bf(v);
+  else if (a.dtype == 0) ((float*)a.y)[i] = v;                  // dtype tags: 0 f32, 1 bf16, 2 i64, 3 i32
+  else if (a.dtype == 3) ((int*)a.y)[i] = (int)v;
+  else ((long long*)a.y)[i] = (long long)v;
+}
+hipError_t launch_fill(const FillArgs& a, hipStream_t s) {
+  if (a.n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(fill_kernel, dim3((unsigned)((a.n + 255) / 256)), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
+__global__ __launch_bounds__(256) void onehot_kernel(OneHotArgs a) {
+  const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (e >= a.n * a.depth) return;
+  const long long i = e / a.depth, d = e - i * a.depth;
+  long long ix = a.idx_i32 ? (long long)((const int*)a.idx)[i] : ((const long long*)a.idx)[i];
+  if (ix < 0) ix += a.depth;
+  const float v = ix == d ? a.on : a.off;
+  if (a.out_bf16) ((bf16_t*)a.y)[e] = f2bf(v);
+  else ((float*)a.y)[e] = v;
+}
+hipError_t launch_onehot(const OneHotArgs& a, hipStream_t s) {
+  const long long total = a.n * a.depth;
+  if (total <= 0) return hipSuccess;
+  hipLaunchKernelGGL(onehot_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s) {
   if (a.rows <= 0 || a.cols <= 0) return hipSuccess;
   const long long eb = L.out_dtype == SOD2_BF16_TAG ? 2 : 4, row_bytes = a.cols * eb;

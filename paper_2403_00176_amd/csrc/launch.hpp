@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -179,6 +179,23 @@ struct RangeArgs {
   int out_i32;
 };
 
+// y[i] = value everywhere (cols == 0), or an identity pattern: 1 where column == row + diag, else 0
+struct FillArgs {
+  void* y;
+  long long n, cols, diag;
+  float value;
+  int dtype;               // SOD2_F32 / SOD2_BF16 / SOD2_I64 / SOD2_I32
+};
+
+// y[i, d] = (index[i] == d, negative indices counted from depth) ? on : off
+struct OneHotArgs {
+  const void* idx;
+  void* y;
+  long long n, depth;
+  float on, off;
+  int idx_i32, out_bf16;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -201,6 +218,8 @@ struct Launch {
     ResizeArgs resize;
     ConcatArgs concat;
     RangeArgs range;
+    FillArgs fill;
+    OneHotArgs onehot;
   } u;
   int unit_bytes = 0;      // resize / concat: bytes of one copy unit
   bool is_layernorm = false;

@@ -8,8 +8,8 @@
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
 //     consumer of the chain so far;
-//  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, and a
-//     Concat or Range that is not folded stand alone; a
+//  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
+//     OneHot, and a Concat, Range, ConstantOfShape or EyeLike that is not folded stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
 //  R4 other elementwise operators chain while every aligned dim pair is proven equal or 1 (Fig. 4);
 //  R5 group id = smallest member id; groups are ordered by the node-order position of their
@@ -37,7 +37,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -199,6 +199,9 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_RESIZE) new_group(G_RESIZE, {n});
     else if (op.kind == SOD2_OP_CONCAT) new_group(G_CONCAT, {n});
     else if (op.kind == SOD2_OP_RANGE) new_group(G_RANGE, {n});
+    else if (op.kind == SOD2_OP_UPSAMPLE) new_group(G_RESIZE, {n});
+    else if (op.kind == SOD2_OP_CONSTANTOFSHAPE || op.kind == SOD2_OP_EYELIKE) new_group(G_FILL, {n});
+    else if (op.kind == SOD2_OP_ONEHOT) new_group(G_ONEHOT, {n});
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);

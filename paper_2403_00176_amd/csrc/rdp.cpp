@@ -15,13 +15,15 @@ namespace sod2 {
 static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
-    "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand"};
+    "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand", "Upsample", "ConstantOfShape",
+    "EyeLike", "OneHot"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
   switch (kind) {
-    case SOD2_OP_SHAPE: return 0;
-    case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: case SOD2_OP_RANGE: case SOD2_OP_EXPAND: return 2;
+    case SOD2_OP_SHAPE: case SOD2_OP_CONSTANTOFSHAPE: case SOD2_OP_EYELIKE: return 0;
+    case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: case SOD2_OP_RANGE: case SOD2_OP_EXPAND:
+    case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: return 2;
     case SOD2_OP_NONZERO: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
     default: return 1;
   }
@@ -415,6 +417,49 @@ struct Analyser {
         }
         if (x.is_list()) return done(LS::list(std::vector<LV>(x.d.size(), LV::nac())));   // the rank survives
         return done(LS::nac());
+      }
+      case SOD2_OP_CONSTANTOFSHAPE: {                    // shape = the values of the input, every element the attribute
+        const LS &ts = in_s(0), &tv = in_v(0);
+        if (ts.k == LS::UNDEF || tv.k == LS::UNDEF) return r;
+        if (tv.is_list()) {
+          LS v = LS::undef();
+          bool consts = tv.d.size() <= 1;
+          for (const LV& d : tv.d) if (!d.val() || !d.e.is_const()) consts = false;
+          if (consts) {
+            int64_t n = tv.d.empty() ? 1 : tv.d[0].e.const_value();
+            if (n <= 16) v = LS::list(std::vector<LV>((size_t)std::max<int64_t>(n, 0), LV::c((int64_t)op.fa)));
+          }
+          return done(LS::list(tv.d), v);
+        }
+        if (ts.is_list() && ts.d.size() == 1 && ts.d[0].val() && ts.d[0].e.is_const())   // the rank is the shape tensor's length
+          return done(LS::list(std::vector<LV>((size_t)ts.d[0].e.const_value(), LV::nac())));
+        return done(LS::nac());
+      }
+      case SOD2_OP_EYELIKE: {
+        const LS& x = in_s(0);
+        if (x.k == LS::UNDEF) return r;
+        if (x.is_list() && x.d.size() != 2) throw Error(SOD2_ERR_SHAPE_MISMATCH, "EyeLike needs a matrix");
+        return done(x);
+      }
+      case SOD2_OP_ONEHOT: {                             // indices.shape + [depth], the depth from the value of input 1
+        const LS &x = in_s(0), &dv = in_v(1);
+        if (x.k == LS::UNDEF || dv.k == LS::UNDEF) return r;
+        if (!x.is_list()) return done(LS::nac());
+        std::vector<LV> d = x.d;
+        d.push_back(dv.is_list() && dv.d.size() == 1 && dv.d[0].val() ? dv.d[0] : LV::nac());
+        return done(LS::list(d));
+      }
+      case SOD2_OP_UPSAMPLE: {                           // every extent times its whole-number factor (a host constant)
+        const Tensor& sc = g.tensors[op.in[1]];
+        if (!sc.has_data || sc.fdata.empty()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Upsample factors must be whole host constants >= 1");
+        for (double f : sc.fdata) if (f != (double)(int64_t)f || f < 1) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Upsample factors must be whole host constants >= 1");
+        const LS& x = in_s(0);
+        if (x.k == LS::UNDEF) return r;
+        if (!x.is_list()) return done(LS::nac());
+        if (x.d.size() != sc.fdata.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Upsample rank");
+        std::vector<LV> d;
+        for (size_t i = 0; i < x.d.size(); ++i) d.push_back(mul(x.d[i], LV::c((int64_t)sc.fdata[i])));
+        return done(LS::list(d));
       }
       case SOD2_OP_SCATTERROWS: {                        // a copy of input 0 with some rows replaced
         if (in_s(0).k == LS::UNDEF) return r;

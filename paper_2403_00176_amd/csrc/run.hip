@@ -24,6 +24,8 @@ hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s);
 hipError_t launch_resize(const Launch& L, const ResizeArgs& a, hipStream_t s);
 hipError_t launch_concat(const Launch& L, const ConcatArgs& a, hipStream_t s);
 hipError_t launch_range(const RangeArgs& a, hipStream_t s);
+hipError_t launch_fill(const FillArgs& a, hipStream_t s);
+hipError_t launch_onehot(const OneHotArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
 
@@ -945,6 +947,59 @@ struct Builder {
     return L;
   }
 
+  Launch fill(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_FILL;
+    const Op& op = G.ops[gr.ops[0]];
+    int dt = G.tensors[gr.out].dtype;
+    std::vector<int64_t> od = eval_dims(gr.out);
+    FillArgs a{};
+    a.n = 1;
+    for (int64_t d : od) a.n *= d;
+    a.dtype = dt;
+    if (op.kind == SOD2_OP_EYELIKE) {
+      if (od.size() != 2) throw Error(SOD2_ERR_SHAPE_MISMATCH, "EyeLike needs a matrix");
+      a.cols = od[1];
+      a.diag = op.ia.empty() ? 0 : op.ia[0];
+      if (a.cols == 0) a.n = 0;
+    } else {
+      a.value = (float)op.fa;
+    }
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_t(gr.out);
+    L.u.fill = a;
+    L.bytes = (double)a.n * dtype_bytes(dt);
+    return L;
+  }
+
+  Launch onehot(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_ONEHOT;
+    const Op& op = G.ops[gr.ops[0]];
+    const View& vi = view_of(op.in[0]);
+    int it = G.tensors[op.in[0]].dtype, dt = G.tensors[gr.out].dtype;
+    const Tensor& vals = G.tensors[op.in[2]];
+    if (!is_int(it) || !vi.contiguous() || (dt != SOD2_BF16 && dt != SOD2_F32) || !vals.has_data || vals.fdata.size() != 2)
+      throw Error(SOD2_ERR_UNSUPPORTED, "OneHot kernel: dense integer indices, a float result, values = host constant [off, on]");
+    std::vector<int64_t> od = eval_dims(gr.out);
+    OneHotArgs a{};
+    a.n = vi.numel();
+    a.depth = od.back();
+    if (a.depth < 0) throw Error(SOD2_ERR_INVALID_ARG, "OneHot with a negative depth");
+    a.off = (float)vals.fdata[0];
+    a.on = (float)vals.fdata[1];
+    a.idx_i32 = it == SOD2_I32;
+    a.out_bf16 = dt == SOD2_BF16;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vi, it);
+    L.r[1] = ref_t(gr.out);
+    L.u.onehot = a;
+    L.bytes = (double)a.n * dtype_bytes(it) + (double)a.n * a.depth * dtype_bytes(dt);
+    return L;
+  }
+
   Launch make(const Group& gr) {
     // a result without elements (an empty compacted batch): nothing to compute
     auto od = b.dims.find(gr.out);
@@ -957,6 +1012,8 @@ struct Builder {
       case G_NONZERO: return nonzero(gr);
       case G_SCATTER: return scatter(gr);
       case G_RANGE: return range(gr);
+      case G_FILL: return fill(gr);
+      case G_ONEHOT: return onehot(gr);
       case G_RESIZE: return resize(gr);
       case G_CONCAT: return concat(gr);
       case G_ATTENTION: return attention(gr);
@@ -1017,6 +1074,16 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       RangeArgs a = L.u.range;
       a.y = P.at(L.r[0]);
       return launch_range(a, s);
+    }
+    case K_FILL: {
+      FillArgs a = L.u.fill;
+      a.y = P.at(L.r[0]);
+      return launch_fill(a, s);
+    }
+    case K_ONEHOT: {
+      OneHotArgs a = L.u.onehot;
+      a.idx = P.at(L.r[0]); a.y = P.at(L.r[1]);
+      return launch_onehot(a, s);
     }
     case K_RESIZE: {
       ResizeArgs a = L.u.resize;

@@ -104,3 +104,34 @@ def test_range_gather_expand(S):
         by_name = dict(zip([g.tensors[t].name for t in g.outputs()], outs))
         assert np.array_equal(to_host(by_name["positions"]), np.arange(L))
         assert rel_err(to_host(by_name["y"]), ref.values[g.tensor_id("y")]) <= 1e-2
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_constantofshape_eyelike_onehot_upsample(S, dtype):
+    """The fill, identity, one-hot and whole-factor enlargement kernels against the oracle; the one-hot
+    code times a table equals the table rows the indices name (negative indices count from the depth)."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    from tests.test_shape_ops import _generators_graph
+    g, half, eye, hot = _generators_graph(dtype)
+    ses = Session(g)
+    po = P.build_plan(g, R.RDP(g).analyse())
+    rs = np.random.RandomState(7)
+    tol = 1e-5 if dtype == "f32" else 1e-2
+    for B, L, N, D in ((1, 1, 1, 2), (3, 7, 5, 11), (8, 64, 48, 40), (2, 33, 17, 3)):
+        sym = {"B": B, "L": L, "N": N, "D": D}
+        print(f"case generators {dtype} {sym}", flush=True)
+        ins = {g.tensor_id("x"): rs.randn(B, L, 8), g.tensor_id("sq"): rs.randn(N, N),
+               g.tensor_id("ids"): rs.randint(-D, D, size=(B, L)), g.tensor_id("table"): rs.randn(D, 8)}
+        b = ses.bind(sym)
+        assert S.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {}, ins)
+        for t, o in zip(g.outputs(), outs):
+            got = to_host(o)
+            assert got.shape == ref.values[t].shape
+            assert rel_err(got, ref.values[t]) <= tol, (g.tensors[t].name, sym, rel_err(got, ref.values[t]))
+        names = [g.tensors[t].name for t in g.outputs()]
+        assert np.array_equal(to_host(outs[names.index("bigger")]), ref.values[g.tensor_id("bigger")])   # a copy: exact

@@ -169,3 +169,81 @@ def test_range_and_expand_are_lowered():
     assert S.sod2_plan_dump(pl) == P.dump(plan)
     for sym in ({"B": 3, "L": 7}, {"B": 8, "L": 300}):
         assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))
+
+
+def _generators_graph(dtype="f32"):
+    """The remaining shape-driven operators of Table 2 in one graph: a constant tensor shaped like x
+    (ConstantOfShape of Shape), an identity shaped like a square input (EyeLike), a one-hot code whose
+    depth is a dim of another tensor (read through Shape), and an enlargement by whole factors."""
+    b = GraphBuilder([("B", 1, 8), ("L", 1, 64), ("N", 1, 48), ("D", 2, 40)])
+    x = b.input("x", dtype, ["B", "L", 8])
+    sq = b.input("sq", dtype, ["N", "N"])
+    ids = b.input("ids", "i64", ["B", "L"])
+    table = b.input("table", dtype, ["D", 8])
+    half = b.op("ConstantOfShape", [b.op("Shape", [x], dtype="i64")], dtype=dtype, value=0.5, hint="half")
+    b.mark_output(b.op("Add", [x, half]), "shifted")
+    eye = b.op("EyeLike", [sq], k=1, hint="eye")
+    b.mark_output(b.op("Add", [b.op("Mul", [eye, b.const("three", 3.0, "f32")]), sq]), "diag")
+    depth = b.op("Gather", [b.op("Shape", [table], dtype="i64"), b.const("i0", [0])], axis=0, dtype="i64")
+    hot = b.op("OneHot", [ids, depth, b.const("offon", [0.0, 1.0], "f32")], dtype=dtype, hint="hot")
+    b.mark_output(b.op("MatMul", [hot, table]), "picked")                     # [B, L, D] x [D, 8]
+    img = b.op("Reshape", [x, b.const("to4", [1, 0, -1, 4])], hint="img")     # [1, L, 2 B... ] any 4-d view
+    b.mark_output(b.op("Upsample", [img, b.const("f", [1.0, 2.0, 3.0, 1.0], "f32")], hint="up"), "bigger")
+    return b.build(), half, eye, hot
+
+
+def test_constantofshape_eyelike_onehot_upsample():
+    g, half, eye, hot = _generators_graph()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.S[half]) == "[s:B, s:L, k:8]"
+    assert R.fmt_list(r.S[eye]) == "[s:N, s:N]"
+    assert R.fmt_list(r.S[hot]) == "[s:B, s:L, s:D]"                            # the depth is a dim of the table
+    up = g.tensor_id("bigger")
+    assert [str(d) for d in r.S[up]][0] == "1" and [str(d) for d in r.S[up]][3] == "4"
+    plan = P.build_plan(g, r)
+    kinds = sorted(plan.groups[it.ref].kind for it in plan.items if it.is_group)
+    assert kinds == sorted(["FILL", "ELTWISE", "FILL", "ELTWISE", "ONEHOT", "GEMM", "RESIZE"])
+    rs = np.random.RandomState(4)
+    for B, L, N, D in ((1, 1, 1, 2), (3, 7, 5, 11), (8, 64, 48, 40)):
+        sym = {"B": B, "L": L, "N": N, "D": D}
+        ins = {g.tensor_id("x"): rs.randn(B, L, 8), g.tensor_id("sq"): rs.randn(N, N),
+               g.tensor_id("ids"): rs.randint(-D, D, size=(B, L)), g.tensor_id("table"): rs.randn(D, 8)}
+        res = execute.run(g, plan.order, {}, ins)
+        f32 = lambda a: O.round_to(a, "f32")
+        x, sq, table = (f32(ins[g.tensor_id(n)]) for n in ("x", "sq", "table"))
+        ids = ins[g.tensor_id("ids")]
+        # closed forms: a shift by the constant, the super-diagonal, a table lookup, pixel repetition
+        assert np.array_equal(res.values[g.tensor_id("shifted")], f32(x + 0.5))
+        ref = sq.copy()
+        ref[np.arange(N - 1), np.arange(1, N)] += 3.0
+        assert np.array_equal(res.values[g.tensor_id("diag")], f32(ref))
+        assert np.allclose(res.values[g.tensor_id("picked")], table[np.where(ids < 0, ids + D, ids)], rtol=1e-6, atol=1e-6)
+        img = x.reshape(1, L, -1, 4)
+        assert np.array_equal(res.values[up], np.repeat(np.repeat(img, 2, axis=1), 3, axis=2))
+        for t, d in ((half, [B, L, 8]), (eye, [N, N]), (hot, [B, L, D])):
+            assert list(res.values[t].shape) == d == [e.eval(sym) for e in r.S[t]]
+    # a short integer constant is known to the analysis and folds: nothing runs for it
+    b = GraphBuilder([])
+    c = b.op("ConstantOfShape", [b.const("s", [3])], dtype="i64", value=7)
+    b.mark_output(b.op("Cast", [b.op("Range", [b.const("z", [0]), b.op("Gather", [c, b.const("i", [1])], axis=0, dtype="i64"),
+                                              b.const("o", [2])], dtype="i64")], dtype="f32"))
+    gd = b.build()
+    rr = R.RDP(gd).analyse()
+    assert [e.const_value() for e in rr.V[c]] == [7, 7, 7]
+    assert P.build_plan(gd, rr).folded[0]
+    assert S.sod2_rdp_dump(S.sod2_rdp_infer(S.sod2_graph_build(gd))) == R.dump(rr)
+    # whole factors only
+    b = GraphBuilder([])
+    b.mark_output(b.op("Upsample", [b.input("x", "f32", [1, 4, 4, 2]), b.const("f", [1.0, 1.5, 2.0, 1.0], "f32")]))
+    with pytest.raises(R.ShapeMismatch):
+        R.RDP(b.build()).analyse()
+    with pytest.raises(S.Sod2Error):
+        S.sod2_rdp_infer(S.sod2_graph_build(b.build()))
+    # the library: identical analysis, plan and bindings
+    gl = S.sod2_graph_build(g)
+    rl = S.sod2_rdp_infer(gl)
+    assert S.sod2_rdp_dump(rl) == R.dump(r)
+    pl = S.sod2_plan(gl, rl)
+    assert S.sod2_plan_dump(pl) == P.dump(plan)
+    for sym in ({"B": 3, "L": 7, "N": 5, "D": 11}, {"B": 8, "L": 64, "N": 48, "D": 40}):
+        assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))

@@ -47,6 +47,10 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "Combine": (),
     "Range": (),              # inputs start, limit, delta (one-element int tensors)
     "Expand": (),             # input 1 = the shape to broadcast to
+    "Upsample": (),           # nearest neighbour by whole factors: input 1 = host constant of one factor per dim
+    "ConstantOfShape": (),    # float attr value; input 0 = the shape
+    "EyeLike": ("k",),        # ones on diagonal k of a matrix shaped like input 0
+    "OneHot": (),             # inputs indices, depth (one-element int tensor), values = host constant [off, on]; last axis
     "Resize": (),             # nearest neighbour, target shape = the values of input 1 ("sizes")
     "ScatterRows": (),        # ScatterND with row indices: copy of input 0 whose rows input 1 are replaced by input 2
 }
