@@ -278,6 +278,16 @@ def main():
     # (every duration is event-to-event and is used as measured; the first two records of a run are one and two
     # empty launches timed the same way: 2 * t1 - t2 estimates what the pair of events adds to each duration,
     # reported as event_overhead_us and in the *_net_of_event_overhead figures, for information only)
+    # sub-graph classes of the plan (all-constant shapes / symbolic-and-constant / execution-determined):
+    # their share of the sub-graphs and of the kernel time, the two panels of the paper's Fig. 8
+    sg_of_group, sg_count, sg_ms = {}, {}, {}
+    for line in S.sod2_plan_dump(ses.plan).splitlines():
+        f = line.split()
+        if f and f[0].startswith("sg") and f[0][2:].isdigit():
+            sg_count[f[1]] = sg_count.get(f[1], 0) + 1
+            for name in f[2:]:
+                if name[0] == "g":
+                    sg_of_group[int(name[1:])] = f[1]
     per = {}
     tokens = 0
     empty_ms = []
@@ -294,6 +304,8 @@ def main():
         for r in recs:
             if r["group"] < 0:
                 continue
+            cls = sg_of_group.get(r["group"], "known")
+            sg_ms[cls] = sg_ms.get(cls, 0.0) + r["ms"]
             k = per.setdefault(r["kernel"], dict(launches=0, ms=0.0, flops=0.0, bytes=0.0, raw_ms=0.0))
             k["launches"] += 1
             k["ms"] += r["ms"]
@@ -308,6 +320,10 @@ def main():
                              avg_us_net_of_event_overhead=round(1e3 * k["raw_ms"] / k["launches"], 2),
                              tflops=round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 2) if k["ms"] else 0.0,
                              gbs=round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1) if k["ms"] else 0.0)
+    n_sg, all_ms = max(sum(sg_count.values()), 1), max(sum(sg_ms.values()), 1e-9)
+    subgraph_classes = {c: dict(subgraphs=sg_count.get(c, 0), share=round(sg_count.get(c, 0) / n_sg, 3),
+                                kernel_time_share=round(sg_ms.get(c, 0.0) / all_ms, 3))
+                        for c in ("known", "mixed", "nac")}
     dom = max(per, key=lambda n: per[n]["ms"])
     d = per[dom]
     traffic = measured_traffic(dom) if args.config == 2 else None
@@ -395,6 +411,7 @@ def main():
         "call_roofline": {"t_roof_ms_per_call": round(t_roof_ms / len(timed), 4),
                           "frac_of_latency": round(t_roof_ms / len(timed) / (sum(lat) / len(lat)), 4)},
         "kernels": kernels,
+        "subgraph_classes": subgraph_classes,
         "event_overhead_us": round(1e3 * sum(empty_ms) / max(len(empty_ms), 1), 2),
         "cpu_baseline": cpu,
         "paper_context": "SoD2 reports up to 3.9x speed-up (vs ONNX Runtime, Adreno 660 GPU, fp16) and up to 88% less "

@@ -275,7 +275,7 @@ class RDP:
                     continue
                 changed |= self._forward(op, n)
                 for k, t in enumerate(op.inputs):
-                    if has_undef(self.S[t]):
+                    if has_undef(self.S[t]) or (g.tensors[t].dtype in ("i64", "i32") and has_undef(self.V[t])):
                         changed |= self._backward(op, k)
         # an undef left at the fixed point cannot be planned: lower it to nac
         for store in (self.S, self.V):
@@ -647,12 +647,21 @@ class RDP:
             return NAC, UNDEF
         return [d_add(p[0], n[0])] + [meet(x, y) for x, y in zip(p[1:], n[1:])], UNDEF
 
-    # -- backward transfer: IS <- F^bs(OS), only where the answer is unique ----
+    # -- backward transfer: IS <- F^bs(OS), IV <- F^bv(OS, OV), only where the answer is unique ----
     def _backward(self, op, k) -> bool:
         out = self.S[op.outputs[0]]
         t = op.inputs[k]
         new = UNDEF
-        if op.kind in UNARY and k == 0:
+        if op.kind == "Shape" and k == 0:
+            v = self.V[op.outputs[0]]                    # the value of the result *is* the input's shape
+            if isinstance(v, list):
+                new = list(v)
+        elif op.kind == "ConstantOfShape" and k == 0:
+            if not isinstance(out, list):                # the result's shape is the value of the input
+                return False
+            ch = self._refine(self.V, t, [UNDEF if d == NAC else d for d in out])
+            return self._refine(self.S, t, [C(len(out))]) or ch
+        elif op.kind in UNARY and k == 0:
             new = out if out != NAC else UNDEF
         elif op.kind == "Transpose" and isinstance(out, list):
             perm = op.attrs["perm"]

@@ -3,7 +3,8 @@
 // Every visit of an operator re-applies its transfer function and meets the result into the
 // stored S-/V-map, so the fixed point is independent of the visiting order; the early return of
 // Alg. 1 is the shortcut valid for the sorted order.  Switch forwards its data input's maps to
-// all outputs, Combine takes the meet of its defined inputs, a backward transfer assigns only
+// all outputs, Combine takes the meet of its defined inputs, a backward transfer (of shapes, and of
+// values through Shape and ConstantOfShape) assigns only
 // what is unique, and whatever is still undef at the fixed point is lowered to nac.
 #include <algorithm>
 #include <functional>
@@ -475,6 +476,16 @@ struct Analyser {
     const LS& out = S[op.out[0]];
     LS nw;
     switch (op.kind) {
+      case SOD2_OP_SHAPE:                               // backward value transfer: the result's value is the input's shape
+        if (k == 0 && V[op.out[0]].is_list()) nw = V[op.out[0]];
+        break;
+      case SOD2_OP_CONSTANTOFSHAPE: {                   // the result's shape is the value of the input
+        if (k != 0 || !out.is_list()) return false;
+        LS v = out;
+        for (auto& d : v.d) if (d.k == LV::NAC) d = LV::undef();
+        bool ch = refine(V, op.in[0], v);
+        return refine(S, op.in[0], LS::list({LV::c((int64_t)out.d.size())})) || ch;
+      }
       case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_CAST:
       case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM:
         if (k == 0 && out.is_list()) nw = out;
@@ -562,7 +573,8 @@ void Rdp::analyse(const std::vector<int>* order_in) {
         }
       }
       for (size_t k = 0; k < op.in.size(); ++k)
-        if (S[op.in[k]].has_undef()) changed |= A.backward(op, (int)k);
+        if (S[op.in[k]].has_undef() || (is_int(gr.tensors[op.in[k]].dtype) && V[op.in[k]].has_undef()))
+          changed |= A.backward(op, (int)k);
     }
   }
   for (auto* store : {&S, &V})

@@ -135,3 +135,24 @@ def test_constantofshape_eyelike_onehot_upsample(S, dtype):
             assert rel_err(got, ref.values[t]) <= tol, (g.tensors[t].name, sym, rel_err(got, ref.values[t]))
         names = [g.tensors[t].name for t in g.outputs()]
         assert np.array_equal(to_host(outs[names.index("bigger")]), ref.values[g.tensor_id("bigger")])   # a copy: exact
+
+
+def test_input_shape_found_by_backward_value_transfer(S):
+    """The graph declares no shape for its input: RDP finds it backwards through Shape and ConstantOfShape,
+    and the run uses it."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    from tests.test_shape_ops import _backward_value_graph
+    g, x, s, z = _backward_value_graph()
+    ses = Session(g)
+    for B, L in ((1, 1), (3, 7), (8, 64)):
+        sym = {"B": B, "L": L}
+        print(f"case backward value {sym}", flush=True)
+        xv = np.random.RandomState(B).randn(B, L, 8)
+        b = ses.bind(sym)
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs({x: xv}), outs)
+        torch.cuda.synchronize()
+        names = [g.tensors[t].name for t in g.outputs()]
+        assert np.array_equal(to_host(outs[names.index("sum")]), xv.astype(np.float32).astype(np.float64) + 1.0)
+        assert np.array_equal(to_host(outs[names.index("y")]), np.ones((B, L, 8)))

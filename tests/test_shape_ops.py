@@ -247,3 +247,54 @@ def test_constantofshape_eyelike_onehot_upsample():
     assert S.sod2_plan_dump(pl) == P.dump(plan)
     for sym in ({"B": 3, "L": 7, "N": 5, "D": 11}, {"B": 8, "L": 64, "N": 48, "D": 40}):
         assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))
+
+
+def _backward_value_graph():
+    """Nothing is declared for the input x; the only declared shape is that of an output two operators
+    behind a ConstantOfShape(Shape(x)).  The shape reaches x backwards: through the unary operator (shape),
+    through ConstantOfShape (the result's shape is the *value* of its input) and through Shape (the
+    result's value is the input's shape): the backward value transfer of Table 3."""
+    b = GraphBuilder([("B", 1, 8), ("L", 1, 64)])
+    x = b.input("x", "f32", None)
+    s = b.op("Shape", [x], dtype="i64", hint="s")
+    z = b.op("ConstantOfShape", [s], dtype="f32", value=1.0, hint="z")
+    y = b.op("Relu", [z])
+    b.g.tensors[y].dims = ["B", "L", 8]
+    b.mark_output(y, "y")
+    b.mark_output(b.op("Add", [x, z]), "sum")
+    return b.build(), x, s, z
+
+
+def test_backward_value_transfer_through_shape_and_constantofshape():
+    g, x, s, z = _backward_value_graph()
+    r = R.RDP(g).analyse()
+    for t in (x, z, g.tensor_id("sum")):
+        assert R.fmt_list(r.S[t]) == "[s:B, s:L, k:8]"
+    assert R.fmt_list(r.V[s]) == "[s:B, s:L, k:8]" and R.fmt_list(r.S[s]) == "[k:3]"
+    # the same fixed point whatever the visiting order
+    import random
+    order = list(range(len(g.ops)))
+    for seed in range(6):
+        random.Random(seed).shuffle(order)
+        assert R.dump(R.RDP(g).analyse(list(order))) == R.dump(r)
+    # without the declared output nothing is known: the transfer invents nothing
+    g2, x2, s2, z2 = _backward_value_graph()
+    g2.tensors[g2.tensor_id("y")].dims = None
+    r2 = R.RDP(g2).analyse()
+    assert r2.S[x2] == R.NAC and r2.S[z2] == R.NAC and r2.V[s2] == R.NAC
+    # a declared shape that contradicts a constant the forward pass finds is an error, not a silent choice
+    g3, x3, _, _ = _backward_value_graph()
+    g3.tensors[x3].dims = [2, 5, 9]
+    with pytest.raises(R.ShapeMismatch):
+        R.RDP(g3).analyse()
+    gl = S.sod2_graph_build(g)
+    rl = S.sod2_rdp_infer(gl)
+    assert S.sod2_rdp_dump(rl) == R.dump(r)
+    assert S.sod2_rdp_dump(S.sod2_rdp_infer(S.sod2_graph_build(g2))) == R.dump(r2)
+    plan = P.build_plan(g, r)
+    pl = S.sod2_plan(gl, rl)
+    assert S.sod2_plan_dump(pl) == P.dump(plan)
+    sym = {"B": 3, "L": 7}
+    assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))
+    res = execute.run(g, plan.order, {}, {x: np.arange(3 * 7 * 8, dtype=np.float64).reshape(3, 7, 8)})
+    assert np.array_equal(res.values[g.tensor_id("sum")], np.arange(168.0).reshape(3, 7, 8) + 1.0)
