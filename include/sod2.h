@@ -58,7 +58,7 @@ enum {
   SOD2_OP_GELU, SOD2_OP_SIGMOID, SOD2_OP_CAST, SOD2_OP_SOFTMAX, SOD2_OP_LAYERNORM,
   SOD2_OP_REDUCEMEAN, SOD2_OP_MAXPOOL, SOD2_OP_ARGMAX, SOD2_OP_CACHEAPPEND, SOD2_OP_NONZERO,
   SOD2_OP_SWITCH, SOD2_OP_COMBINE, SOD2_OP_SCATTERROWS, SOD2_OP_RESIZE, SOD2_OP_RANGE, SOD2_OP_EXPAND,
-  SOD2_OP_UPSAMPLE, SOD2_OP_CONSTANTOFSHAPE, SOD2_OP_EYELIKE, SOD2_OP_ONEHOT, SOD2_OP_COUNT
+  SOD2_OP_UPSAMPLE, SOD2_OP_CONSTANTOFSHAPE, SOD2_OP_EYELIKE, SOD2_OP_ONEHOT, SOD2_OP_TOPK, SOD2_OP_COUNT
 };
 
 #define SOD2_MAX_RANK 8
@@ -222,7 +222,7 @@ typedef struct {
   int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other,
                           8 gather, 9 cache append, 10 argmax, 11 fused attention, 12 nonzero,
                           13 scatter rows, 14 resize (nearest), 15 concat, 16 range, 17 fill (constant / identity),
-                          18 one-hot */
+                          18 one-hot, 19 top-k */
   int32_t variant;
   int32_t reserved;
   float ms;            /* event-to-event duration */

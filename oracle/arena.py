@@ -213,6 +213,13 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
                     for d in b.dims[t]:
                         n *= d
                     b.tensors[t] = ArenaTensor(t, nz_bytes if nz_bytes is not None else align_up(n), step, step)
+                for t in gr.also:                         # the operator's further results
+                    b.dims[t] = concrete_dims(plan, t, env)
+                    if arena_candidate(plan, t):
+                        n = DT_BYTES[g.tensors[t].dtype]
+                        for d in b.dims[t]:
+                            n *= d
+                        b.tensors[t] = ArenaTensor(t, align_up(n), step, step)
             else:
                 op = g.ops[it.ref]
                 if op.kind == "Switch":

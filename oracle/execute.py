@@ -123,6 +123,10 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
             y = np.broadcast_to(xs[0], tgt)
         elif k == "Resize":
             y = O.resize_nearest(xs[0], xs[1])
+        elif k == "TopK":
+            vals, idx = O.topk(xs[0], int(np.asarray(xs[1]).reshape(-1)[0]))
+            val[op.outputs[1]] = idx
+            y = vals
         elif k == "Upsample":
             y = O.resize_nearest(xs[0], [int(d) * int(f) for d, f in zip(xs[0].shape, np.asarray(xs[1]).reshape(-1))])
         elif k == "ConstantOfShape":

@@ -107,3 +107,11 @@ def resize_nearest(x, sizes):
         idx = [(i * d) // s_ for i in range(s_)]
         out = np.take(out, idx, axis=ax)
     return out
+
+
+def topk(x, k):
+    """The k largest entries of every row (last axis), largest first, and their positions; of equal
+    entries the one at the lower position comes first."""
+    x = np.asarray(x)
+    order = np.argsort(-x, axis=-1, kind="stable")[..., :k]
+    return np.take_along_axis(x, order, axis=-1), order.astype(np.int64)

@@ -18,7 +18,7 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     following Transpose is still taken: the permuted store is a layout choice
     of the contraction, and without it the Reshape behind it would need a copy.
 R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
-    ScatterRows, Resize, Upsample, OneHot, and a Concat, Range, ConstantOfShape or EyeLike that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
+    ScatterRows, Resize, Upsample, OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
 R4  Remaining elementwise operators chain while every aligned dim pair of
     every operand is proven equal or 1 (the condition of Fig. 4), up to 8 ops.
@@ -71,7 +71,7 @@ ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast")
 SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
         "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
         "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE",
-        "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT"}
+        "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT", "TopK": "TOPK"}
 
 
 @dataclass
@@ -90,6 +90,7 @@ class Group:
     ops: List[int]
     out: int                              # tensor id written by the group
     ins: List[int] = field(default_factory=list)   # base tensors read from outside the group
+    also: List[int] = field(default_factory=list)  # further results of the same operator (TopK: the indices)
 
 
 @dataclass
@@ -191,7 +192,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     def new_group(kind, members):
         gid = min(members)
         last = max(members, key=lambda n: pos[n])
-        groups[gid] = Group(gid, kind, sorted(members), g.ops[last].outputs[0])
+        groups[gid] = Group(gid, kind, sorted(members), g.ops[last].outputs[0], also=list(g.ops[last].outputs[1:]))
         for n in members:
             assigned[n] = gid
 
@@ -394,7 +395,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     items: List[Item] = []
     for _, is_group, ref in sorted(entries):
         if is_group:
-            items.append(Item(True, ref, list(groups[ref].ins), [groups[ref].out]))
+            items.append(Item(True, ref, list(groups[ref].ins), [groups[ref].out] + groups[ref].also))
         else:
             op = g.ops[ref]
             reads = []
@@ -642,7 +643,8 @@ def dump(plan: Plan) -> str:
     for it in plan.items:
         if it.is_group:
             gr = plan.groups[it.ref]
-            lines.append(f"g{gr.gid} {gr.kind} ops=[{' '.join(map(str, gr.ops))}] out=t{gr.out} "
+            also = "".join(f" also=t{t}" for t in gr.also)
+            lines.append(f"g{gr.gid} {gr.kind} ops=[{' '.join(map(str, gr.ops))}] out=t{gr.out}{also} "
                          f"ins=[{' '.join('t%d' % t for t in gr.ins)}]")
         else:
             lines.append(f"c{it.ref} {g.ops[it.ref].kind}")

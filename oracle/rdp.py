@@ -34,7 +34,7 @@ OP_CLASS = {
     "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
     "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS, "Range": ISVDOS, "Expand": ISVDOS,
-    "OneHot": ISVDOS, "Upsample": ISVDOS,
+    "OneHot": ISVDOS, "Upsample": ISVDOS, "TopK": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
 UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm")
@@ -311,7 +311,7 @@ class RDP:
             r = getattr(self, "_f_" + op.kind if op.kind not in UNARY else "_f_unary")(op)
             if r is None:
                 return False
-            res = [r]
+            res = [r] * len(op.outputs)                 # (TopK: values and indices have one shape)
         ch = False
         for o, (s, v) in zip(op.outputs, res):
             ch |= self._refine(self.S, o, s)
@@ -604,6 +604,17 @@ class RDP:
             return NAC, UNDEF
         depth = dv[0] if isinstance(dv, list) and len(dv) == 1 and is_expr(dv[0]) else NAC
         return list(s) + [depth], UNDEF
+
+    def _f_TopK(self, op):
+        """The k largest entries along the last axis, and their positions: the input's shape with the
+        last extent replaced by the value of input 1 (Fig. 3(c): the shape waits for that value)."""
+        x, kv = self.S[op.inputs[0]], self.V[op.inputs[1]]
+        if x is UNDEF or kv is UNDEF:
+            return None
+        if x == NAC:
+            return NAC, UNDEF
+        k = kv[0] if isinstance(kv, list) and len(kv) == 1 and is_expr(kv[0]) else NAC
+        return list(x[:-1]) + [k], UNDEF
 
     def _f_Upsample(self, op):
         """Nearest-neighbour enlargement by whole-number factors held in a host constant: every extent is

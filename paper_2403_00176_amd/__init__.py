@@ -25,7 +25,7 @@ ROLES = {"inter": 0, "input": 1, "weight": 2, "hostconst": 3}
 OP_KINDS = ["Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul",
             "Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax",
             "CacheAppend", "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand",
-            "Upsample", "ConstantOfShape", "EyeLike", "OneHot"]
+            "Upsample", "ConstantOfShape", "EyeLike", "OneHot", "TopK"]
 OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
 
 EXPORTS = [
@@ -81,7 +81,7 @@ class LaunchRecord(C.Structure):
 
 
 KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other", "gather", "append", "argmax", "attention",
-                "nonzero", "scatter", "resize", "concat", "range", "fill", "onehot"]
+                "nonzero", "scatter", "resize", "concat", "range", "fill", "onehot", "topk"]
 
 _lib.sod2_last_error.restype = C.c_char_p
 _lib.sod2_version.restype = C.c_char_p

@@ -184,6 +184,15 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         }
         if (nz_bytes >= 0) n = nz_bytes;
         if (p.arena_candidate(t) && p.inplace[t] < 0) b.tensors[t] = ArenaTensor{t, (n + 255) / 256 * 256, step, step, -1};
+        for (int t2 : gr.also) {                        // the operator's further results
+          if (!p.rdp->S[t2].resolved())
+            throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t2].name + " is not resolved: " + p.rdp->S[t2].str());
+          std::vector<int64_t> d2;
+          int64_t n2 = dtype_bytes(G.tensors[t2].dtype);
+          for (const CompiledExpr& d : p.cshape[t2]) { d2.push_back(d.eval(b.atom_vals)); n2 *= d2.back(); }
+          b.dims[t2] = d2;
+          if (p.arena_candidate(t2)) b.tensors[t2] = ArenaTensor{t2, (n2 + 255) / 256 * 256, step, step, -1};
+        }
       } else {
         const Op& op = G.ops[it.ref];
         if (op.kind == SOD2_OP_SWITCH) {

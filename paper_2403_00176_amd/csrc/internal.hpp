@@ -160,7 +160,7 @@ struct Rdp {
 // Static plan
 // ---------------------------------------------------------------------------------------------
 enum GroupKind { G_GEMM, G_CONV, G_LAYERNORM, G_SOFTMAX, G_MAXPOOL, G_REDUCEMEAN, G_ARGMAX,
-                 G_CACHEAPPEND, G_NONZERO, G_GATHER, G_ELTWISE, G_ATTENTION, G_SCATTER, G_RESIZE, G_CONCAT, G_RANGE, G_FILL, G_ONEHOT };
+                 G_CACHEAPPEND, G_NONZERO, G_GATHER, G_ELTWISE, G_ATTENTION, G_SCATTER, G_RESIZE, G_CONCAT, G_RANGE, G_FILL, G_ONEHOT, G_TOPK };
 const char* group_kind_name(int k);
 
 struct Group {
@@ -169,6 +169,7 @@ struct Group {
   std::vector<int> chain;                          // members in absorption order (seed first)
   int prologue = -1;                               // LayerNorm operator applied to the contraction's first operand, or -1
   std::vector<int> ins;                            // static bases read from outside
+  std::vector<int> also;                           // further results of the same operator (TopK: the indices)
 };
 struct Item {
   bool is_group = true;

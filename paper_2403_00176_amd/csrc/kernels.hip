@@ -1087,6 +1087,53 @@ hipError_t launch_onehot(const OneHotArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// One wave per row.  The entries are taken in the order (value descending, position ascending): round j
+// scans the row for the best entry that comes strictly after the one taken in round j - 1, so no
+// entry has to be marked; the 64 lanes' candidates are merged with shuffles.  k rounds over a row that
+// stays in the caches: meant for the short k of routing and detection heads.
+template <bool BF>
+__global__ __launch_bounds__(256) void topk_kernel(TopKArgs a) {
+  const long long row = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const int lane = threadIdx.x & 63;
+  if (row >= a.rows) return;
+  const bf16_t* xb = (const bf16_t*)a.x + row * a.n;
+  const float* xf = (const float*)a.x + row * a.n;
+  float last_v = 0.f;
+  long long last_i = -1;
+  for (long long j = 0; j < a.k; ++j) {
+    float best_v = 0.f;
+    long long best_i = -1;
+    for (long long i = lane; i < a.n; i += 64) {
+      const float v = BF ? bf2f(xb[i]) : xf[i];
+      const bool after = j == 0 || v < last_v || (v == last_v && i > last_i);
+      if (after && (best_i < 0 || v > best_v)) { best_v = v; best_i = i; }     // ascending i: the first of equals stays
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+      const float ov = __shfl_xor(best_v, off);
+      const long long oi = __shfl_xor(best_i, off);
+      if (oi >= 0 && (best_i < 0 || ov > best_v || (ov == best_v && oi < best_i))) { best_v = ov; best_i = oi; }
+    }
+    if (best_i < 0) { best_i = 0; best_v = 0.f; }                // only with NaN entries: stay inside the row
+    last_v = best_v;
+    last_i = best_i;
+    if (lane == 0) {
+      const long long o = row * a.k + j;
+      if (BF) ((bf16_t*)a.values)[o] = xb[best_i];
+      else ((float*)a.values)[o] = best_v;
+      if (a.idx_i32) ((int*)a.indices)[o] = (int)best_i;
+      else ((long long*)a.indices)[o] = best_i;
+    }
+  }
+}
+hipError_t launch_topk(const TopKArgs& a, hipStream_t s) {
+  if (a.rows <= 0 || a.k <= 0) return hipSuccess;
+  dim3 grid((unsigned)((a.rows + 3) / 4));
+  if (a.x_bf16) hipLaunchKernelGGL(topk_kernel<true>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(topk_kernel<false>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s) {
   if (a.rows <= 0 || a.cols <= 0) return hipSuccess;
   const long long eb = L.out_dtype == SOD2_BF16_TAG ? 2 : 4, row_bytes = a.cols * eb;

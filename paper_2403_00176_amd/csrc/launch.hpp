@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT, K_TOPK };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -196,6 +196,15 @@ struct OneHotArgs {
   int idx_i32, out_bf16;
 };
 
+// per row of n entries: the k largest, largest first (of equal entries the lower position first), and
+// their positions
+struct TopKArgs {
+  const void* x;
+  void *values, *indices;
+  long long rows, n, k;
+  int x_bf16, idx_i32;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -220,6 +229,7 @@ struct Launch {
     RangeArgs range;
     FillArgs fill;
     OneHotArgs onehot;
+    TopKArgs topk;
   } u;
   int unit_bytes = 0;      // resize / concat: bytes of one copy unit
   bool is_layernorm = false;

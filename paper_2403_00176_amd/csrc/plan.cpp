@@ -9,7 +9,7 @@
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
 //     consumer of the chain so far;
 //  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
-//     OneHot, and a Concat, Range, ConstantOfShape or EyeLike that is not folded stand alone; a
+//     OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
 //  R4 other elementwise operators chain while every aligned dim pair is proven equal or 1 (Fig. 4);
 //  R5 group id = smallest member id; groups are ordered by the node-order position of their
@@ -37,7 +37,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -149,6 +149,7 @@ void Plan::build() {
     int last = chain[0];
     for (int n : chain) if (pos[n] > pos[last]) last = n;
     gr.out = G.ops[last].out[0];
+    gr.also.assign(G.ops[last].out.begin() + 1, G.ops[last].out.end());
     for (int n : chain) group_of_op[n] = gr.gid;
     groups[gr.gid] = gr;
   };
@@ -202,6 +203,7 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_UPSAMPLE) new_group(G_RESIZE, {n});
     else if (op.kind == SOD2_OP_CONSTANTOFSHAPE || op.kind == SOD2_OP_EYELIKE) new_group(G_FILL, {n});
     else if (op.kind == SOD2_OP_ONEHOT) new_group(G_ONEHOT, {n});
+    else if (op.kind == SOD2_OP_TOPK) new_group(G_TOPK, {n});
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);
@@ -371,6 +373,7 @@ void Plan::build() {
     if (e.is_group) {
       it.reads = groups[e.ref].ins;
       it.writes = {groups[e.ref].out};
+      it.writes.insert(it.writes.end(), groups[e.ref].also.begin(), groups[e.ref].also.end());
     } else {
       const Op& op = G.ops[e.ref];
       for (int t : op.in)
@@ -610,7 +613,9 @@ std::string Plan::dump() const {
     if (it.is_group) {
       const Group& gr = groups.at(it.ref);
       out += "g" + std::to_string(gr.gid) + " " + group_kind_name(gr.kind) + " ops=[" + join(gr.ops, "") + "] out=t" +
-             std::to_string(gr.out) + " ins=[" + join(gr.ins, "t") + "]\n";
+             std::to_string(gr.out);
+      for (int t : gr.also) out += " also=t" + std::to_string(t);
+      out += " ins=[" + join(gr.ins, "t") + "]\n";
     } else {
       out += "c" + std::to_string(it.ref) + " " + op_name(g->ops[it.ref].kind) + "\n";
     }

@@ -17,14 +17,14 @@ static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
     "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand", "Upsample", "ConstantOfShape",
-    "EyeLike", "OneHot"};
+    "EyeLike", "OneHot", "TopK"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
   switch (kind) {
     case SOD2_OP_SHAPE: case SOD2_OP_CONSTANTOFSHAPE: case SOD2_OP_EYELIKE: return 0;
     case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: case SOD2_OP_RANGE: case SOD2_OP_EXPAND:
-    case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: return 2;
+    case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: case SOD2_OP_TOPK: return 2;
     case SOD2_OP_NONZERO: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
     default: return 1;
   }
@@ -448,6 +448,15 @@ struct Analyser {
         if (!x.is_list()) return done(LS::nac());
         std::vector<LV> d = x.d;
         d.push_back(dv.is_list() && dv.d.size() == 1 && dv.d[0].val() ? dv.d[0] : LV::nac());
+        return done(LS::list(d));
+      }
+      case SOD2_OP_TOPK: {                               // both results: the input's shape, last extent = the value of input 1
+        const LS &x = in_s(0), &kv = in_v(1);
+        if (x.k == LS::UNDEF || kv.k == LS::UNDEF) return r;
+        if (!x.is_list()) return done(LS::nac());
+        if (x.d.empty()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "TopK of a scalar");
+        std::vector<LV> d(x.d.begin(), x.d.end() - 1);
+        d.push_back(kv.is_list() && kv.d.size() == 1 && kv.d[0].val() ? kv.d[0] : LV::nac());
         return done(LS::list(d));
       }
       case SOD2_OP_UPSAMPLE: {                           // every extent times its whole-number factor (a host constant)

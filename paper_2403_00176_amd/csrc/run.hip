@@ -26,6 +26,7 @@ hipError_t launch_concat(const Launch& L, const ConcatArgs& a, hipStream_t s);
 hipError_t launch_range(const RangeArgs& a, hipStream_t s);
 hipError_t launch_fill(const FillArgs& a, hipStream_t s);
 hipError_t launch_onehot(const OneHotArgs& a, hipStream_t s);
+hipError_t launch_topk(const TopKArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
 
@@ -130,7 +131,8 @@ struct Builder {
       v.dims = eval_dims(t);
       v.strides = contiguous_strides(v.dims);
     } else if (pr < 0 || (!p.view[pr] && G.ops[pr].kind != SOD2_OP_SWITCH && G.ops[pr].kind != SOD2_OP_COMBINE)) {
-      if (pr >= 0 && p.groups.at(p.group_of_op[pr]).out != t)
+      const Group* owner = pr >= 0 ? &p.groups.at(p.group_of_op[pr]) : nullptr;
+      if (owner && owner->out != t && std::find(owner->also.begin(), owner->also.end(), t) == owner->also.end())
         throw Error(SOD2_ERR_UNSUPPORTED, "tensor inside a fused group is read from outside: " + G.tensors[t].name);
       v.base = (pr >= 0 && p.inplace[t] >= 0 && b.dyn_base[t] >= 0) ? b.dyn_base[t] : t;   // in place: the operand's storage
       v.dims = eval_dims(t);
@@ -1000,6 +1002,32 @@ struct Builder {
     return L;
   }
 
+  Launch topk(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_TOPK;
+    const Op& op = G.ops[gr.ops[0]];
+    const View& vx = view_of(op.in[0]);
+    int dt = G.tensors[op.in[0]].dtype, it = G.tensors[op.out[1]].dtype;
+    if (!vx.contiguous() || vx.dims.empty() || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt || !is_int(it))
+      throw Error(SOD2_ERR_UNSUPPORTED, "TopK kernel: last axis of a dense float tensor, integer positions");
+    std::vector<int64_t> od = eval_dims(gr.out);
+    TopKArgs a{};
+    a.n = vx.dims.back();
+    a.k = od.back();
+    a.rows = a.n > 0 ? vx.numel() / a.n : 0;
+    if (a.k < 0 || a.k > a.n) throw Error(SOD2_ERR_INVALID_ARG, "TopK: k outside [0, extent of the last axis]");
+    a.x_bf16 = dt == SOD2_BF16;
+    a.idx_i32 = it == SOD2_I32;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_t(gr.out);
+    L.r[2] = ref_t(op.out[1]);
+    L.u.topk = a;
+    L.bytes = (double)a.rows * (a.n * dtype_bytes(dt) + a.k * (dtype_bytes(dt) + dtype_bytes(it)));
+    return L;
+  }
+
   Launch make(const Group& gr) {
     // a result without elements (an empty compacted batch): nothing to compute
     auto od = b.dims.find(gr.out);
@@ -1014,6 +1042,7 @@ struct Builder {
       case G_RANGE: return range(gr);
       case G_FILL: return fill(gr);
       case G_ONEHOT: return onehot(gr);
+      case G_TOPK: return topk(gr);
       case G_RESIZE: return resize(gr);
       case G_CONCAT: return concat(gr);
       case G_ATTENTION: return attention(gr);
@@ -1079,6 +1108,11 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       FillArgs a = L.u.fill;
       a.y = P.at(L.r[0]);
       return launch_fill(a, s);
+    }
+    case K_TOPK: {
+      TopKArgs a = L.u.topk;
+      a.x = P.at(L.r[0]); a.values = P.at(L.r[1]); a.indices = P.at(L.r[2]);
+      return launch_topk(a, s);
     }
     case K_ONEHOT: {
       OneHotArgs a = L.u.onehot;

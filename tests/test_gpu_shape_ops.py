@@ -154,5 +154,50 @@ def test_input_shape_found_by_backward_value_transfer(S):
         ses.run(b, ses.upload_inputs({x: xv}), outs)
         torch.cuda.synchronize()
         names = [g.tensors[t].name for t in g.outputs()]
-        assert np.array_equal(to_host(outs[names.index("sum")]), xv.astype(np.float32).astype(np.float64) + 1.0)
+        assert np.array_equal(to_host(outs[names.index("sum")]), (xv.astype(np.float32) + np.float32(1.0)).astype(np.float64))
         assert np.array_equal(to_host(outs[names.index("y")]), np.ones((B, L, 8)))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_topk_router(S, dtype):
+    """TopK (values and positions from one kernel), softmax over the chosen scores and a one-hot product
+    that picks the chosen table rows.  Positions are compared exactly where the oracle's chosen scores
+    are distinct after rounding; where scores tie the kernel must still return valid positions."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    from tests.test_shape_ops import _router_graph
+    g, scores, vals, idx = _router_graph(dtype)
+    g.tensors[idx].is_output = True                    # also hand the positions to the caller
+    g.tensors[vals].is_output = True
+    ses = Session(g)
+    weights = {g.tensor_id("wr"): np.random.RandomState(1).randn(40, 64) * 0.1,
+               g.tensor_id("table"): np.random.RandomState(2).randn(40, 8)}
+    ses.upload_weights(weights)
+    po = P.build_plan(g, R.RDP(g).analyse())
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    for B, K in ((1, 1), (5, 3), (64, 16), (33, 40 if False else 16)):
+        sym = {"B": B, "K": K}
+        print(f"case router {dtype} {sym}", flush=True)
+        ins = {g.tensor_id("x"): np.random.RandomState(B + K).randn(B, 64), g.tensor_id("sel"): np.zeros((K, 8))}
+        b = ses.bind(sym)
+        assert S.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, weights, ins)
+        got = {g.tensors[t].name: to_host(o) for t, o in zip(g.outputs(), outs)}
+        gv, gi = got[g.tensors[vals].name], got[g.tensors[idx].name].astype(np.int64)
+        rv = ref.values[vals]
+        assert gv.shape == (B, K) == gi.shape
+        assert rel_err(gv, rv) <= tol
+        assert (np.diff(gv, axis=-1) <= 0).all()                        # largest first
+        assert all(len(set(row)) == K for row in gi) and gi.min() >= 0 and gi.max() < 40
+        # every returned position holds the returned value in the scores the kernel saw; the scores are
+        # not an output, so check against the oracle's within the storage tolerance
+        assert np.abs(np.take_along_axis(ref.values[scores], gi, axis=-1) - gv).max() <= tol * np.abs(rv).max()
+        gap = np.abs(np.diff(np.sort(ref.values[scores], axis=-1), axis=-1)).min(axis=-1)   # per row: closest pair
+        clear = gap > 4 * tol * np.abs(rv).max()
+        assert np.array_equal(gi[clear], ref.values[idx][clear])
+        assert rel_err(got["gates"], ref.values[g.tensor_id("gates")]) <= tol
+        if clear.all():
+            assert rel_err(got["rows"], ref.values[g.tensor_id("rows")]) <= tol

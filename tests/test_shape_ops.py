@@ -298,3 +298,79 @@ def test_backward_value_transfer_through_shape_and_constantofshape():
     assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))
     res = execute.run(g, plan.order, {}, {x: np.arange(3 * 7 * 8, dtype=np.float64).reshape(3, 7, 8)})
     assert np.array_equal(res.values[g.tensor_id("sum")], np.arange(168.0).reshape(3, 7, 8) + 1.0)
+
+
+def _router_graph(dtype="f32"):
+    """A routing head: scores = x W^T, the K best of them per row (K is a dim of another input, read
+    through Shape), softmax over those, and the table rows of the chosen columns picked with a one-hot
+    product.  TopK is the paper's own example of an operator whose output shape waits for a value
+    (Fig. 3(c)); it is also the one operator here with two results."""
+    b = GraphBuilder([("B", 1, 64), ("K", 1, 16)])
+    x = b.input("x", dtype, ["B", 64])
+    sel = b.input("sel", dtype, ["K", 8])
+    wr = b.weight("wr", dtype, [40, 64])
+    table = b.weight("table", dtype, [40, 8])
+    scores = b.op("MatMul", [x, wr], transB=1, hint="scores")
+    kdim = b.op("Gather", [b.op("Shape", [sel], dtype="i64"), b.const("i0", [0])], axis=0, dtype="i64")
+    vals, idx = b.op("TopK", [scores, kdim], n_out=2, hint="top")
+    b.g.tensors[idx].dtype = "i64"
+    b.mark_output(b.op("Softmax", [vals]), "gates")
+    hot = b.op("OneHot", [idx, b.const("depth", [40]), b.const("offon", [0.0, 1.0], "f32")], dtype=dtype)
+    b.mark_output(b.op("MatMul", [hot, table]), "rows")
+    return b.build(), scores, vals, idx
+
+
+def test_topk_brute_force_and_ties():
+    rs = np.random.RandomState(11)
+    for shape, k in (((5, 9), 3), ((2, 3, 7), 7), ((4, 6), 1), ((3, 5), 0)):
+        x = rs.randint(-2, 3, size=shape).astype(np.float64)         # few distinct values: many ties
+        vals, idx = O.topk(x, k)
+        assert vals.shape == shape[:-1] + (k,) and idx.shape == vals.shape
+        if k == 0:
+            continue
+        for row, v, i in zip(x.reshape(-1, shape[-1]), vals.reshape(-1, k), idx.reshape(-1, k)):
+            taken = []
+            for _ in range(k):                                       # pick the largest left, the first of equals
+                best = max((j for j in range(len(row)) if j not in taken), key=lambda j: (row[j], -j))
+                taken.append(best)
+            assert list(i) == taken and list(v) == [row[j] for j in taken]
+
+
+def test_topk_two_results_one_group():
+    g, scores, vals, idx = _router_graph()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.S[vals]) == "[s:B, s:K]" == R.fmt_list(r.S[idx])
+    assert R.OP_CLASS["TopK"] == "ISVDOS"
+    plan = P.build_plan(g, r)
+    top = [gr for gr in plan.groups.values() if gr.kind == "TOPK"]
+    assert len(top) == 1 and top[0].out == vals and top[0].also == [idx]
+    item = [it for it in plan.items if it.is_group and it.ref == top[0].gid][0]
+    assert item.writes == [vals, idx]
+    weights = {g.tensor_id("wr"): np.random.RandomState(1).randn(40, 64) * 0.1,
+               g.tensor_id("table"): np.random.RandomState(2).randn(40, 8)}
+    for B, K in ((1, 1), (5, 3), (64, 16)):
+        sym = {"B": B, "K": K}
+        bd = A.bind(plan, sym)
+        A.check_no_overlap(bd)
+        assert bd.dims[vals] == [B, K] == bd.dims[idx]
+        assert bd.tensors[vals].start == bd.tensors[idx].start and bd.tensors[idx].bytes == (B * K * 8 + 255) // 256 * 256
+        ins = {g.tensor_id("x"): np.random.RandomState(B).randn(B, 64), g.tensor_id("sel"): np.zeros((K, 8))}
+        res = execute.run(g, plan.order, weights, ins)
+        sc, iv = res.values[scores], res.values[idx]
+        assert np.array_equal(np.sort(sc, axis=-1)[:, ::-1][:, :K], res.values[vals])
+        assert np.allclose(res.values[g.tensor_id("gates")].sum(-1), 1.0)
+        assert np.allclose(res.values[g.tensor_id("rows")], O.round_to(weights[g.tensor_id("table")], "f32")[iv], atol=1e-6)
+    # a k that only a run-time value fixes: the shapes behind it wait (nac), as in Fig. 3(c)
+    b = GraphBuilder([("B", 1, 8)])
+    v2, i2 = b.op("TopK", [b.input("x", "f32", ["B", 32]), b.input("k", "i64", [1])], n_out=2)
+    b.mark_output(v2)
+    r2 = R.RDP(b.build()).analyse()
+    assert R.fmt_list(r2.S[v2]) == "nac" == R.fmt_list(r2.S[i2])
+    gl = S.sod2_graph_build(g)
+    rl = S.sod2_rdp_infer(gl)
+    assert S.sod2_rdp_dump(rl) == R.dump(r)
+    assert S.sod2_rdp_dump(S.sod2_rdp_infer(S.sod2_graph_build(b.build()))) == R.dump(r2)
+    pl = S.sod2_plan(gl, rl)
+    assert S.sod2_plan_dump(pl) == P.dump(plan)
+    for sym in ({"B": 5, "K": 3}, {"B": 64, "K": 16}):
+        assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))

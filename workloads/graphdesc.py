@@ -51,6 +51,7 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "ConstantOfShape": (),    # float attr value; input 0 = the shape
     "EyeLike": ("k",),        # ones on diagonal k of a matrix shaped like input 0
     "OneHot": (),             # inputs indices, depth (one-element int tensor), values = host constant [off, on]; last axis
+    "TopK": (),               # inputs x, k (one-element int tensor); results values, indices (last axis, largest first)
     "Resize": (),             # nearest neighbour, target shape = the values of input 1 ("sizes")
     "ScatterRows": (),        # ScatterND with row indices: copy of input 0 whose rows input 1 are replaced by input 2
 }
