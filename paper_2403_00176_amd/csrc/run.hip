@@ -1253,6 +1253,9 @@ std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force
 
 using namespace sod2;
 
+// kernels that must be in flight for sod2_run to plan a Switch's other outcome while it waits for the predicate
+static const int SPECULATE_MIN_QUEUED = 8;
+
 // Pinned host memory that receives the few bytes read back at a Switch or after a NonZero: one slot
 // per host thread, allocated on first use and kept until the process ends.
 static void* readback_slot() {
@@ -1478,8 +1481,9 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
     std::unique_ptr<Builder> lazy;                  // builds the launches of `replanned` on demand
     // an execution-determined fact (a Switch decision, a NonZero count) has just become known at
     // step k: plan what follows with it (Section 4.3) and build the launches of the remaining steps
-    auto replan = [&](size_t k, const char* what) {
-      replanned = bind_plan(p, h->symbols, decisions, true, exec_values);
+    auto replan = [&](size_t k, const char* what, BindResult* ready = nullptr) {
+      if (ready) replanned = std::move(*ready);
+      else replanned = bind_plan(p, h->symbols, decisions, true, exec_values);
       if ((size_t)replanned.arena_bytes > arena_bytes) {
         h->executed = replanned;               // sod2_run_arena_bytes now reports what this path needs
         h->has_executed = true;
@@ -1503,6 +1507,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
       launches = &relaunch;
     };
     size_t k = 0, n_nz = 0;
+    int queued = 0;                                 // kernels enqueued since the stream was last synchronised
     bool assumed = false;                           // a fact confirmed what the plan in use had assumed
     while (k < cur->steps.size()) {
       const Item& it = p.items[cur->steps[k]];
@@ -1518,6 +1523,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
         hipError_t e = dispatch(L, P, s);
         if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
         if (ev) { (void)hipEventRecord(ev[n_ev + 1], s); timed.push_back({n_ev, L}); n_ev += 2; }
+        if (!L.empty) ++queued;
         if (L.kernel == K_NONZERO) {
           // the extent is execution determined: read the count back, then size and plan what follows
           void* slot = P.at(L.r[2]);
@@ -1525,6 +1531,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
           *host = -1;
           e = hipMemcpyAsync(host, slot, 8, hipMemcpyDeviceToHost, s);
           if (e == hipSuccess) e = hipStreamSynchronize(s);
+          queued = 0;
           if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("NonZero count read failed: ") + hipGetErrorString(e));
           const long long count = *host;
           if (count < 0 || count > L.u.nz.n) throw Error(SOD2_ERR_HIP, "NonZero kernel reported an impossible count");
@@ -1546,6 +1553,8 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
         if (which >= decisions.size()) {
           // the predicate is execution determined: read it back, decide, plan what follows (Section 4.3)
           int dec;
+          BindResult other;                        // the plan for the outcome the plan in use does not assume
+          bool have_other = false;
           if (h->has_forced && which < h->forced.size()) {
             dec = h->forced[which] ? 1 : 0;
           } else {
@@ -1556,7 +1565,18 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
             void* host = readback_slot();
             int dt = G.tensors[op.in[1]].dtype;
             hipError_t e = hipMemcpyAsync(host, P.at(r), dt == SOD2_BF16 ? 2 : 4, hipMemcpyDeviceToHost, s);
+            // While the GPU still works through the kernels enqueued since the last synchronise (a layer that
+            // ran: ~100 us), this thread would only wait: it plans the other outcome meanwhile, so that a
+            // decision against the assumed one finds its plan ready.  With little work queued (the previous
+            // layer was skipped too) the plan is computed after the decision, as before.
+            if (e == hipSuccess && queued >= SPECULATE_MIN_QUEUED) {
+              std::vector<int> d2 = decisions;
+              d2.push_back(1);
+              other = bind_plan(p, h->symbols, d2, true, exec_values);
+              have_other = true;
+            }
             if (e == hipSuccess) e = hipStreamSynchronize(s);
+            queued = 0;
             if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("predicate read failed: ") + hipGetErrorString(e));
             if (dt == SOD2_BF16) { uint32_t u = (uint32_t)(*(uint16_t*)host) << 16; std::memcpy(&hv, &u, 4); }
             else std::memcpy(&hv, host, 4);
@@ -1564,7 +1584,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
           }
           decisions.push_back(dec);
           // the current plan assumed that the layer runs: only the other outcome changes it
-          if (dec != 0) replan(k, "Switch");
+          if (dec != 0) replan(k, "Switch", have_other ? &other : nullptr);
           else assumed = true;
         }
       }
