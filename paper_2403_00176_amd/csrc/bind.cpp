@@ -29,8 +29,10 @@ namespace sod2 {
 namespace {
 bool intersects(const ArenaTensor& a, const ArenaTensor& b) { return a.start <= b.end && b.start <= a.end; }
 
-int64_t first_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& placed) {
-  std::vector<std::pair<int64_t, int64_t>> busy;
+typedef std::vector<std::pair<int64_t, int64_t>> Ranges;
+// (busy: scratch of the caller, so that placing a tensor allocates nothing)
+int64_t first_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& placed, Ranges& busy) {
+  busy.clear();
   for (const ArenaTensor* p : placed) if (intersects(t, *p)) busy.push_back({p->offset, p->offset + p->bytes});
   std::sort(busy.begin(), busy.end());
   int64_t off = 0;
@@ -130,6 +132,10 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
   } info{p, G, b, group_dead, memo_dead, memo_base};
 
   std::vector<int> reads_at(nt, -1);
+  b.tensors.reserve(p.items.size() + 8);
+  b.dims.reserve(p.items.size() + 8);
+  b.steps.reserve(p.items.size());
+  b.step_sg.reserve(p.items.size());
   for (size_t s = 0; s < p.subgraphs.size(); ++s) {
     for (int i : p.subgraphs[s]) {
       const Item& it = p.items[i];
@@ -162,16 +168,18 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         const LS& sh = p.rdp->S[t];
         if (!sh.resolved())
           throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t].name + " is not resolved: " + sh.str());
-        std::vector<int64_t> dims;
         int64_t n = dtype_bytes(G.tensors[t].dtype);
-        for (const CompiledExpr& d : p.cshape[t]) { dims.push_back(d.eval(b.atom_vals)); n *= dims.back(); }
-        b.dims[t] = dims;
+        {
+          DimList& dims = b.dims[t];
+          dims.n = 0;
+          for (const CompiledExpr& d : p.cshape[t]) { dims.push_back(d.eval(b.atom_vals)); n *= dims.back(); }
+        }
         for (int n_op : gr.ops) {                       // a CACHEAPPEND group, or appends inside an attention group
           if (G.ops[n_op].kind != SOD2_OP_CACHEAPPEND) continue;
           int tc = G.ops[n_op].out[0];
           auto root = b.session_root.find(G.ops[n_op].in[0]);
           if (root == b.session_root.end()) throw Error(SOD2_ERR_UNSUPPORTED, "CacheAppend must extend a session tensor");
-          std::vector<int64_t> cd;
+          DimList cd;
           int64_t elems = 1;
           for (const CompiledExpr& d : p.cshape[tc]) { cd.push_back(d.eval(b.atom_vals)); elems *= cd.back(); }
           if (p.cshape[tc].empty() && !p.rdp->S[tc].resolved())
@@ -187,7 +195,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         for (int t2 : gr.also) {                        // the operator's further results
           if (!p.rdp->S[t2].resolved())
             throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t2].name + " is not resolved: " + p.rdp->S[t2].str());
-          std::vector<int64_t> d2;
+          DimList d2;
           int64_t n2 = dtype_bytes(G.tensors[t2].dtype);
           for (const CompiledExpr& d : p.cshape[t2]) { d2.push_back(d.eval(b.atom_vals)); n2 *= d2.back(); }
           b.dims[t2] = d2;
@@ -234,6 +242,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
   b.peak_live += b.session_bytes;
 
   std::vector<const ArenaTensor*> placed;
+  Ranges busy;
   if (p.opts.dmp) {
     std::vector<ArenaTensor*> by_start;                // every region takes its tensors from the front
     for (auto& kv : b.tensors) by_start.push_back(&kv.second);
@@ -280,7 +289,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
           if (left == 0) break;
           for (ArenaTensor* a : mine) {
             if (a->offset >= 0 || a->start > pk || a->end < pk) continue;
-            a->offset = first_fit(*a, placed);
+            a->offset = first_fit(*a, placed, busy);
             placed.push_back(a);
             --left;
           }

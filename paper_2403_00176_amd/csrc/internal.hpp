@@ -1,6 +1,7 @@
 // Host-side data structures of the SoD2 library: symbolic expressions, the RDP lattice,
 // the graph, the static plan and a binding.  Device code lives in kernels.hip / run.hip.
 #pragma once
+#include <algorithm>
 #include <cstdint>
 #include <map>
 #include <memory>
@@ -209,6 +210,60 @@ struct Plan {
 // ---------------------------------------------------------------------------------------------
 struct ArenaTensor { int tid; int64_t bytes; int start, end; int64_t offset; };
 
+// The part of std::map<int, V> that a binding needs, over one sorted vector: a plan is bound on the
+// critical path of every call (and again after every execution-determined fact), and a node
+// allocation per tensor was a third of that time.  Iteration is in key order; references stay valid
+// until the next insertion.
+template <class V>
+struct FlatMap {
+  typedef std::pair<int, V> value_type;
+  typedef typename std::vector<value_type>::iterator iterator;
+  typedef typename std::vector<value_type>::const_iterator const_iterator;
+  std::vector<value_type> v;
+  iterator begin() { return v.begin(); }
+  iterator end() { return v.end(); }
+  const_iterator begin() const { return v.begin(); }
+  const_iterator end() const { return v.end(); }
+  size_t size() const { return v.size(); }
+  bool empty() const { return v.empty(); }
+  void reserve(size_t n) { v.reserve(n); }
+  iterator lower(int k) {
+    return std::lower_bound(v.begin(), v.end(), k, [](const value_type& a, int key) { return a.first < key; });
+  }
+  const_iterator lower(int k) const {
+    return std::lower_bound(v.begin(), v.end(), k, [](const value_type& a, int key) { return a.first < key; });
+  }
+  iterator find(int k) { iterator it = lower(k); return (it != v.end() && it->first == k) ? it : v.end(); }
+  const_iterator find(int k) const { const_iterator it = lower(k); return (it != v.end() && it->first == k) ? it : v.end(); }
+  size_t count(int k) const { return find(k) != v.end() ? 1 : 0; }
+  V& operator[](int k) {
+    if (v.empty() || v.back().first < k) { v.push_back(value_type(k, V())); return v.back().second; }
+    iterator it = lower(k);
+    if (it == v.end() || it->first != k) it = v.insert(it, value_type(k, V()));
+    return it->second;
+  }
+  const V& at(int k) const {
+    const_iterator it = find(k);
+    if (it == v.end()) throw std::out_of_range("FlatMap::at");
+    return it->second;
+  }
+};
+
+// extents of one tensor, stored inline (a rank is at most SOD2_MAX_RANK)
+struct DimList {
+  int n = 0;
+  int64_t d[SOD2_MAX_RANK];
+  size_t size() const { return (size_t)n; }
+  const int64_t* begin() const { return d; }
+  const int64_t* end() const { return d + n; }
+  int64_t operator[](size_t i) const { return d[i]; }
+  int64_t back() const { return d[n - 1]; }
+  void push_back(int64_t x) {
+    if (n >= SOD2_MAX_RANK) throw Error(SOD2_ERR_UNSUPPORTED, "tensor rank above SOD2_MAX_RANK");
+    d[n++] = x;
+  }
+};
+
 struct Layout {                                    // where an executed tensor lives
   int base = -1;                                   // tensor whose storage it occupies
   std::vector<int64_t> dims;
@@ -220,8 +275,8 @@ struct BindResult {
   std::vector<int> steps, step_sg;                 // executed item indices
   std::map<int, int> decisions;                    // Switch op id -> 1 when the skip output is taken
   std::vector<int> switch_order;                   // executed Switch operators in order
-  std::map<int, ArenaTensor> tensors;
-  std::map<int, std::vector<int64_t>> dims;        // outputs of executed groups
+  FlatMap<ArenaTensor> tensors;
+  FlatMap<DimList> dims;                           // outputs of executed groups
   std::vector<int> dyn_base;                       // per tensor: the tensor providing its storage, -1 when not executed
   std::set<int> dead_ops;
   std::map<int, std::pair<int64_t, int64_t>> session;   // session input -> (offset, bytes) at the arena bottom
