@@ -47,10 +47,54 @@ namespace {
 
 const int64_t kIntMax = 2147483647LL;
 
+// A short list of extents, strides or axes kept inline (a rank is at most SOD2_MAX_RANK): building
+// the launches of a call allocates nothing per tensor (it used to cost ~1.7 us per launch, on the
+// critical path after every read-back).
+struct Dims {
+  int n = 0;
+  int64_t d[SOD2_MAX_RANK];
+  Dims() {}
+  explicit Dims(size_t count, int64_t v = 0) {
+    if (count > SOD2_MAX_RANK) throw Error(SOD2_ERR_UNSUPPORTED, "tensor rank above SOD2_MAX_RANK");
+    n = (int)count;
+    for (int i = 0; i < n; ++i) d[i] = v;
+  }
+  size_t size() const { return (size_t)n; }
+  bool empty() const { return n == 0; }
+  int64_t& operator[](size_t i) { return d[i]; }
+  int64_t operator[](size_t i) const { return d[i]; }
+  int64_t* begin() { return d; }
+  int64_t* end() { return d + n; }
+  const int64_t* begin() const { return d; }
+  const int64_t* end() const { return d + n; }
+  int64_t& back() { return d[n - 1]; }
+  int64_t back() const { return d[n - 1]; }
+  void push_back(int64_t x) {
+    if (n >= SOD2_MAX_RANK) throw Error(SOD2_ERR_UNSUPPORTED, "tensor rank above SOD2_MAX_RANK");
+    d[n++] = x;
+  }
+  void erase(int64_t* pos) {
+    for (int64_t* q = pos; q + 1 < d + n; ++q) q[0] = q[1];
+    --n;
+  }
+  void assign(size_t count, int64_t v) { *this = Dims(count, v); }
+  int64_t front() const { return d[0]; }
+  int64_t at(size_t i) const {
+    if (i >= (size_t)n) throw Error(SOD2_ERR_INVALID_ARG, "dim index out of range");
+    return d[i];
+  }
+  bool operator==(const Dims& o) const {
+    if (n != o.n) return false;
+    for (int i = 0; i < n; ++i) if (d[i] != o.d[i]) return false;
+    return true;
+  }
+  bool operator!=(const Dims& o) const { return !(*this == o); }
+};
+
 struct View {                    // element units
   int base = -1;
   int64_t off = 0;
-  std::vector<int64_t> dims, strides;
+  Dims dims, strides;
   bool contiguous() const {
     int64_t s = 1;
     for (int i = (int)dims.size() - 1; i >= 0; --i) {
@@ -62,14 +106,14 @@ struct View {                    // element units
   int64_t numel() const { int64_t n = 1; for (auto d : dims) n *= d; return n; }
 };
 
-std::vector<int64_t> contiguous_strides(const std::vector<int64_t>& d) {
-  std::vector<int64_t> s(d.size(), 1);
+Dims contiguous_strides(const Dims& d) {
+  Dims s(d.size(), 1);
   for (int i = (int)d.size() - 2; i >= 0; --i) s[i] = s[i + 1] * d[i + 1];
   return s;
 }
 
 // strides of a reshaped view, or false when the new shape would need a copy
-bool reshape_strides(const View& in, const std::vector<int64_t>& nd, std::vector<int64_t>* ns) {
+bool reshape_strides(const View& in, const Dims& nd, Dims* ns) {
   struct Run { int64_t size, stride; };
   std::vector<Run> runs;                        // maximal blocks that are flat in memory
   for (size_t i = 0; i < in.dims.size(); ++i) {
@@ -104,14 +148,18 @@ struct Builder {
   const BindResult& b;
   int force_variant;
   int force_splits = 0;
-  std::map<int, View> memo;
+  std::vector<int> memo_at;                        // tensor -> position in memo, or -1
+  std::vector<View> memo;                          // reserved for every tensor up front: references stay valid
 
-  Builder(const Plan& p_, const BindResult& b_, int fv) : p(p_), G(*p_.g), b(b_), force_variant(fv) {}
+  Builder(const Plan& p_, const BindResult& b_, int fv) : p(p_), G(*p_.g), b(b_), force_variant(fv) {
+    memo_at.assign(G.tensors.size(), -1);
+    memo.reserve(G.tensors.size());
+  }
 
-  std::vector<int64_t> eval_dims(int t) const {
+  Dims eval_dims(int t) const {
     const LS& s = p.rdp->S[t];
     if (!s.resolved()) throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[t].name + " is not resolved");
-    std::vector<int64_t> d;
+    Dims d;
     for (const CompiledExpr& x : p.cshape[t]) d.push_back(x.eval(b.atom_vals));
     return d;
   }
@@ -121,8 +169,7 @@ struct Builder {
   }
 
   const View& view_of(int t) {
-    auto it = memo.find(t);
-    if (it != memo.end()) return it->second;
+    if (memo_at[t] >= 0) return memo[memo_at[t]];
     View v;
     int pr = G.producer[t];
     auto sr = b.session_root.find(t);
@@ -173,7 +220,7 @@ struct Builder {
             v.dims[a] = e - s;
           }
         } else if (op.kind == SOD2_OP_EXPAND) {         // broadcast dims get stride 0
-          std::vector<int64_t> nd = eval_dims(t), ns(nd.size(), 0);
+          Dims nd = eval_dims(t), ns(nd.size(), 0);
           if (nd.size() < in.dims.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Expand lowers the rank");
           size_t pad = nd.size() - in.dims.size();
           for (size_t i = 0; i < in.dims.size(); ++i) {
@@ -183,7 +230,7 @@ struct Builder {
           v.dims = nd;
           v.strides = ns;
         } else if (op.kind == SOD2_OP_RESHAPE) {
-          std::vector<int64_t> nd = eval_dims(t), ns;
+          Dims nd = eval_dims(t), ns;
           if (View{0, 0, nd, {}}.numel() != in.numel()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Reshape changes the element count");
           if (!reshape_strides(in, nd, &ns))
             throw Error(SOD2_ERR_UNSUPPORTED, "Reshape of a strided view needs a copy: " + G.tensors[t].name);
@@ -192,7 +239,9 @@ struct Builder {
         }
       }
     }
-    return memo[t] = v;
+    memo_at[t] = (int)memo.size();
+    memo.push_back(v);
+    return memo.back();
   }
 
   Ref ref_of(const View& v, int dtype) const {
@@ -305,21 +354,21 @@ struct Builder {
     g.b_sn = tb ? vb.strides[rb - 2] : vb.strides[rb - 1];
     g.b_sk = tb ? vb.strides[rb - 1] : vb.strides[rb - 2];
 
-    std::vector<int64_t> logical = eval_dims(mm.out[0]);
+    Dims logical = eval_dims(mm.out[0]);
     size_t nbatch = logical.size() - 2;
     // strides of C (and the residual) per logical dim
-    std::vector<int64_t> cs;
+    Dims cs;
     if (e.transpose >= 0) {
       const Op& tp = G.ops[e.transpose];
-      std::vector<int64_t> od(logical.size());
+      Dims od(logical.size());
       for (size_t i = 0; i < tp.ia.size(); ++i) od[i] = logical[tp.ia[i]];
-      std::vector<int64_t> os = contiguous_strides(od);
+      Dims os = contiguous_strides(od);
       cs.assign(logical.size(), 0);
       for (size_t i = 0; i < tp.ia.size(); ++i) cs[tp.ia[i]] = os[i];
     } else {
       cs = contiguous_strides(logical);
     }
-    std::vector<int64_t> rs(logical.size(), 0);
+    Dims rs(logical.size(), 0);
     if (e.res >= 0) {
       const View& vr = view_of(e.res);
       if (vr.dims != logical) throw Error(SOD2_ERR_SHAPE_MISMATCH, "residual shape differs from the MatMul result");
@@ -403,7 +452,7 @@ struct Builder {
     L.in_dtype = L.out_dtype = dt;
     const View &vx = view_of(cv.in[0]), &vw = view_of(cv.in[1]);
     if (!vx.contiguous() || !vw.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "Conv needs contiguous NHWC operands");
-    std::vector<int64_t> od = eval_dims(cv.out[0]);
+    Dims od = eval_dims(cv.out[0]);
     ConvArgs c{};
     c.NB = (int)vx.dims[0]; c.H = (int)vx.dims[1]; c.W = (int)vx.dims[2]; c.C = (int)vx.dims[3];
     c.O = (int)vw.dims[0]; c.KH = (int)vw.dims[1]; c.KW = (int)vw.dims[2];
@@ -488,7 +537,7 @@ struct Builder {
     const View& vx = view_of(op.in[0]);
     if (!vx.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "ReduceMean needs a contiguous input");
     int64_t r = (int64_t)vx.dims.size();
-    std::vector<int64_t> axes;
+    Dims axes;
     for (size_t k = 1; k < op.ia.size(); ++k) axes.push_back(((op.ia[k] % r) + r) % r);
     std::sort(axes.begin(), axes.end());
     for (size_t k = 1; k < axes.size(); ++k)
@@ -518,7 +567,7 @@ struct Builder {
     const Op& op = G.ops[gr.chain[0]];
     const View& vx = view_of(op.in[0]);
     if (!vx.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "MaxPool needs a contiguous input");
-    std::vector<int64_t> od = eval_dims(gr.out);
+    Dims od = eval_dims(gr.out);
     PoolArgs a{};
     a.NB = (int)vx.dims[0]; a.H = (int)vx.dims[1]; a.W = (int)vx.dims[2]; a.C = (int)vx.dims[3];
     a.OH = (int)od[1]; a.OW = (int)od[2];
@@ -538,7 +587,7 @@ struct Builder {
     L.group = gr.gid;
     L.kernel = K_ELTWISE;
     EltArgs a{};
-    std::vector<int64_t> od = eval_dims(gr.out);
+    Dims od = eval_dims(gr.out);
     if (od.size() > 6) throw Error(SOD2_ERR_UNSUPPORTED, "elementwise group above rank 6");
     a.rank = (int)od.size();
     a.total = 1;
@@ -730,11 +779,11 @@ struct Builder {
     a.k_sn = a.Lk == 1 ? 0 : str(vk, kn);
     a.v_sn = a.Lk == 1 ? 0 : str(vv, vn);
     // output strides per logical dim of mm2's result [batch..., Lq, d], through the absorbed Transpose
-    std::vector<int64_t> logical = eval_dims(mm2->out[0]), cs;
+    Dims logical = eval_dims(mm2->out[0]), cs;
     if (tp) {
-      std::vector<int64_t> od(logical.size());
+      Dims od(logical.size());
       for (size_t i = 0; i < tp->ia.size(); ++i) od[i] = logical[tp->ia[i]];
-      std::vector<int64_t> os = contiguous_strides(od);
+      Dims os = contiguous_strides(od);
       cs.assign(logical.size(), 0);
       for (size_t i = 0; i < tp->ia.size(); ++i) cs[tp->ia[i]] = os[i];
     } else {
@@ -955,7 +1004,7 @@ struct Builder {
     L.kernel = K_FILL;
     const Op& op = G.ops[gr.ops[0]];
     int dt = G.tensors[gr.out].dtype;
-    std::vector<int64_t> od = eval_dims(gr.out);
+    Dims od = eval_dims(gr.out);
     FillArgs a{};
     a.n = 1;
     for (int64_t d : od) a.n *= d;
@@ -985,7 +1034,7 @@ struct Builder {
     const Tensor& vals = G.tensors[op.in[2]];
     if (!is_int(it) || !vi.contiguous() || (dt != SOD2_BF16 && dt != SOD2_F32) || !vals.has_data || vals.fdata.size() != 2)
       throw Error(SOD2_ERR_UNSUPPORTED, "OneHot kernel: dense integer indices, a float result, values = host constant [off, on]");
-    std::vector<int64_t> od = eval_dims(gr.out);
+    Dims od = eval_dims(gr.out);
     OneHotArgs a{};
     a.n = vi.numel();
     a.depth = od.back();
@@ -1011,7 +1060,7 @@ struct Builder {
     int dt = G.tensors[op.in[0]].dtype, it = G.tensors[op.out[1]].dtype;
     if (!vx.contiguous() || vx.dims.empty() || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt || !is_int(it))
       throw Error(SOD2_ERR_UNSUPPORTED, "TopK kernel: last axis of a dense float tensor, integer positions");
-    std::vector<int64_t> od = eval_dims(gr.out);
+    Dims od = eval_dims(gr.out);
     TopKArgs a{};
     a.n = vx.dims.back();
     a.k = od.back();
@@ -1477,7 +1526,8 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
     std::vector<int> decisions = h->planned_decisions;
     std::vector<int64_t> exec_values = h->planned_exec;
     h->last_exec.clear();
-    std::map<int, int64_t> used_offset;             // arena tensor -> offset used by an executed kernel
+    FlatMap<int64_t> used_offset;                   // arena tensor -> offset used by an executed kernel
+    used_offset.reserve(h->b.steps.size() + 8);
     std::unique_ptr<Builder> lazy;                  // builds the launches of `replanned` on demand
     // an execution-determined fact (a Switch decision, a NonZero count) has just become known at
     // step k: plan what follows with it (Section 4.3) and build the launches of the remaining steps
