@@ -51,7 +51,17 @@ enum {
 enum { SOD2_F32 = 0, SOD2_BF16 = 1, SOD2_I64 = 2, SOD2_I32 = 3 };
 enum { SOD2_INTER = 0, SOD2_INPUT = 1, SOD2_WEIGHT = 2, SOD2_HOSTCONST = 3 };
 
-/* Operator kinds (ONNX names, Table 2, plus the <Switch, Combine> pair). */
+/* Operator kinds (ONNX names, Table 2, plus the <Switch, Combine> pair).  Inputs, where the ONNX
+ * signature is narrowed:
+ *   Slice: data, starts, ends, axes.  CacheAppend: cache (a session tensor), new rows; the result is
+ *   the cache extended in place.  ScatterRows: data, row indices, rows (a copy of data with those rows
+ *   replaced).  Resize: data, sizes (nearest neighbour, floor(i * D / S) per axis).  Upsample: data,
+ *   whole-number factors (a float HOSTCONST, one per dim).  Range: start, limit, delta (one-element
+ *   integer tensors).  Expand: data, shape.  ConstantOfShape: shape.  EyeLike: a matrix.  OneHot:
+ *   indices, depth (one-element integer tensor), values = float HOSTCONST [off, on]; last axis.
+ *   TopK: data, k (one-element integer tensor); two results, values then positions; last axis,
+ *   largest first, of equal entries the lower position first.  Switch: data, predicate (one float);
+ *   two results: taken when predicate <= threshold, taken when predicate > threshold.               */
 enum {
   SOD2_OP_SHAPE = 0, SOD2_OP_GATHER, SOD2_OP_CONCAT, SOD2_OP_RESHAPE, SOD2_OP_SLICE,
   SOD2_OP_TRANSPOSE, SOD2_OP_MATMUL, SOD2_OP_CONV, SOD2_OP_ADD, SOD2_OP_MUL, SOD2_OP_RELU,
@@ -79,7 +89,8 @@ typedef struct {
 /* Integer attributes per kind, in this order:
  *   Gather/Concat: axis.  Transpose: the permutation.  MatMul: transB.  Conv: stride, pad.
  *   Softmax: causal.  ReduceMean: keepdims, then the axes.  MaxPool: kernel, stride, pad.
- * Float attribute: LayerNorm epsilon; Switch threshold.                                         */
+ *   EyeLike: the diagonal k.
+ * Float attribute: LayerNorm epsilon; Switch threshold; ConstantOfShape value.                   */
 typedef struct {
   int32_t kind;
   int32_t n_inputs;
@@ -102,7 +113,7 @@ typedef struct {
   const sod2_op_desc* ops;
 } sod2_graph_desc;
 
-/* The four optimisation switches the paper's breakdown study names (Section 5.3). */
+/* The four optimisation switches the paper's breakdown study names (Section 5.3), and in-place reuse. */
 typedef struct {
   int32_t fusion;  /* RDP-enabled fusion; 0: one group per operator                       */
   int32_t sep;     /* static execution planning; 0: node order                            */
