@@ -29,10 +29,24 @@ def build(verbose: bool = False) -> str:
     def compile_one(src):
         obj = os.path.join(out_dir, src + ".o")
         cmd = [cc] + FLAGS + ["-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        if src.endswith(".hip"):
+            cmd.append("-Rpass-analysis=kernel-resource-usage")
         r = subprocess.run(cmd, capture_output=True, text=True)
-        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        remarks = [l for l in r.stderr.splitlines() if "[-Rpass-analysis=kernel-resource-usage]" in l]
+        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l and
+                        "-Rpass-analysis=kernel-resource-usage" not in l)
         if r.returncode != 0:
             raise RuntimeError(f"{' '.join(cmd)}\n{err}")
+        # No kernel may keep data in scratch (private) memory: an array the compiler could not hold in
+        # registers turns every access into a global memory round trip (this once cost the attention
+        # kernel 2 us per launch without any warning).
+        name = None
+        for l in remarks:
+            if "Function Name:" in l:
+                name = l.split("Function Name:")[1].split("[")[0].strip()
+            for key in ("ScratchSize [bytes/lane]:", "VGPRs Spill:"):
+                if key in l and int(l.split(key)[1].split("[")[0].strip()) != 0:
+                    raise RuntimeError(f"{src}: kernel {name} uses scratch memory ({l.split('remark:')[1].strip()})")
         if verbose and err.strip():
             print(err, file=sys.stderr)
         return obj

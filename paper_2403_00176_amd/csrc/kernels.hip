@@ -1212,8 +1212,9 @@ static hipError_t launch_fast(const AL& al, const GemmArgs& g, hipStream_t s) {
 template <class AL>
 static hipError_t launch_fast_variant(const AL& al, const GemmArgs& g, int variant, hipStream_t s) {
   switch (variant) {
+    case V_XFAT:                                                     // (a 256 x 256 tile of this kernel needs 256 accumulator
+                                                                     //  registers and spills: the version falls back to 256 x 128)
     case V_FAT: return launch_fast<AL, 2, 2, 4, 2>(al, g, s);        // 256 x 128
-    case V_XFAT: return launch_fast<AL, 2, 2, 4, 4>(al, g, s);       // 256 x 256
     case V_SKINNY: return launch_fast<AL, 1, 4, 2, 1>(al, g, s);     // 64 x 128
     case V_SMALL: return launch_fast<AL, 2, 2, 1, 1>(al, g, s);      // 64 x 64
     default: return launch_fast<AL, 2, 2, 2, 2>(al, g, s);           // 128 x 128
