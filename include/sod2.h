@@ -205,9 +205,10 @@ sod2_status sod2_binding_workspace_bytes(const sod2_binding_t*, size_t* workspac
 /* -- run -------------------------------------------------------------------------------------- */
 /* arena: device memory, 256-byte aligned, at least arena_bytes long.  weights / inputs / outputs:
  * host arrays of device pointers, one per tensor with that role, ordered by tensor id.
- * hip_stream: a hipStream_t (NULL = the null stream).  Enqueues and returns; synchronises the
- * stream only at a Switch, whose predicate is read back to the host, and after a NonZero, whose count
- * is read back (8 bytes) so that what follows can be sized and planned.  Kernel arguments are
+ * hip_stream: a hipStream_t (NULL = the null stream).  Enqueues and returns; the host waits for the
+ * GPU only at a Switch, whose predicate it needs, and after a NonZero, whose count (8 bytes) sizes
+ * what follows: a one-thread kernel behind the producing kernel publishes the value into pinned host
+ * memory and the host polls it (after 20 ms without it the stream is synchronised instead).  Kernel arguments are
  * prepared step by step while earlier kernels already execute: when a call fails (a group the
  * kernels do not support, an arena too small for the path taken) the groups before the failing one
  * may have run and the contents of the outputs and of the arena are unspecified. */

@@ -1,5 +1,6 @@
 // Launch-table construction (views, strides, kernel versions) and sod2_run.
 #include <hip/hip_runtime.h>
+#include <chrono>
 
 #include <algorithm>
 #include <cmath>
@@ -1305,16 +1306,68 @@ using namespace sod2;
 // kernels that must be in flight for sod2_run to plan a Switch's other outcome while it waits for the predicate
 static const int SPECULATE_MIN_QUEUED = 8;
 
-// Pinned host memory that receives the few bytes read back at a Switch or after a NonZero: one slot
-// per host thread, allocated on first use and kept until the process ends.
-static void* readback_slot() {
-  static thread_local void* slot = nullptr;
-  if (!slot && hipHostMalloc(&slot, 64, hipHostMallocDefault) != hipSuccess) {
-    slot = nullptr;
-    throw Error(SOD2_ERR_HIP, "pinned host memory for read-backs could not be allocated");
-  }
-  return slot;
+// Read-back of the few bytes a run needs on the host (a Switch predicate, a NonZero count).  A one-thread
+// kernel, enqueued behind the kernel that produced them, stores the bytes and then a sequence number
+// into coherent pinned host memory; the host polls the sequence number.  Against a device-to-host copy
+// followed by a stream synchronise this leaves out the copy engine's set-up and the wake-up of a
+// blocked thread (config 4: 12 read-backs per call).  One slot per host thread, allocated on first use
+// and kept until the process ends.  If the number has not arrived after 20 ms the stream is
+// synchronised instead, so an error on the stream is reported rather than waited for.
+__global__ void publish_kernel(const unsigned char* src, int nbytes, volatile unsigned long long* host,
+                               unsigned long long seq) {
+  unsigned long long v = 0;
+  for (int i = 0; i < nbytes; ++i) v |= (unsigned long long)src[i] << (8 * i);
+  host[0] = v;
+  __threadfence_system();
+  host[1] = seq;
 }
+namespace {
+struct ReadbackSlot {
+  unsigned long long* host = nullptr;
+  unsigned long long* dev = nullptr;
+  unsigned long long seq = 0;
+};
+ReadbackSlot& readback_slot() {
+  static thread_local ReadbackSlot sl;
+  if (!sl.host) {
+    void* mem = nullptr;
+    if (hipHostMalloc(&mem, 64, hipHostMallocCoherent | hipHostMallocMapped) != hipSuccess)
+      throw Error(SOD2_ERR_HIP, "pinned host memory for read-backs could not be allocated");
+    void* dev = nullptr;
+    if (hipHostGetDevicePointer(&dev, mem, 0) != hipSuccess)
+      throw Error(SOD2_ERR_HIP, "pinned host memory for read-backs is not visible to the device");
+    std::memset(mem, 0, 64);
+    sl.host = (unsigned long long*)mem;
+    sl.dev = (unsigned long long*)dev;
+  }
+  return sl;
+}
+// enqueue the read-back of nbytes (<= 8) at src
+void begin_read_back(const void* src, int nbytes, hipStream_t s) {
+  ReadbackSlot& sl = readback_slot();
+  ++sl.seq;
+  hipLaunchKernelGGL(publish_kernel, dim3(1), dim3(1), 0, s, (const unsigned char*)src, nbytes, sl.dev, sl.seq);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("read-back launch failed: ") + hipGetErrorString(e));
+}
+// wait for it; returns the bytes, zero-extended
+unsigned long long finish_read_back(hipStream_t s) {
+  ReadbackSlot& sl = readback_slot();
+  const auto t0 = std::chrono::steady_clock::now();
+  int spins = 0;
+  while (__atomic_load_n(&sl.host[1], __ATOMIC_ACQUIRE) != sl.seq) {
+    __builtin_ia32_pause();
+    if ((++spins & 1023) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(20)) {
+      hipError_t e = hipStreamSynchronize(s);
+      if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("read-back failed: ") + hipGetErrorString(e));
+      if (__atomic_load_n(&sl.host[1], __ATOMIC_ACQUIRE) != sl.seq)
+        throw Error(SOD2_ERR_HIP, "the read-back kernel finished without reporting");
+      break;
+    }
+  }
+  return __atomic_load_n(&sl.host[0], __ATOMIC_ACQUIRE);
+}
+}  // namespace
 
 // ---------------------------------------------------------------------------------------------
 // Replay: the launch sequence of one step captured in a HIP graph; the quantities that change from
@@ -1576,14 +1629,9 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
         if (!L.empty) ++queued;
         if (L.kernel == K_NONZERO) {
           // the extent is execution determined: read the count back, then size and plan what follows
-          void* slot = P.at(L.r[2]);
-          long long* host = (long long*)readback_slot();
-          *host = -1;
-          e = hipMemcpyAsync(host, slot, 8, hipMemcpyDeviceToHost, s);
-          if (e == hipSuccess) e = hipStreamSynchronize(s);
+          begin_read_back(P.at(L.r[2]), 8, s);
+          const long long count = (long long)finish_read_back(s);
           queued = 0;
-          if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("NonZero count read failed: ") + hipGetErrorString(e));
-          const long long count = *host;
           if (count < 0 || count > L.u.nz.n) throw Error(SOD2_ERR_HIP, "NonZero kernel reported an impossible count");
           h->last_exec.push_back(count);
           if (n_nz >= exec_values.size()) {
@@ -1612,24 +1660,22 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
             Builder B(p, *cur, h->force_variant);
             Ref r = B.ref_t(op.in[1]);
             float hv = 0.f;
-            void* host = readback_slot();
             int dt = G.tensors[op.in[1]].dtype;
-            hipError_t e = hipMemcpyAsync(host, P.at(r), dt == SOD2_BF16 ? 2 : 4, hipMemcpyDeviceToHost, s);
+            begin_read_back(P.at(r), dt == SOD2_BF16 ? 2 : 4, s);
             // While the GPU still works through the kernels enqueued since the last synchronise (a layer that
             // ran: ~100 us), this thread would only wait: it plans the other outcome meanwhile, so that a
             // decision against the assumed one finds its plan ready.  With little work queued (the previous
             // layer was skipped too) the plan is computed after the decision, as before.
-            if (e == hipSuccess && queued >= SPECULATE_MIN_QUEUED) {
+            if (queued >= SPECULATE_MIN_QUEUED) {
               std::vector<int> d2 = decisions;
               d2.push_back(1);
               other = bind_plan(p, h->symbols, d2, true, exec_values);
               have_other = true;
             }
-            if (e == hipSuccess) e = hipStreamSynchronize(s);
+            const uint32_t bits = (uint32_t)finish_read_back(s);
             queued = 0;
-            if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("predicate read failed: ") + hipGetErrorString(e));
-            if (dt == SOD2_BF16) { uint32_t u = (uint32_t)(*(uint16_t*)host) << 16; std::memcpy(&hv, &u, 4); }
-            else std::memcpy(&hv, host, 4);
+            const uint32_t u = dt == SOD2_BF16 ? bits << 16 : bits;
+            std::memcpy(&hv, &u, 4);
             dec = hv > (float)op.fa ? 1 : 0;
           }
           decisions.push_back(dec);
