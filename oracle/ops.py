@@ -110,8 +110,9 @@ def resize_nearest(x, sizes):
 
 
 def topk(x, k):
-    """The k largest entries of every row (last axis), largest first, and their positions; of equal
-    entries the one at the lower position comes first."""
+    """TopK (Table 2; the operator of Fig. 3(c)): the k largest entries of every row (last axis),
+    largest first, and their positions; of equal entries the one at the lower position comes first
+    (neither the paper nor ONNX fixes that order)."""
     x = np.asarray(x)
     order = np.argsort(-x, axis=-1, kind="stable")[..., :k]
     return np.take_along_axis(x, order, axis=-1), order.astype(np.int64)

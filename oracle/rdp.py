@@ -588,6 +588,8 @@ class RDP:
         return NAC, UNDEF
 
     def _f_EyeLike(self, op):
+        """The shape of the input, ones on one diagonal (Table 2 lists it with Shape: nothing of the
+        input's values is read)."""
         s = self.S[op.inputs[0]]
         if s is UNDEF:
             return None
@@ -596,7 +598,8 @@ class RDP:
         return (NAC if s == NAC else list(s)), UNDEF
 
     def _f_OneHot(self, op):
-        """indices.shape + [depth], the depth read from the value of input 1 (last axis)."""
+        """indices.shape + [depth], the depth read from the value of input 1 (last axis): an input shape
+        and value determined output shape (Table 2)."""
         s, dv = self.S[op.inputs[0]], self.V[op.inputs[1]]
         if s is UNDEF or dv is UNDEF:
             return None
