@@ -208,7 +208,9 @@ sod2_status sod2_binding_workspace_bytes(const sod2_binding_t*, size_t* workspac
  * hip_stream: a hipStream_t (NULL = the null stream).  Enqueues and returns; the host waits for the
  * GPU only at a Switch, whose predicate it needs, and after a NonZero, whose count (8 bytes) sizes
  * what follows: a one-thread kernel behind the producing kernel publishes the value into pinned host
- * memory and the host polls it (after 20 ms without it the stream is synchronised instead).  Kernel arguments are
+ * memory and the host polls it (after 20 ms without it the stream is synchronised instead).  A run
+ * with such a wait cannot be captured in a HIP graph (it returns SOD2_ERR_HIP under capture); runs
+ * without Switch and NonZero only enqueue kernels and can be.  Kernel arguments are
  * prepared step by step while earlier kernels already execute: when a call fails (a group the
  * kernels do not support, an arena too small for the path taken) the groups before the failing one
  * may have run and the contents of the outputs and of the arena are unspecified. */
