@@ -315,3 +315,25 @@ def test_config4_gate_closed_forms(S):
         arena_exec = S.sod2_run_arena_bytes(b)[0]
         arena_all = S.sod2_binding_arena_bytes(b)[0]
         assert (arena_exec < arena_all // 20) if expect else (arena_exec == arena_all)
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_minimal_and_sub_tile_lengths(S, gated):
+    """The degenerate ends of the symbol ranges: one token, one sequence, lengths below one kernel tile
+    (a single key in the attention, a contraction with one row), with and without the skip decisions
+    (those forced to the oracle's, as in the config 4 test)."""
+    w = configs.encoder(9, 2, 768, 12, 3072, "bf16", (1, 8), (1, 70), 4, final_ln=True, gated=gated)
+    calls = [(0, {"B": 1, "L": 1}), (1, {"B": 8, "L": 1}), (2, {"B": 1, "L": 2}), (3, {"B": 3, "L": 63}),
+             (0, {"B": 2, "L": 65}), (1, {"B": 1, "L": 33})]
+    if not gated:
+        run_case(S, w, calls)
+        return
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    for ci, sym in calls:
+        print(f"case minimal gated call {ci} sym {sym}", flush=True)
+        ses, b, ins, got = _run_gated(S, w, ci, sym)
+        ref = execute.run(w.graph, po.order, ses.W, ins)
+        if [bool(d) for d in S.sod2_run_decisions(b)] != ref.decisions:
+            ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
+        assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
+        assert rel_err(got, ref.values[w.graph.outputs()[0]]) <= TOL["bf16"]
