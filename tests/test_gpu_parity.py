@@ -337,3 +337,20 @@ def test_minimal_and_sub_tile_lengths(S, gated):
             ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
         assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
         assert rel_err(got, ref.values[w.graph.outputs()[0]]) <= TOL["bf16"]
+
+
+def test_config4_full_depth(S):
+    """Config 4 as the bench runs it (12 layers, one decision per layer): executed plan and values against
+    the oracle with the oracle's decisions, on a short and a long call."""
+    w = configs.config4(3)
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    lens = sorted(c["L"] for c in w.calls)
+    for ci, sym in ((0, {"L": lens[0]}), (1, {"L": lens[-1]})):
+        print(f"case cfg4 full depth call {ci} sym {sym}", flush=True)
+        ses, b, ins, got = _run_gated(S, w, ci, sym)
+        ref = execute.run(w.graph, po.order, ses.W, ins)
+        assert len(ref.decisions) == 12
+        if [bool(d) for d in S.sod2_run_decisions(b)] != ref.decisions:
+            ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
+        assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
+        assert rel_err(got, ref.values[w.graph.outputs()[0]]) <= TOL["bf16"]
