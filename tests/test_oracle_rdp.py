@@ -249,3 +249,76 @@ def test_operator_classes_follow_table2():
     for name, cls in rows:
         assert R.OP_CLASS[name] == cls, name
         assert S.sod2_op_kind_class(name) == cls, name
+
+
+def _printed_sweeps(g):
+    """Alg. 1 taken literally: the sorted order only, a forward transfer skipped as soon as no output shape
+    is undef, a backward transfer towards a predecessor skipped as soon as that predecessor's shape is not
+    undef, Combine merged and then passed over, Switch passed over (its outputs take the data input's maps,
+    the "transit to all successors" of the listing), until a sweep changes nothing.  Uses the oracle's
+    transfer functions but none of analyse()'s control: no re-application, no meet on every visit."""
+    r = R.RDP(g)
+    r.set_model_input_shape()
+    order = r.sorted_nodes()
+    changed = True
+    while changed:
+        changed = False
+        r.sweeps += 1
+        for n in order:
+            op = g.ops[n]
+            if op.kind == "Combine":
+                changed |= r._merge(op)
+                continue
+            if op.kind == "Switch":
+                for o in op.outputs:
+                    if R.has_undef(r.S[o]):
+                        changed |= r._refine(r.S, o, r.S[op.inputs[0]])
+                        changed |= r._refine(r.V, o, r.V[op.inputs[0]])
+                if R.has_undef(r.S[op.inputs[0]]):
+                    for o in op.outputs:
+                        changed |= r._refine(r.S, op.inputs[0], r.S[o])
+                continue
+            if any(R.has_undef(r.S[o]) for o in op.outputs):           # forward_transfer's first test
+                changed |= r._forward(op, n)
+            for k, t in enumerate(op.inputs):
+                if R.has_undef(r.S[t]) or (g.tensors[t].dtype in ("i64", "i32") and R.has_undef(r.V[t])):
+                    changed |= r._backward(op, k)                       # backward_transfer's first test
+    for store in (r.S, r.V):
+        for i, x in enumerate(store):
+            if x is R.UNDEF:
+                store[i] = R.NAC
+            elif isinstance(x, list):
+                store[i] = [R.NAC if e is R.UNDEF else e for e in x]
+    return r
+
+
+def _alg1_graphs():
+    from tests.test_shape_ops import _backward_value_graph, _positions_graph, _generators_graph, _router_graph, small_fpn
+    from tests.test_compaction import small
+    dec = configs.decoder(5, layers=2, hidden=128, heads=2, ffn=256, vocab=64, p_range=(4, 12), t_max=6)
+    return {"config1": configs.config1().graph,
+            "config2": configs.config2(1, layers=2).graph,
+            "config3": configs.resnet50(3, 1, stages=(1, 1, 1, 1)).graph,
+            "config4": configs.config4(1, layers=2).graph,
+            "config5_prefill": dec.prefill, "config5_decode": dec.decode,
+            "config6": small().graph, "config7": small_fpn().graph,
+            "tiny0": _tiny_graphs()[0], "tiny1": _tiny_graphs()[1],
+            "positions": _positions_graph()[0], "generators": _generators_graph()[0],
+            "router": _router_graph()[0], "backward_value": _backward_value_graph()[0]}
+
+
+def test_printed_algorithm_reaches_the_same_fixed_point():
+    """The reading "every visit re-applies the transfer function and meets the result in" must not change
+    what Alg. 1 computes: run literally (sorted order, early returns), the listing gives the same S- and
+    V-maps on the configs and on every small graph of this suite, backward-only cases included."""
+    for name, g in _alg1_graphs().items():
+        assert R.dump(_printed_sweeps(g)) == R.dump(analyse(g)), name
+    # graphs whose input shape is recoverable only backwards
+    b2 = GraphBuilder([("I", 1, 9)])
+    x = b2.input("x", "f32", None)
+    z = b2.op("MatMul", [b2.op("Gelu", [x]), b2.weight("w", "f32", [16, 8])], transB=1)
+    b2.mark_output(z)
+    g2 = b2.build()
+    g2.tensors[z].dims = ["I", 4, 16]
+    assert R.dump(_printed_sweeps(g2)) == R.dump(analyse(g2))
+    assert R.fmt_list(_printed_sweeps(g2).S[g2.tensor_id("x")]) == "[s:I, k:4, k:8]"

@@ -81,6 +81,29 @@ def test_row_operators_closed_forms():
     xs = np.linspace(-6, 6, 49)
     assert np.allclose(O.gelu(xs), [0.5 * v * (1 + math.erf(v / math.sqrt(2))) for v in xs], atol=1e-15)
     assert np.allclose(O.sigmoid(xs) + O.sigmoid(-xs), 1)
+    # values, not only the symmetry (1 / (1 + exp(-2x)) is symmetric too): sigma(ln 3) = 3/4, sigma(-ln 3) = 1/4,
+    # sigma(ln 9) = 9/10, sigma(0) = 1/2
+    assert np.allclose(O.sigmoid(np.array([math.log(3.0), -math.log(3.0), math.log(9.0), 0.0])), [0.75, 0.25, 0.9, 0.5],
+                       rtol=0, atol=1e-15)
+
+
+def test_layernorm_epsilon_sits_inside_the_root():
+    """Rows of +-a have mean 0 and variance a^2; with eps = 3 a^2 the denominator is sqrt(a^2 + 3 a^2) = 2a, so the
+    result is +-gamma/2 + beta.  sqrt(var) + eps would give a / (a + 3 a^2), eps left out +-gamma, eps added
+    after the division something else again: each fails here."""
+    a = 0.25
+    x = np.tile(np.array([a, -a]), (3, 4))                       # [3, 8]
+    gamma = np.linspace(0.5, 2.0, 8)
+    beta = np.linspace(-1.0, 1.0, 8)
+    got = O.layernorm(x, gamma, beta, 3 * a * a)
+    ref = np.tile(np.array([0.5, -0.5]), (3, 4)) * gamma + beta
+    assert np.allclose(got, ref, rtol=0, atol=1e-15)
+    # a shifted row: the mean is removed before the variance is taken (biased, divisor n)
+    got = O.layernorm(x + 7.0, gamma, beta, 3 * a * a)
+    assert np.allclose(got, ref, rtol=0, atol=1e-12)
+    # n = 4 values 0, 0, 0, 4: mean 1, biased variance 3 (the unbiased one would be 4); eps = 1 -> root 2
+    got = O.layernorm(np.array([[0.0, 0.0, 0.0, 4.0]]), np.ones(4), np.zeros(4), 1.0)
+    assert np.allclose(got, [[-0.5, -0.5, -0.5, 1.5]], rtol=0, atol=1e-15)
 
 
 def _run(w, sym, call=0, weights=None, **kw):
