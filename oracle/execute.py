@@ -27,9 +27,13 @@ class Result:
 
 def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dict[int, np.ndarray],
         forced: Optional[Sequence[bool]] = None, round_weights=True,
-        state: Optional[Dict[str, np.ndarray]] = None) -> Result:
+        state: Optional[Dict[str, np.ndarray]] = None, exact: bool = False) -> Result:
     """``state``: contents of the session tensors (a KV cache) when the call starts, by name; a session
-    input that is missing starts with zero rows.  ``Result.state`` is what the next call starts from."""
+    input that is missing starts with zero rows.  ``Result.state`` is what the next call starts from.
+    ``exact``: operator results (and the session state) stay in float64 instead of being rounded to the
+    storage type of their tensor; weights and inputs are still what the storage holds.  This is the
+    graph's plain definition; the default (every operator result rounded, as an unfused execution
+    materialises it) differs from it by the rounding noise of the storage type."""
     g = graph
     res = Result()
     val = res.values
@@ -40,7 +44,8 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
             root[i] = t.name
             if t.name not in res.state:
                 res.state[t.name] = np.zeros([0] + [int(d) for d in t.dims[1:]])
-            val[i] = O.round_to(np.asarray(res.state[t.name], np.float64), t.dtype)
+            st = np.asarray(res.state[t.name], np.float64)
+            val[i] = st if exact else O.round_to(st, t.dtype)
         elif t.data is not None:
             val[i] = np.asarray(t.data, dtype=np.int64 if t.dtype in ("i64", "i32") else np.float64)
         elif i in weights:
@@ -145,7 +150,8 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
                 y[int(r)] = xs[2][j]
         else:
             raise ValueError(k)
-        val[op.outputs[0]] = O.round_to(np.asarray(y), g.tensors[op.outputs[0]].dtype)
+        od = g.tensors[op.outputs[0]].dtype
+        val[op.outputs[0]] = np.asarray(y, np.float64) if (exact and od in ("f32", "bf16")) else O.round_to(np.asarray(y), od)
         if k == "CacheAppend":
             root[op.outputs[0]] = root[op.inputs[0]]
             res.state[root[op.outputs[0]]] = val[op.outputs[0]]

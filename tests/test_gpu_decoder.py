@@ -18,18 +18,22 @@ def rel_err(got, ref):
     return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
 
 
-def _oracle_sequence(w, W, plans, prompt, steps):
+def _oracle_sequence(w, W, plans, prompt, steps, exact=False, feed=None):
+    """The oracle's prompt pass and decode steps.  ``feed``: the token given to decode step t (teacher
+    forcing with another run's tokens); by default the run's own greedy token.  ``exact``: the float64
+    definition without rounding of operator results to the storage type."""
     gp, gd = w.prefill, w.decode
     r = execute.run(gp, plans["prefill"].order, w.weights_for(gp, W),
-                    {gp.tensor_id("ids"): prompt, gp.tensor_id("pos"): np.arange(len(prompt))})
+                    {gp.tensor_id("ids"): prompt, gp.tensor_id("pos"): np.arange(len(prompt))}, exact=exact)
     logits = [r.values[gp.tensor_id("logits")][0]]
     toks = [int(r.values[gp.tensor_id("next")][0])]
     state = r.state
     Wd = w.weights_for(gd, W)
     for t in range(steps):
+        tok = toks[-1] if feed is None else feed[t]
         rd = execute.run(gd, plans["decode"].order, Wd,
-                         {gd.tensor_id("ids"): np.array([toks[-1]]), gd.tensor_id("pos"): np.array([len(prompt) + t])},
-                         state=state)
+                         {gd.tensor_id("ids"): np.array([tok]), gd.tensor_id("pos"): np.array([len(prompt) + t])},
+                         state=state, exact=exact)
         state = rd.state
         logits.append(rd.values[gd.tensor_id("logits")][0])
         toks.append(int(rd.values[gd.tensor_id("next")][0]))
@@ -56,6 +60,8 @@ def _run_decoder(S, w, W, seq, steps, check_structure=True):
         Pn = len(prompt)
         print(f"case {w.name} P={Pn} steps={steps}", flush=True)
         ref_logits, ref_toks, ref_state = _oracle_sequence(w, W, plans, prompt, steps)
+        # the same sequence by the plain float64 definition (no rounding of operator results), fed the same tokens
+        _, _, exact_state = _oracle_sequence(w, W, plans, prompt, steps, exact=True, feed=ref_toks)
         ses.start(Pn, w.vocab)
         if check_structure:
             assert S.sod2_binding_dump(ses.b_pre) == A.dump(A.bind(plans["prefill"], {"P": Pn}))
@@ -78,19 +84,24 @@ def _run_decoder(S, w, W, seq, steps, check_structure=True):
         # the cache in the arena's session region against the oracle's state
         bd = A.bind(plans["decode"], {"P": Pn, "t": max(steps - 1, 0)})
         rows = Pn + steps
-        errs = {}
+        errs, errs_exact, noise = {}, {}, {}
         for tid, (off, nbytes) in bd.session.items():
             name = w.decode.tensors[tid].name
             hidden = ref_state[name].shape[1]
             raw = ses.arena[off:off + rows * hidden * 2].view(torch.bfloat16).view(rows, hidden)
-            errs[name] = rel_err(to_host(raw), ref_state[name][:rows])
-        print("cache max rel err per layer:", " ".join(f"{k}={v:.1e}" for k, v in errs.items()), flush=True)
-        for name, e in errs.items():
-            # The cache rows are intermediates, not graph outputs: the bar of the outputs holds for the
-            # first layers; deeper rows carry the bf16 roundings of every block before them (the fused
-            # path rounds once per group, the oracle once per operator), so they get twice the bar.
-            layer = int(name[1:name.index(".")])
-            assert e <= (TOL if layer < 2 else 2 * TOL), (name, e)
+            got_rows = to_host(raw)
+            errs[name] = rel_err(got_rows, ref_state[name][:rows])
+            errs_exact[name] = rel_err(got_rows, exact_state[name][:rows])
+            noise[name] = rel_err(ref_state[name][:rows], exact_state[name][:rows])
+        print("cache max rel err per layer, library vs float64 definition / library vs rounded oracle / rounded oracle vs float64:",
+              " ".join(f"{k}={errs_exact[k]:.1e}/{errs[k]:.1e}/{noise[k]:.1e}" for k in errs), flush=True)
+        for name in errs:
+            # Cache rows are taps on the way, not graph outputs.  Deep layers carry the storage roundings of
+            # every block before them: the unfused oracle (one rounding per operator) is itself up to 1.8e-2
+            # away from the float64 definition at layer 23, so the distance between two correctly rounded
+            # executions can reach the sum of both.  The bar of the outputs is held against the definition,
+            # for every layer; the distance to the rounded oracle is printed above.
+            assert errs_exact[name] <= TOL, (name, errs_exact[name])
     return ses, plans
 
 

@@ -264,6 +264,23 @@ def _run_gated(S, w, ci, sym, forced=None):
 
 
 _run_gated.cache = {}
+GATE_MARGIN = 5e-3      # bf16 storage of the gate's operands moves its value by a few 1e-3 at most
+
+
+def check_free_decisions(dec, ref):
+    """The library's own Switch decisions (nothing forced) against the oracle's, in execution order.  They
+    must be equal up to the first difference, and a difference is accepted only where the oracle's gate
+    value is within GATE_MARGIN of the threshold (what follows a flipped decision sees another residual
+    stream and is not comparable).  Returns the position of the first difference, or -1."""
+    dec = [bool(d) for d in dec]
+    assert len(dec) >= 1
+    for k, (d, dr, p) in enumerate(zip(dec, ref.decisions, ref.logits)):
+        if d != dr:
+            assert abs(p - 0.5) <= GATE_MARGIN, f"decision {k}: library {d}, oracle {dr} with gate value {p}"
+            print(f"decision {k} differs from the oracle's on a gate value of {p:.5f} (within the margin)", flush=True)
+            return k
+    assert len(dec) == len(ref.decisions)
+    return -1
 
 
 def test_config4_control_flow(S):
@@ -279,10 +296,7 @@ def test_config4_control_flow(S):
         ses, b, ins, got = _run_gated(S, w, ci, sym)
         ref = execute.run(w.graph, po.order, ses.W, ins)
         dec = S.sod2_run_decisions(b)
-        assert len(dec) == len(ref.decisions)
-        for d, dr, p in zip(dec, ref.decisions, ref.logits):
-            if abs(p - 0.5) > 5e-3:
-                assert bool(d) == dr
+        check_free_decisions(dec, ref)
         seen.update(ref.decisions)
         if [bool(d) for d in dec] != ref.decisions:
             ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
@@ -333,6 +347,7 @@ def test_minimal_and_sub_tile_lengths(S, gated):
         print(f"case minimal gated call {ci} sym {sym}", flush=True)
         ses, b, ins, got = _run_gated(S, w, ci, sym)
         ref = execute.run(w.graph, po.order, ses.W, ins)
+        check_free_decisions(S.sod2_run_decisions(b), ref)
         if [bool(d) for d in S.sod2_run_decisions(b)] != ref.decisions:
             ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
         assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
@@ -340,17 +355,22 @@ def test_minimal_and_sub_tile_lengths(S, gated):
 
 
 def test_config4_full_depth(S):
-    """Config 4 as the bench runs it (12 layers, one decision per layer): executed plan and values against
-    the oracle with the oracle's decisions, on a short and a long call."""
+    """Config 4 as the bench runs it (12 layers, one decision per layer) on a short and a long call: first the
+    library's own decisions against the oracle's (equal, except on a gate value within the margin of the
+    threshold), then executed plan and values with the oracle's decisions."""
     w = configs.config4(3)
     po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
     lens = sorted(c["L"] for c in w.calls)
+    flipped = 0
     for ci, sym in ((0, {"L": lens[0]}), (1, {"L": lens[-1]})):
         print(f"case cfg4 full depth call {ci} sym {sym}", flush=True)
         ses, b, ins, got = _run_gated(S, w, ci, sym)
         ref = execute.run(w.graph, po.order, ses.W, ins)
         assert len(ref.decisions) == 12
+        print("oracle gate values:", " ".join(f"{p:.4f}" for p in ref.logits), flush=True)
+        flipped += check_free_decisions(S.sod2_run_decisions(b), ref) >= 0
         if [bool(d) for d in S.sod2_run_decisions(b)] != ref.decisions:
             ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
         assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
         assert rel_err(got, ref.values[w.graph.outputs()[0]]) <= TOL["bf16"]
+    print(f"calls whose free-running decisions left the oracle's on a near-threshold gate value: {flipped} of 2", flush=True)
