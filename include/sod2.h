@@ -45,7 +45,8 @@ enum {
   SOD2_ERR_UNSUPPORTED = -6,
   SOD2_ERR_HIP = -7,
   SOD2_ERR_BUFFER_TOO_SMALL = -8,
-  SOD2_ERR_NONCAUSAL_PLAN = -9    /* offsets used before a Switch differ from the final plan */
+  SOD2_ERR_NONCAUSAL_PLAN = -9,   /* offsets used before a Switch differ from the final plan */
+  SOD2_ERR_SCRATCH_TOO_SMALL = -10 /* sod2_run_static: a split-K contraction needs more than the static buffer */
 };
 
 enum { SOD2_F32 = 0, SOD2_BF16 = 1, SOD2_I64 = 2, SOD2_I32 = 3 };
@@ -218,6 +219,27 @@ sod2_status sod2_run(sod2_binding_t*, void* arena_dev, size_t arena_bytes,
                      const void* const* weights_dev, int32_t n_weights,
                      const void* const* inputs_dev, int32_t n_inputs,
                      void* const* outputs_dev, int32_t n_outputs, void* hip_stream);
+/* The same run for callers that cannot allocate device memory (code under HIP graph capture, serving
+ * loops and harnesses that forbid hipMalloc) and therefore cannot lengthen the arena by the split-K
+ * workspace: the fp32 partial tiles of split-K contractions go to a buffer of SOD2_STATIC_SCRATCH_BYTES
+ * that is part of the library's device image (one copy per GPU, held until the process ends).  The call
+ * allocates nothing, on the device or in pinned host memory, and creates no events.  arena_bytes is the
+ * plan's size (sod2_binding_arena_bytes); anything behind it is ignored.  Results are bit-identical to
+ * those of sod2_run with a workspace.
+ *   SOD2_ERR_SCRATCH_TOO_SMALL  a contraction of the binding splits k into so many ranges that its
+ *                               partial tiles exceed the buffer (checked for every launch before the
+ *                               first one is enqueued: nothing has run); sod2_binding_force_splits(b, 1)
+ *                               or sod2_run with a workspace avoid it
+ *   SOD2_ERR_UNSUPPORTED        the graph has Switch or NonZero operators (their read-backs need a pinned
+ *                               host slot), or profiling is on (launch records need events)
+ * All calls on one GPU share the buffer: two calls that overlap in time on the same GPU (different
+ * streams or threads) race on it; calls on one stream are ordered and safe.  Every partial tile is written
+ * before it is read within a call, so nothing is cleared between calls. */
+#define SOD2_STATIC_SCRATCH_BYTES (8u << 20)
+sod2_status sod2_run_static(sod2_binding_t*, void* arena_dev, size_t arena_bytes,
+                            const void* const* weights_dev, int32_t n_weights,
+                            const void* const* inputs_dev, int32_t n_inputs,
+                            void* const* outputs_dev, int32_t n_outputs, void* hip_stream);
 /* decisions taken by the last run, in execution order; *n receives their count */
 sod2_status sod2_run_decisions(const sod2_binding_t*, int32_t* decisions_host, int32_t cap, int32_t* n);
 /* counts found by the NonZero operators of the last run, in execution order; *n receives their number */

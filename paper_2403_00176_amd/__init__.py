@@ -35,7 +35,7 @@ EXPORTS = [
     "sod2_binding_destroy",
     "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_force_decisions", "sod2_binding_force_variant",
     "sod2_binding_force_splits", "sod2_binding_workspace_bytes",
-    "sod2_run", "sod2_run_decisions", "sod2_run_exec_values", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
+    "sod2_run", "sod2_run_static", "sod2_run_decisions", "sod2_run_exec_values", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
     "sod2_binding_launch_records", "sod2_replay_create", "sod2_replay_launch", "sod2_replay_destroy",
     "sod2_last_error", "sod2_version",
 ]
@@ -388,6 +388,19 @@ def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence
     o = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
     _check(_lib.sod2_run(b.ptr, C.c_void_p(arena_ptr), C.c_size_t(arena_bytes), w, len(weight_ptrs), i,
                          len(input_ptrs), o, len(output_ptrs), C.c_void_p(stream)))
+
+
+STATIC_SCRATCH_BYTES = 8 << 20
+
+
+def sod2_run_static(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence[int], input_ptrs: Sequence[int],
+                    output_ptrs: Sequence[int], stream: int = 0):
+    """sod2_run for callers that cannot allocate: split-K partials go to the library's static device buffer."""
+    w = weight_ptrs if isinstance(weight_ptrs, C.Array) else pointer_array(weight_ptrs)
+    i = (C.c_void_p * max(len(input_ptrs), 1))(*input_ptrs)
+    o = (C.c_void_p * max(len(output_ptrs), 1))(*output_ptrs)
+    _check(_lib.sod2_run_static(b.ptr, C.c_void_p(arena_ptr), C.c_size_t(arena_bytes), w, len(weight_ptrs), i,
+                                len(input_ptrs), o, len(output_ptrs), C.c_void_p(stream)))
 
 
 class Replay(_Handle):

@@ -1303,6 +1303,35 @@ std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force
 
 using namespace sod2;
 
+// ---------------------------------------------------------------------------------------------
+// Scratch of sod2_run_static: the fp32 partial tiles of split-K contractions, for callers that cannot
+// hand over a workspace because they cannot allocate one.  One copy per GPU, held until the process
+// ends.  In host code the array's name is only a handle: the address the kernels get comes from
+// hipGetSymbolAddress, asked once per device with that device current.
+// ---------------------------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[SOD2_STATIC_SCRATCH_BYTES];
+namespace {
+const int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];          // per device, null until the first call on that device
+bool g_scratch_known[kMaxDevices];
+
+// device address of `scratch` on the current device
+char* static_scratch() {
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices)
+    throw Error(SOD2_ERR_HIP, "current device could not be determined");
+  if (!g_scratch_known[dev]) {
+    void* ptr = nullptr;
+    hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !ptr)
+      throw Error(SOD2_ERR_HIP, std::string("address of the static scratch buffer: ") + hipGetErrorString(e));
+    g_scratch_ptr[dev] = ptr;
+    g_scratch_known[dev] = true;
+  }
+  return (char*)g_scratch_ptr[dev];
+}
+}  // namespace
+
 // kernels that must be in flight for sod2_run to plan a Switch's other outcome while it waits for the predicate
 static const int SPECULATE_MIN_QUEUED = 8;
 
@@ -1500,13 +1529,23 @@ extern "C" sod2_status sod2_replay_launch(sod2_replay_t* r, int32_t first_step, 
 }
 extern "C" void sod2_replay_destroy(sod2_replay_t* r) { delete r; }
 
-extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_bytes, const void* const* weights,
-                                int32_t n_weights, const void* const* inputs, int32_t n_inputs, void* const* outputs,
-                                int32_t n_outputs, void* stream) {
+// sod2_run and sod2_run_static.  static_ws: split-K partials go to the library's static scratch buffer,
+// and nothing may be allocated (no pinned read-back slot, no events).
+static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, const void* const* weights,
+                            int32_t n_weights, const void* const* inputs, int32_t n_inputs, void* const* outputs,
+                            int32_t n_outputs, void* stream, bool static_ws) {
   try {
     if (!h) throw Error(SOD2_ERR_INVALID_ARG, "null binding");
     const Plan& p = *h->plan;
     const Graph& G = *p.g;
+    if (static_ws) {
+      if (p.n_switches > 0 || !p.exec_ops.empty())
+        throw Error(SOD2_ERR_UNSUPPORTED, "sod2_run_static: a graph with Switch or NonZero operators reads values back through "
+                                          "pinned host memory, which this entry point may not allocate; use sod2_run");
+      if (h->profiling)
+        throw Error(SOD2_ERR_UNSUPPORTED, "sod2_run_static: launch records need events, which this entry point may not create; "
+                                          "switch profiling off or use sod2_run");
+    }
     if (n_weights != (int)G.weight_ids.size() || n_inputs != (int)G.input_ids.size() || n_outputs != (int)G.output_ids.size())
       throw Error(SOD2_ERR_INVALID_ARG, "wrong number of weight, input or output pointers");
     for (int i = 0; i < n_weights; ++i) if (!weights[i]) throw Error(SOD2_ERR_INVALID_ARG, "null weight pointer");
@@ -1524,7 +1563,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
       if (end < (size_t)WS_BYTES || end - (size_t)WS_BYTES < (size_t)((plan_bytes + 255) / 256 * 256)) return nullptr;
       return (char*)arena + end - WS_BYTES;
     };
-    P.ws = workspace_for(h->b.arena_bytes);
+    P.ws = static_ws ? static_scratch() : workspace_for(h->b.arena_bytes);
 
     // The launch table of a new binding is filled step by step as the run reaches each step, so the
     // first kernels are already executing while the later launches are still being prepared (an
@@ -1541,6 +1580,26 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
       }
       first.reset(new Builder(p, h->b, h->force_variant));
       first->force_splits = h->force_splits;
+    }
+    if (static_ws) {
+      // every launch is prepared before the first one is enqueued, so that a contraction whose partial
+      // tiles do not fit the static buffer is refused with nothing launched
+      for (size_t j = 0; j < h->b.steps.size(); ++j) {
+        const Item& it = p.items[h->b.steps[j]];
+        if (it.is_group && h->launches[j].kernel == -2) h->launches[j] = first->make(p.groups.at(it.ref));
+        const Launch& L = h->launches[j];
+        double need = 0;
+        if (L.kernel == K_GEMM && L.u.gemm.splits > 1)
+          need = 4.0 * L.u.gemm.splits * L.u.gemm.nb0 * L.u.gemm.nb1 * (double)L.u.gemm.M * L.u.gemm.N;
+        else if (L.kernel == K_CONV && L.u.conv.splits > 1)
+          need = 4.0 * L.u.conv.splits * (double)L.u.conv.NB * L.u.conv.OH * L.u.conv.OW * L.u.conv.O;
+        if (need > (double)SOD2_STATIC_SCRATCH_BYTES)
+          throw Error(SOD2_ERR_SCRATCH_TOO_SMALL, "sod2_run_static: group " + std::to_string(L.group) + " splits k into " +
+                          std::to_string(L.kernel == K_GEMM ? L.u.gemm.splits : L.u.conv.splits) + " ranges and needs " +
+                          std::to_string((long long)need) + " bytes of partial sums, the static buffer holds " +
+                          std::to_string((long long)SOD2_STATIC_SCRATCH_BYTES) +
+                          "; use sod2_run with a workspace behind the arena, or sod2_binding_force_splits(b, 1)");
+      }
     }
     h->records.clear();
     h->last_decisions.clear();
@@ -1605,7 +1664,7 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
       }
       lazy.reset(new Builder(p, replanned, h->force_variant));
       lazy->force_splits = h->force_splits;
-      P.ws = workspace_for(replanned.arena_bytes);
+      P.ws = static_ws ? static_scratch() : workspace_for(replanned.arena_bytes);
       cur = &replanned;
       launches = &relaunch;
     };
@@ -1721,4 +1780,16 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
     return SOD2_ERR_INVALID_ARG;
   }
   return SOD2_OK;
+}
+
+extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_bytes, const void* const* weights,
+                                int32_t n_weights, const void* const* inputs, int32_t n_inputs, void* const* outputs,
+                                int32_t n_outputs, void* stream) {
+  return run_impl(h, arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs, stream, false);
+}
+
+extern "C" sod2_status sod2_run_static(sod2_binding_t* h, void* arena, size_t arena_bytes, const void* const* weights,
+                                       int32_t n_weights, const void* const* inputs, int32_t n_inputs, void* const* outputs,
+                                       int32_t n_outputs, void* stream) {
+  return run_impl(h, arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs, stream, true);
 }
