@@ -258,6 +258,17 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
+  // epilogue operands that do not depend on the accumulators: this lane's 8 columns and their bias, fetched here,
+  // ahead of the main loop, by the kernels that have the registers to keep them (at most two waves per SIMD)
+  constexpr bool PRE = OCC * LW * KG / 4 <= 2;
+  constexpr int CG = EW / 8, QN = 32 * CG / 64;
+  static_assert(64 % CG == 0 && QN >= 1, "a lane keeps one column group through the epilogue");
+  const int ecg = lane % CG, er0 = lane / CG;
+  const int ecol = n0 + wn * EW + ecg * 8;
+  const bool ecol_full = g.c_vec && ecol + 8 <= g.N;
+  V16 ebv;
+  if (PRE) ebv.u = (g.bias && ecol_full) ? *(const uint4*)((const bf16_t*)g.bias + ecol) : zero4();
+
   // MFMA fragments are double buffered in registers: the LDS reads of k-step ks+1 are issued before
   // the MFMAs of k-step ks, and the ring's global loads go out between the first fragment reads and
   // the first MFMAs, so that LDS latency, address arithmetic and the matrix pipe overlap even with a
@@ -351,6 +362,74 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
   bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
   const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
   float* Wp = gridDim.z > 1 ? (float*)g.ws + ((long long)blockIdx.z * gridDim.y + blockIdx.y) * (long long)g.M * g.N : nullptr;
+  auto store_partial = [&](const float* x, int row, int col) {  // fp32 partial sums of this k range
+    float* w = Wp + (long long)row * g.N + col;
+    if ((g.N & 3) == 0 && col + 8 <= g.N) {
+      *(float4*)w = make_float4(x[0], x[1], x[2], x[3]);
+      *(float4*)(w + 4) = make_float4(x[4], x[5], x[6], x[7]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) if (col + e < g.N) w[e] = x[e];
+    }
+  };
+  if (PRE) {
+    // A lane owns the same 8 columns in every pass (EW / 8 divides 64): its bias values were fetched before the
+    // main loop, and the residual values of the next 32 rows are fetched while the current rows are converted
+    // and stored, so the epilogue pays one memory latency instead of one per pass.
+    const bool rfull = Rp && !Wp && ecol_full;                  // residual rows as 16-byte vectors
+    uint4 rv[2][QN];
+    auto res_fetch = [&](int i, int buf) {
+      const int roww = m0 + wm * TM * 32 + i * 32;
+#pragma unroll
+      for (int q = 0; q < QN; ++q) {
+        const int row = roww + er0 + q * (64 / CG);
+        rv[buf][q] = (rfull && row < g.M) ? *(const uint4*)(Rp + (long long)row * g.r_sm + ecol) : zero4();
+      }
+    };
+    if (rfull) res_fetch(0, 0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+#pragma unroll
+      for (int j = 0; j < TN; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+          patch[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * ELD + j * 32 + (lane & 31)] = acc[i][j][r];
+      if (rfull && i + 1 < TM) res_fetch(i + 1, (i + 1) & 1);
+      const int roww = m0 + wm * TM * 32 + i * 32;
+#pragma unroll
+      for (int q = 0; q < QN; ++q) {
+        const int rr = er0 + q * (64 / CG);
+        const int row = roww + rr;
+        if (row >= g.M || ecol >= g.N) continue;
+        float x[8];
+        {
+          const float4 p0 = *(const float4*)&patch[rr * ELD + ecg * 8], p1 = *(const float4*)&patch[rr * ELD + ecg * 8 + 4];
+          x[0] = p0.x; x[1] = p0.y; x[2] = p0.z; x[3] = p0.w; x[4] = p1.x; x[5] = p1.y; x[6] = p1.z; x[7] = p1.w;
+        }
+        if (Wp) {
+          store_partial(x, row, ecol);
+        } else if (ecol_full) {                                 // whole 16-byte vectors: the operands fetched ahead
+#pragma unroll
+          for (int e = 0; e < 8; ++e) x[e] = x[e] * g.scale + bf2f(ebv.h[e]);
+          act8(x, g.act1);
+          if (Rp) {
+            V16 r8; r8.u = rv[i & 1][q];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] += bf2f(r8.h[e]);
+            act8(x, g.act2);
+          }
+          V16 o;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) o.h[e] = f2bf(x[e]);
+          *(uint4*)(Cp + (long long)row * g.c_sm + ecol) = o.u;
+        } else {
+          epilogue8(x, g, Cp, Rp, row, ecol);
+        }
+      }
+    }
+    return;
+  }
+  // kernels that run four or more waves per SIMD have no registers to fetch ahead: operands are read pass by pass
   const int colw = n0 + wn * EW;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
@@ -371,18 +450,8 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
         const float4 p0 = *(const float4*)&patch[rr * ELD + cc], p1 = *(const float4*)&patch[rr * ELD + cc + 4];
         x[0] = p0.x; x[1] = p0.y; x[2] = p0.z; x[3] = p0.w; x[4] = p1.x; x[5] = p1.y; x[6] = p1.z; x[7] = p1.w;
       }
-      if (Wp) {                                                 // fp32 partial sums of this k range
-        float* w = Wp + (long long)row * g.N + col;
-        if ((g.N & 3) == 0 && col + 8 <= g.N) {
-          *(float4*)w = make_float4(x[0], x[1], x[2], x[3]);
-          *(float4*)(w + 4) = make_float4(x[4], x[5], x[6], x[7]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) if (col + e < g.N) w[e] = x[e];
-        }
-      } else {
-        epilogue8(x, g, Cp, Rp, row, col);
-      }
+      if (Wp) store_partial(x, row, col);
+      else epilogue8(x, g, Cp, Rp, row, col);
     }
   }
 }

@@ -7,7 +7,7 @@ the near-best candidates."""
 import numpy as np
 import pytest
 
-from oracle import rdp as R, plan as P, arena as A, execute
+from oracle import rdp as R, plan as P, arena as A, execute, ops as O
 from workloads import configs
 
 pytestmark = pytest.mark.gpu
@@ -23,17 +23,20 @@ def _oracle_sequence(w, W, plans, prompt, steps, exact=False, feed=None):
     forcing with another run's tokens); by default the run's own greedy token.  ``exact``: the float64
     definition without rounding of operator results to the storage type."""
     gp, gd = w.prefill, w.decode
-    r = execute.run(gp, plans["prefill"].order, w.weights_for(gp, W),
-                    {gp.tensor_id("ids"): prompt, gp.tensor_id("pos"): np.arange(len(prompt))}, exact=exact)
+    # weights rounded to their storage type once, not once per step
+    Wr = {n: O.round_to(np.asarray(v, np.float64), w.dtype) for n, v in W.items()}
+    r = execute.run(gp, plans["prefill"].order, w.weights_for(gp, Wr),
+                    {gp.tensor_id("ids"): prompt, gp.tensor_id("pos"): np.arange(len(prompt))}, exact=exact,
+                    round_weights=False)
     logits = [r.values[gp.tensor_id("logits")][0]]
     toks = [int(r.values[gp.tensor_id("next")][0])]
     state = r.state
-    Wd = w.weights_for(gd, W)
+    Wd = w.weights_for(gd, Wr)
     for t in range(steps):
         tok = toks[-1] if feed is None else feed[t]
         rd = execute.run(gd, plans["decode"].order, Wd,
                          {gd.tensor_id("ids"): np.array([tok]), gd.tensor_id("pos"): np.array([len(prompt) + t])},
-                         state=state, exact=exact)
+                         state=state, exact=exact, round_weights=False)
         state = rd.state
         logits.append(rd.values[gd.tensor_id("logits")][0])
         toks.append(int(rd.values[gd.tensor_id("next")][0]))
@@ -49,7 +52,7 @@ def _check_token(row_ref, tok_gpu, tok_ref):
         assert row_ref[tok_gpu] >= top[1] - 2 * TOL * scale
 
 
-def _run_decoder(S, w, W, seq, steps, check_structure=True):
+def _run_decoder(S, w, W, seq, steps, check_structure=True, exact_taps=True):
     import torch
     from paper_2403_00176_amd.session import DecoderSession, to_host
     plans = {n: P.build_plan(g, R.RDP(g).analyse()) for n, g in (("prefill", w.prefill), ("decode", w.decode))}
@@ -61,7 +64,7 @@ def _run_decoder(S, w, W, seq, steps, check_structure=True):
         print(f"case {w.name} P={Pn} steps={steps}", flush=True)
         ref_logits, ref_toks, ref_state = _oracle_sequence(w, W, plans, prompt, steps)
         # the same sequence by the plain float64 definition (no rounding of operator results), fed the same tokens
-        _, _, exact_state = _oracle_sequence(w, W, plans, prompt, steps, exact=True, feed=ref_toks)
+        exact_state = _oracle_sequence(w, W, plans, prompt, steps, exact=True, feed=ref_toks)[2] if exact_taps else ref_state
         ses.start(Pn, w.vocab)
         if check_structure:
             assert S.sod2_binding_dump(ses.b_pre) == A.dump(A.bind(plans["prefill"], {"P": Pn}))
@@ -139,6 +142,25 @@ def test_config5_full_depth(S_lib):
     W = w.make_weights_by_name()
     i = int(np.argmin(w.prompts))
     _run_decoder(S_lib, w, W, [w.make_prompt(i)], steps=3)
+
+
+def test_longest_prompt_and_last_decode_steps(S_lib):
+    """Config 5's widths on 2 layers with the longest prompt the config allows (P = 512: several query tiles in
+    the prompt pass) and all 256 teacher-forced decode steps, so that the last steps run against cache lengths
+    762 .. 767; every step's logits are compared, and the cache rows at the end."""
+    w = configs.decoder(layers=2, n_prompts=4)
+    W = w.make_weights_by_name()
+    prompt = np.concatenate([w.make_prompt(i) for i in range(4)])
+    assert len(prompt) >= 512
+    _run_decoder(S_lib, w, W, [prompt[:512]], steps=256, check_structure=False, exact_taps=False)
+
+
+def test_config5_full_depth_mid_prompt(S_lib):
+    """All 24 layers with a prompt of mid length (P ~ 300) and two decode steps."""
+    w = configs.config5()
+    W = w.make_weights_by_name()
+    i = int(np.argsort(w.prompts)[len(w.prompts) // 2])
+    _run_decoder(S_lib, w, W, [w.make_prompt(i)], steps=2)
 
 
 def test_free_running_generation_is_deterministic(S_lib):

@@ -1,0 +1,76 @@
+"""The configurations at the sizes and depths the benchmark runs them, against the oracle: the largest call
+of config 2 through all 12 layers, config 3 at 640 x 640 and at an odd size through the full [3, 4, 6, 3]
+stack, config 5 with the longest prompt and the last decode steps (cache lengths 762 .. 767) and at full
+depth with a mid-length prompt.  The tapped variants of the encoder and the CNN expose the residual stream
+after every layer / the feature map after every stage as further graph outputs (same operators, weights and
+values), so a difference is located; every tap is held to the same bar as the final output.
+
+Tolerance: max |library - oracle| / max |oracle| <= 2e-2 per tensor (bf16 storage, fp32 accumulation)."""
+import numpy as np
+import pytest
+
+from oracle import rdp as R, plan as P, arena as A, execute, ops as O
+from workloads import configs
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-2
+
+
+def rel_err(got, ref):
+    return float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-30))
+
+
+def _run_against_oracle(S, w, ci, sym, taps_of=None):
+    """Runs call ci of workload w (and, when given, of its tapped twin) on the GPU; one oracle run serves both:
+    the twin has the same tensors, it only marks more of them as outputs."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    W = w.make_weights()
+    Wr = {t: O.round_to(np.asarray(v, np.float64), w.graph.tensors[t].dtype) for t, v in W.items()}
+    ins = w.make_inputs(ci, sym)
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    ref = execute.run(w.graph, po.order, Wr, ins, round_weights=False)
+    out = {}
+    for name, wl in (("plain", w), ("tapped", taps_of)):
+        if wl is None:
+            continue
+        pl = po if wl is w else P.build_plan(wl.graph, R.RDP(wl.graph).analyse())
+        ses = Session(wl.graph)
+        ses.upload_weights(W)
+        b = ses.bind(sym)
+        assert S.sod2_binding_dump(b) == A.dump(A.bind(pl, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        errs = []
+        for t, o in zip(wl.graph.outputs(), outs):
+            got = to_host(o)
+            assert got.shape == ref.values[t].shape and np.isfinite(got).all()
+            errs.append(rel_err(got, ref.values[t]))
+        print(f"{w.name} {name} {sym}: max rel err per output " + " ".join(f"{e:.1e}" for e in errs), flush=True)
+        out[name] = errs
+        del ses
+        torch.cuda.empty_cache()
+    for name, errs in out.items():
+        for k, e in enumerate(errs):
+            assert e <= TOL, (w.name, name, sym, k, e)
+    return out
+
+
+def test_config2_largest_call_all_layers(S_lib):
+    """The call of the benchmark's draw list with the most tokens (B x L ~ 4000), 12 layers: the graph the bench
+    times, then its tapped twin (residual stream after every layer)."""
+    w = configs.config2(64)
+    ci = max(range(len(w.calls)), key=lambda i: w.calls[i]["B"] * w.calls[i]["L"])
+    assert w.calls[ci]["B"] * w.calls[ci]["L"] >= 3500
+    out = _run_against_oracle(S_lib, w, ci, w.calls[ci], taps_of=configs.config2(64, taps=True))
+    assert len(out["tapped"]) == 13
+
+
+@pytest.mark.parametrize("sym", [{"H": 640, "W": 640}, {"H": 417, "W": 231}])
+def test_config3_largest_and_odd_size_full_stack(S_lib, sym):
+    """ResNet-50 layout, stages [3, 4, 6, 3]: 640 x 640 (the first stage contracts 25 600 rows) and a size that is
+    no multiple of 32 and not square (every floor in the shape expressions rounds); feature maps after every stage."""
+    w = configs.config3()
+    out = _run_against_oracle(S_lib, w, 0, sym, taps_of=configs.resnet50(3, 32, taps=True))
+    assert len(out["tapped"]) == 5

@@ -120,13 +120,15 @@ def _draws(seed, spec, n_calls):
 
 def encoder(config: int, layers: int, hidden: int, heads: int, ffn: int, dtype: str,
             batch, seq_range, n_calls: int, final_ln: bool, gated=False,
-            gate_bias: float = None) -> Workload:
+            gate_bias: float = None, taps: bool = False) -> Workload:
     """Configs 1, 2, 4 and 6: a stack of pre-LN encoder blocks on x[B, L, hidden].
 
     ``gated=True``: one skip decision per layer and call (<Switch, Combine>, config 4).
     ``gated="sample"``: one decision per layer and *sequence*; the sequences that run the layer are
     compacted with NonZero + Gather (an execution-determined batch size), the block runs on the
-    compacted batch, ScatterRows writes its rows back (config 6)."""
+    compacted batch, ScatterRows writes its rows back (config 6).
+    ``taps=True``: the residual stream after every layer is a graph output as well (same operators, same
+    weights, same values; a test can then say in which layer a difference starts)."""
     syms = [("L", seq_range[0], seq_range[1])]
     if isinstance(batch, tuple):
         syms = [("B", batch[0], batch[1])] + syms
@@ -171,6 +173,8 @@ def encoder(config: int, layers: int, hidden: int, heads: int, ffn: int, dtype: 
             x = b.op("Combine", [y, skip], hint=f"cmb{l}")
         else:
             x = _encoder_layer(b, w, x, hidden, heads, ffn, f"l{l}", dtype, lead)
+        if taps:
+            b.mark_output(x)
     if final_ln:
         x = _layernorm(b, w, x, hidden, "lnf", dtype)
     b.mark_output(x, "y")
@@ -190,8 +194,8 @@ def config1(n_calls=8):
     return encoder(1, 1, 256, 4, 1024, "f32", 1, (16, 128), n_calls, final_ln=False)
 
 
-def config2(n_calls=64, layers=12):
-    return encoder(2, layers, 768, 12, 3072, "bf16", (1, 8), (32, 512), n_calls, final_ln=True)
+def config2(n_calls=64, layers=12, taps=False):
+    return encoder(2, layers, 768, 12, 3072, "bf16", (1, 8), (32, 512), n_calls, final_ln=True, taps=taps)
 
 
 def config4(n_calls=64, layers=12, gate_bias=None):
@@ -229,7 +233,8 @@ def _bottleneck(b, w, x, cin, mid, cout, stride, project, name, dtype):
 
 
 def resnet50(config=3, n_calls=32, sizes=tuple(range(224, 641, 32)), stages=(3, 4, 6, 3),
-             classes=1000, dtype="bf16") -> Workload:
+             classes=1000, dtype="bf16", taps=False) -> Workload:
+    """``taps=True``: the feature map after every stage is a graph output as well (same operators and values)."""
     b = GraphBuilder([("H", min(sizes), max(sizes)), ("W", min(sizes), max(sizes))])
     w = _Weights(config)
     x = b.input("x", dtype, [1, "H", "W", 3])
@@ -242,6 +247,8 @@ def resnet50(config=3, n_calls=32, sizes=tuple(range(224, 641, 32)), stages=(3, 
             stride = 2 if (i == 0 and s > 0) else 1
             y = _bottleneck(b, w, y, cin, mid, cout, stride, i == 0, f"s{s}b{i}", dtype)
             cin = cout
+        if taps:
+            b.mark_output(y)
     y = b.op("ReduceMean", [y], axes=(1, 2), keepdims=0, hint="gap")
     y = _linear(b, w, y, cin, classes, "fc", dtype)
     b.mark_output(y, "logits")
