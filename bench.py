@@ -167,7 +167,7 @@ def main():
     ap.add_argument("--steps", type=int, default=64)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2)
-    ap.add_argument("--cpu-seconds", type=float, default=12.0, help="budget of the oracle timing leg (0 = skip)")
+    ap.add_argument("--cpu-seconds", type=float, default=25.0, help="budget of the oracle timing leg (0 = skip)")
     ap.add_argument("--ablation", action="store_true",
                     help="optimisation breakdown: the same calls with fusion, execution planning, memory planning and "
                          "kernel versions switched on one after the other")
@@ -280,39 +280,56 @@ def main():
     # reported as event_overhead_us and in the *_net_of_event_overhead figures, for information only)
     # sub-graph classes of the plan (all-constant shapes / symbolic-and-constant / execution-determined):
     # their share of the sub-graphs and of the kernel time, the two panels of the paper's Fig. 8
-    sg_of_group, sg_count, sg_ms = {}, {}, {}
-    for line in S.sod2_plan_dump(ses.plan).splitlines():
-        f = line.split()
-        if f and f[0].startswith("sg") and f[0][2:].isdigit():
-            sg_count[f[1]] = sg_count.get(f[1], 0) + 1
-            for name in f[2:]:
-                if name[0] == "g":
-                    sg_of_group[int(name[1:])] = f[1]
+    sg_of_group, sg_count, sg_ms, seen_sg, versions = {}, {}, {}, set(), {}
+    for gi in range(S.sod2_plan_counts(ses.plan)[0]):
+        gr = S.sod2_plan_query_group(ses.plan, gi)
+        sg_of_group[gr["gid"]] = gr["sg_class"]
+        if gr["subgraph"] not in seen_sg:
+            seen_sg.add(gr["subgraph"])
+            sg_count[gr["sg_class"]] = sg_count.get(gr["sg_class"], 0) + 1
+        if gr["kind"] == "ELTWISE":
+            versions[gr["versions"]] = versions.get(gr["versions"], 0) + 1
     per = {}
     tokens = 0
     empty_ms = []
     t_roof_ms = 0.0          # per launch max(flops / MFMA peak, bytes / HBM peak), summed over the timed calls
+    # which roofline binds a launch: the matrix cores when 2MNK / peak >= algorithmic bytes / HBM peak, else HBM
+    # (a contraction against a [K, N] weight is weight-bandwidth bound below ~300 rows); per class the summed
+    # algorithmic work over the summed event durations, against that class's own peak
+    cls = {}
+    big = sorted((c[1].get("B", 1) * c[1].get("L", c[1].get("H", 1)) for c in timed))[(3 * len(timed)) // 4]
+    chains_big = {}          # memory-bound chains on the largest quarter of the calls (bandwidth-bound sizes)
     for ci, sym, ins, outs in timed:
         b = ses.bind(sym)
         S.sod2_binding_set_profiling(b, True)
         ses.run(b, ins, outs)
         stream.synchronize()
-        tokens += sym.get("B", 1) * sym.get("L", sym.get("H", 1))
+        n_tok = sym.get("B", 1) * sym.get("L", sym.get("H", 1))
+        tokens += n_tok
         recs = S.sod2_binding_launch_records(b)
         base = max(2 * recs[0]["ms"] - recs[1]["ms"], 0.0) if len(recs) > 1 and recs[1]["group"] == -2 else 0.0
         empty_ms.append(base)
         for r in recs:
             if r["group"] < 0:
                 continue
-            cls = sg_of_group.get(r["group"], "known")
-            sg_ms[cls] = sg_ms.get(cls, 0.0) + r["ms"]
+            c_ = sg_of_group.get(r["group"], "known")
+            sg_ms[c_] = sg_ms.get(c_, 0.0) + r["ms"]
             k = per.setdefault(r["kernel"], dict(launches=0, ms=0.0, flops=0.0, bytes=0.0, raw_ms=0.0))
             k["launches"] += 1
             k["ms"] += r["ms"]
             k["raw_ms"] += max(r["ms"] - base, 1e-4)
             k["flops"] += r["flops"]
             k["bytes"] += r["bytes"]
-            t_roof_ms += max(r["flops"] / (PEAK_BF16_TFLOPS * 1e12), r["bytes"] / (PEAK_HBM_GBS * 1e9)) * 1e3
+            t_mfma, t_hbm = r["flops"] / (PEAK_BF16_TFLOPS * 1e12), r["bytes"] / (PEAK_HBM_GBS * 1e9)
+            t_roof_ms += max(t_mfma, t_hbm) * 1e3
+            fam = "contraction" if r["kernel"] in ("gemm", "conv") else r["kernel"]
+            name = f"{fam}:{'mfma' if t_mfma >= t_hbm else 'hbm'}"
+            q = cls.setdefault(name, dict(launches=0, ms=0.0, raw_ms=0.0, flops=0.0, bytes=0.0))
+            q["launches"] += 1; q["ms"] += r["ms"]; q["raw_ms"] += max(r["ms"] - base, 1e-4)
+            q["flops"] += r["flops"]; q["bytes"] += r["bytes"]
+            if n_tok >= big and fam not in ("contraction", "attention"):
+                q = chains_big.setdefault(fam, dict(launches=0, ms=0.0, raw_ms=0.0, bytes=0.0))
+                q["launches"] += 1; q["ms"] += r["ms"]; q["raw_ms"] += max(r["ms"] - base, 1e-4); q["bytes"] += r["bytes"]
     kernels = {}
     for name, k in per.items():
         kernels[name] = dict(launches=k["launches"], total_ms=round(k["ms"], 3),
@@ -320,6 +337,28 @@ def main():
                              avg_us_net_of_event_overhead=round(1e3 * k["raw_ms"] / k["launches"], 2),
                              tflops=round(k["flops"] / (k["ms"] * 1e-3) / 1e12, 2) if k["ms"] else 0.0,
                              gbs=round(k["bytes"] / (k["ms"] * 1e-3) / 1e9, 1) if k["ms"] else 0.0)
+    roofline_by_class = {}
+    for name, q in sorted(cls.items()):
+        bound = name.split(":")[1]
+        if bound == "mfma":
+            a = q["flops"] / (q["ms"] * 1e-3) / 1e12
+            a_net = q["flops"] / (q["raw_ms"] * 1e-3) / 1e12
+            roofline_by_class[name] = dict(bound="mfma", launches=q["launches"], avg_us=round(1e3 * q["ms"] / q["launches"], 2),
+                                           achieved=round(a, 1), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s", frac=round(a / PEAK_BF16_TFLOPS, 4),
+                                           frac_net_of_event_overhead=round(a_net / PEAK_BF16_TFLOPS, 4))
+        else:
+            a = q["bytes"] / (q["ms"] * 1e-3) / 1e9
+            a_net = q["bytes"] / (q["raw_ms"] * 1e-3) / 1e9
+            roofline_by_class[name] = dict(bound="hbm", launches=q["launches"], avg_us=round(1e3 * q["ms"] / q["launches"], 2),
+                                           achieved=round(a, 1), peak=PEAK_HBM_GBS, unit="GB/s", frac=round(a / PEAK_HBM_GBS, 4),
+                                           frac_net_of_event_overhead=round(a_net / PEAK_HBM_GBS, 4))
+    chains_on_largest_calls = {
+        fam: dict(launches=q["launches"], avg_us=round(1e3 * q["ms"] / q["launches"], 2),
+                  mb_per_launch=round(q["bytes"] / q["launches"] / 1e6, 3),
+                  achieved_gbs=round(q["bytes"] / (q["ms"] * 1e-3) / 1e9, 1),
+                  frac_of_hbm=round(q["bytes"] / (q["ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                  frac_of_hbm_net_of_event_overhead=round(q["bytes"] / (q["raw_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS, 4))
+        for fam, q in sorted(chains_big.items())}
     n_sg, all_ms = max(sum(sg_count.values()), 1), max(sum(sg_ms.values()), 1e-9)
     subgraph_classes = {c: dict(subgraphs=sg_count.get(c, 0), share=round(sg_count.get(c, 0) / n_sg, 3),
                                 kernel_time_share=round(sg_ms.get(c, 0.0) / all_ms, 3))
@@ -327,17 +366,21 @@ def main():
     dom = max(per, key=lambda n: per[n]["ms"])
     d = per[dom]
     traffic = measured_traffic(dom) if args.config == 2 else None
+    traffic_source = ("profiles/config2_fetch_size.txt + profiles/config2_write_size.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
+                      "this command, committed summaries (counters cannot be read inside the run)") if traffic is not None else None
     if dom in ("gemm", "conv"):
         achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
-                        frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic,
+                        frac=round(achieved / PEAK_BF16_TFLOPS, 4), traffic=traffic, traffic_source=traffic_source,
                         algorithmic_bytes_per_launch=d["bytes"] / d["launches"],
                         avg_launch_us=round(1e3 * d["ms"] / d["launches"], 2),
-                        flops_per_launch=d["flops"] / d["launches"])
+                        flops_per_launch=d["flops"] / d["launches"],
+                        note="all contraction launches against the MFMA peak, the weight-bandwidth-bound ones included; "
+                             "roofline_by_class separates them")
     else:
         achieved = d["bytes"] / (d["ms"] * 1e-3) / 1e9
         roofline = dict(bound="hbm", kernel=dom, achieved=round(achieved, 1), peak=PEAK_HBM_GBS, unit="GB/s",
-                        frac=round(achieved / PEAK_HBM_GBS, 4), traffic=traffic,
+                        frac=round(achieved / PEAK_HBM_GBS, 4), traffic=traffic, traffic_source=traffic_source,
                         avg_launch_us=round(1e3 * d["ms"] / d["launches"], 2),
                         bytes_per_launch=d["bytes"] / d["launches"])
 
@@ -352,9 +395,16 @@ def main():
             cores = os.cpu_count() or 1
         ro = R.RDP(w.graph).analyse()
         po = P.build_plan(w.graph, ro)
-        sample = sorted(timed, key=lambda c: c[1].get("B", 1) * c[1].get("L", 1))
-        spent, times, gpu_same, desc = 0.0, [], [], []
-        for ci, sym, ins, outs in sample:
+        # a stratified sample of the timed calls: median size first, then the quartiles, the octiles, ... until the
+        # time budget is used up (the largest calls alone would take minutes), so the sample keeps the size mix
+        by_size = sorted(timed, key=lambda c: c[1].get("B", 1) * c[1].get("L", c[1].get("H", 1)))
+        order_, seen_, frac_ = [], set(), [0.5, 0.25, 0.75, 0.125, 0.375, 0.625, 0.875] + [(2 * i + 1) / 32 for i in range(16)]
+        for f in frac_:
+            i = min(int(f * len(by_size)), len(by_size) - 1)
+            if i not in seen_:
+                seen_.add(i); order_.append(by_size[i])
+        spent, times, gpu_same, desc, toks = 0.0, [], [], [], 0
+        for ci, sym, ins, outs in order_:
             if spent >= args.cpu_seconds:
                 break
             host_in = w.make_inputs(ci, sym)
@@ -365,8 +415,11 @@ def main():
             times.append(dt * 1e3)
             gpu_same.append(lat[[c[0] for c in timed].index(ci)])
             desc.append("x".join(str(v) for v in sym.values()))
+            toks += sym.get("B", 1) * sym.get("L", sym.get("H", 1))
         cpu = dict(value=round(sum(times) / len(times), 2), unit="ms", cores=int(cores), kind="oracle",
-                   sample=f"{len(times)} smallest of the timed calls (B x L = {', '.join(desc)}), float64 numpy, unfused",
+                   sample=f"{len(times)} of the {len(timed)} timed calls, drawn at the median, quartiles, octiles, ... of the call "
+                          f"sizes until {args.cpu_seconds:.0f} s of CPU time were used (symbol values {', '.join(desc)}; "
+                          f"{toks} tokens / pixels rows against {tokens} in all timed calls); float64 numpy, unfused",
                    gpu_ms_same_calls=round(sum(gpu_same) / len(gpu_same), 3))
 
     out = {
@@ -401,11 +454,17 @@ def main():
         "compile_once_ms": round(compile_ms, 2),
         "peak_arena_mb": {"min": round(min(arena_mb), 3), "max": round(max(arena_mb), 3),
                           "mean": round(sum(arena_mb) / len(arena_mb), 3)},
+        # device memory the session holds beyond weights, inputs and outputs: the largest planned arena plus the
+        # optional split-K workspace behind it (not part of the plan, not in peak_arena_mb)
+        "workspace_mb": round(ses.workspace_bytes / 2 ** 20, 3),
+        "arena_allocation_mb": round(ses.arena.numel() / 2 ** 20, 3),
         "weight_mb": round(weight_bytes / 2 ** 20, 1),
         **({"kept_fraction": round(sum(sum(k) for k in kept) / max(sum(len(k) * c[1]["B"] for k, c in zip(kept, timed)), 1), 3)}
            if any(kept) else {}),
         "tokens_per_s": round(tokens / total_s, 1),
         "roofline": roofline,
+        "roofline_by_class": roofline_by_class,
+        "chains_on_largest_calls": chains_on_largest_calls,
         # whole call against the roofline: what the launches of a call would take at the peak that binds each
         # of them, over the measured latency of the call (launch gaps, planning and the synchronise included)
         "call_roofline": {"t_roof_ms_per_call": round(t_roof_ms / len(timed), 4),

@@ -119,7 +119,7 @@ typedef struct {
   int32_t fusion;  /* RDP-enabled fusion; 0: one group per operator                       */
   int32_t sep;     /* static execution planning; 0: node order                            */
   int32_t dmp;     /* peak-first arena plan; 0: best-fit greedy in execution order        */
-  int32_t mvc;     /* multi-version kernels; 0: always the regular version                */
+  int32_t mvc;     /* multi-version kernels; 0: one version (128 x 128 x 64 tile) for every shape  */
   int32_t inplace; /* a group's result may take over the storage of an operand that dies there */
 } sod2_plan_opts;
 
@@ -160,6 +160,26 @@ sod2_status sod2_plan(const sod2_graph_t*, const sod2_rdp_t*, const sod2_plan_op
 void sod2_plan_destroy(sod2_plan_t*);
 sod2_status sod2_plan_counts(const sod2_plan_t*, int32_t* n_groups, int32_t* n_subgraphs, int32_t* n_switches);
 sod2_status sod2_plan_dump(const sod2_plan_t*, char* buf_host, size_t cap, size_t* needed);
+/* The plan as records (the text dump stays the canonical form for byte comparison).  Groups are numbered
+ * 0 .. n_groups-1 in planned execution order (sub-graph by sub-graph, Section 4.3).  ops_host / ins_host receive up
+ * to the given capacities of the member operators (Section 4.2: the operators fused into one kernel) and of the
+ * tensors the group reads from outside itself; info->n_ops / n_ins always hold the full counts. */
+enum { SOD2_G_GEMM = 0, SOD2_G_CONV, SOD2_G_LAYERNORM, SOD2_G_SOFTMAX, SOD2_G_MAXPOOL, SOD2_G_REDUCEMEAN, SOD2_G_ARGMAX,
+       SOD2_G_CACHEAPPEND, SOD2_G_NONZERO, SOD2_G_GATHER, SOD2_G_ELTWISE, SOD2_G_ATTENTION, SOD2_G_SCATTER, SOD2_G_RESIZE,
+       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK };
+typedef struct {
+  int32_t gid;        /* group id: the smallest operator id in the group */
+  int32_t kind;       /* SOD2_G_* */
+  int32_t out;        /* tensor the group writes */
+  int32_t out2;       /* second result (TopK: the positions), or -1 */
+  int32_t n_ops, n_ins;
+  int32_t subgraph;   /* sub-graph the group is planned in */
+  int32_t sg_class;   /* of that sub-graph: 0 every shape constant, 1 symbolic and constant, 2 execution determined (Fig. 8) */
+  int32_t inplace_of; /* tensor whose storage the result takes over, or -1 */
+  int32_t versions;   /* code versions of the fused loop nest (Fig. 4): 1 when every broadcast pair is proven */
+} sod2_group_info;
+sod2_status sod2_plan_query_group(const sod2_plan_t*, int32_t index, sod2_group_info* info_host,
+                                  int32_t* ops_host, int32_t ops_cap, int32_t* ins_host, int32_t ins_cap);
 
 /* -- bind (Section 4.4.1) ------------------------------------------------------------------- */
 /* symbol_values_host: one value per declared symbol, in declaration order.  For graphs with
@@ -189,6 +209,19 @@ void sod2_binding_destroy(sod2_binding_t*);
 /* bytes the arena passed to sod2_run must have; peak of summed live tensor bytes */
 sod2_status sod2_binding_arena_bytes(const sod2_binding_t*, size_t* arena_bytes, size_t* peak_live_bytes);
 sod2_status sod2_binding_dump(const sod2_binding_t*, char* buf_host, size_t cap, size_t* needed);
+/* One tensor of the bound plan (Section 4.4.1: sizes, lifetimes and offsets exist once the symbols are bound).
+ * executed = 0: no executed group writes it in this binding (a skipped branch, a folded or fused-away tensor): the
+ * other fields are then unset.  where: 0 planned in the arena (offset, bytes, life valid), 1 a session slot at the
+ * arena's bottom (offset, bytes valid), 2 the storage of another tensor taken over in place (base = that tensor),
+ * 3 caller memory (a graph output).  sod2_run_query_tensor answers for the plan the last run executed. */
+typedef struct {
+  int32_t executed, where, base, rank;
+  int64_t dims[SOD2_MAX_RANK];
+  int64_t offset, bytes;
+  int32_t life_start, life_end;   /* first and last executed step that needs the storage */
+} sod2_tensor_info;
+sod2_status sod2_binding_query_tensor(const sod2_binding_t*, int32_t tensor, sod2_tensor_info* info_host);
+sod2_status sod2_run_query_tensor(const sod2_binding_t*, int32_t tensor, sod2_tensor_info* info_host);
 /* force the decisions of the next runs (replay of a reference decision vector); n = 0 clears */
 sod2_status sod2_binding_force_decisions(sod2_binding_t*, const int32_t* decisions_host, int32_t n);
 /* force one kernel version for every contraction: -1 automatic, 0 regular, 1 fat, 2 skinny,
@@ -206,7 +239,10 @@ sod2_status sod2_binding_workspace_bytes(const sod2_binding_t*, size_t* workspac
 /* -- run -------------------------------------------------------------------------------------- */
 /* arena: device memory, 256-byte aligned, at least arena_bytes long.  weights / inputs / outputs:
  * host arrays of device pointers, one per tensor with that role, ordered by tensor id.
- * hip_stream: a hipStream_t (NULL = the null stream).  Enqueues and returns; the host waits for the
+ * hip_stream: a hipStream_t (NULL = the null stream).  The first run of a graph with Switch or NonZero operators on
+ * a host thread allocates one 64-byte slot of pinned, device-visible host memory (hipHostMalloc) for the read-backs;
+ * it is kept until the process ends.  Nothing else is allocated by a run (launch records: events, created when
+ * profiling is switched on).  Enqueues and returns; the host waits for the
  * GPU only at a Switch, whose predicate it needs, and after a NonZero, whose count (8 bytes) sizes
  * what follows: a one-thread kernel behind the producing kernel publishes the value into pinned host
  * memory and the host polls it (after 20 ms without it the stream is synchronised instead).  A run
@@ -244,6 +280,18 @@ sod2_status sod2_run_static(sod2_binding_t*, void* arena_dev, size_t arena_bytes
 sod2_status sod2_run_decisions(const sod2_binding_t*, int32_t* decisions_host, int32_t cap, int32_t* n);
 /* counts found by the NonZero operators of the last run, in execution order; *n receives their number */
 sod2_status sod2_run_exec_values(const sod2_binding_t*, int64_t* values_host, int32_t cap, int32_t* n);
+
+/* What the last run did, step by step (Section 4.3: with control flow only the taken path is launched; Section
+ * 4.4.2: the kernel version is picked at run time).  One entry per executed step: a group with the kernel family
+ * (numbering of sod2_launch_record.kernel; -1 for a group whose result was empty), version and split-K count it was
+ * launched with, or a control operator with the decision taken (Switch: 1 = the skip output, else -1). */
+typedef struct {
+  int32_t is_group;   /* 1 a group (ref = group id), 0 a Switch / Combine (ref = operator id) */
+  int32_t ref;
+  int32_t kernel, variant, splits;
+  int32_t decision;
+} sod2_trace_entry;
+sod2_status sod2_run_trace(const sod2_binding_t*, sod2_trace_entry* entries_host, int32_t cap, int32_t* n);
 
 /* plan actually executed by the last run (differs from the bind-time plan only with Switches):
  * same text format as sod2_binding_dump; arena bytes and live peak of the executed path */

@@ -31,9 +31,9 @@ OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
 EXPORTS = [
     "sod2_graph_build", "sod2_graph_destroy", "sod2_graph_op_class", "sod2_op_kind_class", "sod2_rdp_infer", "sod2_rdp_infer_ordered",
     "sod2_rdp_destroy", "sod2_rdp_query", "sod2_rdp_sweeps", "sod2_rdp_dump", "sod2_plan", "sod2_plan_destroy",
-    "sod2_plan_counts", "sod2_plan_dump", "sod2_bind", "sod2_bind_decided", "sod2_bind_executed",
+    "sod2_plan_counts", "sod2_plan_dump", "sod2_plan_query_group", "sod2_bind", "sod2_bind_decided", "sod2_bind_executed",
     "sod2_binding_destroy",
-    "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_force_decisions", "sod2_binding_force_variant",
+    "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_query_tensor", "sod2_run_query_tensor", "sod2_run_trace", "sod2_binding_force_decisions", "sod2_binding_force_variant",
     "sod2_binding_force_splits", "sod2_binding_workspace_bytes",
     "sod2_run", "sod2_run_static", "sod2_run_decisions", "sod2_run_exec_values", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
     "sod2_binding_launch_records", "sod2_replay_create", "sod2_replay_launch", "sod2_replay_destroy",
@@ -391,6 +391,64 @@ def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence
 
 
 STATIC_SCRATCH_BYTES = 8 << 20
+
+GROUP_KINDS = ["GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX", "CACHEAPPEND", "NONZERO", "GATHER",
+               "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK"]
+SG_CLASSES = ["known", "mixed", "nac"]
+
+
+class GroupInfo(C.Structure):
+    _fields_ = [("gid", C.c_int32), ("kind", C.c_int32), ("out", C.c_int32), ("out2", C.c_int32), ("n_ops", C.c_int32),
+                ("n_ins", C.c_int32), ("subgraph", C.c_int32), ("sg_class", C.c_int32), ("inplace_of", C.c_int32),
+                ("versions", C.c_int32)]
+
+
+class TensorInfo(C.Structure):
+    _fields_ = [("executed", C.c_int32), ("where", C.c_int32), ("base", C.c_int32), ("rank", C.c_int32),
+                ("dims", C.c_int64 * 8), ("offset", C.c_int64), ("bytes", C.c_int64), ("life_start", C.c_int32),
+                ("life_end", C.c_int32)]
+
+
+class TraceEntry(C.Structure):
+    _fields_ = [("is_group", C.c_int32), ("ref", C.c_int32), ("kernel", C.c_int32), ("variant", C.c_int32),
+                ("splits", C.c_int32), ("decision", C.c_int32)]
+
+
+def sod2_plan_query_group(p: "Plan", index: int) -> dict:
+    """Group `index` (planned execution order) as a dict: gid, kind, out, out2, ops, ins, subgraph, sg_class, ..."""
+    info = GroupInfo()
+    _check(_lib.sod2_plan_query_group(p.ptr, index, C.byref(info), None, 0, None, 0))
+    ops = (C.c_int32 * max(info.n_ops, 1))()
+    ins = (C.c_int32 * max(info.n_ins, 1))()
+    _check(_lib.sod2_plan_query_group(p.ptr, index, C.byref(info), ops, info.n_ops, ins, info.n_ins))
+    return dict(gid=info.gid, kind=GROUP_KINDS[info.kind], out=info.out, out2=info.out2, ops=list(ops[:info.n_ops]),
+                ins=list(ins[:info.n_ins]), subgraph=info.subgraph, sg_class=SG_CLASSES[info.sg_class],
+                inplace_of=info.inplace_of, versions=info.versions)
+
+
+def _tensor_info(fn, b: "Binding", tensor: int) -> dict:
+    info = TensorInfo()
+    _check(fn(b.ptr, int(tensor), C.byref(info)))
+    return dict(executed=bool(info.executed), where=["arena", "session", "inplace", "external"][info.where], base=info.base,
+                dims=list(info.dims[:info.rank]), offset=info.offset, bytes=info.bytes, life=(info.life_start, info.life_end))
+
+
+def sod2_binding_query_tensor(b: "Binding", tensor: int) -> dict:
+    return _tensor_info(_lib.sod2_binding_query_tensor, b, tensor)
+
+
+def sod2_run_query_tensor(b: "Binding", tensor: int) -> dict:
+    return _tensor_info(_lib.sod2_run_query_tensor, b, tensor)
+
+
+def sod2_run_trace(b: "Binding") -> list:
+    """Executed steps of the last run: dicts with is_group, ref, kernel, variant, splits, decision."""
+    n = C.c_int32()
+    _check(_lib.sod2_run_trace(b.ptr, None, 0, C.byref(n)))
+    arr = (TraceEntry * max(n.value, 1))()
+    _check(_lib.sod2_run_trace(b.ptr, arr, n.value, C.byref(n)))
+    return [dict(is_group=bool(e.is_group), ref=e.ref, kernel=e.kernel, variant=e.variant, splits=e.splits, decision=e.decision)
+            for e in arr[:n.value]]
 
 
 def sod2_run_static(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence[int], input_ptrs: Sequence[int],

@@ -194,6 +194,71 @@ sod2_status sod2_plan_dump(const sod2_plan_t* p, char* buf, size_t cap, size_t* 
   return copy_text(p->p.dump(), buf, cap, needed);
 }
 
+sod2_status sod2_plan_query_group(const sod2_plan_t* p, int32_t index, sod2_group_info* info, int32_t* ops, int32_t ops_cap,
+                                  int32_t* ins, int32_t ins_cap) {
+  if (!p || !info) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
+  const Plan& pl = p->p;
+  int seen = 0;
+  for (size_t sg = 0; sg < pl.subgraphs.size(); ++sg) {
+    for (int i : pl.subgraphs[sg]) {
+      const Item& it = pl.items[i];
+      if (!it.is_group) continue;
+      if (seen++ != index) continue;
+      const Group& gr = pl.groups.at(it.ref);
+      info->gid = gr.gid; info->kind = gr.kind; info->out = gr.out; info->out2 = gr.also.empty() ? -1 : gr.also[0];
+      info->n_ops = (int)gr.ops.size(); info->n_ins = (int)gr.ins.size();
+      info->subgraph = (int)sg;
+      info->sg_class = pl.sg_class[sg] == "known" ? 0 : (pl.sg_class[sg] == "mixed" ? 1 : 2);
+      info->inplace_of = pl.inplace[gr.out];
+      info->versions = gr.versions;
+      for (int k = 0; k < info->n_ops && k < ops_cap && ops; ++k) ops[k] = gr.ops[k];
+      for (int k = 0; k < info->n_ins && k < ins_cap && ins; ++k) ins[k] = gr.ins[k];
+      return SOD2_OK;
+    }
+  }
+  g_err = "group index outside 0 .. n_groups-1";
+  return SOD2_ERR_INVALID_ARG;
+}
+
+static sod2_status query_tensor(const Plan& pl, const BindResult& b, int32_t t, sod2_tensor_info* info) {
+  if (!info || t < 0 || t >= (int)pl.g->tensors.size()) { g_err = "null argument or tensor id out of range"; return SOD2_ERR_INVALID_ARG; }
+  std::memset(info, 0, sizeof *info);
+  info->base = -1;
+  auto d = b.dims.find(t);
+  if (d == b.dims.end()) return SOD2_OK;             // not written by an executed group
+  info->executed = 1;
+  info->rank = (int)d->second.size();
+  for (int i = 0; i < info->rank; ++i) info->dims[i] = d->second[i];
+  auto at = b.tensors.find(t);
+  if (at != b.tensors.end()) {
+    info->where = 0; info->base = t;
+    info->offset = at->second.offset; info->bytes = at->second.bytes;
+    info->life_start = at->second.start; info->life_end = at->second.end;
+  } else if (b.session_root.count(t)) {
+    info->where = 1; info->base = b.session_root.at(t);
+    info->offset = b.session.at(info->base).first; info->bytes = b.session.at(info->base).second;
+  } else if (pl.inplace[t] >= 0) {
+    info->where = 2; info->base = b.dyn_base[t];
+  } else {
+    info->where = 3; info->base = t;
+  }
+  return SOD2_OK;
+}
+sod2_status sod2_binding_query_tensor(const sod2_binding_t* b, int32_t t, sod2_tensor_info* info) {
+  if (!b) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
+  return query_tensor(*b->plan, b->b, t, info);
+}
+sod2_status sod2_run_query_tensor(const sod2_binding_t* b, int32_t t, sod2_tensor_info* info) {
+  if (!b) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
+  return query_tensor(*b->plan, b->has_executed ? b->executed : b->b, t, info);
+}
+sod2_status sod2_run_trace(const sod2_binding_t* b, sod2_trace_entry* e, int32_t cap, int32_t* n) {
+  if (!b || !n) { g_err = "null argument"; return SOD2_ERR_INVALID_ARG; }
+  *n = (int)b->trace.size();
+  for (int i = 0; i < *n && i < cap && e; ++i) e[i] = b->trace[i];
+  return SOD2_OK;
+}
+
 static sod2_status do_bind(const sod2_plan_t* p, const int64_t* sym, int32_t n, const int32_t* dec, int32_t nd,
                            bool allow_undecided, sod2_binding_t** out, const int64_t* ev = nullptr, int32_t ne = 0) {
   SOD2_TRY

@@ -22,6 +22,7 @@ struct sod2_binding_s {
   sod2::BindResult executed;                // plan of the last run when it contained Switches
   bool has_executed = false;
   std::vector<sod2_launch_record> records;
+  std::vector<sod2_trace_entry> trace;      // executed steps of the last run
   std::vector<sod2::Launch> launches;       // one per executed step that runs a kernel
   bool launches_valid = false;
   void* events = nullptr;                   // profiling events, owned by run.hip

@@ -171,6 +171,7 @@ struct Group {
   int prologue = -1;                               // LayerNorm operator applied to the contraction's first operand, or -1
   std::vector<int> ins;                            // static bases read from outside
   std::vector<int> also;                           // further results of the same operator (TopK: the indices)
+  int versions = 1;                                // code versions of the fused loop nest (Fig. 4; 1: every pair proven)
 };
 struct Item {
   bool is_group = true;

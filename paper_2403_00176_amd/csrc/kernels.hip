@@ -214,246 +214,6 @@ __global__ __launch_bounds__(256) void gemm_mfma(AL al, GemmArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Fast MFMA contraction: vector loads only (A and B both k-contiguous, 16-byte aligned), BK = 32,
-// register prefetch two tiles ahead, two LDS stages, XCD-aware tile order, and an epilogue that
-// goes through LDS so that bias / residual loads and the result stores are 16 bytes wide.
-// Rows past M are clamped (their results are never stored); k past K is zero-filled.
-// ---------------------------------------------------------------------------------------------
-struct MatAF {
-  const bf16_t* p;
-  long long sm;
-  int M;
-  struct Row { const bf16_t* ptr; };
-  __device__ __forceinline__ void init_row(Row& r, int m) const { r.ptr = p + (long long)min(m, M - 1) * sm; }
-  __device__ __forceinline__ void tile(int) {}
-  __device__ __forceinline__ uint4 load(const Row& r, int k) const { return *(const uint4*)(r.ptr + k); }
-};
-struct ConvAF {                     // needs C % 32 == 0: a k-tile stays inside one (kh, kw)
-  const bf16_t* p;
-  int H, W, C, KW, stride, pad, OH, OW, M;
-  int kh, kw, c0;
-  struct Row { const bf16_t* img; int ih0, iw0; };
-  __device__ __forceinline__ void init_row(Row& r, int m) const {
-    m = min(m, M - 1);
-    int ow = m % OW, t = m / OW;
-    int oh = t % OH, nb = t / OH;
-    r.img = p + (long long)nb * H * W * C;
-    r.ih0 = oh * stride - pad;
-    r.iw0 = ow * stride - pad;
-  }
-  __device__ __forceinline__ void tile(int k0) { int kk = k0 / C; c0 = k0 - kk * C; kh = kk / KW; kw = kk - kh * KW; }
-  __device__ __forceinline__ uint4 load(const Row& r, int k) const {   // k = k0 + 8 * chunk, same tile as tile(k0)
-    int ih = r.ih0 + kh, iw = r.iw0 + kw;
-    if (ih < 0 || ih >= H || iw < 0 || iw >= W) return zero4();
-    return *(const uint4*)(r.img + ((long long)ih * W + iw) * C + c0 + (k & 31));
-  }
-  // (K = KH*KW*C is a multiple of 32 here, so the k clamp of the caller never changes k)
-};
-
-template <class AL, int WM, int WN, int TM, int TN>
-__global__ __launch_bounds__(256, (TM * TN > 4) ? 1 : 2) void gemm_fast(AL al, GemmArgs g) {
-  constexpr int BM = WM * TM * 32, BN = WN * TN * 32, BK = 32, LDK = BK, KV = BK / 8;
-  constexpr int AV = BM * KV / 256, BV = BN * KV / 256;
-  constexpr int STAGE = (BM + BN) * LDK;                       // bf16 elements per LDS stage
-  constexpr int EPI = 4 * 32 * (TN * 32 + 4) * 2;             // fp32 staging of the epilogue, in bf16 units
-  constexpr int LDS_ELEMS = (2 * STAGE > EPI) ? 2 * STAGE : EPI;
-  static_assert(WM * WN == 4 && AV >= 1 && BV >= 1, "four waves per workgroup");
-  __shared__ __attribute__((aligned(16))) bf16_t lds[LDS_ELEMS];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int wm = wave / WN, wn = wave % WN;
-  const int tiles_m = (g.M + BM - 1) / BM, tiles_n = (g.N + BN - 1) / BN;
-  // XCD-aware order: workgroups are dealt round-robin to the 8 XCDs, so give each XCD one
-  // contiguous range of tiles (m fastest) to keep its L2 working set to a few A and B panels
-  const int nblk = tiles_m * tiles_n;
-  int lid;
-  {
-    const int b = blockIdx.x, q = nblk >> 3, r = nblk & 7, x = b & 7;
-    lid = x * q + min(x, r) + (b >> 3);
-  }
-  const int tm = lid % tiles_m, tn = lid / tiles_m;
-  const int b0 = blockIdx.y / g.nb1, b1 = blockIdx.y % g.nb1;
-  const int m0 = tm * BM, n0 = tn * BN;
-
-  al.p += b0 * g.a_sb0 + b1 * g.a_sb1;
-  const bf16_t* Bp = (const bf16_t*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
-
-  typename AL::Row arow[AV];
-  const bf16_t* brow[BV];
-#pragma unroll
-  for (int i = 0; i < AV; ++i) al.init_row(arow[i], m0 + (tid + i * 256) / KV);
-#pragma unroll
-  for (int i = 0; i < BV; ++i) brow[i] = Bp + (long long)min(n0 + (tid + i * 256) / KV, g.N - 1) * g.b_sn;
-  const int kc8 = (tid % KV) * 8;                              // same k chunk for every slot of a thread (256 % KV == 0)
-
-  auto swz = [](int row, int chunk) { return row * LDK + ((chunk ^ ((row >> 1) & 3) ^ ((row >> 3) & 1)) << 3); };
-  const int nk = (g.K + BK - 1) / BK;
-  const int ktail = g.K - (nk - 1) * BK;                      // valid k of the last tile (1..BK)
-  // Loads are issued unconditionally (tiles past the end re-read the last one, k past K re-reads
-  // the last chunk): a branch around them would make the wait-count pass assume the worst path
-  // and serialise the prefetch.  Zero-filling of the k tail happens when the data goes to LDS.
-  auto gload = [&](int t, uint4* ra, uint4* rb) {
-    t = min(t, nk - 1);
-    const int k = min(t * BK + kc8, g.K - 8);
-    al.tile(t * BK);
-#pragma unroll
-    for (int i = 0; i < AV; ++i) ra[i] = al.load(arow[i], k);
-#pragma unroll
-    for (int i = 0; i < BV; ++i) rb[i] = *(const uint4*)(brow[i] + k);
-  };
-  auto sstore = [&](int buf, int t, const uint4* ra, const uint4* rb) {
-    bf16_t* As = lds + buf * STAGE;
-    bf16_t* Bs = As + BM * LDK;
-    if (t >= nk - 1 && ktail < BK) {                        // uniform: only the last, partial tile
-      const bool keep = kc8 < ktail;
-#pragma unroll
-      for (int i = 0; i < AV; ++i) *(uint4*)&As[swz((tid + i * 256) / KV, tid % KV)] = keep ? ra[i] : zero4();
-#pragma unroll
-      for (int i = 0; i < BV; ++i) *(uint4*)&Bs[swz((tid + i * 256) / KV, tid % KV)] = keep ? rb[i] : zero4();
-    } else {
-#pragma unroll
-      for (int i = 0; i < AV; ++i) *(uint4*)&As[swz((tid + i * 256) / KV, tid % KV)] = ra[i];
-#pragma unroll
-      for (int i = 0; i < BV; ++i) *(uint4*)&Bs[swz((tid + i * 256) / KV, tid % KV)] = rb[i];
-    }
-  };
-
-  f32x16_t acc[TM][TN];
-#pragma unroll
-  for (int i = 0; i < TM; ++i)
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
-
-  // rows are 64 bytes with no padding; the 16-byte chunk index is XOR-swizzled with the row so that
-  // both the 16-byte row-major stores and the MFMA fragment reads (32 consecutive rows, one chunk)
-  // spread over all LDS banks.  Tile rows are multiples of 32, so the swizzle of a fragment row
-  // depends on (lane & 31) only.
-  const int frow = lane & 31, fchunk = lane >> 5;
-  auto compute = [&](int buf) {
-    const bf16_t* S = lds + buf * STAGE;
-#pragma unroll
-    for (int ks = 0; ks < BK / 16; ++ks) {
-      V16 af[TM], bf[TN];
-#pragma unroll
-      for (int i = 0; i < TM; ++i) af[i].u = *(const uint4*)&S[(wm * TM * 32 + i * 32) * LDK + swz(frow, ks * 2 + fchunk)];
-#pragma unroll
-      for (int j = 0; j < TN; ++j)
-        bf[j].u = *(const uint4*)&S[(BM + wn * TN * 32 + j * 32) * LDK + swz(frow, ks * 2 + fchunk)];
-#pragma unroll
-      for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[i].b, bf[j].b, acc[i][j], 0, 0, 0);
-    }
-  };
-
-  uint4 ra0[AV], rb0[BV], ra1[AV], rb1[BV];
-  gload(0, ra0, rb0);
-  gload(1, ra1, rb1);
-  sstore(0, 0, ra0, rb0);
-  __syncthreads();
-  // sched_barrier keeps the order "issue prefetch, compute, consume the older prefetch": left to
-  // itself the scheduler sinks the loads below the MFMAs and hoists their consumers above them
-  for (int kt = 0; kt < nk; kt += 2) {
-    gload(kt + 2, ra0, rb0);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(0);
-    __builtin_amdgcn_sched_barrier(0);
-    sstore(1, kt + 1, ra1, rb1);
-    __syncthreads();
-    if (kt + 1 >= nk) break;
-    gload(kt + 3, ra1, rb1);
-    __builtin_amdgcn_sched_barrier(0);
-    compute(1);
-    __builtin_amdgcn_sched_barrier(0);
-    sstore(0, kt + 2, ra0, rb0);
-    __syncthreads();
-  }
-
-  // ---- epilogue: 32 rows of the wave tile at a time through a wave-private fp32 LDS patch ----
-  constexpr int EW = TN * 32, ELD = EW + 4;
-  float* patch = (float*)lds + wave * 32 * ELD;
-  bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
-  const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
-  const bf16_t* bias = (const bf16_t*)g.bias;
-  const int colw = n0 + wn * EW;
-  auto act8 = [](float* x, int act) {
-    if (act == ACT_RELU) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = fmaxf(x[e], 0.f);
-    } else if (act == ACT_GELU) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = gelu_erf(x[e]);
-    } else if (act == ACT_SIGMOID) {
-#pragma unroll
-      for (int e = 0; e < 8; ++e) x[e] = 1.f / (1.f + __expf(-x[e]));
-    }
-  };
-  auto finish_rows = [&](int roww) {
-#pragma unroll 1
-    for (int q = 0; q < 32 * EW / 8 / 64; ++q) {
-      const int v = lane + q * 64;
-      const int rr = v / (EW / 8), cc = (v % (EW / 8)) * 8;
-      const int row = roww + rr, col = colw + cc;
-      if (row >= g.M || col >= g.N) continue;
-      float x[8];
-      {
-        const float4 p0 = *(const float4*)&patch[rr * ELD + cc], p1 = *(const float4*)&patch[rr * ELD + cc + 4];
-        x[0] = p0.x; x[1] = p0.y; x[2] = p0.z; x[3] = p0.w; x[4] = p1.x; x[5] = p1.y; x[6] = p1.z; x[7] = p1.w;
-      }
-      const bool full = g.c_vec && col + 8 <= g.N;
-      if (bias) {
-        if (full) {
-          V16 bv; bv.u = *(const uint4*)(bias + col);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) x[e] = x[e] * g.scale + bf2f(bv.h[e]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e) x[e] = x[e] * g.scale + (col + e < g.N ? bf2f(bias[col + e]) : 0.f);
-        }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) x[e] *= g.scale;
-      }
-      act8(x, g.act1);
-      if (Rp) {
-        if (full) {
-          V16 rv; rv.u = *(const uint4*)(Rp + (long long)row * g.r_sm + col);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) x[e] += bf2f(rv.h[e]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            if (col + e < g.N) x[e] += bf2f(Rp[(long long)row * g.r_sm + (long long)(col + e) * g.r_sn]);
-        }
-        act8(x, g.act2);
-      }
-      if (full) {
-        V16 o;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) o.h[e] = f2bf(x[e]);
-        *(uint4*)(Cp + (long long)row * g.c_sm + col) = o.u;
-      } else {
-#pragma unroll
-        for (int e = 0; e < 8; ++e)
-          if (col + e < g.N) Cp[(long long)row * g.c_sm + (long long)(col + e) * g.c_sn] = f2bf(x[e]);
-      }
-    }
-  };
-#pragma unroll
-  for (int i = 0; i < TM; ++i) {
-#pragma unroll
-    for (int j = 0; j < TN; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r)
-        patch[((r >> 2) * 8 + (lane >> 5) * 4 + (r & 3)) * ELD + j * 32 + (lane & 31)] = acc[i][j][r];
-    finish_rows(m0 + wm * TM * 32 + i * 32);
-  }
-}
-
-// ---------------------------------------------------------------------------------------------
 // Plain FMA contraction for any dtype and any strides
 // ---------------------------------------------------------------------------------------------
 template <class T>
@@ -1202,25 +962,6 @@ static hipError_t launch_mfma_variant(const AL& al, const GemmArgs& g, int varia
   }
 }
 
-template <class AL, int WM, int WN, int TM, int TN>
-static hipError_t launch_fast(const AL& al, const GemmArgs& g, hipStream_t s) {
-  constexpr int BM = WM * TM * 32, BN = WN * TN * 32;
-  dim3 grid(((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN), g.nb0 * g.nb1);
-  hipLaunchKernelGGL((gemm_fast<AL, WM, WN, TM, TN>), grid, dim3(256), 0, s, al, g);
-  return hipGetLastError();
-}
-template <class AL>
-static hipError_t launch_fast_variant(const AL& al, const GemmArgs& g, int variant, hipStream_t s) {
-  switch (variant) {
-    case V_XFAT:                                                     // (a 256 x 256 tile of this kernel needs 256 accumulator
-                                                                     //  registers and spills: the version falls back to 256 x 128)
-    case V_FAT: return launch_fast<AL, 2, 2, 4, 2>(al, g, s);        // 256 x 128
-    case V_SKINNY: return launch_fast<AL, 1, 4, 2, 1>(al, g, s);     // 64 x 128
-    case V_SMALL: return launch_fast<AL, 2, 2, 1, 1>(al, g, s);      // 64 x 64
-    default: return launch_fast<AL, 2, 2, 2, 2>(al, g, s);           // 128 x 128
-  }
-}
-
 hipError_t launch_gemm_dl(const GemmArgs& g, int tile, hipStream_t s);
 hipError_t launch_conv_dl(const ConvArgs& c, const GemmArgs& g, int tile, hipStream_t s);
 
@@ -1292,10 +1033,6 @@ hipError_t launch_gemm(const Launch& L, const GemmArgs& g, hipStream_t s) {
     if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(gemm_simple<bf16_t>, grid, dim3(256), 0, s, g);
     else hipLaunchKernelGGL(gemm_simple<float>, grid, dim3(256), 0, s, g);
     return hipGetLastError();
-  }
-  if (g.a_vec && g.b_mode == 0) {
-    MatAF af{(const bf16_t*)g.A, g.a_sm, g.M};
-    return launch_fast_variant(af, g, L.variant, s);
   }
   MatA al{(const bf16_t*)g.A, g.a_sm, g.a_sk, g.M, g.K, g.a_vec};
   return launch_mfma_variant(al, g, L.variant, s);
@@ -1427,10 +1164,6 @@ hipError_t launch_conv(const Launch& L, const ConvArgs& c, hipStream_t s) {
     g.group_m = 8;
     if (c.splits > 1 && c.ws) { g.splits = c.splits; g.ws = c.ws; }
     return launch_conv_dl(c, g, L.variant - V_DL0, s);
-  }
-  if (c.vec && c.C % 32 == 0 && g.b_mode == 0) {
-    ConvAF af{(const bf16_t*)c.x, c.H, c.W, c.C, c.KW, c.stride, c.pad, c.OH, c.OW, g.M, 0, 0, 0};
-    return launch_fast_variant(af, g, L.variant, s);
   }
   ConvA al{(const bf16_t*)c.x, c.H, c.W, c.C, c.KW, c.stride, c.pad, c.OH, c.OW, g.M, g.K, c.vec};
   return launch_mfma_variant(al, g, L.variant, s);

@@ -295,7 +295,9 @@ struct Builder {
   int pick_variant(int dtype, int64_t M, int64_t N, int64_t K, int64_t batch) const {
     if (dtype != SOD2_BF16) return (M <= 8 && force_variant != V_SIMPLE && p.opts.mvc) ? V_GEMV : V_SIMPLE;   // fp32: plain FMA kernels
     if (force_variant >= 0) return force_variant;
-    if (!p.opts.mvc) return V_REGULAR;
+    // multi-version kernels off (the breakdown study of Section 5.3): one version of the same kernel for every
+    // shape -- the 128 x 128 x 64 tile, no skinny version, no k groups, no split-K
+    if (!p.opts.mvc) return V_DL0 + DL_128x128x64_S2_W8;
     if (M <= 8) return V_GEMV;                     // decode shape: weight streaming, one wave per column
     const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
     const int64_t t64 = ((M + 63) / 64) * ((N + 63) / 64) * batch;
@@ -1602,6 +1604,7 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
       }
     }
     h->records.clear();
+    h->trace.clear();
     h->last_decisions.clear();
     hipEvent_t* ev = nullptr;
     if (h->profiling) {
@@ -1686,6 +1689,12 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
         if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("kernel launch failed: ") + hipGetErrorString(e));
         if (ev) { (void)hipEventRecord(ev[n_ev + 1], s); timed.push_back({n_ev, L}); n_ev += 2; }
         if (!L.empty) ++queued;
+        {
+          int splits = 1;
+          if (L.kernel == K_GEMM && P.ws) splits = std::max(L.u.gemm.splits, 1);
+          else if (L.kernel == K_CONV && P.ws) splits = std::max(L.u.conv.splits, 1);
+          h->trace.push_back(sod2_trace_entry{1, it.ref, L.empty ? -1 : L.kernel, L.variant, splits, -1});
+        }
         if (L.kernel == K_NONZERO) {
           // the extent is execution determined: read the count back, then size and plan what follows
           begin_read_back(P.at(L.r[2]), 8, s);
@@ -1742,6 +1751,9 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
           if (dec != 0) replan(k, "Switch", have_other ? &other : nullptr);
           else assumed = true;
         }
+        h->trace.push_back(sod2_trace_entry{0, it.ref, -1, 0, 1, decisions[which]});
+      } else {
+        h->trace.push_back(sod2_trace_entry{0, it.ref, -1, 0, 1, -1});      // Combine: forwards the taken path's tensor
       }
       ++k;
     }

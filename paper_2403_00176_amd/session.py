@@ -8,7 +8,7 @@ import numpy as np
 import torch
 
 from . import (pointer_array, sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run, sod2_binding_arena_bytes,
-               sod2_binding_dump, sod2_run_decisions, sod2_run_arena_bytes, sod2_binding_workspace_bytes,
+               sod2_binding_query_tensor, sod2_run_decisions, sod2_run_arena_bytes, sod2_binding_workspace_bytes,
                sod2_replay_create, sod2_replay_launch, Sod2Error)
 
 _NP = {"f32": np.float32, "i64": np.int64, "i32": np.int32}
@@ -94,13 +94,8 @@ class Session:
                 self.arena = None
 
     def output_shapes(self, binding) -> List[List[int]]:
-        """Concrete shapes of the graph outputs, read from the binding's text dump."""
-        dims = {}
-        for line in sod2_binding_dump(binding).splitlines():
-            if line.startswith("t") and " dims=[" in line:
-                tid = int(line[1:line.index(" ")])
-                dims[tid] = [int(v) for v in line[line.index("[") + 1:line.index("]")].split()]
-        return [dims[t] for t in self.desc.outputs()]
+        """Concrete shapes of the graph outputs under this binding."""
+        return [sod2_binding_query_tensor(binding, t)["dims"] for t in self.desc.outputs()]
 
 
 class DecoderSession:

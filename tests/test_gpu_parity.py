@@ -302,6 +302,16 @@ def test_config4_control_flow(S):
             ses, b, ins, got = _run_gated(S, w, ci, sym, forced=[int(d) for d in ref.decisions])
         assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
         assert S.sod2_run_arena_bytes(b)[0] == A.bind(po, sym, ref.decisions).arena_bytes
+        # the run's trace as records: the executed steps of the oracle's binding, in order, Switch entries carrying
+        # the decisions, every group with the kernel it was launched with
+        bo = A.bind(po, sym, ref.decisions)
+        tr = S.sod2_run_trace(b)
+        assert [(e["is_group"], e["ref"]) for e in tr] == [(po.items[i].is_group, po.items[i].ref) for i in bo.steps]
+        assert [e["decision"] for e in tr if not e["is_group"] and w.graph.ops[e["ref"]].kind == "Switch"] == \
+            [int(d) for d in ref.decisions]
+        assert all(e["kernel"] >= 0 for e in tr if e["is_group"])
+        out_t = w.graph.outputs()[0]
+        assert S.sod2_run_query_tensor(b, out_t)["dims"] == list(ref.values[out_t].shape)
         t = w.graph.outputs()[0]
         assert rel_err(got, ref.values[t]) <= TOL["bf16"]
     # forcing the opposite decisions changes the executed plan accordingly

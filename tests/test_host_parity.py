@@ -149,3 +149,45 @@ def test_tiny_fixture_graphs_match_oracle():
         ro = R.RDP(gd).analyse()
         assert S.sod2_rdp_dump(r) == R.dump(ro)
         assert S.sod2_plan_dump(S.sod2_plan(g, r)) == P.dump(P.build_plan(gd, ro))
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4])
+def test_structured_queries_agree_with_the_oracle(cfg):
+    """sod2_plan_query_group and sod2_binding_query_tensor (records, not text) against the oracle's plan and
+    binding objects: groups in planned order with members, inputs, sub-graph and class; per tensor the
+    concrete dims, where it lives, offset, bytes and lifetime."""
+    w = small(cfg)
+    g = S.sod2_graph_build(w.graph)
+    r = S.sod2_rdp_infer(g)
+    p = S.sod2_plan(g, r)
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    n_groups = S.sod2_plan_counts(p)[0]
+    expect = [(s, po.items[i].ref) for s, sg in enumerate(po.subgraphs) for i in sg if po.items[i].is_group]
+    assert n_groups == len(expect)
+    for k, (sg, gid) in enumerate(expect):
+        q = S.sod2_plan_query_group(p, k)
+        gr = po.groups[gid]
+        assert (q["gid"], q["kind"], q["out"], q["ops"], q["ins"]) == (gr.gid, gr.kind, gr.out, gr.ops, gr.ins)
+        assert q["out2"] == (gr.also[0] if gr.also else -1)
+        assert (q["subgraph"], q["sg_class"]) == (sg, po.sg_class[sg])
+        assert q["inplace_of"] == po.inplace.get(gr.out, -1)
+    with pytest.raises(S.Sod2Error):
+        S.sod2_plan_query_group(p, n_groups)
+    call = w.calls[0]
+    n_sw = sum(1 for op in w.graph.ops if op.kind == "Switch")
+    dec = [k % 2 == 0 for k in range(n_sw)]
+    b = S.sod2_bind(p, call, dec)
+    bo = A.bind(po, call, dec)
+    for t in range(len(w.graph.tensors)):
+        q = S.sod2_binding_query_tensor(b, t)
+        assert q["executed"] == (t in bo.dims), t
+        if not q["executed"]:
+            continue
+        assert q["dims"] == list(bo.dims[t])
+        if t in bo.tensors:
+            a = bo.tensors[t]
+            assert (q["where"], q["offset"], q["bytes"], q["life"]) == ("arena", a.offset, a.bytes, (a.start, a.end))
+        elif w.graph.tensors[t].is_output:
+            assert q["where"] == "external"
+    with pytest.raises(S.Sod2Error):
+        S.sod2_binding_query_tensor(b, len(w.graph.tensors))
