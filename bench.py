@@ -471,6 +471,9 @@ def main():
                           "frac_of_latency": round(t_roof_ms / len(timed) / (sum(lat) / len(lat)), 4)},
         "kernels": kernels,
         "subgraph_classes": subgraph_classes,
+        # fused elementwise groups by the number of code versions they need (Fig. 8's 1 / 2-4 / 5-8 buckets)
+        "eltwise_group_versions": {"1": versions.get(1, 0), "2-4": sum(v for k, v in versions.items() if 2 <= k <= 4),
+                                   "5-8": sum(v for k, v in versions.items() if 5 <= k <= 8)},
         "event_overhead_us": round(1e3 * sum(empty_ms) / max(len(empty_ms), 1), 2),
         "cpu_baseline": cpu,
         "paper_context": "SoD2 reports up to 3.9x speed-up (vs ONNX Runtime, Adreno 660 GPU, fp16) and up to 88% less "

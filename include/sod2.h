@@ -121,6 +121,14 @@ typedef struct {
   int32_t dmp;     /* peak-first arena plan; 0: best-fit greedy in execution order        */
   int32_t mvc;     /* multi-version kernels; 0: one version (128 x 128 x 64 tile) for every shape  */
   int32_t inplace; /* a group's result may take over the storage of an operand that dies there */
+  /* Limits of the fusion rules; 0 selects the default.  max_versions: most code versions a fused elementwise group
+   * may need (Section 4.2, Fig. 4: two per dim pair that RDP can prove neither equal nor 1; default 8, the largest
+   * bucket of Fig. 8; 1: only proven chains fuse).  The others state what the kernels behind the plan can fuse --
+   * they shape the groups, never a value: the head size of the fused attention group (default 64), the most rows a
+   * CacheAppend inside it may add (4), and for a LayerNorm run as the prologue of a contraction the most rows (8),
+   * the largest normalised extent (1024) and the multiple it must be of (64). */
+  int32_t max_versions;
+  int32_t attn_head_dim, append_max_rows, prologue_max_rows, prologue_max_k, prologue_k_multiple;
 } sod2_plan_opts;
 
 typedef struct sod2_graph_s sod2_graph_t;

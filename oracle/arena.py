@@ -83,6 +83,7 @@ class Binding:
     session_root: Dict[int, int] = field(default_factory=dict)          # session tensor -> its session input
     session_bytes: int = 0
     exec: List[Tuple[int, int, bool]] = field(default_factory=list)     # executed NonZero: (op id, extent used, known?)
+    versions: Dict[int, str] = field(default_factory=dict)   # multi-version group -> the version the bound symbols select
 
 
 def concrete_dims(plan: Plan, t: int, env) -> List[int]:
@@ -90,6 +91,20 @@ def concrete_dims(plan: Plan, t: int, env) -> List[int]:
     if not isinstance(s, list) or any(not R.is_expr(d) for d in s):
         raise UnresolvedShape(f"tensor {t} ({plan.graph.tensors[t].name})")
     return [d.eval(env) for d in s]
+
+
+def select_version(plan: Plan, gr, env) -> str:
+    """Section 4.2: of the code versions of a fused group with unproven broadcast pairs, the one that holds for the
+    bound symbols.  One letter per unproven pair, in the plan's order: 'e' the two extents are equal, 'a' the first
+    operand's is 1 (it is broadcast), 'b' the second's.  (Anything else does not broadcast: evaluating the result's
+    extent has already failed.)"""
+    out = []
+    for a, b, k in gr.unproven:
+        da, db = concrete_dims(plan, a, env), concrete_dims(plan, b, env)
+        x = da[-k] if k <= len(da) else 1
+        y = db[-k] if k <= len(db) else 1
+        out.append("e" if x == y else ("a" if x == 1 else "b"))
+    return "".join(out)
 
 
 def intersects(a: ArenaTensor, b: ArenaTensor) -> bool:
@@ -194,6 +209,8 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
                     b.exec.append((n_op, v, known))
                     nz_bytes = align_up((len(src) * ub + 1) * DT_BYTES[g.tensors[t].dtype])
                 b.dims[t] = concrete_dims(plan, t, env)
+                if gr.versions > 1:
+                    b.versions[gr.gid] = select_version(plan, gr, env)
                 for n_op in gr.ops:                       # a CACHEAPPEND group, or appends inside an attention group
                     if g.ops[n_op].kind != "CacheAppend":
                         continue
@@ -356,6 +373,8 @@ def dump(b: Binding) -> str:
     for k, i in enumerate(b.steps):
         it = plan.items[i]
         lines.append(f"step {k} {'g' if it.is_group else 'c'}{it.ref}")
+    for gid in sorted(b.versions):
+        lines.append(f"version g{gid} {b.versions[gid]} of {plan.groups[gid].versions}")
     for t in sorted(b.dims):
         dims = " ".join(map(str, b.dims[t]))
         if t in b.tensors:

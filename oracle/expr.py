@@ -2,8 +2,11 @@
 the RDP lattice (Section 4.1, the domain V').
 
 An expression is a polynomial with integer coefficients over *atoms*.  An atom
-is a symbol, or floordiv(e, c) / mod(e, c) of a canonical expression e and a
-positive integer c that could not be simplified.  Two expressions are equal
+is a symbol, floordiv(e, c) / mod(e, c) of a canonical expression e and a
+positive integer c that could not be simplified, or bcast(e1, e2): the extent
+two aligned dims broadcast to when neither is provably 1 or equal to the other
+(Section 4.2, Fig. 4: which of the cases holds is only seen when the symbols are
+bound; it evaluates to the common value, or to the other one when one is 1).  Two expressions are equal
 exactly when their canonical strings are equal (sound, not complete).
 
 Canonical string: terms sorted by (degree, atom strings); a term is
@@ -14,7 +17,11 @@ from __future__ import annotations
 
 from typing import Dict, Tuple
 
-_ATOMS: Dict[str, tuple] = {}   # atom string -> ("sym", name) | ("floordiv", Expr, c) | ("mod", Expr, c)
+_ATOMS: Dict[str, tuple] = {}   # atom string -> ("sym", name) | ("floordiv", Expr, c) | ("mod", Expr, c) | ("bcast", Expr, Expr)
+
+
+class BroadcastMismatch(Exception):
+    """Two extents that must broadcast are different and neither is 1."""
 
 
 class Expr:
@@ -133,6 +140,21 @@ class Expr:
         _ATOMS.setdefault(name, ("mod", self, c))
         return Expr({(name,): 1})
 
+    def bcast(self, o: "Expr") -> "Expr":
+        """Extent of the broadcast of two aligned dims (the larger one when one of them is 1)."""
+        if self == o:
+            return self
+        if self.is_const() and self.const_value() == 1:
+            return o
+        if o.is_const() and o.const_value() == 1:
+            return self
+        if self.is_const() and o.is_const():
+            raise BroadcastMismatch(f"{self} vs {o}")
+        a, b = sorted((self, o), key=str)
+        name = f"bcast({a}, {b})"
+        _ATOMS.setdefault(name, ("bcast", a, b))
+        return Expr({(name,): 1})
+
     def exact_div(self, o: "Expr"):
         """self / o when o is a single term that divides every term of self, else None."""
         if len(o.terms) != 1:
@@ -166,4 +188,11 @@ def _eval_atom(a: str, env: Dict[str, int]) -> int:
     if d[0] == "sym":
         return int(env[d[1]])
     inner = d[1].eval(env)
+    if d[0] == "bcast":
+        other = d[2].eval(env)
+        if inner == other or other == 1:
+            return inner
+        if inner == 1:
+            return other
+        raise BroadcastMismatch(f"{d[1]} = {inner} vs {d[2]} = {other}")
     return inner // d[2] if d[0] == "floordiv" else inner % d[2]

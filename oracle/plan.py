@@ -20,31 +20,42 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
 R3  LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
     ScatterRows, Resize, Upsample, OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
-R4  Remaining elementwise operators chain while every aligned dim pair of
-    every operand is proven equal or 1 (the condition of Fig. 4), up to 8 ops.
+R4  Remaining elementwise operators chain, up to 8 ops.  An aligned dim pair of
+    the two operands of a binary member is *proven* when RDP shows the two
+    extents equal or one of them 1 (the condition of Fig. 4): the fused loop nest
+    then has one form.  A pair of two resolved but unrelated extents is
+    *unproven*: each such pair doubles the number of code versions of the fused
+    nest (Fig. 4: 8 versions for three unproven pairs), of which one is selected
+    when the symbols are bound (Section 4.2).  The chain stops before the member
+    that would take the group beyond ``Opts.max_versions`` versions (8, the
+    largest bucket of Fig. 8; 1 = fuse proven chains only), and at any pair with
+    an unresolved extent.  A group of a single operator has one version (the
+    plain operator with run-time broadcast strides).
 R5  Group id = smallest operator id in it; groups are ordered by the position
     of their last member in the node order (a topological order of groups).
 R6  Attention: a GEMM group that is only MatMul [+ Mul by a host scalar], whose
     result is read by one Softmax alone, whose result in turn is the first
     operand of one MatMul alone that leads a GEMM group of MatMul [+ Transpose]:
     the three groups become one ATTENTION group (scores and probabilities are
-    never materialised, Section 4.2's "fusion removes intermediate results").
-    Only for bf16 tensors with a known head size of 64 (the size the one fused
-    kernel of the library is written for).
+    never materialised: Section 4.2, fusion reduces the materialisation of
+    intermediate results).  Only for bf16 tensors with a known head size among
+    ``Opts.attn_head_dims`` (what the executing backend declares it can fuse).
 R8  Cache append inside attention: when the key operand and the value operand
     of an ATTENTION group are, through views only and with no other reader, the
     results of two CacheAppend operators that each append a known number of at
-    most 4 bf16 rows (the decode step), the two CACHEAPPEND groups join the
+    most ``Opts.append_max_rows`` bf16 rows (the decode step), the two CACHEAPPEND groups join the
     ATTENTION group: its kernel writes the new rows into the session slots and
     reads them from where they were produced.
 R7  LayerNorm as a prologue: a LAYERNORM group whose result is read by one
     MatMul alone, as its first operand, joins that MatMul's GEMM group when the
-    row count is a known constant of at most 8 (the decode step: every wave of
-    the skinny contraction kernel can afford to normalise the few rows itself),
-    the normalised dim (= the contraction dim) is a known constant of at most
-    1024 and a multiple of 64, and everything is bf16.  The LayerNorm result is
-    never materialised.  (For many rows a fused version was measured slower
-    than the two kernels, so the rule stops at 8.)
+    row count is a known constant of at most ``Opts.prologue_max_rows`` (the
+    decode step), the normalised dim (= the contraction dim) is a known constant
+    of at most ``Opts.prologue_max_k`` and a multiple of
+    ``Opts.prologue_k_multiple``, and everything is bf16.  The LayerNorm result
+    is never materialised.
+The limits of R6-R8 are capabilities of whatever executes the plan, handed in
+with the options (the same numbers go to the library's planner); they shape
+the groups, never a value.
 
 Execution-determined extents (Section 4.3: what follows an EDO can only be
 planned once it has executed).  When the graph holds a NonZero the plan uses
@@ -81,6 +92,13 @@ class Opts:
     dmp: bool = True         # peak-first arena plan; off: best-fit greedy in execution order
     mvc: bool = True         # multi-version kernels (library only; no effect on structure)
     inplace: bool = True     # a group's result may take over the storage of an operand that dies there
+    max_versions: int = 8    # R4: most code versions a fused elementwise group may need (1: proven chains only)
+    # what the executing backend can fuse (R6-R8); structure only
+    attn_head_dims: tuple = (64,)
+    append_max_rows: int = 4
+    prologue_max_rows: int = 8
+    prologue_max_k: int = 1024
+    prologue_k_multiple: int = 64
 
 
 @dataclass
@@ -91,6 +109,8 @@ class Group:
     out: int                              # tensor id written by the group
     ins: List[int] = field(default_factory=list)   # base tensors read from outside the group
     also: List[int] = field(default_factory=list)  # further results of the same operator (TopK: the indices)
+    versions: int = 1                              # code versions of the fused loop nest (Fig. 4)
+    unproven: List[tuple] = field(default_factory=list)   # (operand a, operand b, aligned dim) pairs behind them
 
 
 @dataclass
@@ -126,11 +146,25 @@ def _shape_equal(a, b) -> bool:
         all(R.is_expr(x) and R.is_expr(y) and x == y for x, y in zip(a, b))
 
 
-def _bcast_proven(out, other) -> bool:
-    if not isinstance(out, list) or not isinstance(other, list) or len(other) > len(out):
-        return False
-    pad = [R.C(1)] * (len(out) - len(other)) + other
-    return all(R.pair_proven(x, y) for x, y in zip(out, pad))
+def _unproven_pairs(rdp, op):
+    """Aligned dim pairs of the two operands of a binary elementwise operator that RDP cannot prove equal or 1, as
+    (operand a, operand b, dim counted from the last); [] for a unary operator; None when an extent is unresolved."""
+    if len(op.inputs) != 2:
+        return []
+    a, b = op.inputs
+    sa, sb = rdp.S[a], rdp.S[b]
+    if not isinstance(sa, list) or not isinstance(sb, list):
+        return None
+    out = []
+    for k in range(1, max(len(sa), len(sb)) + 1):
+        x = sa[-k] if k <= len(sa) else R.C(1)
+        y = sb[-k] if k <= len(sb) else R.C(1)
+        if R.pair_proven(x, y):
+            continue
+        if not (R.is_expr(x) and R.is_expr(y)):
+            return None
+        out.append((a, b, k))
+    return out
 
 
 def tensor_bytes_expr(plan_or_rdp, graph, tid) -> Optional[Expr]:
@@ -246,17 +280,22 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             new_group("GATHER", members)
         elif op.kind in ELTWISE:
             members, cur = [n], op.outputs[0]
+            pairs = _unproven_pairs(rdp, op) or []           # of the seed itself; they count once it has company
             while opts.fusion and len(members) < 8:
                 c = sole_consumer(cur)
                 if c is None or c in assigned or g.ops[c].kind not in ELTWISE:
                     break
                 cop = g.ops[c]
-                if len(cop.inputs) == 2 and not (_bcast_proven(rdp.S[cop.outputs[0]], rdp.S[other(cop, cur)])
-                                                 and _bcast_proven(rdp.S[cop.outputs[0]], rdp.S[cur])):
+                more = _unproven_pairs(rdp, cop)
+                if more is None or 2 ** (len(pairs) + len(more)) > max(opts.max_versions, 1):
                     break
+                pairs = pairs + more
                 members.append(c)
                 cur = cop.outputs[0]
             new_group("ELTWISE", members)
+            if len(members) > 1 and pairs:
+                groups[min(members)].versions = 2 ** len(pairs)
+                groups[min(members)].unproven = pairs
         else:
             raise ValueError(f"no grouping rule for {op.kind}")
     for c in absorbed_transpose:
@@ -277,7 +316,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
                 return None
             rows = rdp.S[op.inputs[1]]
             if g.tensors[t].dtype != "bf16" or not isinstance(rows, list) or not rows or not R.is_expr(rows[0]) \
-                    or not rows[0].is_const() or rows[0].const_value() > 4:
+                    or not rows[0].is_const() or rows[0].const_value() > opts.append_max_rows:
                 return None
             return p
 
@@ -308,7 +347,8 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
                 continue
             sq, sv = rdp.S[mm1.inputs[0]], rdp.S[g.ops[c2].inputs[1]]
             if not (isinstance(sq, list) and isinstance(sv, list) and sq and sv and R.is_expr(sq[-1]) and
-                    R.is_expr(sv[-1]) and sq[-1] == R.C(64) and sv[-1] == R.C(64)):
+                    R.is_expr(sv[-1]) and sq[-1] == sv[-1] and sq[-1].is_const() and
+                    sq[-1].const_value() in opts.attn_head_dims):
                 continue
             members = g1.ops + [n] + g2.ops
             for gid in (g1.gid, assigned[n], g2.gid):
@@ -350,7 +390,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             kdim, rows = sx[-1].const_value(), 1
             for d in sx[:-1]:
                 rows *= d.const_value()
-            if kdim > 1024 or kdim % 64 != 0 or rows > 8:
+            if kdim > opts.prologue_max_k or kdim % opts.prologue_k_multiple != 0 or rows > opts.prologue_max_rows:
                 continue
             members = [n] + gm.ops
             del groups[assigned[n]]
@@ -644,8 +684,11 @@ def dump(plan: Plan) -> str:
         if it.is_group:
             gr = plan.groups[it.ref]
             also = "".join(f" also=t{t}" for t in gr.also)
+            ver = ""
+            if gr.versions > 1:
+                ver = f" versions={gr.versions} unproven=[" + " ".join(f"t{a}~t{b}@{k}" for a, b, k in gr.unproven) + "]"
             lines.append(f"g{gr.gid} {gr.kind} ops=[{' '.join(map(str, gr.ops))}] out=t{gr.out}{also} "
-                         f"ins=[{' '.join('t%d' % t for t in gr.ins)}]")
+                         f"ins=[{' '.join('t%d' % t for t in gr.ins)}]{ver}")
         else:
             lines.append(f"c{it.ref} {g.ops[it.ref].kind}")
     for t in sorted(plan.inplace):

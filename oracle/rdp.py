@@ -143,7 +143,9 @@ def broadcast_dim(a, b):
             return a
         if a.is_const() and b.is_const():
             raise ShapeMismatch(f"broadcast {a} vs {b}")
-        return NAC                       # unproven: could be equal, could be 1
+        # unproven: could be equal, one of them could be 1 (Fig. 4).  The extent is still a function of the
+        # symbols -- an operation-inferred constant, evaluated (and checked) when they are bound
+        return a.bcast(b)
     for x, y in ((a, b), (b, a)):
         if is_expr(x) and x.is_const() and x.const_value() != 1 and (y is UNDEF or y == NAC):
             return x                     # the other side is 1 or x: the output is x either way

@@ -68,7 +68,9 @@ class _GraphDesc(C.Structure):
 
 class PlanOpts(C.Structure):
     _fields_ = [("fusion", C.c_int32), ("sep", C.c_int32), ("dmp", C.c_int32), ("mvc", C.c_int32),
-                ("inplace", C.c_int32)]
+                ("inplace", C.c_int32), ("max_versions", C.c_int32), ("attn_head_dim", C.c_int32),
+                ("append_max_rows", C.c_int32), ("prologue_max_rows", C.c_int32), ("prologue_max_k", C.c_int32),
+                ("prologue_k_multiple", C.c_int32)]
 
 
 class DimInfo(C.Structure):
@@ -261,9 +263,12 @@ def sod2_rdp_dump(r: Rdp) -> str:
     return _text(_lib.sod2_rdp_dump, r.ptr)
 
 
-def sod2_plan(g: Graph, r: Rdp, fusion=1, sep=1, dmp=1, mvc=1, inplace=1) -> Plan:
+def sod2_plan(g: Graph, r: Rdp, fusion=1, sep=1, dmp=1, mvc=1, inplace=1, max_versions=0, attn_head_dim=0,
+              append_max_rows=0, prologue_max_rows=0, prologue_max_k=0, prologue_k_multiple=0) -> Plan:
+    """The last six options are limits of the fusion rules; 0 = the library's default (see sod2_plan_opts)."""
     out = C.c_void_p()
-    opts = PlanOpts(int(fusion), int(sep), int(dmp), int(mvc), int(inplace))
+    opts = PlanOpts(int(fusion), int(sep), int(dmp), int(mvc), int(inplace), int(max_versions), int(attn_head_dim),
+                    int(append_max_rows), int(prologue_max_rows), int(prologue_max_k), int(prologue_k_multiple))
     _check(_lib.sod2_plan(g.ptr, r.ptr, C.byref(opts), C.byref(out)))
     p = Plan(out, keep=(g, r))
     p.graph = g

@@ -174,6 +174,18 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
           dims.n = 0;
           for (const CompiledExpr& d : p.cshape[t]) { dims.push_back(d.eval(b.atom_vals)); n *= dims.back(); }
         }
+        if (gr.versions > 1) {
+          // Section 4.2: of the code versions of a fused group with unproven broadcast pairs, the one that holds for
+          // the bound symbols; per pair 'e' equal extents, 'a' the first operand's is 1 (broadcast), 'b' the second's
+          std::string v;
+          for (const Group::Pair& pr : gr.unproven) {
+            const auto &ca = p.cshape[pr.a], &cb = p.cshape[pr.b];
+            const int64_t x = pr.k <= (int)ca.size() ? ca[ca.size() - pr.k].eval(b.atom_vals) : 1;
+            const int64_t y = pr.k <= (int)cb.size() ? cb[cb.size() - pr.k].eval(b.atom_vals) : 1;
+            v += x == y ? 'e' : (x == 1 ? 'a' : 'b');
+          }
+          b.versions[gr.gid] = v;
+        }
         for (int n_op : gr.ops) {                       // a CACHEAPPEND group, or appends inside an attention group
           if (G.ops[n_op].kind != SOD2_OP_CACHEAPPEND) continue;
           int tc = G.ops[n_op].out[0];
@@ -326,6 +338,8 @@ std::string BindResult::dump(const Plan& p) const {
     const Item& it = p.items[steps[k]];
     out += "step " + std::to_string(k) + " " + (it.is_group ? "g" : "c") + std::to_string(it.ref) + "\n";
   }
+  for (const auto& kv : versions)
+    out += "version g" + std::to_string(kv.first) + " " + kv.second + " of " + std::to_string(p.groups.at(kv.first).versions) + "\n";
   for (const auto& kv : dims) {
     out += "t" + std::to_string(kv.first) + " dims=[";
     for (size_t i = 0; i < kv.second.size(); ++i) { if (i) out += " "; out += std::to_string(kv.second[i]); }

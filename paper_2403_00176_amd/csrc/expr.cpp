@@ -8,7 +8,13 @@
 
 namespace sod2 {
 namespace {
-struct AtomDef { int kind; std::string sym; std::shared_ptr<Expr> inner; int64_t c; };  // 0 sym 1 floordiv 2 mod
+// kind: 0 symbol, 1 floordiv(inner, c), 2 mod(inner, c), 3 bcast(inner, inner2): the extent two aligned dims broadcast to
+struct AtomDef { int kind; std::string sym; std::shared_ptr<Expr> inner; int64_t c; std::shared_ptr<Expr> inner2; };
+int64_t bcast_value(int64_t a, int64_t b, const std::string& what) {
+  if (a == b || b == 1) return a;
+  if (a == 1) return b;
+  throw Error(SOD2_ERR_SHAPE_MISMATCH, "extents " + std::to_string(a) + " and " + std::to_string(b) + " do not broadcast (" + what + ")");
+}
 std::map<std::string, AtomDef>& atoms() { static std::map<std::string, AtomDef> a; return a; }
 std::mutex& atoms_mu() { static std::mutex m; return m; }
 
@@ -32,7 +38,7 @@ void prune(std::map<Expr::Mono, int64_t>& t) {
 
 Expr Expr::constant(int64_t c) { Expr e; if (c) e.terms[Mono()] = c; return e; }
 Expr Expr::symbol(const std::string& name) {
-  put_atom(name, AtomDef{0, name, nullptr, 0});
+  put_atom(name, AtomDef{0, name, nullptr, 0, nullptr});
   Expr e; e.terms[Mono{name}] = 1; return e;
 }
 Expr Expr::parse(const std::string& text) {
@@ -113,7 +119,18 @@ Expr Expr::floordiv(int64_t c) const {
     if (d.kind == 1) return d.inner->floordiv(d.c * c);        // floor(floor(e/a)/b) = floor(e/(a*b))
   }
   std::string name = "floordiv(" + str() + ", " + std::to_string(c) + ")";
-  put_atom(name, AtomDef{1, "", std::make_shared<Expr>(*this), c});
+  put_atom(name, AtomDef{1, "", std::make_shared<Expr>(*this), c, nullptr});
+  Expr r; r.terms[Mono{name}] = 1; return r;
+}
+Expr Expr::bcast(const Expr& o) const {
+  if (*this == o) return *this;
+  if (is_const() && const_value() == 1) return o;
+  if (o.is_const() && o.const_value() == 1) return *this;
+  if (is_const() && o.is_const()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "cannot broadcast " + str() + " with " + o.str());
+  const bool first = str() <= o.str();
+  const Expr &a = first ? *this : o, &b = first ? o : *this;
+  std::string name = "bcast(" + a.str() + ", " + b.str() + ")";
+  put_atom(name, AtomDef{3, "", std::make_shared<Expr>(a), 0, std::make_shared<Expr>(b)});
   Expr r; r.terms[Mono{name}] = 1; return r;
 }
 Expr Expr::mod(int64_t c) const {
@@ -123,7 +140,7 @@ Expr Expr::mod(int64_t c) const {
   if (all) return Expr();
   if (is_const()) return Expr::constant(floor_mod(const_value(), c));
   std::string name = "mod(" + str() + ", " + std::to_string(c) + ")";
-  put_atom(name, AtomDef{2, "", std::make_shared<Expr>(*this), c});
+  put_atom(name, AtomDef{2, "", std::make_shared<Expr>(*this), c, nullptr});
   Expr r; r.terms[Mono{name}] = 1; return r;
 }
 bool Expr::exact_div(const Expr& o, Expr* q) const {
@@ -157,7 +174,7 @@ int64_t Expr::eval(const std::map<std::string, int64_t>& env) const {
         v *= it->second;
       } else {
         int64_t inner = d.inner->eval(env);
-        v *= (d.kind == 1) ? floor_div(inner, d.c) : floor_mod(inner, d.c);
+        v *= d.kind == 3 ? bcast_value(inner, d.inner2->eval(env), a) : ((d.kind == 1) ? floor_div(inner, d.c) : floor_mod(inner, d.c));
       }
     }
     total += v;
@@ -176,12 +193,13 @@ int ExprCompiler::intern(const std::string& name) {
   auto it = index.find(name);
   if (it != index.end()) return it->second;
   const AtomDef& d = atom_of(name);
-  Atom a{d.kind, -1, d.c, CompiledExpr()};
+  Atom a{d.kind, -1, d.c, CompiledExpr(), CompiledExpr(), name};
   if (d.kind == 0) {
     for (size_t i = 0; i < symbols.size(); ++i) if (symbols[i] == d.sym) a.sym = (int)i;
     if (a.sym < 0) throw Error(SOD2_ERR_INVALID_ARG, "symbol without a declaration: " + d.sym);
   } else {
     a.inner = compile(*d.inner);                   // its atoms get smaller indices than this one
+    if (d.kind == 3) a.inner2 = compile(*d.inner2);
   }
   atoms.push_back(a);
   index[name] = (int)atoms.size() - 1;
@@ -202,7 +220,7 @@ void ExprCompiler::atom_values(const std::vector<int64_t>& sv, std::vector<int64
     const Atom& a = atoms[i];
     if (a.kind == 0) { (*out)[i] = sv[a.sym]; continue; }
     int64_t inner = a.inner.eval(*out);
-    (*out)[i] = a.kind == 1 ? floor_div(inner, a.c) : floor_mod(inner, a.c);
+    (*out)[i] = a.kind == 3 ? bcast_value(inner, a.inner2.eval(*out), a.name) : (a.kind == 1 ? floor_div(inner, a.c) : floor_mod(inner, a.c));
   }
 }
 

@@ -21,7 +21,7 @@ struct Error : std::runtime_error {
 
 // ---------------------------------------------------------------------------------------------
 // Expressions: polynomials with integer coefficients over atoms (symbols, unsimplified floordiv /
-// mod).  These are the "operation-inferred constants" of the RDP domain (Section 4.1, V').
+// mod, and bcast(a, b): the extent two unrelated dims broadcast to, checked when the symbols are bound).  These are the "operation-inferred constants" of the RDP domain (Section 4.1, V').
 // ---------------------------------------------------------------------------------------------
 struct Expr {
   typedef std::vector<std::string> Mono;           // sorted atom names
@@ -44,6 +44,7 @@ struct Expr {
   Expr operator*(const Expr& o) const;
   Expr floordiv(int64_t c) const;
   Expr mod(int64_t c) const;
+  Expr bcast(const Expr& o) const;                 // extent of the broadcast of two aligned dims (Section 4.2, Fig. 4)
   bool exact_div(const Expr& o, Expr* q) const;    // o a single term dividing every term
   int64_t eval(const std::map<std::string, int64_t>& env) const;
 };
@@ -64,7 +65,7 @@ struct CompiledExpr {
   }
 };
 struct ExprCompiler {
-  struct Atom { int kind; int sym; int64_t c; CompiledExpr inner; };   // 0 symbol, 1 floordiv, 2 mod
+  struct Atom { int kind; int sym; int64_t c; CompiledExpr inner, inner2; std::string name; };   // 0 symbol, 1 floordiv, 2 mod, 3 bcast
   std::vector<std::string> symbols;                // position = index of the value handed to atom_values
   std::vector<Atom> atoms;
   std::map<std::string, int> index;
@@ -172,6 +173,8 @@ struct Group {
   std::vector<int> ins;                            // static bases read from outside
   std::vector<int> also;                           // further results of the same operator (TopK: the indices)
   int versions = 1;                                // code versions of the fused loop nest (Fig. 4; 1: every pair proven)
+  struct Pair { int a, b, k; };                    // operands of a binary member and the aligned dim, counted from the last
+  std::vector<Pair> unproven;
 };
 struct Item {
   bool is_group = true;
@@ -185,7 +188,14 @@ struct Plan {
   std::shared_ptr<Rdp> named;                      // analysis with named EDO extents, owned (see Rdp::named_edo)
   std::vector<int> exec_ops;                       // NonZero operators in the node order
   bool execution_determined(int t) const;          // nac in the paper's lattice: unresolved or in an execution symbol
-  sod2_plan_opts opts{1, 1, 1, 1, 1};
+  sod2_plan_opts opts{1, 1, 1, 1, 1, 0, 0, 0, 0, 0, 0};
+  // the limits of R4 and R6-R8 with the defaults (what this library's kernels fuse) filled in
+  int max_versions() const { return opts.max_versions > 0 ? opts.max_versions : 8; }
+  int attn_head_dim() const { return opts.attn_head_dim > 0 ? opts.attn_head_dim : 64; }
+  int append_max_rows() const { return opts.append_max_rows > 0 ? opts.append_max_rows : 4; }
+  int prologue_max_rows() const { return opts.prologue_max_rows > 0 ? opts.prologue_max_rows : 8; }
+  int prologue_max_k() const { return opts.prologue_max_k > 0 ? opts.prologue_max_k : 1024; }
+  int prologue_k_multiple() const { return opts.prologue_k_multiple > 0 ? opts.prologue_k_multiple : 64; }
   std::vector<int> order;
   std::vector<char> folded, view;
   std::map<int, Group> groups;
@@ -282,6 +292,7 @@ struct BindResult {
   std::set<int> dead_ops;
   std::map<int, std::pair<int64_t, int64_t>> session;   // session input -> (offset, bytes) at the arena bottom
   std::map<int, int> session_root;                 // session tensor -> the session input whose slot it occupies
+  std::map<int, std::string> versions;             // multi-version group -> the version the bound symbols select
   int64_t session_bytes = 0;
   int64_t arena_bytes = 0, peak_live = 0;
   int undecided = 0;                               // Switches met without a given decision

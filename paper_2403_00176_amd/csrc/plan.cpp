@@ -11,16 +11,19 @@
 //  R3 LayerNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
 //     OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
-//  R4 other elementwise operators chain while every aligned dim pair is proven equal or 1 (Fig. 4);
+//  R4 other elementwise operators chain (up to 8).  A dim pair of the two operands of a binary member is proven when
+//     RDP shows the extents equal or one of them 1: one form of the fused loop nest.  A pair of two resolved but
+//     unrelated extents doubles the number of code versions (Fig. 4), one of which is selected at bind; the chain
+//     stops before the member that would need more than max_versions (8) and at an unresolved extent;
 //  R5 group id = smallest member id; groups are ordered by the node-order position of their
 //     last member;
 //  R6 attention: a GEMM group of MatMul [+ Mul by a host scalar] read by one Softmax alone, whose
 //     result is the first operand of one MatMul alone leading a GEMM group of MatMul [+ Transpose]:
 //     the three become one ATTENTION group (scores and probabilities never reach memory); bf16
-//     tensors and a known head size of 64 only (what the fused kernel is written for).
+//     tensors and the known head size the options state (64: what the fused kernel is written for).
 //  R8 cache append inside attention: when the key and the value operand of an ATTENTION group are,
 //     through views only and with no other reader, the results of two CacheAppend operators that
-//     each append a known number of at most 4 bf16 rows (the decode step), their CACHEAPPEND groups
+//     each append a known number of at most append_max_rows (4) bf16 rows (the decode step), their CACHEAPPEND groups
 //     join the ATTENTION group: its kernel writes the new rows into the session slots itself.
 // Partition: cut around control operators and NonZero, after a group with a nac output, wherever
 // at most one arena tensor is live, and every 14 items.  Order inside a sub-graph: the sequence
@@ -55,11 +58,21 @@ bool shape_equal(const LS& a, const LS& b) {
 bool pair_proven(const LV& a, const LV& b) {
   return a.val() && b.val() && (a.e == b.e || a.is_c(1) || b.is_c(1));
 }
-bool bcast_proven(const LS& out, const LS& other) {
-  if (!out.is_list() || !other.is_list() || other.d.size() > out.d.size()) return false;
-  size_t pad = out.d.size() - other.d.size();
-  for (size_t i = 0; i < out.d.size(); ++i)
-    if (!pair_proven(out.d[i], i < pad ? LV::c(1) : other.d[i - pad])) return false;
+// Dim pairs of the two operands of a binary elementwise operator that RDP cannot prove equal or 1, the dim counted
+// from the last; none for a unary operator; false when an extent is unresolved
+bool unproven_pairs(const Rdp& R, const Op& op, std::vector<Group::Pair>* out) {
+  out->clear();
+  if (op.in.size() != 2) return true;
+  const LS &sa = R.S[op.in[0]], &sb = R.S[op.in[1]];
+  if (!sa.is_list() || !sb.is_list()) return false;
+  const size_t r = std::max(sa.d.size(), sb.d.size());
+  for (size_t k = 1; k <= r; ++k) {
+    const LV x = k <= sa.d.size() ? sa.d[sa.d.size() - k] : LV::c(1);
+    const LV y = k <= sb.d.size() ? sb.d[sb.d.size() - k] : LV::c(1);
+    if (pair_proven(x, y)) continue;
+    if (!x.val() || !y.val()) return false;
+    out->push_back({op.in[0], op.in[1], (int)k});
+  }
   return true;
 }
 int64_t align_up(int64_t n) { return (n + 255) / 256 * 256; }
@@ -214,17 +227,24 @@ void Plan::build() {
     } else if (is_eltwise(op.kind)) {
       std::vector<int> chain{n};
       int cur = op.out[0];
+      std::vector<Group::Pair> pairs;
+      if (!unproven_pairs(R, op, &pairs)) pairs.clear();    // of the seed itself: they count once it has company
       while (opts.fusion && chain.size() < 8) {
         int c = sole_consumer(cur);
         if (c < 0 || group_of_op[c] >= 0 || !is_eltwise(G.ops[c].kind)) break;
         const Op& cop = G.ops[c];
-        if (cop.in.size() == 2 &&
-            !(bcast_proven(R.S[cop.out[0]], R.S[other(cop, cur)]) && bcast_proven(R.S[cop.out[0]], R.S[cur])))
-          break;
+        std::vector<Group::Pair> more;
+        if (!unproven_pairs(R, cop, &more) || (1LL << (pairs.size() + more.size())) > std::max(max_versions(), 1)) break;
+        pairs.insert(pairs.end(), more.begin(), more.end());
         chain.push_back(c);
         cur = cop.out[0];
       }
       new_group(G_ELTWISE, chain);
+      if (chain.size() > 1 && !pairs.empty()) {
+        Group& gr = groups[*std::min_element(chain.begin(), chain.end())];
+        gr.versions = 1 << pairs.size();
+        gr.unproven = pairs;
+      }
     } else {
       throw Error(SOD2_ERR_UNSUPPORTED, std::string("no grouping rule for ") + op_name(op.kind));
     }
@@ -249,7 +269,7 @@ void Plan::build() {
         if (ca.kind != SOD2_OP_CACHEAPPEND || group_of_op[pr] < 0 || groups[group_of_op[pr]].kind != G_CACHEAPPEND) return -1;
         const LS& rows = R.S[ca.in[1]];
         if (G.tensors[t].dtype != SOD2_BF16 || !rows.is_list() || rows.d.empty() || !rows.d[0].val() ||
-            !rows.d[0].e.is_const() || rows.d[0].e.const_value() > 4)
+            !rows.d[0].e.is_const() || rows.d[0].e.const_value() > append_max_rows())
           return -1;
         return pr;
       }
@@ -271,7 +291,7 @@ void Plan::build() {
       bool bf = true;
       for (int t : {mm1.in[0], mm1.in[1], G.ops[c2].in[1], x, y, g2.out}) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
       const LS &sq = R.S[mm1.in[0]], &sv = R.S[G.ops[c2].in[1]];
-      if (!bf || !sq.is_list() || !sv.is_list() || sq.d.empty() || sv.d.empty() || !sq.d.back().is_c(64) || !sv.d.back().is_c(64))
+      if (!bf || !sq.is_list() || !sv.is_list() || sq.d.empty() || sv.d.empty() || !sq.d.back().is_c(attn_head_dim()) || !sv.d.back().is_c(attn_head_dim()))
         continue;
       Group gr;
       gr.kind = G_ATTENTION;
@@ -317,7 +337,7 @@ void Plan::build() {
       if (!known) continue;
       int64_t kdim = sx.d.back().e.const_value(), rows = 1;
       for (size_t i = 0; i + 1 < sx.d.size(); ++i) rows *= sx.d[i].e.const_value();
-      if (kdim > 1024 || kdim % 64 != 0 || rows > 8) continue;
+      if (kdim > prologue_max_k() || kdim % prologue_k_multiple() != 0 || rows > prologue_max_rows()) continue;
       Group gr;
       gr.kind = G_GEMM;
       gr.chain = gm.chain;                       // the contraction stays the seed; the LayerNorm is its prologue
@@ -615,7 +635,15 @@ std::string Plan::dump() const {
       out += "g" + std::to_string(gr.gid) + " " + group_kind_name(gr.kind) + " ops=[" + join(gr.ops, "") + "] out=t" +
              std::to_string(gr.out);
       for (int t : gr.also) out += " also=t" + std::to_string(t);
-      out += " ins=[" + join(gr.ins, "t") + "]\n";
+      out += " ins=[" + join(gr.ins, "t") + "]";
+      if (gr.versions > 1) {
+        out += " versions=" + std::to_string(gr.versions) + " unproven=[";
+        for (size_t k = 0; k < gr.unproven.size(); ++k)
+          out += std::string(k ? " " : "") + "t" + std::to_string(gr.unproven[k].a) + "~t" + std::to_string(gr.unproven[k].b) + "@" +
+                 std::to_string(gr.unproven[k].k);
+        out += "]";
+      }
+      out += "\n";
     } else {
       out += "c" + std::to_string(it.ref) + " " + op_name(g->ops[it.ref].kind) + "\n";
     }

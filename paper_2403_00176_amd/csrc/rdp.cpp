@@ -122,7 +122,9 @@ LV bcast_dim(const LV& a, const LV& b) {
     if (b.is_c(1)) return a;
     if (a.e.is_const() && b.e.is_const())
       throw Error(SOD2_ERR_SHAPE_MISMATCH, "cannot broadcast " + a.e.str() + " with " + b.e.str());
-    return LV::nac();
+    // unproven: equal, or one of them 1 (Fig. 4); the extent is still a function of the symbols -- an
+    // operation-inferred constant, evaluated and checked when they are bound
+    return LV::of(a.e.bcast(b.e));
   }
   // a known constant other than 1 fixes the output whatever the other side turns out to be
   if (a.val() && a.e.is_const() && a.e.const_value() != 1) return a;

@@ -3,7 +3,7 @@ import numpy as np
 import pytest
 
 from oracle import rdp as R, plan as P, arena as A, execute
-from workloads import configs, GraphBuilder
+from workloads import configs, GraphBuilder, rng
 
 pytestmark = pytest.mark.gpu
 
@@ -201,3 +201,44 @@ def test_topk_router(S, dtype):
         assert rel_err(got["gates"], ref.values[g.tensor_id("gates")]) <= tol
         if clear.all():
             assert rel_err(got["rows"], ref.values[g.tensor_id("rows")]) <= tol
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_multi_version_fused_chain(S_lib, dtype):
+    """Fig. 4 on the GPU: Sigmoid(A) + B, * 2 with nothing relating A's extents to B's.  The chain runs as ONE
+    kernel (8 code versions planned; the broadcast strides of the version that holds are selected at bind) and gives
+    the oracle's values in every case: equal extents, A broadcast in some dims, B broadcast in others; the same graph
+    planned without fusion runs three kernels and gives the same values; symbols that do not broadcast are refused."""
+    import torch
+    from tests.test_host_parity import _multi_version_graph
+    from paper_2403_00176_amd.session import Session, to_host
+    S = S_lib
+    g = _multi_version_graph(dtype=dtype)
+    po = P.build_plan(g, R.RDP(g).analyse())
+    a_id, b_id, out = g.tensor_id("A"), g.tensor_id("B"), g.outputs()[0]
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    runs = {}
+    for fusion in (1, 0):
+        ses = Session(g, fusion=fusion)
+        ses.upload_weights({})
+        for k, sym in enumerate((dict(I=37, J=70, K=129, P=37, Q=70, R=129), dict(I=37, J=70, K=129, P=1, Q=70, R=1),
+                                 dict(I=1, J=70, K=1, P=53, Q=1, R=129), dict(I=37, J=1, K=129, P=37, Q=90, R=1),
+                                 dict(I=5, J=3, K=600, P=5, Q=3, R=600))):
+            ins = {a_id: rng.normal(800 + k, (sym["P"], sym["Q"], sym["R"])), b_id: rng.normal(900 + k, (sym["I"], sym["J"], sym["K"]))}
+            b = ses.bind(sym)
+            if fusion:
+                assert S.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+            outs = ses.alloc_outputs(ses.output_shapes(b))
+            ses.run(b, ses.upload_inputs(ins), outs)
+            torch.cuda.synchronize()
+            ref = execute.run(g, po.order, {}, ins).values[out]
+            got = to_host(outs[0])
+            assert got.shape == ref.shape
+            assert np.abs(got - ref).max() / np.abs(ref).max() <= tol, (fusion, sym)
+            launches = [e for e in S.sod2_run_trace(b) if e["is_group"]]
+            assert len(launches) == (1 if fusion else 3)
+            runs[(fusion, k)] = got
+    ses = Session(g)
+    with pytest.raises(S.Sod2Error) as e:
+        ses.bind(dict(I=3, J=4, K=5, P=2, Q=4, R=5))
+    assert e.value.code == -3

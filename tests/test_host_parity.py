@@ -191,3 +191,64 @@ def test_structured_queries_agree_with_the_oracle(cfg):
             assert q["where"] == "external"
     with pytest.raises(S.Sod2Error):
         S.sod2_binding_query_tensor(b, len(w.graph.tensors))
+
+
+def _multi_version_graph(dimsA=("P", "Q", "R"), dtype="f32"):
+    """Sigmoid(A) + B, then * 2: the example of Fig. 4 with one more member; nothing relates A's extents to B's."""
+    b = GraphBuilder([(s, 1, 600) for s in "IJKPQR"])
+    A = b.input("A", dtype, list(dimsA))
+    Bt = b.input("B", dtype, ["I", "J", "K"])
+    y = b.op("Mul", [b.op("Add", [b.op("Sigmoid", [A]), Bt]), b.const("two", 2.0, "f32")])
+    b.mark_output(y, "y")
+    return b.build()
+
+
+def test_multi_version_groups_match_the_oracle():
+    """Section 4.2: a fused chain over extents RDP cannot relate is planned with 2 code versions per unproven dim pair
+    (Fig. 4) and the version is selected at bind.  RDP maps (bcast extents), groups, version counts, the selected
+    version and the refusal of symbols that do not broadcast: library == oracle."""
+    for dimsA in (("I", 1, 1), ("I", "Q", 1), ("P", "Q", 1), ("P", "Q", "R")):
+        gd = _multi_version_graph(dimsA)
+        g = S.sod2_graph_build(gd)
+        r = S.sod2_rdp_infer(g)
+        ro = R.RDP(gd).analyse()
+        assert S.sod2_rdp_dump(r) == R.dump(ro)
+        for mv in (0, 1, 2, 4):
+            p = S.sod2_plan(g, r, max_versions=mv)
+            po = P.build_plan(gd, ro, P.Opts(max_versions=mv or 8))
+            assert S.sod2_plan_dump(p) == P.dump(po), (dimsA, mv)
+            q = S.sod2_plan_query_group(p, 0)
+            assert q["versions"] == po.groups[q["gid"]].versions
+            for sym in (dict(I=3, J=4, K=5, P=3, Q=4, R=5), dict(I=3, J=4, K=5, P=1, Q=1, R=1),
+                        dict(I=1, J=4, K=1, P=3, Q=4, R=5), dict(I=3, J=1, K=5, P=3, Q=4, R=1)):
+                assert S.sod2_binding_dump(S.sod2_bind(p, sym)) == A.dump(A.bind(po, sym))
+    gd = _multi_version_graph()
+    g = S.sod2_graph_build(gd)
+    r = S.sod2_rdp_infer(g)
+    p = S.sod2_plan(g, r)
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_bind(p, dict(I=3, J=4, K=5, P=2, Q=4, R=5))
+    assert e.value.code == -3                       # SOD2_ERR_SHAPE_MISMATCH
+
+
+def test_backend_limits_of_the_fusion_rules_are_options():
+    """R6-R8 take their limits (fused head size, rows appended inside attention, LayerNorm-prologue rows / extent)
+    from the plan options on both sides: other values change the groups alike."""
+    dec = configs.decoder(5, layers=2, hidden=128, heads=2, ffn=256, vocab=64, p_range=(4, 12), t_max=6)
+    enc = configs.config2(1, layers=1)
+    for gd in (dec.decode, dec.prefill, enc.graph):
+        g = S.sod2_graph_build(gd)
+        r = S.sod2_rdp_infer(g)
+        ro = R.RDP(gd).analyse()
+        base = S.sod2_plan_dump(S.sod2_plan(g, r))
+        assert base == P.dump(P.build_plan(gd, ro))
+        variants = [(dict(attn_head_dim=32), dict(attn_head_dims=(32,))),
+                    (dict(append_max_rows=1, prologue_max_rows=1), dict(append_max_rows=1, prologue_max_rows=1)),
+                    (dict(prologue_max_k=64), dict(prologue_max_k=64)),
+                    (dict(prologue_k_multiple=256), dict(prologue_k_multiple=256))]
+        changed = 0
+        for lib_opts, ora_opts in variants:
+            d = S.sod2_plan_dump(S.sod2_plan(g, r, **lib_opts))
+            assert d == P.dump(P.build_plan(gd, ro, P.Opts(**ora_opts))), lib_opts
+            changed += d != base
+        assert changed >= 1

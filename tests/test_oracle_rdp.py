@@ -123,15 +123,79 @@ def test_fig4_fusion_versions_match_paper():
     B = [I, J, K]
     assert R.fused_versions([R.NAC] * 3, B) == int(gold["unknown_A"])
     assert R.fused_versions([I, Expr.const(1), Expr.const(1)], B) == int(gold["rdp_I_1_1"])
-    # and through the analysis + fusion rule: Sigmoid(A) + B fuse into one group only with the RDP result
-    for dimsA, ngroups in ((["I", 1, 1], 1), (["P", "Q", "R"], 2)):
+    # and through the analysis + fusion rule.  With the RDP result (A = [I, 1, 1]) the pair fuses into one group with
+    # a single code version; with nothing known about A it still fuses, as the paper's second option, with the 8
+    # versions the figure counts; 2 and 4 versions in between; with multi-versioning off (max_versions = 1) or a cap
+    # below the need the pair stays two groups (the paper's first option: no fusion)
+    def graph(dimsA):
         b = GraphBuilder([(s, 1, 9) for s in "IJKPQR"])
         A = b.input("A", "f32", dimsA)
         Bt = b.input("B", "f32", ["I", "J", "K"])
         b.mark_output(b.op("Add", [b.op("Sigmoid", [A]), Bt]))
-        g = b.build()
+        return b.build()
+    for dimsA, versions in ((["I", 1, 1], int(gold["rdp_I_1_1"])), (["I", "Q", 1], 2), (["P", "Q", 1], 4),
+                            (["P", "Q", "R"], int(gold["unknown_A"]))):
+        g = graph(dimsA)
         p = plan.build_plan(g, analyse(g))
-        assert len(p.groups) == ngroups
+        assert len(p.groups) == 1 and p.groups[0].versions == versions, dimsA
+        assert len(p.groups[0].unproven) == {1: 0, 2: 1, 4: 2, 8: 3}[versions]
+        p1 = plan.build_plan(g, analyse(g), plan.Opts(max_versions=1))
+        assert len(p1.groups) == (1 if versions == 1 else 2)
+        p4 = plan.build_plan(g, analyse(g), plan.Opts(max_versions=4))
+        assert len(p4.groups) == (1 if versions <= 4 else 2)
+    # a rank-4 pair with four unrelated extents would need 16 versions: beyond the cap, not fused
+    b = GraphBuilder([(s, 1, 9) for s in "IJKLPQRS"])
+    A = b.input("A", "f32", ["P", "Q", "R", "S"])
+    Bt = b.input("B", "f32", ["I", "J", "K", "L"])
+    b.mark_output(b.op("Add", [b.op("Sigmoid", [A]), Bt]))
+    g = b.build()
+    assert len(plan.build_plan(g, analyse(g)).groups) == 2
+
+
+def test_unproven_broadcast_extent_is_an_operation_inferred_constant():
+    """Two unrelated symbolic extents broadcast to bcast(a, b): resolved once the symbols are bound (the common value,
+    or the other one when one is 1), an error when they cannot broadcast; the version selected at bind says which
+    case held, and the values equal the plain operator-by-operator run whatever the version."""
+    from oracle import arena
+    from oracle.expr import BroadcastMismatch
+    b = GraphBuilder([(s, 1, 9) for s in "IJKPQR"])
+    A = b.input("A", "f32", ["P", "Q", "R"])
+    Bt = b.input("B", "f32", ["I", "J", "K"])
+    out = b.mark_output(b.op("Mul", [b.op("Add", [b.op("Sigmoid", [A]), Bt]), b.const("two", 2.0, "f32")]))
+    g = b.build()
+    r = analyse(g)
+    assert R.fmt_list(r.S[out]) == "[e:bcast(I, P), e:bcast(J, Q), e:bcast(K, R)]"
+    I, P = Expr.sym("I"), Expr.sym("P")
+    e = I.bcast(P)
+    assert e == P.bcast(I) and e.kind() == "opinf"
+    assert I.bcast(I) == I and I.bcast(Expr.const(1)) == I and Expr.const(1).bcast(P) == P
+    assert [e.eval({"I": i, "P": p}) for i, p in ((5, 5), (5, 1), (1, 7))] == [5, 5, 7]
+    with pytest.raises(BroadcastMismatch):
+        e.eval({"I": 5, "P": 3})
+    with pytest.raises(BroadcastMismatch):
+        Expr.const(3).bcast(Expr.const(4))
+    p = plan.build_plan(g, r)
+    assert len(p.groups) == 1 and p.groups[0].versions == 8 and len(p.groups[0].ops) == 3
+    rs = np.random.RandomState(5)
+    seen = set()
+    for sym in (dict(I=3, J=4, K=5, P=3, Q=4, R=5), dict(I=3, J=4, K=5, P=1, Q=4, R=1), dict(I=1, J=4, K=5, P=6, Q=1, R=5),
+                dict(I=3, J=1, K=1, P=3, Q=7, R=2)):
+        bd = arena.bind(p, sym)
+        seen.add(bd.versions[0])
+        a = rs.randn(sym["P"], sym["Q"], sym["R"])
+        bb = rs.randn(sym["I"], sym["J"], sym["K"])
+        res = execute.run(g, p.order, {}, {A: a, Bt: bb})
+        ref = ((1.0 / (1.0 + np.exp(-a.astype(np.float32).astype(np.float64)))).astype(np.float32).astype(np.float64)
+               + bb.astype(np.float32).astype(np.float64)).astype(np.float32).astype(np.float64) * 2.0
+        assert bd.dims[out] == list(ref.shape) == list(res.values[out].shape)
+        assert np.allclose(res.values[out], ref, rtol=1e-6)
+        # letters: per unproven pair (last dim first) e = equal, a = the Sigmoid result is broadcast, b = B is
+        want = "".join("e" if x == y else ("a" if x == 1 else "b")
+                       for x, y in ((sym["R"], sym["K"]), (sym["Q"], sym["J"]), (sym["P"], sym["I"])))
+        assert bd.versions[0] == want
+    assert len(seen) == 4
+    with pytest.raises(BroadcastMismatch):
+        arena.bind(p, dict(I=3, J=4, K=5, P=2, Q=4, R=5))
 
 
 def test_backward_add_does_not_invent_a_dim():
