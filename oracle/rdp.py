@@ -445,13 +445,18 @@ class RDP:
         for s, e, a in zip(st, en, ax):
             a = a.const_value() % len(x)
             D = x[a]
-            if not (is_expr(s) and s.is_const() and is_expr(e) and e.is_const()):
+            if not (is_expr(s) and is_expr(e)):
                 out[a] = NAC
                 bounds.append(None)
                 continue
-            s, e = s.const_value(), e.const_value()
-            lo = d_add(D, C(s)) if s < 0 else C(s)
-            hi = D if e >= INT_MAX else (d_add(D, C(e)) if e < 0 else C(e))
+            # a constant bound follows the usual conventions (negative: counted from the end; INT_MAX: the end);
+            # a computed one -- an expression carried by the value map (Section 3: input shape and value determined
+            # output shape) -- is a position as it stands: 0 <= start <= end <= extent is checked when it is bound
+            lo = (d_add(D, s) if s.const_value() < 0 else s) if s.is_const() else s
+            if e.is_const():
+                hi = D if e.const_value() >= INT_MAX else (d_add(D, e) if e.const_value() < 0 else e)
+            else:
+                hi = e
             out[a] = d_sub(hi, lo)
             bounds.append((lo, hi))
         v = UNDEF

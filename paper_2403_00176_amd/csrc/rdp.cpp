@@ -280,14 +280,19 @@ struct Analyser {
           size_t a = norm_axis(ax.d[k].e.const_value(), x.d.size());
           const LV &s = st.d[k], &e = en.d[k];
           const LV& D = x.d[a];
-          if (!(s.val() && s.e.is_const() && e.val() && e.e.is_const())) {
+          if (!(s.val() && e.val())) {
             o.d[a] = LV::nac();
             if (k == 0) bad0 = true;
             continue;
           }
-          int64_t sv = s.e.const_value(), ev = e.e.const_value();
-          LV lo = sv < 0 ? add(D, LV::c(sv)) : LV::c(sv);
-          LV hi = ev >= kIntMax ? D : (ev < 0 ? add(D, LV::c(ev)) : LV::c(ev));
+          // a constant bound follows the usual conventions (negative: from the end; INT_MAX: the end); a computed one
+          // (an expression from the value map) is a position as it stands, range-checked when it is bound
+          LV lo = s, hi = e;
+          if (s.e.is_const() && s.e.const_value() < 0) lo = add(D, s);
+          if (e.e.is_const()) {
+            const int64_t ev = e.e.const_value();
+            hi = ev >= kIntMax ? D : (ev < 0 ? add(D, e) : e);
+          }
           o.d[a] = sub(hi, lo);
           if (k == 0) { have0 = true; lo0 = lo; hi0 = hi; }
         }

@@ -208,14 +208,18 @@ struct Builder {
           v.dims.erase(v.dims.begin() + ax);
           v.strides.erase(v.strides.begin() + ax);
         } else if (op.kind == SOD2_OP_SLICE) {
-          const Tensor &st = G.tensors[op.in[1]], &en = G.tensors[op.in[2]], &ax = G.tensors[op.in[3]];
-          if (!st.has_data || !en.has_data || !ax.has_data)
-            throw Error(SOD2_ERR_UNSUPPORTED, "Slice bounds must be host constants");
-          for (size_t k = 0; k < ax.idata.size(); ++k) {
+          // bounds and axes as RDP carries them: host constants, or expressions computed from shapes (value maps),
+          // evaluated at the bound symbols
+          const LS &st = p.rdp->V[op.in[1]], &en = p.rdp->V[op.in[2]], &ax = p.rdp->V[op.in[3]];
+          if (!st.resolved() || !en.resolved() || !ax.resolved() || st.d.size() != ax.d.size() || en.d.size() != ax.d.size())
+            throw Error(SOD2_ERR_UNSUPPORTED, "Slice bounds must be known to RDP (host constants or values computed from shapes)");
+          for (size_t k = 0; k < ax.d.size(); ++k) {
             int64_t r = (int64_t)in.dims.size();
-            int64_t a = ((ax.idata[k] % r) + r) % r, D = in.dims[a];
-            int64_t s = st.idata[k] < 0 ? D + st.idata[k] : st.idata[k];
-            int64_t e = en.idata[k] >= kIntMax ? D : (en.idata[k] < 0 ? D + en.idata[k] : en.idata[k]);
+            int64_t a = ((ax.d[k].e.eval(b.env) % r) + r) % r, D = in.dims[a];
+            const int64_t sv = st.d[k].e.eval(b.env), ev = en.d[k].e.eval(b.env);
+            const bool sc = st.d[k].e.is_const(), ec = en.d[k].e.is_const();
+            int64_t s = (sc && sv < 0) ? D + sv : sv;
+            int64_t e = (ec && ev >= kIntMax) ? D : ((ec && ev < 0) ? D + ev : ev);
             if (s < 0 || e > D || s > e) throw Error(SOD2_ERR_INVALID_ARG, "Slice bounds outside the tensor");
             v.off += s * in.strides[a];
             v.dims[a] = e - s;

@@ -242,3 +242,38 @@ def test_multi_version_fused_chain(S_lib, dtype):
     with pytest.raises(S.Sod2Error) as e:
         ses.bind(dict(I=3, J=4, K=5, P=2, Q=4, R=5))
     assert e.value.code == -3
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_slice_with_computed_bounds(S_lib, dtype):
+    """Slices whose bounds are values computed from shapes run as views (offset and extent evaluated at bind) feeding
+    fused elementwise kernels; a bound outside the tensor is refused when the launch is prepared."""
+    import torch
+    from tests.test_shape_ops import _computed_slice_graph
+    from paper_2403_00176_amd.session import Session, to_host
+    g = _computed_slice_graph(dtype)[0]
+    po = P.build_plan(g, R.RDP(g).analyse())
+    ses = Session(g)
+    ses.upload_weights({})
+    tol = 1e-4 if dtype == "f32" else 2e-2
+    for k, sym in enumerate(({"B": 2, "L": 7, "M": 4}, {"B": 1, "L": 2, "M": 2}, {"B": 8, "L": 300, "M": 300}, {"B": 5, "L": 129, "M": 65})):
+        ins = {g.tensor_id("x"): rng.normal(700 + k, (sym["B"], sym["L"], 8)), g.tensor_id("m"): rng.normal(750 + k, (sym["M"], 8))}
+        b = ses.bind(sym)
+        assert S_lib.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {}, ins)
+        for t, o in zip(g.outputs(), outs):
+            got = to_host(o)
+            assert got.shape == ref.values[t].shape
+            assert rel_err(got, ref.values[t]) <= tol, (sym, g.tensors[t].name)
+    # M beyond L: the head slice would end outside x
+    sym = {"B": 1, "L": 4, "M": 9}
+    b = ses.bind(sym)
+    ins = {g.tensor_id("x"): rng.normal(1, (1, 4, 8)), g.tensor_id("m"): rng.normal(2, (9, 8))}
+    outs = ses.alloc_outputs(ses.output_shapes(b))
+    with pytest.raises(S_lib.Sod2Error) as e:
+        ses.run(b, ses.upload_inputs(ins), outs)
+    assert e.value.code == -1 and "Slice bounds" in str(e.value)
+    torch.cuda.synchronize()

@@ -374,3 +374,53 @@ def test_topk_two_results_one_group():
     assert S.sod2_plan_dump(pl) == P.dump(plan)
     for sym in ({"B": 5, "K": 3}, {"B": 64, "K": 16}):
         assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))
+
+
+def _computed_slice_graph(dtype="f32"):
+    """Slice whose bounds are computed from shapes (Table 2 lists Slice as input shape *and value* determined): the
+    difference of neighbouring tokens x[:, 1:L] - x[:, 0:L-1] with L read through Shape (and L - 1 made by arithmetic
+    on the value map), and the first M tokens x[:, :M] with M the extent of another input."""
+    b = GraphBuilder([("B", 1, 8), ("L", 2, 300), ("M", 1, 300)])
+    x = b.input("x", dtype, ["B", "L", 8])
+    m = b.input("m", dtype, ["M", 8])
+    L = b.op("Gather", [b.op("Shape", [x], dtype="i64"), b.const("i1", [1])], axis=0, dtype="i64")
+    Lm1 = b.op("Add", [L, b.const("minus1", [-1])], dtype="i64")
+    ax = b.const("ax1", [1])
+    late = b.op("Slice", [x, b.const("one", [1]), L, ax], hint="late")           # [B, L - 1, 8]
+    early = b.op("Slice", [x, b.const("zero", [0]), Lm1, ax], hint="early")      # [B, L - 1, 8]
+    diff = b.op("Add", [late, b.op("Mul", [early, b.const("neg", -1.0, "f32")])], hint="diff")
+    b.mark_output(diff, "diff")
+    M = b.op("Gather", [b.op("Shape", [m], dtype="i64"), b.const("i0", [0])], axis=0, dtype="i64")
+    head = b.op("Slice", [x, b.const("zero2", [0]), M, ax], hint="head")         # [B, M, 8]
+    b.mark_output(b.op("Add", [head, m]), "shifted")
+    return b.build(), late, early, head
+
+
+def test_slice_with_computed_bounds_is_lowered():
+    g, late, early, head = _computed_slice_graph()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.S[late]) == "[s:B, e:-1 + L, k:8]" == R.fmt_list(r.S[early])
+    assert R.fmt_list(r.S[head]) == "[s:B, s:M, k:8]"
+    p = P.build_plan(g, r)
+    # both slices are views, the token difference is one fused group with a single code version (the two extents
+    # are provably equal: L - 1 both times), and so is the shifted head (M against M)
+    kinds = sorted(gr.kind for gr in p.groups.values())
+    assert kinds == ["ELTWISE", "ELTWISE"] and all(gr.versions == 1 for gr in p.groups.values())
+    rs = np.random.RandomState(3)
+    for sym in ({"B": 2, "L": 7, "M": 4}, {"B": 1, "L": 2, "M": 2}, {"B": 3, "L": 33, "M": 1}):
+        xv, mv = rs.randn(sym["B"], sym["L"], 8), rs.randn(sym["M"], 8)
+        res = execute.run(g, p.order, {}, {g.tensor_id("x"): xv, g.tensor_id("m"): mv})
+        x32, m32 = xv.astype(np.float32).astype(np.float64), mv.astype(np.float32).astype(np.float64)
+        assert np.allclose(res.values[g.tensor_id("diff")], x32[:, 1:] - x32[:, :-1], atol=1e-6)
+        assert np.allclose(res.values[g.tensor_id("shifted")], x32[:, :sym["M"]] + m32, atol=1e-6)
+        bd = A.bind(p, sym)
+        for t, v in res.values.items():
+            if t in bd.dims:
+                assert bd.dims[t] == list(np.shape(v))
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    assert S.sod2_rdp_dump(lr) == R.dump(r)
+    lp = S.sod2_plan(lg, lr)
+    assert S.sod2_plan_dump(lp) == P.dump(p)
+    for sym in ({"B": 2, "L": 7, "M": 4}, {"B": 8, "L": 300, "M": 300}):
+        assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(p, sym))
