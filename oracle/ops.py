@@ -85,6 +85,18 @@ def layernorm(x, gamma, beta, eps):
     return (x - mu) / np.sqrt(var + eps) * gamma + beta
 
 
+def groupnorm(x, gamma, beta, groups, eps):
+    """GroupNormalization (Table 2), channels last: x [N, ..., C]; the C channels form ``groups`` groups of consecutive
+    channels; per sample and group, mean and biased variance over the group's channels at every position; then the
+    per-channel scale and shift."""
+    n, c = x.shape[0], x.shape[-1]
+    assert c % groups == 0
+    xs = x.reshape(n, -1, groups, c // groups)
+    mu = xs.mean(axis=(1, 3), keepdims=True)
+    var = ((xs - mu) ** 2).mean(axis=(1, 3), keepdims=True)
+    return ((xs - mu) / np.sqrt(var + eps)).reshape(x.shape) * gamma + beta
+
+
 def slice_(x, starts, ends, axes):
     idx = [slice(None)] * x.ndim
     for s, e, a in zip(starts, ends, axes):

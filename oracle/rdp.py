@@ -34,10 +34,10 @@ OP_CLASS = {
     "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
     "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS, "Range": ISVDOS, "Expand": ISVDOS,
-    "OneHot": ISVDOS, "Upsample": ISVDOS, "TopK": ISVDOS,
+    "OneHot": ISVDOS, "Upsample": ISVDOS, "TopK": ISVDOS, "GroupNorm": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
-UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm")
+UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "GroupNorm")   # result shaped like input 0
 EXEC_PREFIX = "@nz"   # name of an execution symbol: EXEC_PREFIX + operator id
 
 

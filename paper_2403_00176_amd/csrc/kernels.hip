@@ -1190,6 +1190,54 @@ hipError_t launch_row(const Launch& L, const RowArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// ---------------------------------------------------------------------------------------------
+// GroupNormalization, channels last.  One workgroup per (sample, group): its slab is s positions of cpg
+// consecutive channels, `C` elements apart.  Three walks over the slab (mean, centred sum of squares, apply):
+// the slab of one group stays in the L2 between them, and the two-pass variance matches the definition.
+// A thread handles whole positions (cpg contiguous elements), so the loads of a wave cover runs of cpg elements.
+// ---------------------------------------------------------------------------------------------
+template <class T>
+__global__ __launch_bounds__(256) void groupnorm_kernel(GroupNormArgs a) {
+  __shared__ float red[8];
+  const int g = blockIdx.x % a.groups;
+  const long long n = blockIdx.x / a.groups;
+  const int C = a.groups * a.cpg;
+  const T* x = (const T*)a.x + n * a.s * C + (long long)g * a.cpg;
+  T* y = (T*)a.y + n * a.s * C + (long long)g * a.cpg;
+  const long long total = a.s * a.cpg;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  auto block_sum = [&](float v) {
+    v = wave_sum(v);
+    __syncthreads();
+    if (lane == 0) red[wave] = v;
+    __syncthreads();
+    return red[0] + red[1] + red[2] + red[3];
+  };
+  float sum = 0.f;
+  for (long long e = threadIdx.x; e < total; e += 256) sum += to_f<T>(x[(e / a.cpg) * C + e % a.cpg]);
+  const float mean = block_sum(sum) / (float)total;
+  float ss = 0.f;
+  for (long long e = threadIdx.x; e < total; e += 256) {
+    const float d = to_f<T>(x[(e / a.cpg) * C + e % a.cpg]) - mean;
+    ss += d * d;
+  }
+  const float rstd = rsqrtf(block_sum(ss) / (float)total + a.eps);
+  const T* gam = (const T*)a.gamma + g * a.cpg;
+  const T* bet = (const T*)a.beta + g * a.cpg;
+  for (long long e = threadIdx.x; e < total; e += 256) {
+    const int c = (int)(e % a.cpg);
+    const long long at = (e / a.cpg) * C + c;
+    y[at] = from_f<T>((to_f<T>(x[at]) - mean) * rstd * to_f<T>(gam[c]) + to_f<T>(bet[c]));
+  }
+}
+hipError_t launch_groupnorm(const Launch& L, const GroupNormArgs& a, hipStream_t s) {
+  if (a.n * a.groups <= 0 || a.s <= 0) return hipSuccess;
+  dim3 grid((unsigned)(a.n * a.groups));
+  if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(groupnorm_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(groupnorm_kernel<float>, grid, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s) {
   bool ib = L.in_dtype == SOD2_BF16_TAG, ob = L.out_dtype == SOD2_BF16_TAG;
   if (ib && a.C % 8 == 0 && ((uintptr_t)a.x & 15) == 0 && a.R >= 64) {

@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT, K_TOPK };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT, K_TOPK, K_GROUPNORM };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -205,6 +205,15 @@ struct TopKArgs {
   int x_bf16, idx_i32;
 };
 
+// GroupNormalization, channels last: x[n, s, c] with s positions and C = groups * cpg channels, dense;
+// y = (x - mean(n, g)) / sqrt(var(n, g) + eps) * gamma[c] + beta[c], statistics over the s * cpg elements of a group
+struct GroupNormArgs {
+  const void* x; void* y; const void* gamma; const void* beta;
+  long long n, s;
+  int groups, cpg;
+  float eps;
+};
+
 struct Launch {
   int group = -1;
   int kernel = K_OTHER;
@@ -230,6 +239,7 @@ struct Launch {
     FillArgs fill;
     OneHotArgs onehot;
     TopKArgs topk;
+    GroupNormArgs gn;
   } u;
   int unit_bytes = 0;      // resize / concat: bytes of one copy unit
   bool is_layernorm = false;

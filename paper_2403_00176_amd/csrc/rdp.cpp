@@ -17,14 +17,14 @@ static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
     "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand", "Upsample", "ConstantOfShape",
-    "EyeLike", "OneHot", "TopK"};
+    "EyeLike", "OneHot", "TopK", "GroupNorm"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
   switch (kind) {
     case SOD2_OP_SHAPE: case SOD2_OP_CONSTANTOFSHAPE: case SOD2_OP_EYELIKE: return 0;
     case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: case SOD2_OP_RANGE: case SOD2_OP_EXPAND:
-    case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: case SOD2_OP_TOPK: return 2;
+    case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: case SOD2_OP_TOPK: case SOD2_OP_GROUPNORM: return 2;
     case SOD2_OP_NONZERO: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
     default: return 1;
   }
@@ -178,7 +178,7 @@ struct Analyser {
         return done(LS::list({LV::c((int64_t)x.d.size())}), LS::list(x.d));   // ISDO: value = input shape
       }
       case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_CAST:
-      case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM: {
+      case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM: case SOD2_OP_GROUPNORM: {
         if (in_s(0).k == LS::UNDEF) return r;
         return done(in_s(0));
       }
@@ -503,7 +503,7 @@ struct Analyser {
         return refine(S, op.in[0], LS::list({LV::c((int64_t)out.d.size())})) || ch;
       }
       case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_CAST:
-      case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM:
+      case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM: case SOD2_OP_GROUPNORM:
         if (k == 0 && out.is_list()) nw = out;
         break;
       case SOD2_OP_TRANSPOSE:

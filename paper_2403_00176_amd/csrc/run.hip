@@ -28,6 +28,7 @@ hipError_t launch_range(const RangeArgs& a, hipStream_t s);
 hipError_t launch_fill(const FillArgs& a, hipStream_t s);
 hipError_t launch_onehot(const OneHotArgs& a, hipStream_t s);
 hipError_t launch_topk(const TopKArgs& a, hipStream_t s);
+hipError_t launch_groupnorm(const Launch& L, const GroupNormArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
 
@@ -1084,6 +1085,39 @@ struct Builder {
     return L;
   }
 
+  Launch groupnorm(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_GROUPNORM;
+    const Op& op = G.ops[gr.ops[0]];
+    const View& vx = view_of(op.in[0]);
+    int dt = G.tensors[op.in[0]].dtype;
+    if (!vx.contiguous() || vx.dims.size() < 2 || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt ||
+        G.tensors[op.in[1]].dtype != dt || G.tensors[op.in[2]].dtype != dt)
+      throw Error(SOD2_ERR_UNSUPPORTED, "GroupNorm kernel: a dense float tensor [N, ..., C] with scale and bias of its type");
+    GroupNormArgs a{};
+    const int64_t C = vx.dims.back(), groups = op.ia.empty() ? 0 : op.ia[0];
+    if (groups <= 0 || C % groups != 0) throw Error(SOD2_ERR_SHAPE_MISMATCH, "GroupNorm: the channel count must be a multiple of the group count");
+    const View &vg = view_of(op.in[1]), &vb = view_of(op.in[2]);
+    if (vg.numel() != C || vb.numel() != C || !vg.contiguous() || !vb.contiguous())
+      throw Error(SOD2_ERR_SHAPE_MISMATCH, "GroupNorm: scale and bias must hold one value per channel");
+    a.n = vx.dims[0];
+    a.s = 1;
+    for (size_t k = 1; k + 1 < vx.dims.size(); ++k) a.s *= vx.dims[k];
+    a.groups = (int)groups;
+    a.cpg = (int)(C / groups);
+    a.eps = (float)op.fa;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_t(gr.out);
+    L.r[2] = ref_of(vg, dt);
+    L.r[3] = ref_of(vb, dt);
+    L.u.gn = a;
+    L.flops = 8.0 * (double)vx.numel();
+    L.bytes = dtype_bytes(dt) * (2.0 * (double)vx.numel() + 2.0 * C);
+    return L;
+  }
+
   Launch make(const Group& gr) {
     // a result without elements (an empty compacted batch): nothing to compute
     auto od = b.dims.find(gr.out);
@@ -1099,6 +1133,7 @@ struct Builder {
       case G_FILL: return fill(gr);
       case G_ONEHOT: return onehot(gr);
       case G_TOPK: return topk(gr);
+      case G_GROUPNORM: return groupnorm(gr);
       case G_RESIZE: return resize(gr);
       case G_CONCAT: return concat(gr);
       case G_ATTENTION: return attention(gr);
@@ -1169,6 +1204,11 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       TopKArgs a = L.u.topk;
       a.x = P.at(L.r[0]); a.values = P.at(L.r[1]); a.indices = P.at(L.r[2]);
       return launch_topk(a, s);
+    }
+    case K_GROUPNORM: {
+      GroupNormArgs a = L.u.gn;
+      a.x = P.at(L.r[0]); a.y = P.at(L.r[1]); a.gamma = P.at(L.r[2]); a.beta = P.at(L.r[3]);
+      return launch_groupnorm(L, a, s);
     }
     case K_ONEHOT: {
       OneHotArgs a = L.u.onehot;

@@ -277,3 +277,24 @@ def test_slice_with_computed_bounds(S_lib, dtype):
         ses.run(b, ses.upload_inputs(ins), outs)
     assert e.value.code == -1 and "Slice bounds" in str(e.value)
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("dtype,groups,channels", [("f32", 4, 32), ("bf16", 32, 256), ("bf16", 1, 8), ("f32", 6, 6)])
+def test_groupnorm_kernel(S_lib, dtype, groups, channels):
+    import torch
+    from tests.test_shape_ops import _groupnorm_graph
+    from paper_2403_00176_amd.session import Session, to_host
+    g = _groupnorm_graph(dtype, groups, channels)[0]
+    po = P.build_plan(g, R.RDP(g).analyse())
+    ses = Session(g)
+    W = {g.tensor_id("gn.g"): rng.normal(31, (channels,), 1.0, 0.2), g.tensor_id("gn.b"): rng.normal(32, (channels,), 0.0, 0.2)}
+    ses.upload_weights(W)
+    for k, sym in enumerate(({"H": 1, "W": 1}, {"H": 7, "W": 9}, {"H": 64, "W": 64})):
+        ins = {g.tensor_id("x"): rng.normal(600 + k, (2, sym["H"], sym["W"], channels), 0.5, 2.0)}
+        b = ses.bind(sym)
+        assert S_lib.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, W, ins).values[g.outputs()[0]]
+        assert rel_err(to_host(outs[0]), ref) <= (1e-4 if dtype == "f32" else 2e-2), sym

@@ -424,3 +424,48 @@ def test_slice_with_computed_bounds_is_lowered():
     assert S.sod2_plan_dump(lp) == P.dump(p)
     for sym in ({"B": 2, "L": 7, "M": 4}, {"B": 8, "L": 300, "M": 300}):
         assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(p, sym))
+
+
+def _groupnorm_graph(dtype="f32", groups=4, channels=32):
+    """conv-free block around GroupNormalization (Table 2): y = Relu(GroupNorm(x)) + x on a channels-last image."""
+    b = GraphBuilder([("H", 1, 64), ("W", 1, 64)])
+    x = b.input("x", dtype, [2, "H", "W", channels])
+    gam = b.weight("gn.g", dtype, [channels])
+    bet = b.weight("gn.b", dtype, [channels])
+    y = b.op("GroupNorm", [x, gam, bet], groups=groups, eps=1e-5, hint="gn")
+    b.mark_output(b.op("Add", [b.op("Relu", [y]), x]), "y")
+    return b.build(), y
+
+
+def test_groupnorm_closed_forms_and_structure():
+    rs = np.random.RandomState(9)
+    # against explicit loops over (sample, group)
+    x = rs.randn(2, 5, 3, 12) * 2 + 1
+    g_, b_ = rs.randn(12), rs.randn(12)
+    got = O.groupnorm(x, g_, b_, 3, 1e-5)
+    for n in range(2):
+        for gi in range(3):
+            slab = x[n, :, :, gi * 4:(gi + 1) * 4]
+            ref = (slab - slab.mean()) / np.sqrt(slab.var() + 1e-5) * g_[gi * 4:(gi + 1) * 4] + b_[gi * 4:(gi + 1) * 4]
+            assert np.allclose(got[n, :, :, gi * 4:(gi + 1) * 4], ref, atol=1e-12)
+    # one group over one position = LayerNorm over the channels; as many groups as channels and a constant image = bias
+    row = rs.randn(4, 1, 1, 16)
+    assert np.allclose(O.groupnorm(row, g_[:1].repeat(16), b_[:1].repeat(16), 1, 1e-5).reshape(4, 16),
+                       O.layernorm(row.reshape(4, 16), g_[:1].repeat(16), b_[:1].repeat(16), 1e-5))
+    assert np.allclose(O.groupnorm(np.full((1, 3, 3, 12), 2.5), g_, b_, 12, 1e-5), np.broadcast_to(b_, (1, 3, 3, 12)))
+    # eps inside the root: a slab of +-a has variance a^2; eps = 3 a^2 -> the result is +-gamma / 2 + beta
+    a = 0.5
+    img = np.tile(np.array([a, -a]), (1, 2, 2, 2))                 # [1, 2, 2, 4], two groups of (+a, -a)
+    assert np.allclose(O.groupnorm(img, np.ones(4), np.zeros(4), 2, 3 * a * a), img / (2 * a))
+    g, y = _groupnorm_graph()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.S[y]) == "[k:2, s:H, s:W, k:32]" and R.OP_CLASS["GroupNorm"] == "ISVDOS"
+    p = P.build_plan(g, r)
+    assert sorted(gr.kind for gr in p.groups.values()) == ["ELTWISE", "GROUPNORM"]
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    lp = S.sod2_plan(lg, lr)
+    assert S.sod2_rdp_dump(lr) == R.dump(r) and S.sod2_plan_dump(lp) == P.dump(p)
+    assert S.sod2_op_kind_class("GroupNorm") == "ISVDOS"
+    for sym in ({"H": 7, "W": 9}, {"H": 64, "W": 64}):
+        assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(p, sym))

@@ -53,6 +53,7 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "OneHot": (),             # inputs indices, depth (one-element int tensor), values = host constant [off, on]; last axis
     "TopK": (),               # inputs x, k (one-element int tensor); results values, indices (last axis, largest first)
     "Resize": (),             # nearest neighbour, target shape = the values of input 1 ("sizes")
+    "GroupNorm": ("groups",), # GroupNormalization, channels last: inputs x [N, ..., C], scale [C], bias [C]; float attr eps
     "ScatterRows": (),        # ScatterND with row indices: copy of input 0 whose rows input 1 are replaced by input 2
 }
 OP_KINDS = tuple(OP_ATTRS)
