@@ -350,6 +350,80 @@ def optimal_arena_bytes(tensors: Sequence[ArenaTensor]) -> int:
     return best or 0
 
 
+def optimal_arena_bytes_bnb(tensors: Sequence[ArenaTensor], node_limit: int = 3_000_000, incumbent: int = None):
+    """Optimum of the offset assignment (dynamic storage allocation) by branch and bound, for the mid-size lifetime
+    sets the exhaustive search cannot reach.  As in ``optimal_arena_bytes`` the optimum is reached by first fit in
+    *some* order (sort an optimal layout by offset: by induction first fit puts every tensor at or below its offset
+    there), so the search runs over orders, extending a partial order by one tensor at its first-fit offset.  Cuts: a
+    tensor that would end at or above the best layout found; a partial layout already seen with the same set of
+    placed tensors and offsets no better (memo on the frozen layout).  It stops as soon as a layout reaches the lower
+    bound (the largest sum of bytes alive at one step).  Returns (bytes, proven): proven is False when the node limit
+    ended the search; the value is then the best layout found, an upper bound of the optimum.  ``incumbent``: the
+    bytes of a layout already known (a planner's), used as the first bound."""
+    ts = sorted(tensors, key=lambda a: (-a.bytes * (a.end - a.start + 1), a.tid))
+    n = len(ts)
+    if n == 0:
+        return 0, True
+    steps = sorted({k for a in ts for k in range(a.start, a.end + 1)})
+    lower = max(sum(a.bytes for a in ts if a.start <= k <= a.end) for k in steps)
+    conflicts = [[j for j in range(n) if j != i and intersects(ts[i], ts[j])] for i in range(n)]
+    off = [-1] * n
+
+    def fit(i: int) -> int:
+        busy = sorted((off[j], off[j] + ts[j].bytes) for j in conflicts[i] if off[j] >= 0)
+        o = 0
+        for lo, hi in busy:
+            if o + ts[i].bytes <= lo:
+                break
+            o = max(o, hi)
+        return o
+
+    best = 0
+    for i in range(n):                         # a first incumbent: first fit, largest first
+        off[i] = fit(i)
+        best = max(best, off[i] + ts[i].bytes)
+    off = [-1] * n
+    if incumbent is not None:
+        best = min(best, incumbent)
+    state = {"best": best, "nodes": 0, "stop": best == lower, "out_of_nodes": False}
+    seen = set()
+
+    def rec(placed: int, top: int):
+        if state["stop"]:
+            return
+        if placed == n:
+            if top < state["best"]:
+                state["best"] = top
+                state["stop"] = top == lower
+            return
+        state["nodes"] += 1
+        if state["nodes"] > node_limit:
+            state["stop"] = state["out_of_nodes"] = True
+            return
+        key = tuple(off)
+        if key in seen:
+            return
+        seen.add(key)
+        # every tensor still to come must fit below the incumbent wherever it lands: cheap look-ahead
+        cand = []
+        for i in range(n):
+            if off[i] >= 0:
+                continue
+            o = fit(i)
+            if o + ts[i].bytes >= state["best"]:
+                return                          # it only moves up as more tensors are placed
+            cand.append((o, i))
+        for o, i in sorted(cand):
+            off[i] = o
+            rec(placed + 1, max(top, o + ts[i].bytes))
+            off[i] = -1
+            if state["stop"]:
+                return
+
+    rec(0, 0)
+    return state["best"], not state["out_of_nodes"]
+
+
 def check_no_overlap(b: Binding):
     ts = list(b.tensors.values())
     slots = sorted(b.session.values())

@@ -254,6 +254,41 @@ def test_against_exhaustive_optimum_and_best_fit():
     assert mean["peak"] <= mean["best"] and mean["peak"] < 1.06
 
 
+def test_branch_and_bound_optimum():
+    """The branch and bound used for the mid-size sets: equal to the exhaustive optimum where that one is feasible,
+    never below the lower bound (peak of live bytes), never above either planner, and proven on sets of 12-16
+    tensors; the committed study (profiles/planner_quality_configs.txt) is this function applied to the configs."""
+    rnd = random.Random(6)
+    for trial in range(40):
+        n = rnd.randint(3, 7)
+        ts = []
+        for i in range(n):
+            s = rnd.randint(0, 6)
+            ts.append(A.ArenaTensor(i, 256 * rnd.randint(1, 9), s, s + rnd.randint(0, 3)))
+        opt, proven = A.optimal_arena_bytes_bnb(ts)
+        assert proven and opt == A.optimal_arena_bytes(ts)
+    ratio = []
+    for trial in range(12):
+        n = rnd.randint(12, 16)
+        ts = []
+        for i in range(n):
+            s = rnd.randint(0, 12)
+            ts.append(A.ArenaTensor(i, 256 * rnd.randint(1, 16), s, s + rnd.randint(0, 5)))
+        opt, proven = A.optimal_arena_bytes_bnb(ts, node_limit=300_000)
+        live = [sum(t.bytes for t in ts if t.start <= k <= t.end) for k in range(20)]
+        assert opt >= max(live)
+        mine = [A.ArenaTensor(t.tid, t.bytes, t.start, t.end) for t in ts]
+        placed = []
+        A.place_region(mine, list(range(20)), live, placed)
+        top = max(c.offset + c.bytes for c in placed)
+        assert top >= opt
+        # a layout handed in as the incumbent is never made worse
+        assert A.optimal_arena_bytes_bnb(ts, node_limit=1000, incumbent=top)[0] <= top
+        if proven:
+            ratio.append(top / opt)
+    assert len(ratio) >= 8 and sum(ratio) / len(ratio) < 1.06
+
+
 def test_dmp_switch_and_symbol_range():
     w = small(2)
     p_on, p_off = make(w), make(w, dmp=False)
