@@ -259,8 +259,9 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.f;
 
   // epilogue operands that do not depend on the accumulators: this lane's 8 columns and their bias, fetched here,
-  // ahead of the main loop, by the kernels that have the registers to keep them (at most two waves per SIMD)
-  constexpr bool PRE = OCC * LW * KG / 4 <= 2;
+  // ahead of the main loop, by the kernels that have the registers to keep them (the 256-row tile that runs four
+  // waves per SIMD, 128 registers each, has none to spare)
+  constexpr bool PRE = !(BM * BN >= 256 * 128 && OCC * LW * KG / 4 > 2);
   constexpr int CG = EW / 8, QN = 32 * CG / 64;
   static_assert(64 % CG == 0 && QN >= 1, "a lane keeps one column group through the epilogue");
   const int ecg = lane % CG, er0 = lane / CG;
@@ -429,7 +430,7 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
     }
     return;
   }
-  // kernels that run four or more waves per SIMD have no registers to fetch ahead: operands are read pass by pass
+  // no registers to fetch ahead: operands are read pass by pass
   const int colw = n0 + wn * EW;
 #pragma unroll
   for (int i = 0; i < TM; ++i) {
