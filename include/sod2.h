@@ -131,6 +131,9 @@ typedef struct {
    * the largest normalised extent (1024) and the multiple it must be of (64). */
   int32_t max_versions;
   int32_t attn_head_dim, append_max_rows, prologue_max_rows, prologue_max_k, prologue_k_multiple;
+  /* fold_ln = 1: a LayerNorm that reads the result of a contraction group and feeds one MatMul becomes that group's
+   * second result (one kernel fewer per LayerNorm); its extent must be a multiple of fold_k_multiple (0: 64). */
+  int32_t fold_ln, fold_k_multiple;
 } sod2_plan_opts;
 
 typedef struct sod2_graph_s sod2_graph_t;
@@ -246,6 +249,26 @@ sod2_status sod2_binding_force_splits(sod2_binding_t*, int32_t n);
  * sums; with a shorter arena no contraction splits k.  Either way the same call is bit-reproducible. */
 sod2_status sod2_binding_workspace_bytes(const sod2_binding_t*, size_t* workspace_bytes);
 
+/* Constants derived from the weights, for the normalisations that the plan made the second result of a
+ * contraction (Section 4.2: fusion across operators whose shapes RDP relates; sod2_plan_opts.fold_ln).  The
+ * contraction that reads such a normalisation multiplies the un-normalised rows and finishes the normalisation
+ * in its epilogue, which needs, per output column n, sum_k gamma[k] W[n][k] and sum_k beta[k] W[n][k] (+ bias[n])
+ * in fp32.  They depend on the weights only:
+ *   sod2_plan_constants_bytes    size of the buffer (0: the plan has no such pair)
+ *   sod2_plan_prepare_constants  computes them into constants_dev (device memory of the caller, 256-byte aligned,
+ *                                at least that size) from weights_dev (device pointers, one per weight tensor in
+ *                                graph order) with kernels on hip_stream; call it again when the weights change
+ *   sod2_binding_set_constants   runs of this binding use the buffer (it must stay valid and unchanged while runs
+ *                                are in flight); NULL: back to the default
+ * Without constants (the default, and always in replays) every such normalisation is
+ * computed by its own kernel right behind the contraction that produces its input; with them, no kernel of its own
+ * runs, whenever both contractions of the pair run tiled matrix-core kernels on dense operands.  The two ways round
+ * differently (within the tolerance of the storage type), each is bit-reproducible. */
+sod2_status sod2_plan_constants_bytes(const sod2_plan_t*, size_t* bytes);
+sod2_status sod2_plan_prepare_constants(const sod2_plan_t*, const void* const* weights_dev, int32_t n_weights,
+                                        void* constants_dev, size_t bytes, void* hip_stream);
+sod2_status sod2_binding_set_constants(sod2_binding_t*, const void* constants_dev, size_t bytes);
+
 /* -- run -------------------------------------------------------------------------------------- */
 /* arena: device memory, 256-byte aligned, at least arena_bytes long.  weights / inputs / outputs:
  * host arrays of device pointers, one per tensor with that role, ordered by tensor id.
@@ -300,6 +323,9 @@ typedef struct {
   int32_t ref;
   int32_t kernel, variant, splits;
   int32_t decision;
+  int32_t fold;       /* a contraction and a folded normalisation: 0 none; 1 its kernel also wrote the normalisation of
+                         its result as a second result; 3 the normalisation's own kernel ran right behind it; 2 its first
+                         operand was such a second result and its epilogue finished the normalisation */
 } sod2_trace_entry;
 sod2_status sod2_run_trace(const sod2_binding_t*, sod2_trace_entry* entries_host, int32_t cap, int32_t* n);
 

@@ -121,6 +121,17 @@ def first_fit(t: ArenaTensor, placed: Sequence[ArenaTensor]) -> int:
     return off
 
 
+def last_fit(t: ArenaTensor, placed: Sequence[ArenaTensor], ceiling: int) -> int:
+    """The highest offset that fits below ``ceiling``; the lowest offset that fits when there is none."""
+    busy = sorted(((p.offset, p.offset + p.bytes) for p in placed if intersects(t, p)), key=lambda r: (-r[1], -r[0]))
+    end = ceiling
+    for lo, hi in busy:
+        if end - t.bytes >= hi:
+            break
+        end = min(end, lo)
+    return end - t.bytes if end - t.bytes >= 0 else first_fit(t, placed)
+
+
 def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
          exec_values: Sequence[int] = ()) -> Binding:
     g = plan.graph
@@ -236,6 +247,8 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
                         n = DT_BYTES[g.tensors[t].dtype]
                         for d in b.dims[t]:
                             n *= d
+                        if t in plan.fold_y:              # R9: rows plus their partial sums (8 bytes per 32 columns)
+                            n = n * 9 // 8
                         b.tensors[t] = ArenaTensor(t, align_up(n), step, step)
             else:
                 op = g.ops[it.ref]
@@ -288,11 +301,34 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
 def place_region(mine: Sequence[ArenaTensor], ks: Sequence[int], live_bytes: Sequence[int], placed: List[ArenaTensor]):
     """Peak-first placement of the tensors that start in the steps ``ks``: the steps are visited from the
     one with the most live bytes down (earlier first on ties); at each, the tensors live there that have
-    no offset yet are placed by (start, id) at the lowest offset that fits."""
-    for p in sorted(ks, key=lambda k: (-live_bytes[k], k)):
-        for a in sorted((a for a in mine if a.offset < 0 and a.start <= p <= a.end), key=lambda a: (a.start, a.tid)):
-            a.offset = first_fit(a, placed)
-            placed.append(a)
+    no offset yet are placed one by one.  The region cannot end below ``ceiling``, the larger of its own
+    peak of live bytes and what is already placed.  Four variants of the pass are tried in a fixed order
+    and the first one that ends lowest is kept (the search stops at the first that ends at the ceiling):
+    tensors of a step by (start, id) or by (size descending, start, id), each at the lowest offset that
+    fits or at the highest offset below the ceiling that fits."""
+    mine = list(mine)
+    if not mine:
+        return
+    ceiling = max(max(live_bytes[k] for k in ks), max((p.offset + p.bytes for p in placed), default=0))
+    by_need = sorted(ks, key=lambda k: (-live_bytes[k], k))
+    best = None
+    for by_size, high in ((False, False), (True, False), (False, True), (True, True)):
+        for a in mine:
+            a.offset = -1
+        cur = list(placed)
+        key = (lambda a: (-a.bytes, a.start, a.tid)) if by_size else (lambda a: (a.start, a.tid))
+        for p in by_need:
+            for a in sorted((a for a in mine if a.offset < 0 and a.start <= p <= a.end), key=key):
+                a.offset = last_fit(a, cur, ceiling) if high else first_fit(a, cur)
+                cur.append(a)
+        top = max(a.offset + a.bytes for a in mine)
+        if best is None or top < best[0]:
+            best = (top, [a.offset for a in mine])
+        if best[0] <= ceiling:
+            break
+    for a, o in zip(mine, best[1]):
+        a.offset = o
+    placed.extend(mine)
 
 
 def planning_regions(plan: Plan, b: Binding) -> List[List[int]]:

@@ -53,7 +53,20 @@ R7  LayerNorm as a prologue: a LAYERNORM group whose result is read by one
     of at most ``Opts.prologue_max_k`` and a multiple of
     ``Opts.prologue_k_multiple``, and everything is bf16.  The LayerNorm result
     is never materialised.
-The limits of R6-R8 are capabilities of whatever executes the plan, handed in
+R9  LayerNorm behind a contraction: a LAYERNORM group whose input is the result
+    of a GEMM group (MatMul with any epilogue but a permuted store; no LayerNorm
+    prologue, no second result yet) and whose result is read by one MatMul alone
+    -- as its first operand, against a rank-2 weight [n, k] stored k-contiguous,
+    leading its GEMM group -- joins the *producing* group: that group gets a
+    second result, the LayerNorm's tensor, and the consuming group is marked
+    (``lnfold``).  Everything bf16; the normalised extent a known constant that
+    is a multiple of ``Opts.fold_k_multiple``.  What the producing kernel writes
+    into the second result is its business (the normalised rows, or the rows
+    scaled by gamma together with per-row partial sums from which the consumer
+    finishes the normalisation in its epilogue): the tensor is sized for the
+    latter, 2.25 bytes per element instead of 2 (per row and 32 columns an
+    8-byte pair of partial sums).  The group keeps its place in the order.
+The limits of R6-R9 are capabilities of whatever executes the plan, handed in
 with the options (the same numbers go to the library's planner); they shape
 the groups, never a value.
 
@@ -99,6 +112,8 @@ class Opts:
     prologue_max_rows: int = 8
     prologue_max_k: int = 1024
     prologue_k_multiple: int = 64
+    fold_ln: bool = True     # R9: a LayerNorm behind a contraction becomes that contraction's second result
+    fold_k_multiple: int = 64
 
 
 @dataclass
@@ -111,6 +126,8 @@ class Group:
     also: List[int] = field(default_factory=list)  # further results of the same operator (TopK: the indices)
     versions: int = 1                              # code versions of the fused loop nest (Fig. 4)
     unproven: List[tuple] = field(default_factory=list)   # (operand a, operand b, aligned dim) pairs behind them
+    lnfold: int = -1                               # R9: the LayerNorm operator whose result this contraction reads
+    key: int = -1                                  # position in the node order that places the group among the items
 
 
 @dataclass
@@ -139,6 +156,7 @@ class Plan:
     paper_rdp: R.RDP = None               # Alg. 1 as printed (EDO outputs nac); == rdp without a NonZero
     exec_ops: List[int] = field(default_factory=list)    # NonZero operators, in the node order
     inplace: Dict[int, int] = field(default_factory=dict)   # group result -> the operand whose storage it takes over
+    fold_y: Dict[int, int] = field(default_factory=dict)    # R9: LayerNorm result produced by a contraction -> the LayerNorm
 
 
 def _shape_equal(a, b) -> bool:
@@ -400,6 +418,45 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             for m in members:
                 assigned[m] = gid
 
+    # R9: LayerNorm as the second result of the contraction that produces its input ----------
+    fold_y: Dict[int, int] = {}
+    for gr in groups.values():
+        gr.key = max(pos[m] for m in gr.ops)
+    if opts.fusion and opts.fold_ln:
+        for n in order:
+            op = g.ops[n]
+            if op.kind != "LayerNorm" or n not in assigned or groups[assigned[n]].kind != "LAYERNORM":
+                continue
+            x, y = op.inputs[0], op.outputs[0]
+            px = rdp.producer[x]
+            if px < 0 or px not in assigned:
+                continue
+            gp = groups[assigned[px]]
+            kinds = [g.ops[m].kind for m in gp.ops]
+            if gp.kind != "GEMM" or gp.out != x or gp.also or kinds[0] != "MatMul" or \
+                    any(k in ("Transpose", "LayerNorm", "CacheAppend") for k in kinds):
+                continue
+            c = sole_consumer(y)
+            if c is None or g.ops[c].kind != "MatMul" or g.ops[c].inputs[0] != y or g.ops[c].inputs[1] == y:
+                continue
+            gm = groups[assigned[c]]
+            wt = g.ops[c].inputs[1]
+            sw, sx = rdp.S[wt], rdp.S[x]
+            if gm.kind != "GEMM" or min(gm.ops) != c or gm.lnfold >= 0 or not g.ops[c].attrs.get("transB", 0) or \
+                    g.tensors[wt].role != "weight" or not isinstance(sw, list) or len(sw) != 2:
+                continue
+            if any(g.tensors[t].dtype != "bf16" for t in list(op.inputs) + [y, wt, gm.out]):
+                continue
+            if not (isinstance(sx, list) and sx and all(R.is_expr(d) for d in sx) and sx[-1].is_const()
+                    and sx[-1].const_value() % opts.fold_k_multiple == 0 and sx[-1].const_value() > 0):
+                continue
+            del groups[assigned[n]]
+            gp.ops = sorted(gp.ops + [n])
+            gp.also = [y]
+            assigned[n] = gp.gid
+            gm.lnfold = n
+            fold_y[y] = n
+
     # statistic: loop-nest versions a fuser without RDP results would emit (Fig. 4)
     versions = 0
     for i, op in enumerate(g.ops):
@@ -430,7 +487,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
         gr.ins = reads_of(gr.ops)
 
     # items in topological order (R5) --------------------------------------------
-    entries = [(max(pos[n] for n in gr.ops), True, gid) for gid, gr in groups.items()]
+    entries = [(gr.key if gr.key >= 0 else max(pos[n] for n in gr.ops), True, gid) for gid, gr in groups.items()]
     entries += [(pos[n], False, n) for n, op in enumerate(g.ops) if op.kind in ("Switch", "Combine")]
     items: List[Item] = []
     for _, is_group, ref in sorted(entries):
@@ -446,6 +503,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
 
     plan = Plan(g, rdp, opts, order, folded, view, groups, assigned, items, [], [], sbase, versions,
                 paper_rdp, [n for n in order if g.ops[n].kind == "NonZero"])
+    plan.fold_y = fold_y
     _partition(plan)
     if opts.inplace:
         _mark_inplace(plan)
@@ -479,8 +537,9 @@ def _mark_inplace(plan: Plan):
         gr = plan.groups[it.ref]
         if gr.kind not in ("GEMM", "CONV", "ELTWISE") or not arena_candidate(plan, gr.out):
             continue
-        if any(g.ops[n].kind in ("Transpose", "LayerNorm", "CacheAppend") for n in gr.ops):
-            continue
+        if any(g.ops[n].kind in ("Transpose", "CacheAppend") or
+               (g.ops[n].kind == "LayerNorm" and n not in plan.fold_y.values()) for n in gr.ops):
+            continue                     # (a LayerNorm that is the group's second result, R9, reads the finished rows)
         inside = {o for n in gr.ops for o in g.ops[n].outputs}
         outer = [t for n in gr.ops for t in g.ops[n].inputs if t not in inside and plan.sbase[t] not in inside]
         if gr.kind == "ELTWISE":
@@ -569,7 +628,10 @@ def _classify(plan: Plan, piece) -> str:
 def _bytes_at(plan: Plan, t: int, env) -> int:
     """Size used by the order search; an execution-determined tensor counts as 0 (unknown)."""
     e = tensor_bytes_expr(plan.rdp, plan.graph, t)
-    return 0 if e is None or execution_determined(plan, t) else align_up(e.eval(env))
+    if e is None or execution_determined(plan, t):
+        return 0
+    n = e.eval(env)
+    return align_up(n * 9 // 8 if t in plan.fold_y else n)      # R9: the partial sums behind the rows
 
 
 def subgraph_peak(plan: Plan, seq, last_read, env) -> int:
@@ -687,6 +749,8 @@ def dump(plan: Plan) -> str:
             ver = ""
             if gr.versions > 1:
                 ver = f" versions={gr.versions} unproven=[" + " ".join(f"t{a}~t{b}@{k}" for a, b, k in gr.unproven) + "]"
+            if gr.lnfold >= 0:
+                ver += f" lnfold={gr.lnfold}"
             lines.append(f"g{gr.gid} {gr.kind} ops=[{' '.join(map(str, gr.ops))}] out=t{gr.out}{also} "
                          f"ins=[{' '.join('t%d' % t for t in gr.ins)}]{ver}")
         else:

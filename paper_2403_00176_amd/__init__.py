@@ -35,6 +35,7 @@ EXPORTS = [
     "sod2_binding_destroy",
     "sod2_binding_arena_bytes", "sod2_binding_dump", "sod2_binding_query_tensor", "sod2_run_query_tensor", "sod2_run_trace", "sod2_binding_force_decisions", "sod2_binding_force_variant",
     "sod2_binding_force_splits", "sod2_binding_workspace_bytes",
+    "sod2_plan_constants_bytes", "sod2_plan_prepare_constants", "sod2_binding_set_constants",
     "sod2_run", "sod2_run_static", "sod2_run_decisions", "sod2_run_exec_values", "sod2_run_plan_dump", "sod2_run_arena_bytes", "sod2_binding_set_profiling",
     "sod2_binding_launch_records", "sod2_replay_create", "sod2_replay_launch", "sod2_replay_destroy",
     "sod2_last_error", "sod2_version",
@@ -70,7 +71,7 @@ class PlanOpts(C.Structure):
     _fields_ = [("fusion", C.c_int32), ("sep", C.c_int32), ("dmp", C.c_int32), ("mvc", C.c_int32),
                 ("inplace", C.c_int32), ("max_versions", C.c_int32), ("attn_head_dim", C.c_int32),
                 ("append_max_rows", C.c_int32), ("prologue_max_rows", C.c_int32), ("prologue_max_k", C.c_int32),
-                ("prologue_k_multiple", C.c_int32)]
+                ("prologue_k_multiple", C.c_int32), ("fold_ln", C.c_int32), ("fold_k_multiple", C.c_int32)]
 
 
 class DimInfo(C.Structure):
@@ -267,11 +268,13 @@ def sod2_rdp_dump(r: Rdp) -> str:
 
 
 def sod2_plan(g: Graph, r: Rdp, fusion=1, sep=1, dmp=1, mvc=1, inplace=1, max_versions=0, attn_head_dim=0,
-              append_max_rows=0, prologue_max_rows=0, prologue_max_k=0, prologue_k_multiple=0) -> Plan:
+              append_max_rows=0, prologue_max_rows=0, prologue_max_k=0, prologue_k_multiple=0, fold_ln=1,
+              fold_k_multiple=0) -> Plan:
     """The last six options are limits of the fusion rules; 0 = the library's default (see sod2_plan_opts)."""
     out = C.c_void_p()
     opts = PlanOpts(int(fusion), int(sep), int(dmp), int(mvc), int(inplace), int(max_versions), int(attn_head_dim),
-                    int(append_max_rows), int(prologue_max_rows), int(prologue_max_k), int(prologue_k_multiple))
+                    int(append_max_rows), int(prologue_max_rows), int(prologue_max_k), int(prologue_k_multiple),
+                    int(fold_ln), int(fold_k_multiple))
     _check(_lib.sod2_plan(g.ptr, r.ptr, C.byref(opts), C.byref(out)))
     p = Plan(out, keep=(g, r))
     p.graph = g
@@ -353,6 +356,23 @@ def sod2_binding_workspace_bytes(b: Binding) -> int:
     return n.value
 
 
+def sod2_plan_constants_bytes(p) -> int:
+    n = C.c_size_t()
+    _check(_lib.sod2_plan_constants_bytes(p.ptr, C.byref(n)))
+    return n.value
+
+
+def sod2_plan_prepare_constants(p, weight_ptrs: Sequence[int], constants_ptr: int, nbytes: int, stream: int = 0):
+    """Computes the plan's derived constants (device memory of the caller) from the weights, on ``stream``."""
+    w = weight_ptrs if isinstance(weight_ptrs, C.Array) else pointer_array(weight_ptrs)
+    _check(_lib.sod2_plan_prepare_constants(p.ptr, w, len(weight_ptrs), C.c_void_p(constants_ptr), C.c_size_t(nbytes),
+                                            C.c_void_p(stream)))
+
+
+def sod2_binding_set_constants(b: Binding, constants_ptr: int, nbytes: int):
+    _check(_lib.sod2_binding_set_constants(b.ptr, C.c_void_p(constants_ptr or None), C.c_size_t(nbytes)))
+
+
 def sod2_binding_set_profiling(b: Binding, on: bool):
     _check(_lib.sod2_binding_set_profiling(b.ptr, int(on)))
 
@@ -419,7 +439,7 @@ class TensorInfo(C.Structure):
 
 class TraceEntry(C.Structure):
     _fields_ = [("is_group", C.c_int32), ("ref", C.c_int32), ("kernel", C.c_int32), ("variant", C.c_int32),
-                ("splits", C.c_int32), ("decision", C.c_int32)]
+                ("splits", C.c_int32), ("decision", C.c_int32), ("fold", C.c_int32)]
 
 
 def sod2_plan_query_group(p: "Plan", index: int) -> dict:
@@ -450,12 +470,13 @@ def sod2_run_query_tensor(b: "Binding", tensor: int) -> dict:
 
 
 def sod2_run_trace(b: "Binding") -> list:
-    """Executed steps of the last run: dicts with is_group, ref, kernel, variant, splits, decision."""
+    """Executed steps of the last run: dicts with is_group, ref, kernel, variant, splits, decision, fold."""
     n = C.c_int32()
     _check(_lib.sod2_run_trace(b.ptr, None, 0, C.byref(n)))
     arr = (TraceEntry * max(n.value, 1))()
     _check(_lib.sod2_run_trace(b.ptr, arr, n.value, C.byref(n)))
-    return [dict(is_group=bool(e.is_group), ref=e.ref, kernel=e.kernel, variant=e.variant, splits=e.splits, decision=e.decision)
+    return [dict(is_group=bool(e.is_group), ref=e.ref, kernel=e.kernel, variant=e.variant, splits=e.splits, decision=e.decision,
+                 fold=e.fold)
             for e in arr[:n.value]]
 
 

@@ -42,6 +42,18 @@ int64_t first_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& p
   }
   return off;
 }
+// the highest offset that fits below the ceiling; the lowest offset that fits when there is none
+int64_t last_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& placed, Ranges& busy, int64_t ceiling) {
+  busy.clear();
+  for (const ArenaTensor* p : placed) if (intersects(t, *p)) busy.push_back({p->offset + p->bytes, p->offset});   // (hi, lo)
+  std::sort(busy.begin(), busy.end(), [](const std::pair<int64_t, int64_t>& x, const std::pair<int64_t, int64_t>& y) { return x > y; });
+  int64_t end = ceiling;
+  for (const auto& b : busy) {
+    if (end - t.bytes >= b.first) break;
+    end = std::min(end, b.second);
+  }
+  return end - t.bytes >= 0 ? end - t.bytes : first_fit(t, placed, busy);
+}
 // comparison strategy of Section 4.4.1: the smallest free slot that can hold the tensor
 int64_t best_fit(const ArenaTensor& t, const std::vector<const ArenaTensor*>& placed) {
   std::vector<std::pair<int64_t, int64_t>> busy;
@@ -211,6 +223,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
           int64_t n2 = dtype_bytes(G.tensors[t2].dtype);
           for (const CompiledExpr& d : p.cshape[t2]) { d2.push_back(d.eval(b.atom_vals)); n2 *= d2.back(); }
           b.dims[t2] = d2;
+          if (p.fold_y[t2] >= 0) n2 = n2 * 9 / 8;       // R9: rows plus their partial sums (8 bytes per 32 columns)
           if (p.arena_candidate(t2)) b.tensors[t2] = ArenaTensor{t2, (n2 + 255) / 256 * 256, step, step, -1};
         }
       } else {
@@ -255,6 +268,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
 
   std::vector<const ArenaTensor*> placed;
   Ranges busy;
+  int64_t top = 0;                                     // highest byte of anything placed so far
   if (p.opts.dmp) {
     std::vector<ArenaTensor*> by_start;                // every region takes its tensors from the front
     for (auto& kv : b.tensors) by_start.push_back(&kv.second);
@@ -289,23 +303,48 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
       while (next_t < by_start.size() && by_start[next_t]->start <= k1) mine.push_back(by_start[next_t++]);
       if (!mine.empty()) {
         // the peak first, then the next highest step, and so on; at each step the tensors live there
-        // that have no offset yet, by (start, id), each at the lowest offset that fits
+        // that have no offset yet are placed one by one.  The region cannot end below the ceiling (its
+        // own peak of live bytes, or what is already placed).  Four variants of the pass, in a fixed
+        // order, the first that ends lowest is kept and the search stops at one that ends at the
+        // ceiling: tensors of a step by (start, id) or by (size descending, start, id), each at the
+        // lowest offset that fits or at the highest one below the ceiling that fits.
         std::vector<int> steps_by_need;
-        for (int k = k0; k <= k1; ++k) steps_by_need.push_back(k);
+        int64_t ceiling = top;
+        for (int k = k0; k <= k1; ++k) { steps_by_need.push_back(k); ceiling = std::max(ceiling, live_bytes[k]); }
         std::stable_sort(steps_by_need.begin(), steps_by_need.end(), [&](int x, int y) { return live_bytes[x] > live_bytes[y]; });
         std::sort(mine.begin(), mine.end(), [](const ArenaTensor* x, const ArenaTensor* y) {
           return x->start != y->start ? x->start < y->start : x->tid < y->tid;
         });
-        size_t left = mine.size();
-        for (int pk : steps_by_need) {
-          if (left == 0) break;
-          for (ArenaTensor* a : mine) {
-            if (a->offset >= 0 || a->start > pk || a->end < pk) continue;
-            a->offset = first_fit(*a, placed, busy);
-            placed.push_back(a);
-            --left;
+        std::vector<ArenaTensor*> by_size = mine;
+        std::stable_sort(by_size.begin(), by_size.end(), [](const ArenaTensor* x, const ArenaTensor* y) { return x->bytes > y->bytes; });
+        const size_t n_before = placed.size();
+        int64_t best_top = -1;
+        std::vector<int64_t> best_off(mine.size());
+        for (int variant = 0; variant < 4; ++variant) {
+          const std::vector<ArenaTensor*>& order = (variant & 1) ? by_size : mine;
+          const bool high = variant >= 2;
+          for (ArenaTensor* a : mine) a->offset = -1;
+          placed.resize(n_before);
+          size_t left = mine.size();
+          int64_t region_top = 0;
+          for (int pk : steps_by_need) {
+            if (left == 0) break;
+            for (ArenaTensor* a : order) {
+              if (a->offset >= 0 || a->start > pk || a->end < pk) continue;
+              a->offset = high ? last_fit(*a, placed, busy, ceiling) : first_fit(*a, placed, busy);
+              region_top = std::max(region_top, a->offset + a->bytes);
+              placed.push_back(a);
+              --left;
+            }
           }
+          if (best_top < 0 || region_top < best_top) {
+            best_top = region_top;
+            for (size_t i = 0; i < mine.size(); ++i) best_off[i] = mine[i]->offset;
+          }
+          if (best_top <= ceiling) break;
         }
+        for (size_t i = 0; i < mine.size(); ++i) mine[i]->offset = best_off[i];
+        top = std::max(top, best_top);
       }
       k0 = k1 + 1;
     }

@@ -94,7 +94,40 @@ __device__ __forceinline__ void act8(float* x, int act) {
   }
 }
 
-// scale, bias, activation, residual, activation and the store of 8 consecutive columns of one row
+// sum over the 4 lanes of a quad (lanes 4 q .. 4 q + 3), in every lane, through the data-parallel-primitive lane swaps
+// (no LDS round trip)
+__device__ __forceinline__ float quad_sum(float v) {
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0xB1, 0xF, 0xF, false));   // lanes 1 0 3 2
+  v += __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), 0x4E, 0xF, 0xF, false));   // lanes 2 3 0 1
+  return v;
+}
+
+// The second result of a contraction with a LayerNorm behind it, for the 8 consecutive columns a lane has just stored
+// (o: the rounded values): xg = bf16(x * gamma) into fold_y, and per row and 32 columns the pair (sum, sum of squared
+// distances from the mean of the 32) behind fold_y's M x N elements, as [N / 32][M] pairs.  The 4 lanes that hold one run of 32 columns are
+// neighbours aligned to 4, and all of them get here together (N is a multiple of 32).
+__device__ __forceinline__ void fold_emit8(const V16& o, const V16& gam, const GemmArgs& g, int row, int col) {
+  float v[8], sum = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) { v[e] = bf2f(o.h[e]); sum += v[e]; }
+  sum = quad_sum(sum);
+  const float m = sum * (1.f / 32.f);
+  float d2 = 0.f;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) d2 = fmaf(v[e] - m, v[e] - m, d2);
+  d2 = quad_sum(d2);
+  V16 y;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) y.h[e] = f2bf(v[e] * bf2f(gam.h[e]));
+  bf16_t* Y = (bf16_t*)g.fold_y;
+  *(uint4*)(Y + (long long)row * g.N + col) = y.u;
+  if ((col & 31) == 0)                           // [run of 32 columns][row]: a wave's 16 rows are one 128-byte line
+    *(float2*)((float*)(Y + (long long)g.M * g.N) + ((long long)(col >> 5) * g.M + row) * 2) = make_float2(sum, d2);
+}
+
+// activation, residual, activation and the store of 8 consecutive columns of one row
+__device__ __forceinline__ void finish8(float* x, const GemmArgs& g, bf16_t* Cp, const bf16_t* Rp, int row, int col);
+// scale and bias first
 __device__ __forceinline__ void epilogue8(float* x, const GemmArgs& g, bf16_t* Cp, const bf16_t* Rp, int row, int col) {
   const bf16_t* bias = (const bf16_t*)g.bias;
   const bool full = g.c_vec && col + 8 <= g.N;
@@ -111,6 +144,10 @@ __device__ __forceinline__ void epilogue8(float* x, const GemmArgs& g, bf16_t* C
 #pragma unroll
     for (int e = 0; e < 8; ++e) x[e] *= g.scale;
   }
+  finish8(x, g, Cp, Rp, row, col);
+}
+__device__ __forceinline__ void finish8(float* x, const GemmArgs& g, bf16_t* Cp, const bf16_t* Rp, int row, int col) {
+  const bool full = g.c_vec && col + 8 <= g.N;
   act8(x, g.act1);
   if (Rp) {
     if (full) {
@@ -144,7 +181,10 @@ __device__ __forceinline__ void epilogue8(float* x, const GemmArgs& g, bf16_t* C
 // accumulators are summed through LDS in the order q = 0, 1, ... before the epilogue: a workgroup walks
 // k KG times faster, which is what bounds a contraction with fewer tiles than CUs.
 // OCC workgroups per CU (the second launch bound counts waves per SIMD).
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN, int KG = 1>
+// FOLD 1: the rows of the result also go out normalisation-ready (GemmArgs::fold_y); FOLD 2: the first operand is such
+// a second result, and the epilogue finishes the normalisation with the rows' statistics (reduced once per workgroup
+// into LDS while the first k-tiles are on their way) and the two constant vectors derived from the weights.
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN, int KG = 1, int FOLD = 0>
 __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al, GemmArgs g) {
   constexpr int NCW = WM * WN, NWV = LW, NT = NWV * 64;
   constexpr int KV = BK / 8, TM = BM / (WM * 32), TN = BN / (WN * 32);
@@ -158,7 +198,12 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
                     (BM + BN) * KV % NT == 0 && BM % (64 / KV) == 0 && (KG == 1 || LW == NCW),
                 "4 or 8 compute waves per group, at most 16 waves");
   static_assert((ST - 2) * LT <= 63, "vmcnt is a 6-bit counter");
-  __shared__ __attribute__((aligned(16))) bf16_t lds[LDS_ELEMS];
+  // behind the ring: FOLD 1 the tile's BN values of gamma; FOLD 2 per tile row (scale * rstd, -scale * rstd * mean),
+  // then the tile's BN values of fold_s and of fold_c (staged here so that no register holds them through the k loop)
+  __shared__ __attribute__((aligned(16))) bf16_t lds[LDS_ELEMS + (FOLD == 2 ? BM * 4 + BN * 4 : (FOLD == 1 ? BN : 0))];
+  float* rowstat = (float*)(lds + LDS_ELEMS);
+  float* colc = rowstat + BM * 2;
+  bf16_t* gam_lds = lds + LDS_ELEMS;
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave_all = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -267,7 +312,7 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
   const int ecg = lane % CG, er0 = lane / CG;
   const int ecol = n0 + wn * EW + ecg * 8;
   const bool ecol_full = g.c_vec && ecol + 8 <= g.N;
-  V16 ebv;
+  V16 ebv, egam;
   if (PRE) ebv.u = (g.bias && ecol_full) ? *(const uint4*)((const bf16_t*)g.bias + ecol) : zero4();
 
   // MFMA fragments are double buffered in registers: the LDS reads of k-step ks+1 are issued before
@@ -309,6 +354,41 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
   // still issued (they fetch zeros into a stage nobody reads again), so the wait counts stay uniform.
 #pragma unroll
   for (int s = 0; s < ST - 1; ++s) issue(s, s);
+  if (FOLD == 1 && tid < BN / 8)
+    *(uint4*)&gam_lds[tid * 8] = (n0 + tid * 8 + 8 <= g.N) ? *(const uint4*)((const bf16_t*)g.fold_gamma + n0 + tid * 8) : zero4();
+  if (FOLD == 2) {
+    if (tid < BN / 4) {
+      const bool in = n0 + tid * 4 + 4 <= g.N;
+      *(float4*)&colc[tid * 4] = in ? *(const float4*)((const float*)g.fold_s + n0 + tid * 4) : make_float4(0, 0, 0, 0);
+      *(float4*)&colc[BN + tid * 4] = in ? *(const float4*)((const float*)g.fold_c + n0 + tid * 4) : make_float4(0, 0, 0, 0);
+    }
+    // four threads per tile row add up the row's partial statistics (one pair per run of 32 columns of the operand,
+    // stored behind its M x K elements as [run][row]): mean = S / K, variance = (sum of the runs' squared distances
+    // from their own means + sum of s_j^2 / 32 - S^2 / K) / K.  (These 8 K / 32 bytes per row are three quarters of a
+    // k-tile's traffic for K = 768: what the read side of a folded LayerNorm costs.)
+    const int P = g.K >> 5;
+    const float2* st = (const float2*)((const bf16_t*)g.A + (long long)g.M * g.K);
+    for (int idx = tid; idx < BM * 4; idx += NT * KG) {
+      const int row = idx >> 2, part = idx & 3;
+      float s1 = 0.f, s2 = 0.f, m2 = 0.f;
+      if (m0 + row < g.M) {
+        const float2* pr = st + (m0 + row);
+        // 8 loads in flight at a time (a loop over a run-time count would wait for each load in turn)
+        for (int j0 = part; j0 < P; j0 += 32) {
+          float2 v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[u] = (j0 + 4 * u < P) ? pr[(long long)(j0 + 4 * u) * g.M] : make_float2(0.f, 0.f);
+#pragma unroll
+          for (int u = 0; u < 8; ++u) { s1 += v[u].x; s2 = fmaf(v[u].x, v[u].x, s2); m2 += v[u].y; }
+        }
+      }
+      s1 = quad_sum(s1); s2 = quad_sum(s2); m2 = quad_sum(m2);
+      const float inv_k = 1.f / (float)g.K, mean = s1 * inv_k;
+      const float var = fmaxf((m2 + s2 * (1.f / 32.f) - s1 * mean) * inv_k, 0.f);
+      const float a = g.scale * rsqrtf(var + g.ln_eps);
+      if (part == 0) *(float2*)&rowstat[row * 2] = make_float2(a, -a * mean);
+    }
+  }
   int rd = 0, wr = ST - 1;
   for (int t = 0; t < nk; ++t) {
     wait_loads<(ST - 2) * LT>();                         // tile t has landed (this wave's part)
@@ -373,6 +453,14 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
       for (int e = 0; e < 8; ++e) if (col + e < g.N) w[e] = x[e];
     }
   };
+  float es[FOLD == 2 ? 8 : 1], ec[FOLD == 2 ? 8 : 1];
+  if (FOLD == 1 && PRE) egam.u = *(const uint4*)&gam_lds[wn * EW + ecg * 8];
+  if (FOLD == 2 && PRE) {
+    const float4 s0 = *(const float4*)&colc[wn * EW + ecg * 8], s1 = *(const float4*)&colc[wn * EW + ecg * 8 + 4];
+    const float4 c0 = *(const float4*)&colc[BN + wn * EW + ecg * 8], c1 = *(const float4*)&colc[BN + wn * EW + ecg * 8 + 4];
+    es[0] = s0.x; es[1] = s0.y; es[2] = s0.z; es[3] = s0.w; es[4] = s1.x; es[5] = s1.y; es[6] = s1.z; es[7] = s1.w;
+    ec[0] = c0.x; ec[1] = c0.y; ec[2] = c0.z; ec[3] = c0.w; ec[4] = c1.x; ec[5] = c1.y; ec[6] = c1.z; ec[7] = c1.w;
+  }
   if (PRE) {
     // A lane owns the same 8 columns in every pass (EW / 8 divides 64): its bias values were fetched before the
     // main loop, and the residual values of the next 32 rows are fetched while the current rows are converted
@@ -410,8 +498,14 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
         if (Wp) {
           store_partial(x, row, ecol);
         } else if (ecol_full) {                                 // whole 16-byte vectors: the operands fetched ahead
+          if (FOLD == 2) {
+            const float2 ab = *(const float2*)&rowstat[(wm * TM * 32 + i * 32 + rr) * 2];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) x[e] = x[e] * g.scale + bf2f(ebv.h[e]);
+            for (int e = 0; e < 8; ++e) x[e] = fmaf(ab.x, x[e], fmaf(ab.y, es[e], ec[e]));
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) x[e] = x[e] * g.scale + bf2f(ebv.h[e]);
+          }
           act8(x, g.act1);
           if (Rp) {
             V16 r8; r8.u = rv[i & 1][q];
@@ -423,6 +517,7 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
 #pragma unroll
           for (int e = 0; e < 8; ++e) o.h[e] = f2bf(x[e]);
           *(uint4*)(Cp + (long long)row * g.c_sm + ecol) = o.u;
+          if (FOLD == 1) fold_emit8(o, egam, g, row, ecol);
         } else {
           epilogue8(x, g, Cp, Rp, row, ecol);
         }
@@ -451,8 +546,23 @@ __global__ __launch_bounds__(LW * KG * 64, OCC * LW * KG / 4) void gemm_dl(AL al
         const float4 p0 = *(const float4*)&patch[rr * ELD + cc], p1 = *(const float4*)&patch[rr * ELD + cc + 4];
         x[0] = p0.x; x[1] = p0.y; x[2] = p0.z; x[3] = p0.w; x[4] = p1.x; x[5] = p1.y; x[6] = p1.z; x[7] = p1.w;
       }
-      if (Wp) store_partial(x, row, col);
-      else epilogue8(x, g, Cp, Rp, row, col);
+      if (Wp) { store_partial(x, row, col); continue; }
+      if (FOLD == 2) {                                          // (no bias: it is part of fold_c; the scale is in rowstat)
+        const float2 ab = *(const float2*)&rowstat[(wm * TM * 32 + i * 32 + rr) * 2];
+        const float* sp = colc + (col - n0);
+        const float* cp = colc + BN + (col - n0);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) x[e] = fmaf(ab.x, x[e], fmaf(ab.y, sp[e], cp[e]));
+        finish8(x, g, Cp, Rp, row, col);
+      } else {
+        epilogue8(x, g, Cp, Rp, row, col);
+      }
+      if (FOLD == 1) {
+        V16 o, gm;
+        o.u = *(const uint4*)(Cp + (long long)row * g.c_sm + col);
+        gm.u = *(const uint4*)&gam_lds[col - n0];
+        fold_emit8(o, gm, g, row, col);
+      }
     }
   }
 }
@@ -480,6 +590,39 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs g, int splits) {
   bf16_t* Cp = (bf16_t*)g.C + b0 * g.c_sb0 + b1 * g.c_sb1;
   const bf16_t* Rp = g.res ? (const bf16_t*)g.res + b0 * g.r_sb0 + b1 * g.r_sb1 : nullptr;
   epilogue8(x, g, Cp, Rp, row, col);
+  if (g.fold == 1) {                                            // (N a multiple of 32: 4 neighbouring threads share a run)
+    V16 o, gm;
+    o.u = *(const uint4*)(Cp + (long long)row * g.c_sm + col);
+    gm.u = *(const uint4*)((const bf16_t*)g.fold_gamma + col);
+    fold_emit8(o, gm, g, row, col);
+  }
+}
+
+// fold_s[n] = sum_k gamma[k] W[n][k], fold_c[n] = scale * sum_k beta[k] W[n][k] + bias[n] (one wave per n; fp32 sums of
+// exact products)
+__global__ __launch_bounds__(256) void fold_constants_kernel(const bf16_t* W, const bf16_t* gamma, const bf16_t* beta,
+                                                             const bf16_t* bias, float scale, int N, int K, float* s_out,
+                                                             float* c_out) {
+  const int n = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (n >= N) return;
+  float s = 0.f, c = 0.f;
+  for (int k = lane; k < K; k += 64) {
+    const float w = bf2f(W[(long long)n * K + k]);
+    s = fmaf(bf2f(gamma[k]), w, s);
+    c = fmaf(bf2f(beta[k]), w, c);
+  }
+  s = wave_sum(s);
+  c = wave_sum(c);
+  if (lane == 0) {
+    s_out[n] = s;
+    c_out[n] = scale * c + (bias ? bf2f(bias[n]) : 0.f);
+  }
+}
+hipError_t launch_fold_constants(const void* W, const void* gamma, const void* beta, const void* bias, float scale, int N,
+                                 int K, void* s_out, void* c_out, hipStream_t s) {
+  hipLaunchKernelGGL(fold_constants_kernel, dim3((N + 3) / 4), dim3(256), 0, s, (const bf16_t*)W, (const bf16_t*)gamma,
+                     (const bf16_t*)beta, (const bf16_t*)bias, scale, N, K, (float*)s_out, (float*)c_out);
+  return hipGetLastError();
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -624,12 +767,12 @@ hipError_t launch_gemv(const GemmArgs& g, hipStream_t s) {
 // ---------------------------------------------------------------------------------------------
 // host-side launchers
 // ---------------------------------------------------------------------------------------------
-template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN, int KG = 1>
+template <class AL, int BM, int BN, int BK, int ST, int WM, int WN, int OCC, int LW = WM * WN, int KG = 1, int FOLD = 0>
 static hipError_t launch_dl(const AL& al, const GemmArgs& g, hipStream_t s) {
   const int tiles = ((g.M + BM - 1) / BM) * ((g.N + BN - 1) / BN);
   const int splits = g.splits > 1 ? g.splits : 1;
   dim3 grid(tiles, g.nb0 * g.nb1, splits);
-  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC, LW, KG>), grid, dim3(LW * KG * 64), 0, s, al, g);
+  hipLaunchKernelGGL((gemm_dl<AL, BM, BN, BK, ST, WM, WN, OCC, LW, KG, FOLD>), grid, dim3(LW * KG * 64), 0, s, al, g);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess || splits == 1) return e;
   const long long nvec = (long long)g.M * ((g.N + 7) / 8);
@@ -663,6 +806,8 @@ hipError_t launch_dl_variant(const AL& al, const GemmArgs& g, int tile, hipStrea
     case DL_128x128x64_S2_G2: return launch_dl<AL, 128, 128, 64, 2, 2, 2, 1, 4, 2>(al, g, s);
     case DL_64x64x64_S2_G2: return launch_dl<AL, 64, 64, 64, 2, 2, 2, 2, 4, 2>(al, g, s);
     case DL_128x128x64_S2_W8G2: return launch_dl<AL, 128, 128, 64, 2, 2, 4, 1, 8, 2>(al, g, s);
+    case DL_128x128x64_S2_W8T: return launch_dl<AL, 128, 128, 64, 2, 4, 2, 2>(al, g, s);     // _T: 4 x 2 waves, a wave's rows are 128 bytes
+    case DL_128x128x64_S3_W8T: return launch_dl<AL, 128, 128, 64, 3, 4, 2, 1>(al, g, s);
     default: return hipErrorInvalidValue;
   }
 }
@@ -675,8 +820,24 @@ hipError_t launch_null(hipStream_t s) {
   return hipGetLastError();
 }
 
+// the versions that write or read a LayerNorm as a second result: the tiles the shape rule picks
+template <int FOLD>
+static hipError_t launch_dl_fold(const DlMat& al, const GemmArgs& g, int tile, hipStream_t s) {
+  switch (tile) {
+    case DL_128x128x64_S2_W8T: return launch_dl<DlMat, 128, 128, 64, 2, 4, 2, 2, 8, 1, FOLD>(al, g, s);
+    case DL_256x128x32_S3_W8: return launch_dl<DlMat, 256, 128, 32, 3, 4, 2, 2, 8, 1, FOLD>(al, g, s);
+    case DL_64x64x64_S4_W4: return launch_dl<DlMat, 64, 64, 64, 4, 2, 2, 2, 4, 1, FOLD>(al, g, s);
+    case DL_128x128x64_S3_W8T: return launch_dl<DlMat, 128, 128, 64, 3, 4, 2, 1, 8, 1, FOLD>(al, g, s);
+    case DL_256x256x64_S2_W8: return launch_dl<DlMat, 256, 256, 64, 2, 2, 4, 1, 8, 1, FOLD>(al, g, s);
+    case DL_64x64x64_S3_G2: return launch_dl<DlMat, 64, 64, 64, 3, 2, 2, 1, 4, 2, FOLD>(al, g, s);
+    case DL_64x64x64_S2_G2: return launch_dl<DlMat, 64, 64, 64, 2, 2, 2, 2, 4, 2, FOLD>(al, g, s);
+    default: return hipErrorInvalidValue;                        // (the 16-wave tile with two k groups has no registers left for it)
+  }
+}
 hipError_t launch_gemm_dl(const GemmArgs& g, int tile, hipStream_t s) {
   DlMat al{(const bf16_t*)g.A, g.a_sm, g.M, g.K, 0};
+  if (g.fold == 1) return (g.N % 32 == 0 && g.c_vec) ? launch_dl_fold<1>(al, g, tile, s) : hipErrorInvalidValue;
+  if (g.fold == 2) return (g.K % 32 == 0 && g.N % 8 == 0 && g.c_vec && g.splits <= 1) ? launch_dl_fold<2>(al, g, tile, s) : hipErrorInvalidValue;
   return launch_dl_variant(al, g, tile, s);
 }
 hipError_t launch_conv_dl(const ConvArgs& c, const GemmArgs& g, int tile, hipStream_t s) {

@@ -18,6 +18,8 @@ struct sod2_binding_s {
   int force_variant = -1;
   int force_splits = 0;                     // 0 automatic, 1 never split k, n > 1 that many k ranges where possible
   bool profiling = false;
+  const void* constants = nullptr;          // constants derived from the weights (folded LayerNorms), or null: not folded
+  size_t constants_bytes = 0;
   std::vector<int> last_decisions;
   sod2::BindResult executed;                // plan of the last run when it contained Switches
   bool has_executed = false;

@@ -175,6 +175,8 @@ struct Group {
   int versions = 1;                                // code versions of the fused loop nest (Fig. 4; 1: every pair proven)
   struct Pair { int a, b, k; };                    // operands of a binary member and the aligned dim, counted from the last
   std::vector<Pair> unproven;
+  int lnfold = -1;                                 // the LayerNorm (a second result of the producing group) this contraction reads
+  int key = -1;                                    // node-order position that places the group among the items
 };
 struct Item {
   bool is_group = true;
@@ -188,7 +190,11 @@ struct Plan {
   std::shared_ptr<Rdp> named;                      // analysis with named EDO extents, owned (see Rdp::named_edo)
   std::vector<int> exec_ops;                       // NonZero operators in the node order
   bool execution_determined(int t) const;          // nac in the paper's lattice: unresolved or in an execution symbol
-  sod2_plan_opts opts{1, 1, 1, 1, 1, 0, 0, 0, 0, 0, 0};
+  sod2_plan_opts opts{1, 1, 1, 1, 1, 0, 0, 0, 0, 0, 0, 1, 0};
+  int fold_k_multiple() const { return opts.fold_k_multiple > 0 ? opts.fold_k_multiple : 64; }
+  std::vector<int> fold_y;                         // per tensor: the LayerNorm that makes it a contraction's second result, or -1
+  std::map<int, int64_t> const_off;                // group reading a folded LayerNorm -> byte offset of its derived constants
+  int64_t const_bytes = 0;                         // size of the buffer that holds them all
   // the limits of R4 and R6-R8 with the defaults (what this library's kernels fuse) filled in
   int max_versions() const { return opts.max_versions > 0 ? opts.max_versions : 8; }
   int attn_head_dim() const { return opts.attn_head_dim > 0 ? opts.attn_head_dim : 64; }

@@ -22,7 +22,7 @@ enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL
 enum DlTile { DL_128x128x64_S3_W4 = 0, DL_128x128x64_S2_W4, DL_128x128x32_S3_W4, DL_128x128x64_S2_W8, DL_256x128x64_S2_W8,
               DL_256x128x32_S3_W8, DL_64x128x64_S3_W4, DL_64x64x64_S4_W4, DL_128x64x64_S3_W4, DL_128x128x64_S3_W8,
               DL_256x256x32_S3_W8, DL_64x64x64_S4_L8, DL_64x64x64_S4_L16, DL_128x128x64_S2_L16, DL_64x128x64_S3_L8, DL_256x256x64_S2_W8, DL_256x128x64_S3_W8,
-              DL_64x64x64_S4_G2, DL_64x64x64_S3_G2, DL_64x64x64_S2_G4, DL_128x128x64_S2_G2, DL_64x64x64_S2_G2, DL_128x128x64_S2_W8G2, DL_TILES };   // _Gn: n wave groups split k inside the workgroup
+              DL_64x64x64_S4_G2, DL_64x64x64_S3_G2, DL_64x64x64_S2_G4, DL_128x128x64_S2_G2, DL_64x64x64_S2_G2, DL_128x128x64_S2_W8G2, DL_128x128x64_S2_W8T, DL_128x128x64_S3_W8T, DL_TILES };   // _Gn: n wave groups split k inside the workgroup
 
 // C[b0,b1,m,n] = act2( act1( scale * sum_k A[b0,b1,m,k] * B[b0,b1,k,n] + bias[n] ) + R[b0,b1,m,n] )
 struct GemmArgs {
@@ -44,6 +44,17 @@ struct GemmArgs {
   const void* ln_gamma;    // LayerNorm prologue over the rows of A (all of K), or null
   const void* ln_beta;
   float ln_eps;
+  // A LayerNorm over the result's rows as a second result (fold == 1), read back by the contraction that consumes it
+  // (fold == 2).  The second result is xg = bf16(x * gamma) (x the rounded first result, rows of N elements) and, behind
+  // its M x N elements, per run of 32 columns and row ([N / 32][M]) the pair (sum of x, sum of squared distances from the mean of those 32).
+  // The consumer multiplies xg by its weights and finishes the normalisation in its epilogue:
+  // out = scale * rstd * (acc - mean * fold_s[n]) + fold_c[n], with fold_s[n] = sum_k gamma[k] W[n][k] and
+  // fold_c[n] = scale * sum_k beta[k] W[n][k] + bias[n], both fp32, derived from the weights once.
+  int fold;                // 0 plain, 1 emits the second result, 2 reads one
+  void* fold_y;            // fold 1: xg, then the statistics
+  const void* fold_gamma;  // fold 1: gamma of the LayerNorm (N elements, the first result's type)
+  const void* fold_s;      // fold 2
+  const void* fold_c;
 };
 
 // Optional workspace behind the planned arena (fp32 partial tiles of split-K contractions)
@@ -219,7 +230,7 @@ struct Launch {
   int kernel = K_OTHER;
   int variant = 0;
   int in_dtype = 0, out_dtype = 0;
-  Ref r[7];                // operand references, meaning depends on the kernel
+  Ref r[10];               // operand references, meaning depends on the kernel
   union {
     GemmArgs gemm;
     ConvArgs conv;
@@ -247,6 +258,13 @@ struct Launch {
   long long d_past = 0;    // replay: rows the CacheAppend position / keys the attention length gain per step
   int d_lk = 0;
   bool empty = false;      // the group's result has no elements: nothing is launched
+  // a contraction whose group holds a LayerNorm of its result (r[7] the LayerNorm's result, r[8] gamma, r[9] beta):
+  // post_ln: the LayerNorm's row kernel runs right behind the contraction, or, with fold_pair (both contractions of the
+  // pair run kernels that can), the contraction emits the second result itself.  fold_read: the contraction whose first
+  // operand is such a second result; const_off: where its derived constants start in the plan's constants buffer.
+  bool post_ln = false, fold_pair = false, fold_read = false;
+  long long const_off = -1;
+  RowArgs post;
   Launch() { std::memset(&u, 0, sizeof u); }
 };
 

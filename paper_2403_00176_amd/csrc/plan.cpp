@@ -96,6 +96,7 @@ static int64_t bytes_at(const Plan& p, int t, const std::map<std::string, int64_
   if (p.execution_determined(t)) return 0;
   int64_t n = dtype_bytes(p.g->tensors[t].dtype);
   for (const auto& d : s.d) n *= d.e.eval(env);
+  if (p.fold_y[t] >= 0) n = n * 9 / 8;             // R9: per row and 32 columns an 8-byte pair of partial sums behind the rows
   return align_up(n);
 }
 
@@ -355,6 +356,60 @@ void Plan::build() {
     }
   }
 
+  // R9: a LayerNorm behind a contraction becomes that contraction's second result
+  fold_y.assign(G.tensors.size(), -1);
+  for (auto& kv : groups) {
+    kv.second.key = 0;
+    for (int m : kv.second.ops) kv.second.key = std::max(kv.second.key, pos[m]);
+  }
+  if (opts.fusion && opts.fold_ln) {
+    for (int n : order) {
+      const Op& op = G.ops[n];
+      if (op.kind != SOD2_OP_LAYERNORM || group_of_op[n] < 0 || groups[group_of_op[n]].kind != G_LAYERNORM) continue;
+      const int x = op.in[0], y = op.out[0];
+      const int px = G.producer[x];
+      if (px < 0 || group_of_op[px] < 0) continue;
+      Group& gp = groups[group_of_op[px]];
+      if (gp.kind != G_GEMM || gp.out != x || !gp.also.empty() || G.ops[gp.ops.front()].kind != SOD2_OP_MATMUL) continue;
+      bool barred = false;
+      for (int m : gp.ops) {
+        const int k = G.ops[m].kind;
+        if (k == SOD2_OP_TRANSPOSE || k == SOD2_OP_LAYERNORM || k == SOD2_OP_CACHEAPPEND) barred = true;
+      }
+      if (barred) continue;
+      const int c = sole_consumer(y);
+      if (c < 0 || G.ops[c].kind != SOD2_OP_MATMUL || G.ops[c].in[0] != y || G.ops[c].in[1] == y) continue;
+      Group& gm = groups[group_of_op[c]];
+      const int wt = G.ops[c].in[1];
+      const LS &sw = R.S[wt], &sx = R.S[x];
+      if (gm.kind != G_GEMM || gm.ops.front() != c || gm.lnfold >= 0 || G.ops[c].ia.empty() || !G.ops[c].ia[0] ||
+          G.tensors[wt].role != SOD2_WEIGHT || !sw.is_list() || sw.d.size() != 2)
+        continue;
+      bool bf = true;
+      for (int t : op.in) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
+      for (int t : {y, wt, gm.out}) if (G.tensors[t].dtype != SOD2_BF16) bf = false;
+      if (!bf || !sx.resolved() || sx.d.empty() || !sx.d.back().e.is_const() || sx.d.back().e.const_value() <= 0 ||
+          sx.d.back().e.const_value() % fold_k_multiple() != 0)
+        continue;
+      groups.erase(group_of_op[n]);
+      gp.ops.push_back(n);
+      std::sort(gp.ops.begin(), gp.ops.end());
+      gp.also = {y};
+      group_of_op[n] = gp.gid;
+      gm.lnfold = n;
+      fold_y[y] = n;
+    }
+  }
+  // constants derived from the weights for the contractions that read a folded LayerNorm: two fp32 vectors over
+  // the contraction's columns each, one block per group
+  for (const auto& kv : groups) {
+    if (kv.second.lnfold < 0) continue;
+    const LS& sw = R.S[G.ops[kv.second.ops.front()].in[1]];
+    if (!sw.d[0].e.is_const()) continue;
+    const_off[kv.first] = const_bytes;
+    const_bytes += (2 * sw.d[0].e.const_value() * 4 + 255) / 256 * 256;
+  }
+
   // static storage bases: views and Switch outputs alias their (data) input
   int nt = (int)G.tensors.size();
   sbase.resize(nt);
@@ -381,9 +436,7 @@ void Plan::build() {
   struct Entry { int pos; bool is_group; int ref; };
   std::vector<Entry> entries;
   for (const auto& kv : groups) {
-    int last = 0;
-    for (int n : kv.second.ops) last = std::max(last, pos[n]);
-    entries.push_back({last, true, kv.first});
+    entries.push_back({kv.second.key, true, kv.first});
   }
   for (int n = 0; n < nops; ++n) if (is_control(G.ops[n].kind)) entries.push_back({pos[n], false, n});
   std::sort(entries.begin(), entries.end(), [](const Entry& a, const Entry& b) { return a.pos < b.pos; });
@@ -557,7 +610,8 @@ void Plan::build() {
       bool barred = false;
       for (int n : gr.ops) {
         int k = G.ops[n].kind;
-        if (k == SOD2_OP_TRANSPOSE || k == SOD2_OP_LAYERNORM || k == SOD2_OP_CACHEAPPEND) barred = true;
+        // (a LayerNorm that is the group's second result, R9, reads the finished rows: no bar)
+        if (k == SOD2_OP_TRANSPOSE || (k == SOD2_OP_LAYERNORM && fold_y[G.ops[n].out[0]] != n) || k == SOD2_OP_CACHEAPPEND) barred = true;
       }
       if (barred) continue;
       std::set<int> inside;
@@ -644,6 +698,7 @@ std::string Plan::dump() const {
                  std::to_string(gr.unproven[k].k);
         out += "]";
       }
+      if (gr.lnfold >= 0) out += " lnfold=" + std::to_string(gr.lnfold);
       out += "\n";
     } else {
       out += "c" + std::to_string(it.ref) + " " + op_name(g->ops[it.ref].kind) + "\n";

@@ -31,6 +31,8 @@ hipError_t launch_topk(const TopKArgs& a, hipStream_t s);
 hipError_t launch_groupnorm(const Launch& L, const GroupNormArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
+hipError_t launch_fold_constants(const void* W, const void* gamma, const void* beta, const void* bias, float scale, int N,
+                                 int K, void* s_out, void* c_out, hipStream_t s);
 
 void destroy_events(void* events, int n) {
   hipEvent_t* e = (hipEvent_t*)events;
@@ -150,6 +152,7 @@ struct Builder {
   const BindResult& b;
   int force_variant;
   int force_splits = 0;
+  bool folding = false;                            // the caller has handed over the constants folded LayerNorms need
   std::vector<int> memo_at;                        // tensor -> position in memo, or -1
   std::vector<View> memo;                          // reserved for every tensor up front: references stay valid
 
@@ -302,14 +305,18 @@ struct Builder {
     if (force_variant >= 0) return force_variant;
     // multi-version kernels off (the breakdown study of Section 5.3): one version of the same kernel for every
     // shape -- the 128 x 128 x 64 tile, no skinny version, no k groups, no split-K
-    if (!p.opts.mvc) return V_DL0 + DL_128x128x64_S2_W8;
+    if (!p.opts.mvc) return V_DL0 + DL_128x128x64_S2_W8T;
     if (M <= 8) return V_GEMV;                     // decode shape: weight streaming, one wave per column
     const int64_t t128 = ((M + 127) / 128) * ((N + 127) / 128) * batch;
     const int64_t t64 = ((M + 63) / 64) * ((N + 63) / 64) * batch;
     if (t128 >= 1024) return V_DL0 + (K >= 2048 ? DL_256x256x64_S2_W8 : DL_256x128x32_S3_W8);   // fat versions
     // the 64x64 tile runs two workgroups per CU: as long as all its tiles are resident at once
     // (512 on 256 CUs) it finishes first; one tile more and a second round starts, then 128x128 wins
-    if (t64 > 512) return V_DL0 + (K >= 2048 ? (t128 <= 256 ? DL_128x128x64_S2_W8G2 : DL_128x128x64_S3_W8) : DL_128x128x64_S2_W8);
+    // (128 x 128 tiles: 4 x 2 waves, so that a wave stores whole 128-byte lines; with at most one tile per CU the
+    // three-stage ring with one workgroup per CU beats two stages and two per CU, k short or long)
+    if (t64 > 512)
+      return V_DL0 + (t128 <= 256 ? (K >= 2048 ? DL_128x128x64_S2_W8G2 : DL_128x128x64_S3_W8T)
+                                  : (K >= 2048 ? DL_128x128x64_S3_W8T : DL_128x128x64_S2_W8T));
     // with at most one tile per CU a workgroup's walk over k is the whole duration: two wave groups
     // share the tile and split k between them (0.5 - 4 us less per launch on config 2's shapes)
     if (t64 <= 256) return V_DL0 + DL_64x64x64_S3_G2;
@@ -338,7 +345,7 @@ struct Builder {
     return (int)std::max<int64_t>(s, 1);
   }
 
-  Launch gemm(const Group& gr) {
+  Launch gemm_core(const Group& gr) {
     Launch L;
     L.group = gr.gid;
     L.kernel = K_GEMM;
@@ -426,6 +433,10 @@ struct Builder {
     if (e.res >= 0) L.r[4] = ref_of(view_of(e.res), dt);
     int64_t batch = (int64_t)g.nb0 * g.nb1;
     L.variant = pick_variant(dt, g.M, g.N, g.K, batch);
+    // the one tile of the shape rule that cannot write or read a folded LayerNorm gives way to its neighbour
+    if (folding && force_variant < 0 && L.variant == V_DL0 + DL_128x128x64_S2_W8G2 &&
+        ((!gr.also.empty() && p.fold_y[gr.also[0]] >= 0) || gr.lnfold >= 0))
+      L.variant = V_DL0 + DL_128x128x64_S3_W8T;
     g.splits = pick_splits(L.variant, g.M, g.N, g.K, batch);
     if (ln) {
       if (g.a_sk != 1 || g.K % 64 != 0 || g.K > 1024 || (g.M > 1 && g.a_sm % 8 != 0) || !tb || g.b_sk != 1)
@@ -445,6 +456,80 @@ struct Builder {
     if (ln) {
       L.flops += 8.0 * g.M * g.K * batch;
       L.bytes += eb * 2.0 * g.K;
+    }
+    return L;
+  }
+
+  // A contraction that takes part in the folding of a LayerNorm (the LayerNorm behind it is its second result, or its
+  // first operand is such a second result).  Whether the pair of kernels can do it is decided here, from both launches,
+  // so that the two sides always agree; otherwise the LayerNorm's row kernel runs right behind the producing contraction.
+  static bool dl_can_fold(int variant) {
+    switch (variant - V_DL0) {
+      case DL_256x256x64_S2_W8: case DL_256x128x32_S3_W8: case DL_128x128x64_S3_W8T:
+      case DL_128x128x64_S2_W8T: case DL_64x64x64_S3_G2: case DL_64x64x64_S2_G2: case DL_64x64x64_S4_W4: return true;
+      default: return false;
+    }
+  }
+  std::map<int, bool> pair_memo;
+  bool pair_ok(int ln) {
+    if (!folding) return false;
+    auto it = pair_memo.find(ln);
+    if (it != pair_memo.end()) return it->second;
+    bool ok = false;
+    const Group& gp = p.groups.at(p.group_of_op[ln]);
+    const Group* gc = nullptr;
+    for (const auto& kv : p.groups) if (kv.second.lnfold == ln) gc = &kv.second;
+    if (gc && gp.lnfold < 0 && gc->also.empty() && gc->prologue < 0 && G.tensors[gp.out].dtype == SOD2_BF16 &&
+        G.tensors[G.ops[ln].in[1]].role == SOD2_WEIGHT && G.tensors[G.ops[ln].in[2]].role == SOD2_WEIGHT) {
+      Launch lp, lc;
+      try {
+        lp = gemm_core(gp);
+        lc = gemm_core(*gc);
+      } catch (const Error&) {                                  // (the consumer sits in a branch this binding skips)
+        pair_memo[ln] = false;
+        return false;
+      }
+      const GemmArgs &a = lp.u.gemm, &c = lc.u.gemm;
+      const Epi ep = epilogue(gp), ec = epilogue(*gc);
+      const bool prod = dl_can_fold(lp.variant) && a.nb0 * a.nb1 == 1 && a.c_sn == 1 && a.c_sm == a.N && a.N % 32 == 0 &&
+                        a.a_sk == 1 && a.K % 8 == 0 && a.a_sm % 8 == 0 && a.b_sk == 1 && a.b_sn % 8 == 0 &&
+                        (ep.res < 0 || (a.r_sn == 1 && a.r_sm % 8 == 0));
+      const bool cons = dl_can_fold(lc.variant) && c.splits == 1 && c.nb0 * c.nb1 == 1 && c.a_sk == 1 && c.a_sm == c.K &&
+                        c.b_sk == 1 && c.b_sn % 8 == 0 && c.c_sn == 1 && c.c_sm % 8 == 0 && c.N % 8 == 0 &&
+                        (ec.res < 0 || (c.r_sn == 1 && c.r_sm % 8 == 0)) && c.M == a.M && c.K == a.N &&
+                        (ec.bias < 0 || G.tensors[ec.bias].role == SOD2_WEIGHT) && p.const_off.count(gc->gid);
+      ok = prod && cons;
+    }
+    pair_memo[ln] = ok;
+    return ok;
+  }
+  Launch gemm(const Group& gr) {
+    Launch L = gemm_core(gr);
+    const int y = (!gr.also.empty() && p.fold_y[gr.also[0]] >= 0) ? gr.also[0] : -1;
+    if (y >= 0) {
+      const Op& ln = G.ops[p.fold_y[y]];
+      const View& vx = view_of(gr.out);
+      if (!vx.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "LayerNorm behind a contraction needs a dense result");
+      RowArgs a{};
+      a.cols = (int)vx.dims.back();
+      a.rows = vx.numel() / std::max<int64_t>(a.cols, 1);
+      a.x_stride = a.y_stride = a.cols;
+      a.eps = (float)ln.fa;
+      L.post = a;
+      L.post_ln = true;
+      L.r[7] = ref_t(y);
+      L.r[8] = ref_t(ln.in[1]);
+      L.r[9] = ref_t(ln.in[2]);
+      L.fold_pair = pair_ok(p.fold_y[y]);
+      double eb = dtype_bytes(L.out_dtype);
+      L.flops += 8.0 * a.rows * a.cols;
+      L.bytes += eb * a.rows * a.cols + (L.fold_pair ? 0.25 * a.rows * a.cols : eb * a.rows * a.cols);
+    }
+    if (gr.lnfold >= 0 && pair_ok(gr.lnfold)) {
+      L.fold_read = true;
+      L.const_off = p.const_off.at(gr.gid);
+      L.u.gemm.ln_eps = (float)G.ops[gr.lnfold].fa;
+      L.bytes += 0.25 * L.u.gemm.M * L.u.gemm.K + 8.0 * L.u.gemm.N;
     }
     return L;
   }
@@ -1162,6 +1247,7 @@ struct Pointers {
   const void* const* w = nullptr; int nw = 0;
   const void* const* in = nullptr; int nin = 0;
   void* const* out = nullptr; int nout = 0;
+  const char* constants = nullptr; size_t constants_bytes = 0;   // constants derived from the weights for folded LayerNorms, or null
   Pointers(void* arena_, size_t bytes, const void* const* w_, int nw_, const void* const* in_, int nin_, void* const* out_, int nout_)
       : arena((char*)arena_), arena_bytes(bytes), w(w_), nw(nw_), in(in_), nin(nin_), out(out_), nout(nout_) {}
   void* at(const Ref& r) const {
@@ -1261,7 +1347,30 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       } else {
         g.splits = 1;
       }
-      return launch_gemm(L, g, s);
+      const bool folding = P.constants != nullptr;             // both sides of every pair see the same answer
+      if (L.fold_read && folding) {
+        if (L.const_off < 0 || (size_t)L.const_off + 8u * (size_t)g.N > P.constants_bytes) return hipErrorInvalidValue;
+        g.fold = 2;
+        g.fold_s = P.constants + L.const_off;
+        g.fold_c = P.constants + L.const_off + 4ll * g.N;
+        g.bias = nullptr;                                      // part of fold_c
+      }
+      if (L.post_ln && L.fold_pair && folding) {
+        g.fold = 1;
+        g.fold_y = P.at(L.r[7]);
+        g.fold_gamma = P.at(L.r[8]);
+      }
+      if (g.fold && !(L.variant >= V_DL0 && g.a_vec && g.b_mode == 0 && g.c_vec && al16(g.fold_y) && al16(g.fold_gamma)))
+        return hipErrorInvalidValue;                           // the pair was promised a kernel that cannot run here
+      hipError_t e = launch_gemm(L, g, s);
+      if (e != hipSuccess || !L.post_ln || g.fold == 1) return e;
+      RowArgs a = L.post;
+      a.x = g.C; a.y = P.at(L.r[7]); a.gamma = P.at(L.r[8]); a.beta = P.at(L.r[9]);
+      Launch row;
+      row.kernel = K_LAYERNORM;
+      row.is_layernorm = true;
+      row.in_dtype = row.out_dtype = L.out_dtype;
+      return launch_row(row, a, s);
     }
     case K_CONV: {
       ConvArgs c = L.u.conv;
@@ -1331,9 +1440,10 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
 // launch table for every executed group step of `b`, indexed by step (-1 kernel for control steps);
 // steps before `first_step` (already run when a plan is rebuilt in mid-run) are left unbuilt (-2)
 std::vector<Launch> build_launches(const Plan& p, const BindResult& b, int force_variant, int force_splits,
-                                   size_t first_step = 0) {
+                                   size_t first_step = 0, bool folding = false) {
   Builder B(p, b, force_variant);
   B.force_splits = force_splits;
+  B.folding = folding;
   std::vector<Launch> out;
   for (size_t k = 0; k < b.steps.size(); ++k) {
     const Item& it = p.items[b.steps[k]];
@@ -1603,6 +1713,13 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
     if (((uintptr_t)arena & 255) != 0) throw Error(SOD2_ERR_INVALID_ARG, "arena must be 256-byte aligned");
     hipStream_t s = (hipStream_t)stream;
     Pointers P(arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs);
+    if (h->constants && h->constants_bytes < (size_t)p.const_bytes)
+      throw Error(SOD2_ERR_INVALID_ARG, "constants buffer of " + std::to_string(h->constants_bytes) + " bytes, plan needs " +
+                                            std::to_string(p.const_bytes));
+    if (h->constants && p.const_bytes > 0) {
+      P.constants = (const char*)h->constants;
+      P.constants_bytes = h->constants_bytes;
+    }
     // an arena longer than the plan by WS_BYTES carries the optional workspace at its end
     auto workspace_for = [&](int64_t plan_bytes) -> char* {
       size_t end = arena_bytes & ~(size_t)255;
@@ -1626,6 +1743,7 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
       }
       first.reset(new Builder(p, h->b, h->force_variant));
       first->force_splits = h->force_splits;
+      first->folding = P.constants != nullptr;
     }
     if (static_ws) {
       // every launch is prepared before the first one is enqueued, so that a contraction whose partial
@@ -1711,6 +1829,7 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
       }
       lazy.reset(new Builder(p, replanned, h->force_variant));
       lazy->force_splits = h->force_splits;
+      lazy->folding = P.constants != nullptr;
       P.ws = static_ws ? static_scratch() : workspace_for(replanned.arena_bytes);
       cur = &replanned;
       launches = &relaunch;
@@ -1737,7 +1856,12 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
           int splits = 1;
           if (L.kernel == K_GEMM && P.ws) splits = std::max(L.u.gemm.splits, 1);
           else if (L.kernel == K_CONV && P.ws) splits = std::max(L.u.conv.splits, 1);
-          h->trace.push_back(sod2_trace_entry{1, it.ref, L.empty ? -1 : L.kernel, L.variant, splits, -1});
+          int fold = 0;
+          if (L.kernel == K_GEMM && !L.empty) {
+            if (L.post_ln) fold = (L.fold_pair && P.constants) ? 1 : 3;
+            if (L.fold_read && P.constants) fold = 2;
+          }
+          h->trace.push_back(sod2_trace_entry{1, it.ref, L.empty ? -1 : L.kernel, L.variant, splits, -1, fold});
         }
         if (L.kernel == K_NONZERO) {
           // the extent is execution determined: read the count back, then size and plan what follows
@@ -1795,9 +1919,9 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
           if (dec != 0) replan(k, "Switch", have_other ? &other : nullptr);
           else assumed = true;
         }
-        h->trace.push_back(sod2_trace_entry{0, it.ref, -1, 0, 1, decisions[which]});
+        h->trace.push_back(sod2_trace_entry{0, it.ref, -1, 0, 1, decisions[which], 0});
       } else {
-        h->trace.push_back(sod2_trace_entry{0, it.ref, -1, 0, 1, -1});      // Combine: forwards the taken path's tensor
+        h->trace.push_back(sod2_trace_entry{0, it.ref, -1, 0, 1, -1, 0});      // Combine: forwards the taken path's tensor
       }
       ++k;
     }
@@ -1842,6 +1966,73 @@ extern "C" sod2_status sod2_run(sod2_binding_t* h, void* arena, size_t arena_byt
                                 int32_t n_weights, const void* const* inputs, int32_t n_inputs, void* const* outputs,
                                 int32_t n_outputs, void* stream) {
   return run_impl(h, arena, arena_bytes, weights, n_weights, inputs, n_inputs, outputs, n_outputs, stream, false);
+}
+
+extern "C" sod2_status sod2_plan_constants_bytes(const sod2_plan_t* h, size_t* bytes) {
+  if (!h || !bytes) { set_error("null argument"); return SOD2_ERR_INVALID_ARG; }
+  *bytes = (size_t)h->p.const_bytes;
+  return SOD2_OK;
+}
+
+extern "C" sod2_status sod2_plan_prepare_constants(const sod2_plan_t* h, const void* const* weights, int32_t n_weights,
+                                                   void* constants, size_t bytes, void* stream) {
+  try {
+    if (!h || !weights) throw Error(SOD2_ERR_INVALID_ARG, "null argument");
+    const Plan& p = h->p;
+    const Graph& G = *p.g;
+    if (n_weights != (int)G.weight_ids.size()) throw Error(SOD2_ERR_INVALID_ARG, "wrong number of weight pointers");
+    if (p.const_bytes == 0) return SOD2_OK;
+    if (!constants || bytes < (size_t)p.const_bytes || ((uintptr_t)constants & 255))
+      throw Error(SOD2_ERR_INVALID_ARG, "constants buffer must be 256-byte aligned and hold " + std::to_string(p.const_bytes) + " bytes");
+    for (const auto& kv : p.const_off) {
+      const Group& gr = p.groups.at(kv.first);
+      const Op& mm = G.ops[gr.chain[0]];
+      const Op& ln = G.ops[gr.lnfold];
+      // scale and bias of the contraction's epilogue, as the run reads them
+      float scale = 1.f;
+      int bias = -1, cur = mm.out[0];
+      bool seen_other = false;
+      for (size_t k = 1; k < gr.chain.size(); ++k) {
+        const Op& op = G.ops[gr.chain[k]];
+        const int o = op.in.size() > 1 ? (op.in[0] == cur ? op.in[1] : op.in[0]) : -1;
+        if (op.kind == SOD2_OP_MUL) scale *= (float)G.tensors[o].fdata.at(0);
+        else if (op.kind == SOD2_OP_ADD && G.tensors[o].role == SOD2_WEIGHT && bias < 0 && !seen_other) bias = o;
+        else if (op.kind != SOD2_OP_TRANSPOSE) seen_other = true;
+        cur = op.out[0];
+      }
+      auto wptr = [&](int t) -> const void* {
+        if (t < 0) return nullptr;
+        if (G.weight_pos[t] < 0) throw Error(SOD2_ERR_UNSUPPORTED, "folded LayerNorm parameter is not a weight: " + G.tensors[t].name);
+        const void* q = weights[G.weight_pos[t]];
+        if (!q) throw Error(SOD2_ERR_INVALID_ARG, "null weight pointer");
+        return q;
+      };
+      if (G.weight_pos[ln.in[1]] < 0 || G.weight_pos[ln.in[2]] < 0) continue;   // such a pair never folds at run time
+      if (bias >= 0 && G.weight_pos[bias] < 0) continue;
+      const LS& sw = p.rdp->S[mm.in[1]];
+      const int N = (int)sw.d[0].e.const_value(), K = (int)sw.d[1].e.const_value();
+      char* base = (char*)constants + kv.second;
+      hipError_t e = launch_fold_constants(wptr(mm.in[1]), wptr(ln.in[1]), wptr(ln.in[2]), wptr(bias), scale, N, K, base,
+                                           base + 4ll * N, (hipStream_t)stream);
+      if (e != hipSuccess) throw Error(SOD2_ERR_HIP, std::string("constants kernel: ") + hipGetErrorString(e));
+    }
+    return SOD2_OK;
+  } catch (const Error& e) {
+    set_error(e.what());
+    return e.code;
+  } catch (const std::exception& e) {
+    set_error(e.what());
+    return SOD2_ERR_INVALID_ARG;
+  }
+}
+
+extern "C" sod2_status sod2_binding_set_constants(sod2_binding_t* h, const void* constants, size_t bytes) {
+  if (!h) { set_error("null argument"); return SOD2_ERR_INVALID_ARG; }
+  if (constants && ((uintptr_t)constants & 255)) { set_error("constants buffer must be 256-byte aligned"); return SOD2_ERR_INVALID_ARG; }
+  h->constants = constants;
+  h->constants_bytes = constants ? bytes : 0;
+  h->launches_valid = false;
+  return SOD2_OK;
 }
 
 extern "C" sod2_status sod2_run_static(sod2_binding_t* h, void* arena, size_t arena_bytes, const void* const* weights,

@@ -9,7 +9,8 @@ import torch
 
 from . import (pointer_array, sod2_graph_build, sod2_rdp_infer, sod2_plan, sod2_bind, sod2_run, sod2_binding_arena_bytes,
                sod2_binding_query_tensor, sod2_run_decisions, sod2_run_arena_bytes, sod2_binding_workspace_bytes,
-               sod2_replay_create, sod2_replay_launch, Sod2Error)
+               sod2_replay_create, sod2_replay_launch, sod2_plan_constants_bytes, sod2_plan_prepare_constants,
+               sod2_binding_set_constants, Sod2Error)
 
 _NP = {"f32": np.float32, "i64": np.int64, "i32": np.int32}
 _TORCH = {"f32": torch.float32, "bf16": torch.bfloat16, "i64": torch.int64, "i32": torch.int32}
@@ -38,7 +39,9 @@ def to_host(t: torch.Tensor) -> np.ndarray:
 class Session:
     """One graph on one GPU: graph -> RDP -> plan once; bind + run per call."""
 
-    def __init__(self, graph_desc, device="cuda:0", **plan_opts):
+    def __init__(self, graph_desc, device="cuda:0", derive_constants=True, **plan_opts):
+        """``derive_constants``: hand every binding the constants derived from the weights, so that normalisations
+        folded into contractions run without a kernel of their own (sod2_plan_prepare_constants)."""
         if not torch.cuda.is_available():
             raise RuntimeError("Session needs a GPU: the HIP path has no CPU fallback")
         self.desc = graph_desc
@@ -51,9 +54,24 @@ class Session:
         self.arena: Optional[torch.Tensor] = None
         self.workspace_bytes = 0
         self.stream = torch.cuda.current_stream(self.device)
+        self.derive_constants = bool(derive_constants)
+        self.constants: Optional[torch.Tensor] = None
 
     def upload_weights(self, weights: Dict[int, np.ndarray]):
         self.weights = [to_device(weights[t], self.desc.tensors[t].dtype, self.device) for t in self.desc.weights()]
+        self.prepare_constants()
+
+    def prepare_constants(self):
+        """(Re)computes the derived constants from the device weights; to be called when the weights change."""
+        n = sod2_plan_constants_bytes(self.plan) if self.derive_constants else 0
+        if n == 0:
+            self.constants = None
+            return
+        if self.constants is None or self.constants.numel() < n:
+            with torch.cuda.stream(self.stream):
+                self.constants = torch.empty(n, dtype=torch.uint8, device=self.device)
+        sod2_plan_prepare_constants(self.plan, [w.data_ptr() for w in self.weights], self.constants.data_ptr(), n,
+                                    self.stream.cuda_stream)
 
     def ensure_arena(self, nbytes: int):
         """The planned arena plus the optional workspace behind it (enables split-K)."""
@@ -73,6 +91,8 @@ class Session:
         b = sod2_bind(self.plan, sym)
         if not self.workspace_bytes:
             self.workspace_bytes = sod2_binding_workspace_bytes(b)
+        if self.constants is not None:
+            sod2_binding_set_constants(b, self.constants.data_ptr(), self.constants.numel())
         return b
 
     def run(self, binding, inputs: List[torch.Tensor], outputs: List[torch.Tensor]):
@@ -121,6 +141,8 @@ class DecoderSession:
         names = [self.dec.desc.tensors[t].name for t in self.dec.desc.weights()]
         assert names == [d.tensors[t].name for t in d.weights()], "the two graphs must declare the same weights"
         self.dec.weights = self.pre.weights
+        self.pre.prepare_constants()
+        self.dec.prepare_constants()
 
     def start(self, P: int, vocab: int):
         """Buffers of one sequence: the arena (sized for the prompt pass and the last decode step), the

@@ -5,7 +5,14 @@ depth with a mid-length prompt.  The tapped variants of the encoder and the CNN 
 after every layer / the feature map after every stage as further graph outputs (same operators, weights and
 values), so a difference is located; every tap is held to the same bar as the final output.
 
-Tolerance: max |library - oracle| / max |oracle| <= 2e-2 per tensor (bf16 storage, fp32 accumulation)."""
+The reference is the graph's plain definition: every operator evaluated in float64 on the stored weights and
+inputs, no intermediate rounded (execute.run(..., exact=True)).  Which intermediates a fused execution rounds to
+the storage type depends on the fusion plan (Section 4.2 removes their materialisation, and a LayerNorm folded
+into the contractions around it rounds x * gamma where an unfused run rounds the normalised row), so an
+operator-by-operator rounding is one execution among several, itself up to 2e-2 (max norm, 12 layers deep) away
+from the definition; the definition is what all of them approximate.
+
+Tolerance: max |library - definition| / max |definition| <= 2e-2 per tensor (bf16 storage, fp32 accumulation)."""
 import numpy as np
 import pytest
 
@@ -29,7 +36,7 @@ def _run_against_oracle(S, w, ci, sym, taps_of=None):
     Wr = {t: O.round_to(np.asarray(v, np.float64), w.graph.tensors[t].dtype) for t, v in W.items()}
     ins = w.make_inputs(ci, sym)
     po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
-    ref = execute.run(w.graph, po.order, Wr, ins, round_weights=False)
+    ref = execute.run(w.graph, po.order, Wr, ins, round_weights=False, exact=True)
     out = {}
     for name, wl in (("plain", w), ("tapped", taps_of)):
         if wl is None:

@@ -24,10 +24,10 @@ def S():
     return S
 
 
-def run_case(S, w, calls, variant=-1, check_structure=True, splits=0, **opts):
+def run_case(S, w, calls, variant=-1, check_structure=True, splits=0, derive_constants=True, traces=None, **opts):
     from paper_2403_00176_amd.session import Session, to_host
     import torch
-    ses = Session(w.graph, **opts)
+    ses = Session(w.graph, derive_constants=derive_constants, **opts)
     W = w.make_weights()
     ses.upload_weights(W)
     ro = R.RDP(w.graph).analyse()
@@ -46,6 +46,8 @@ def run_case(S, w, calls, variant=-1, check_structure=True, splits=0, **opts):
         outs = ses.alloc_outputs(ses.output_shapes(b))
         ses.run(b, ses.upload_inputs(ins), outs)
         torch.cuda.synchronize()
+        if traces is not None:
+            traces.append(S.sod2_run_trace(b))
         ref = execute.run(w.graph, po.order, W, ins)
         for t, o in zip(w.graph.outputs(), outs):
             got = to_host(o)
@@ -100,7 +102,7 @@ def test_encoder_bf16_small(S, variant):
     print("encoder small max rel err", variant, max(errs))
 
 
-@pytest.mark.parametrize("variant", list(range(10, 33)))
+@pytest.mark.parametrize("variant", list(range(10, 35)))
 def test_direct_to_lds_tiles(S, variant):
     """Every tile of the direct-to-LDS contraction kernel forced in turn (variant 10 + tile) on ragged
     encoder shapes (M tails, several k tiles, K = 3072 ring wrap-around) and on a small CNN."""
@@ -109,6 +111,38 @@ def test_direct_to_lds_tiles(S, variant):
     w = configs.resnet50(3, 1, sizes=(64, 96), stages=(1, 1, 1, 1))
     errs += run_case(S, w, [(0, {"H": 96, "W": 96})], variant=variant)
     print("dl tile", variant - 10, "max rel err", max(errs))
+
+
+@pytest.mark.parametrize("variant", [-1, 15, 17, 25, 28, 31, 33, 34, 13, 32, 3])
+def test_layernorm_as_second_result(S, variant):
+    """A LayerNorm behind a contraction, three ways on the same ragged encoder calls: (1) with the constants derived
+    from the weights the producing contraction writes the normalisation-ready rows and their statistics and the
+    reading contraction finishes the normalisation in its epilogue -- no LayerNorm kernel runs; (2) without the
+    constants the LayerNorm's kernel runs right behind the producer; (3) with the rule off it is a group of its own.
+    All three stay within the bar.  Forced in turn: the rule's own pick, every tile that has the two extra versions,
+    two that have not (the pair then goes way 2), and the plain kernel (way 2 as well).  Split k on the producer too."""
+    w = configs.config2(3, layers=2)
+    calls = [(0, {"B": 3, "L": 77}), (1, {"B": 1, "L": 32}), (2, {"B": 2, "L": 200}), (3, {"B": 4, "L": 333})]
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    n_pairs = sum(1 for gr in po.groups.values() if gr.lnfold >= 0)
+    assert n_pairs == 3           # behind each layer's attention output, and behind the first layer's FFN
+    can = variant in (-1, 15, 17, 25, 28, 31, 33, 34)
+    tr = []
+    e1 = run_case(S, w, calls, variant=variant, traces=tr)
+    for t in tr:
+        folds = [e["fold"] for e in t if e["is_group"]]
+        assert folds.count(1) == (n_pairs if can else 0) and folds.count(2) == (n_pairs if can else 0)
+        assert folds.count(3) == (0 if can else n_pairs)
+        assert sum(1 for e in t if e["is_group"] and e["kernel"] == S.KERNEL_NAMES.index("layernorm")) == 2
+    tr = []
+    e2 = run_case(S, w, calls, variant=variant, derive_constants=False, traces=tr)
+    for t in tr:
+        folds = [e["fold"] for e in t if e["is_group"]]
+        assert folds.count(3) == n_pairs and folds.count(1) == 0 and folds.count(2) == 0
+    e3 = run_case(S, w, calls, variant=variant, fold_ln=False)
+    if variant in (17, 28):
+        e1 += run_case(S, w, calls, variant=variant, splits=4)
+    print("layernorm fold", variant, "max rel err: folded", max(e1), "kernel behind", max(e2), "own group", max(e3))
 
 
 @pytest.mark.parametrize("splits", [2, 4, 16])

@@ -74,7 +74,7 @@ def test_without_fusion_every_operator_is_its_own_group(cfg):
 
 def test_encoder_layers_give_identical_subgraphs():
     w = configs.config2(2, layers=4)
-    p = make(w)
+    p = make(w, fold_ln=False)
     kinds = [[p.groups[p.items[i].ref].kind for i in sg] for sg in p.subgraphs]
     # layer 0 reads the graph input (caller memory, never in the arena) and is cut more finely;
     # every later layer gives 2 sub-graphs (attention half, MLP half); then the final LayerNorm
@@ -86,6 +86,45 @@ def test_encoder_layers_give_identical_subgraphs():
     assert per_layer[1] == per_layer[3] == per_layer[5] == ["LAYERNORM", "GEMM", "GEMM"]
     assert per_layer[6] == ["LAYERNORM"]
     assert set(p.sg_class) == {"mixed"}
+
+
+def test_layernorm_behind_a_contraction_is_its_second_result():
+    """R9: every LayerNorm of the stack but the first (it reads the graph input) and the last (it feeds the output)
+    is produced by the contraction before it: 2 * layers - 1 groups fewer, each such contraction has two results, the
+    consuming contraction names the LayerNorm, the second result is sized 2.25 bytes per element, the plan stays
+    topological and the arena still equals the peak of live bytes."""
+    layers = 4
+    w = configs.config2(2, layers=layers)
+    p, p0 = make(w), make(w, fold_ln=False)
+    assert len(p0.groups) - len(p.groups) == 2 * layers - 1
+    kinds = [p.groups[it.ref].kind for it in p.items]
+    assert kinds == ["LAYERNORM"] + ["GEMM", "ATTENTION", "GEMM", "GEMM", "GEMM"] * layers + ["LAYERNORM"]
+    g = w.graph
+    folded = [gr for gr in p.groups.values() if gr.also]
+    assert len(folded) == 2 * layers - 1 == len(p.fold_y)
+    for gr in folded:
+        ln = [n for n in gr.ops if g.ops[n].kind == "LayerNorm"]
+        assert len(ln) == 1 and g.ops[ln[0]].outputs[0] == gr.also[0] and g.ops[ln[0]].inputs[0] == gr.out
+        consumer = [c for c in p.groups.values() if c.lnfold == ln[0]]
+        assert len(consumer) == 1 and gr.also[0] in consumer[0].ins
+    # items stay in a topological order (every read is written earlier, or comes from outside)
+    written = set()
+    for it in p.items:
+        for t in it.reads:
+            pr = p.rdp.producer[t]
+            assert pr < 0 or p.folded[pr] or t in written, (it.ref, t)
+        written.update(it.writes)
+    for sym in ({"B": 2, "L": 100}, {"B": 8, "L": 512}, {"B": 1, "L": 32}):
+        b, b0 = A.bind(p, sym), A.bind(p0, sym)
+        A.check_no_overlap(b)
+        assert b.arena_bytes == b.peak_live
+        rows = sym["B"] * sym["L"]
+        for y in p.fold_y:
+            assert b.tensors[y].bytes == A.align_up(rows * 768 * 2 * 9 // 8)
+        # the second result replaces the LayerNorm tensor of the unfolded plan at 9/8 of its size: the peak (first MLP
+        # contraction: residual, normalised rows, hidden rows) grows by rows * 768 * 2 / 8 bytes
+        assert b.peak_live == b0.peak_live + rows * 768 * 2 // 8
+        assert len(b.steps) == len(b0.steps) - (2 * layers - 1)
 
 
 def _all_orders_peak(p, piece, last_read, env):
@@ -169,6 +208,8 @@ def test_arena_invariants(cfg):
             n = P.DT_BYTES[w.graph.tensors[t].dtype]
             for d in b.dims[t]:
                 n *= d
+            if t in p.fold_y:                     # R9: rows plus their partial sums, 8 bytes per 32 columns
+                n = n * 9 // 8
             assert a.bytes == (n + 255) // 256 * 256 and a.start <= a.end
         outs = w.graph.outputs()
         assert all(t not in b.tensors for t in outs)              # outputs live in caller memory
@@ -212,10 +253,13 @@ def test_peak_first_needs_no_extra_space_on_layer_chains():
         p5 = P.build_plan(gd, R.RDP(gd).analyse())
         b = A.bind(p5, sym)
         assert b.arena_bytes == b.peak_live
-    # with fused attention the FFN hidden tensor dominates at every length
+    # with fused attention the FFN hidden tensor dominates at every length; a normalisation that is the
+    # second result of a contraction carries its row statistics, an eighth of its own size
     big, small_ = A.bind(p, {"B": 8, "L": 512}), A.bind(p, {"B": 8, "L": 32})
-    assert big.peak_live == 8 * 512 * (3072 + 768 + 768) * 2
-    assert small_.peak_live == 8 * 32 * (3072 + 768 + 768) * 2
+    assert big.peak_live == 8 * 512 * (3072 + 768 + 768 + 96) * 2
+    assert small_.peak_live == 8 * 32 * (3072 + 768 + 768 + 96) * 2
+    plain = P.build_plan(w.graph, R.RDP(w.graph).analyse(), P.Opts(fold_ln=False))
+    assert A.bind(plain, {"B": 8, "L": 512}).peak_live == 8 * 512 * (3072 + 768 + 768) * 2
 
 
 def test_against_exhaustive_optimum_and_best_fit():
@@ -352,9 +396,9 @@ def test_layernorm_prologue_rule():
         gr = p.groups[p.group_of_op[n]]
         assert gr.kind == "GEMM" and gr.gid == n and g.ops[gr.ops[1]].kind == "MatMul"
         assert g.ops[n].outputs[0] not in b.tensors
-    pp = P.build_plan(w.prefill, R.RDP(w.prefill).analyse())
+    pp = P.build_plan(w.prefill, R.RDP(w.prefill).analyse(), P.Opts(fold_ln=False))
     assert [gr.kind for gr in pp.groups.values()].count("LAYERNORM") == 4      # the final one sees one row: fused
-    assert [gr.kind for gr in make(configs.config2(1, layers=2)).groups.values()].count("LAYERNORM") == 5
+    assert [gr.kind for gr in make(configs.config2(1, layers=2), fold_ln=False).groups.values()].count("LAYERNORM") == 5
     assert [gr.kind for gr in P.build_plan(g, R.RDP(g).analyse(), P.Opts(fusion=False)).groups.values()].count("LAYERNORM") == 5
 
 
@@ -392,8 +436,9 @@ def replay_storage(plan, b):
                 if b.dyn_base.get(d) in b.tensors:
                     assert tag[b.dyn_base[d]] == d, (g.tensors[t].name, g.tensors[d].name)
                     reads += 1
-        if b.dyn_base.get(gr.out) in b.tensors:
-            tag[b.dyn_base[gr.out]] = gr.out
+        for o in [gr.out] + list(gr.also):
+            if b.dyn_base.get(o) in b.tensors:
+                tag[b.dyn_base[o]] = o
     return reads
 
 
