@@ -140,12 +140,65 @@ def bench_decoder(args, S, dev):
     print(json.dumps(out))
 
 
-def measured_traffic(family):
+def bench_gemm_table(args, S, dev):
+    """The four weight contractions of config 2's layer as graphs of their own (MatMul + bias through the same C ABI),
+    at M = 1024, 2048, 4096: kernel version the shape rule picks, duration (HIP events on the launch stream, net of
+    the event overhead measured in the same run) and TFLOP/s against the bf16 MFMA peak.  Not a bench line of the
+    driver: the table behind profiles/config2_contraction_shapes.txt."""
+    import numpy as np
+    import torch
+    from paper_2403_00176_amd.session import Session
+    from workloads import GraphBuilder
+    rows = []
+    for name, N, K in (("QKV", 2304, 768), ("attention output", 768, 768), ("FFN1", 3072, 768), ("FFN2", 768, 3072)):
+        gb = GraphBuilder([("M", 1, 8192)])
+        x = gb.input("x", "bf16", ["M", K])
+        wt = gb.weight("w", "bf16", [N, K])
+        bias = gb.weight("b", "bf16", [N])
+        gb.mark_output(gb.op("Add", [gb.op("MatMul", [x, wt], transB=1), bias]), "y")
+        g = gb.build()
+        ses = Session(g, device=dev)
+        rs = np.random.RandomState(N + K)
+        ses.upload_weights({wt: rs.randn(N, K) * 0.02, bias: rs.randn(N) * 0.02})
+        for M in (1024, 2048, 4096):
+            b = ses.bind({"M": M})
+            ins = ses.upload_inputs({x: rs.randn(M, K)})
+            outs = ses.alloc_outputs(ses.output_shapes(b))
+            for _ in range(5):
+                ses.run(b, ins, outs)
+            torch.cuda.synchronize()
+            S.sod2_binding_set_profiling(b, True)
+            us, ovh, variant = [], [], None
+            for _ in range(args.steps):
+                ses.run(b, ins, outs)
+                torch.cuda.synchronize()
+                recs = S.sod2_binding_launch_records(b)
+                # (the first two records are one and two empty launches between the same kind of event pair)
+                ovh.append(max(2 * recs[0]["ms"] - recs[1]["ms"], 0.0) * 1e3 if len(recs) > 1 and recs[1]["group"] == -2 else 0.0)
+                for r in recs:
+                    if r["group"] >= 0 and r["kernel"] == "gemm":
+                        us.append(r["ms"] * 1e3)
+                        variant = r["variant"]
+            raw = float(np.median(us))
+            over = float(np.median(ovh))
+            net = raw - over
+            flops = 2.0 * M * N * K
+            rows.append(dict(contraction=name, M=M, N=N, K=K, variant=variant, us_events=round(raw, 2), event_overhead_us=round(over, 2),
+                             us_net=round(net, 2), tflops_events=round(flops / raw / 1e6, 1), tflops_net=round(flops / net / 1e6, 1),
+                             frac_of_mfma_peak_net=round(flops / net / 1e6 / PEAK_BF16_TFLOPS, 4)))
+            print(json.dumps(rows[-1]), file=sys.stderr, flush=True)
+        del ses
+    print(json.dumps({"metric": "contraction shapes of config 2", "unit": "TFLOP/s", "peak": PEAK_BF16_TFLOPS, "rows": rows}))
+
+
+def measured_traffic(family, config=2):
     """HBM bytes per launch of a kernel family, from the committed rocprofv3 --pmc summaries of this same
     command (FETCH_SIZE and WRITE_SIZE, each scaled by a plain copy of known size): counters cannot be read
     from inside the process, so the number comes from profiles/ and is None when no summary is there."""
     total = 0.0
-    for name in ("config2_fetch_size.txt", "config2_write_size.txt"):
+    if family == "conv":                  # the implicit-GEMM convolutions run the contraction kernels: the summaries list them there
+        family = "gemm"
+    for name in (f"config{config}_fetch_size.txt", f"config{config}_write_size.txt"):
         path = os.path.join(ROOT, "profiles", name)
         if not os.path.exists(path):
             return None
@@ -171,6 +224,8 @@ def main():
     ap.add_argument("--ablation", action="store_true",
                     help="optimisation breakdown: the same calls with fusion, execution planning, memory planning and "
                          "kernel versions switched on one after the other")
+    ap.add_argument("--gemm-table", action="store_true",
+                    help="the four weight contractions of config 2 at M = 1024, 2048, 4096, each a graph of its own")
     ap.add_argument("--calibration-copy-mb", type=int, default=0,
                     help="before the timed region, run a plain device copy of this many MiB three times: under "
                          "rocprofv3 --pmc it gives the scale of FETCH_SIZE / WRITE_SIZE")
@@ -193,6 +248,8 @@ def main():
     dev = torch.device("cuda:0")
     if args.ablation:
         return bench_ablation(args, S, dev)
+    if args.gemm_table:
+        return bench_gemm_table(args, S, dev)
     if args.config == 5:
         return bench_decoder(args, S, dev)
     n_calls = args.steps + args.warmup
@@ -365,9 +422,10 @@ def main():
                         for c in ("known", "mixed", "nac")}
     dom = max(per, key=lambda n: per[n]["ms"])
     d = per[dom]
-    traffic = measured_traffic(dom) if args.config == 2 else None
-    traffic_source = ("profiles/config2_fetch_size.txt + profiles/config2_write_size.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of "
-                      "this command, committed summaries (counters cannot be read inside the run)") if traffic is not None else None
+    traffic = measured_traffic(dom, args.config) if args.config in (2, 3) else None
+    traffic_source = (f"profiles/config{args.config}_fetch_size.txt + profiles/config{args.config}_write_size.txt: rocprofv3 --pmc FETCH_SIZE / "
+                      "WRITE_SIZE of this command, committed summaries (counters cannot be read inside the run); per launch of every "
+                      "contraction kernel of the run") if traffic is not None else None
     if dom in ("gemm", "conv"):
         achieved = d["flops"] / (d["ms"] * 1e-3) / 1e12
         roofline = dict(bound="mfma", kernel=dom, achieved=round(achieved, 2), peak=PEAK_BF16_TFLOPS, unit="TFLOP/s",
