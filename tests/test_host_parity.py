@@ -252,3 +252,37 @@ def test_backend_limits_of_the_fusion_rules_are_options():
             assert d == P.dump(P.build_plan(gd, ro, P.Opts(**ora_opts))), lib_opts
             changed += d != base
         assert changed >= 1
+
+
+def test_derived_constants_layout_and_argument_checks():
+    """The constants a plan's folded LayerNorms need (R9): two fp32 vectors over the columns of every contraction
+    that reads such a LayerNorm, each block rounded up to 256 bytes; none with the rule off or when no pair exists.
+    Argument errors are reported on the host (no kernel is launched for them)."""
+    w = configs.config2(4, layers=2)
+    g = S.sod2_graph_build(w.graph)
+    r = S.sod2_rdp_infer(g)
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    readers = [gr for gr in po.groups.values() if gr.lnfold >= 0]
+    assert len(readers) == 3
+    want = 0
+    for gr in readers:
+        wt = w.graph.ops[gr.ops[0]].inputs[1]
+        n = int(w.graph.tensors[wt].dims[0])
+        want += (2 * n * 4 + 255) // 256 * 256
+    p = S.sod2_plan(g, r)
+    assert S.sod2_plan_constants_bytes(p) == want == 2 * (2 * 3072 * 4) + 2 * 2304 * 4   # FFN1 of both layers, QKV of the second
+    assert S.sod2_plan_constants_bytes(S.sod2_plan(g, r, fold_ln=0)) == 0
+    w1 = configs.config1()
+    g1 = S.sod2_graph_build(w1.graph)
+    assert S.sod2_plan_constants_bytes(S.sod2_plan(g1, S.sod2_rdp_infer(g1))) == 0      # fp32 graph: the rule wants bf16
+    b = S.sod2_bind(p, {"B": 1, "L": 32})
+    with pytest.raises(S.Sod2Error):
+        S.sod2_binding_set_constants(b, 0x1008, want)                 # not 256-byte aligned
+    S.sod2_binding_set_constants(b, 0, 0)                             # back to the default
+    with pytest.raises(S.Sod2Error):
+        S.sod2_plan_prepare_constants(p, [0x1000] * 3, 0x1000, want)  # wrong number of weight pointers
+    n_w = len(w.graph.weights())
+    with pytest.raises(S.Sod2Error):
+        S.sod2_plan_prepare_constants(p, [0x1000] * n_w, 0x1000, want - 256)   # buffer too small
+    with pytest.raises(S.Sod2Error):
+        S.sod2_plan_prepare_constants(p, [0x1000] * n_w, 0x1010, want)         # buffer misaligned
