@@ -100,6 +100,10 @@ def same(a, b) -> bool:
     return a == b
 
 
+def g_is_int(g, t) -> bool:
+    return g.tensors[t].dtype in ("i64", "i32")
+
+
 def has_undef(x) -> bool:
     if x is UNDEF:
         return True
@@ -673,6 +677,7 @@ class RDP:
         out = self.S[op.outputs[0]]
         t = op.inputs[k]
         new = UNDEF
+        ch0 = False
         if op.kind == "Shape" and k == 0:
             v = self.V[op.outputs[0]]                    # the value of the result *is* the input's shape
             if isinstance(v, list):
@@ -684,6 +689,25 @@ class RDP:
             return self._refine(self.S, t, [C(len(out))]) or ch
         elif op.kind in UNARY and k == 0:
             new = out if out != NAC else UNDEF
+            if op.kind == "Cast" and g_is_int(self.g, t) and g_is_int(self.g, op.outputs[0]):
+                ch0 = self._backward_values(op, t, self.V[op.outputs[0]])     # F^bv: an integer Cast changes no value
+        elif op.kind == "Add" and g_is_int(self.g, t):
+            # F^bv: with the other operand's values known, in = out - other (unique when this operand has as
+            # many elements as the result: a broadcast one could not be told from its repeats)
+            ov, other = self.V[op.outputs[0]], self.V[op.inputs[1 - k]]
+            if isinstance(ov, list) and isinstance(other, list) and len(other) in (1, len(ov)) and \
+                    not any(e is UNDEF or e == NAC for e in other):
+                return self._backward_values(op, t, [d_sub(ov[i], other[i % len(other)]) for i in range(len(ov))])
+            return False
+        elif op.kind == "Concat" and g_is_int(self.g, t):
+            # F^bv: input k of a Concat of vectors holds the elements behind those of the inputs before it
+            ov = self.V[op.outputs[0]]
+            lens = [self.S[i] for i in op.inputs]
+            if isinstance(ov, list) and all(isinstance(x, list) and len(x) == 1 and is_expr(x[0]) and x[0].is_const() for x in lens):
+                n = [x[0].const_value() for x in lens]
+                if sum(n) == len(ov):
+                    return self._backward_values(op, t, ov[sum(n[:k]):sum(n[:k + 1])])
+            return False
         elif op.kind == "Transpose" and isinstance(out, list):
             perm = op.attrs["perm"]
             new = [UNDEF] * len(perm)
@@ -703,9 +727,20 @@ class RDP:
                 n = out[0] if isinstance(out, list) else UNDEF
                 new = [n, UNDEF, UNDEF, w[3]]
         if new is UNDEF:
-            return False
+            return ch0
         new = [UNDEF if d == NAC else d for d in new]    # a nac carries no backward information
-        return self._refine(self.S, t, new)
+        return self._refine(self.S, t, new) or ch0
+
+    def _backward_values(self, op, t, vals) -> bool:
+        """IV <- F^bv(OV): the values of input t, as many as it has elements (a vector or a scalar, known to RDP)."""
+        s = self.S[t]
+        if not isinstance(vals, list) or not isinstance(s, list) or len(s) > 1:
+            return False
+        if len(s) == 1 and not (is_expr(s[0]) and s[0].is_const() and s[0].const_value() == len(vals)):
+            return False
+        if len(s) == 0 and len(vals) != 1:
+            return False
+        return self._refine(self.V, t, [UNDEF if d == NAC else d for d in vals])
 
 
 # ---------------------------------------------------------------------------

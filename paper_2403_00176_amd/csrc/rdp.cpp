@@ -487,10 +487,22 @@ struct Analyser {
     }
   }
 
+  // IV <- F^bv(OV): the values of input t, as many as it has elements (a vector or a scalar, known to RDP)
+  bool backward_values(int t, LS vals) {
+    const LS& s = S[t];
+    if (!vals.is_list() || !s.is_list() || s.d.size() > 1) return false;
+    if (s.d.size() == 1 && !(s.d[0].k == LV::VAL && s.d[0].e.is_const() && s.d[0].e.const_value() == (int64_t)vals.d.size())) return false;
+    if (s.d.empty() && vals.d.size() != 1) return false;
+    for (auto& d : vals.d) if (d.k == LV::NAC) d = LV::undef();
+    return refine(V, t, vals);
+  }
+
   // IS <- F^bs(OS), only where the answer is unique (Section 3: Add is ambiguous, so nothing)
   bool backward(const Op& op, int k) {
     const LS& out = S[op.out[0]];
     LS nw;
+    bool ch0 = false;
+    const Graph& G = g;
     switch (op.kind) {
       case SOD2_OP_SHAPE:                               // backward value transfer: the result's value is the input's shape
         if (k == 0 && V[op.out[0]].is_list()) nw = V[op.out[0]];
@@ -505,7 +517,37 @@ struct Analyser {
       case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_CAST:
       case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM: case SOD2_OP_GROUPNORM:
         if (k == 0 && out.is_list()) nw = out;
+        if (k == 0 && op.kind == SOD2_OP_CAST && is_int(G.tensors[op.in[0]].dtype) && is_int(G.tensors[op.out[0]].dtype))
+          ch0 = backward_values(op.in[0], V[op.out[0]]);   // F^bv: an integer Cast changes no value
         break;
+      case SOD2_OP_ADD: {
+        // F^bv: with the other operand's values known, in = out - other (unique when this operand has as many
+        // elements as the result: a broadcast one could not be told from its repeats)
+        if (!is_int(G.tensors[op.in[k]].dtype)) return false;
+        const LS &ov = V[op.out[0]], &other = V[op.in[1 - k]];
+        if (!ov.is_list() || !other.is_list() || !(other.d.size() == 1 || other.d.size() == ov.d.size())) return false;
+        for (const auto& d : other.d) if (d.k != LV::VAL) return false;
+        LS vals = LS::list({});
+        for (size_t i = 0; i < ov.d.size(); ++i) vals.d.push_back(sub(ov.d[i], other.d[i % other.d.size()]));
+        return backward_values(op.in[k], vals);
+      }
+      case SOD2_OP_CONCAT: {
+        // F^bv: input k of a Concat of vectors holds the elements behind those of the inputs before it
+        if (!is_int(G.tensors[op.in[k]].dtype)) return false;
+        const LS& ov = V[op.out[0]];
+        if (!ov.is_list()) return false;
+        std::vector<int64_t> n;
+        for (int t : op.in) {
+          const LS& x = S[t];
+          if (!x.is_list() || x.d.size() != 1 || x.d[0].k != LV::VAL || !x.d[0].e.is_const()) return false;
+          n.push_back(x.d[0].e.const_value());
+        }
+        int64_t before = 0, total = 0;
+        for (size_t i = 0; i < n.size(); ++i) { if ((int)i < k) before += n[i]; total += n[i]; }
+        if (total != (int64_t)ov.d.size()) return false;
+        LS vals = LS::list(std::vector<LV>(ov.d.begin() + before, ov.d.begin() + before + n[k]));
+        return backward_values(op.in[k], vals);
+      }
       case SOD2_OP_TRANSPOSE:
         if (out.is_list()) {
           nw = LS::list(std::vector<LV>(op.ia.size()));
@@ -535,9 +577,9 @@ struct Analyser {
       default:
         break;
     }
-    if (nw.k != LS::LIST) return false;
+    if (nw.k != LS::LIST) return ch0;
     for (auto& d : nw.d) if (d.k == LV::NAC) d = LV::undef();   // a nac carries no backward information
-    return refine(S, op.in[k], nw);
+    return refine(S, op.in[k], nw) || ch0;
   }
 };
 }  // namespace

@@ -158,6 +158,32 @@ def test_input_shape_found_by_backward_value_transfer(S):
         assert np.array_equal(to_host(outs[names.index("y")]), np.ones((B, L, 8)))
 
 
+def test_runtime_sizes_found_by_backward_value_transfer(S):
+    """Sizes that arrive as a run-time integer input: RDP knows their values backwards from a declared extent
+    (through ConstantOfShape, an integer Cast, Concat and Add), so the Reshape that reads them is planned ahead of
+    time and runs as a view."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    from tests.test_shape_ops import _runtime_sizes_graph
+    g, sz, y = _runtime_sizes_graph()
+    po = P.build_plan(g, R.RDP(g).analyse())
+    ses = Session(g)
+    ses.upload_weights({})
+    for B, L in ((1, 1), (3, 5), (8, 64)):
+        sym = {"B": B, "L": L}
+        print(f"case run-time sizes {sym}", flush=True)
+        xv = np.random.RandomState(L).randn(B, 2, L, 2)
+        ins = {g.tensor_id("x"): xv, sz: np.array([2 * B, 2 * L])}
+        b = ses.bind(sym)
+        assert S.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {}, ins)
+        for t, o in zip(g.outputs(), outs):
+            assert np.array_equal(to_host(o), ref.values[t])
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_topk_router(S, dtype):
     """TopK (values and positions from one kernel), softmax over the chosen scores and a one-hot product

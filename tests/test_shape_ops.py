@@ -300,6 +300,64 @@ def test_backward_value_transfer_through_shape_and_constantofshape():
     assert np.array_equal(res.values[g.tensor_id("sum")], np.arange(168.0).reshape(3, 7, 8) + 1.0)
 
 
+def _runtime_sizes_graph(declared=True):
+    """A target size that arrives as a run-time integer input (`sz`, two values nobody knows ahead of time) and is
+    used twice: a Reshape of x to it, and -- through Add, Concat and an integer Cast -- the shape of a zero tensor
+    whose extents the graph declares.  That declaration is the only source of knowledge about the values of `sz`."""
+    b = GraphBuilder([("B", 1, 8), ("L", 1, 64)])
+    x = b.input("x", "f32", ["B", 2, "L", 2])
+    sz = b.input("sz", "i64", [2])
+    plus = b.op("Add", [sz, b.const("off", [0, 3])])                      # [2 B, 2 L + 3]
+    cat = b.op("Concat", [b.const("lead", [2]), plus], axis=0)            # [2, 2 B, 2 L + 3]
+    z = b.op("ConstantOfShape", [b.op("Cast", [cat], dtype="i32")], dtype="f32", value=0.0)
+    if declared:
+        b.g.tensors[z].dims = [2, "B+B", "L+L+3"]
+    b.mark_output(z, "zeros")
+    y = b.op("Reshape", [x, sz])
+    b.mark_output(b.op("Relu", [y]), "y")
+    return b.build(), sz, y
+
+
+def test_backward_value_transfer_through_add_concat_and_cast():
+    """Table 3's F^bv beyond Shape / ConstantOfShape: values flow backwards through an integer Cast (unchanged),
+    a Concat of vectors (each input gets its own stretch) and an Add whose other operand is known (the
+    difference).  The Reshape that reads the same run-time sizes then has a resolved symbolic shape instead of
+    nac, so what follows it is planned ahead of time."""
+    g, sz, y = _runtime_sizes_graph()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.V[sz]) == "[e:2*B, e:2*L]"
+    assert R.fmt_list(r.S[y]) == "[e:2*B, e:2*L]"
+    import random
+    order = list(range(len(g.ops)))
+    for seed in range(6):
+        random.Random(seed).shuffle(order)
+        assert R.dump(R.RDP(g).analyse(list(order))) == R.dump(r)
+    # without the declaration the sizes stay unknown and the Reshape's result is not a constant of any kind
+    g2, sz2, y2 = _runtime_sizes_graph(declared=False)
+    r2 = R.RDP(g2).analyse()
+    assert r2.V[sz2] == R.NAC and r2.S[y2] == R.NAC
+    # an Add never hands values to an operand it may have broadcast (a scalar against a vector result)
+    b = GraphBuilder([("B", 1, 8)])
+    one = b.input("one", "i64", [1])
+    zz = b.op("ConstantOfShape", [b.op("Add", [one, b.const("c", [1, 2])])], dtype="f32", value=0.0)
+    b.g.tensors[zz].dims = ["B", "B+1"]
+    b.mark_output(zz, "z")
+    r3 = R.RDP(b.build()).analyse()
+    assert r3.V[one] == R.NAC
+    for gg, rr in ((g, r), (g2, r2), (b.build(), r3)):
+        assert S.sod2_rdp_dump(S.sod2_rdp_infer(S.sod2_graph_build(gg))) == R.dump(rr)
+    plan = P.build_plan(g, r)
+    gl = S.sod2_graph_build(g)
+    pl = S.sod2_plan(gl, S.sod2_rdp_infer(gl))
+    assert S.sod2_plan_dump(pl) == P.dump(plan)
+    sym = {"B": 3, "L": 5}
+    assert S.sod2_binding_dump(S.sod2_bind(pl, sym)) == A.dump(A.bind(plan, sym))
+    xs = np.arange(3 * 2 * 5 * 2, dtype=np.float64).reshape(3, 2, 5, 2) - 20.0
+    res = execute.run(g, plan.order, {}, {g.tensor_id("x"): xs, sz: np.array([6, 10])})
+    assert np.array_equal(res.values[g.tensor_id("y")], np.maximum(xs.reshape(6, 10), 0.0))
+    assert res.values[g.tensor_id("zeros")].shape == (2, 6, 13)
+
+
 def _router_graph(dtype="f32"):
     """A routing head: scores = x W^T, the K best of them per row (K is a dim of another input, read
     through Shape), softmax over those, and the table rows of the chosen columns picked with a one-hot
