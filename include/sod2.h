@@ -61,7 +61,10 @@ enum { SOD2_INTER = 0, SOD2_INPUT = 1, SOD2_WEIGHT = 2, SOD2_HOSTCONST = 3 };
  *   integer tensors).  Expand: data, shape.  ConstantOfShape: shape.  EyeLike: a matrix.  OneHot:
  *   indices, depth (one-element integer tensor), values = float HOSTCONST [off, on]; last axis.
  *   TopK: data, k (one-element integer tensor); two results, values then positions; last axis,
- *   largest first, of equal entries the lower position first.  GroupNorm (GroupNormalization, channels last): data
+ *   largest first, of equal entries the lower position first.  MaxUnpool (channels last): data x, int64 indices of the
+ *   same shape (positions in the flattened result, distinct; positions outside it are ignored), output_shape (a short
+ *   int tensor whose values are the result's shape; Table 2: ISVDOS); the rest of the result is zero.
+ *   GroupNorm (GroupNormalization, channels last): data
  *   [N, ..., C], scale [C], bias [C]; per sample and group of C / groups channels, mean and biased variance over the
  *   group's channels at every position.  Switch: data, predicate (one float);
  *   two results: taken when predicate <= threshold, taken when predicate > threshold.               */
@@ -71,7 +74,7 @@ enum {
   SOD2_OP_GELU, SOD2_OP_SIGMOID, SOD2_OP_CAST, SOD2_OP_SOFTMAX, SOD2_OP_LAYERNORM,
   SOD2_OP_REDUCEMEAN, SOD2_OP_MAXPOOL, SOD2_OP_ARGMAX, SOD2_OP_CACHEAPPEND, SOD2_OP_NONZERO,
   SOD2_OP_SWITCH, SOD2_OP_COMBINE, SOD2_OP_SCATTERROWS, SOD2_OP_RESIZE, SOD2_OP_RANGE, SOD2_OP_EXPAND,
-  SOD2_OP_UPSAMPLE, SOD2_OP_CONSTANTOFSHAPE, SOD2_OP_EYELIKE, SOD2_OP_ONEHOT, SOD2_OP_TOPK, SOD2_OP_GROUPNORM, SOD2_OP_COUNT
+  SOD2_OP_UPSAMPLE, SOD2_OP_CONSTANTOFSHAPE, SOD2_OP_EYELIKE, SOD2_OP_ONEHOT, SOD2_OP_TOPK, SOD2_OP_GROUPNORM, SOD2_OP_MAXUNPOOL, SOD2_OP_COUNT
 };
 
 #define SOD2_MAX_RANK 8
@@ -179,7 +182,7 @@ sod2_status sod2_plan_dump(const sod2_plan_t*, char* buf_host, size_t cap, size_
  * tensors the group reads from outside itself; info->n_ops / n_ins always hold the full counts. */
 enum { SOD2_G_GEMM = 0, SOD2_G_CONV, SOD2_G_LAYERNORM, SOD2_G_SOFTMAX, SOD2_G_MAXPOOL, SOD2_G_REDUCEMEAN, SOD2_G_ARGMAX,
        SOD2_G_CACHEAPPEND, SOD2_G_NONZERO, SOD2_G_GATHER, SOD2_G_ELTWISE, SOD2_G_ATTENTION, SOD2_G_SCATTER, SOD2_G_RESIZE,
-       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM };
+       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM, SOD2_G_MAXUNPOOL };
 typedef struct {
   int32_t gid;        /* group id: the smallest operator id in the group */
   int32_t kind;       /* SOD2_G_* */
@@ -342,7 +345,7 @@ typedef struct {
   int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other,
                           8 gather, 9 cache append, 10 argmax, 11 fused attention, 12 nonzero,
                           13 scatter rows, 14 resize (nearest), 15 concat, 16 range, 17 fill (constant / identity),
-                          18 one-hot, 19 top-k, 20 group normalisation */
+                          18 one-hot, 19 top-k, 20 group normalisation, 21 max-unpool */
   int32_t variant;
   int32_t reserved;
   float ms;            /* event-to-event duration */

@@ -109,6 +109,8 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
             y = O.softmax(xs[0], a.get("causal", 0))
         elif k == "LayerNorm":
             y = O.layernorm(xs[0], xs[1], xs[2], a["eps"])
+        elif k == "MaxUnpool":
+            y = O.maxunpool(xs[0], xs[1], xs[2])
         elif k == "GroupNorm":
             y = O.groupnorm(xs[0], xs[1], xs[2], int(a["groups"]), a["eps"])
         elif k == "ReduceMean":

@@ -85,6 +85,21 @@ def layernorm(x, gamma, beta, eps):
     return (x - mu) / np.sqrt(var + eps) * gamma + beta
 
 
+def maxunpool(x, idx, out_shape):
+    """MaxUnpool (Table 2; the partial inverse of MaxPool): a tensor of zeros of shape ``out_shape`` in which
+    element ``idx[i]`` (a position in the flattened result, as a pooling operator reports where it found each
+    maximum) holds ``x[i]``.  Positions outside the result are ignored; the positions are expected to be distinct
+    (windows that do not overlap), with repeats the highest ``i`` stays."""
+    out_shape = tuple(int(v) for v in np.asarray(out_shape).reshape(-1))
+    y = np.zeros(int(np.prod(out_shape)), dtype=np.float64)
+    flat_x = np.asarray(x, np.float64).reshape(-1)
+    flat_i = np.asarray(idx, np.int64).reshape(-1)
+    for i in range(flat_x.size):
+        if 0 <= flat_i[i] < y.size:
+            y[flat_i[i]] = flat_x[i]
+    return y.reshape(out_shape)
+
+
 def groupnorm(x, gamma, beta, groups, eps):
     """GroupNormalization (Table 2), channels last: x [N, ..., C]; the C channels form ``groups`` groups of consecutive
     channels; per sample and group, mean and biased variance over the group's channels at every position; then the

@@ -17,7 +17,7 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     operator that does not fit.  With fusion switched off only a directly
     following Transpose is still taken: the permuted store is a layout choice
     of the contraction, and without it the Reshape behind it would need a copy.
-R3  LayerNorm, GroupNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
+R3  LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
     ScatterRows, Resize, Upsample, OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
 R4  Remaining elementwise operators chain, up to 8 ops.  An aligned dim pair of
@@ -95,7 +95,7 @@ ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast")
 SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
         "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
         "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE",
-        "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT", "TopK": "TOPK", "GroupNorm": "GROUPNORM"}
+        "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT", "TopK": "TOPK", "GroupNorm": "GROUPNORM", "MaxUnpool": "MAXUNPOOL"}
 
 
 @dataclass

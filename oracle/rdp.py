@@ -34,7 +34,7 @@ OP_CLASS = {
     "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
     "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS, "Range": ISVDOS, "Expand": ISVDOS,
-    "OneHot": ISVDOS, "Upsample": ISVDOS, "TopK": ISVDOS, "GroupNorm": ISVDOS,
+    "OneHot": ISVDOS, "Upsample": ISVDOS, "TopK": ISVDOS, "GroupNorm": ISVDOS, "MaxUnpool": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
 UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "GroupNorm")   # result shaped like input 0
@@ -658,6 +658,19 @@ class RDP:
             return list(tv), UNDEF
         if isinstance(x, list):
             return [NAC] * len(x), UNDEF               # the rank survives, the extents do not
+        return NAC, UNDEF
+
+    def _f_MaxUnpool(self, op):
+        """Output shape = the values of the output_shape input (Table 2 lists MaxUnpool under ISVDOS)."""
+        x, ts, tv = self.S[op.inputs[0]], self.S[op.inputs[2]], self.V[op.inputs[2]]
+        if x is UNDEF or ts is UNDEF or tv is UNDEF:
+            return None
+        if isinstance(tv, list):
+            if isinstance(x, list) and len(x) != len(tv):
+                raise ShapeMismatch("MaxUnpool rank")
+            return list(tv), UNDEF
+        if isinstance(x, list):
+            return [NAC] * len(x), UNDEF
         return NAC, UNDEF
 
     def _f_ScatterRows(self, op):

@@ -830,6 +830,32 @@ hipError_t launch_fill(const FillArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// MaxUnpool: the result is cleared by one kernel and the values are dropped at their positions by a second one on
+// the same stream (positions are distinct by contract: the stores of one launch never meet).
+template <class T>
+__global__ __launch_bounds__(256) void unpool_clear_kernel(UnpoolArgs a) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i < a.n_out) ((T*)a.y)[i] = (T)0;
+}
+template <class T>
+__global__ __launch_bounds__(256) void unpool_scatter_kernel(UnpoolArgs a) {
+  const long long i = (long long)blockIdx.x * 256 + threadIdx.x;
+  if (i >= a.n_in) return;
+  const long long at = ((const long long*)a.idx)[i];
+  if (at >= 0 && at < a.n_out) ((T*)a.y)[at] = ((const T*)a.x)[i];
+}
+hipError_t launch_unpool(const Launch& L, const UnpoolArgs& a, hipStream_t s) {
+  if (a.n_out <= 0) return hipSuccess;
+  const dim3 go((unsigned)((a.n_out + 255) / 256)), gi((unsigned)((a.n_in + 255) / 256));
+  if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(unpool_clear_kernel<unsigned short>, go, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(unpool_clear_kernel<unsigned int>, go, dim3(256), 0, s, a);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess || a.n_in <= 0) return e;
+  if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(unpool_scatter_kernel<unsigned short>, gi, dim3(256), 0, s, a);
+  else hipLaunchKernelGGL(unpool_scatter_kernel<unsigned int>, gi, dim3(256), 0, s, a);
+  return hipGetLastError();
+}
+
 __global__ __launch_bounds__(256) void onehot_kernel(OneHotArgs a) {
   const long long e = (long long)blockIdx.x * 256 + threadIdx.x;
   if (e >= a.n * a.depth) return;

@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT, K_TOPK, K_GROUPNORM };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT, K_TOPK, K_GROUPNORM, K_MAXUNPOOL };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -216,6 +216,12 @@ struct TopKArgs {
   int x_bf16, idx_i32;
 };
 
+// MaxUnpool: y (n_out elements) = 0 except y[idx[i]] = x[i] for the n_in elements of x
+struct UnpoolArgs {
+  const void* x; const void* idx; void* y;
+  long long n_in, n_out;
+};
+
 // GroupNormalization, channels last: x[n, s, c] with s positions and C = groups * cpg channels, dense;
 // y = (x - mean(n, g)) / sqrt(var(n, g) + eps) * gamma[c] + beta[c], statistics over the s * cpg elements of a group
 struct GroupNormArgs {
@@ -251,6 +257,7 @@ struct Launch {
     OneHotArgs onehot;
     TopKArgs topk;
     GroupNormArgs gn;
+    UnpoolArgs unpool;
   } u;
   int unit_bytes = 0;      // resize / concat: bytes of one copy unit
   bool is_layernorm = false;

@@ -8,7 +8,7 @@
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
 //     consumer of the chain so far;
-//  R3 LayerNorm, GroupNorm, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
+//  R3 LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
 //     OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
 //  R4 other elementwise operators chain (up to 8).  A dim pair of the two operands of a binary member is proven when
@@ -40,7 +40,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -219,6 +219,7 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_ONEHOT) new_group(G_ONEHOT, {n});
     else if (op.kind == SOD2_OP_TOPK) new_group(G_TOPK, {n});
     else if (op.kind == SOD2_OP_GROUPNORM) new_group(G_GROUPNORM, {n});
+    else if (op.kind == SOD2_OP_MAXUNPOOL) new_group(G_MAXUNPOOL, {n});
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);

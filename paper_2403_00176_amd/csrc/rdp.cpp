@@ -17,14 +17,14 @@ static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
     "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand", "Upsample", "ConstantOfShape",
-    "EyeLike", "OneHot", "TopK", "GroupNorm"};
+    "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
   switch (kind) {
     case SOD2_OP_SHAPE: case SOD2_OP_CONSTANTOFSHAPE: case SOD2_OP_EYELIKE: return 0;
     case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: case SOD2_OP_RANGE: case SOD2_OP_EXPAND:
-    case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: case SOD2_OP_TOPK: case SOD2_OP_GROUPNORM: return 2;
+    case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: case SOD2_OP_TOPK: case SOD2_OP_GROUPNORM: case SOD2_OP_MAXUNPOOL: return 2;
     case SOD2_OP_NONZERO: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
     default: return 1;
   }
@@ -424,6 +424,16 @@ struct Analyser {
           return done(LS::list(tv.d));
         }
         if (x.is_list()) return done(LS::list(std::vector<LV>(x.d.size(), LV::nac())));   // the rank survives
+        return done(LS::nac());
+      }
+      case SOD2_OP_MAXUNPOOL: {                          // output shape = the values of the output_shape input (ISVDOS)
+        const LS &x = in_s(0), &ts = in_s(2), &tv = in_v(2);
+        if (x.k == LS::UNDEF || ts.k == LS::UNDEF || tv.k == LS::UNDEF) return r;
+        if (tv.is_list()) {
+          if (x.is_list() && x.d.size() != tv.d.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "MaxUnpool rank");
+          return done(LS::list(tv.d));
+        }
+        if (x.is_list()) return done(LS::list(std::vector<LV>(x.d.size(), LV::nac())));
         return done(LS::nac());
       }
       case SOD2_OP_CONSTANTOFSHAPE: {                    // shape = the values of the input, every element the attribute

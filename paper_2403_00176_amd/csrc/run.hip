@@ -29,6 +29,7 @@ hipError_t launch_fill(const FillArgs& a, hipStream_t s);
 hipError_t launch_onehot(const OneHotArgs& a, hipStream_t s);
 hipError_t launch_topk(const TopKArgs& a, hipStream_t s);
 hipError_t launch_groupnorm(const Launch& L, const GroupNormArgs& a, hipStream_t s);
+hipError_t launch_unpool(const Launch& L, const UnpoolArgs& a, hipStream_t s);
 hipError_t launch_attention(const AttnArgs& a, hipStream_t s);
 hipError_t launch_null(hipStream_t s);
 hipError_t launch_fold_constants(const void* W, const void* gamma, const void* beta, const void* bias, float scale, int N,
@@ -1203,6 +1204,30 @@ struct Builder {
     return L;
   }
 
+  Launch maxunpool(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_MAXUNPOOL;
+    const Op& op = G.ops[gr.ops[0]];
+    const View &vx = view_of(op.in[0]), &vi = view_of(op.in[1]);
+    const int dt = G.tensors[op.in[0]].dtype;
+    if (!vx.contiguous() || !vi.contiguous() || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt ||
+        G.tensors[op.in[1]].dtype != SOD2_I64)
+      throw Error(SOD2_ERR_UNSUPPORTED, "MaxUnpool kernel: dense float data, dense int64 positions, a result of the data's type");
+    if (vi.dims != vx.dims) throw Error(SOD2_ERR_SHAPE_MISMATCH, "MaxUnpool: data and positions differ in shape");
+    UnpoolArgs a{};
+    a.n_in = vx.numel();
+    a.n_out = 1;
+    for (int64_t d : eval_dims(gr.out)) a.n_out *= d;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(vx, dt);
+    L.r[1] = ref_of(vi, SOD2_I64);
+    L.r[2] = ref_t(gr.out);
+    L.u.unpool = a;
+    L.bytes = (double)dtype_bytes(dt) * ((double)a.n_in + (double)a.n_out) + 8.0 * (double)a.n_in;
+    return L;
+  }
+
   Launch make(const Group& gr) {
     // a result without elements (an empty compacted batch): nothing to compute
     auto od = b.dims.find(gr.out);
@@ -1219,6 +1244,7 @@ struct Builder {
       case G_ONEHOT: return onehot(gr);
       case G_TOPK: return topk(gr);
       case G_GROUPNORM: return groupnorm(gr);
+      case G_MAXUNPOOL: return maxunpool(gr);
       case G_RESIZE: return resize(gr);
       case G_CONCAT: return concat(gr);
       case G_ATTENTION: return attention(gr);
@@ -1290,6 +1316,12 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       TopKArgs a = L.u.topk;
       a.x = P.at(L.r[0]); a.values = P.at(L.r[1]); a.indices = P.at(L.r[2]);
       return launch_topk(a, s);
+    }
+    case K_MAXUNPOOL: {
+      UnpoolArgs a = L.u.unpool;
+      a.x = P.at(L.r[0]); a.idx = P.at(L.r[1]); a.y = P.at(L.r[2]);
+      if (((uintptr_t)a.idx & 7) != 0) return hipErrorInvalidValue;
+      return launch_unpool(L, a, s);
     }
     case K_GROUPNORM: {
       GroupNormArgs a = L.u.gn;

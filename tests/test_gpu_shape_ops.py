@@ -324,3 +324,36 @@ def test_groupnorm_kernel(S_lib, dtype, groups, channels):
         torch.cuda.synchronize()
         ref = execute.run(g, po.order, W, ins).values[g.outputs()[0]]
         assert rel_err(to_host(outs[0]), ref) <= (1e-4 if dtype == "f32" else 2e-2), sym
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_maxunpool_kernel(S_lib, dtype):
+    """MaxUnpool on the GPU: bit-exact (a copy of stored values to computed positions, zeros elsewhere), several
+    sizes including one whose element count is no multiple of the workgroup size; positions outside the result
+    are dropped."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    from oracle import ops as O
+    from tests.test_shape_ops import _unpool_graph, _pool_positions
+    g, y = _unpool_graph(dtype)
+    po = P.build_plan(g, R.RDP(g).analyse())
+    ses = Session(g)
+    ses.upload_weights({})
+    rs = np.random.RandomState(2)
+    for N, H, W in ((1, 1, 1), (2, 3, 5), (4, 32, 32), (3, 17, 9)):
+        sym = {"N": N, "H": H, "W": W}
+        print(f"case maxunpool {dtype} {sym}", flush=True)
+        pooled, pos = _pool_positions(rs.randn(N, 2 * H, 2 * W, 8) + 3.0)
+        if H > 1:
+            pos[0, 0, 0, 0] = -5                         # outside: dropped
+            pos[-1, -1, -1, -1] = N * 4 * H * W * 8      # one past the end: dropped
+        ins = {g.tensor_id("x"): pooled, g.tensor_id("idx"): pos}
+        b = ses.bind(sym)
+        assert S_lib.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {}, ins)
+        got = to_host(outs[0])
+        assert got.shape == (N, 2 * H, 2 * W, 8) and np.array_equal(got, ref.values[g.tensor_id("y")])
+        assert np.count_nonzero(got) == pooled.size - (2 if H > 1 else 0)

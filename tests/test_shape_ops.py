@@ -527,3 +527,65 @@ def test_groupnorm_closed_forms_and_structure():
     assert S.sod2_op_kind_class("GroupNorm") == "ISVDOS"
     for sym in ({"H": 7, "W": 9}, {"H": 64, "W": 64}):
         assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(p, sym))
+
+
+def _unpool_graph(dtype="f32", known_sizes=True):
+    """x [N, h, w, C] and the positions of its elements in a map twice as large per side, whose shape is computed
+    in the graph from the shape of x (Shape, Mul by [1, 2, 2, 1]): MaxUnpool's output_shape input."""
+    b = GraphBuilder([("N", 1, 4), ("H", 1, 32), ("W", 1, 32)])
+    x = b.input("x", dtype, ["N", "H", "W", 8])
+    idx = b.input("idx", "i64", ["N", "H", "W", 8])
+    if known_sizes:
+        shp = b.op("Mul", [b.op("Shape", [x], dtype="i64"), b.const("two", [1, 2, 2, 1])])
+    else:
+        shp = b.input("shp", "i64", [4])
+    y = b.op("MaxUnpool", [x, idx, shp], dtype=dtype)
+    b.mark_output(b.op("Relu", [y]), "y")
+    return b.build(), y
+
+
+def _pool_positions(big):
+    """Non-overlapping 2 x 2 max-pool of a channels-last map: the maxima and their positions in the flattened map."""
+    n, hh, ww, c = big.shape
+    h, w = hh // 2, ww // 2
+    win = big.reshape(n, h, 2, w, 2, c).transpose(0, 1, 3, 5, 2, 4).reshape(n, h, w, c, 4)
+    arg = win.argmax(-1)
+    dy, dx = arg // 2, arg % 2
+    nn, yy, xx, cc = np.meshgrid(np.arange(n), np.arange(h), np.arange(w), np.arange(c), indexing="ij")
+    pos = ((nn * hh + 2 * yy + dy) * ww + 2 * xx + dx) * c + cc
+    return win.max(-1), pos
+
+
+def test_maxunpool_against_its_definition_and_structure():
+    """MaxUnpool (Table 2, ISVDOS) puts each pooled value back where the pooling found it, zeros elsewhere:
+    pooling the result again returns the pooled values; the sum is preserved; out-of-range positions are dropped.
+    The result's shape comes from a value map (computed from Shape here; nac when it is a run-time input)."""
+    rs = np.random.RandomState(4)
+    big = rs.randn(2, 6, 10, 3) + 3.0                               # positive: the zeros never win a window
+    pooled, pos = _pool_positions(big)
+    back = O.maxunpool(pooled, pos, [2, 6, 10, 3])
+    assert back.shape == big.shape and np.count_nonzero(back) == pooled.size
+    assert np.array_equal(back.reshape(-1)[pos.reshape(-1)], pooled.reshape(-1))
+    assert np.array_equal(_pool_positions(back)[0], pooled) and np.isclose(back.sum(), pooled.sum())
+    assert np.array_equal(back != 0, big == np.repeat(np.repeat(pooled, 2, 1), 2, 2))
+    # a hand-made case, and positions outside the result are ignored
+    assert np.array_equal(O.maxunpool([5.0, 7.0], [3, 0], [4]), [7.0, 0.0, 0.0, 5.0])
+    assert np.array_equal(O.maxunpool([5.0, 7.0, 9.0], [3, -1, 4], [4]), [0.0, 0.0, 0.0, 5.0])
+    g, y = _unpool_graph()
+    r = R.RDP(g).analyse()
+    assert R.fmt_list(r.S[y]) == "[s:N, e:2*H, e:2*W, k:8]" and R.OP_CLASS["MaxUnpool"] == "ISVDOS"
+    g2, y2 = _unpool_graph(known_sizes=False)
+    assert R.RDP(g2).analyse().S[y2] == R.NAC
+    p = P.build_plan(g, r)
+    assert sorted(gr.kind for gr in p.groups.values()) == ["ELTWISE", "MAXUNPOOL"]
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    lp = S.sod2_plan(lg, lr)
+    assert S.sod2_rdp_dump(lr) == R.dump(r) and S.sod2_plan_dump(lp) == P.dump(p)
+    assert S.sod2_rdp_dump(S.sod2_rdp_infer(S.sod2_graph_build(g2))) == R.dump(R.RDP(g2).analyse())
+    assert S.sod2_op_kind_class("MaxUnpool") == "ISVDOS"
+    for sym in ({"N": 1, "H": 3, "W": 5}, {"N": 4, "H": 32, "W": 32}):
+        assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(p, sym))
+    pooled8, pos8 = _pool_positions(rs.randn(2, 6, 10, 8) + 3.0)
+    res = execute.run(g, p.order, {}, {g.tensor_id("x"): pooled8, g.tensor_id("idx"): pos8})
+    assert np.array_equal(_pool_positions(res.values[g.tensor_id("y")])[0], O.round_to(pooled8, "f32"))

@@ -54,6 +54,7 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "TopK": (),               # inputs x, k (one-element int tensor); results values, indices (last axis, largest first)
     "Resize": (),             # nearest neighbour, target shape = the values of input 1 ("sizes")
     "GroupNorm": ("groups",), # GroupNormalization, channels last: inputs x [N, ..., C], scale [C], bias [C]; float attr eps
+    "MaxUnpool": (),          # channels last: inputs x [N, h, w, C], indices (same shape, flat positions in the result), output_shape (its values)
     "ScatterRows": (),        # ScatterND with row indices: copy of input 0 whose rows input 1 are replaced by input 2
 }
 OP_KINDS = tuple(OP_ATTRS)
