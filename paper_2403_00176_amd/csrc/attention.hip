@@ -272,9 +272,7 @@ __global__ __launch_bounds__(DEC_THREADS) void decode_attention_kernel(AttnArgs 
       float s = 0.f;
 #pragma unroll
       for (int e = 0; e < 8; ++e) s = fmaf(qf[e], bf2f(k[u].h[e]), s);
-      s += __shfl_xor(s, 1, 64);
-      s += __shfl_xor(s, 2, 64);
-      s += __shfl_xor(s, 4, 64);
+      s = octet_sum(s);                                // the 8 lanes that share the key
       const int t = t0 + u * DEC_KG;
       if (t < n_keys) {
         if (dc == 0) prob[t] = s;

@@ -55,14 +55,39 @@ __device__ __forceinline__ float apply_act(float v, int act) {
   return v;
 }
 
+// Reductions over the 64 lanes of a wave (all of them active), through the data-parallel-primitive lane moves: no LDS
+// round trip per step as with a lane permute (a chain of six of those is ~0.3 us; three such chains made up a sixth
+// of the one-row LayerNorm + contraction kernel).  Steps: lane ^ 1 and lane ^ 2 inside a quad, the mirror inside a
+// half row of 8 and inside a row of 16, then lane 15 of rows 0 and 2 into rows 1 and 3 and lane 31 into the upper
+// half: lane 63 holds the result, which every lane reads.
+template <int CTRL, int ROW_MASK = 0xF>
+__device__ __forceinline__ float dpp_move(float old, float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, old), __builtin_bit_cast(int, v), CTRL,
+                                                               ROW_MASK, 0xF, false));
+}
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
-  return v;
+  v += dpp_move<0xB1>(0.f, v);                    // quad_perm [1, 0, 3, 2]
+  v += dpp_move<0x4E>(0.f, v);                    // quad_perm [2, 3, 0, 1]
+  v += dpp_move<0x141>(0.f, v);                   // row_half_mirror
+  v += dpp_move<0x140>(0.f, v);                   // row_mirror
+  v += dpp_move<0x142, 0xA>(0.f, v);              // row_bcast15 into rows 1 and 3
+  v += dpp_move<0x143, 0xC>(0.f, v);              // row_bcast31 into rows 2 and 3
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
 }
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  v = fmaxf(v, dpp_move<0xB1>(v, v));
+  v = fmaxf(v, dpp_move<0x4E>(v, v));
+  v = fmaxf(v, dpp_move<0x141>(v, v));
+  v = fmaxf(v, dpp_move<0x140>(v, v));
+  v = fmaxf(v, dpp_move<0x142, 0xA>(v, v));
+  v = fmaxf(v, dpp_move<0x143, 0xC>(v, v));
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+// sum over the 8 lanes 8 q .. 8 q + 7, in every one of them
+__device__ __forceinline__ float octet_sum(float v) {
+  v += dpp_move<0xB1>(0.f, v);
+  v += dpp_move<0x4E>(0.f, v);
+  v += dpp_move<0x141>(0.f, v);
   return v;
 }
 

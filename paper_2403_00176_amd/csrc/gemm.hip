@@ -724,18 +724,35 @@ __global__ __launch_bounds__(256) void gemv_kernel(GemmArgs g) {
 #pragma unroll
   for (int m = 0; m < MR; ++m) acc[m] = 0.f;
   const int nchunk = g.K >> 3;
-#pragma unroll 4
-  for (int c = lane; c < nchunk; c += 64) {
-    V16 w; w.u = *(const uint4*)(B + c * 8);
-    float wf[8];
+  // 8 weight chunks in flight per lane (a whole column for K <= 4096): a loop over a run-time count would wait for
+  // each load before it issues the next
+  for (int c0 = lane; c0 < nchunk; c0 += 64 * 8) {
+    V16 w[8], a0[MR == 1 ? 8 : 1];
 #pragma unroll
-    for (int e = 0; e < 8; ++e) wf[e] = bf2f(w.h[e]);
+    for (int u = 0; u < 8; ++u) w[u].u = (c0 + 64 * u < nchunk) ? *(const uint4*)(B + (c0 + 64 * u) * 8) : zero4();
+    if (MR == 1) {                                  // the single row's chunks go out with the weights
 #pragma unroll
-    for (int m = 0; m < MR; ++m) {
-      if (m < g.M) {
-        V16 a; a.u = *(const uint4*)(A + (long long)m * g.a_sm + c * 8);
+      for (int u = 0; u < 8; ++u) a0[u].u = (c0 + 64 * u < nchunk) ? *(const uint4*)(A + (c0 + 64 * u) * 8) : zero4();
+    }
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc[m] = fmaf(bf2f(a.h[e]), wf[e], acc[m]);
+    for (int u = 0; u < 8; ++u) {
+      const int c = c0 + 64 * u;
+      if (c >= nchunk) continue;
+      float wf[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) wf[e] = bf2f(w[u].h[e]);
+      if (MR == 1) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[0] = fmaf(bf2f(a0[u].h[e]), wf[e], acc[0]);
+        continue;
+      }
+#pragma unroll
+      for (int m = 0; m < MR; ++m) {
+        if (m < g.M) {
+          V16 a; a.u = *(const uint4*)(A + (long long)m * g.a_sm + c * 8);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc[m] = fmaf(bf2f(a.h[e]), wf[e], acc[m]);
+        }
       }
     }
   }
