@@ -444,7 +444,13 @@ __global__ __launch_bounds__(256) void reduce_mean_kernel(ReduceArgs a) {
   float s = 0.f;
   if (c < a.C) {
     const TI* x = (const TI*)a.x + (long long)b * a.R * a.C + c;
-    for (long long r = w; r < a.R; r += 4) s += to_f<TI>(x[r * a.C]);
+    for (long long r0 = w; r0 < a.R; r0 += 4 * 8) {          // 8 rows in flight per lane, added in row order
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (r0 + 4 * u < a.R) ? to_f<TI>(x[(r0 + 4 * u) * a.C]) : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
   }
   part[w][lane] = s;
   __syncthreads();
@@ -454,8 +460,7 @@ __global__ __launch_bounds__(256) void reduce_mean_kernel(ReduceArgs a) {
   }
 }
 
-// The same for bf16 rows with 16 waves splitting the rows, so that every wave has only a few
-// independent loads in flight.  A lane owns CPL consecutive channels (8: 16-byte loads, a workgroup
+// The same for bf16 rows with 16 waves splitting the rows.  A lane owns CPL consecutive channels (8: 16-byte loads, a workgroup
 // covers 512 channels; 2: 4-byte loads, 128 channels per workgroup, for when 512-channel workgroups
 // would be too few to pull the rows through more than a couple of CUs).
 template <class TO, int CPL>
@@ -468,15 +473,26 @@ __global__ __launch_bounds__(1024) void reduce_mean_bf16_wide_kernel(ReduceArgs 
   for (int e = 0; e < CPL; ++e) s[e] = 0.f;
   if (c0 < a.C) {
     const bf16_t* x = (const bf16_t*)a.x + (long long)b * a.R * a.C + c0;
-    for (long long r = w; r < a.R; r += 16) {
+    // 8 rows in flight per lane (a loop over the run-time row count would wait for each load in turn); rows are
+    // added in the same order as one by one
+    for (long long r0 = w; r0 < a.R; r0 += 16 * 8) {
       if (CPL == 8) {
-        V16 v; v.u = *(const uint4*)(x + r * a.C);
+        V16 v[8];
 #pragma unroll
-        for (int e = 0; e < CPL; ++e) s[e] += bf2f(v.h[e]);
+        for (int u = 0; u < 8; ++u) v[u].u = (r0 + 16 * u < a.R) ? *(const uint4*)(x + (r0 + 16 * u) * a.C) : zero4();
+#pragma unroll
+        for (int u = 0; u < 8; ++u)
+#pragma unroll
+          for (int e = 0; e < CPL; ++e) s[e] += bf2f(v[u].h[e]);
       } else {
-        const uint32_t v = *(const uint32_t*)(x + r * a.C);
-        s[0] += __uint_as_float(v << 16);
-        s[CPL - 1] += __uint_as_float(v & 0xffff0000u);
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = (r0 + 16 * u < a.R) ? *(const uint32_t*)(x + (r0 + 16 * u) * a.C) : 0u;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          s[0] += __uint_as_float(v[u] << 16);
+          s[CPL - 1] += __uint_as_float(v[u] & 0xffff0000u);
+        }
       }
     }
   }
@@ -514,6 +530,44 @@ __global__ void maxpool_kernel(PoolArgs p) {
     }
   }
   ((T*)p.y)[idx] = from_f<T>(best);
+}
+
+// bf16 with C % 8 == 0 and a K x K window known at compile time: a thread owns 8 consecutive channels of one output
+// position; the K * K rows of the window are requested together (16-byte loads) and then compared.
+template <int K>
+__global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(PoolArgs p) {
+  const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
+  const int cv = p.C >> 3;
+  const long long total = (long long)p.NB * p.OH * p.OW * cv;
+  if (idx >= total) return;
+  const int c8 = (int)(idx % cv);
+  long long m = idx / cv;
+  const int ow = (int)(m % p.OW);
+  m /= p.OW;
+  const int oh = (int)(m % p.OH), nb = (int)(m / p.OH);
+  const bf16_t* x = (const bf16_t*)p.x + (long long)nb * p.H * p.W * p.C + c8 * 8;
+  V16 v[K * K];
+  bool ok[K * K];
+#pragma unroll
+  for (int i = 0; i < K; ++i)
+#pragma unroll
+    for (int j = 0; j < K; ++j) {
+      const int ih = oh * p.stride - p.pad + i, iw = ow * p.stride - p.pad + j;
+      ok[i * K + j] = ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+      v[i * K + j].u = ok[i * K + j] ? *(const uint4*)(x + ((long long)ih * p.W + iw) * p.C) : zero4();
+    }
+  float best[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+#pragma unroll
+  for (int q = 0; q < K * K; ++q)
+    if (ok[q])
+#pragma unroll
+      for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], bf2f(v[q].h[e]));
+  V16 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o.h[e] = f2bf(best[e]);
+  *(uint4*)((bf16_t*)p.y + idx * 8) = o.u;
 }
 
 template <class TO>
@@ -1287,6 +1341,14 @@ hipError_t launch_reduce(const Launch& L, const ReduceArgs& a, hipStream_t s) {
 }
 
 hipError_t launch_pool(const Launch& L, const PoolArgs& p, hipStream_t s) {
+  if (L.in_dtype == SOD2_BF16_TAG && p.C % 8 == 0 && (p.k == 2 || p.k == 3) && ((uintptr_t)p.x & 15) == 0 && ((uintptr_t)p.y & 15) == 0) {
+    const long long tv = (long long)p.NB * p.OH * p.OW * (p.C / 8);
+    if (tv <= 0) return hipSuccess;
+    const dim3 gv((unsigned)((tv + 255) / 256));
+    if (p.k == 3) hipLaunchKernelGGL(maxpool_bf16x8_kernel<3>, gv, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL(maxpool_bf16x8_kernel<2>, gv, dim3(256), 0, s, p);
+    return hipGetLastError();
+  }
   long long total = (long long)p.NB * p.OH * p.OW * p.C;
   dim3 grid((unsigned)((total + 255) / 256));
   if (L.in_dtype == SOD2_BF16_TAG) hipLaunchKernelGGL(maxpool_kernel<bf16_t>, grid, dim3(256), 0, s, p);
