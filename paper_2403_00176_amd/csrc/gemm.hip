@@ -577,12 +577,26 @@ __global__ __launch_bounds__(256) void splitk_reduce(GemmArgs g, int splits) {
   const int b0 = batch / g.nb1, b1 = batch % g.nb1;
   const long long plane = (long long)g.M * g.N, nbatch = (long long)g.nb0 * g.nb1;
   float x[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  for (int z = 0; z < splits; ++z) {
-    const float* w = (const float*)g.ws + (z * nbatch + batch) * plane + (long long)row * g.N + col;
-    if ((g.N & 3) == 0 && col + 8 <= g.N) {
-      const float4 p0 = *(const float4*)w, p1 = *(const float4*)(w + 4);
-      x[0] += p0.x; x[1] += p0.y; x[2] += p0.z; x[3] += p0.w; x[4] += p1.x; x[5] += p1.y; x[6] += p1.z; x[7] += p1.w;
-    } else {
+  if ((g.N & 3) == 0 && col + 8 <= g.N) {
+    // the partials of 4 splits are requested together (summed in z order all the same)
+    for (int z0 = 0; z0 < splits; z0 += 4) {
+      float4 p[4][2];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const float* w = (const float*)g.ws + ((z0 + u) * nbatch + batch) * plane + (long long)row * g.N + col;
+        p[u][0] = (z0 + u < splits) ? *(const float4*)w : make_float4(0, 0, 0, 0);
+        p[u][1] = (z0 + u < splits) ? *(const float4*)(w + 4) : make_float4(0, 0, 0, 0);
+      }
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        if (z0 + u >= splits) continue;
+        x[0] += p[u][0].x; x[1] += p[u][0].y; x[2] += p[u][0].z; x[3] += p[u][0].w;
+        x[4] += p[u][1].x; x[5] += p[u][1].y; x[6] += p[u][1].z; x[7] += p[u][1].w;
+      }
+    }
+  } else {
+    for (int z = 0; z < splits; ++z) {
+      const float* w = (const float*)g.ws + (z * nbatch + batch) * plane + (long long)row * g.N + col;
 #pragma unroll
       for (int e = 0; e < 8; ++e) if (col + e < g.N) x[e] += w[e];
     }

@@ -228,17 +228,29 @@ __global__ __launch_bounds__(256) void gemm_simple(GemmArgs g) {
   const T* A = (const T*)g.A + b0 * g.a_sb0 + b1 * g.a_sb1;
   const T* B = (const T*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
   float acc[4][4] = {};
+  // the next k-tile's 8 elements are requested before the current tile is multiplied (otherwise every 16-wide
+  // k-tile costs a full memory round trip with nothing to hide it)
+  float pa[4], pb[4];
+  auto fetch = [&](int k0) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = tid + i * 256;
+      const int r = e / BK, k = e % BK;                  // 64 rows x 16 k
+      const int m = m0 + r, n = n0 + r, kk = k0 + k;
+      pa[i] = (m < g.M && kk < g.K) ? to_f<T>(A[(long long)m * g.a_sm + (long long)kk * g.a_sk]) : 0.f;
+      pb[i] = (n < g.N && kk < g.K) ? to_f<T>(B[(long long)kk * g.b_sk + (long long)n * g.b_sn]) : 0.f;
+    }
+  };
+  fetch(0);
   for (int k0 = 0; k0 < g.K; k0 += BK) {
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      int e = tid + i * 256;
-      int r = e / BK, k = e % BK;                        // 64 rows x 16 k
-      int m = m0 + r, kk = k0 + k;
-      As[k][r] = (m < g.M && kk < g.K) ? to_f<T>(A[(long long)m * g.a_sm + (long long)kk * g.a_sk]) : 0.f;
-      int n = n0 + r;
-      Bs[k][r] = (n < g.N && kk < g.K) ? to_f<T>(B[(long long)kk * g.b_sk + (long long)n * g.b_sn]) : 0.f;
+      const int e = tid + i * 256;
+      As[e % BK][e / BK] = pa[i];
+      Bs[e % BK][e / BK] = pb[i];
     }
     __syncthreads();
+    if (k0 + BK < g.K) fetch(k0 + BK);
 #pragma unroll
     for (int k = 0; k < BK; ++k) {
       float a[4], b[4];
