@@ -218,7 +218,7 @@ __global__ __launch_bounds__(256) void gemm_mfma(AL al, GemmArgs g) {
 // ---------------------------------------------------------------------------------------------
 template <class T>
 __global__ __launch_bounds__(256) void gemm_simple(GemmArgs g) {
-  constexpr int BT = 64, BK = 16;
+  constexpr int BT = 64, BK = 32, PT = BT * BK / 256;   // PT elements of each operand tile per thread
   __shared__ float As[BK][BT + 1];
   __shared__ float Bs[BK][BT + 1];
   const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
@@ -228,14 +228,14 @@ __global__ __launch_bounds__(256) void gemm_simple(GemmArgs g) {
   const T* A = (const T*)g.A + b0 * g.a_sb0 + b1 * g.a_sb1;
   const T* B = (const T*)g.B + b0 * g.b_sb0 + b1 * g.b_sb1;
   float acc[4][4] = {};
-  // the next k-tile's 8 elements are requested before the current tile is multiplied (otherwise every 16-wide
+  // the next k-tile's 8 elements are requested before the current tile is multiplied (otherwise every
   // k-tile costs a full memory round trip with nothing to hide it)
-  float pa[4], pb[4];
+  float pa[PT], pb[PT];
   auto fetch = [&](int k0) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < PT; ++i) {
       const int e = tid + i * 256;
-      const int r = e / BK, k = e % BK;                  // 64 rows x 16 k
+      const int r = e / BK, k = e % BK;                  // 64 rows x BK k
       const int m = m0 + r, n = n0 + r, kk = k0 + k;
       pa[i] = (m < g.M && kk < g.K) ? to_f<T>(A[(long long)m * g.a_sm + (long long)kk * g.a_sk]) : 0.f;
       pb[i] = (n < g.N && kk < g.K) ? to_f<T>(B[(long long)kk * g.b_sk + (long long)n * g.b_sn]) : 0.f;
@@ -244,7 +244,7 @@ __global__ __launch_bounds__(256) void gemm_simple(GemmArgs g) {
   fetch(0);
   for (int k0 = 0; k0 < g.K; k0 += BK) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < PT; ++i) {
       const int e = tid + i * 256;
       As[e % BK][e / BK] = pa[i];
       Bs[e % BK][e / BK] = pb[i];
