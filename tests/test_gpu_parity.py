@@ -145,6 +145,79 @@ def test_layernorm_as_second_result(S, variant):
     print("layernorm fold", variant, "max rel err: folded", max(e1), "kernel behind", max(e2), "own group", max(e3))
 
 
+def _fold_chain_workload():
+    """Three LayerNorm-behind-a-contraction pairs with different surroundings: (1) both contractions carry the full
+    epilogue (scale, bias, activation, added tensor, activation) and the reader's width is not a tile multiple;
+    (2) the LayerNorm's weight is computed in the graph, so no constants can be derived for it; (3) the smallest
+    normalised extent the rule takes, a reader without bias."""
+    from workloads import GraphBuilder, rng
+    from workloads.configs import Workload
+    b = GraphBuilder([("M", 1, 4096)])
+    W = {}
+
+    def wt(name, dims, mean, std):
+        t = b.weight(name, "bf16", dims)
+        W[t] = (mean, std)
+        return t
+
+    def lin(x, n_in, n_out, name, scale=None, bias=True, act1=None, res=None, act2=None):
+        y = b.op("MatMul", [x, wt(name + ".w", [n_out, n_in], 0.0, 0.06)], transB=1, hint=name)
+        if scale is not None:
+            y = b.op("Mul", [y, b.const(name + ".s", scale, "f32")])
+        if bias:
+            y = b.op("Add", [y, wt(name + ".b", [n_out], 0.0, 0.1)])
+        if act1:
+            y = b.op(act1, [y])
+        if res is not None:
+            y = b.op("Add", [y, res])
+        if act2:
+            y = b.op(act2, [y])
+        return y
+
+    x = b.input("x", "bf16", ["M", 128])
+    r1 = b.input("r1", "bf16", ["M", 256])
+    r2 = b.input("r2", "bf16", ["M", 192])
+    t1 = lin(x, 128, 256, "p1", scale=0.5, act1="Gelu", res=r1, act2="Relu")
+    n1 = b.op("LayerNorm", [t1, wt("ln1.g", [256], 1.0, 0.1), wt("ln1.b", [256], 0.0, 0.1)], eps=1e-5)
+    t2 = lin(n1, 256, 192, "c1", scale=2.0, act1="Gelu", res=r2, act2="Sigmoid")
+    t3 = lin(t2, 192, 320, "p2", bias=False)
+    g2 = b.op("Add", [wt("ln2.g", [320], 1.0, 0.1), wt("ln2.g2", [320], 0.0, 0.1)])
+    n2 = b.op("LayerNorm", [t3, g2, wt("ln2.b", [320], 0.0, 0.1)], eps=1e-3)
+    t4 = lin(n2, 320, 104, "c2")
+    t5 = lin(t4, 104, 64, "p3", act1="Relu")
+    n3 = b.op("LayerNorm", [t5, wt("ln3.g", [64], 1.0, 0.1), wt("ln3.b", [64], 0.0, 0.1)], eps=1e-5)
+    b.mark_output(lin(n3, 64, 200, "c3", bias=False), "y")
+    b.mark_output(t2, "t2")
+    g = b.build()
+
+    def make_weights():
+        return {t: rng.normal(7000 + t, tuple(g.tensors[t].dims), m, s) for t, (m, s) in sorted(W.items())}
+
+    def make_inputs(ci, sym):
+        M = sym["M"]
+        return {g.tensor_id("x"): rng.normal(ci, (M, 128)), g.tensor_id("r1"): rng.normal(ci + 40, (M, 256)),
+                g.tensor_id("r2"): rng.normal(ci + 80, (M, 192))}
+    return Workload("fold_chain", 0, g, "bf16", [], make_weights, make_inputs)
+
+
+@pytest.mark.parametrize("variant", [-1, 17, 28, 33])
+def test_layernorm_fold_with_full_epilogues(S, variant):
+    w = _fold_chain_workload()
+    po = P.build_plan(w.graph, R.RDP(w.graph).analyse())
+    assert sum(1 for gr in po.groups.values() if gr.lnfold >= 0) == 3
+    calls = [(0, {"M": 1}), (1, {"M": 77}), (2, {"M": 128}), (3, {"M": 1000}), (4, {"M": 4096})]
+    tr = []
+    e = run_case(S, w, calls, variant=variant, traces=tr)
+    for (ci, sym), t in zip(calls, tr):
+        folds = [x["fold"] for x in t if x["is_group"] and x["fold"]]
+        # pairs 1 and 3 go through the two contractions' epilogues; pair 2's LayerNorm weight is computed at run time,
+        # no constants exist for it, so its kernel runs behind the producer.  A single row with no tile forced takes
+        # the skinny contraction kernel, which has no such epilogue: all three LayerNorm kernels run then.
+        assert folds == ([3, 3, 3] if variant < 0 and sym["M"] == 1 else [1, 2, 3, 1, 2]), (sym, folds)
+    e2 = run_case(S, w, calls, variant=variant, fold_ln=False)
+    print("fold chain", variant, "max rel err: folded", max(e), "own groups", max(e2))
+
+
 @pytest.mark.parametrize("splits", [2, 4, 16])
 def test_split_k(S, splits):
     """Split-K forced on every contraction that can split (fp32 partials in the workspace behind the
