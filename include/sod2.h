@@ -66,7 +66,9 @@ enum { SOD2_INTER = 0, SOD2_INPUT = 1, SOD2_WEIGHT = 2, SOD2_HOSTCONST = 3 };
  *   int tensor whose values are the result's shape; Table 2: ISVDOS); the rest of the result is zero.
  *   GroupNorm (GroupNormalization, channels last): data
  *   [N, ..., C], scale [C], bias [C]; per sample and group of C / groups channels, mean and biased variance over the
- *   group's channels at every position.  Switch: data, predicate (one float);
+ *   group's channels at every position.  AveragePool (channels last, like MaxPool): the mean over the window
+ *   positions inside the input (padding is not counted; 0 <= pad < kernel).  Round: to the nearest integer, halves
+ *   to the even one.  Switch: data, predicate (one float);
  *   two results: taken when predicate <= threshold, taken when predicate > threshold.               */
 enum {
   SOD2_OP_SHAPE = 0, SOD2_OP_GATHER, SOD2_OP_CONCAT, SOD2_OP_RESHAPE, SOD2_OP_SLICE,
@@ -74,7 +76,8 @@ enum {
   SOD2_OP_GELU, SOD2_OP_SIGMOID, SOD2_OP_CAST, SOD2_OP_SOFTMAX, SOD2_OP_LAYERNORM,
   SOD2_OP_REDUCEMEAN, SOD2_OP_MAXPOOL, SOD2_OP_ARGMAX, SOD2_OP_CACHEAPPEND, SOD2_OP_NONZERO,
   SOD2_OP_SWITCH, SOD2_OP_COMBINE, SOD2_OP_SCATTERROWS, SOD2_OP_RESIZE, SOD2_OP_RANGE, SOD2_OP_EXPAND,
-  SOD2_OP_UPSAMPLE, SOD2_OP_CONSTANTOFSHAPE, SOD2_OP_EYELIKE, SOD2_OP_ONEHOT, SOD2_OP_TOPK, SOD2_OP_GROUPNORM, SOD2_OP_MAXUNPOOL, SOD2_OP_COUNT
+  SOD2_OP_UPSAMPLE, SOD2_OP_CONSTANTOFSHAPE, SOD2_OP_EYELIKE, SOD2_OP_ONEHOT, SOD2_OP_TOPK, SOD2_OP_GROUPNORM, SOD2_OP_MAXUNPOOL,
+  SOD2_OP_AVERAGEPOOL, SOD2_OP_ROUND, SOD2_OP_COUNT
 };
 
 #define SOD2_MAX_RANK 8
@@ -94,7 +97,7 @@ typedef struct {
 
 /* Integer attributes per kind, in this order:
  *   Gather/Concat: axis.  Transpose: the permutation.  MatMul: transB.  Conv: stride, pad.
- *   Softmax: causal.  ReduceMean: keepdims, then the axes.  MaxPool: kernel, stride, pad.
+ *   Softmax: causal.  ReduceMean: keepdims, then the axes.  MaxPool, AveragePool: kernel, stride, pad.
  *   EyeLike: the diagonal k.  GroupNorm: the number of groups.
  * Float attribute: LayerNorm and GroupNorm epsilon; Switch threshold; ConstantOfShape value.     */
 typedef struct {
@@ -182,7 +185,7 @@ sod2_status sod2_plan_dump(const sod2_plan_t*, char* buf_host, size_t cap, size_
  * tensors the group reads from outside itself; info->n_ops / n_ins always hold the full counts. */
 enum { SOD2_G_GEMM = 0, SOD2_G_CONV, SOD2_G_LAYERNORM, SOD2_G_SOFTMAX, SOD2_G_MAXPOOL, SOD2_G_REDUCEMEAN, SOD2_G_ARGMAX,
        SOD2_G_CACHEAPPEND, SOD2_G_NONZERO, SOD2_G_GATHER, SOD2_G_ELTWISE, SOD2_G_ATTENTION, SOD2_G_SCATTER, SOD2_G_RESIZE,
-       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM, SOD2_G_MAXUNPOOL };
+       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM, SOD2_G_MAXUNPOOL, SOD2_G_AVGPOOL };
 typedef struct {
   int32_t gid;        /* group id: the smallest operator id in the group */
   int32_t kind;       /* SOD2_G_* */

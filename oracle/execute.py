@@ -117,6 +117,10 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
             y = xs[0].mean(axis=tuple(a["axes"]), keepdims=bool(a.get("keepdims", 1)))
         elif k == "MaxPool":
             y = O.maxpool_nhwc(xs[0], a["kernel"], a["stride"], a["pad"])
+        elif k == "AveragePool":
+            y = O.avgpool_nhwc(xs[0], a["kernel"], a["stride"], a["pad"])
+        elif k == "Round":
+            y = np.rint(xs[0])
         elif k == "ArgMax":
             y = np.argmax(xs[0], axis=-1)
         elif k == "CacheAppend":

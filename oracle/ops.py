@@ -59,6 +59,21 @@ def maxpool_nhwc(x, k, stride, pad):
     return out
 
 
+def avgpool_nhwc(x, k, stride, pad):
+    """AveragePool (Table 2), channels last: the mean over the window positions that lie inside the input
+    (padding positions are not counted)."""
+    n, h, wd, c = x.shape
+    oh = (h + 2 * pad - k) // stride + 1
+    ow = (wd + 2 * pad - k) // stride + 1
+    out = np.zeros((n, oh, ow, c))
+    for i in range(oh):
+        r0, r1 = max(i * stride - pad, 0), min(i * stride - pad + k, h)
+        for j in range(ow):
+            c0, c1 = max(j * stride - pad, 0), min(j * stride - pad + k, wd)
+            out[:, i, j, :] = x[:, r0:r1, c0:c1, :].sum(axis=(1, 2)) / ((r1 - r0) * (c1 - c0))
+    return out
+
+
 def gelu(x):
     return 0.5 * x * (1.0 + erf(x / np.sqrt(2.0)))
 

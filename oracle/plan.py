@@ -17,10 +17,12 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     operator that does not fit.  With fusion switched off only a directly
     following Transpose is still taken: the permuted store is a layout choice
     of the contraction, and without it the Reshape behind it would need a copy.
-R3  LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero,
+R3  LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, AveragePool, ReduceMean, ArgMax, CacheAppend, NonZero,
     ScatterRows, Resize, Upsample, OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
-R4  Remaining elementwise operators chain, up to 8 ops.  An aligned dim pair of
+R4  Remaining elementwise operators chain, up to 8 ops (a Round joins a chain
+    only behind an fp32 value, otherwise it starts one: it has to round what
+    would have been stored).  An aligned dim pair of
     the two operands of a binary member is *proven* when RDP shows the two
     extents equal or one of them 1 (the condition of Fig. 4): the fused loop nest
     then has one form.  A pair of two resolved but unrelated extents is
@@ -91,11 +93,12 @@ MAX_SG = 14
 DT_BYTES = {"f32": 4, "bf16": 2, "i64": 8, "i32": 4}
 VIEW_KINDS = ("Reshape", "Slice", "Transpose", "Expand")
 ACTS = ("Relu", "Gelu", "Sigmoid")
-ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast")
+ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast", "Round")
 SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
         "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
         "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE",
-        "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT", "TopK": "TOPK", "GroupNorm": "GROUPNORM", "MaxUnpool": "MAXUNPOOL"}
+        "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT", "TopK": "TOPK", "GroupNorm": "GROUPNORM", "MaxUnpool": "MAXUNPOOL",
+        "AveragePool": "AVGPOOL"}
 
 
 @dataclass
@@ -304,6 +307,8 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
                 if c is None or c in assigned or g.ops[c].kind not in ELTWISE:
                     break
                 cop = g.ops[c]
+                if cop.kind == "Round" and g.tensors[cur].dtype != "f32":
+                    break                # Round decides an integer: it must see the value as stored, not the chain's fp32
                 more = _unproven_pairs(rdp, cop)
                 if more is None or 2 ** (len(pairs) + len(more)) > max(opts.max_versions, 1):
                     break

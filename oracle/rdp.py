@@ -31,13 +31,13 @@ OP_CLASS = {
     "Shape": ISDO, "ConstantOfShape": ISDO, "EyeLike": ISDO,
     "Gather": ISDOS, "Concat": ISDOS, "Transpose": ISDOS, "MatMul": ISDOS, "Conv": ISDOS,
     "Add": ISDOS, "Mul": ISDOS, "Relu": ISDOS, "Gelu": ISDOS, "Sigmoid": ISDOS, "Cast": ISDOS,
-    "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS,
+    "Softmax": ISDOS, "LayerNorm": ISDOS, "ReduceMean": ISDOS, "MaxPool": ISDOS, "AveragePool": ISDOS, "Round": ISDOS,
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
     "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS, "Range": ISVDOS, "Expand": ISVDOS,
     "OneHot": ISVDOS, "Upsample": ISVDOS, "TopK": ISVDOS, "GroupNorm": ISVDOS, "MaxUnpool": ISVDOS,
     "NonZero": EDO, "Switch": EDO, "Combine": EDO,
 }
-UNARY = ("Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "GroupNorm")   # result shaped like input 0
+UNARY = ("Relu", "Gelu", "Sigmoid", "Round", "Cast", "Softmax", "LayerNorm", "GroupNorm")   # result shaped like input 0
 EXEC_PREFIX = "@nz"   # name of an execution symbol: EXEC_PREFIX + operator id
 
 
@@ -513,6 +513,8 @@ class RDP:
             return NAC, UNDEF
         k, s, p = op.attrs["kernel"], op.attrs["stride"], op.attrs["pad"]
         return [x[0], self._window(x[1], k, s, p), self._window(x[2], k, s, p), x[3]], UNDEF
+
+    _f_AveragePool = _f_MaxPool
 
     def _binary(self, op, vfun):
         a, b = self.S[op.inputs[0]], self.S[op.inputs[1]]

@@ -25,7 +25,7 @@ ROLES = {"inter": 0, "input": 1, "weight": 2, "hostconst": 3}
 OP_KINDS = ["Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul",
             "Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax",
             "CacheAppend", "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand",
-            "Upsample", "ConstantOfShape", "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool"]
+            "Upsample", "ConstantOfShape", "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool", "AveragePool", "Round"]
 OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
 
 EXPORTS = [
@@ -116,7 +116,7 @@ def _attrs(kind: str, attrs: dict):
         ia = [int(attrs.get("causal", 0))]
     elif kind == "ReduceMean":
         ia = [int(attrs.get("keepdims", 1))] + [int(a) for a in attrs["axes"]]
-    elif kind == "MaxPool":
+    elif kind in ("MaxPool", "AveragePool"):
         ia = [int(attrs["kernel"]), int(attrs["stride"]), int(attrs["pad"])]
     elif kind == "LayerNorm":
         fa = float(attrs["eps"])
@@ -421,7 +421,7 @@ def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence
 STATIC_SCRATCH_BYTES = 8 << 20
 
 GROUP_KINDS = ["GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX", "CACHEAPPEND", "NONZERO", "GATHER",
-               "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL"]
+               "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL"]
 SG_CLASSES = ["known", "mixed", "nac"]
 
 

@@ -531,22 +531,27 @@ __global__ void maxpool_kernel(PoolArgs p) {
   long long t = m / p.OW;
   int oh = t % p.OH, nb = t / p.OH;
   const T* x = (const T*)p.x + (long long)nb * p.H * p.W * p.C;
-  float best = -INFINITY;
+  float best = -INFINITY, sum = 0.f;
+  int cnt = 0;
   for (int i = 0; i < p.k; ++i) {
     int ih = oh * p.stride - p.pad + i;
     if (ih < 0 || ih >= p.H) continue;
     for (int j = 0; j < p.k; ++j) {
       int iw = ow * p.stride - p.pad + j;
       if (iw < 0 || iw >= p.W) continue;
-      best = fmaxf(best, to_f<T>(x[((long long)ih * p.W + iw) * p.C + c]));
+      const float v = to_f<T>(x[((long long)ih * p.W + iw) * p.C + c]);
+      best = fmaxf(best, v);
+      sum += v;
+      ++cnt;
     }
   }
-  ((T*)p.y)[idx] = from_f<T>(best);
+  ((T*)p.y)[idx] = from_f<T>(p.avg ? sum / (float)cnt : best);      // (pad < k: every window holds an input position)
 }
 
 // bf16 with C % 8 == 0 and a K x K window known at compile time: a thread owns 8 consecutive channels of one output
-// position; the K * K rows of the window are requested together (16-byte loads) and then compared.
-template <int K>
+// position; the K * K rows of the window are requested together (16-byte loads) and then compared (AVG: summed in
+// window order and divided by the number of positions inside the input).
+template <int K, bool AVG>
 __global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(PoolArgs p) {
   const long long idx = (long long)blockIdx.x * 256 + threadIdx.x;
   const int cv = p.C >> 3;
@@ -570,15 +575,18 @@ __global__ __launch_bounds__(256) void maxpool_bf16x8_kernel(PoolArgs p) {
     }
   float best[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) best[e] = -INFINITY;
+  for (int e = 0; e < 8; ++e) best[e] = AVG ? 0.f : -INFINITY;
+  int cnt = 0;
 #pragma unroll
   for (int q = 0; q < K * K; ++q)
-    if (ok[q])
+    if (ok[q]) {
+      ++cnt;
 #pragma unroll
-      for (int e = 0; e < 8; ++e) best[e] = fmaxf(best[e], bf2f(v[q].h[e]));
+      for (int e = 0; e < 8; ++e) best[e] = AVG ? best[e] + bf2f(v[q].h[e]) : fmaxf(best[e], bf2f(v[q].h[e]));
+    }
   V16 o;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) o.h[e] = f2bf(best[e]);
+  for (int e = 0; e < 8; ++e) o.h[e] = f2bf(AVG ? best[e] / (float)cnt : best[e]);
   *(uint4*)((bf16_t*)p.y + idx * 8) = o.u;
 }
 
@@ -605,6 +613,7 @@ __global__ void eltwise_kernel(EltArgs a) {
       case E_RELU: v = fmaxf(v, 0.f); break;
       case E_GELU: v = apply_act(v, ACT_GELU); break;
       case E_SIGMOID: v = apply_act(v, ACT_SIGMOID); break;
+      case E_ROUND: v = rintf(v); break;                 // halves to the even integer
       default: break;
     }
   }
@@ -1357,8 +1366,10 @@ hipError_t launch_pool(const Launch& L, const PoolArgs& p, hipStream_t s) {
     const long long tv = (long long)p.NB * p.OH * p.OW * (p.C / 8);
     if (tv <= 0) return hipSuccess;
     const dim3 gv((unsigned)((tv + 255) / 256));
-    if (p.k == 3) hipLaunchKernelGGL(maxpool_bf16x8_kernel<3>, gv, dim3(256), 0, s, p);
-    else hipLaunchKernelGGL(maxpool_bf16x8_kernel<2>, gv, dim3(256), 0, s, p);
+    if (p.k == 3 && p.avg) hipLaunchKernelGGL((maxpool_bf16x8_kernel<3, true>), gv, dim3(256), 0, s, p);
+    else if (p.k == 3) hipLaunchKernelGGL((maxpool_bf16x8_kernel<3, false>), gv, dim3(256), 0, s, p);
+    else if (p.avg) hipLaunchKernelGGL((maxpool_bf16x8_kernel<2, true>), gv, dim3(256), 0, s, p);
+    else hipLaunchKernelGGL((maxpool_bf16x8_kernel<2, false>), gv, dim3(256), 0, s, p);
     return hipGetLastError();
   }
   long long total = (long long)p.NB * p.OH * p.OW * p.C;

@@ -86,11 +86,12 @@ struct ReduceArgs {         // y[b, c] = mean_r x[b, r, c]
 struct PoolArgs {
   const void* x; void* y;
   int NB, H, W, C, OH, OW, k, stride, pad;
+  int avg;                 // 0: maximum of the window; 1: mean over the window positions inside the input
 };
 
 // out[idx] = chain of up to 8 elementwise operators over the output index space; operands are
 // broadcast through zero strides (the single fused loop nest of Fig. 4)
-enum EltOp { E_ADD = 0, E_MUL, E_RELU, E_GELU, E_SIGMOID, E_CAST };
+enum EltOp { E_ADD = 0, E_MUL, E_RELU, E_GELU, E_SIGMOID, E_CAST, E_ROUND };
 struct EltArgs {
   const void* in[5];
   void* out;

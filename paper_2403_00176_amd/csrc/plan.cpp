@@ -8,10 +8,10 @@
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
 //     consumer of the chain so far;
-//  R3 LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
+//  R3 LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, AveragePool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
 //     OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
-//  R4 other elementwise operators chain (up to 8).  A dim pair of the two operands of a binary member is proven when
+//  R4 other elementwise operators chain (up to 8; a Round joins only behind an fp32 value, else it starts a chain).  A dim pair of the two operands of a binary member is proven when
 //     RDP shows the extents equal or one of them 1: one form of the fused loop nest.  A pair of two resolved but
 //     unrelated extents doubles the number of code versions (Fig. 4), one of which is selected at bind; the chain
 //     stops before the member that would need more than max_versions (8) and at an unresolved extent;
@@ -40,14 +40,14 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
 const int kMaxSubgraph = 14;
 
 bool is_act(int k) { return k == SOD2_OP_RELU || k == SOD2_OP_GELU || k == SOD2_OP_SIGMOID; }
-bool is_eltwise(int k) { return k == SOD2_OP_ADD || k == SOD2_OP_MUL || is_act(k) || k == SOD2_OP_CAST; }
+bool is_eltwise(int k) { return k == SOD2_OP_ADD || k == SOD2_OP_MUL || is_act(k) || k == SOD2_OP_CAST || k == SOD2_OP_ROUND; }
 bool is_control(int k) { return k == SOD2_OP_SWITCH || k == SOD2_OP_COMBINE; }
 
 bool shape_equal(const LS& a, const LS& b) {
@@ -220,6 +220,7 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_TOPK) new_group(G_TOPK, {n});
     else if (op.kind == SOD2_OP_GROUPNORM) new_group(G_GROUPNORM, {n});
     else if (op.kind == SOD2_OP_MAXUNPOOL) new_group(G_MAXUNPOOL, {n});
+    else if (op.kind == SOD2_OP_AVERAGEPOOL) new_group(G_AVGPOOL, {n});
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);
@@ -236,6 +237,7 @@ void Plan::build() {
         int c = sole_consumer(cur);
         if (c < 0 || group_of_op[c] >= 0 || !is_eltwise(G.ops[c].kind)) break;
         const Op& cop = G.ops[c];
+        if (cop.kind == SOD2_OP_ROUND && G.tensors[cur].dtype != SOD2_F32) break;   // Round must see the value as stored
         std::vector<Group::Pair> more;
         if (!unproven_pairs(R, cop, &more) || (1LL << (pairs.size() + more.size())) > std::max(max_versions(), 1)) break;
         pairs.insert(pairs.end(), more.begin(), more.end());

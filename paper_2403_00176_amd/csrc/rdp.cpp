@@ -17,7 +17,7 @@ static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
     "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand", "Upsample", "ConstantOfShape",
-    "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool"};
+    "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool", "AveragePool", "Round"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
@@ -177,7 +177,7 @@ struct Analyser {
         if (x.k == LS::NAC) return done(LS::nac(), LS::nac());
         return done(LS::list({LV::c((int64_t)x.d.size())}), LS::list(x.d));   // ISDO: value = input shape
       }
-      case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_CAST:
+      case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_ROUND: case SOD2_OP_CAST:
       case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM: case SOD2_OP_GROUPNORM: {
         if (in_s(0).k == LS::UNDEF) return r;
         return done(in_s(0));
@@ -333,7 +333,7 @@ struct Analyser {
         return done(LS::list({x.d[0], window(x.d[1], w.d[1].e.const_value(), s, p),
                               window(x.d[2], w.d[2].e.const_value(), s, p), w.d[0]}));
       }
-      case SOD2_OP_MAXPOOL: {
+      case SOD2_OP_MAXPOOL: case SOD2_OP_AVERAGEPOOL: {
         const LS& x = in_s(0);
         if (x.k == LS::UNDEF) return r;
         if (x.k == LS::NAC) return done(LS::nac());
@@ -524,7 +524,7 @@ struct Analyser {
         bool ch = refine(V, op.in[0], v);
         return refine(S, op.in[0], LS::list({LV::c((int64_t)out.d.size())})) || ch;
       }
-      case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_CAST:
+      case SOD2_OP_RELU: case SOD2_OP_GELU: case SOD2_OP_SIGMOID: case SOD2_OP_ROUND: case SOD2_OP_CAST:
       case SOD2_OP_SOFTMAX: case SOD2_OP_LAYERNORM: case SOD2_OP_GROUPNORM:
         if (k == 0 && out.is_list()) nw = out;
         if (k == 0 && op.kind == SOD2_OP_CAST && is_int(G.tensors[op.in[0]].dtype) && is_int(G.tensors[op.out[0]].dtype))

@@ -660,12 +660,14 @@ struct Builder {
     L.kernel = K_POOL;
     const Op& op = G.ops[gr.chain[0]];
     const View& vx = view_of(op.in[0]);
-    if (!vx.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "MaxPool needs a contiguous input");
+    if (!vx.contiguous()) throw Error(SOD2_ERR_UNSUPPORTED, "a pooling operator needs a contiguous input");
     Dims od = eval_dims(gr.out);
     PoolArgs a{};
     a.NB = (int)vx.dims[0]; a.H = (int)vx.dims[1]; a.W = (int)vx.dims[2]; a.C = (int)vx.dims[3];
     a.OH = (int)od[1]; a.OW = (int)od[2];
     a.k = (int)op.ia.at(0); a.stride = (int)op.ia.at(1); a.pad = (int)op.ia.at(2);
+    a.avg = op.kind == SOD2_OP_AVERAGEPOOL;
+    if (a.k < 1 || a.stride < 1 || a.pad < 0 || a.pad >= a.k) throw Error(SOD2_ERR_UNSUPPORTED, "pooling window: kernel >= 1, stride >= 1, 0 <= pad < kernel");
     L.in_dtype = L.out_dtype = G.tensors[op.in[0]].dtype;
     L.r[0] = ref_of(vx, L.in_dtype);
     L.r[1] = ref_t(gr.out);
@@ -721,6 +723,7 @@ struct Builder {
         case SOD2_OP_RELU: a.op[o] = E_RELU; break;
         case SOD2_OP_GELU: a.op[o] = E_GELU; break;
         case SOD2_OP_SIGMOID: a.op[o] = E_SIGMOID; break;
+        case SOD2_OP_ROUND: a.op[o] = E_ROUND; break;
         default: a.op[o] = E_CAST; break;
       }
       if (op.in.size() == 2) {
@@ -1256,7 +1259,7 @@ struct Builder {
       case G_LAYERNORM: return row(gr, true);
       case G_SOFTMAX: return row(gr, false);
       case G_REDUCEMEAN: return reduce(gr);
-      case G_MAXPOOL: return pool(gr);
+      case G_MAXPOOL: case G_AVGPOOL: return pool(gr);
       case G_ELTWISE: return eltwise(gr);
       default:
         throw Error(SOD2_ERR_UNSUPPORTED, std::string("no kernel for group kind ") + group_kind_name(gr.kind));

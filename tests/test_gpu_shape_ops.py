@@ -357,3 +357,37 @@ def test_maxunpool_kernel(S_lib, dtype):
         got = to_host(outs[0])
         assert got.shape == (N, 2 * H, 2 * W, 8) and np.array_equal(got, ref.values[g.tensor_id("y")])
         assert np.count_nonzero(got) == pooled.size - (2 if H > 1 else 0)
+
+
+@pytest.mark.parametrize("dtype,channels,kernel,stride,pad", [("f32", 16, 3, 2, 1), ("bf16", 16, 3, 2, 1), ("bf16", 64, 2, 2, 0),
+                                                                ("bf16", 5, 3, 1, 1), ("f32", 3, 5, 3, 2)])
+def test_averagepool_and_round_kernels(S_lib, dtype, channels, kernel, stride, pad):
+    """AveragePool (wide bf16 kernel and the plain one) within the bar; Round is exact: in fp32 the chain
+    Mul, Round, Mul is one kernel whose Round sees the same fp32 product as the definition, in bf16 the Round starts
+    its own kernel on the stored value.  Inputs of Round(x) include exact halves."""
+    import torch
+    from tests.test_shape_ops import _avgpool_round_graph
+    from paper_2403_00176_amd.session import Session, to_host
+    g, _ = _avgpool_round_graph(dtype, channels, kernel, stride, pad)
+    po = P.build_plan(g, R.RDP(g).analyse())
+    ses = Session(g)
+    ses.upload_weights({})
+    for k, sym in enumerate(({"N": 1, "H": 5, "W": 5}, {"N": 2, "H": 7, "W": 9}, {"N": 3, "H": 128, "W": 96}, {"N": 8, "H": 33, "W": 1 + kernel})):
+        print(f"case avgpool {dtype} c={channels} k={kernel} s={stride} p={pad} {sym}", flush=True)
+        x = np.round(rng.normal(700 + k, (sym["N"], sym["H"], sym["W"], channels), 0.0, 3.0) * 8) / 8     # multiples of 1/8: halves occur
+        ins = {g.tensor_id("x"): x}
+        b = ses.bind(sym)
+        assert S_lib.sod2_binding_dump(b) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(b))
+        ses.run(b, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {}, ins)
+        got = {t: to_host(o) for t, o in zip(g.outputs(), outs)}
+        assert np.array_equal(got[g.tensor_id("rx")], ref.values[g.tensor_id("rx")])           # Round of stored values: exact
+        q, qr = got[g.tensor_id("q")], ref.values[g.tensor_id("q")]
+        assert q.shape == qr.shape
+        # the pooled mean is a float result (fp32 sum / count against the exact one): a mean within rounding distance of
+        # a quantisation boundary may land on the neighbouring step, nothing else may differ
+        d = np.abs(q - qr)
+        print("  quantised means that differ:", int((d > 1e-6).sum()), "of", d.size, "max", float(d.max()), flush=True)
+        assert d.max() <= 0.25 + 1e-6 and np.mean(d > 1e-6) <= 1e-4, (sym, d.max(), np.mean(d > 1e-6))

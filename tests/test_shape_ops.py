@@ -589,3 +589,68 @@ def test_maxunpool_against_its_definition_and_structure():
     pooled8, pos8 = _pool_positions(rs.randn(2, 6, 10, 8) + 3.0)
     res = execute.run(g, p.order, {}, {g.tensor_id("x"): pooled8, g.tensor_id("idx"): pos8})
     assert np.array_equal(_pool_positions(res.values[g.tensor_id("y")])[0], O.round_to(pooled8, "f32"))
+
+
+def _avgpool_round_graph(dtype="f32", channels=16, kernel=3, stride=2, pad=1):
+    """A quantising pooling block on a channels-last image: q = Round(AveragePool(x) * 4) / 4, and Round(x).
+    (Table 2 lists AveragePool and Round with the operators whose output shape follows from the input shapes.)"""
+    b = GraphBuilder([("N", 1, 8), ("H", 1, 128), ("W", 1, 128)])
+    x = b.input("x", dtype, ["N", "H", "W", channels])
+    p = b.op("AveragePool", [x], kernel=kernel, stride=stride, pad=pad, hint="avg")
+    q = b.op("Mul", [p, b.const("four", 4.0, "f32")])
+    q = b.op("Round", [q])
+    q = b.op("Mul", [q, b.const("quarter", 0.25, "f32")])
+    b.mark_output(q, "q")
+    b.mark_output(b.op("Round", [x]), "rx")
+    return b.build(), p
+
+
+def test_averagepool_and_round_against_their_definitions_and_structure():
+    rs = np.random.RandomState(12)
+    # explicit loops over every output position, padding positions not counted
+    x = rs.randn(2, 7, 6, 3)
+    for k, s, p in ((3, 2, 1), (2, 2, 0), (3, 1, 1), (2, 1, 1), (5, 3, 2)):
+        got = O.avgpool_nhwc(x, k, s, p)
+        oh, ow = (7 + 2 * p - k) // s + 1, (6 + 2 * p - k) // s + 1
+        assert got.shape == (2, oh, ow, 3)
+        for i in range(oh):
+            for j in range(ow):
+                vals = [x[:, a, b_, :] for a in range(i * s - p, i * s - p + k) for b_ in range(j * s - p, j * s - p + k)
+                        if 0 <= a < 7 and 0 <= b_ < 6]
+                assert np.allclose(got[:, i, j, :], np.mean(vals, axis=0), atol=1e-13)
+    # a constant image stays that constant, padding or not (a divisor of k*k at the border would lower the rim);
+    # the window covering the whole image is the mean over it; a 1 x 1 window is the identity
+    assert np.allclose(O.avgpool_nhwc(np.full((1, 5, 5, 2), 3.25), 3, 2, 1), 3.25)
+    assert np.allclose(O.avgpool_nhwc(x, 6, 1, 0)[:, 0, 0, :], x[:, :6, :6, :].mean(axis=(1, 2)))
+    assert np.array_equal(O.avgpool_nhwc(x, 1, 1, 0), x)
+    # a hand-made corner: 2 x 2 image [[1, 2], [3, 4]], window 3, pad 1, stride 1: every window sees all four values
+    # except that nothing beyond the image counts -> all four results are 2.5
+    assert np.allclose(O.avgpool_nhwc(np.array([1.0, 2, 3, 4]).reshape(1, 2, 2, 1), 3, 1, 1), 2.5)
+    # the mean never exceeds the maximum over the same window
+    assert (O.avgpool_nhwc(x, 3, 2, 1) <= O.maxpool_nhwc(x, 3, 2, 1) + 1e-12).all()
+
+    g, p = _avgpool_round_graph()
+    # Round: halves go to the even integer, the sign survives
+    ins = {g.tensor_id("x"): np.array([0.5, 1.5, 2.5, -0.5, -1.5, 2.4999, 2.5001, -3.0] * 2, dtype=np.float64).reshape(1, 1, 1, 16)}
+    r = R.RDP(g).analyse()
+    po = P.build_plan(g, r)
+    out = execute.run(g, po.order, {}, ins)
+    assert out.values[g.tensor_id("rx")].reshape(-1)[:8].tolist() == [0.0, 2.0, 2.0, -0.0, -2.0, 2.0, 3.0, -3.0]
+    assert np.signbit(out.values[g.tensor_id("rx")].reshape(-1)[3])
+    assert R.fmt_list(r.S[p]) == "[s:N, e:1 + floordiv(-1 + H, 2), e:1 + floordiv(-1 + W, 2), k:16]"   # the window formula
+    assert R.OP_CLASS["AveragePool"] == "ISDOS" and R.OP_CLASS["Round"] == "ISDOS"
+    kinds = sorted(gr.kind for gr in po.groups.values())
+    assert kinds == ["AVGPOOL", "ELTWISE", "ELTWISE"]
+    chain = [gr for gr in po.groups.values() if gr.kind == "ELTWISE" and len(gr.ops) == 3]
+    assert len(chain) == 1                      # Mul, Round, Mul in one loop nest (fp32: the Round sees the stored value)
+    gb, _ = _avgpool_round_graph("bf16")
+    pb = P.build_plan(gb, R.RDP(gb).analyse())
+    assert sorted(len(gr.ops) for gr in pb.groups.values() if gr.kind == "ELTWISE") == [1, 1, 2]   # bf16: the Round starts a chain
+    for gg, pp in ((g, po), (gb, pb)):
+        lg = S.sod2_graph_build(gg)
+        lr = S.sod2_rdp_infer(lg)
+        lp = S.sod2_plan(lg, lr)
+        assert S.sod2_rdp_dump(lr) == R.dump(R.RDP(gg).analyse()) and S.sod2_plan_dump(lp) == P.dump(pp)
+        for sym in ({"N": 1, "H": 1, "W": 1}, {"N": 2, "H": 7, "W": 9}, {"N": 8, "H": 128, "W": 128}):
+            assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(pp, sym))
+    assert S.sod2_op_kind_class("AveragePool") == "ISDOS" and S.sod2_op_kind_class("Round") == "ISDOS"

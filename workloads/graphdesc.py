@@ -40,6 +40,8 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "LayerNorm": (),          # float attr eps
     "ReduceMean": ("axes", "keepdims"),
     "MaxPool": ("kernel", "stride", "pad"),
+    "AveragePool": ("kernel", "stride", "pad"),   # channels last; positions in the padding do not count
+    "Round": (),              # to the nearest integer, halves to the even one
     "ArgMax": (),
     "CacheAppend": (),
     "NonZero": (),
