@@ -68,7 +68,12 @@ enum { SOD2_INTER = 0, SOD2_INPUT = 1, SOD2_WEIGHT = 2, SOD2_HOSTCONST = 3 };
  *   [N, ..., C], scale [C], bias [C]; per sample and group of C / groups channels, mean and biased variance over the
  *   group's channels at every position.  AveragePool (channels last, like MaxPool): the mean over the window
  *   positions inside the input (padding is not counted; 0 <= pad < kernel).  Round: to the nearest integer, halves
- *   to the even one.  Switch: data, predicate (one float);
+ *   to the even one.  NMS (non-maximum suppression; Table 2: execution determined): scores [N] and boxes [N, 4]
+ *   (x1, y1, x2, y2 with x1 <= x2, y1 <= y2), both f32, N <= 4096, no NaN; boxes are visited by decreasing score
+ *   (equal scores: increasing index) and kept unless one already kept overlaps them by more than the threshold,
+ *   decided in fp32 as intersection > threshold * ((area_a + area_b) - intersection); result: the kept boxes'
+ *   indices in visiting order, int64, a vector whose length is known once the operator has run (handled like
+ *   NonZero's count).  Switch: data, predicate (one float);
  *   two results: taken when predicate <= threshold, taken when predicate > threshold.               */
 enum {
   SOD2_OP_SHAPE = 0, SOD2_OP_GATHER, SOD2_OP_CONCAT, SOD2_OP_RESHAPE, SOD2_OP_SLICE,
@@ -77,7 +82,7 @@ enum {
   SOD2_OP_REDUCEMEAN, SOD2_OP_MAXPOOL, SOD2_OP_ARGMAX, SOD2_OP_CACHEAPPEND, SOD2_OP_NONZERO,
   SOD2_OP_SWITCH, SOD2_OP_COMBINE, SOD2_OP_SCATTERROWS, SOD2_OP_RESIZE, SOD2_OP_RANGE, SOD2_OP_EXPAND,
   SOD2_OP_UPSAMPLE, SOD2_OP_CONSTANTOFSHAPE, SOD2_OP_EYELIKE, SOD2_OP_ONEHOT, SOD2_OP_TOPK, SOD2_OP_GROUPNORM, SOD2_OP_MAXUNPOOL,
-  SOD2_OP_AVERAGEPOOL, SOD2_OP_ROUND, SOD2_OP_COUNT
+  SOD2_OP_AVERAGEPOOL, SOD2_OP_ROUND, SOD2_OP_NMS, SOD2_OP_COUNT
 };
 
 #define SOD2_MAX_RANK 8
@@ -98,8 +103,8 @@ typedef struct {
 /* Integer attributes per kind, in this order:
  *   Gather/Concat: axis.  Transpose: the permutation.  MatMul: transB.  Conv: stride, pad.
  *   Softmax: causal.  ReduceMean: keepdims, then the axes.  MaxPool, AveragePool: kernel, stride, pad.
- *   EyeLike: the diagonal k.  GroupNorm: the number of groups.
- * Float attribute: LayerNorm and GroupNorm epsilon; Switch threshold; ConstantOfShape value.     */
+ *   EyeLike: the diagonal k.  GroupNorm: the number of groups.  NMS: the largest number of boxes to keep (0: no limit).
+ * Float attribute: LayerNorm and GroupNorm epsilon; Switch threshold; ConstantOfShape value; NMS overlap threshold. */
 typedef struct {
   int32_t kind;
   int32_t n_inputs;
@@ -185,7 +190,7 @@ sod2_status sod2_plan_dump(const sod2_plan_t*, char* buf_host, size_t cap, size_
  * tensors the group reads from outside itself; info->n_ops / n_ins always hold the full counts. */
 enum { SOD2_G_GEMM = 0, SOD2_G_CONV, SOD2_G_LAYERNORM, SOD2_G_SOFTMAX, SOD2_G_MAXPOOL, SOD2_G_REDUCEMEAN, SOD2_G_ARGMAX,
        SOD2_G_CACHEAPPEND, SOD2_G_NONZERO, SOD2_G_GATHER, SOD2_G_ELTWISE, SOD2_G_ATTENTION, SOD2_G_SCATTER, SOD2_G_RESIZE,
-       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM, SOD2_G_MAXUNPOOL, SOD2_G_AVGPOOL };
+       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM, SOD2_G_MAXUNPOOL, SOD2_G_AVGPOOL, SOD2_G_NMS };
 typedef struct {
   int32_t gid;        /* group id: the smallest operator id in the group */
   int32_t kind;       /* SOD2_G_* */
@@ -213,9 +218,9 @@ sod2_status sod2_bind(const sod2_plan_t*, const int64_t* symbol_values_host, int
 /* pure planning with a given decision vector (1 = the skip output of the Switch is taken); no run */
 sod2_status sod2_bind_decided(const sod2_plan_t*, const int64_t* symbol_values_host, int32_t n_symbols,
                               const int32_t* decisions_host, int32_t n_decisions, sod2_binding_t** out);
-/* The same for graphs with execution-determined extents (NonZero, Table 2's EDO class; Section 4.3):
- * exec_values_host = the counts found by the NonZero operators that have executed so far, in
- * execution order.  A NonZero still to run is planned at its upper bound, the element count of its
+/* The same for graphs with execution-determined extents (NonZero and NMS, Table 2's EDO class; Section 4.3):
+ * exec_values_host = the counts found by the NonZero / NMS operators that have executed so far, in
+ * execution order.  One still to run is planned at its upper bound, the element count of its first
  * input (this is also what sod2_bind does for all of them).  sod2_run reads each count back when the
  * operator has run and plans what follows with it; the exact plan usually needs less than the
  * upper-bound plan but may need more (first fit is not monotone in the sizes): then sod2_run stops
@@ -277,16 +282,17 @@ sod2_status sod2_binding_set_constants(sod2_binding_t*, const void* constants_de
 
 /* -- run -------------------------------------------------------------------------------------- */
 /* arena: device memory, 256-byte aligned, at least arena_bytes long.  weights / inputs / outputs:
- * host arrays of device pointers, one per tensor with that role, ordered by tensor id.
- * hip_stream: a hipStream_t (NULL = the null stream).  The first run of a graph with Switch or NonZero operators on
+ * host arrays of device pointers, one per tensor with that role, ordered by tensor id (the pointer of an input or
+ * output that has no elements at the bound symbols may be NULL, any other NULL is SOD2_ERR_INVALID_ARG).
+ * hip_stream: a hipStream_t (NULL = the null stream).  The first run of a graph with Switch, NonZero or NMS operators on
  * a host thread allocates one 64-byte slot of pinned, device-visible host memory (hipHostMalloc) for the read-backs;
  * it is kept until the process ends.  Nothing else is allocated by a run (launch records: events, created when
  * profiling is switched on).  Enqueues and returns; the host waits for the
- * GPU only at a Switch, whose predicate it needs, and after a NonZero, whose count (8 bytes) sizes
+ * GPU only at a Switch, whose predicate it needs, and after a NonZero or NMS, whose count (8 bytes) sizes
  * what follows: a one-thread kernel behind the producing kernel publishes the value into pinned host
  * memory and the host polls it (after 20 ms without it the stream is synchronised instead).  A run
  * with such a wait cannot be captured in a HIP graph (it returns SOD2_ERR_HIP under capture); runs
- * without Switch and NonZero only enqueue kernels and can be.  Kernel arguments are
+ * without Switch, NonZero and NMS only enqueue kernels and can be.  Kernel arguments are
  * prepared step by step while earlier kernels already execute: when a call fails (a group the
  * kernels do not support, an arena too small for the path taken) the groups before the failing one
  * may have run and the contents of the outputs and of the arena are unspecified. */
@@ -305,7 +311,7 @@ sod2_status sod2_run(sod2_binding_t*, void* arena_dev, size_t arena_bytes,
  *                               partial tiles exceed the buffer (checked for every launch before the
  *                               first one is enqueued: nothing has run); sod2_binding_force_splits(b, 1)
  *                               or sod2_run with a workspace avoid it
- *   SOD2_ERR_UNSUPPORTED        the graph has Switch or NonZero operators (their read-backs need a pinned
+ *   SOD2_ERR_UNSUPPORTED        the graph has Switch, NonZero or NMS operators (their read-backs need a pinned
  *                               host slot), or profiling is on (launch records need events)
  * All calls on one GPU share the buffer: two calls that overlap in time on the same GPU (different
  * streams or threads) race on it; calls on one stream are ordered and safe.  Every partial tile is written
@@ -317,7 +323,7 @@ sod2_status sod2_run_static(sod2_binding_t*, void* arena_dev, size_t arena_bytes
                             void* const* outputs_dev, int32_t n_outputs, void* hip_stream);
 /* decisions taken by the last run, in execution order; *n receives their count */
 sod2_status sod2_run_decisions(const sod2_binding_t*, int32_t* decisions_host, int32_t cap, int32_t* n);
-/* counts found by the NonZero operators of the last run, in execution order; *n receives their number */
+/* counts found by the NonZero / NMS operators of the last run, in execution order; *n receives their number */
 sod2_status sod2_run_exec_values(const sod2_binding_t*, int64_t* values_host, int32_t cap, int32_t* n);
 
 /* What the last run did, step by step (Section 4.3: with control flow only the taken path is launched; Section
@@ -348,7 +354,7 @@ typedef struct {
   int32_t kernel;      /* 0 gemm, 1 conv, 2 layernorm, 3 softmax, 4 eltwise, 5 pool, 6 reduce, 7 other,
                           8 gather, 9 cache append, 10 argmax, 11 fused attention, 12 nonzero,
                           13 scatter rows, 14 resize (nearest), 15 concat, 16 range, 17 fill (constant / identity),
-                          18 one-hot, 19 top-k, 20 group normalisation, 21 max-unpool */
+                          18 one-hot, 19 top-k, 20 group normalisation, 21 max-unpool, 22 non-maximum suppression */
   int32_t variant;
   int32_t reserved;
   float ms;            /* event-to-event duration */

@@ -42,7 +42,7 @@ from typing import Dict, List, Sequence, Tuple
 
 from . import rdp as R
 from .expr import Expr
-from .plan import Plan, DT_BYTES, align_up, arena_candidate
+from .plan import Plan, DT_BYTES, align_up, arena_candidate, COUNTING_GROUPS
 
 
 class SymbolOutOfRange(Exception):
@@ -206,7 +206,7 @@ def bind(plan: Plan, sym: Dict[str, int], decisions: Sequence[bool] = (),
                     reads_at[info(t)[1]] = step
                 t = gr.out
                 nz_bytes = None
-                if gr.kind == "NONZERO":
+                if gr.kind in COUNTING_GROUPS:
                     n_op = gr.ops[0]
                     src = concrete_dims(plan, g.ops[n_op].inputs[0], env)
                     ub = 1
@@ -343,7 +343,7 @@ def planning_regions(plan: Plan, b: Binding) -> List[List[int]]:
     alone = []
     for k in range(len(b.steps)):
         it = plan.items[b.steps[k]]
-        nz = it.is_group and plan.groups[it.ref].kind == "NONZERO"
+        nz = it.is_group and plan.groups[it.ref].kind in COUNTING_GROUPS
         alone.append((not it.is_group) or nz or (plan.sg_class[b.step_sg[k]] == "nac" and seen > known))
         seen += nz
     regions: List[List[int]] = []

@@ -128,6 +128,9 @@ def run(graph, order: Sequence[int], weights: Dict[int, np.ndarray], inputs: Dic
         elif k == "NonZero":
             y = O.nonzero(xs[0])
             res.exec_values.append(int(y.shape[1]))
+        elif k == "NMS":
+            y = O.nms(xs[0], xs[1], int(a.get("max_out", 0)), a["iou"])
+            res.exec_values.append(int(y.shape[0]))
         elif k == "Range":
             y = np.arange(int(np.asarray(xs[0]).reshape(-1)[0]), int(np.asarray(xs[1]).reshape(-1)[0]),
                           int(np.asarray(xs[2]).reshape(-1)[0]), dtype=np.int64)

@@ -134,6 +134,33 @@ def slice_(x, starts, ends, axes):
     return x[tuple(idx)]
 
 
+def nms(scores, boxes, max_out, iou):
+    """Non-maximum suppression (Table 2 lists NMS with the execution-determined operators: how many boxes
+    survive is known only once it has run).  Boxes are visited by decreasing score, equal scores by increasing
+    index; a box is kept unless it overlaps an already kept box by more than ``iou`` (intersection over union),
+    and at most ``max_out`` boxes are kept (0: no limit).  The overlap test decides an integer result, so it is
+    taken in the operands' own precision, fp32, each operation rounded on its own:
+    intersection > iou * ((area_a + area_b) - intersection).  Returns the kept indices in visiting order."""
+    f = np.float32
+    s = np.asarray(scores, dtype=f).reshape(-1)
+    b = np.asarray(boxes, dtype=f).reshape(-1, 4)
+    order = np.argsort(-s, kind="stable")
+    thr = f(iou)
+    area = (b[:, 2] - b[:, 0]) * (b[:, 3] - b[:, 1])              # float32 arrays: every operation rounds to fp32
+    kept = []
+    for i in order:
+        k = b[kept]                                               # the boxes kept so far
+        iw = np.maximum(f(0), np.minimum(b[i, 2], k[:, 2]) - np.maximum(b[i, 0], k[:, 0]))
+        ih = np.maximum(f(0), np.minimum(b[i, 3], k[:, 3]) - np.maximum(b[i, 1], k[:, 1]))
+        inter = iw * ih
+        union = (area[i] + area[kept]) - inter
+        if not (inter > thr * union).any():
+            kept.append(int(i))
+            if max_out > 0 and len(kept) == max_out:
+                break
+    return np.asarray(kept, dtype=np.int64)
+
+
 def nonzero(x):
     """Coordinates of the non-zero elements, one column per element in row-major order: [rank, count]."""
     x = np.asarray(x)

@@ -17,7 +17,7 @@ R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     operator that does not fit.  With fusion switched off only a directly
     following Transpose is still taken: the permuted store is a layout choice
     of the contraction, and without it the Reshape behind it would need a copy.
-R3  LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, AveragePool, ReduceMean, ArgMax, CacheAppend, NonZero,
+R3  LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, AveragePool, ReduceMean, ArgMax, CacheAppend, NonZero, NMS,
     ScatterRows, Resize, Upsample, OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded are groups of their own; a non-view Gather absorbs one following Add whose
     other operand has a proven-equal shape.
 R4  Remaining elementwise operators chain, up to 8 ops (a Round joins a chain
@@ -73,9 +73,9 @@ with the options (the same numbers go to the library's planner); they shape
 the groups, never a value.
 
 Execution-determined extents (Section 4.3: what follows an EDO can only be
-planned once it has executed).  When the graph holds a NonZero the plan uses
+planned once it has executed).  When the graph holds a NonZero or an NMS the plan uses
 the analysis with *named* EDO extents (``RDP(named_edo=True)``): sizes after
-the NonZero are expressions in its execution symbol, evaluated at run time as
+such an operator are expressions in its execution symbol, evaluated at run time as
 soon as the count is known.  A tensor that is nac or mentions an execution
 symbol counts as nac for the partition: a cut follows every item that writes
 one, and such sub-graphs keep the node order (no search).
@@ -93,10 +93,12 @@ MAX_SG = 14
 DT_BYTES = {"f32": 4, "bf16": 2, "i64": 8, "i32": 4}
 VIEW_KINDS = ("Reshape", "Slice", "Transpose", "Expand")
 ACTS = ("Relu", "Gelu", "Sigmoid")
+COUNTING = ("NonZero", "NMS")                  # execution-determined operators whose result has a length found by running
+COUNTING_GROUPS = ("NONZERO", "NMS")
 ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast", "Round")
 SOLO = {"LayerNorm": "LAYERNORM", "Softmax": "SOFTMAX", "MaxPool": "MAXPOOL",
         "ReduceMean": "REDUCEMEAN", "ArgMax": "ARGMAX", "CacheAppend": "CACHEAPPEND",
-        "NonZero": "NONZERO", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE",
+        "NonZero": "NONZERO", "NMS": "NMS", "ScatterRows": "SCATTER", "Resize": "RESIZE", "Concat": "CONCAT", "Range": "RANGE",
         "Upsample": "RESIZE", "ConstantOfShape": "FILL", "EyeLike": "FILL", "OneHot": "ONEHOT", "TopK": "TOPK", "GroupNorm": "GROUPNORM", "MaxUnpool": "MAXUNPOOL",
         "AveragePool": "AVGPOOL"}
 
@@ -206,7 +208,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     opts = opts or Opts()
     g = graph
     paper_rdp = rdp
-    if any(op.kind == "NonZero" for op in g.ops):
+    if any(op.kind in COUNTING for op in g.ops):
         rdp = R.RDP(g, named_edo=True).analyse()
     order = rdp.sorted_nodes()
     pos = {n: i for i, n in enumerate(order)}
@@ -507,7 +509,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             items.append(Item(False, ref, reads, list(op.outputs) if op.kind == "Combine" else []))
 
     plan = Plan(g, rdp, opts, order, folded, view, groups, assigned, items, [], [], sbase, versions,
-                paper_rdp, [n for n in order if g.ops[n].kind == "NonZero"])
+                paper_rdp, [n for n in order if g.ops[n].kind in COUNTING])
     plan.fold_y = fold_y
     _partition(plan)
     if opts.inplace:
@@ -556,7 +558,7 @@ def _mark_inplace(plan: Plan):
             if d.role != "inter" or not arena_candidate(plan, r) or r in combined or r in plan.inplace.values():
                 continue
             pr = prod[r]
-            if pr < 0 or plan.folded[pr] or plan.view[pr] or g.ops[pr].kind in ("Switch", "Combine", "NonZero"):
+            if pr < 0 or plan.folded[pr] or plan.view[pr] or g.ops[pr].kind in ("Switch", "Combine") + COUNTING:
                 continue
             if plan.groups[plan.group_of_op[pr]].out != r:
                 continue
@@ -600,7 +602,7 @@ def _partition(plan: Plan):
             if arena_candidate(plan, t) and last_read.get(t, -1) > i:
                 live.add(t)
         live = {t for t in live if last_read[t] > i}
-        is_edo = (not it.is_group) or plan.groups[it.ref].kind == "NONZERO"
+        is_edo = (not it.is_group) or plan.groups[it.ref].kind in COUNTING_GROUPS
         if is_edo:
             cut_after[i] = True
             if i > 0:

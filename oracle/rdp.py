@@ -35,7 +35,7 @@ OP_CLASS = {
     "ArgMax": ISDOS, "CacheAppend": ISDOS, "ScatterRows": ISDOS,
     "Reshape": ISVDOS, "Slice": ISVDOS, "Resize": ISVDOS, "Range": ISVDOS, "Expand": ISVDOS,
     "OneHot": ISVDOS, "Upsample": ISVDOS, "TopK": ISVDOS, "GroupNorm": ISVDOS, "MaxUnpool": ISVDOS,
-    "NonZero": EDO, "Switch": EDO, "Combine": EDO,
+    "NonZero": EDO, "NMS": EDO, "Switch": EDO, "Combine": EDO,
 }
 UNARY = ("Relu", "Gelu", "Sigmoid", "Round", "Cast", "Softmax", "LayerNorm", "GroupNorm")   # result shaped like input 0
 EXEC_PREFIX = "@nz"   # name of an execution symbol: EXEC_PREFIX + operator id
@@ -311,6 +311,10 @@ class RDP:
             if s is UNDEF:
                 return False
             res = [(NAC if s == NAC else [C(len(s)), Expr.sym(exec_symbol(n))], NAC)]
+        elif cls == EDO and self.named_edo and op.kind == "NMS":
+            if self.S[op.inputs[0]] is UNDEF:
+                return False
+            res = [([Expr.sym(exec_symbol(n))], NAC)]   # the kept boxes' indices: a vector whose length is found by running
         elif cls == EDO:
             res = [(NAC, NAC) for _ in op.outputs]
         else:

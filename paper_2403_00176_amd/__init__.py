@@ -25,7 +25,7 @@ ROLES = {"inter": 0, "input": 1, "weight": 2, "hostconst": 3}
 OP_KINDS = ["Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul",
             "Relu", "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax",
             "CacheAppend", "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand",
-            "Upsample", "ConstantOfShape", "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool", "AveragePool", "Round"]
+            "Upsample", "ConstantOfShape", "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool", "AveragePool", "Round", "NMS"]
 OP_CLASS_NAMES = ["ISDO", "ISDOS", "ISVDOS", "EDO"]
 
 EXPORTS = [
@@ -84,7 +84,7 @@ class LaunchRecord(C.Structure):
 
 
 KERNEL_NAMES = ["gemm", "conv", "layernorm", "softmax", "eltwise", "pool", "reduce", "other", "gather", "append", "argmax", "attention",
-                "nonzero", "scatter", "resize", "concat", "range", "fill", "onehot", "topk", "groupnorm", "maxunpool"]
+                "nonzero", "scatter", "resize", "concat", "range", "fill", "onehot", "topk", "groupnorm", "maxunpool", "nms"]
 
 _lib.sod2_last_error.restype = C.c_char_p
 _lib.sod2_version.restype = C.c_char_p
@@ -126,6 +126,9 @@ def _attrs(kind: str, attrs: dict):
         fa = float(attrs.get("value", 0.0))
     elif kind == "EyeLike":
         ia = [int(attrs.get("k", 0))]
+    elif kind == "NMS":
+        ia = [int(attrs.get("max_out", 0))]
+        fa = float(attrs["iou"])
     elif kind == "GroupNorm":
         ia = [int(attrs["groups"])]
         fa = float(attrs["eps"])
@@ -421,7 +424,7 @@ def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence
 STATIC_SCRATCH_BYTES = 8 << 20
 
 GROUP_KINDS = ["GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX", "CACHEAPPEND", "NONZERO", "GATHER",
-               "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL"]
+               "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL", "NMS"]
 SG_CLASSES = ["known", "mixed", "nac"]
 
 

@@ -94,7 +94,7 @@ sod2_status sod2_graph_build(const sod2_graph_desc* d, sod2_graph_t** out) {
     op.out.assign(od.outputs, od.outputs + od.n_outputs);
     if (od.n_iattr) op.ia.assign(od.iattr, od.iattr + od.n_iattr);
     op.fa = od.fattr;
-    static const int n_in[SOD2_OP_COUNT] = {1, 2, -1, 2, 4, 1, 2, 2, 2, 2, 1, 1, 1, 1, 1, 3, 1, 1, 1, 2, 1, 2, -1, 3, 2, 3, 2, 2, 1, 1, 3, 2, 3, 3, 1, 1};
+    static const int n_in[SOD2_OP_COUNT] = {1, 2, -1, 2, 4, 1, 2, 2, 2, 2, 1, 1, 1, 1, 1, 3, 1, 1, 1, 2, 1, 2, -1, 3, 2, 3, 2, 2, 1, 1, 3, 2, 3, 3, 1, 1, 2};
     if (n_in[op.kind] >= 0 && (int)op.in.size() != n_in[op.kind])
       throw Error(SOD2_ERR_INVALID_ARG, std::string("wrong input count for ") + op_name(op.kind));
     if (op.out.empty() || ((op.kind == SOD2_OP_SWITCH || op.kind == SOD2_OP_TOPK) && op.out.size() != 2))

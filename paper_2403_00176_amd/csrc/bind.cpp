@@ -14,8 +14,8 @@
 // the arena, in tensor-id order, sized for the declared capacity at the bound symbols; every other
 // offset starts above that region.  CacheAppend writes into the slot of its first input.
 //
-// Execution-determined extents (Section 4.3): a NonZero whose count is not known yet is planned at
-// its upper bound (the element count of its input); binding again with the count gives the plan for
+// Execution-determined extents (Section 4.3): a NonZero (or NMS) whose count is not known yet is planned at
+// its upper bound (the element count of its first input); binding again with the count gives the plan for
 // what follows, and nothing that already ran moves (a cut follows every NonZero, sub-graphs are
 // placed in execution order).  Its result is allocated before the extent is known: always rank x
 // upper bound indices plus one 8-byte slot for the count.  First fit is not monotone in the sizes:
@@ -162,7 +162,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         for (int t : ext) reads_at[info(t).second] = step;
         int t = gr.out;
         int64_t nz_bytes = -1;
-        if (gr.kind == G_NONZERO) {
+        if (gr.kind == G_NONZERO || gr.kind == G_NMS) {
           int n_op = gr.ops[0], src = G.ops[n_op].in[0];
           if (p.cshape[src].empty() && !p.rdp->S[src].resolved())
             throw Error(SOD2_ERR_UNRESOLVED_SHAPE, "shape of " + G.tensors[src].name + " is not resolved");
@@ -282,7 +282,7 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
       for (const auto& e : b.exec) known += e.known ? 1 : 0;
       for (int k = 0; k < nsteps; ++k) {
         const Item& it = p.items[b.steps[k]];
-        bool nz = it.is_group && p.groups.at(it.ref).kind == G_NONZERO;
+        bool nz = it.is_group && (p.groups.at(it.ref).kind == G_NONZERO || p.groups.at(it.ref).kind == G_NMS);
         alone_v[k] = !it.is_group || nz || (p.sg_class[b.step_sg[k]] == "nac" && seen > known);
         seen += nz ? 1 : 0;
       }

@@ -807,6 +807,109 @@ hipError_t launch_nonzero(const NonzeroArgs& a, hipStream_t s) {
   return hipGetLastError();
 }
 
+// Non-maximum suppression.  One workgroup of 16 waves: (1) a bitonic sort in LDS of 64-bit keys (score, made
+// decreasing, above the box index, so equal scores keep the index order); (2) the boxes copied to LDS in that order;
+// (3) the greedy walk, 64 boxes at a time: the waves compute which box of the block suppresses which later box of
+// the block (a 64 x 64 bit matrix, one ballot per row); every wave then resolves the block on its own with scalar
+// bit operations (a box still alive is kept and clears the boxes its row names), wave 0 writes the kept indices,
+// and all threads test the boxes behind the block against the block's kept boxes.  Two barriers per block.
+// The overlap test is taken with separately rounded fp32 operations (no fused multiply-add), as the operator's
+// definition states it: a kept box i suppresses j when inter > iou * ((area_i + area_j) - inter).
+constexpr int NMS_THREADS = 1024;
+__device__ inline bool nms_overlaps(const float4 bi, const float4 bj, float iou) {
+#pragma clang fp contract(off)
+  const float iw = fmaxf(0.f, fminf(bi.z, bj.z) - fmaxf(bi.x, bj.x));
+  const float ih = fmaxf(0.f, fminf(bi.w, bj.w) - fmaxf(bi.y, bj.y));
+  const float inter = iw * ih;
+  const float area_i = (bi.z - bi.x) * (bi.w - bi.y);
+  const float area_j = (bj.z - bj.x) * (bj.w - bj.y);
+  const float uni = (area_i + area_j) - inter;
+  return inter > iou * uni;
+}
+__global__ __launch_bounds__(NMS_THREADS) void nms_kernel(NmsArgs a) {
+  __shared__ unsigned long long key[NMS_MAX_BOXES];
+  __shared__ float4 box[NMS_MAX_BOXES];
+  __shared__ unsigned char alive[NMS_MAX_BOXES];
+  __shared__ unsigned long long rowmask[64];
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int P = 1;
+  while (P < a.n) P <<= 1;
+  for (int i = tid; i < P; i += NMS_THREADS) {
+    unsigned long long k = ~0ull;                      // padding sorts behind every box
+    if (i < a.n) {
+      unsigned u = __float_as_uint(a.scores[i] + 0.f); // (-0 becomes +0: the two are one score)
+      u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);  // increasing with the score
+      k = ((unsigned long long)(~u) << 32) | (unsigned)i;
+    }
+    key[i] = k;
+  }
+  __syncthreads();
+  for (int size = 2; size <= P; size <<= 1)
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = tid; t < P / 2; t += NMS_THREADS) {
+        const int lo = 2 * t - (t & (stride - 1)), hi = lo + stride;
+        const bool up = (lo & size) == 0;
+        const unsigned long long x = key[lo], y = key[hi];
+        if ((x > y) == up) { key[lo] = y; key[hi] = x; }
+      }
+      __syncthreads();
+    }
+  for (int i = tid; i < a.n; i += NMS_THREADS) {
+    box[i] = *(const float4*)(a.boxes + 4ll * (unsigned)key[i]);
+    alive[i] = 1;
+  }
+  __syncthreads();
+  int count = 0;
+  for (int b0 = 0; b0 < a.n; b0 += 64) {
+    const int nb = min(64, a.n - b0);
+    // which box of the block suppresses which later box of the block: wave w owns rows 4 w .. 4 w + 3, a lane a column
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int r = wave * 4 + q;
+      bool bit = false;
+      if (r < nb && lane < nb && lane > r) bit = nms_overlaps(box[b0 + r], box[b0 + lane], a.iou);
+      const unsigned long long m = __ballot(bit);
+      if (lane == 0) rowmask[r] = m;
+    }
+    __syncthreads();
+    // every wave resolves the block (the same scalar walk in each: nothing to broadcast)
+    const unsigned long long mine = rowmask[lane];
+    const int mlo = (int)(unsigned)mine, mhi = (int)(unsigned)(mine >> 32);
+    unsigned long long live = __ballot(lane < nb && alive[b0 + lane] != 0);
+    unsigned long long kept = 0;
+    int cnt = count;
+#pragma unroll
+    for (int r = 0; r < 64; ++r) {
+      const unsigned long long m = (unsigned long long)(unsigned)__builtin_amdgcn_readlane(mlo, r) |
+                                   ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(mhi, r) << 32);
+      if (((live >> r) & 1) && !(a.max_out > 0 && cnt >= a.max_out)) {
+        kept |= 1ull << r;
+        ++cnt;
+        live &= ~m;
+      }
+    }
+    if (wave == 0 && ((kept >> lane) & 1))
+      a.out[count + __popcll(kept & ((1ull << lane) - 1))] = (long long)(unsigned)key[b0 + lane];
+    count = cnt;
+    if (a.max_out > 0 && count >= a.max_out) break;    // (the same in every thread)
+    // the block's kept boxes against everything behind the block
+    for (int j = b0 + 64 + tid; j < a.n; j += NMS_THREADS) {
+      if (!alive[j]) continue;
+      const float4 bj = box[j];
+      for (unsigned long long m = kept; m; m &= m - 1)
+        if (nms_overlaps(box[b0 + (int)__builtin_ctzll(m)], bj, a.iou)) { alive[j] = 0; break; }
+    }
+    __syncthreads();
+  }
+  if (tid == 0) *a.count = count;
+}
+
+hipError_t launch_nms(const NmsArgs& a, hipStream_t s) {
+  if (a.n < 0 || a.n > NMS_MAX_BOXES) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(nms_kernel, dim3(1), dim3(NMS_THREADS), 0, s, a);
+  return hipGetLastError();
+}
+
 // V: the unit a row is copied in (16 bytes when rows and pointers allow it, else one element)
 template <class V, class I>
 __global__ __launch_bounds__(256) void scatter_rows_kernel(ScatterArgs a, long long row_units) {

@@ -15,7 +15,7 @@ struct Ref {
 };
 
 enum KernelKind { K_GEMM = 0, K_CONV, K_LAYERNORM, K_SOFTMAX, K_ELTWISE, K_POOL, K_REDUCE, K_OTHER, K_GATHER, K_APPEND,
-                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT, K_TOPK, K_GROUPNORM, K_MAXUNPOOL };
+                  K_ARGMAX, K_ATTENTION, K_NONZERO, K_SCATTER, K_RESIZE, K_CONCAT, K_RANGE, K_FILL, K_ONEHOT, K_TOPK, K_GROUPNORM, K_MAXUNPOOL, K_NMS };
 enum Act { ACT_NONE = 0, ACT_RELU, ACT_GELU, ACT_SIGMOID };
 enum GemmVariant { V_REGULAR = 0, V_FAT = 1, V_SKINNY = 2, V_SIMPLE = 3, V_SMALL = 4, V_XFAT = 5, V_GEMV = 6, V_DL0 = 10 };   // (a contraction with a LayerNorm prologue has one kernel per shape class: ln_gamma set)
 // tiles of the direct-to-LDS contraction (variant = V_DL0 + tile): BM x BN x BK, ring stages
@@ -160,6 +160,16 @@ struct NonzeroArgs {
   long long dims[4];
 };
 
+// Non-maximum suppression (Table 2's EDO class): boxes visited by decreasing score (equal scores by increasing
+// index), kept unless an already kept box overlaps them by more than `iou`; out[j] = index of the j-th kept box,
+// *count = how many (8 bytes behind the upper-bound storage of n indices).  One workgroup, n <= NMS_MAX_BOXES.
+constexpr int NMS_MAX_BOXES = 4096;
+struct NmsArgs {
+  const float* scores; const float* boxes; long long* out; long long* count;
+  int n, max_out;
+  float iou;
+};
+
 // out = x with the rows idx[j] replaced by y[j] (j < n; the last j wins on duplicates); rows of
 // `cols` elements, everything dense
 struct ScatterArgs {
@@ -259,6 +269,7 @@ struct Launch {
     TopKArgs topk;
     GroupNormArgs gn;
     UnpoolArgs unpool;
+    NmsArgs nms;
   } u;
   int unit_bytes = 0;      // resize / concat: bytes of one copy unit
   bool is_layernorm = false;

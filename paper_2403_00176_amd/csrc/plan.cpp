@@ -8,7 +8,7 @@
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
 //     consumer of the chain so far;
-//  R3 LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, AveragePool, ReduceMean, ArgMax, CacheAppend, NonZero, ScatterRows, Resize, Upsample,
+//  R3 LayerNorm, GroupNorm, MaxUnpool, Softmax, MaxPool, AveragePool, ReduceMean, ArgMax, CacheAppend, NonZero, NMS, ScatterRows, Resize, Upsample,
 //     OneHot, TopK (one group, two results), and a Concat, Range, ConstantOfShape or EyeLike that is not folded stand alone; a
 //     non-view Gather absorbs one Add of proven-equal shape;
 //  R4 other elementwise operators chain (up to 8; a Round joins only behind an fp32 value, else it starts a chain).  A dim pair of the two operands of a binary member is proven when
@@ -25,11 +25,11 @@
 //     through views only and with no other reader, the results of two CacheAppend operators that
 //     each append a known number of at most append_max_rows (4) bf16 rows (the decode step), their CACHEAPPEND groups
 //     join the ATTENTION group: its kernel writes the new rows into the session slots itself.
-// Partition: cut around control operators and NonZero, after a group with a nac output, wherever
+// Partition: cut around control operators, NonZero and NMS, after a group with a nac output, wherever
 // at most one arena tensor is live, and every 14 items.  Order inside a sub-graph: the sequence
 // with the smallest peak of live bytes at the symbols' upper bounds, ties to smaller group ids.
 //
-// Execution-determined extents (Section 4.3): with a NonZero in the graph the plan is built on the
+// Execution-determined extents (Section 4.3): with a NonZero or an NMS in the graph the plan is built on the
 // analysis with named EDO extents; a tensor that is unresolved or sized by an execution symbol
 // counts as nac: a cut follows every item that writes one and such sub-graphs keep the node order.
 #include <algorithm>
@@ -40,7 +40,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL", "NMS"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -49,6 +49,7 @@ const int kMaxSubgraph = 14;
 bool is_act(int k) { return k == SOD2_OP_RELU || k == SOD2_OP_GELU || k == SOD2_OP_SIGMOID; }
 bool is_eltwise(int k) { return k == SOD2_OP_ADD || k == SOD2_OP_MUL || is_act(k) || k == SOD2_OP_CAST || k == SOD2_OP_ROUND; }
 bool is_control(int k) { return k == SOD2_OP_SWITCH || k == SOD2_OP_COMBINE; }
+bool is_counting(int k) { return k == SOD2_OP_NONZERO || k == SOD2_OP_NMS; }   // a result whose length is found by running
 
 bool shape_equal(const LS& a, const LS& b) {
   if (!a.resolved() || !b.resolved() || a.d.size() != b.d.size()) return false;
@@ -104,7 +105,7 @@ void Plan::build() {
   const Graph& G = *g;
   paper_rdp = rdp;
   for (const Op& op : G.ops)
-    if (op.kind == SOD2_OP_NONZERO && !named) {
+    if (is_counting(op.kind) && !named) {
       // Section 4.3: what follows an EDO is planned when it has executed.  With its extent named,
       // the sizes that follow are expressions evaluated at that moment instead of re-inferred.
       named = std::make_shared<Rdp>();
@@ -221,6 +222,7 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_GROUPNORM) new_group(G_GROUPNORM, {n});
     else if (op.kind == SOD2_OP_MAXUNPOOL) new_group(G_MAXUNPOOL, {n});
     else if (op.kind == SOD2_OP_AVERAGEPOOL) new_group(G_AVGPOOL, {n});
+    else if (op.kind == SOD2_OP_NMS) new_group(G_NMS, {n});
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);
@@ -475,7 +477,7 @@ void Plan::build() {
     const Item& it = items[i];
     for (int t : it.writes) if (arena_candidate(t) && lr(t) > i) live.insert(t);
     for (auto p = live.begin(); p != live.end();) p = (lr(*p) > i) ? std::next(p) : live.erase(p);
-    bool edo = !it.is_group || groups[it.ref].kind == G_NONZERO;
+    bool edo = !it.is_group || groups[it.ref].kind == G_NONZERO || groups[it.ref].kind == G_NMS;
     if (edo) {
       cut_after[i] = 1;
       if (i > 0) cut_after[i - 1] = 1;
@@ -630,7 +632,7 @@ void Plan::build() {
         const Tensor& d = G.tensors[r];
         if (d.role != SOD2_INTER || !arena_candidate(r) || combined.count(r) || taken.count(r)) continue;
         int pr = G.producer[r];
-        if (pr < 0 || folded[pr] || view[pr] || is_control(G.ops[pr].kind) || G.ops[pr].kind == SOD2_OP_NONZERO) continue;
+        if (pr < 0 || folded[pr] || view[pr] || is_control(G.ops[pr].kind) || is_counting(G.ops[pr].kind)) continue;
         if (groups.at(group_of_op[pr]).out != r) continue;
         if (d.dtype != G.tensors[gr.out].dtype || !shape_equal(R.S[r], R.S[gr.out])) continue;
         int through = 0;
@@ -649,7 +651,7 @@ void Plan::build() {
 
   // flattened forms used by every bind
   for (const Symbol& sy : G.symbols) xc.symbols.push_back(sy.name);
-  for (int n : order) if (G.ops[n].kind == SOD2_OP_NONZERO) exec_ops.push_back(n);
+  for (int n : order) if (is_counting(G.ops[n].kind)) exec_ops.push_back(n);
   for (int n : exec_ops) xc.symbols.push_back(exec_symbol(n));   // their values follow the graph symbols'
   cshape.assign(nt, {});
   for (int t = 0; t < nt; ++t) {

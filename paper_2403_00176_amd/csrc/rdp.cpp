@@ -17,7 +17,7 @@ static const char* kOpNames[SOD2_OP_COUNT] = {
     "Shape", "Gather", "Concat", "Reshape", "Slice", "Transpose", "MatMul", "Conv", "Add", "Mul", "Relu",
     "Gelu", "Sigmoid", "Cast", "Softmax", "LayerNorm", "ReduceMean", "MaxPool", "ArgMax", "CacheAppend",
     "NonZero", "Switch", "Combine", "ScatterRows", "Resize", "Range", "Expand", "Upsample", "ConstantOfShape",
-    "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool", "AveragePool", "Round"};
+    "EyeLike", "OneHot", "TopK", "GroupNorm", "MaxUnpool", "AveragePool", "Round", "NMS"};
 const char* op_name(int kind) { return (kind >= 0 && kind < SOD2_OP_COUNT) ? kOpNames[kind] : "?"; }
 
 int op_class(int kind) {   // Table 2
@@ -25,7 +25,7 @@ int op_class(int kind) {   // Table 2
     case SOD2_OP_SHAPE: case SOD2_OP_CONSTANTOFSHAPE: case SOD2_OP_EYELIKE: return 0;
     case SOD2_OP_RESHAPE: case SOD2_OP_SLICE: case SOD2_OP_RESIZE: case SOD2_OP_RANGE: case SOD2_OP_EXPAND:
     case SOD2_OP_ONEHOT: case SOD2_OP_UPSAMPLE: case SOD2_OP_TOPK: case SOD2_OP_GROUPNORM: case SOD2_OP_MAXUNPOOL: return 2;
-    case SOD2_OP_NONZERO: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
+    case SOD2_OP_NONZERO: case SOD2_OP_NMS: case SOD2_OP_SWITCH: case SOD2_OP_COMBINE: return 3;
     default: return 1;
   }
 }
@@ -392,6 +392,11 @@ struct Analyser {
         if (x.k == LS::UNDEF) return r;
         if (x.k == LS::NAC) return done(LS::nac(), LS::nac());
         return done(LS::list({LV::c((int64_t)x.d.size()), LV::of(Expr::symbol(exec_symbol(op_id)))}), LS::nac());
+      }
+      case SOD2_OP_NMS: {                                // execution determined: how many boxes are kept
+        if (!named_edo) return done(LS::nac(), LS::nac());
+        if (in_s(0).k == LS::UNDEF) return r;
+        return done(LS::list({LV::of(Expr::symbol(exec_symbol(op_id)))}), LS::nac());
       }
       case SOD2_OP_RANGE: {          // length ceil((limit - start) / delta) for a known positive delta (limit >= start assumed)
         for (int k = 0; k < 3; ++k) if (in_v(k).k == LS::UNDEF) return r;

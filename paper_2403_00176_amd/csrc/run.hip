@@ -21,6 +21,7 @@ hipError_t launch_gather(const Launch& L, const GatherArgs& a, hipStream_t s);
 hipError_t launch_append(const Launch& L, const AppendArgs& a, hipStream_t s);
 hipError_t launch_argmax(const Launch& L, const ArgmaxArgs& a, hipStream_t s);
 hipError_t launch_nonzero(const NonzeroArgs& a, hipStream_t s);
+hipError_t launch_nms(const NmsArgs& a, hipStream_t s);
 hipError_t launch_scatter(const Launch& L, const ScatterArgs& a, hipStream_t s);
 hipError_t launch_resize(const Launch& L, const ResizeArgs& a, hipStream_t s);
 hipError_t launch_concat(const Launch& L, const ConcatArgs& a, hipStream_t s);
@@ -750,7 +751,7 @@ struct Builder {
     const Op& op = G.ops[gr.chain[0]];
     const View &vt = view_of(op.in[0]), &vi = view_of(op.in[1]);
     int dt = G.tensors[op.in[0]].dtype, it = G.tensors[op.in[1]].dtype;
-    if (vt.dims.size() < 2 || !vt.contiguous() || vi.dims.size() != 1 || !vi.contiguous() || !is_int(it) ||
+    if (vt.dims.size() < 1 || !vt.contiguous() || vi.dims.size() != 1 || !vi.contiguous() || !is_int(it) ||
         (!op.ia.empty() && op.ia[0] != 0) || (dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt)
       throw Error(SOD2_ERR_UNSUPPORTED, "Gather kernel: leading-dim slices of a contiguous float tensor by a rank-1 index tensor");
     GatherArgs a{};
@@ -970,6 +971,37 @@ struct Builder {
     L.r[2].byte_off += (int64_t)a.rank * a.n * 8;
     L.u.nz = a;
     L.bytes = (double)a.n * dtype_bytes(dt);
+    return L;
+  }
+
+  // NMS: the kept boxes' indices into the upper-bound storage (one per box), the count behind them
+  Launch nms(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_NMS;
+    const Op& op = G.ops[gr.ops[0]];
+    const View &vs = view_of(op.in[0]), &vb = view_of(op.in[1]);
+    if (G.tensors[op.in[0]].dtype != SOD2_F32 || G.tensors[op.in[1]].dtype != SOD2_F32 || G.tensors[gr.out].dtype != SOD2_I64 ||
+        !vs.contiguous() || !vb.contiguous() || vs.dims.size() != 1 || vb.dims.size() != 2 || vb.dims[1] != 4)
+      throw Error(SOD2_ERR_UNSUPPORTED, "NMS kernel: dense f32 scores [N] and boxes [N, 4], int64 result");
+    if (vb.dims[0] != vs.dims[0]) throw Error(SOD2_ERR_SHAPE_MISMATCH, "NMS: one score per box");
+    if (vs.dims[0] > NMS_MAX_BOXES) throw Error(SOD2_ERR_UNSUPPORTED, "NMS kernel: at most " + std::to_string(NMS_MAX_BOXES) + " boxes");
+    if (!b.tensors.count(gr.out))                      // a caller buffer has no room for the count
+      throw Error(SOD2_ERR_UNSUPPORTED, "the result of NMS must be an intermediate tensor (read it through a Gather or Cast)");
+    NmsArgs a{};
+    a.n = (int)vs.dims[0];
+    a.max_out = op.ia.empty() ? 0 : (int)op.ia[0];
+    a.iou = (float)op.fa;
+    if (a.max_out < 0) throw Error(SOD2_ERR_INVALID_ARG, "NMS: max_out must not be negative");
+    L.in_dtype = SOD2_F32;
+    L.out_dtype = SOD2_I64;
+    L.r[0] = ref_of(vs, SOD2_F32);
+    L.r[1] = ref_of(vb, SOD2_F32);
+    L.r[2] = ref_t(gr.out);
+    L.r[3] = L.r[2];                                   // the count: behind the upper bound of n indices
+    L.r[3].byte_off += (int64_t)a.n * 8;
+    L.u.nms = a;
+    L.bytes = 20.0 * a.n;
     return L;
   }
 
@@ -1237,10 +1269,11 @@ struct Builder {
     if (od != b.dims.end()) {
       int64_t n = 1;
       for (int64_t d : od->second) n *= d;
-      if (n == 0 && gr.kind != G_NONZERO) { Launch L; L.group = gr.gid; L.kernel = K_OTHER; L.empty = true; return L; }
+      if (n == 0 && gr.kind != G_NONZERO && gr.kind != G_NMS) { Launch L; L.group = gr.gid; L.kernel = K_OTHER; L.empty = true; return L; }
     }
     switch (gr.kind) {
       case G_NONZERO: return nonzero(gr);
+      case G_NMS: return nms(gr);
       case G_SCATTER: return scatter(gr);
       case G_RANGE: return range(gr);
       case G_FILL: return fill(gr);
@@ -1304,6 +1337,12 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       NonzeroArgs a = L.u.nz;
       a.x = P.at(L.r[0]); a.out = (long long*)P.at(L.r[1]); a.count = (long long*)P.at(L.r[2]);
       return launch_nonzero(a, s);
+    }
+    case K_NMS: {
+      NmsArgs a = L.u.nms;
+      a.scores = (const float*)P.at(L.r[0]); a.boxes = (const float*)P.at(L.r[1]);
+      a.out = (long long*)P.at(L.r[2]); a.count = (long long*)P.at(L.r[3]);
+      return launch_nms(a, s);
     }
     case K_RANGE: {
       RangeArgs a = L.u.range;
@@ -1731,7 +1770,7 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
     const Graph& G = *p.g;
     if (static_ws) {
       if (p.n_switches > 0 || !p.exec_ops.empty())
-        throw Error(SOD2_ERR_UNSUPPORTED, "sod2_run_static: a graph with Switch or NonZero operators reads values back through "
+        throw Error(SOD2_ERR_UNSUPPORTED, "sod2_run_static: a graph with Switch, NonZero or NMS operators reads values back through "
                                           "pinned host memory, which this entry point may not allocate; use sod2_run");
       if (h->profiling)
         throw Error(SOD2_ERR_UNSUPPORTED, "sod2_run_static: launch records need events, which this entry point may not create; "
@@ -1740,8 +1779,15 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
     if (n_weights != (int)G.weight_ids.size() || n_inputs != (int)G.input_ids.size() || n_outputs != (int)G.output_ids.size())
       throw Error(SOD2_ERR_INVALID_ARG, "wrong number of weight, input or output pointers");
     for (int i = 0; i < n_weights; ++i) if (!weights[i]) throw Error(SOD2_ERR_INVALID_ARG, "null weight pointer");
-    for (int i = 0; i < n_inputs; ++i) if (!inputs[i]) throw Error(SOD2_ERR_INVALID_ARG, "null input pointer");
-    for (int i = 0; i < n_outputs; ++i) if (!outputs[i]) throw Error(SOD2_ERR_INVALID_ARG, "null output pointer");
+    auto has_elements = [&](int t) {                   // (a tensor without elements may come with a null pointer)
+      if (!p.rdp->S[t].resolved()) return true;
+      for (const CompiledExpr& x : p.cshape[t]) if (x.eval(h->b.atom_vals) == 0) return false;
+      return true;
+    };
+    for (int i = 0; i < n_inputs; ++i)
+      if (!inputs[i] && has_elements(G.input_ids[i])) throw Error(SOD2_ERR_INVALID_ARG, "null input pointer");
+    for (int i = 0; i < n_outputs; ++i)
+      if (!outputs[i] && has_elements(G.output_ids[i])) throw Error(SOD2_ERR_INVALID_ARG, "null output pointer");
     if ((size_t)h->b.arena_bytes > arena_bytes || (h->b.arena_bytes > 0 && !arena))
       throw Error(SOD2_ERR_ARENA_TOO_SMALL, "arena of " + std::to_string(arena_bytes) + " bytes, plan needs " +
                                                 std::to_string(h->b.arena_bytes));
@@ -1898,20 +1944,22 @@ static sod2_status run_impl(sod2_binding_t* h, void* arena, size_t arena_bytes, 
           }
           h->trace.push_back(sod2_trace_entry{1, it.ref, L.empty ? -1 : L.kernel, L.variant, splits, -1, fold});
         }
-        if (L.kernel == K_NONZERO) {
+        if (L.kernel == K_NONZERO || L.kernel == K_NMS) {
           // the extent is execution determined: read the count back, then size and plan what follows
-          begin_read_back(P.at(L.r[2]), 8, s);
+          const bool is_nms = L.kernel == K_NMS;
+          begin_read_back(P.at(L.r[is_nms ? 3 : 2]), 8, s);
           const long long count = (long long)finish_read_back(s);
           queued = 0;
-          if (count < 0 || count > L.u.nz.n) throw Error(SOD2_ERR_HIP, "NonZero kernel reported an impossible count");
+          if (count < 0 || count > (is_nms ? (long long)L.u.nms.n : L.u.nz.n))
+            throw Error(SOD2_ERR_HIP, "a NonZero or NMS kernel reported an impossible count");
           h->last_exec.push_back(count);
           if (n_nz >= exec_values.size()) {
             exec_values.push_back(count);
             // (also when the count equals the assumed upper bound: with the count known the sub-graphs
             //  that follow are planned together instead of one by one)
-            replan(k, "NonZero");
+            replan(k, is_nms ? "NMS" : "NonZero");
           } else if (exec_values[n_nz] != count) {
-            throw Error(SOD2_ERR_INVALID_ARG, "the binding was planned for a NonZero count of " + std::to_string(exec_values[n_nz]) +
+            throw Error(SOD2_ERR_INVALID_ARG, "the binding was planned for a NonZero / NMS count of " + std::to_string(exec_values[n_nz]) +
                                                   ", the run found " + std::to_string(count));
           }
           ++n_nz;

@@ -391,3 +391,44 @@ def test_averagepool_and_round_kernels(S_lib, dtype, channels, kernel, stride, p
         d = np.abs(q - qr)
         print("  quantised means that differ:", int((d > 1e-6).sum()), "of", d.size, "max", float(d.max()), flush=True)
         assert d.max() <= 0.25 + 1e-6 and np.mean(d > 1e-6) <= 1e-4, (sym, d.max(), np.mean(d > 1e-6))
+
+
+@pytest.mark.parametrize("max_out,iou", [(0, 0.5), (0, 0.3), (10, 0.25)])
+def test_nms_kernel(S_lib, max_out, iou):
+    """Non-maximum suppression on the GPU: the count read back in mid-run, the kept indices (through the two
+    Gathers behind them) bit-exact against the definition, whose overlap test is taken in fp32 on both sides.
+    Integer-corner boxes with tied scores, and arbitrary float boxes; none, one, a few, and the largest number of
+    boxes the kernel takes (several sort passes per thread, a padded sort for sizes that are no power of two)."""
+    import torch
+    from tests.test_shape_ops import _nms_graph, _grid_boxes
+    from paper_2403_00176_amd.session import Session, to_host
+    from oracle import ops as O
+    g, sel = _nms_graph(max_out, iou)
+    po = P.build_plan(g, R.RDP(g).analyse())
+    ses = Session(g)
+    ses.upload_weights({})
+    rs = np.random.RandomState(17)
+    for N, kind in ((0, "grid"), (1, "grid"), (5, "grid"), (100, "grid"), (1000, "float"), (1500, "grid"), (4096, "grid"), (4096, "float")):
+        print(f"case nms max_out={max_out} iou={iou} N={N} {kind}", flush=True)
+        if kind == "grid":
+            scores, boxes = _grid_boxes(rs, N, span=30 + N // 8, side=14)
+        else:
+            c = rs.rand(N, 2) * (20 + N / 16.0)
+            wh = rs.rand(N, 2) * 9 + 0.5
+            boxes = np.concatenate([c - wh / 2, c + wh / 2], axis=1).astype(np.float32).astype(np.float64)
+            scores = rs.rand(N).astype(np.float32).astype(np.float64)
+        ins = {g.tensor_id("scores"): scores, g.tensor_id("boxes"): boxes.reshape(N, 4)}
+        sym = {"N": N}
+        bnd = ses.bind(sym)
+        outs = ses.alloc_outputs(ses.output_shapes(bnd))               # sized for the upper bound
+        ses.run(bnd, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        kept = O.nms(scores, boxes.reshape(N, 4), max_out, iou)
+        assert S_lib.sod2_run_exec_values(bnd) == [len(kept)]
+        assert S_lib.sod2_run_plan_dump(bnd) == A.dump(A.bind(po, sym, exec_values=[len(kept)]))
+        n = len(kept)
+        got_b = to_host(outs[0]).reshape(-1, 4)[:n]
+        got_s = to_host(outs[1]).reshape(-1)[:n]
+        assert np.array_equal(got_b, boxes.reshape(N, 4)[kept]) and np.array_equal(got_s, scores[kept])
+        if N >= 100:
+            assert 0 < n < N

@@ -654,3 +654,92 @@ def test_averagepool_and_round_against_their_definitions_and_structure():
         for sym in ({"N": 1, "H": 1, "W": 1}, {"N": 2, "H": 7, "W": 9}, {"N": 8, "H": 128, "W": 128}):
             assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(pp, sym))
     assert S.sod2_op_kind_class("AveragePool") == "ISDOS" and S.sod2_op_kind_class("Round") == "ISDOS"
+
+
+def _nms_graph(max_out=0, iou=0.5):
+    """Detection post-processing: the kept boxes and their scores, gathered by the indices NMS returns
+    (Table 2 lists NMS with the execution-determined operators)."""
+    b = GraphBuilder([("N", 0, 4096)])
+    sc = b.input("scores", "f32", ["N"])
+    bx = b.input("boxes", "f32", ["N", 4])
+    sel = b.op("NMS", [sc, bx], dtype="i64", max_out=max_out, iou=iou, hint="sel")
+    b.mark_output(b.op("Gather", [bx, sel], axis=0), "kept_boxes")
+    b.mark_output(b.op("Gather", [sc, sel], axis=0), "kept_scores")
+    return b.build(), sel
+
+
+def _grid_boxes(rs, n, span=40, side=12):
+    """Boxes with integer corners (areas, intersections and the products with a dyadic threshold are exact in
+    every precision) clustered so that many overlap; scores with ties."""
+    x1 = rs.randint(0, span, n)
+    y1 = rs.randint(0, span, n)
+    boxes = np.stack([x1, y1, x1 + rs.randint(1, side, n), y1 + rs.randint(1, side, n)], axis=1).astype(np.float64)
+    scores = rs.randint(0, max(n // 2, 2), n) / 64.0
+    return scores, boxes
+
+
+def _iou64(a, b_):
+    iw = max(0.0, min(a[2], b_[2]) - max(a[0], b_[0]))
+    ih = max(0.0, min(a[3], b_[3]) - max(a[1], b_[1]))
+    inter = iw * ih
+    return inter / ((a[2] - a[0]) * (a[3] - a[1]) + (b_[2] - b_[0]) * (b_[3] - b_[1]) - inter)
+
+
+def test_nms_against_its_definition_and_structure():
+    # hand-made: A and B overlap by 2 / 6, C is far away
+    boxes = np.array([[0, 0, 2, 2], [1, 0, 3, 2], [10, 10, 12, 12]], dtype=np.float64)
+    scores = np.array([0.9, 0.8, 0.7])
+    assert O.nms(scores, boxes, 0, 0.3).tolist() == [0, 2]
+    assert O.nms(scores, boxes, 0, 0.4).tolist() == [0, 1, 2]
+    assert O.nms(scores[::-1].copy(), boxes, 0, 0.3).tolist() == [2, 1]          # visiting order follows the scores
+    assert O.nms(scores, boxes, 1, 0.4).tolist() == [0] and O.nms(scores, boxes, 2, 0.4).tolist() == [0, 1]
+    # the comparison is strict: an overlap of exactly the threshold survives (1 / 2 here), one just above does not
+    half = np.array([[0, 0, 2, 1], [0, 0, 1, 1]], dtype=np.float64)
+    assert O.nms(np.array([1.0, 0.5]), half, 0, 0.5).tolist() == [0, 1]
+    assert O.nms(np.array([1.0, 0.5]), half, 0, 0.49).tolist() == [0]
+    # equal scores: the lower index first (and -0 is the same score as +0); a box never suppresses itself
+    same = np.array([[0, 0, 4, 4], [0, 0, 4, 4], [0, 0, 4, 4]], dtype=np.float64)
+    assert O.nms(np.array([0.5, 0.5, 0.5]), same, 0, 0.5).tolist() == [0]
+    assert O.nms(np.array([0.0, -0.0, 0.0]), np.array([[0, 0, 1, 1], [5, 5, 6, 6], [9, 9, 10, 10]], dtype=np.float64), 0, 0.5).tolist() == [0, 1, 2]
+    assert O.nms(np.zeros(0), np.zeros((0, 4)), 0, 0.5).tolist() == []
+    # degenerate boxes (zero area) have no overlap with anything: all kept
+    assert O.nms(np.array([3.0, 2.0, 1.0]), np.array([[1, 1, 1, 5], [1, 1, 1, 5], [0, 0, 9, 9]], dtype=np.float64), 0, 0.1).tolist() == [0, 1, 2]
+    # what fixes the result without naming the procedure: kept boxes in visiting order, no two of them overlap by
+    # more than the threshold, and every dropped box overlaps a kept one visited before it
+    rs = np.random.RandomState(21)
+    for n, thr in ((40, 0.5), (300, 0.25), (300, 0.5), (1000, 0.125)):
+        scores, boxes = _grid_boxes(rs, n)
+        kept = O.nms(scores, boxes, 0, thr).tolist()
+        rank = {int(i): r for r, i in enumerate(np.argsort(-scores, kind="stable"))}
+        assert [rank[i] for i in kept] == sorted(rank[i] for i in kept) and len(set(kept)) == len(kept)
+        for a_ in range(len(kept)):
+            for c_ in range(a_):
+                assert _iou64(boxes[kept[a_]], boxes[kept[c_]]) <= thr
+        ks = set(kept)
+        for i in range(n):
+            if i not in ks:
+                assert any(rank[j] < rank[i] and _iou64(boxes[i], boxes[j]) > thr for j in kept), i
+        assert 0 < len(kept) < n
+        lim = O.nms(scores, boxes, 7, thr).tolist()
+        assert lim == kept[:7]
+
+    g, sel = _nms_graph()
+    assert R.OP_CLASS["NMS"] == "EDO" and S.sod2_op_kind_class("NMS") == "EDO"
+    r = R.RDP(g).analyse()
+    assert r.S[sel] == R.NAC                               # Alg. 1 as printed: an EDO's output is nac
+    po = P.build_plan(g, r)
+    assert R.fmt_list(po.rdp.S[sel]) == "[s:@nz0]" and po.exec_ops == [0]   # named: a vector whose length is found by running
+    assert [gr.kind for gr in po.groups.values()] == ["NMS", "GATHER", "GATHER"]
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    lp = S.sod2_plan(lg, lr)
+    assert S.sod2_rdp_dump(lr) == R.dump(r) and S.sod2_plan_dump(lp) == P.dump(po)
+    for sym, ev in (({"N": 100}, ()), ({"N": 100}, [0]), ({"N": 100}, [37]), ({"N": 100}, [100]), ({"N": 1}, [1]), ({"N": 4096}, ()), ({"N": 0}, ())):
+        assert S.sod2_binding_dump(S.sod2_bind(lp, sym, exec_values=list(ev))) == A.dump(A.bind(po, sym, exec_values=list(ev))), (sym, ev)
+    assert "exec @nz0=100 bound" in S.sod2_binding_dump(S.sod2_bind(lp, {"N": 100}))
+    with pytest.raises(S.Sod2Error):
+        S.sod2_bind(lp, {"N": 100}, exec_values=[101])
+    scores, boxes = _grid_boxes(np.random.RandomState(3), 50)
+    out = execute.run(g, po.order, {}, {g.tensor_id("scores"): scores, g.tensor_id("boxes"): boxes})
+    kept = O.nms(scores, boxes, 0, 0.5)
+    assert out.exec_values == [len(kept)] and np.array_equal(out.values[g.tensor_id("kept_boxes")], boxes[kept])

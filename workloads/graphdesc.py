@@ -45,6 +45,7 @@ OP_ATTRS: Dict[str, Tuple[str, ...]] = {
     "ArgMax": (),
     "CacheAppend": (),
     "NonZero": (),
+    "NMS": ("max_out",),      # inputs scores [N], boxes [N, 4] (x1, y1, x2, y2), both f32; float attr iou; result: kept box indices, i64
     "Switch": (),             # float attr threshold
     "Combine": (),
     "Range": (),              # inputs start, limit, delta (one-element int tensors)
