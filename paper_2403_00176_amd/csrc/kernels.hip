@@ -904,8 +904,146 @@ __global__ __launch_bounds__(NMS_THREADS) void nms_kernel(NmsArgs a) {
   if (tid == 0) *a.count = count;
 }
 
+// The same result from three kernels, for many boxes and a workspace to hold the suppression matrix: the pair tests
+// are spread over the chip instead of running on one CU.  Workspace: the boxes in visiting order, their indices, and
+// the matrix as 64 x 64-bit tiles, tile (rb, cb) = which of the 64 boxes of column block cb each box of row block rb
+// suppresses (only cb >= rb is written and read).
+constexpr long long NMS_WS_BOX = 0, NMS_WS_IDX = 64 << 10, NMS_WS_MASK = 128 << 10;
+constexpr long long NMS_WS_BYTES = NMS_WS_MASK + (long long)NMS_MAX_BOXES * (NMS_MAX_BOXES / 64) * 8;
+static_assert(NMS_WS_BYTES <= WS_BYTES, "the suppression matrix must fit the workspace");
+
+__global__ __launch_bounds__(NMS_THREADS) void nms_sort_kernel(NmsArgs a) {
+  __shared__ unsigned long long key[NMS_MAX_BOXES];
+  const int tid = threadIdx.x;
+  int P = 1;
+  while (P < a.n) P <<= 1;
+  for (int i = tid; i < P; i += NMS_THREADS) {
+    unsigned long long k = ~0ull;
+    if (i < a.n) {
+      unsigned u = __float_as_uint(a.scores[i] + 0.f);
+      u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+      k = ((unsigned long long)(~u) << 32) | (unsigned)i;
+    }
+    key[i] = k;
+  }
+  __syncthreads();
+  for (int size = 2; size <= P; size <<= 1)
+    for (int stride = size >> 1; stride > 0; stride >>= 1) {
+      for (int t = tid; t < P / 2; t += NMS_THREADS) {
+        const int lo = 2 * t - (t & (stride - 1)), hi = lo + stride;
+        const bool up = (lo & size) == 0;
+        const unsigned long long x = key[lo], y = key[hi];
+        if ((x > y) == up) { key[lo] = y; key[hi] = x; }
+      }
+      __syncthreads();
+    }
+  float4* sbox = (float4*)(a.ws + NMS_WS_BOX);
+  unsigned* sidx = (unsigned*)(a.ws + NMS_WS_IDX);
+  for (int i = tid; i < a.n; i += NMS_THREADS) {
+    const unsigned id = (unsigned)key[i];
+    sbox[i] = *(const float4*)(a.boxes + 4ll * id);
+    sidx[i] = id;
+  }
+}
+
+// grid (column block, row block), 64 threads: thread t owns row rb * 64 + t of the tile
+__global__ __launch_bounds__(64) void nms_mask_kernel(NmsArgs a) {
+  __shared__ float4 cbox[64];
+  const int cb = blockIdx.x, rb = blockIdx.y, t = threadIdx.x;
+  if (cb < rb) return;
+  const float4* sbox = (const float4*)(a.ws + NMS_WS_BOX);
+  const int W = (a.n + 63) >> 6;
+  const int i = rb * 64 + t, jc = cb * 64 + t;
+  cbox[t] = jc < a.n ? sbox[jc] : make_float4(0.f, 0.f, 0.f, 0.f);
+  __syncthreads();
+  unsigned long long word = 0;
+  if (i < a.n) {
+    const float4 bi = sbox[i];
+    const int c_end = min(64, a.n - cb * 64);
+    for (int c = 0; c < c_end; ++c)
+      if (cb * 64 + c > i && nms_overlaps(bi, cbox[c], a.iou)) word |= 1ull << c;
+  }
+  ((unsigned long long*)(a.ws + NMS_WS_MASK))[((long long)rb * W + cb) * 64 + t] = word;
+}
+
+// One workgroup of 4 waves walks the blocks in order.  `dead` (wave 0, lane w = column block w) collects the boxes
+// suppressed so far; for a block, wave 0 holds its 64 matrix rows in registers (lane w: the words of column block w),
+// decides which boxes of the block are kept with scalar operations (only the block's own columns matter for that)
+// and then ORs the kept rows into `dead`; meanwhile every thread already holds its share of the next block's rows.
+// A block costs about 4 us, the ~2000 instructions one wave executes for it (fetching two blocks ahead changes nothing).
+constexpr int NMS_SCAN_THREADS = 256;
+__global__ __launch_bounds__(NMS_SCAN_THREADS) void nms_scan_kernel(NmsArgs a) {
+  __shared__ unsigned long long rows[64][65];          // [row of the block][column block], padded against bank conflicts
+  __shared__ int stop;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int W = (a.n + 63) >> 6;
+  const unsigned long long* mask = (const unsigned long long*)(a.ws + NMS_WS_MASK);
+  const unsigned* sidx = (const unsigned*)(a.ws + NMS_WS_IDX);
+  constexpr int PT = 64 * 64 / NMS_SCAN_THREADS;       // words of a block's rows per thread
+  unsigned long long nxt[PT];
+  auto fetch = [&](int b) {                            // tile (b, cb), word r  ->  element e = cb * 64 + r of the block
+#pragma unroll
+    for (int u = 0; u < PT; ++u) {
+      const int e = tid + u * NMS_SCAN_THREADS, cb = e >> 6;
+      nxt[u] = (cb >= b && cb < W) ? mask[((long long)b * W + cb) * 64 + (e & 63)] : 0ull;
+    }
+  };
+  if (tid == 0) stop = 0;
+  unsigned long long dead = 0;
+  int count = 0;
+  if (W > 0) fetch(0);
+  for (int b = 0; b < W; ++b) {
+#pragma unroll
+    for (int u = 0; u < PT; ++u) {
+      const int e = tid + u * NMS_SCAN_THREADS;
+      rows[e & 63][e >> 6] = nxt[u];
+    }
+    __syncthreads();
+    if (b + 1 < W) fetch(b + 1);
+    if (wave == 0) {
+      const int nb = min(64, a.n - b * 64);
+      unsigned long long row[64];
+#pragma unroll
+      for (int r = 0; r < 64; ++r) row[r] = rows[r][lane];
+      // the serial part runs on scalars: lane r's word of the block's own columns, and the block's word of `dead`
+      const unsigned long long own = rows[lane][b];
+      const int olo = (int)(unsigned)own, ohi = (int)(unsigned)(own >> 32);
+      unsigned long long cur = (unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)dead, b) |
+                               ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(dead >> 32), b) << 32);
+      unsigned long long kept = 0;
+      int cnt = count;
+#pragma unroll
+      for (int r = 0; r < 64; ++r) {
+        const unsigned long long w = (unsigned long long)(unsigned)__builtin_amdgcn_readlane(olo, r) |
+                                     ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(ohi, r) << 32);
+        if (r < nb && !((cur >> r) & 1) && !(a.max_out > 0 && cnt >= a.max_out)) {
+          kept |= 1ull << r;
+          ++cnt;
+          cur |= w;
+        }
+      }
+#pragma unroll
+      for (int r = 0; r < 64; ++r)
+        if ((kept >> r) & 1) dead |= row[r];           // (the same branch in every lane)
+      if ((kept >> lane) & 1) a.out[count + __popcll(kept & ((1ull << lane) - 1))] = (long long)sidx[b * 64 + lane];
+      count = cnt;
+      if (lane == 0 && a.max_out > 0 && count >= a.max_out) stop = 1;
+    }
+    __syncthreads();
+    if (stop) break;
+  }
+  if (tid == 0) *a.count = count;
+}
+
 hipError_t launch_nms(const NmsArgs& a, hipStream_t s) {
   if (a.n < 0 || a.n > NMS_MAX_BOXES) return hipErrorInvalidValue;
+  if (a.ws && a.n > 512) {
+    const int W = (a.n + 63) / 64;
+    hipLaunchKernelGGL(nms_sort_kernel, dim3(1), dim3(NMS_THREADS), 0, s, a);
+    hipLaunchKernelGGL(nms_mask_kernel, dim3(W, W), dim3(64), 0, s, a);
+    hipLaunchKernelGGL(nms_scan_kernel, dim3(1), dim3(NMS_SCAN_THREADS), 0, s, a);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(nms_kernel, dim3(1), dim3(NMS_THREADS), 0, s, a);
   return hipGetLastError();
 }

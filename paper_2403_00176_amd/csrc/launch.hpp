@@ -168,6 +168,7 @@ struct NmsArgs {
   const float* scores; const float* boxes; long long* out; long long* count;
   int n, max_out;
   float iou;
+  char* ws;                  // the workspace (WS_BYTES) or null: with it, many boxes go through three kernels
 };
 
 // out = x with the rows idx[j] replaced by y[j] (j < n; the last j wins on duplicates); rows of

@@ -1342,6 +1342,7 @@ hipError_t dispatch(Launch L, const Pointers& P, hipStream_t s) {
       NmsArgs a = L.u.nms;
       a.scores = (const float*)P.at(L.r[0]); a.boxes = (const float*)P.at(L.r[1]);
       a.out = (long long*)P.at(L.r[2]); a.count = (long long*)P.at(L.r[3]);
+      a.ws = P.ws;
       return launch_nms(a, s);
     }
     case K_RANGE: {

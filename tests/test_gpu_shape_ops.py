@@ -432,3 +432,14 @@ def test_nms_kernel(S_lib, max_out, iou):
         assert np.array_equal(got_b, boxes.reshape(N, 4)[kept]) and np.array_equal(got_s, scores[kept])
         if N >= 100:
             assert 0 < n < N
+        if N > 512:
+            # with a workspace behind the arena (Session hands one over) that many boxes take the three-kernel path;
+            # without one the single workgroup does all of it: the same indices
+            outs2 = ses.alloc_outputs(ses.output_shapes(bnd))
+            bnd2 = ses.bind(sym)
+            arena = torch.empty(S_lib.sod2_binding_arena_bytes(bnd2)[0], dtype=torch.uint8, device="cuda")
+            S_lib.sod2_run(bnd2, arena.data_ptr(), arena.numel(), [], [x.data_ptr() for x in ses.upload_inputs(ins)],
+                           [x.data_ptr() for x in outs2], ses.stream.cuda_stream)
+            torch.cuda.synchronize()
+            assert S_lib.sod2_run_exec_values(bnd2) == [n]
+            assert np.array_equal(to_host(outs2[0]).reshape(-1, 4)[:n], got_b) and np.array_equal(to_host(outs2[1]).reshape(-1)[:n], got_s)
