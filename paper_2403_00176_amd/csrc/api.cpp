@@ -37,6 +37,52 @@ extern "C" {
 const char* sod2_last_error(void) { return g_err.c_str(); }
 const char* sod2_version(void) { return "sod2-mi355x 0.1 (gfx950)"; }
 
+// integer attributes that every later stage indexes or divides by: refused here, once
+static void check_attrs(const Op& op) {
+  auto bad = [&](const char* what) { throw Error(SOD2_ERR_INVALID_ARG, std::string(op_name(op.kind)) + ": " + what); };
+  const std::vector<int64_t>& a = op.ia;
+  switch (op.kind) {
+    case SOD2_OP_TRANSPOSE: {
+      std::vector<char> seen(a.size(), 0);
+      for (int64_t p : a) {
+        if (p < 0 || p >= (int64_t)a.size() || seen[p]) bad("the attribute must be a permutation of 0 .. rank-1");
+        seen[p] = 1;
+      }
+      if (a.empty() || a.size() > SOD2_MAX_RANK) bad("a permutation of 1 .. SOD2_MAX_RANK axes");
+      break;
+    }
+    case SOD2_OP_CONV:
+      if (a.size() != 2 || a[0] < 1 || a[0] > 64 || a[1] < 0 || a[1] > 64) bad("attributes stride (1 .. 64) and pad (0 .. 64)");
+      break;
+    case SOD2_OP_MAXPOOL: case SOD2_OP_AVERAGEPOOL:
+      if (a.size() != 3 || a[0] < 1 || a[0] > 64 || a[1] < 1 || a[1] > 64 || a[2] < 0 || a[2] >= a[0])
+        bad("attributes kernel (1 .. 64), stride (1 .. 64) and pad (0 .. kernel-1)");
+      break;
+    case SOD2_OP_GATHER: case SOD2_OP_CONCAT:
+      if (a.size() != 1 || a[0] < -SOD2_MAX_RANK || a[0] >= SOD2_MAX_RANK) bad("one axis attribute");
+      break;
+    case SOD2_OP_MATMUL: case SOD2_OP_SOFTMAX:
+      if (a.size() > 1 || (a.size() == 1 && a[0] != 0 && a[0] != 1)) bad("the attribute is 0 or 1");
+      break;
+    case SOD2_OP_REDUCEMEAN:
+      if (a.size() < 2 || a.size() > 1 + SOD2_MAX_RANK || (a[0] != 0 && a[0] != 1)) bad("attributes keepdims (0 or 1), then the axes");
+      for (size_t i = 1; i < a.size(); ++i) if (a[i] < -SOD2_MAX_RANK || a[i] >= SOD2_MAX_RANK) bad("axis out of range");
+      break;
+    case SOD2_OP_GROUPNORM:
+      if (a.size() != 1 || a[0] < 1) bad("the number of groups must be positive");
+      break;
+    case SOD2_OP_NMS:
+      if (a.size() > 1 || (a.size() == 1 && (a[0] < 0 || a[0] > 0x7fffffff))) bad("max_out must not be negative");
+      if (!(op.fa >= 0.0 && op.fa <= 1.0)) bad("the overlap threshold lies in [0, 1]");
+      break;
+    case SOD2_OP_LAYERNORM:
+      if (!(op.fa >= 0.0)) bad("epsilon must not be negative");
+      break;
+    default: break;
+  }
+  if (op.in.size() > 64 || op.out.size() > 8) bad("too many inputs or outputs");
+}
+
 sod2_status sod2_graph_build(const sod2_graph_desc* d, sod2_graph_t** out) {
   SOD2_TRY
   if (!d || !out) throw Error(SOD2_ERR_INVALID_ARG, "null argument");
@@ -99,6 +145,7 @@ sod2_status sod2_graph_build(const sod2_graph_desc* d, sod2_graph_t** out) {
       throw Error(SOD2_ERR_INVALID_ARG, std::string("wrong input count for ") + op_name(op.kind));
     if (op.out.empty() || ((op.kind == SOD2_OP_SWITCH || op.kind == SOD2_OP_TOPK) && op.out.size() != 2))
       throw Error(SOD2_ERR_INVALID_ARG, std::string("wrong output count for ") + op_name(op.kind));
+    check_attrs(op);
     g.ops.push_back(op);
   }
   g.finish();

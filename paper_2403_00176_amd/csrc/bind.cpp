@@ -26,6 +26,9 @@
 #include "internal.hpp"
 
 namespace sod2 {
+
+static const int64_t kMaxTensorBytes = (int64_t)1 << 44;   // far beyond any device memory; keeps the byte arithmetic in range
+
 namespace {
 bool intersects(const ArenaTensor& a, const ArenaTensor& b) { return a.start <= b.end && b.start <= a.end; }
 
@@ -184,7 +187,13 @@ BindResult bind_plan(const Plan& p, const std::vector<int64_t>& symbols, const s
         {
           DimList& dims = b.dims[t];
           dims.n = 0;
-          for (const CompiledExpr& d : p.cshape[t]) { dims.push_back(d.eval(b.atom_vals)); n *= dims.back(); }
+          for (const CompiledExpr& d : p.cshape[t]) {
+            dims.push_back(d.eval(b.atom_vals));
+            // (a window larger than its input, symbols at extreme values: refuse instead of planning with garbage)
+            if (dims.back() < 0 || (dims.back() > 0 && n > kMaxTensorBytes / dims.back()))
+              throw Error(SOD2_ERR_SHAPE_MISMATCH, "extent of " + G.tensors[t].name + " at the bound symbols is negative or the tensor exceeds 2^44 bytes");
+            n *= dims.back();
+          }
         }
         if (gr.versions > 1) {
           // Section 4.2: of the code versions of a fused group with unproven broadcast pairs, the one that holds for

@@ -66,6 +66,16 @@ void Graph::finish() {
   for (const Op& op : ops)
     if (op.kind == SOD2_OP_CACHEAPPEND && !tensors[op.in[0]].session)
       throw Error(SOD2_ERR_UNSUPPORTED, "CacheAppend must extend a session tensor");
+  // the operators must form a directed acyclic graph: in the node order every input is produced earlier
+  std::vector<int> order = sorted_nodes();
+  std::vector<int> pos(ops.size(), -1);
+  for (size_t i = 0; i < order.size(); ++i) pos[order[i]] = (int)i;
+  for (size_t i = 0; i < ops.size(); ++i) {
+    if (pos[i] < 0) throw Error(SOD2_ERR_INVALID_ARG, "operator unreachable from the graph inputs (or on a cycle)");
+    for (int t : ops[i].in)
+      if (producer[t] >= 0 && pos[producer[t]] >= pos[i])
+        throw Error(SOD2_ERR_INVALID_ARG, "the graph has a cycle through " + tensors[t].name);
+  }
 }
 
 std::vector<int> Graph::sorted_nodes() const {
@@ -143,7 +153,11 @@ std::vector<LV> bcast(std::vector<LV> a, std::vector<LV> b) {
 LV window(const LV& d, int64_t k, int64_t stride, int64_t pad) {   // floor((d + 2p - k)/s) + 1
   return add(fdiv(add(d, LV::c(2 * pad - k)), stride), LV::c(1));
 }
-int64_t norm_axis(int64_t a, size_t rank) { int64_t r = (int64_t)rank; return ((a % r) + r) % r; }
+int64_t norm_axis(int64_t a, size_t rank) {         // an axis or an index in [-rank, rank)
+  int64_t r = (int64_t)rank;
+  if (a < -r || a >= r) throw Error(SOD2_ERR_SHAPE_MISMATCH, "axis or index " + std::to_string(a) + " outside a rank or length of " + std::to_string(r));
+  return a < 0 ? a + r : a;
+}
 
 struct Out { bool ready = false; LS s, v; };     // result of one forward transfer
 }  // namespace

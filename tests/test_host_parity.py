@@ -286,3 +286,111 @@ def test_derived_constants_layout_and_argument_checks():
         S.sod2_plan_prepare_constants(p, [0x1000] * n_w, 0x1000, want - 256)   # buffer too small
     with pytest.raises(S.Sod2Error):
         S.sod2_plan_prepare_constants(p, [0x1000] * n_w, 0x1010, want)         # buffer misaligned
+
+
+def test_malformed_graphs_are_refused_not_crashed():
+    """Descriptors a caller could get wrong are turned into errors at graph build: a cycle (also one through an
+    operator that is only a view), a Transpose whose attribute is no permutation, pooling and convolution windows
+    that later stages would divide by, an axis outside the rank.  Then a seeded batch of random corruptions of real
+    graphs (attributes, ids, types, ranks, roles, dropped operators): each must end in an error or in a plan."""
+    import copy
+    import random
+    w = small(2)
+
+    def build(g):
+        h = S.sod2_graph_build(g)
+        p = S.sod2_plan(h, S.sod2_rdp_infer(h))
+        return S.sod2_bind(p, {"B": 2, "L": 40})
+
+    def mutated(f):
+        g = copy.deepcopy(w.graph)
+        f(g)
+        return g
+
+    def first(g, kind):
+        return next(op for op in g.ops if op.kind == kind)
+
+    def self_loop(g):
+        op = first(g, "Reshape")
+        op.inputs[0] = op.outputs[0]
+
+    def two_cycle(g):
+        a, b = [op for op in g.ops if op.kind == "Add"][:2]
+        a.inputs[0], b.inputs[0] = b.outputs[0], a.outputs[0]
+
+    cases = {
+        "cycle": [self_loop, two_cycle],
+        "permutation": [lambda g: first(g, "Transpose").attrs.update(perm=(7, -5, 9, 8, 1)),
+                        lambda g: first(g, "Transpose").attrs.update(perm=(0, 0, 1, 2, 3))],
+        "axis": [lambda g: first(g, "Concat").attrs.update(axis=5),
+                 lambda g: first(g, "Gather").inputs.reverse()],
+    }
+    for what, fs in cases.items():
+        for f in fs:
+            with pytest.raises(S.Sod2Error) as e:
+                build(mutated(f))
+            assert e.value.code in (-1, -3), (what, str(e.value))
+    w3 = small(3)
+    for attrs in (dict(kernel=0, stride=2, pad=0), dict(kernel=3, stride=0, pad=1), dict(kernel=3, stride=2, pad=3)):
+        g = copy.deepcopy(w3.graph)
+        first(g, "MaxPool").attrs.update(attrs)
+        with pytest.raises(S.Sod2Error):
+            S.sod2_graph_build(g)
+    g = copy.deepcopy(w3.graph)
+    first(g, "Conv").attrs.update(stride=0)
+    with pytest.raises(S.Sod2Error):
+        S.sod2_graph_build(g)
+
+    # extents at the bound symbols: a window larger than its input gives an empty or a negative extent (the latter is
+    # refused), a tensor beyond 2^44 bytes is refused before any byte count can overflow
+    gb = GraphBuilder([("H", 1, 2 ** 40)])
+    x = gb.input("x", "f32", [1, "H", "H", 8])
+    gb.mark_output(gb.op("MaxPool", [x], kernel=5, stride=1, pad=0), "y")
+    hg = S.sod2_graph_build(gb.build())
+    hp = S.sod2_plan(hg, S.sod2_rdp_infer(hg))
+    assert S.sod2_binding_arena_bytes(S.sod2_bind(hp, {"H": 4}))[0] == 0       # nothing to compute
+    for H in (2, 2 ** 20, 2 ** 31, 2 ** 40):
+        with pytest.raises(S.Sod2Error) as e:
+            S.sod2_bind(hp, {"H": H})
+        assert e.value.code == -3
+
+    rnd = random.Random(2024)
+    outcomes = {"refused": 0, "planned": 0}
+    for trial in range(120):
+        g = copy.deepcopy((w, w3)[trial % 2].graph)
+        for _ in range(rnd.randint(1, 3)):
+            op = rnd.choice(g.ops)
+            m = rnd.randint(0, 7)
+            if m == 0 and op.attrs:
+                k = rnd.choice(sorted(op.attrs))
+                v = op.attrs[k]
+                op.attrs[k] = [rnd.randint(-9, 9) for _ in v] if isinstance(v, (list, tuple)) else \
+                    (rnd.choice([0.0, -1.0, 1e30]) if isinstance(v, float) else rnd.choice([-3, -1, 0, 1, 7, 1000, 2 ** 31]))
+            elif m == 1:
+                rnd.choice(g.tensors).dtype = rnd.choice(["f32", "bf16", "i64", "i32"])
+            elif m == 2:
+                t = rnd.choice([t for t in g.tensors if t.dims])
+                t.dims = list(t.dims) + [3] if rnd.random() < 0.5 else list(t.dims)[:-1]
+            elif m == 3 and len(op.inputs) >= 2:
+                op.inputs[0], op.inputs[1] = op.inputs[1], op.inputs[0]
+            elif m == 4:
+                op.inputs[rnd.randrange(len(op.inputs))] = rnd.randrange(len(g.tensors))
+            elif m == 5:
+                t = rnd.choice([t for t in g.tensors if t.dims])
+                t.dims = list(t.dims)
+                t.dims[rnd.randrange(len(t.dims))] = rnd.choice([0, 1, 7, "B", "L", "B+L", 2 ** 40])
+            elif m == 6:
+                g.ops.remove(op)
+            else:
+                op.outputs = list(op.outputs) + [rnd.randrange(len(g.tensors))]
+        try:
+            h = S.sod2_graph_build(g)
+            p = S.sod2_plan(h, S.sod2_rdp_infer(h))
+            b = S.sod2_bind(p, {name: min(hi, lo + 7) for name, lo, hi in g.symbols})
+            S.sod2_binding_dump(b)
+            outcomes["planned"] += 1
+        except S.Sod2Error:
+            outcomes["refused"] += 1
+        except (KeyError, TypeError, ValueError, OverflowError):
+            outcomes["refused"] += 1          # stopped by the binding's own marshalling
+    assert outcomes["refused"] > 40 and outcomes["planned"] > 0, outcomes
