@@ -170,6 +170,12 @@ struct Builder {
     for (const CompiledExpr& x : p.cshape[t]) d.push_back(x.eval(b.atom_vals));
     return d;
   }
+  // a per-column parameter (bias, LayerNorm scale / shift): a dense vector of exactly n elements
+  void need_vector(int t, int64_t n, const char* what) {
+    const View& v = view_of(t);
+    if (!v.contiguous() || v.numel() != n)
+      throw Error(SOD2_ERR_SHAPE_MISMATCH, std::string(what) + " " + G.tensors[t].name + " must be a dense vector of " + std::to_string(n) + " elements");
+  }
   bool live(int t) const {
     int pr = G.producer[t];
     return pr < 0 || p.folded[pr] || b.dyn_base[t] >= 0;
@@ -431,7 +437,7 @@ struct Builder {
     L.r[0] = ref_of(va, dt);
     L.r[1] = ref_of(vb, dt);
     L.r[2] = ref_t(gr.out);
-    if (e.bias >= 0) L.r[3] = ref_t(e.bias);
+    if (e.bias >= 0) { need_vector(e.bias, g.N, "bias"); L.r[3] = ref_t(e.bias); }
     if (e.res >= 0) L.r[4] = ref_of(view_of(e.res), dt);
     int64_t batch = (int64_t)g.nb0 * g.nb1;
     L.variant = pick_variant(dt, g.M, g.N, g.K, batch);
@@ -444,6 +450,8 @@ struct Builder {
       if (g.a_sk != 1 || g.K % 64 != 0 || g.K > 1024 || (g.M > 1 && g.a_sm % 8 != 0) || !tb || g.b_sk != 1)
         throw Error(SOD2_ERR_UNSUPPORTED, "LayerNorm prologue needs dense k-contiguous operands and K a multiple of 64 up to 1024");
       if (g.M > 8 || batch != 1) throw Error(SOD2_ERR_UNSUPPORTED, "LayerNorm prologue is for at most 8 rows");
+      need_vector(ln->in[1], g.K, "LayerNorm scale");
+      need_vector(ln->in[2], g.K, "LayerNorm shift");
       L.r[5] = ref_t(ln->in[1]);
       L.r[6] = ref_t(ln->in[2]);
       g.ln_eps = (float)ln->fa;
@@ -519,6 +527,8 @@ struct Builder {
       a.eps = (float)ln.fa;
       L.post = a;
       L.post_ln = true;
+      need_vector(ln.in[1], a.cols, "LayerNorm scale");
+      need_vector(ln.in[2], a.cols, "LayerNorm shift");
       L.r[7] = ref_t(y);
       L.r[8] = ref_t(ln.in[1]);
       L.r[9] = ref_t(ln.in[2]);
@@ -559,7 +569,7 @@ struct Builder {
     L.r[0] = ref_of(vx, dt);
     L.r[1] = ref_of(vw, dt);
     L.r[2] = ref_t(gr.out);
-    if (e.bias >= 0) L.r[3] = ref_t(e.bias);
+    if (e.bias >= 0) { need_vector(e.bias, c.O, "bias"); L.r[3] = ref_t(e.bias); }
     if (e.res >= 0) {
       const View& vr = view_of(e.res);
       if (!vr.contiguous() || vr.dims != od) throw Error(SOD2_ERR_UNSUPPORTED, "Conv residual must be contiguous and of the output shape");
@@ -611,6 +621,8 @@ struct Builder {
     L.r[0] = ref_of(vx, dt);
     L.r[1] = ref_t(gr.out);
     if (layernorm) {
+      need_vector(op.in[1], a.cols, "LayerNorm scale");
+      need_vector(op.in[2], a.cols, "LayerNorm shift");
       L.r[2] = ref_t(op.in[1]);
       L.r[3] = ref_t(op.in[2]);
     } else {
@@ -1270,6 +1282,24 @@ struct Builder {
       int64_t n = 1;
       for (int64_t d : od->second) n *= d;
       if (n == 0 && gr.kind != G_NONZERO && gr.kind != G_NMS) { Launch L; L.group = gr.gid; L.kernel = K_OTHER; L.empty = true; return L; }
+    }
+    // The kernels of these groups read every float operand in the group's one storage type: a description that
+    // mixes types there would make them read beyond a buffer, so it is refused here (host constants are not read
+    // by kernels; elementwise chains, Cast, ReduceMean and the generators convert per operand).
+    switch (gr.kind) {
+      case G_GEMM: case G_CONV: case G_LAYERNORM: case G_SOFTMAX: case G_GROUPNORM: case G_ATTENTION: case G_MAXPOOL:
+      case G_AVGPOOL: case G_CACHEAPPEND: case G_SCATTER: case G_CONCAT: case G_RESIZE: case G_MAXUNPOOL: case G_GATHER: {
+        const int dt = G.tensors[gr.out].dtype;
+        for (int n : gr.ops)
+          for (int t : G.ops[n].in) {
+            const Tensor& td = G.tensors[t];
+            if (!td.has_data && !is_int(td.dtype) && td.dtype != dt)
+              throw Error(SOD2_ERR_UNSUPPORTED, std::string(group_kind_name(gr.kind)) + " group: operand " + td.name +
+                                                    " is not of the result's float type");
+          }
+        break;
+      }
+      default: break;
     }
     switch (gr.kind) {
       case G_NONZERO: return nonzero(gr);

@@ -491,3 +491,39 @@ def test_config4_full_depth(S):
         assert S.sod2_run_plan_dump(b) == A.dump(A.bind(po, sym, ref.decisions))
         assert rel_err(got, ref.values[w.graph.outputs()[0]]) <= TOL["bf16"]
     print(f"calls whose free-running decisions left the oracle's on a near-threshold gate value: {flipped} of 2", flush=True)
+
+
+def test_mistyped_operands_are_refused_before_any_launch(S):
+    """Descriptions that plan but that the kernels would read beyond a buffer for -- a LayerNorm scale of another
+    float type or of the wrong length, a bias of another type -- end in an error when the launches are prepared;
+    no kernel of such a group runs."""
+    import torch
+    from workloads import GraphBuilder, rng
+    from paper_2403_00176_amd.session import Session
+
+    def run(build, weights):
+        b = GraphBuilder([("M", 1, 64)])
+        x = b.input("x", "bf16", ["M", 128])
+        b.mark_output(build(b, x), "y")
+        g = b.build()
+        ses = Session(g)
+        ses.upload_weights({g.tensor_id(n): rng.normal(1, s) for n, s in weights.items()})
+        bnd = ses.bind({"M": 8})
+        outs = ses.alloc_outputs(ses.output_shapes(bnd))
+        ses.run(bnd, ses.upload_inputs({g.tensor_id("x"): rng.normal(2, (8, 128))}), outs)
+        torch.cuda.synchronize()
+
+    run(lambda b, x: b.op("LayerNorm", [x, b.weight("g", "bf16", [128]), b.weight("be", "bf16", [128])], eps=1e-5),
+        {"g": (128,), "be": (128,)})                                  # the well-formed case runs
+    with pytest.raises(S.Sod2Error) as e:
+        run(lambda b, x: b.op("LayerNorm", [x, b.weight("g", "f32", [128]), b.weight("be", "bf16", [128])], eps=1e-5),
+            {"g": (128,), "be": (128,)})
+    assert e.value.code == -6 and "float type" in str(e.value)
+    with pytest.raises(S.Sod2Error) as e:
+        run(lambda b, x: b.op("LayerNorm", [x, b.weight("g", "bf16", [64]), b.weight("be", "bf16", [128])], eps=1e-5),
+            {"g": (64,), "be": (128,)})
+    assert e.value.code == -3 and "dense vector of 128" in str(e.value)
+    with pytest.raises(S.Sod2Error) as e:
+        run(lambda b, x: b.op("Add", [b.op("MatMul", [x, b.weight("w", "bf16", [256, 128])], transB=1), b.weight("bias", "f32", [256])]),
+            {"w": (256, 128), "bias": (256,)})
+    assert e.value.code == -6
