@@ -527,3 +527,45 @@ def test_mistyped_operands_are_refused_before_any_launch(S):
         run(lambda b, x: b.op("Add", [b.op("MatMul", [x, b.weight("w", "bf16", [256, 128])], transB=1), b.weight("bias", "f32", [256])]),
             {"w": (256, 128), "bias": (256,)})
     assert e.value.code == -6
+
+
+def test_run_can_be_captured_in_a_hip_graph(S):
+    """A run of a graph without execution-determined operators only enqueues kernels: captured once on a side stream,
+    every replay gives the eager result bit for bit, with eager runs of the same binding on other inputs and
+    synchronisations between the replays (with and without the split-K workspace in use)."""
+    import torch
+    from paper_2403_00176_amd.session import Session
+    w = configs.config2(1, layers=2)
+    ses = Session(w.graph)
+    ses.upload_weights(w.make_weights())
+    sym = {"B": 2, "L": 100}
+    for splits in (0, 4):
+        b = ses.bind(sym)
+        if splits:
+            S.sod2_binding_force_variant(b, 17)
+            S.sod2_binding_force_splits(b, splits)
+        ins = ses.upload_inputs(w.make_inputs(0, sym))
+        ins2 = ses.upload_inputs(w.make_inputs(1, sym))
+        eager, eager2, other, replayed = (ses.alloc_outputs(ses.output_shapes(b)) for _ in range(4))
+        ses.run(b, ins, eager)
+        ses.run(b, ins2, eager2)
+        torch.cuda.synchronize()
+        assert not torch.equal(eager[0].view(torch.int16), eager2[0].view(torch.int16))
+        arena = ses.arena
+        src = [torch.empty_like(x) for x in ins]                     # the captured run reads these buffers
+        wp, ip, op = [x.data_ptr() for x in ses.weights], [x.data_ptr() for x in src], [x.data_ptr() for x in replayed]
+        side = torch.cuda.Stream()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            S.sod2_run(b, arena.data_ptr(), arena.numel(), wp, ip, op, torch.cuda.current_stream().cuda_stream)
+        for k in range(3):
+            for dst, a_, b_ in zip(src, ins, ins2):
+                dst.copy_(a_ if k % 2 == 0 else b_)
+            replayed[0].zero_()
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
+            want = eager if k % 2 == 0 else eager2
+            assert torch.equal(replayed[0].view(torch.int16), want[0].view(torch.int16)), (splits, k)
+            ses.run(b, ins2 if k % 2 == 0 else ins, other)           # eager work on the same arena in between
+            torch.cuda.synchronize()
