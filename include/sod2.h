@@ -196,7 +196,7 @@ sod2_status sod2_plan_dump(const sod2_plan_t*, char* buf_host, size_t cap, size_
  * tensors the group reads from outside itself; info->n_ops / n_ins always hold the full counts. */
 enum { SOD2_G_GEMM = 0, SOD2_G_CONV, SOD2_G_LAYERNORM, SOD2_G_SOFTMAX, SOD2_G_MAXPOOL, SOD2_G_REDUCEMEAN, SOD2_G_ARGMAX,
        SOD2_G_CACHEAPPEND, SOD2_G_NONZERO, SOD2_G_GATHER, SOD2_G_ELTWISE, SOD2_G_ATTENTION, SOD2_G_SCATTER, SOD2_G_RESIZE,
-       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM, SOD2_G_MAXUNPOOL, SOD2_G_AVGPOOL, SOD2_G_NMS };
+       SOD2_G_CONCAT, SOD2_G_RANGE, SOD2_G_FILL, SOD2_G_ONEHOT, SOD2_G_TOPK, SOD2_G_GROUPNORM, SOD2_G_MAXUNPOOL, SOD2_G_AVGPOOL, SOD2_G_NMS, SOD2_G_COPY };
 typedef struct {
   int32_t gid;        /* group id: the smallest operator id in the group */
   int32_t kind;       /* SOD2_G_* */

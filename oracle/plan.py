@@ -8,7 +8,10 @@ build's reading; the library follows the same written rules independently.
 R0  An operator whose outputs are all integer tensors with a fully resolved
     value map is *folded*: its result is known from RDP (Fig. 1(a)), nothing runs.
 R1  Reshape, Slice, Transpose, Expand and Gather-with-a-scalar-host-index are *views*:
-    their output aliases the input's storage; no kernel, no arena tensor.
+    their output aliases the input's storage; no kernel, no arena tensor.  One
+    whose result is a graph output is a group of its own (COPY): the view is
+    written out densely into the caller's buffer.  Likewise an operator with a
+    known value map is not folded when its result is a graph output.
 R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     this order and each at most once: Mul by a host scalar; Add of a rank-1
     weight equal to the last dim (bias); activation; Add of a non-constant
@@ -220,14 +223,15 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
         if op.kind in ("Switch", "Combine"):
             continue
         outs_int = all(g.tensors[o].dtype in ("i64", "i32") for o in op.outputs)
-        if outs_int and all(isinstance(rdp.V[o], list) and all(R.is_expr(e) for e in rdp.V[o])
-                            for o in op.outputs):
+        to_caller = any(g.tensors[o].is_output for o in op.outputs)      # its result must reach the caller's buffer
+        if outs_int and not to_caller and all(isinstance(rdp.V[o], list) and all(R.is_expr(e) for e in rdp.V[o])
+                                              for o in op.outputs):
             folded[i] = True
         elif op.kind in VIEW_KINDS:
-            view[i] = True
+            view[i] = not to_caller
         elif op.kind == "Gather":
             idx = g.tensors[op.inputs[1]]
-            view[i] = idx.data is not None and idx.data.ndim == 0
+            view[i] = idx.data is not None and idx.data.ndim == 0 and not to_caller
 
     def sole_consumer(t) -> Optional[int]:
         if g.tensors[t].is_output or len(rdp.consumers[t]) != 1:
@@ -294,6 +298,9 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             new_group("GEMM" if op.kind == "MatMul" else "CONV", members)
         elif op.kind in SOLO:
             new_group(SOLO[op.kind], [n])
+        elif op.kind in VIEW_KINDS or (op.kind == "Gather" and g.tensors[op.inputs[1]].data is not None
+                                       and g.tensors[op.inputs[1]].data.ndim == 0):
+            new_group("COPY", [n])           # a view whose result is a graph output: materialised in the caller's buffer
         elif op.kind == "Gather":
             members = [n]
             c = sole_consumer(op.outputs[0])

@@ -424,7 +424,7 @@ def sod2_run(b: Binding, arena_ptr: int, arena_bytes: int, weight_ptrs: Sequence
 STATIC_SCRATCH_BYTES = 8 << 20
 
 GROUP_KINDS = ["GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX", "CACHEAPPEND", "NONZERO", "GATHER",
-               "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL", "NMS"]
+               "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL", "NMS", "COPY"]
 SG_CLASSES = ["known", "mixed", "nac"]
 
 

@@ -162,7 +162,7 @@ struct Rdp {
 // Static plan
 // ---------------------------------------------------------------------------------------------
 enum GroupKind { G_GEMM, G_CONV, G_LAYERNORM, G_SOFTMAX, G_MAXPOOL, G_REDUCEMEAN, G_ARGMAX,
-                 G_CACHEAPPEND, G_NONZERO, G_GATHER, G_ELTWISE, G_ATTENTION, G_SCATTER, G_RESIZE, G_CONCAT, G_RANGE, G_FILL, G_ONEHOT, G_TOPK, G_GROUPNORM, G_MAXUNPOOL, G_AVGPOOL, G_NMS };
+                 G_CACHEAPPEND, G_NONZERO, G_GATHER, G_ELTWISE, G_ATTENTION, G_SCATTER, G_RESIZE, G_CONCAT, G_RANGE, G_FILL, G_ONEHOT, G_TOPK, G_GROUPNORM, G_MAXUNPOOL, G_AVGPOOL, G_NMS, G_COPY };
 const char* group_kind_name(int k);
 
 struct Group {

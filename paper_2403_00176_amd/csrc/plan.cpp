@@ -3,7 +3,9 @@
 //
 // Rules (the paper leaves them to an earlier fusion system and to "exhaustive search"):
 //  R0 an operator whose outputs are integer tensors with a fully resolved value map is folded;
-//  R1 Reshape / Slice / Transpose / Expand / Gather-with-scalar-host-index are views (no kernel);
+//  R1 Reshape / Slice / Transpose / Expand / Gather-with-scalar-host-index are views (no kernel); one whose result is a
+//     graph output is a COPY group (the view written out densely into the caller's buffer), and an operator with a
+//     known value map is not folded when its result is a graph output;
 //  R2 MatMul / Conv absorbs, in order and each at most once: Mul by a host scalar, Add of a rank-1
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
@@ -40,7 +42,7 @@
 namespace sod2 {
 
 static const char* kGroupNames[] = {"GEMM", "CONV", "LAYERNORM", "SOFTMAX", "MAXPOOL", "REDUCEMEAN", "ARGMAX",
-                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL", "NMS"};
+                                    "CACHEAPPEND", "NONZERO", "GATHER", "ELTWISE", "ATTENTION", "SCATTER", "RESIZE", "CONCAT", "RANGE", "FILL", "ONEHOT", "TOPK", "GROUPNORM", "MAXUNPOOL", "AVGPOOL", "NMS", "COPY"};
 const char* group_kind_name(int k) { return kGroupNames[k]; }
 
 namespace {
@@ -48,6 +50,11 @@ const int kMaxSubgraph = 14;
 
 bool is_act(int k) { return k == SOD2_OP_RELU || k == SOD2_OP_GELU || k == SOD2_OP_SIGMOID; }
 bool is_eltwise(int k) { return k == SOD2_OP_ADD || k == SOD2_OP_MUL || is_act(k) || k == SOD2_OP_CAST || k == SOD2_OP_ROUND; }
+bool is_view_kind(int k) { return k == SOD2_OP_RESHAPE || k == SOD2_OP_SLICE || k == SOD2_OP_TRANSPOSE || k == SOD2_OP_EXPAND; }
+bool scalar_gather(const Graph& G, const Op& op) {     // Gather with a scalar host index: a view
+  const Tensor& idx = G.tensors[op.in[1]];
+  return idx.has_data && idx.host_rank == 0;
+}
 bool is_control(int k) { return k == SOD2_OP_SWITCH || k == SOD2_OP_COMBINE; }
 bool is_counting(int k) { return k == SOD2_OP_NONZERO || k == SOD2_OP_NMS; }   // a result whose length is found by running
 
@@ -128,17 +135,15 @@ void Plan::build() {
   for (int i = 0; i < nops; ++i) {
     const Op& op = G.ops[i];
     if (is_control(op.kind)) { if (op.kind == SOD2_OP_SWITCH) ++n_switches; continue; }
-    bool ints = true, known = true;
+    bool ints = true, known = true, to_caller = false;   // to_caller: its result must reach the caller's buffer
     for (int o : op.out) {
       if (!is_int(G.tensors[o].dtype)) ints = false;
       if (!R.V[o].resolved()) known = false;
+      if (G.tensors[o].is_output) to_caller = true;
     }
-    if (ints && known) folded[i] = 1;
-    else if (op.kind == SOD2_OP_RESHAPE || op.kind == SOD2_OP_SLICE || op.kind == SOD2_OP_TRANSPOSE || op.kind == SOD2_OP_EXPAND) view[i] = 1;
-    else if (op.kind == SOD2_OP_GATHER) {
-      const Tensor& idx = G.tensors[op.in[1]];
-      view[i] = idx.has_data && idx.host_rank == 0;
-    }
+    if (ints && known && !to_caller) folded[i] = 1;
+    else if (is_view_kind(op.kind)) view[i] = !to_caller;
+    else if (op.kind == SOD2_OP_GATHER) view[i] = scalar_gather(G, op) && !to_caller;
   }
 
   auto sole_consumer = [&](int t) -> int {
@@ -223,6 +228,8 @@ void Plan::build() {
     else if (op.kind == SOD2_OP_MAXUNPOOL) new_group(G_MAXUNPOOL, {n});
     else if (op.kind == SOD2_OP_AVERAGEPOOL) new_group(G_AVGPOOL, {n});
     else if (op.kind == SOD2_OP_NMS) new_group(G_NMS, {n});
+    else if (is_view_kind(op.kind) || (op.kind == SOD2_OP_GATHER && scalar_gather(G, op)))
+      new_group(G_COPY, {n});          // a view whose result is a graph output: materialised in the caller's buffer
     else if (op.kind == SOD2_OP_GATHER) {
       std::vector<int> chain{n};
       int c = sole_consumer(op.out[0]);

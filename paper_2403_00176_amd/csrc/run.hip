@@ -206,59 +206,65 @@ struct Builder {
         if (src < 0) throw Error(SOD2_ERR_INVALID_ARG, "Combine without a live input");
         v = view_of(src);
       } else {
-        const View& in = view_of(op.in[0]);
-        v = in;
-        if (op.kind == SOD2_OP_TRANSPOSE) {
-          for (size_t i = 0; i < op.ia.size(); ++i) { v.dims[i] = in.dims[op.ia[i]]; v.strides[i] = in.strides[op.ia[i]]; }
-        } else if (op.kind == SOD2_OP_GATHER) {
-          int64_t r = (int64_t)in.dims.size();
-          int64_t ax = ((op.ia.at(0) % r) + r) % r;
-          int64_t idx = G.tensors[op.in[1]].idata.at(0);
-          if (idx < 0) idx += in.dims[ax];
-          if (idx < 0 || idx >= in.dims[ax]) throw Error(SOD2_ERR_INVALID_ARG, "Gather index out of range");
-          v.off += idx * in.strides[ax];
-          v.dims.erase(v.dims.begin() + ax);
-          v.strides.erase(v.strides.begin() + ax);
-        } else if (op.kind == SOD2_OP_SLICE) {
-          // bounds and axes as RDP carries them: host constants, or expressions computed from shapes (value maps),
-          // evaluated at the bound symbols
-          const LS &st = p.rdp->V[op.in[1]], &en = p.rdp->V[op.in[2]], &ax = p.rdp->V[op.in[3]];
-          if (!st.resolved() || !en.resolved() || !ax.resolved() || st.d.size() != ax.d.size() || en.d.size() != ax.d.size())
-            throw Error(SOD2_ERR_UNSUPPORTED, "Slice bounds must be known to RDP (host constants or values computed from shapes)");
-          for (size_t k = 0; k < ax.d.size(); ++k) {
-            int64_t r = (int64_t)in.dims.size();
-            int64_t a = ((ax.d[k].e.eval(b.env) % r) + r) % r, D = in.dims[a];
-            const int64_t sv = st.d[k].e.eval(b.env), ev = en.d[k].e.eval(b.env);
-            const bool sc = st.d[k].e.is_const(), ec = en.d[k].e.is_const();
-            int64_t s = (sc && sv < 0) ? D + sv : sv;
-            int64_t e = (ec && ev >= kIntMax) ? D : ((ec && ev < 0) ? D + ev : ev);
-            if (s < 0 || e > D || s > e) throw Error(SOD2_ERR_INVALID_ARG, "Slice bounds outside the tensor");
-            v.off += s * in.strides[a];
-            v.dims[a] = e - s;
-          }
-        } else if (op.kind == SOD2_OP_EXPAND) {         // broadcast dims get stride 0
-          Dims nd = eval_dims(t), ns(nd.size(), 0);
-          if (nd.size() < in.dims.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Expand lowers the rank");
-          size_t pad = nd.size() - in.dims.size();
-          for (size_t i = 0; i < in.dims.size(); ++i) {
-            if (in.dims[i] == nd[pad + i]) ns[pad + i] = in.strides[i];
-            else if (in.dims[i] != 1) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Expand of a dim that is neither 1 nor the target");
-          }
-          v.dims = nd;
-          v.strides = ns;
-        } else if (op.kind == SOD2_OP_RESHAPE) {
-          Dims nd = eval_dims(t), ns;
-          if (View{0, 0, nd, {}}.numel() != in.numel()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Reshape changes the element count");
-          if (!reshape_strides(in, nd, &ns))
-            throw Error(SOD2_ERR_UNSUPPORTED, "Reshape of a strided view needs a copy: " + G.tensors[t].name);
-          v.dims = nd;
-          v.strides = ns;
-        }
+        v = derived_view(op, t);
       }
     }
     memo_at[t] = (int)memo.size();
     memo.push_back(v);
     return memo.back();
+  }
+
+  // the view a Reshape / Slice / Transpose / Expand / scalar-index Gather makes of its first operand; t = its result
+  View derived_view(const Op& op, int t) {
+    const View in = view_of(op.in[0]);
+    View v = in;
+    if (op.kind == SOD2_OP_TRANSPOSE) {
+      for (size_t i = 0; i < op.ia.size(); ++i) { v.dims[i] = in.dims[op.ia[i]]; v.strides[i] = in.strides[op.ia[i]]; }
+    } else if (op.kind == SOD2_OP_GATHER) {
+      int64_t r = (int64_t)in.dims.size();
+      int64_t ax = ((op.ia.at(0) % r) + r) % r;
+      int64_t idx = G.tensors[op.in[1]].idata.at(0);
+      if (idx < 0) idx += in.dims[ax];
+      if (idx < 0 || idx >= in.dims[ax]) throw Error(SOD2_ERR_INVALID_ARG, "Gather index out of range");
+      v.off += idx * in.strides[ax];
+      v.dims.erase(v.dims.begin() + ax);
+      v.strides.erase(v.strides.begin() + ax);
+    } else if (op.kind == SOD2_OP_SLICE) {
+      // bounds and axes as RDP carries them: host constants, or expressions computed from shapes (value maps),
+      // evaluated at the bound symbols
+      const LS &st = p.rdp->V[op.in[1]], &en = p.rdp->V[op.in[2]], &ax = p.rdp->V[op.in[3]];
+      if (!st.resolved() || !en.resolved() || !ax.resolved() || st.d.size() != ax.d.size() || en.d.size() != ax.d.size())
+        throw Error(SOD2_ERR_UNSUPPORTED, "Slice bounds must be known to RDP (host constants or values computed from shapes)");
+      for (size_t k = 0; k < ax.d.size(); ++k) {
+        int64_t r = (int64_t)in.dims.size();
+        int64_t a = ((ax.d[k].e.eval(b.env) % r) + r) % r, D = in.dims[a];
+        const int64_t sv = st.d[k].e.eval(b.env), ev = en.d[k].e.eval(b.env);
+        const bool sc = st.d[k].e.is_const(), ec = en.d[k].e.is_const();
+        int64_t s = (sc && sv < 0) ? D + sv : sv;
+        int64_t e = (ec && ev >= kIntMax) ? D : ((ec && ev < 0) ? D + ev : ev);
+        if (s < 0 || e > D || s > e) throw Error(SOD2_ERR_INVALID_ARG, "Slice bounds outside the tensor");
+        v.off += s * in.strides[a];
+        v.dims[a] = e - s;
+      }
+    } else if (op.kind == SOD2_OP_EXPAND) {         // broadcast dims get stride 0
+      Dims nd = eval_dims(t), ns(nd.size(), 0);
+      if (nd.size() < in.dims.size()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Expand lowers the rank");
+      size_t pad = nd.size() - in.dims.size();
+      for (size_t i = 0; i < in.dims.size(); ++i) {
+        if (in.dims[i] == nd[pad + i]) ns[pad + i] = in.strides[i];
+        else if (in.dims[i] != 1) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Expand of a dim that is neither 1 nor the target");
+      }
+      v.dims = nd;
+      v.strides = ns;
+    } else if (op.kind == SOD2_OP_RESHAPE) {
+      Dims nd = eval_dims(t), ns;
+      if (View{0, 0, nd, {}}.numel() != in.numel()) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Reshape changes the element count");
+      if (!reshape_strides(in, nd, &ns))
+        throw Error(SOD2_ERR_UNSUPPORTED, "Reshape of a strided view needs a copy: " + G.tensors[t].name);
+      v.dims = nd;
+      v.strides = ns;
+    }
+    return v;
   }
 
   Ref ref_of(const View& v, int dtype) const {
@@ -753,6 +759,36 @@ struct Builder {
     L.u.elt = a;
     L.flops = (double)a.total * a.n_ops;
     L.bytes += (double)a.total * dtype_bytes(L.out_dtype);
+    return L;
+  }
+
+  // COPY: a view operator whose result is a graph output; the view of its operand, read through its strides by the
+  // elementwise kernel (one identity operation) and written densely
+  Launch copy(const Group& gr) {
+    Launch L;
+    L.group = gr.gid;
+    L.kernel = K_ELTWISE;
+    const Op& op = G.ops[gr.ops[0]];
+    const int dt = G.tensors[op.in[0]].dtype;
+    if ((dt != SOD2_BF16 && dt != SOD2_F32) || G.tensors[gr.out].dtype != dt)
+      throw Error(SOD2_ERR_UNSUPPORTED, "a view that is a graph output is copied by the elementwise kernel: bf16 or f32 only");
+    const View src = derived_view(op, gr.out);
+    if (src.dims.size() > 6) throw Error(SOD2_ERR_UNSUPPORTED, "elementwise group above rank 6");
+    EltArgs a{};
+    a.rank = (int)src.dims.size();
+    a.total = 1;
+    for (size_t i = 0; i < src.dims.size(); ++i) { a.dims[i] = src.dims[i]; a.total *= src.dims[i]; a.stride[0][i] = src.strides[i]; }
+    if (a.rank == 0) { a.rank = 1; a.dims[0] = 1; a.stride[0][0] = 0; }
+    a.n_in = 1;
+    a.in_bf16[0] = dt == SOD2_BF16;
+    a.n_ops = 1;
+    a.op[0] = E_CAST;
+    a.src[0] = -1;
+    L.in_dtype = L.out_dtype = dt;
+    L.r[0] = ref_of(src, dt);
+    L.r[5] = ref_t(gr.out);
+    L.u.elt = a;
+    L.bytes = 2.0 * (double)a.total * dtype_bytes(dt);
     return L;
   }
 
@@ -1324,6 +1360,7 @@ struct Builder {
       case G_REDUCEMEAN: return reduce(gr);
       case G_MAXPOOL: case G_AVGPOOL: return pool(gr);
       case G_ELTWISE: return eltwise(gr);
+      case G_COPY: return copy(gr);
       default:
         throw Error(SOD2_ERR_UNSUPPORTED, std::string("no kernel for group kind ") + group_kind_name(gr.kind));
     }

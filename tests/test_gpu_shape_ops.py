@@ -443,3 +443,45 @@ def test_nms_kernel(S_lib, max_out, iou):
             torch.cuda.synchronize()
             assert S_lib.sod2_run_exec_values(bnd2) == [n]
             assert np.array_equal(to_host(outs2[0]).reshape(-1, 4)[:n], got_b) and np.array_equal(to_host(outs2[1]).reshape(-1)[:n], got_s)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_views_as_graph_outputs_are_written_out(S_lib, dtype):
+    """A Transpose, Slice, Reshape, Expand or scalar-index Gather whose result is a graph output has no storage of its
+    own to alias: the planner makes it a COPY group and the view is written densely into the caller's buffer (bit
+    exact), also when the same view is read by another operator."""
+    import torch
+    from paper_2403_00176_amd.session import Session, to_host
+    b = GraphBuilder([("A", 1, 40), ("B", 1, 40)])
+    x = b.input("x", dtype, ["A", "B", 8])
+    y = b.op("Mul", [x, b.const("two", 2.0, "f32")])                                  # a computed tensor in the arena
+    t = b.mark_output(b.op("Transpose", [y], perm=(2, 0, 1)), "transposed")
+    b.mark_output(b.op("Slice", [y, b.const("s", [1]), b.const("e", [7]), b.const("ax", [2])]), "sliced")
+    shp = b.op("Shape", [y], dtype="i64")
+    lead = b.op("Slice", [shp, b.const("l0", [0]), b.const("l1", [1]), b.const("lax", [0])], dtype="i64")
+    b.mark_output(b.op("Reshape", [y, b.op("Concat", [lead, b.const("m1", [-1])], axis=0, dtype="i64")]), "flat")
+    b.mark_output(b.op("Gather", [y, b.const("i3", 3)], axis=2), "column")
+    b.mark_output(b.op("Expand", [b.op("ReduceMean", [y], axes=(1,), keepdims=1), shp]), "expanded")
+    b.mark_output(b.op("Relu", [t]), "relu_of_view")                                  # the view is also read
+    b.mark_output(b.op("Transpose", [x], perm=(1, 0, 2)), "input_transposed")         # a view of a graph input
+    g = b.build()
+    po = P.build_plan(g, R.RDP(g).analyse())
+    assert sum(1 for gr in po.groups.values() if gr.kind == "COPY") == 6
+    ses = Session(g)
+    ses.upload_weights({})
+    for k, sym in enumerate(({"A": 1, "B": 1}, {"A": 3, "B": 5}, {"A": 40, "B": 33})):
+        ins = {g.tensor_id("x"): rng.normal(900 + k, (sym["A"], sym["B"], 8))}
+        bnd = ses.bind(sym)
+        assert S_lib.sod2_binding_dump(bnd) == A.dump(A.bind(po, sym))
+        outs = ses.alloc_outputs(ses.output_shapes(bnd))
+        ses.run(bnd, ses.upload_inputs(ins), outs)
+        torch.cuda.synchronize()
+        ref = execute.run(g, po.order, {}, ins)
+        for t_, o in zip(g.outputs(), outs):
+            got = to_host(o)
+            assert got.shape == ref.values[t_].shape, (g.tensors[t_].name, sym)
+            if g.tensors[t_].name == "expanded":            # a computed mean under the view: within the bar, and constant along B
+                assert rel_err(got, ref.values[t_]) <= (1e-5 if dtype == "f32" else 2e-2)
+                assert np.array_equal(got, np.broadcast_to(got[:, :1, :], got.shape))
+            else:                                           # copies of exactly computed values: bit exact
+                assert np.array_equal(got, ref.values[t_]), (g.tensors[t_].name, sym)

@@ -1,0 +1,151 @@
+"""Differential test on seeded random graphs (CPU only): the library's RDP, plan and binding against the oracle's,
+byte for byte, and the oracle's inferred shapes against the shapes of an actual execution.  The graphs mix what the
+configurations use one at a time: broadcasting elementwise chains, contractions with epilogues, row operators,
+views (Transpose, Slice, Reshape through computed shapes), Concat, ReduceMean, Cast and Round, over two symbols."""
+import random
+
+import numpy as np
+import pytest
+
+import paper_2403_00176_amd as S
+from oracle import rdp as R, plan as P, arena as A, execute
+from workloads import GraphBuilder
+
+
+def random_graph(seed):
+    rnd = random.Random(seed)
+    b = GraphBuilder([("A", 1, 9), ("B", 1, 12)])
+    pool = []                                  # (tensor id, dims as tokens: "A", "B" or an int)
+    weights = {}
+
+    def add(t, dims):
+        pool.append((t, list(dims)))
+        return t
+
+    def weight(dims):
+        t = b.weight(f"w{len(weights)}", "f32", dims)
+        weights[t] = tuple(dims)
+        return t
+
+    add(b.input("x0", "f32", ["A", "B", 8]), ["A", "B", 8])
+    add(b.input("x1", "f32", ["A", 1, 8]), ["A", 1, 8])
+    add(b.input("x2", "f32", ["B", 8]), ["B", 8])
+    n_const = [0]
+
+    def const(values, dtype="i64"):
+        n_const[0] += 1
+        return b.const(f"c{n_const[0]}", values, dtype)
+
+    def broadcastable(x, y):
+        for p, q in zip(reversed(x), reversed(y)):
+            if p != q and p != 1 and q != 1:
+                return False
+        return True
+
+    def bshape(x, y):
+        n = max(len(x), len(y))
+        x, y = [1] * (n - len(x)) + list(x), [1] * (n - len(y)) + list(y)
+        return [q if p == 1 else p for p, q in zip(x, y)]
+
+    for _ in range(rnd.randint(6, 14)):
+        t, d = rnd.choice(pool)
+        kind = rnd.choice(["unary", "unary", "binary", "binary", "scalar", "matmul", "layernorm", "softmax", "transpose",
+                           "reduce", "concat", "slice", "flatten", "cast"])
+        if kind == "unary":
+            add(b.op(rnd.choice(["Relu", "Gelu", "Sigmoid", "Round"]), [t]), d)
+        elif kind == "scalar":
+            add(b.op(rnd.choice(["Add", "Mul"]), [t, const(rnd.choice([0.5, 2.0, -1.0]), "f32")]), d)
+        elif kind == "binary":
+            cands = [(u, e) for u, e in pool if u != t and broadcastable(d, e)]
+            if cands:
+                u, e = rnd.choice(cands)
+                args = [t, u] if rnd.random() < 0.5 else [u, t]
+                add(b.op(rnd.choice(["Add", "Mul"]), args), bshape(d, e))
+        elif kind == "matmul" and isinstance(d[-1], int) and len(d) >= 2:
+            n = rnd.choice([4, 8, 16])
+            y = b.op("MatMul", [t, weight([n, d[-1]])], transB=1)
+            if rnd.random() < 0.6:
+                y = b.op("Add", [y, weight([n])])
+            if rnd.random() < 0.4:
+                y = b.op(rnd.choice(["Relu", "Gelu"]), [y])
+            add(y, d[:-1] + [n])
+        elif kind == "layernorm" and isinstance(d[-1], int):
+            add(b.op("LayerNorm", [t, weight([d[-1]]), weight([d[-1]])], eps=1e-5), d)
+        elif kind == "softmax":
+            add(b.op("Softmax", [t], causal=0), d)
+        elif kind == "transpose" and len(d) >= 2:
+            perm = list(range(len(d)))
+            rnd.shuffle(perm)
+            add(b.op("Transpose", [t], perm=tuple(perm)), [d[p] for p in perm])
+        elif kind == "reduce" and len(d) >= 2:
+            ax = rnd.randrange(len(d))
+            keep = rnd.randint(0, 1)
+            add(b.op("ReduceMean", [t], axes=(ax,), keepdims=keep), [1 if i == ax else e for i, e in enumerate(d)] if keep
+                else [e for i, e in enumerate(d) if i != ax])
+        elif kind == "concat":
+            cands = [(u, e) for u, e in pool if e == d]
+            u, e = rnd.choice(cands)
+            ax = rnd.randrange(len(d))
+            if isinstance(d[ax], int):
+                add(b.op("Concat", [t, u], axis=ax), [2 * e2 if i == ax else e2 for i, e2 in enumerate(d)])
+        elif kind == "slice" and isinstance(d[-1], int) and d[-1] >= 4:
+            lo, hi = 1, d[-1] - 1
+            add(b.op("Slice", [t, const([lo]), const([hi]), const([len(d) - 1])]), d[:-1] + [hi - lo])
+        elif kind == "flatten" and len(d) >= 3:
+            # [.., p, q] -> [.., p * q] through Shape, Slice of the leading dims and Concat with -1
+            shp = b.op("Shape", [t], dtype="i64")
+            lead = b.op("Slice", [shp, const([0]), const([len(d) - 2]), const([0])], dtype="i64")
+            tgt = b.op("Concat", [lead, const([-1])], axis=0, dtype="i64")
+            p, q = d[-2], d[-1]
+            merged = p * q if isinstance(p, int) and isinstance(q, int) else None
+            if merged is not None:
+                add(b.op("Reshape", [t, tgt]), d[:-2] + [merged])
+        elif kind == "cast":
+            add(b.op("Cast", [b.op("Cast", [t], dtype="bf16")], dtype="f32"), d)
+    outs = {pool[-1][0]}
+    outs.add(rnd.choice(pool[3:] or pool)[0])
+    for k, t in enumerate(sorted(outs)):
+        if b.g.tensors[t].role == "inter":
+            b.mark_output(t, f"out{k}")
+    g = b.build()
+    if not g.outputs():
+        return None, None, None
+    return g, weights, dict(pool)
+
+
+def concrete(dims, sym):
+    return tuple(sym[d] if isinstance(d, str) else d for d in dims)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_graph_library_equals_oracle(seed):
+    g, weights, shapes = random_graph(seed)
+    if g is None:
+        pytest.skip("no operator survived the draw")
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    ro = R.RDP(g).analyse()
+    assert S.sod2_rdp_dump(lr) == R.dump(ro)
+    # the generator's own bookkeeping of the shapes (plain token arithmetic) agrees with RDP
+    for t, d in shapes.items():
+        if g.tensors[t].role == "inter":
+            got = ro.S[t]
+            assert isinstance(got, list) and len(got) == len(d), (g.tensors[t].name, R.fmt_list(got), d)
+    for opts in ({}, {"fusion": 0}, {"sep": 0, "inplace": 0}):
+        lp = S.sod2_plan(lg, lr, **opts)
+        po = P.build_plan(g, ro, P.Opts(**{k: bool(v) for k, v in opts.items()}))
+        assert S.sod2_plan_dump(lp) == P.dump(po), opts
+        for sym in ({"A": 1, "B": 1}, {"A": 3, "B": 7}, {"A": 9, "B": 12}):
+            bo = A.bind(po, sym)
+            assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(bo), (opts, sym)
+    # executed shapes == inferred shapes, values finite
+    rs = np.random.RandomState(seed)
+    sym = {"A": 3, "B": 5}
+    ins = {t: rs.randn(*concrete(shapes[t], sym)) for t in g.inputs()}
+    W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
+    po = P.build_plan(g, ro)
+    ref = execute.run(g, po.order, W, ins)
+    bo = A.bind(po, sym)
+    for t in g.outputs():
+        assert ref.values[t].shape == concrete(shapes[t], sym) == tuple(bo.dims[t])
+        assert np.isfinite(ref.values[t]).all()
