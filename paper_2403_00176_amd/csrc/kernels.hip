@@ -614,6 +614,7 @@ __global__ void eltwise_kernel(EltArgs a) {
       case E_GELU: v = apply_act(v, ACT_GELU); break;
       case E_SIGMOID: v = apply_act(v, ACT_SIGMOID); break;
       case E_ROUND: v = rintf(v); break;                 // halves to the even integer
+      case E_CAST_BF16: v = bf2f(f2bf(v)); break;
       default: break;
     }
   }

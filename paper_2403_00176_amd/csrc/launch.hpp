@@ -91,7 +91,7 @@ struct PoolArgs {
 
 // out[idx] = chain of up to 8 elementwise operators over the output index space; operands are
 // broadcast through zero strides (the single fused loop nest of Fig. 4)
-enum EltOp { E_ADD = 0, E_MUL, E_RELU, E_GELU, E_SIGMOID, E_CAST, E_ROUND };
+enum EltOp { E_ADD = 0, E_MUL, E_RELU, E_GELU, E_SIGMOID, E_CAST, E_ROUND, E_CAST_BF16 };   // E_CAST_BF16: round to bf16 (a Cast inside a chain)
 struct EltArgs {
   const void* in[5];
   void* out;
@@ -187,7 +187,8 @@ struct ResizeArgs {
   long long row_units;       // copy units (16 bytes or one element) per innermost vector
 };
 
-// Concat of up to 4 dense tensors along the last dim: out[r, :] = x0[r, :] | x1[r, :] | ...
+// Concat of up to 4 dense tensors along one axis, seen as rows (the dims before the axis) of runs (the axis and the
+// dims behind it): out[r, :] = x0[r, :] | x1[r, :] | ...
 struct ConcatArgs {
   const void* x[4]; void* y;
   long long rows;

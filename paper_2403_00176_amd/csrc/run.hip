@@ -743,7 +743,12 @@ struct Builder {
         case SOD2_OP_GELU: a.op[o] = E_GELU; break;
         case SOD2_OP_SIGMOID: a.op[o] = E_SIGMOID; break;
         case SOD2_OP_ROUND: a.op[o] = E_ROUND; break;
-        default: a.op[o] = E_CAST; break;
+        default: {                                     // Cast: what it rounds to is part of the value, also inside a chain
+          const int to = G.tensors[op.out[0]].dtype;
+          if (is_int(to)) throw Error(SOD2_ERR_UNSUPPORTED, "Cast to an integer type in an elementwise group");
+          a.op[o] = to == SOD2_BF16 ? E_CAST_BF16 : E_CAST;
+          break;
+        }
       }
       if (op.in.size() == 2) {
         int ot = (k == 0) ? op.in[1] : other(op, cur);
@@ -1125,12 +1130,16 @@ struct Builder {
     int dt = G.tensors[gr.out].dtype;
     size_t r = vo.dims.size(), n = op.in.size();
     int64_t ax = op.ia.empty() ? 0 : ((op.ia[0] % (int64_t)r) + (int64_t)r) % (int64_t)r;
-    if (n < 1 || n > 4 || r < 1 || ax != (int64_t)r - 1 || (dt != SOD2_BF16 && dt != SOD2_F32))
-      throw Error(SOD2_ERR_UNSUPPORTED, "Concat kernel: up to 4 dense float tensors along the last dim");
+    if (n < 1 || n > 4 || r < 1 || (dt != SOD2_BF16 && dt != SOD2_F32))
+      throw Error(SOD2_ERR_UNSUPPORTED, "Concat kernel: up to 4 dense float tensors");
+    // dense operands joined along axis ax: for every index of the dims before ax, operand k contributes one run of
+    // (its extent along ax) x (the dims behind ax) elements -- rows of runs, whatever the axis
     ConcatArgs a{};
     a.n_in = (int)n;
     a.rows = 1;
-    for (size_t k = 0; k + 1 < r; ++k) a.rows *= vo.dims[k];
+    for (int64_t k = 0; k < ax; ++k) a.rows *= vo.dims[k];
+    int64_t inner = 1;
+    for (size_t k = (size_t)ax + 1; k < r; ++k) inner *= vo.dims[k];
     int64_t eb = dtype_bytes(dt);
     int64_t cols[4] = {0, 0, 0, 0};
     bool v16 = true;
@@ -1138,8 +1147,9 @@ struct Builder {
       const View& vi = view_of(op.in[k]);
       if (!vi.contiguous() || vi.dims.size() != r || G.tensors[op.in[k]].dtype != dt)
         throw Error(SOD2_ERR_UNSUPPORTED, "Concat kernel: operands must be dense and of the result's type and rank");
-      for (size_t j = 0; j + 1 < r; ++j) if (vi.dims[j] != vo.dims[j]) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Concat operands differ outside the axis");
-      cols[k] = vi.dims[r - 1];
+      for (size_t j = 0; j < r; ++j)
+        if ((int64_t)j != ax && vi.dims[j] != vo.dims[j]) throw Error(SOD2_ERR_SHAPE_MISMATCH, "Concat operands differ outside the axis");
+      cols[k] = vi.dims[ax] * inner;
       L.r[k] = ref_of(vi, dt);
       if ((cols[k] * eb) % 16 != 0 || L.r[k].byte_off % 16 != 0) v16 = false;
     }

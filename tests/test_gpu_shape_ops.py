@@ -485,3 +485,44 @@ def test_views_as_graph_outputs_are_written_out(S_lib, dtype):
                 assert np.array_equal(got, np.broadcast_to(got[:, :1, :], got.shape))
             else:                                           # copies of exactly computed values: bit exact
                 assert np.array_equal(got, ref.values[t_]), (g.tensors[t_].name, sym)
+
+
+def test_random_graphs_against_the_oracle(S_lib):
+    """The seeded random graphs of tests/test_random_graphs.py (broadcasting chains, small contractions with
+    epilogues, row operators over views, Concat, ReduceMean, views as outputs) through the C ABI in fp32: every
+    output within the bar of the oracle's values, or the binding refused with "unsupported" before anything ran."""
+    import torch
+    from tests.test_random_graphs import random_graph, concrete
+    from paper_2403_00176_amd.session import Session, to_host
+    ran = refused = 0
+    for seed in range(40):
+        g, weights, shapes = random_graph(seed)
+        if g is None:
+            continue
+        po = P.build_plan(g, R.RDP(g).analyse())
+        ses = Session(g)
+        rs = np.random.RandomState(seed)
+        W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
+        ses.upload_weights(W)
+        for sym in ({"A": 3, "B": 5}, {"A": 9, "B": 12}, {"A": 1, "B": 1}):
+            print(f"case random graph seed {seed} {sym} groups {[gr.kind for gr in po.groups.values()]}", flush=True)
+            ins = {t: rs.randn(*concrete(shapes[t], sym)) for t in g.inputs()}
+            bnd = ses.bind(sym)
+            assert S_lib.sod2_binding_dump(bnd) == A.dump(A.bind(po, sym))
+            outs = ses.alloc_outputs(ses.output_shapes(bnd))
+            try:
+                ses.run(bnd, ses.upload_inputs(ins), outs)
+            except S_lib.Sod2Error as e:
+                assert e.code == -6, (seed, sym, str(e))
+                refused += 1
+                print("  refused:", str(e)[:120], flush=True)
+                continue
+            torch.cuda.synchronize()
+            ran += 1
+            ref = execute.run(g, po.order, W, ins)
+            for t, o in zip(g.outputs(), outs):
+                got = to_host(o)
+                assert got.shape == ref.values[t].shape and np.isfinite(got).all()
+                assert rel_err(got, ref.values[t]) <= 1e-4, (seed, sym, g.tensors[t].name, rel_err(got, ref.values[t]))
+    print("random graphs: ran", ran, "refused", refused)
+    assert ran >= 60
