@@ -487,16 +487,19 @@ def test_views_as_graph_outputs_are_written_out(S_lib, dtype):
                 assert np.array_equal(got, ref.values[t_]), (g.tensors[t_].name, sym)
 
 
-def test_random_graphs_against_the_oracle(S_lib):
-    """The seeded random graphs of tests/test_random_graphs.py (broadcasting chains, small contractions with
-    epilogues, row operators over views, Concat, ReduceMean, views as outputs) through the C ABI in fp32: every
-    output within the bar of the oracle's values, or the binding refused with "unsupported" before anything ran."""
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_graphs_against_the_oracle(S_lib, dtype):
+    """The seeded random graphs of tests/test_random_graphs.py (broadcasting chains, small contractions and
+    convolutions with epilogues, row operators, pools, GroupNorm, views also as outputs, Concat, ReduceMean) through
+    the C ABI in fp32 and bf16: every output within the bar of the oracle's values, or the run refused with
+    "unsupported" before the group's kernel ran (a strided view handed to a kernel that wants dense operands)."""
     import torch
-    from tests.test_random_graphs import random_graph, concrete
+    from tests.test_random_graphs import random_graph, concrete, make_inputs
     from paper_2403_00176_amd.session import Session, to_host
     ran = refused = 0
+    worst = 0.0
     for seed in range(40):
-        g, weights, shapes = random_graph(seed)
+        g, weights, shapes = random_graph(seed, dtype)
         if g is None:
             continue
         po = P.build_plan(g, R.RDP(g).analyse())
@@ -506,7 +509,7 @@ def test_random_graphs_against_the_oracle(S_lib):
         ses.upload_weights(W)
         for sym in ({"A": 3, "B": 5}, {"A": 9, "B": 12}, {"A": 1, "B": 1}):
             print(f"case random graph seed {seed} {sym} groups {[gr.kind for gr in po.groups.values()]}", flush=True)
-            ins = {t: rs.randn(*concrete(shapes[t], sym)) for t in g.inputs()}
+            ins = make_inputs(g, shapes, sym, rs)
             bnd = ses.bind(sym)
             assert S_lib.sod2_binding_dump(bnd) == A.dump(A.bind(po, sym))
             outs = ses.alloc_outputs(ses.output_shapes(bnd))
@@ -523,6 +526,8 @@ def test_random_graphs_against_the_oracle(S_lib):
             for t, o in zip(g.outputs(), outs):
                 got = to_host(o)
                 assert got.shape == ref.values[t].shape and np.isfinite(got).all()
-                assert rel_err(got, ref.values[t]) <= 1e-4, (seed, sym, g.tensors[t].name, rel_err(got, ref.values[t]))
-    print("random graphs: ran", ran, "refused", refused)
+                err = rel_err(got, ref.values[t])
+                worst = max(worst, err)
+                assert err <= (1e-4 if dtype == "f32" else 2e-2), (seed, sym, g.tensors[t].name, err)
+    print("random graphs", dtype, ": ran", ran, "refused", refused, "worst rel err", worst)
     assert ran >= 60

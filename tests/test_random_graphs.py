@@ -1,7 +1,8 @@
 """Differential test on seeded random graphs (CPU only): the library's RDP, plan and binding against the oracle's,
 byte for byte, and the oracle's inferred shapes against the shapes of an actual execution.  The graphs mix what the
-configurations use one at a time: broadcasting elementwise chains, contractions with epilogues, row operators,
-views (Transpose, Slice, Reshape through computed shapes), Concat, ReduceMean, Cast and Round, over two symbols."""
+configurations use one at a time: broadcasting elementwise chains, contractions and convolutions with epilogues, row
+operators, pools, GroupNorm, views (Transpose, Slice, Expand, Reshape through computed shapes), Gather by an index
+tensor, Concat, ReduceMean, Cast and Round, over two symbols."""
 import random
 
 import numpy as np
@@ -12,7 +13,7 @@ from oracle import rdp as R, plan as P, arena as A, execute
 from workloads import GraphBuilder
 
 
-def random_graph(seed):
+def random_graph(seed, dtype="f32"):
     rnd = random.Random(seed)
     b = GraphBuilder([("A", 1, 9), ("B", 1, 12)])
     pool = []                                  # (tensor id, dims as tokens: "A", "B" or an int)
@@ -23,13 +24,15 @@ def random_graph(seed):
         return t
 
     def weight(dims):
-        t = b.weight(f"w{len(weights)}", "f32", dims)
+        t = b.weight(f"w{len(weights)}", dtype, dims)
         weights[t] = tuple(dims)
         return t
 
-    add(b.input("x0", "f32", ["A", "B", 8]), ["A", "B", 8])
-    add(b.input("x1", "f32", ["A", 1, 8]), ["A", 1, 8])
-    add(b.input("x2", "f32", ["B", 8]), ["B", 8])
+    add(b.input("x0", dtype, ["A", "B", 8]), ["A", "B", 8])
+    add(b.input("x1", dtype, ["A", 1, 8]), ["A", 1, 8])
+    add(b.input("x2", dtype, ["B", 8]), ["B", 8])
+    add(b.input("img", dtype, [2, "A", "B", 8]), [2, "A", "B", 8])            # channels last
+    idx = b.input("idx", "i64", ["B"])                                         # row numbers below 8
     n_const = [0]
 
     def const(values, dtype="i64"):
@@ -50,7 +53,7 @@ def random_graph(seed):
     for _ in range(rnd.randint(6, 14)):
         t, d = rnd.choice(pool)
         kind = rnd.choice(["unary", "unary", "binary", "binary", "scalar", "matmul", "layernorm", "softmax", "transpose",
-                           "reduce", "concat", "slice", "flatten", "cast"])
+                           "reduce", "concat", "slice", "flatten", "cast", "conv", "pool", "groupnorm", "gather", "expand"])
         if kind == "unary":
             add(b.op(rnd.choice(["Relu", "Gelu", "Sigmoid", "Round"]), [t]), d)
         elif kind == "scalar":
@@ -100,8 +103,29 @@ def random_graph(seed):
             merged = p * q if isinstance(p, int) and isinstance(q, int) else None
             if merged is not None:
                 add(b.op("Reshape", [t, tgt]), d[:-2] + [merged])
+        elif kind == "conv" and len(d) == 4 and isinstance(d[3], int):
+            k = rnd.choice([1, 3])                      # stride 1 and pad k // 2 keep the image dims
+            o = rnd.choice([4, 8, 16])
+            y = b.op("Conv", [t, weight([o, k, k, d[3]])], stride=1, pad=k // 2)
+            if rnd.random() < 0.6:
+                y = b.op("Add", [y, weight([o])])
+            if rnd.random() < 0.5:
+                y = b.op("Relu", [y])
+            add(y, d[:3] + [o])
+        elif kind == "pool" and len(d) == 4:
+            add(b.op(rnd.choice(["MaxPool", "AveragePool"]), [t], kernel=3, stride=1, pad=1), d)
+        elif kind == "groupnorm" and len(d) >= 2 and isinstance(d[-1], int) and d[-1] % 4 == 0:
+            add(b.op("GroupNorm", [t, weight([d[-1]]), weight([d[-1]])], groups=rnd.choice([1, 2, 4]), eps=1e-5), d)
+        elif kind == "gather" and len(d) >= 2 and d[0] == 8:
+            add(b.op("Gather", [t, idx], axis=0), ["B"] + d[1:])
+        elif kind == "expand":
+            cands = [(u, e) for u, e in pool if u != t and len(e) >= len(d) and broadcastable(d, e) and bshape(d, e) == e and e != d]
+            if cands:
+                u, e = rnd.choice(cands)
+                add(b.op("Expand", [t, b.op("Shape", [u], dtype="i64")]), e)
         elif kind == "cast":
-            add(b.op("Cast", [b.op("Cast", [t], dtype="bf16")], dtype="f32"), d)
+            other_dt = "bf16" if dtype == "f32" else "f32"
+            add(b.op("Cast", [b.op("Cast", [t], dtype=other_dt)], dtype=dtype), d)
     outs = {pool[-1][0]}
     outs.add(rnd.choice(pool[3:] or pool)[0])
     for k, t in enumerate(sorted(outs)):
@@ -117,7 +141,17 @@ def concrete(dims, sym):
     return tuple(sym[d] if isinstance(d, str) else d for d in dims)
 
 
-@pytest.mark.parametrize("seed", range(40))
+def make_inputs(g, shapes, sym, rs):
+    ins = {}
+    for t in g.inputs():
+        if g.tensors[t].dtype == "i64":
+            ins[t] = rs.randint(0, 8, size=(sym["B"],)).astype(np.int64)
+        else:
+            ins[t] = rs.randn(*concrete(shapes[t], sym))
+    return ins
+
+
+@pytest.mark.parametrize("seed", range(60))
 def test_random_graph_library_equals_oracle(seed):
     g, weights, shapes = random_graph(seed)
     if g is None:
@@ -141,7 +175,7 @@ def test_random_graph_library_equals_oracle(seed):
     # executed shapes == inferred shapes, values finite
     rs = np.random.RandomState(seed)
     sym = {"A": 3, "B": 5}
-    ins = {t: rs.randn(*concrete(shapes[t], sym)) for t in g.inputs()}
+    ins = make_inputs(g, shapes, sym, rs)
     W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
     po = P.build_plan(g, ro)
     ref = execute.run(g, po.order, W, ins)
