@@ -11,7 +11,12 @@ R1  Reshape, Slice, Transpose, Expand and Gather-with-a-scalar-host-index are *v
     their output aliases the input's storage; no kernel, no arena tensor.  One
     whose result is a graph output is a group of its own (COPY): the view is
     written out densely into the caller's buffer.  Likewise an operator with a
-    known value map is not folded when its result is a graph output.
+    known value map is not folded when its result is a graph output.  A view that
+    a kernel could not walk is a COPY group too (its result an arena tensor): a
+    strided view (a permutation, a slice or index of a dim other than the first,
+    an Expand, or a view of such a view) read by an operator whose kernel wants
+    dense operands (Concat, ReduceMean, pools, GroupNorm, Conv, ...), and a
+    permuted view read by LayerNorm or Softmax.
 R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     this order and each at most once: Mul by a host scalar; Add of a rank-1
     weight equal to the last dim (bias); activation; Add of a non-constant
@@ -96,6 +101,9 @@ MAX_SG = 14
 DT_BYTES = {"f32": 4, "bf16": 2, "i64": 8, "i32": 4}
 VIEW_KINDS = ("Reshape", "Slice", "Transpose", "Expand")
 ACTS = ("Relu", "Gelu", "Sigmoid")
+DENSE_ONLY = ("Concat", "ReduceMean", "MaxPool", "AveragePool", "GroupNorm", "Conv", "MaxUnpool", "Resize", "Upsample",
+              "ScatterRows", "TopK", "ArgMax", "NonZero", "NMS")        # operators whose kernels want dense operands
+ROW_OPS = ("LayerNorm", "Softmax")                 # a dense last dim and evenly spaced rows suffice: a permutation breaks that
 COUNTING = ("NonZero", "NMS")                  # execution-determined operators whose result has a length found by running
 COUNTING_GROUPS = ("NONZERO", "NMS")
 ELTWISE = ("Add", "Mul", "Relu", "Gelu", "Sigmoid", "Cast", "Round")
@@ -232,6 +240,40 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
         elif op.kind == "Gather":
             idx = g.tensors[op.inputs[1]]
             view[i] = idx.data is not None and idx.data.ndim == 0 and not to_caller
+
+    # R1, second half: a view that a kernel could not walk is written out.  Decided from the graph alone, in the node
+    # order so that a view of a view inherits: a view is *strided* when it permutes dims, slices or indexes a dim other
+    # than the first, or repeats elements (Expand); *permuted* when a Transpose is involved.
+    strided, permuted = [False] * nops, [False] * nops
+    for n in order:
+        if not view[n]:
+            continue
+        op = g.ops[n]
+        src = op.inputs[0]
+        pr = rdp.producer[src]
+        s_in = pr >= 0 and view[pr] and strided[pr]
+        p_in = pr >= 0 and view[pr] and permuted[pr]
+        rank = len(rdp.S[src]) if isinstance(rdp.S[src], list) else None
+        s = p = False
+        if op.kind == "Transpose":
+            s = p = list(op.attrs["perm"]) != list(range(len(op.attrs["perm"])))
+        elif op.kind == "Slice":
+            ax = rdp.V[op.inputs[3]]
+            known = rank is not None and isinstance(ax, list) and all(R.is_expr(e) and e.is_const() for e in ax)
+            s = not known or any(e.const_value() % rank != 0 for e in ax)
+        elif op.kind == "Expand":
+            s = True
+        elif op.kind == "Gather":
+            s = rank is None or op.attrs["axis"] % rank != 0
+        strided[n], permuted[n] = s or s_in, p or p_in
+        for c in rdp.consumers[op.outputs[0]]:
+            k = g.ops[c].kind
+            if folded[c]:
+                continue
+            if (k in DENSE_ONLY and strided[n]) or (k in ROW_OPS and permuted[n]):
+                view[n] = False                    # a COPY group: its result is dense
+                strided[n] = permuted[n] = False
+                break
 
     def sole_consumer(t) -> Optional[int]:
         if g.tensors[t].is_output or len(rdp.consumers[t]) != 1:

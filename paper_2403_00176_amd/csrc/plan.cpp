@@ -5,7 +5,9 @@
 //  R0 an operator whose outputs are integer tensors with a fully resolved value map is folded;
 //  R1 Reshape / Slice / Transpose / Expand / Gather-with-scalar-host-index are views (no kernel); one whose result is a
 //     graph output is a COPY group (the view written out densely into the caller's buffer), and an operator with a
-//     known value map is not folded when its result is a graph output;
+//     known value map is not folded when its result is a graph output; a strided view (a permutation, a slice or index
+//     of a dim other than the first, an Expand, or a view of one) read by an operator whose kernel wants dense operands,
+//     and a permuted view read by LayerNorm or Softmax, is a COPY group as well (its result an arena tensor);
 //  R2 MatMul / Conv absorbs, in order and each at most once: Mul by a host scalar, Add of a rank-1
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
@@ -54,6 +56,14 @@ bool is_view_kind(int k) { return k == SOD2_OP_RESHAPE || k == SOD2_OP_SLICE || 
 bool scalar_gather(const Graph& G, const Op& op) {     // Gather with a scalar host index: a view
   const Tensor& idx = G.tensors[op.in[1]];
   return idx.has_data && idx.host_rank == 0;
+}
+bool is_dense_only(int k) {                          // operators whose kernels want dense operands
+  switch (k) {
+    case SOD2_OP_CONCAT: case SOD2_OP_REDUCEMEAN: case SOD2_OP_MAXPOOL: case SOD2_OP_AVERAGEPOOL: case SOD2_OP_GROUPNORM:
+    case SOD2_OP_CONV: case SOD2_OP_MAXUNPOOL: case SOD2_OP_RESIZE: case SOD2_OP_UPSAMPLE: case SOD2_OP_SCATTERROWS:
+    case SOD2_OP_TOPK: case SOD2_OP_ARGMAX: case SOD2_OP_NONZERO: case SOD2_OP_NMS: return true;
+    default: return false;
+  }
 }
 bool is_control(int k) { return k == SOD2_OP_SWITCH || k == SOD2_OP_COMBINE; }
 bool is_counting(int k) { return k == SOD2_OP_NONZERO || k == SOD2_OP_NMS; }   // a result whose length is found by running
@@ -144,6 +154,45 @@ void Plan::build() {
     if (ints && known && !to_caller) folded[i] = 1;
     else if (is_view_kind(op.kind)) view[i] = !to_caller;
     else if (op.kind == SOD2_OP_GATHER) view[i] = scalar_gather(G, op) && !to_caller;
+  }
+  // R1, second half: a view that a kernel could not walk is written out.  In the node order, so that a view of a view
+  // inherits: strided = permutes dims, slices or indexes a dim other than the first, or repeats elements; permuted =
+  // a Transpose is involved.
+  {
+    std::vector<char> strided(nops, 0), permuted(nops, 0);
+    for (int n : order) {
+      if (!view[n]) continue;
+      const Op& op = G.ops[n];
+      const int src = op.in[0], pr = G.producer[src];
+      const bool s_in = pr >= 0 && view[pr] && strided[pr], p_in = pr >= 0 && view[pr] && permuted[pr];
+      const LS& ss = R.S[src];
+      const int64_t rank = ss.is_list() ? (int64_t)ss.d.size() : -1;
+      bool s = false, pm = false;
+      if (op.kind == SOD2_OP_TRANSPOSE) {
+        for (size_t i = 0; i < op.ia.size(); ++i) if (op.ia[i] != (int64_t)i) s = pm = true;
+      } else if (op.kind == SOD2_OP_SLICE) {
+        const LS& ax = R.V[op.in[3]];
+        bool known = rank > 0 && ax.is_list();
+        if (known) for (const auto& e : ax.d) if (!(e.val() && e.e.is_const())) known = false;
+        s = !known;
+        if (known) for (const auto& e : ax.d) if (((e.e.const_value() % rank) + rank) % rank != 0) s = true;
+      } else if (op.kind == SOD2_OP_EXPAND) {
+        s = true;
+      } else if (op.kind == SOD2_OP_GATHER) {
+        s = rank <= 0 || ((op.ia.at(0) % rank) + rank) % rank != 0;
+      }
+      strided[n] = s || s_in;
+      permuted[n] = pm || p_in;
+      for (int c2 : G.consumers[op.out[0]]) {
+        if (folded[c2]) continue;
+        const int k = G.ops[c2].kind;
+        if ((is_dense_only(k) && strided[n]) || ((k == SOD2_OP_LAYERNORM || k == SOD2_OP_SOFTMAX) && permuted[n])) {
+          view[n] = 0;                               // a COPY group: its result is dense
+          strided[n] = permuted[n] = 0;
+          break;
+        }
+      }
+    }
   }
 
   auto sole_consumer = [&](int t) -> int {

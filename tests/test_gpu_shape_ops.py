@@ -491,8 +491,8 @@ def test_views_as_graph_outputs_are_written_out(S_lib, dtype):
 def test_random_graphs_against_the_oracle(S_lib, dtype):
     """The seeded random graphs of tests/test_random_graphs.py (broadcasting chains, small contractions and
     convolutions with epilogues, row operators, pools, GroupNorm, views also as outputs, Concat, ReduceMean) through
-    the C ABI in fp32 and bf16: every output within the bar of the oracle's values, or the run refused with
-    "unsupported" before the group's kernel ran (a strided view handed to a kernel that wants dense operands)."""
+    the C ABI in fp32 and bf16: every output within the bar of the oracle's values.  None of these graphs is refused:
+    a strided view handed to an operator whose kernel wants dense operands is written out first (a COPY group)."""
     import torch
     from tests.test_random_graphs import random_graph, concrete, make_inputs
     from paper_2403_00176_amd.session import Session, to_host
@@ -530,4 +530,4 @@ def test_random_graphs_against_the_oracle(S_lib, dtype):
                 worst = max(worst, err)
                 assert err <= (1e-4 if dtype == "f32" else 2e-2), (seed, sym, g.tensors[t].name, err)
     print("random graphs", dtype, ": ran", ran, "refused", refused, "worst rel err", worst)
-    assert ran >= 60
+    assert ran >= 100 and refused == 0
