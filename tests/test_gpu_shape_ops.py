@@ -531,3 +531,47 @@ def test_random_graphs_against_the_oracle(S_lib, dtype):
                 assert err <= (1e-4 if dtype == "f32" else 2e-2), (seed, sym, g.tensors[t].name, err)
     print("random graphs", dtype, ": ran", ran, "refused", refused, "worst rel err", worst)
     assert ran >= 100 and refused == 0
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_wide_random_graphs_against_the_oracle(S_lib, dtype):
+    """The same generator with inner extents of 64 and more and up to 6400 rows: contractions on the tiled
+    matrix-core kernels with ragged row counts and every epilogue, the LayerNorm behind a contraction folded into
+    its neighbours (constants derived by the session), convolutions with 64 and 128 channels."""
+    import torch
+    from tests.test_random_graphs import random_graph, make_inputs
+    from paper_2403_00176_amd.session import Session, to_host
+    ran = folds = 0
+    worst = 0.0
+    for seed in range(16):
+        g, weights, shapes = random_graph(seed, dtype, wide=True)
+        if g is None:
+            continue
+        po = P.build_plan(g, R.RDP(g).analyse())
+        # a Cast to bf16 quantises: a value that the two sides compute a rounding error apart may fall on either side
+        # of a bf16 boundary, so behind such a Cast the bf16 bar applies also in an fp32 graph
+        narrowing = any(op.kind == "Cast" and g.tensors[op.outputs[0]].dtype == "bf16" for op in g.ops)
+        bar = 2e-4 if dtype == "f32" and not narrowing else 2e-2
+        ses = Session(g)
+        rs = np.random.RandomState(seed)
+        W = {t: rs.randn(*d) * (0.5 / np.sqrt(d[-1])) for t, d in weights.items()}
+        ses.upload_weights(W)
+        for sym in ({"A": 3, "B": 33}, {"A": 64, "B": 100}, {"A": 1, "B": 1}):
+            print(f"case wide random graph {dtype} seed {seed} {sym} groups {[gr.kind for gr in po.groups.values()]}", flush=True)
+            ins = make_inputs(g, shapes, sym, rs)
+            bnd = ses.bind(sym)
+            assert S_lib.sod2_binding_dump(bnd) == A.dump(A.bind(po, sym))
+            outs = ses.alloc_outputs(ses.output_shapes(bnd))
+            ses.run(bnd, ses.upload_inputs(ins), outs)
+            torch.cuda.synchronize()
+            ran += 1
+            folds += sum(1 for e in S_lib.sod2_run_trace(bnd) if e["is_group"] and e["fold"] == 2)
+            ref = execute.run(g, po.order, W, ins)
+            for t, o in zip(g.outputs(), outs):
+                got = to_host(o)
+                assert got.shape == ref.values[t].shape and np.isfinite(got).all()
+                err = rel_err(got, ref.values[t])
+                worst = max(worst, err)
+                assert err <= bar, (seed, sym, g.tensors[t].name, err)
+    print("wide random graphs", dtype, ": ran", ran, "LayerNorms finished in a contraction's epilogue", folds, "worst rel err", worst)
+    assert ran >= 40 and (dtype == "f32" or folds > 0)

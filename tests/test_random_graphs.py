@@ -13,9 +13,12 @@ from oracle import rdp as R, plan as P, arena as A, execute
 from workloads import GraphBuilder
 
 
-def random_graph(seed, dtype="f32"):
+def random_graph(seed, dtype="f32", wide=False):
+    """``wide``: inner extents of 64 and more and symbols up to 70 x 130, so that contractions take the tiled
+    matrix-core kernels with ragged row counts, epilogues and the LayerNorm-behind-a-contraction rule."""
     rnd = random.Random(seed)
-    b = GraphBuilder([("A", 1, 9), ("B", 1, 12)])
+    C0 = 64 if wide else 8                       # the inner extent of the inputs
+    b = GraphBuilder([("A", 1, 70), ("B", 1, 130)] if wide else [("A", 1, 9), ("B", 1, 12)])
     pool = []                                  # (tensor id, dims as tokens: "A", "B" or an int)
     weights = {}
 
@@ -28,10 +31,10 @@ def random_graph(seed, dtype="f32"):
         weights[t] = tuple(dims)
         return t
 
-    add(b.input("x0", dtype, ["A", "B", 8]), ["A", "B", 8])
-    add(b.input("x1", dtype, ["A", 1, 8]), ["A", 1, 8])
-    add(b.input("x2", dtype, ["B", 8]), ["B", 8])
-    add(b.input("img", dtype, [2, "A", "B", 8]), [2, "A", "B", 8])            # channels last
+    add(b.input("x0", dtype, ["A", "B", C0]), ["A", "B", C0])
+    add(b.input("x1", dtype, ["A", 1, C0]), ["A", 1, C0])
+    add(b.input("x2", dtype, ["B", C0]), ["B", C0])
+    add(b.input("img", dtype, [2, "A", "B", C0]), [2, "A", "B", C0])            # channels last
     idx = b.input("idx", "i64", ["B"])                                         # row numbers below 8
     n_const = [0]
 
@@ -53,7 +56,8 @@ def random_graph(seed, dtype="f32"):
     for _ in range(rnd.randint(6, 14)):
         t, d = rnd.choice(pool)
         kind = rnd.choice(["unary", "unary", "binary", "binary", "scalar", "matmul", "layernorm", "softmax", "transpose",
-                           "reduce", "concat", "slice", "flatten", "cast", "conv", "pool", "groupnorm", "gather", "expand"])
+                           "reduce", "concat", "slice", "flatten", "cast", "conv", "pool", "groupnorm", "gather", "expand"] +
+                          (["matmul", "matmul", "mlp", "mlp"] if wide else []))
         if kind == "unary":
             add(b.op(rnd.choice(["Relu", "Gelu", "Sigmoid", "Round"]), [t]), d)
         elif kind == "scalar":
@@ -65,13 +69,24 @@ def random_graph(seed, dtype="f32"):
                 args = [t, u] if rnd.random() < 0.5 else [u, t]
                 add(b.op(rnd.choice(["Add", "Mul"]), args), bshape(d, e))
         elif kind == "matmul" and isinstance(d[-1], int) and len(d) >= 2:
-            n = rnd.choice([4, 8, 16])
+            n = rnd.choice([64, 96, 136, 256] if wide else [4, 8, 16])
             y = b.op("MatMul", [t, weight([n, d[-1]])], transB=1)
             if rnd.random() < 0.6:
                 y = b.op("Add", [y, weight([n])])
             if rnd.random() < 0.4:
                 y = b.op(rnd.choice(["Relu", "Gelu"]), [y])
             add(y, d[:-1] + [n])
+        elif kind == "mlp" and isinstance(d[-1], int) and len(d) >= 2:
+            # contraction (+ bias, residual) -> LayerNorm -> contraction (+ bias, activation): the pair rule R9 looks for
+            n1, n2 = rnd.choice([64, 128, 192]), rnd.choice([64, 96, 256])
+            y = b.op("Add", [b.op("MatMul", [t, weight([n1, d[-1]])], transB=1), weight([n1])])
+            if n1 == d[-1] and rnd.random() < 0.5:
+                y = b.op("Add", [y, t])
+            y = b.op("LayerNorm", [y, weight([n1]), weight([n1])], eps=1e-5)
+            y = b.op("Add", [b.op("MatMul", [y, weight([n2, n1])], transB=1), weight([n2])])
+            if rnd.random() < 0.5:
+                y = b.op("Gelu", [y])
+            add(y, d[:-1] + [n2])
         elif kind == "layernorm" and isinstance(d[-1], int):
             add(b.op("LayerNorm", [t, weight([d[-1]]), weight([d[-1]])], eps=1e-5), d)
         elif kind == "softmax":
@@ -105,7 +120,7 @@ def random_graph(seed, dtype="f32"):
                 add(b.op("Reshape", [t, tgt]), d[:-2] + [merged])
         elif kind == "conv" and len(d) == 4 and isinstance(d[3], int):
             k = rnd.choice([1, 3])                      # stride 1 and pad k // 2 keep the image dims
-            o = rnd.choice([4, 8, 16])
+            o = rnd.choice([64, 128] if wide else [4, 8, 16])
             y = b.op("Conv", [t, weight([o, k, k, d[3]])], stride=1, pad=k // 2)
             if rnd.random() < 0.6:
                 y = b.op("Add", [y, weight([o])])
@@ -116,7 +131,7 @@ def random_graph(seed, dtype="f32"):
             add(b.op(rnd.choice(["MaxPool", "AveragePool"]), [t], kernel=3, stride=1, pad=1), d)
         elif kind == "groupnorm" and len(d) >= 2 and isinstance(d[-1], int) and d[-1] % 4 == 0:
             add(b.op("GroupNorm", [t, weight([d[-1]]), weight([d[-1]])], groups=rnd.choice([1, 2, 4]), eps=1e-5), d)
-        elif kind == "gather" and len(d) >= 2 and d[0] == 8:
+        elif kind == "gather" and len(d) >= 2 and isinstance(d[0], int) and d[0] >= 8:
             add(b.op("Gather", [t, idx], axis=0), ["B"] + d[1:])
         elif kind == "expand":
             cands = [(u, e) for u, e in pool if u != t and len(e) >= len(d) and broadcastable(d, e) and bshape(d, e) == e and e != d]
@@ -151,9 +166,12 @@ def make_inputs(g, shapes, sym, rs):
     return ins
 
 
+@pytest.mark.parametrize("wide", [False, True])
 @pytest.mark.parametrize("seed", range(60))
-def test_random_graph_library_equals_oracle(seed):
-    g, weights, shapes = random_graph(seed)
+def test_random_graph_library_equals_oracle(seed, wide):
+    if wide and seed >= 25:
+        pytest.skip("25 wide graphs")
+    g, weights, shapes = random_graph(seed, "bf16" if wide else "f32", wide)
     if g is None:
         pytest.skip("no operator survived the draw")
     lg = S.sod2_graph_build(g)
@@ -169,7 +187,7 @@ def test_random_graph_library_equals_oracle(seed):
         lp = S.sod2_plan(lg, lr, **opts)
         po = P.build_plan(g, ro, P.Opts(**{k: bool(v) for k, v in opts.items()}))
         assert S.sod2_plan_dump(lp) == P.dump(po), opts
-        for sym in ({"A": 1, "B": 1}, {"A": 3, "B": 7}, {"A": 9, "B": 12}):
+        for sym in ({"A": 1, "B": 1}, {"A": 3, "B": 7}, {"A": 70, "B": 130} if wide else {"A": 9, "B": 12}):
             bo = A.bind(po, sym)
             assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(bo), (opts, sym)
     # executed shapes == inferred shapes, values finite
