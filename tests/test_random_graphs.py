@@ -187,6 +187,15 @@ def test_random_graph_library_equals_oracle(seed, wide):
         for sym in ({"A": 1, "B": 1}, {"A": 3, "B": 7}, {"A": 70, "B": 130} if wide else {"A": 9, "B": 12}):
             bo = A.bind(po, sym)
             assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(bo), (opts, sym)
+            # the layout itself: tensors alive at the same step never share a byte, the arena is at least the peak
+            ts = sorted(bo.tensors.values(), key=lambda a: a.offset)
+            for i, x in enumerate(ts):
+                assert x.offset >= 0 and x.offset % 256 == 0 and x.offset + x.bytes <= bo.arena_bytes
+                for y in ts[i + 1:]:
+                    if y.offset >= x.offset + x.bytes:
+                        break
+                    assert x.end < y.start or y.end < x.start, (g.tensors[x.tid].name, g.tensors[y.tid].name, sym)
+            assert bo.arena_bytes >= bo.peak_live
     # executed shapes == inferred shapes, values finite
     rs = np.random.RandomState(seed)
     sym = {"A": 3, "B": 5}
