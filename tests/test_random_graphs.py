@@ -207,3 +207,42 @@ def test_random_graph_library_equals_oracle(seed, wide):
     for t in g.outputs():
         assert ref.values[t].shape == concrete(shapes[t], sym) == tuple(bo.dims[t])
         assert np.isfinite(ref.values[t]).all()
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_graph_with_an_undeclared_input(seed):
+    """One input loses its declared shape: what backward transfer recovers (and what it leaves nac) must be the same on
+    both sides, and so must the outcome of planning and binding: equal dumps, or the same kind of refusal."""
+    import copy
+    g, weights, shapes = random_graph(seed)
+    if g is None:
+        pytest.skip("no operator survived the draw")
+    g = copy.deepcopy(g)
+    floats = [t for t in g.inputs() if g.tensors[t].dtype != "i64"]
+    g.tensors[floats[seed % len(floats)]].dims = None
+    lg = S.sod2_graph_build(g)
+
+    def oracle():
+        ro = R.RDP(g).analyse()
+        po = P.build_plan(g, ro)
+        return R.dump(ro), P.dump(po), A.dump(A.bind(po, {"A": 3, "B": 7}))
+
+    def library():
+        lr = S.sod2_rdp_infer(lg)
+        lp = S.sod2_plan(lg, lr)
+        return S.sod2_rdp_dump(lr), S.sod2_plan_dump(lp), S.sod2_binding_dump(S.sod2_bind(lp, {"A": 3, "B": 7}))
+
+    def outcome(f):
+        try:
+            return ("ok",) + f()
+        except S.Sod2Error as e:
+            return ("refused", {-3: "mismatch", -4: "unresolved", -6: "unsupported"}.get(e.code, e.code))
+        except R.ShapeMismatch:
+            return ("refused", "mismatch")
+        except A.UnresolvedShape:
+            return ("refused", "unresolved")
+        except ValueError as e:                      # the oracle's "no grouping rule for ..."
+            assert "no grouping rule" in str(e)
+            return ("refused", "unsupported")
+
+    assert outcome(library) == outcome(oracle)
