@@ -74,7 +74,9 @@ enum { SOD2_INTER = 0, SOD2_INPUT = 1, SOD2_WEIGHT = 2, SOD2_HOSTCONST = 3 };
  *   decided in fp32 as intersection > threshold * ((area_a + area_b) - intersection); result: the kept boxes'
  *   indices in visiting order, int64, a vector whose length is known once the operator has run (handled like
  *   NonZero's count).  Switch: data, predicate (one float);
- *   two results: taken when predicate <= threshold, taken when predicate > threshold.               */
+ *   two results: taken when predicate <= threshold, taken when predicate > threshold.  Switch and Combine forward
+ *   storage and write none: their results must not be graph outputs (sod2_plan: SOD2_ERR_UNSUPPORTED; an operator
+ *   behind the Combine, e.g. a Cast to its own type, makes the copy).                                          */
 enum {
   SOD2_OP_SHAPE = 0, SOD2_OP_GATHER, SOD2_OP_CONCAT, SOD2_OP_RESHAPE, SOD2_OP_SLICE,
   SOD2_OP_TRANSPOSE, SOD2_OP_MATMUL, SOD2_OP_CONV, SOD2_OP_ADD, SOD2_OP_MUL, SOD2_OP_RELU,

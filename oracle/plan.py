@@ -15,8 +15,9 @@ R1  Reshape, Slice, Transpose, Expand and Gather-with-a-scalar-host-index are *v
     a kernel could not walk is a COPY group too (its result an arena tensor): a
     strided view (a permutation, a slice or index of a dim other than the first,
     an Expand, or a view of such a view) read by an operator whose kernel wants
-    dense operands (Concat, ReduceMean, pools, GroupNorm, Conv, ...), and a
-    permuted view read by LayerNorm or Softmax.
+    dense operands (Concat, ReduceMean, pools, GroupNorm, Conv, the table of a
+    Gather by an index tensor, ...), and a permuted view read by LayerNorm or
+    Softmax.
 R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     this order and each at most once: Mul by a host scalar; Add of a rank-1
     weight equal to the last dim (bias); activation; Add of a non-constant
@@ -229,6 +230,10 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     folded, view = [False] * nops, [False] * nops
     for i, op in enumerate(g.ops):
         if op.kind in ("Switch", "Combine"):
+            if any(g.tensors[o].is_output for o in op.outputs):
+                # control operators forward storage, they write none: nothing would reach the caller's buffer
+                raise ValueError("a graph output must not be the direct result of a Switch or Combine "
+                                 "(put an operator behind it: a Cast to its own type copies it)")
             continue
         outs_int = all(g.tensors[o].dtype in ("i64", "i32") for o in op.outputs)
         to_caller = any(g.tensors[o].is_output for o in op.outputs)      # its result must reach the caller's buffer
@@ -270,7 +275,8 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             k = g.ops[c].kind
             if folded[c]:
                 continue
-            if (k in DENSE_ONLY and strided[n]) or (k in ROW_OPS and permuted[n]):
+            table = k == "Gather" and not view[c] and g.ops[c].inputs[0] == op.outputs[0]     # rows picked by an index tensor
+            if ((k in DENSE_ONLY or table) and strided[n]) or (k in ROW_OPS and permuted[n]):
                 view[n] = False                    # a COPY group: its result is dense
                 strided[n] = permuted[n] = False
                 break

@@ -144,7 +144,14 @@ void Plan::build() {
   view.assign(nops, 0);
   for (int i = 0; i < nops; ++i) {
     const Op& op = G.ops[i];
-    if (is_control(op.kind)) { if (op.kind == SOD2_OP_SWITCH) ++n_switches; continue; }
+    if (is_control(op.kind)) {
+      for (int o : op.out)
+        if (G.tensors[o].is_output)            // control operators forward storage, they write none
+          throw Error(SOD2_ERR_UNSUPPORTED, "a graph output must not be the direct result of a Switch or Combine "
+                                            "(put an operator behind it: a Cast to its own type copies it)");
+      if (op.kind == SOD2_OP_SWITCH) ++n_switches;
+      continue;
+    }
     bool ints = true, known = true, to_caller = false;   // to_caller: its result must reach the caller's buffer
     for (int o : op.out) {
       if (!is_int(G.tensors[o].dtype)) ints = false;
@@ -186,7 +193,8 @@ void Plan::build() {
       for (int c2 : G.consumers[op.out[0]]) {
         if (folded[c2]) continue;
         const int k = G.ops[c2].kind;
-        if ((is_dense_only(k) && strided[n]) || ((k == SOD2_OP_LAYERNORM || k == SOD2_OP_SOFTMAX) && permuted[n])) {
+        const bool table = k == SOD2_OP_GATHER && !view[c2] && G.ops[c2].in[0] == op.out[0];   // rows picked by an index tensor
+        if (((is_dense_only(k) || table) && strided[n]) || ((k == SOD2_OP_LAYERNORM || k == SOD2_OP_SOFTMAX) && permuted[n])) {
           view[n] = 0;                               // a COPY group: its result is dense
           strided[n] = permuted[n] = 0;
           break;

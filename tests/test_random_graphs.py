@@ -13,9 +13,11 @@ from oracle import rdp as R, plan as P, arena as A, execute
 from workloads import GraphBuilder
 
 
-def random_graph(seed, dtype="f32", wide=False):
+def random_graph(seed, dtype="f32", wide=False, gates=False):
     """``wide``: inner extents of 64 and more and symbols up to 70 x 130, so that contractions take the tiled
-    matrix-core kernels with ragged row counts, epilogues and the LayerNorm-behind-a-contraction rule."""
+    matrix-core kernels with ragged row counts, epilogues and the LayerNorm-behind-a-contraction rule.
+    ``gates``: <Switch, Combine> pairs around short branches, each decided by a one-element graph input (so that a
+    test sets the decisions exactly)."""
     rnd = random.Random(seed)
     C0 = 64 if wide else 8                       # the inner extent of the inputs
     b = GraphBuilder([("A", 1, 70), ("B", 1, 130)] if wide else [("A", 1, 9), ("B", 1, 12)])
@@ -57,8 +59,28 @@ def random_graph(seed, dtype="f32", wide=False):
         t, d = rnd.choice(pool)
         kind = rnd.choice(["unary", "unary", "binary", "binary", "scalar", "matmul", "layernorm", "softmax", "transpose",
                            "reduce", "concat", "slice", "flatten", "cast", "conv", "pool", "groupnorm", "gather", "expand"] +
-                          (["matmul", "matmul", "mlp", "mlp"] if wide else []))
-        if kind == "unary":
+                          (["matmul", "matmul", "mlp", "mlp"] if wide else []) + (["gate"] * 4 if gates else []))
+        if kind == "gate" and b.g.tensors[t].dtype == dtype:
+            n_gates = sum(1 for op in b.g.ops if op.kind == "Switch")
+            pred = b.input(f"p{n_gates}", "f32", [1])
+            taken, other = b.op("Switch", [t, pred], n_out=2, threshold=0.5)
+
+            def branch(x, n_ops):
+                for _ in range(n_ops):
+                    c = rnd.choice(["unary", "scalar", "softmax", "layernorm"])
+                    if c == "unary":
+                        x = b.op(rnd.choice(["Relu", "Gelu", "Sigmoid"]), [x])
+                    elif c == "scalar":
+                        x = b.op(rnd.choice(["Add", "Mul"]), [x, const(rnd.choice([0.5, 2.0, -1.0]), "f32")])
+                    elif c == "softmax":
+                        x = b.op("Softmax", [x], causal=0)
+                    elif isinstance(d[-1], int):
+                        x = b.op("LayerNorm", [x, weight([d[-1]]), weight([d[-1]])], eps=1e-5)
+                return x
+            merged = b.op("Combine", [branch(taken, rnd.randint(1, 3)), branch(other, rnd.randint(0, 2))])
+            # (a Combine forwards storage and writes none: behind it an operator, so that the result may be an output)
+            add(b.op("Cast", [merged], dtype=dtype) if rnd.random() < 0.5 else b.op("Relu", [merged]), d)
+        elif kind == "unary":
             add(b.op(rnd.choice(["Relu", "Gelu", "Sigmoid", "Round"]), [t]), d)
         elif kind == "scalar":
             add(b.op(rnd.choice(["Add", "Mul"]), [t, const(rnd.choice([0.5, 2.0, -1.0]), "f32")]), d)
@@ -161,6 +183,8 @@ def make_inputs(g, shapes, sym, rs):
     for t in g.inputs():
         if g.tensors[t].dtype == "i64":
             ins[t] = rs.randint(0, 8, size=(sym["B"],)).astype(np.int64)
+        elif g.tensors[t].name.startswith("p") and g.tensors[t].name[1:].isdigit():
+            ins[t] = np.array([float(rs.randint(0, 2))])              # a gate's predicate: 0 or 1 against the threshold 0.5
         else:
             ins[t] = rs.randn(*concrete(shapes[t], sym))
     return ins
@@ -246,3 +270,57 @@ def test_random_graph_with_an_undeclared_input(seed):
             return ("refused", "unsupported")
 
     assert outcome(library) == outcome(oracle)
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_graph_with_gates(seed):
+    """<Switch, Combine> pairs in random places: the analysis (a Combine merges its branches), the partition around the
+    control operators, and the plan for every decision vector tried -- the one a run of the oracle takes on random
+    predicates, all-run, all-skip -- agree between the library and the oracle; the plan with nothing decided binds."""
+    g, weights, shapes = random_graph(seed, gates=True)
+    if g is None or not any(op.kind == "Switch" for op in g.ops):
+        pytest.skip("no gate in this draw")
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    ro = R.RDP(g).analyse()
+    assert S.sod2_rdp_dump(lr) == R.dump(ro)
+    lp = S.sod2_plan(lg, lr)
+    po = P.build_plan(g, ro)
+    assert S.sod2_plan_dump(lp) == P.dump(po)
+    n_sw = sum(1 for op in g.ops if op.kind == "Switch")
+    rs = np.random.RandomState(seed)
+    sym = {"A": 3, "B": 5}
+    W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
+    vectors = [[False] * n_sw, [True] * n_sw]
+    for _ in range(3):
+        ref = execute.run(g, po.order, W, make_inputs(g, shapes, sym, rs))
+        assert len(ref.decisions) == n_sw                # gates are never nested here: every Switch executes
+        vectors.append(list(ref.decisions))
+        for t in g.outputs():
+            assert ref.values[t].shape == concrete(shapes[t], sym)
+    for dec in vectors:
+        assert S.sod2_binding_dump(S.sod2_bind(lp, sym, decisions=dec)) == A.dump(A.bind(po, sym, dec)), dec
+    arena, peak = S.sod2_binding_arena_bytes(S.sod2_bind(lp, sym))     # nothing decided yet: every branch is planned
+    assert arena >= peak > 0
+
+
+def test_control_results_cannot_be_graph_outputs():
+    """A Switch or Combine forwards storage and writes none; as a graph output its result would never reach the
+    caller's buffer.  Both planners refuse such a graph, and accept it with a Cast behind the Combine."""
+    def graph(cast):
+        b = GraphBuilder([("A", 1, 9)])
+        x = b.input("x", "f32", ["A", 8])
+        run, skip = b.op("Switch", [x, b.input("p", "f32", [1])], n_out=2, threshold=0.5)
+        y = b.op("Combine", [b.op("Relu", [run]), skip])
+        b.mark_output(b.op("Cast", [y], dtype="f32") if cast else y, "y")
+        return b.build()
+    g = graph(False)
+    with pytest.raises(ValueError):
+        P.build_plan(g, R.RDP(g).analyse())
+    lg = S.sod2_graph_build(g)
+    with pytest.raises(S.Sod2Error) as e:
+        S.sod2_plan(lg, S.sod2_rdp_infer(lg))
+    assert e.value.code == -6
+    g = graph(True)
+    lg = S.sod2_graph_build(g)
+    assert S.sod2_plan_dump(S.sod2_plan(lg, S.sod2_rdp_infer(lg))) == P.dump(P.build_plan(g, R.RDP(g).analyse()))
