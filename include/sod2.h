@@ -156,8 +156,8 @@ typedef struct sod2_binding_s sod2_binding_t;
 
 /* -- graph (Section 4.1, G; Section 3 classes) -------------------------------------------- */
 /* Copies the description.  SOD2_ERR_INVALID_ARG for what no later stage could make sense of: tensor ids out of
- * range, a tensor written twice, an operator on a cycle or unreachable from the inputs (the operators must form a
- * DAG), a wrong input / output count, attributes out of their range (a Transpose attribute that is no permutation,
+ * range, a tensor written twice, a graph output that no operator produces, an operator on a cycle or unreachable
+ * from the inputs (the operators must form a DAG), a wrong input / output count, attributes out of their range (a Transpose attribute that is no permutation,
  * a window with kernel < 1, stride < 1 or pad >= kernel, ...).  Shapes that contradict each other are found by
  * sod2_rdp_infer / sod2_plan (SOD2_ERR_SHAPE_MISMATCH); extents that are negative, or tensors beyond 2^44 bytes, at
  * the symbols of a call by sod2_bind (SOD2_ERR_SHAPE_MISMATCH). */

@@ -226,6 +226,9 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     pos = {n: i for i, n in enumerate(order)}
     nops = len(g.ops)
 
+    for t, d in enumerate(g.tensors):
+        if d.is_output and rdp.producer[t] < 0:
+            raise ValueError(f"graph output {d.name} is produced by no operator")
     # R0 / R1 ---------------------------------------------------------------
     folded, view = [False] * nops, [False] * nops
     for i, op in enumerate(g.ops):

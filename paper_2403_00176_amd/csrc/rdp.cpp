@@ -66,6 +66,10 @@ void Graph::finish() {
   for (const Op& op : ops)
     if (op.kind == SOD2_OP_CACHEAPPEND && !tensors[op.in[0]].session)
       throw Error(SOD2_ERR_UNSUPPORTED, "CacheAppend must extend a session tensor");
+  for (int t = 0; t < nt; ++t)
+    if (tensors[t].is_output && producer[t] < 0)
+      throw Error(SOD2_ERR_INVALID_ARG, "graph output " + tensors[t].name + " is produced by no operator (an input, a weight or a "
+                                        "dangling tensor cannot be an output: nothing would write the caller's buffer)");
   // the operators must form a directed acyclic graph: in the node order every input is produced earlier
   std::vector<int> order = sorted_nodes();
   std::vector<int> pos(ops.size(), -1);

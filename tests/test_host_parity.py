@@ -341,6 +341,19 @@ def test_malformed_graphs_are_refused_not_crashed():
     with pytest.raises(S.Sod2Error):
         S.sod2_graph_build(g)
 
+    # an output that no operator produces (a graph input, a weight, a dangling tensor): nothing would write it
+    for what in ("input", "weight", "dangling"):
+        gb = GraphBuilder([("A", 1, 9)])
+        x = gb.input("x", "f32", ["A", 8])
+        wt = gb.weight("w", "f32", [8])
+        gb.mark_output(gb.op("Add", [x, wt]), "y")
+        gb.mark_output({"input": x, "weight": wt, "dangling": gb._tmp("f32", "lost")}[what])
+        with pytest.raises(S.Sod2Error) as e:
+            S.sod2_graph_build(gb.build())
+        assert e.value.code == -1 and "produced by no operator" in str(e.value)
+        with pytest.raises(ValueError):
+            P.build_plan(gb.build(), R.RDP(gb.build()).analyse())
+
     # extents at the bound symbols: a window larger than its input gives an empty or a negative extent (the latter is
     # refused), a tensor beyond 2^44 bytes is refused before any byte count can overflow
     gb = GraphBuilder([("H", 1, 2 ** 40)])
