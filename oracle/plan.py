@@ -16,8 +16,9 @@ R1  Reshape, Slice, Transpose, Expand and Gather-with-a-scalar-host-index are *v
     strided view (a permutation, a slice or index of a dim other than the first,
     an Expand, or a view of such a view) read by an operator whose kernel wants
     dense operands (Concat, ReduceMean, pools, GroupNorm, Conv, the table of a
-    Gather by an index tensor, ...), and a permuted view read by LayerNorm or
-    Softmax.
+    Gather by an index tensor, ...), and a permuted view read by LayerNorm,
+    Softmax or Reshape (regrouping the dims of a permutation needs its elements
+    in the new order).
 R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     this order and each at most once: Mul by a host scalar; Add of a rank-1
     weight equal to the last dim (bias); activation; Add of a non-constant
@@ -279,7 +280,7 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             if folded[c]:
                 continue
             table = k == "Gather" and not view[c] and g.ops[c].inputs[0] == op.outputs[0]     # rows picked by an index tensor
-            if ((k in DENSE_ONLY or table) and strided[n]) or (k in ROW_OPS and permuted[n]):
+            if ((k in DENSE_ONLY or table) and strided[n]) or (k in ROW_OPS + ("Reshape",) and permuted[n]):
                 view[n] = False                    # a COPY group: its result is dense
                 strided[n] = permuted[n] = False
                 break

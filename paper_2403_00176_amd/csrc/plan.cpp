@@ -7,7 +7,7 @@
 //     graph output is a COPY group (the view written out densely into the caller's buffer), and an operator with a
 //     known value map is not folded when its result is a graph output; a strided view (a permutation, a slice or index
 //     of a dim other than the first, an Expand, or a view of one) read by an operator whose kernel wants dense operands,
-//     and a permuted view read by LayerNorm or Softmax, is a COPY group as well (its result an arena tensor);
+//     and a permuted view read by LayerNorm, Softmax or Reshape, is a COPY group as well (its result an arena tensor);
 //  R2 MatMul / Conv absorbs, in order and each at most once: Mul by a host scalar, Add of a rank-1
 //     weight equal to the last dim, an activation, Add of a non-constant tensor of proven-equal
 //     shape, an activation, a Transpose (stored permuted); each absorbed operator must be the sole
@@ -194,7 +194,8 @@ void Plan::build() {
         if (folded[c2]) continue;
         const int k = G.ops[c2].kind;
         const bool table = k == SOD2_OP_GATHER && !view[c2] && G.ops[c2].in[0] == op.out[0];   // rows picked by an index tensor
-        if (((is_dense_only(k) || table) && strided[n]) || ((k == SOD2_OP_LAYERNORM || k == SOD2_OP_SOFTMAX) && permuted[n])) {
+        if (((is_dense_only(k) || table) && strided[n]) ||
+            ((k == SOD2_OP_LAYERNORM || k == SOD2_OP_SOFTMAX || k == SOD2_OP_RESHAPE) && permuted[n])) {
           view[n] = 0;                               // a COPY group: its result is dense
           strided[n] = permuted[n] = 0;
           break;

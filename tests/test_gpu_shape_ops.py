@@ -463,10 +463,15 @@ def test_views_as_graph_outputs_are_written_out(S_lib, dtype):
     b.mark_output(b.op("Gather", [y, b.const("i3", 3)], axis=2), "column")
     b.mark_output(b.op("Expand", [b.op("ReduceMean", [y], axes=(1,), keepdims=1), shp]), "expanded")
     b.mark_output(b.op("Relu", [t]), "relu_of_view")                                  # the view is also read
+    # a permutation regrouped by a Reshape: [A, B, 8] -> [B, A, 8] -> [B, A * 8] needs the elements in the new order
+    yt = b.op("Transpose", [y], perm=(1, 0, 2))
+    lead_t = b.op("Slice", [b.op("Shape", [yt], dtype="i64"), b.const("t0", [0]), b.const("t1", [1]), b.const("tax", [0])], dtype="i64")
+    b.mark_output(b.op("Relu", [b.op("Reshape", [yt, b.op("Concat", [lead_t, b.const("tm1", [-1])], axis=0, dtype="i64")])]),
+                  "regrouped")
     b.mark_output(b.op("Transpose", [x], perm=(1, 0, 2)), "input_transposed")         # a view of a graph input
     g = b.build()
     po = P.build_plan(g, R.RDP(g).analyse())
-    assert sum(1 for gr in po.groups.values() if gr.kind == "COPY") == 6
+    assert sum(1 for gr in po.groups.values() if gr.kind == "COPY") == 7
     ses = Session(g)
     ses.upload_weights({})
     for k, sym in enumerate(({"A": 1, "B": 1}, {"A": 3, "B": 5}, {"A": 40, "B": 33})):
