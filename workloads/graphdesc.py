@@ -142,6 +142,12 @@ class GraphBuilder:
         return self._add(TensorDesc(f"{hint}_{self._n}", dtype))
 
     def mark_output(self, tid: int, name: Optional[str] = None) -> int:
+        # Switch and Combine forward storage and write none: as a graph output their result gets a Cast to its own
+        # type behind it, which makes the copy into the caller's buffer (the planners refuse the bare form)
+        for op in self.g.ops:
+            if op.kind in ("Switch", "Combine") and tid in op.outputs:
+                tid = self.op("Cast", [tid], dtype=self.g.tensors[tid].dtype, hint="out")
+                break
         self.g.tensors[tid].is_output = True
         if name:
             self.g.tensors[tid].name = name
