@@ -907,9 +907,10 @@ __global__ __launch_bounds__(NMS_THREADS) void nms_kernel(NmsArgs a) {
 
 // The same result from three kernels, for many boxes and a workspace to hold the suppression matrix: the pair tests
 // are spread over the chip instead of running on one CU.  Workspace: the boxes in visiting order, their indices, and
-// the matrix as 64 x 64-bit tiles, tile (rb, cb) = which of the 64 boxes of column block cb each box of row block rb
-// suppresses (only cb >= rb is written and read).
-constexpr long long NMS_WS_BOX = 0, NMS_WS_IDX = 64 << 10, NMS_WS_MASK = 128 << 10;
+// the matrix as 64 x 64-bit tiles, stored by column: word c of tile (rb, cb) = which of the 64 boxes of row block rb
+// suppress box c of column block cb (only cb >= rb is written and read); for the diagonal tiles also by row
+// (word r = which boxes of the block box r suppresses), which is what resolving a block needs.
+constexpr long long NMS_WS_BOX = 0, NMS_WS_IDX = 64 << 10, NMS_WS_OWN = 96 << 10, NMS_WS_MASK = 128 << 10;
 constexpr long long NMS_WS_BYTES = NMS_WS_MASK + (long long)NMS_MAX_BOXES * (NMS_MAX_BOXES / 64) * 8;
 static_assert(NMS_WS_BYTES <= WS_BYTES, "the suppression matrix must fit the workspace");
 
@@ -947,88 +948,111 @@ __global__ __launch_bounds__(NMS_THREADS) void nms_sort_kernel(NmsArgs a) {
   }
 }
 
-// grid (column block, row block), 64 threads: thread t owns row rb * 64 + t of the tile
+// grid (column block, row block), 64 threads: thread t owns column cb * 64 + t of the tile (and, on the diagonal,
+// row rb * 64 + t as well)
 __global__ __launch_bounds__(64) void nms_mask_kernel(NmsArgs a) {
-  __shared__ float4 cbox[64];
+  __shared__ float4 rbox[64];
   const int cb = blockIdx.x, rb = blockIdx.y, t = threadIdx.x;
   if (cb < rb) return;
   const float4* sbox = (const float4*)(a.ws + NMS_WS_BOX);
   const int W = (a.n + 63) >> 6;
-  const int i = rb * 64 + t, jc = cb * 64 + t;
-  cbox[t] = jc < a.n ? sbox[jc] : make_float4(0.f, 0.f, 0.f, 0.f);
+  const int ir = rb * 64 + t, j = cb * 64 + t;
+  rbox[t] = ir < a.n ? sbox[ir] : make_float4(0.f, 0.f, 0.f, 0.f);
   __syncthreads();
+  const int r_end = min(64, a.n - rb * 64);
   unsigned long long word = 0;
-  if (i < a.n) {
-    const float4 bi = sbox[i];
-    const int c_end = min(64, a.n - cb * 64);
-    for (int c = 0; c < c_end; ++c)
-      if (cb * 64 + c > i && nms_overlaps(bi, cbox[c], a.iou)) word |= 1ull << c;
+  if (j < a.n) {
+    const float4 bj = sbox[j];
+    for (int r = 0; r < r_end; ++r)
+      if (rb * 64 + r < j && nms_overlaps(rbox[r], bj, a.iou)) word |= 1ull << r;
   }
   ((unsigned long long*)(a.ws + NMS_WS_MASK))[((long long)rb * W + cb) * 64 + t] = word;
+  if (cb == rb) {                                      // by row: the boxes of the block that box t suppresses
+    unsigned long long own = 0;
+    if (ir < a.n) {
+      const float4 bi = rbox[t];
+      for (int c = t + 1; c < r_end; ++c)
+        if (nms_overlaps(bi, rbox[c], a.iou)) own |= 1ull << c;
+    }
+    ((unsigned long long*)(a.ws + NMS_WS_OWN))[ir] = own;
+  }
 }
 
-// One workgroup of 4 waves walks the blocks in order.  `dead` (wave 0, lane w = column block w) collects the boxes
-// suppressed so far; for a block, wave 0 holds its 64 matrix rows in registers (lane w: the words of column block w),
-// decides which boxes of the block are kept with scalar operations (only the block's own columns matter for that)
-// and then ORs the kept rows into `dead`; meanwhile every thread already holds its share of the next block's rows.
-// A block costs about 4 us, the ~2000 instructions one wave executes for it (fetching two blocks ahead changes nothing).
-constexpr int NMS_SCAN_THREADS = 256;
+// One workgroup of 4 waves walks the blocks in order; dead[w] = the boxes of block w suppressed so far.  Per block:
+// wave 0 decides with scalar operations which boxes are kept (a box not yet dead is kept and kills what its own row
+// names) and writes their indices; then every wave, for its share of the column blocks behind, turns the block's
+// column words into the newly suppressed boxes with one ballot each (box c dies when a kept box is among the rows
+// its word names).  The column words of the next block are requested before the current one is resolved.
+constexpr int NMS_SCAN_THREADS = 256, NMS_SCAN_WAVES = NMS_SCAN_THREADS / 64, NMS_SCAN_PT = 64 / NMS_SCAN_WAVES;
 __global__ __launch_bounds__(NMS_SCAN_THREADS) void nms_scan_kernel(NmsArgs a) {
-  __shared__ unsigned long long rows[64][65];          // [row of the block][column block], padded against bank conflicts
+  __shared__ unsigned long long dead[64];
+  __shared__ unsigned long long kept_s;
   __shared__ int stop;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int W = (a.n + 63) >> 6;
   const unsigned long long* mask = (const unsigned long long*)(a.ws + NMS_WS_MASK);
+  const unsigned long long* ownm = (const unsigned long long*)(a.ws + NMS_WS_OWN);
   const unsigned* sidx = (const unsigned*)(a.ws + NMS_WS_IDX);
-  constexpr int PT = 64 * 64 / NMS_SCAN_THREADS;       // words of a block's rows per thread
-  unsigned long long nxt[PT];
-  auto fetch = [&](int b) {                            // tile (b, cb), word r  ->  element e = cb * 64 + r of the block
+  unsigned long long cur[NMS_SCAN_PT], nxt[NMS_SCAN_PT], own_nxt = 0;
+  unsigned idx_nxt = 0;
+  auto fetch = [&](int b) {                            // column words of tiles (b, w), w = b + wave, b + wave + 4, ...
 #pragma unroll
-    for (int u = 0; u < PT; ++u) {
-      const int e = tid + u * NMS_SCAN_THREADS, cb = e >> 6;
-      nxt[u] = (cb >= b && cb < W) ? mask[((long long)b * W + cb) * 64 + (e & 63)] : 0ull;
+    for (int u = 0; u < NMS_SCAN_PT; ++u) {
+      const int w = b + wave + u * NMS_SCAN_WAVES;
+      nxt[u] = (b < W && w < W) ? mask[((long long)b * W + w) * 64 + lane] : 0ull;
+    }
+    if (wave == 0 && b < W) {
+      own_nxt = ownm[b * 64 + lane];
+      idx_nxt = b * 64 + lane < a.n ? sidx[b * 64 + lane] : 0u;
     }
   };
+  if (tid < 64) dead[tid] = 0;
   if (tid == 0) stop = 0;
-  unsigned long long dead = 0;
   int count = 0;
-  if (W > 0) fetch(0);
+  fetch(0);
+  __syncthreads();
   for (int b = 0; b < W; ++b) {
 #pragma unroll
-    for (int u = 0; u < PT; ++u) {
-      const int e = tid + u * NMS_SCAN_THREADS;
-      rows[e & 63][e >> 6] = nxt[u];
-    }
-    __syncthreads();
-    if (b + 1 < W) fetch(b + 1);
+    for (int u = 0; u < NMS_SCAN_PT; ++u) cur[u] = nxt[u];
+    const unsigned long long own = own_nxt;
+    const unsigned my_idx = idx_nxt;
+    fetch(b + 1);
     if (wave == 0) {
       const int nb = min(64, a.n - b * 64);
-      unsigned long long row[64];
-#pragma unroll
-      for (int r = 0; r < 64; ++r) row[r] = rows[r][lane];
-      // the serial part runs on scalars: lane r's word of the block's own columns, and the block's word of `dead`
-      const unsigned long long own = rows[lane][b];
       const int olo = (int)(unsigned)own, ohi = (int)(unsigned)(own >> 32);
-      unsigned long long cur = (unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)dead, b) |
-                               ((unsigned long long)(unsigned)__builtin_amdgcn_readlane((int)(unsigned)(dead >> 32), b) << 32);
+      // (scalar values throughout: read through lane 0 so that the compiler keeps the walk on the scalar unit, and
+      //  without branches: a taken branch costs more than the few operations it would skip)
+      const unsigned long long d0 = dead[b];
+      unsigned long long gone = (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)d0) |
+                                ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(unsigned)(d0 >> 32)) << 32);
+      if (nb < 64) gone |= ~0ull << nb;                // positions behind the last box count as dead
+      const int lim = a.max_out > 0 ? a.max_out : 0x7fffffff;
       unsigned long long kept = 0;
       int cnt = count;
 #pragma unroll
       for (int r = 0; r < 64; ++r) {
         const unsigned long long w = (unsigned long long)(unsigned)__builtin_amdgcn_readlane(olo, r) |
                                      ((unsigned long long)(unsigned)__builtin_amdgcn_readlane(ohi, r) << 32);
-        if (r < nb && !((cur >> r) & 1) && !(a.max_out > 0 && cnt >= a.max_out)) {
-          kept |= 1ull << r;
-          ++cnt;
-          cur |= w;
-        }
+        const unsigned long long take = (~(gone >> r) & 1ull) & (unsigned long long)(cnt < lim);   // 0 or 1
+        const unsigned long long m = 0ull - take;                                                    // 0 or all ones
+        kept |= (1ull << r) & m;
+        gone |= w & m;
+        cnt += (int)take;
       }
-#pragma unroll
-      for (int r = 0; r < 64; ++r)
-        if ((kept >> r) & 1) dead |= row[r];           // (the same branch in every lane)
-      if ((kept >> lane) & 1) a.out[count + __popcll(kept & ((1ull << lane) - 1))] = (long long)sidx[b * 64 + lane];
+      if ((kept >> lane) & 1) a.out[count + __popcll(kept & ((1ull << lane) - 1))] = (long long)my_idx;
       count = cnt;
-      if (lane == 0 && a.max_out > 0 && count >= a.max_out) stop = 1;
+      if (lane == 0) {
+        kept_s = kept;
+        if (a.max_out > 0 && count >= a.max_out) stop = 1;
+      }
+    }
+    __syncthreads();
+    const unsigned long long kept = kept_s;
+#pragma unroll
+    for (int u = 0; u < NMS_SCAN_PT; ++u) {
+      const int w = b + wave + u * NMS_SCAN_WAVES;
+      const unsigned long long hit = __ballot((cur[u] & kept) != 0);
+      if (w < W && lane == 0) dead[w] |= hit;          // (a column block belongs to one wave)
     }
     __syncthreads();
     if (stop) break;
