@@ -492,8 +492,9 @@ def test_views_as_graph_outputs_are_written_out(S_lib, dtype):
                 assert np.array_equal(got, ref.values[t_]), (g.tensors[t_].name, sym)
 
 
+@pytest.mark.parametrize("opts", [{}, {"fusion": 0}, {"sep": 0, "inplace": 0}], ids=["default", "unfused", "node-order-no-inplace"])
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-def test_random_graphs_against_the_oracle(S_lib, dtype):
+def test_random_graphs_against_the_oracle(S_lib, dtype, opts):
     """The seeded random graphs of tests/test_random_graphs.py (broadcasting chains, small contractions and
     convolutions with epilogues, row operators, pools, GroupNorm, views also as outputs, Concat, ReduceMean) through
     the C ABI in fp32 and bf16: every output within the bar of the oracle's values.  None of these graphs is refused:
@@ -507,8 +508,8 @@ def test_random_graphs_against_the_oracle(S_lib, dtype):
         g, weights, shapes = random_graph(seed, dtype)
         if g is None:
             continue
-        po = P.build_plan(g, R.RDP(g).analyse())
-        ses = Session(g)
+        po = P.build_plan(g, R.RDP(g).analyse(), P.Opts(**{k: bool(v) for k, v in opts.items()}))
+        ses = Session(g, **opts)
         rs = np.random.RandomState(seed)
         W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
         ses.upload_weights(W)
