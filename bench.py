@@ -226,7 +226,7 @@ def main():
                     help="optimisation breakdown: the same calls with fusion, execution planning, memory planning and "
                          "kernel versions switched on one after the other")
     ap.add_argument("--no-other-configs", action="store_true",
-                    help="the default line (config 2) also carries a short run of configs 1, 3, 4 and 5 (field "
+                    help="the default line (config 2) also carries a short run of configs 1, 3, 4, 5, 6 and 7 (field "
                          "other_configs), each in a child process started before this one touches the GPU; this switches it off")
     ap.add_argument("--gemm-table", action="store_true",
                     help="the four weight contractions of config 2 at M = 1024, 2048, 4096, each a graph of its own")
@@ -245,7 +245,8 @@ def main():
     if args.config == 2 and not (args.ablation or args.gemm_table or args.no_other_configs or args.calibration_copy_mb):
         import subprocess
         other = {}
-        for c, extra in ((1, ["--steps", "16"]), (3, ["--steps", "16"]), (4, ["--steps", "16"]), (5, ["--steps", "2"])):
+        for c, extra in ((1, ["--steps", "16"]), (3, ["--steps", "16"]), (4, ["--steps", "16"]), (5, ["--steps", "2"]),
+                         (6, ["--steps", "16"]), (7, ["--steps", "16"])):
             cmd = [sys.executable, os.path.abspath(__file__), "--config", str(c), "--warmup", "2", "--cpu-seconds", "0",
                    "--no-other-configs"] + extra
             try:
