@@ -13,11 +13,12 @@ from oracle import rdp as R, plan as P, arena as A, execute
 from workloads import GraphBuilder
 
 
-def random_graph(seed, dtype="f32", wide=False, gates=False):
+def random_graph(seed, dtype="f32", wide=False, gates=False, compact=False):
     """``wide``: inner extents of 64 and more and symbols up to 70 x 130, so that contractions take the tiled
     matrix-core kernels with ragged row counts, epilogues and the LayerNorm-behind-a-contraction rule.
     ``gates``: <Switch, Combine> pairs around short branches, each decided by a one-element graph input (so that a
-    test sets the decisions exactly)."""
+    test sets the decisions exactly).  ``compact``: rows picked by NonZero of a 0 / 1 graph input, a short branch on
+    the picked rows only, ScatterRows back (batch compaction with an execution-determined row count)."""
     rnd = random.Random(seed)
     C0 = 64 if wide else 8                       # the inner extent of the inputs
     b = GraphBuilder([("A", 1, 70), ("B", 1, 130)] if wide else [("A", 1, 9), ("B", 1, 12)])
@@ -59,8 +60,25 @@ def random_graph(seed, dtype="f32", wide=False, gates=False):
         t, d = rnd.choice(pool)
         kind = rnd.choice(["unary", "unary", "binary", "binary", "scalar", "matmul", "layernorm", "softmax", "transpose",
                            "reduce", "concat", "slice", "flatten", "cast", "conv", "pool", "groupnorm", "gather", "expand"] +
-                          (["matmul", "matmul", "mlp", "mlp"] if wide else []) + (["gate"] * 4 if gates else []))
-        if kind == "gate" and b.g.tensors[t].dtype == dtype:
+                          (["matmul", "matmul", "mlp", "mlp"] if wide else []) + (["gate"] * 4 if gates else []) + (["compact"] * 4 if compact else []))
+        if kind == "compact" and b.g.tensors[t].dtype == dtype and len(d) >= 2 and d[0] in ("A", "B"):
+            n_masks = sum(1 for op in b.g.ops if op.kind == "NonZero")
+            mask = b.input(f"m{n_masks}{d[0]}", "f32", [d[0]])                     # 0 / 1 per row
+            nz = b.op("NonZero", [mask], dtype="i64")                               # [1, count]
+            rows = b.op("Gather", [nz, const(0)], axis=0, dtype="i64")              # [count]
+            x = b.op("Gather", [t, rows], axis=0)                                   # the picked rows
+            for _ in range(rnd.randint(1, 3)):
+                c = rnd.choice(["unary", "scalar", "softmax", "layernorm"])
+                if c == "unary":
+                    x = b.op(rnd.choice(["Relu", "Gelu", "Sigmoid"]), [x])
+                elif c == "scalar":
+                    x = b.op(rnd.choice(["Add", "Mul"]), [x, const(rnd.choice([0.5, 2.0, -1.0]), "f32")])
+                elif c == "softmax":
+                    x = b.op("Softmax", [x], causal=0)
+                elif isinstance(d[-1], int):
+                    x = b.op("LayerNorm", [x, weight([d[-1]]), weight([d[-1]])], eps=1e-5)
+            add(b.op("ScatterRows", [t, rows, x]), d)
+        elif kind == "gate" and b.g.tensors[t].dtype == dtype:
             n_gates = sum(1 for op in b.g.ops if op.kind == "Switch")
             pred = b.input(f"p{n_gates}", "f32", [1])
             taken, other = b.op("Switch", [t, pred], n_out=2, threshold=0.5)
@@ -183,6 +201,10 @@ def make_inputs(g, shapes, sym, rs):
     for t in g.inputs():
         if g.tensors[t].dtype == "i64":
             ins[t] = rs.randint(0, 8, size=(sym["B"],)).astype(np.int64)
+        elif g.tensors[t].name[0] == "m" and g.tensors[t].name[-1] in "AB" and g.tensors[t].name[1:-1].isdigit():
+            n = sym[g.tensors[t].name[-1]]                                     # a row mask: none, all, or some rows
+            how = rs.randint(0, 4)
+            ins[t] = np.zeros(n) if how == 0 else (np.ones(n) if how == 1 else (rs.rand(n) < 0.5).astype(np.float64))
         elif g.tensors[t].name.startswith("p") and g.tensors[t].name[1:].isdigit():
             ins[t] = np.array([float(rs.randint(0, 2))])              # a gate's predicate: 0 or 1 against the threshold 0.5
         else:
@@ -328,3 +350,32 @@ def test_control_results_cannot_be_graph_outputs():
     g = graph(True)
     lg = S.sod2_graph_build(g)
     assert S.sod2_plan_dump(S.sod2_plan(lg, S.sod2_rdp_infer(lg))) == P.dump(P.build_plan(g, R.RDP(g).analyse()))
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_random_graph_with_compaction(seed):
+    """NonZero / Gather / ScatterRows around short branches in random places: the two analyses (Alg. 1 as printed, and
+    with the row counts named), the plan, and the bindings -- at the upper bounds, and with the counts a run of the
+    oracle finds, also partly known -- agree between the library and the oracle."""
+    g, weights, shapes = random_graph(seed, compact=True)
+    if g is None or not any(op.kind == "NonZero" for op in g.ops):
+        pytest.skip("no compaction in this draw")
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    ro = R.RDP(g).analyse()
+    assert S.sod2_rdp_dump(lr) == R.dump(ro)
+    lp = S.sod2_plan(lg, lr)
+    po = P.build_plan(g, ro)
+    assert S.sod2_plan_dump(lp) == P.dump(po)
+    rs = np.random.RandomState(seed)
+    W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
+    for sym in ({"A": 3, "B": 5}, {"A": 9, "B": 12}, {"A": 1, "B": 1}):
+        assert S.sod2_binding_dump(S.sod2_bind(lp, sym)) == A.dump(A.bind(po, sym))
+        for _ in range(2):
+            ref = execute.run(g, po.order, W, make_inputs(g, shapes, sym, rs))
+            ev = list(ref.exec_values)
+            assert len(ev) == sum(1 for op in g.ops if op.kind == "NonZero")
+            for known in (ev, ev[:1]):
+                assert S.sod2_binding_dump(S.sod2_bind(lp, sym, exec_values=known)) == A.dump(A.bind(po, sym, exec_values=known)), (sym, known)
+            for t in g.outputs():
+                assert ref.values[t].shape == concrete(shapes[t], sym)
