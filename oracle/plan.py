@@ -18,7 +18,8 @@ R1  Reshape, Slice, Transpose, Expand and Gather-with-a-scalar-host-index are *v
     dense operands (Concat, ReduceMean, pools, GroupNorm, Conv, the table of a
     Gather by an index tensor, ...), and a permuted view read by LayerNorm,
     Softmax or Reshape (regrouping the dims of a permutation needs its elements
-    in the new order).
+    in the new order).  "Read by" looks through Switch and Combine, which hand
+    the storage on under another name.
 R2  MatMul / Conv seeds a group and absorbs the chain of its sole consumers, in
     this order and each at most once: Mul by a host scalar; Add of a rank-1
     weight equal to the last dim (bias); activation; Add of a non-constant
@@ -253,15 +254,38 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
     # R1, second half: a view that a kernel could not walk is written out.  Decided from the graph alone, in the node
     # order so that a view of a view inherits: a view is *strided* when it permutes dims, slices or indexes a dim other
     # than the first, or repeats elements (Expand); *permuted* when a Transpose is involved.
-    strided, permuted = [False] * nops, [False] * nops
+    nt = len(g.tensors)
+    strided, permuted = [False] * nt, [False] * nt     # per tensor: it is such a view (control operators pass it on)
+
+    def readers(t):
+        """The operators that get to read tensor t, with the tensor they read it as: its consumers, looking through
+        Switch and Combine (which hand the storage on under another name)."""
+        out, stack, seen = [], [t], set()
+        while stack:
+            u = stack.pop()
+            for c in rdp.consumers[u]:
+                if (c, u) in seen or folded[c]:
+                    continue
+                seen.add((c, u))
+                if g.ops[c].kind in ("Switch", "Combine"):
+                    stack.extend(g.ops[c].outputs)
+                else:
+                    out.append((c, u))
+        return sorted(out)
+
     for n in order:
+        op = g.ops[n]
+        if op.kind == "Switch":
+            for o in op.outputs:
+                strided[o], permuted[o] = strided[op.inputs[0]], permuted[op.inputs[0]]
+            continue
+        if op.kind == "Combine":
+            strided[op.outputs[0]] = any(strided[t] for t in op.inputs)
+            permuted[op.outputs[0]] = any(permuted[t] for t in op.inputs)
+            continue
         if not view[n]:
             continue
-        op = g.ops[n]
-        src = op.inputs[0]
-        pr = rdp.producer[src]
-        s_in = pr >= 0 and view[pr] and strided[pr]
-        p_in = pr >= 0 and view[pr] and permuted[pr]
+        src, res = op.inputs[0], op.outputs[0]
         rank = len(rdp.S[src]) if isinstance(rdp.S[src], list) else None
         s = p = False
         if op.kind == "Transpose":
@@ -274,15 +298,13 @@ def build_plan(graph, rdp: R.RDP, opts: Opts = None) -> Plan:
             s = True
         elif op.kind == "Gather":
             s = rank is None or op.attrs["axis"] % rank != 0
-        strided[n], permuted[n] = s or s_in, p or p_in
-        for c in rdp.consumers[op.outputs[0]]:
+        strided[res], permuted[res] = s or strided[src], p or permuted[src]
+        for c, u in readers(res):
             k = g.ops[c].kind
-            if folded[c]:
-                continue
-            table = k == "Gather" and not view[c] and g.ops[c].inputs[0] == op.outputs[0]     # rows picked by an index tensor
-            if ((k in DENSE_ONLY or table) and strided[n]) or (k in ROW_OPS + ("Reshape",) and permuted[n]):
+            table = k == "Gather" and not view[c] and g.ops[c].inputs[0] == u      # rows picked by an index tensor
+            if ((k in DENSE_ONLY or table) and strided[res]) or (k in ROW_OPS + ("Reshape",) and permuted[res]):
                 view[n] = False                    # a COPY group: its result is dense
-                strided[n] = permuted[n] = False
+                strided[res] = permuted[res] = False
                 break
 
     def sole_consumer(t) -> Optional[int]:

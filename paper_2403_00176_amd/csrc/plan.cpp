@@ -37,6 +37,7 @@
 // analysis with named EDO extents; a tensor that is unresolved or sized by an execution symbol
 // counts as nac: a cut follows every item that writes one and such sub-graphs keep the node order.
 #include <algorithm>
+#include <set>
 #include <limits>
 
 #include "internal.hpp"
@@ -166,12 +167,37 @@ void Plan::build() {
   // inherits: strided = permutes dims, slices or indexes a dim other than the first, or repeats elements; permuted =
   // a Transpose is involved.
   {
-    std::vector<char> strided(nops, 0), permuted(nops, 0);
+    const int nten = (int)G.tensors.size();
+    std::vector<char> strided(nten, 0), permuted(nten, 0);   // per tensor: it is such a view (control operators pass it on)
+    // the operators that get to read tensor t, with the tensor they read it as: consumers, looking through Switch / Combine
+    auto readers = [&](int t) {
+        std::vector<std::pair<int, int>> out;
+        std::vector<int> stack{t};
+        std::set<std::pair<int, int>> seen;
+        while (!stack.empty()) {
+          const int u = stack.back();
+          stack.pop_back();
+          for (int c : G.consumers[u]) {
+            if (folded[c] || !seen.insert({c, u}).second) continue;
+            if (is_control(G.ops[c].kind)) stack.insert(stack.end(), G.ops[c].out.begin(), G.ops[c].out.end());
+            else out.push_back({c, u});
+          }
+        }
+        std::sort(out.begin(), out.end());
+        return out;
+    };
     for (int n : order) {
-      if (!view[n]) continue;
       const Op& op = G.ops[n];
-      const int src = op.in[0], pr = G.producer[src];
-      const bool s_in = pr >= 0 && view[pr] && strided[pr], p_in = pr >= 0 && view[pr] && permuted[pr];
+      if (op.kind == SOD2_OP_SWITCH) {
+        for (int o : op.out) { strided[o] = strided[op.in[0]]; permuted[o] = permuted[op.in[0]]; }
+        continue;
+      }
+      if (op.kind == SOD2_OP_COMBINE) {
+        for (int t : op.in) { strided[op.out[0]] |= strided[t]; permuted[op.out[0]] |= permuted[t]; }
+        continue;
+      }
+      if (!view[n]) continue;
+      const int src = op.in[0], res = op.out[0];
       const LS& ss = R.S[src];
       const int64_t rank = ss.is_list() ? (int64_t)ss.d.size() : -1;
       bool s = false, pm = false;
@@ -188,16 +214,15 @@ void Plan::build() {
       } else if (op.kind == SOD2_OP_GATHER) {
         s = rank <= 0 || ((op.ia.at(0) % rank) + rank) % rank != 0;
       }
-      strided[n] = s || s_in;
-      permuted[n] = pm || p_in;
-      for (int c2 : G.consumers[op.out[0]]) {
-        if (folded[c2]) continue;
-        const int k = G.ops[c2].kind;
-        const bool table = k == SOD2_OP_GATHER && !view[c2] && G.ops[c2].in[0] == op.out[0];   // rows picked by an index tensor
-        if (((is_dense_only(k) || table) && strided[n]) ||
-            ((k == SOD2_OP_LAYERNORM || k == SOD2_OP_SOFTMAX || k == SOD2_OP_RESHAPE) && permuted[n])) {
+      strided[res] = s || strided[src];
+      permuted[res] = pm || permuted[src];
+      for (const auto& cu : readers(res)) {
+        const int c2 = cu.first, k = G.ops[c2].kind;
+        const bool table = k == SOD2_OP_GATHER && !view[c2] && G.ops[c2].in[0] == cu.second;   // rows picked by an index tensor
+        if (((is_dense_only(k) || table) && strided[res]) ||
+            ((k == SOD2_OP_LAYERNORM || k == SOD2_OP_SOFTMAX || k == SOD2_OP_RESHAPE) && permuted[res])) {
           view[n] = 0;                               // a COPY group: its result is dense
-          strided[n] = permuted[n] = 0;
+          strided[res] = permuted[res] = 0;
           break;
         }
       }

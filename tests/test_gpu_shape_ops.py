@@ -663,3 +663,43 @@ def test_random_graphs_with_compaction_against_the_oracle(S_lib, dtype):
                 assert err <= (1e-4 if dtype == "f32" else 2e-2), (seed, sym, g.tensors[t].name, err)
     print("compacting random graphs", dtype, ": ran", ran, "counts read back", counts, "worst rel err", worst)
     assert ran >= 60 and counts >= 100
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_random_graphs_with_gates_and_compaction_against_the_oracle(S_lib, dtype):
+    """<Switch, Combine> pairs and NonZero compaction in one random graph: decisions, counts, the plan made in mid-run
+    with both kinds of read-back, and every output against the oracle."""
+    import torch
+    from tests.test_random_graphs import random_graph, make_inputs
+    from paper_2403_00176_amd.session import Session, to_host
+    ran = 0
+    worst = 0.0
+    for seed in range(80):
+        g, weights, shapes = random_graph(seed, dtype, gates=True, compact=True)
+        if g is None or not (any(op.kind == "NonZero" for op in g.ops) and any(op.kind == "Switch" for op in g.ops)):
+            continue
+        po = P.build_plan(g, R.RDP(g).analyse())
+        ses = Session(g)
+        rs = np.random.RandomState(seed)
+        W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
+        ses.upload_weights(W)
+        for sym in ({"A": 3, "B": 5}, {"A": 9, "B": 12}, {"A": 1, "B": 1}):
+            ins = make_inputs(g, shapes, sym, rs)
+            ref = execute.run(g, po.order, W, ins)
+            print(f"case mixed random graph {dtype} seed {seed} {sym} decisions {ref.decisions} counts {ref.exec_values}", flush=True)
+            bnd = ses.bind(sym)
+            outs = ses.alloc_outputs(ses.output_shapes(bnd))
+            ses.run(bnd, ses.upload_inputs(ins), outs)
+            torch.cuda.synchronize()
+            ran += 1
+            assert [bool(d) for d in S_lib.sod2_run_decisions(bnd)] == ref.decisions
+            assert S_lib.sod2_run_exec_values(bnd) == ref.exec_values
+            assert S_lib.sod2_run_plan_dump(bnd) == A.dump(A.bind(po, sym, ref.decisions, ref.exec_values))
+            for t, o in zip(g.outputs(), outs):
+                got = to_host(o)
+                assert got.shape == ref.values[t].shape and np.isfinite(got).all()
+                err = rel_err(got, ref.values[t])
+                worst = max(worst, err)
+                assert err <= (1e-4 if dtype == "f32" else 2e-2), (seed, sym, g.tensors[t].name, err)
+    print("mixed random graphs", dtype, ": ran", ran, "worst rel err", worst)
+    assert ran >= 60

@@ -379,3 +379,27 @@ def test_random_graph_with_compaction(seed):
                 assert S.sod2_binding_dump(S.sod2_bind(lp, sym, exec_values=known)) == A.dump(A.bind(po, sym, exec_values=known)), (sym, known)
             for t in g.outputs():
                 assert ref.values[t].shape == concrete(shapes[t], sym)
+
+
+@pytest.mark.parametrize("seed", range(80))
+def test_random_graph_with_gates_and_compaction(seed):
+    """Both kinds of execution-determined operators in one graph: the plan, and the bindings for the decisions and
+    counts a run of the oracle takes, agree between the library and the oracle."""
+    g, weights, shapes = random_graph(seed, gates=True, compact=True)
+    if g is None or not (any(op.kind == "NonZero" for op in g.ops) and any(op.kind == "Switch" for op in g.ops)):
+        pytest.skip("this draw does not hold both")
+    lg = S.sod2_graph_build(g)
+    lr = S.sod2_rdp_infer(lg)
+    ro = R.RDP(g).analyse()
+    assert S.sod2_rdp_dump(lr) == R.dump(ro)
+    lp = S.sod2_plan(lg, lr)
+    po = P.build_plan(g, ro)
+    assert S.sod2_plan_dump(lp) == P.dump(po)
+    rs = np.random.RandomState(seed)
+    W = {t: rs.randn(*d) * 0.3 for t, d in weights.items()}
+    for sym in ({"A": 3, "B": 5}, {"A": 9, "B": 12}):
+        for _ in range(3):
+            ref = execute.run(g, po.order, W, make_inputs(g, shapes, sym, rs))
+            dec, ev = list(ref.decisions), list(ref.exec_values)
+            assert S.sod2_binding_dump(S.sod2_bind(lp, sym, decisions=dec, exec_values=ev)) == \
+                A.dump(A.bind(po, sym, dec, ev)), (sym, dec, ev)
