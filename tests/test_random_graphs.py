@@ -212,6 +212,15 @@ def make_inputs(g, shapes, sym, rs):
     return ins
 
 
+def _has(g, *kinds):
+    return g is not None and all(any(op.kind == k for op in g.ops) for k in kinds)
+
+
+def _seeds(n, kinds, **modes):
+    """The seeds below n whose draw holds every operator kind named (decided when the tests are collected)."""
+    return [s for s in range(n) if _has(random_graph(s, **modes)[0], *kinds)]
+
+
 @pytest.mark.parametrize("seed,wide", [(s, False) for s in range(60)] + [(s, True) for s in range(25)])
 def test_random_graph_library_equals_oracle(seed, wide):
     g, weights, shapes = random_graph(seed, "bf16" if wide else "f32", wide)
@@ -294,14 +303,12 @@ def test_random_graph_with_an_undeclared_input(seed):
     assert outcome(library) == outcome(oracle)
 
 
-@pytest.mark.parametrize("seed", range(30))
+@pytest.mark.parametrize("seed", _seeds(30, ("Switch",), gates=True))
 def test_random_graph_with_gates(seed):
     """<Switch, Combine> pairs in random places: the analysis (a Combine merges its branches), the partition around the
     control operators, and the plan for every decision vector tried -- the one a run of the oracle takes on random
     predicates, all-run, all-skip -- agree between the library and the oracle; the plan with nothing decided binds."""
     g, weights, shapes = random_graph(seed, gates=True)
-    if g is None or not any(op.kind == "Switch" for op in g.ops):
-        pytest.skip("no gate in this draw")
     lg = S.sod2_graph_build(g)
     lr = S.sod2_rdp_infer(lg)
     ro = R.RDP(g).analyse()
@@ -352,14 +359,12 @@ def test_control_results_cannot_be_graph_outputs():
     assert S.sod2_plan_dump(S.sod2_plan(lg, S.sod2_rdp_infer(lg))) == P.dump(P.build_plan(g, R.RDP(g).analyse()))
 
 
-@pytest.mark.parametrize("seed", range(30))
+@pytest.mark.parametrize("seed", _seeds(30, ("NonZero",), compact=True))
 def test_random_graph_with_compaction(seed):
     """NonZero / Gather / ScatterRows around short branches in random places: the two analyses (Alg. 1 as printed, and
     with the row counts named), the plan, and the bindings -- at the upper bounds, and with the counts a run of the
     oracle finds, also partly known -- agree between the library and the oracle."""
     g, weights, shapes = random_graph(seed, compact=True)
-    if g is None or not any(op.kind == "NonZero" for op in g.ops):
-        pytest.skip("no compaction in this draw")
     lg = S.sod2_graph_build(g)
     lr = S.sod2_rdp_infer(lg)
     ro = R.RDP(g).analyse()
@@ -381,13 +386,11 @@ def test_random_graph_with_compaction(seed):
                 assert ref.values[t].shape == concrete(shapes[t], sym)
 
 
-@pytest.mark.parametrize("seed", range(80))
+@pytest.mark.parametrize("seed", _seeds(80, ("Switch", "NonZero"), gates=True, compact=True))
 def test_random_graph_with_gates_and_compaction(seed):
     """Both kinds of execution-determined operators in one graph: the plan, and the bindings for the decisions and
     counts a run of the oracle takes, agree between the library and the oracle."""
     g, weights, shapes = random_graph(seed, gates=True, compact=True)
-    if g is None or not (any(op.kind == "NonZero" for op in g.ops) and any(op.kind == "Switch" for op in g.ops)):
-        pytest.skip("this draw does not hold both")
     lg = S.sod2_graph_build(g)
     lr = S.sod2_rdp_infer(lg)
     ro = R.RDP(g).analyse()
